@@ -1,0 +1,160 @@
+"""ctypes front end of the fp64 CPU oracle (sattn_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, by the smoke check and by the cpu_baseline
+leg of the benchmark.  It shares nothing with the HIP path and the product never calls it.
+
+Every function takes numpy arrays (any float dtype; converted exactly to float64) laid out
+[B, H, N, d], and returns float64 numpy arrays.  `bias` is the scalar b of the boxed
+sigmoid-attention equation in Section 2; `alibi_slopes` is an optional length-H array m_h;
+`causal` keeps keys j <= i.
+"""
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "sattn_oracle.c")
+_LIB = os.path.join(_HERE, "libsattn_oracle.so")
+
+_dp = ctypes.POINTER(ctypes.c_double)
+_ip = ctypes.POINTER(ctypes.c_int)
+
+
+def build(force=False):
+    """Compile the C oracle with gcc (OpenMP).  Returns the library path."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-fopenmp", "-fno-fast-math", "-ffp-contract=off", "-shared", "-fPIC",
+               "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        _lib = ctypes.CDLL(_LIB)
+        for name in dir(_lib):
+            pass
+        _lib.oracle_num_threads.restype = ctypes.c_int
+    return _lib
+
+
+def num_threads():
+    return int(_load().oracle_num_threads())
+
+
+def _f64(x):
+    if hasattr(x, "detach"):  # torch tensor (bf16 has no numpy dtype: widen first, exactly)
+        x = x.detach().cpu().double().numpy()
+    return np.ascontiguousarray(np.asarray(x, dtype=np.float64))
+
+
+def _ptr(a):
+    return a.ctypes.data_as(_dp)
+
+
+def _slopes(alibi_slopes, H):
+    if alibi_slopes is None:
+        return None, None
+    s = _f64(alibi_slopes).reshape(-1)
+    assert s.shape[0] == H
+    return s, _ptr(s)
+
+
+def sigmoid_attn_fwd(q, k, v, bias, causal=False, alibi_slopes=None):
+    q, k, v = _f64(q), _f64(k), _f64(v)
+    B, H, N, d = q.shape
+    assert k.shape == q.shape and v.shape == q.shape
+    o = np.empty_like(q)
+    s, sp = _slopes(alibi_slopes, H)
+    _load().oracle_sigmoid_attn_fwd(_ptr(q), _ptr(k), _ptr(v), _ptr(o), B, H, N, d, ctypes.c_double(bias),
+                                    int(bool(causal)), sp)
+    return o
+
+
+def sigmoid_attn_bwd(q, k, v, dout, bias, causal=False, alibi_slopes=None):
+    q, k, v, dout = _f64(q), _f64(k), _f64(v), _f64(dout)
+    B, H, N, d = q.shape
+    assert k.shape == q.shape and v.shape == q.shape and dout.shape == q.shape
+    dq, dk, dv = np.empty_like(q), np.empty_like(q), np.empty_like(q)
+    s, sp = _slopes(alibi_slopes, H)
+    _load().oracle_sigmoid_attn_bwd(_ptr(q), _ptr(k), _ptr(v), _ptr(dout), _ptr(dq), _ptr(dk), _ptr(dv), B, H, N,
+                                    d, ctypes.c_double(bias), int(bool(causal)), sp)
+    return dq, dk, dv
+
+
+def softmax_attn_fwd(q, k, v, causal=False, alibi_slopes=None):
+    """Returns (O, LSE) with LSE [B,H,N] in natural-log units."""
+    q, k, v = _f64(q), _f64(k), _f64(v)
+    B, H, N, d = q.shape
+    o = np.empty_like(q)
+    lse = np.empty((B, H, N), dtype=np.float64)
+    s, sp = _slopes(alibi_slopes, H)
+    _load().oracle_softmax_attn_fwd(_ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), B, H, N, d, int(bool(causal)),
+                                    sp)
+    return o, lse
+
+
+def softmax_attn_bwd(q, k, v, dout, causal=False, alibi_slopes=None):
+    q, k, v, dout = _f64(q), _f64(k), _f64(v), _f64(dout)
+    B, H, N, d = q.shape
+    dq, dk, dv = np.empty_like(q), np.empty_like(q), np.empty_like(q)
+    s, sp = _slopes(alibi_slopes, H)
+    _load().oracle_softmax_attn_bwd(_ptr(q), _ptr(k), _ptr(v), _ptr(dout), _ptr(dq), _ptr(dk), _ptr(dv), B, H, N,
+                                    d, int(bool(causal)), sp)
+    return dq, dk, dv
+
+
+# ---- sampled rows of ONE head: q,k,v,dout are [N, d]; rows is a list of indices -------------
+
+def _rows(rows):
+    r = np.ascontiguousarray(np.asarray(rows, dtype=np.int32))
+    return r, r.ctypes.data_as(_ip)
+
+
+def sigmoid_attn_fwd_rows(q, k, v, bias, causal, slope, rows):
+    q, k, v = _f64(q), _f64(k), _f64(v)
+    N, d = q.shape
+    r, rp = _rows(rows)
+    out = np.empty((len(r), d), dtype=np.float64)
+    _load().oracle_sigmoid_attn_fwd_rows(_ptr(q), _ptr(k), _ptr(v), N, d, ctypes.c_double(bias), int(bool(causal)),
+                                         ctypes.c_double(slope), rp, len(r), _ptr(out))
+    return out
+
+
+def sigmoid_attn_dq_rows(q, k, v, dout, bias, causal, slope, rows):
+    q, k, v, dout = _f64(q), _f64(k), _f64(v), _f64(dout)
+    N, d = q.shape
+    r, rp = _rows(rows)
+    out = np.empty((len(r), d), dtype=np.float64)
+    _load().oracle_sigmoid_attn_dq_rows(_ptr(q), _ptr(k), _ptr(v), _ptr(dout), N, d, ctypes.c_double(bias),
+                                        int(bool(causal)), ctypes.c_double(slope), rp, len(r), _ptr(out))
+    return out
+
+
+def sigmoid_attn_dkdv_rows(q, k, v, dout, bias, causal, slope, rows):
+    q, k, v, dout = _f64(q), _f64(k), _f64(v), _f64(dout)
+    N, d = q.shape
+    r, rp = _rows(rows)
+    dk = np.empty((len(r), d), dtype=np.float64)
+    dv = np.empty((len(r), d), dtype=np.float64)
+    _load().oracle_sigmoid_attn_dkdv_rows(_ptr(q), _ptr(k), _ptr(v), _ptr(dout), N, d, ctypes.c_double(bias),
+                                          int(bool(causal)), ctypes.c_double(slope), rp, len(r), _ptr(dk), _ptr(dv))
+    return dk, dv
+
+
+def softmax_attn_fwd_rows(q, k, v, causal, slope, rows):
+    q, k, v = _f64(q), _f64(k), _f64(v)
+    N, d = q.shape
+    r, rp = _rows(rows)
+    out = np.empty((len(r), d), dtype=np.float64)
+    lse = np.empty((len(r),), dtype=np.float64)
+    _load().oracle_softmax_attn_fwd_rows(_ptr(q), _ptr(k), _ptr(v), N, d, int(bool(causal)), ctypes.c_double(slope),
+                                         rp, len(r), _ptr(out), _ptr(lse))
+    return out, lse

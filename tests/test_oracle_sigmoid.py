@@ -1,0 +1,298 @@
+"""Pins for the fp64 CPU oracle of sigmoid attention.
+
+None of these re-types the oracle's loop: each pins it to a closed form, an identity, a
+limit, a library routine (PyTorch fp64 CPU ops + autograd) or finite differences, chosen so
+that a dropped term, a wrong sign/index/scale or a transposed operand fails at least one.
+"""
+import math
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import sattn_oracle as orc
+
+RNG = np.random.default_rng(20240904)
+GOLD = os.path.join(os.path.dirname(__file__), "golden", "closed_forms.txt")
+
+
+def _golden():
+    out = {}
+    for line in open(GOLD):
+        line = line.split("#")[0].strip()
+        if "=" in line:
+            k, v = line.split("=", 1)
+            out[k.strip()] = v.strip()
+    return out
+
+
+def _rand(B, H, N, d, scale=1.0):
+    return RNG.standard_normal((B, H, N, d)) * scale
+
+
+def _alibi_slopes(H):
+    return np.array([2.0 ** (-8.0 * (h + 1) / H) for h in range(H)])
+
+
+# ------------------------------------------------------------------ closed forms
+
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("d", [3, 16])
+def test_zero_logits_give_sigma_b_times_sum_of_visible_v(causal, d):
+    # Q = 0 => every logit is b, whatever d: O_i = sigma(b) * sum_{j visible} V_j
+    B, H, N = 2, 3, 11
+    v = _rand(B, H, N, d)
+    k = _rand(B, H, N, d)
+    q = np.zeros_like(v)
+    for b in (0.0, -math.log(N), -math.log(N - 1), 1.7):
+        o = orc.sigmoid_attn_fwd(q, k, v, b, causal=causal)
+        sb = 1.0 / (1.0 + math.exp(-b))
+        csum = np.cumsum(v, axis=2) if causal else np.broadcast_to(v.sum(2, keepdims=True), v.shape)
+        np.testing.assert_allclose(o, sb * csum, rtol=1e-13, atol=1e-13)
+
+
+def test_paper_bias_values():
+    # Appendix E: exp(-b) = n-1 makes all weights 1/n (O = mean V); b=-log n gives 1/(n+1); b=0 gives 1/2.
+    g = _golden()
+    assert g["uniform_weight_bias"] == "-log(n-1)" and g["practice_bias_weight"] == "1/(n+1)"
+    N, d = 37, 5
+    v = _rand(1, 1, N, d)
+    z = np.zeros_like(v)
+    np.testing.assert_allclose(orc.sigmoid_attn_fwd(z, z, v, -math.log(N - 1)),
+                               np.broadcast_to(v.mean(2, keepdims=True), v.shape), rtol=1e-13)
+    np.testing.assert_allclose(orc.sigmoid_attn_fwd(z, z, v, -math.log(N)),
+                               np.broadcast_to(v.sum(2, keepdims=True) / (N + 1), v.shape), rtol=1e-13)
+    np.testing.assert_allclose(orc.sigmoid_attn_fwd(z, z, v, 0.0),
+                               np.broadcast_to(float(g["heaviside_at_zero"]) * v.sum(2, keepdims=True), v.shape),
+                               rtol=1e-13)
+
+
+def test_single_token_scalar_case_fixes_scale_and_bias_order():
+    # N=1, d=4, q=k=(1,1,1,1): q.k/sqrt(d) = 2, so O = sigmoid(2+b) v.  A missing 1/sqrt(d)
+    # (sigmoid(4)), a sqrt(d) factor (sigmoid(8)) or b scaled with the logits would all differ.
+    g = _golden()
+    q = np.ones((1, 1, 1, 4))
+    v = np.array([[[[1.0, -2.0, 0.5, 3.0]]]])
+    np.testing.assert_allclose(orc.sigmoid_attn_fwd(q, q, v, 0.0), float(g["sigmoid(2)"]) * v, rtol=1e-15)
+    np.testing.assert_allclose(orc.sigmoid_attn_fwd(q, q, v, -3.0), float(g["sigmoid(-1)"]) * v, rtol=1e-15)
+    # d=16, q.k = 2 -> 2/4 = 0.5
+    q16 = np.zeros((1, 1, 1, 16)); q16[..., 0] = 2.0
+    k16 = np.zeros((1, 1, 1, 16)); k16[..., 0] = 1.0
+    v16 = _rand(1, 1, 1, 16)
+    np.testing.assert_allclose(orc.sigmoid_attn_fwd(q16, k16, v16, 0.0), float(g["sigmoid(0.5)"]) * v16, rtol=1e-15)
+
+
+def test_two_token_hand_example_fixes_operand_roles():
+    # i indexes queries, j keys: O_0 = s(q0.k0) v0 + s(q0.k1) v1.  Swapping Q and K, or using
+    # V^T, changes the result.  d=1 so the logits are plain products.
+    q = np.array([[[[1.0], [0.0]]]])
+    k = np.array([[[[2.0], [-1.0]]]])
+    v = np.array([[[[10.0], [100.0]]]])
+    g = _golden()
+    s2, sm1 = float(g["sigmoid(2)"]), float(g["sigmoid(-1)"])
+    o = orc.sigmoid_attn_fwd(q, k, v, 0.0)
+    np.testing.assert_allclose(o[0, 0, 0, 0], s2 * 10 + sm1 * 100, rtol=1e-15)
+    np.testing.assert_allclose(o[0, 0, 1, 0], 0.5 * 110, rtol=1e-15)
+    oc = orc.sigmoid_attn_fwd(q, k, v, 0.0, causal=True)
+    np.testing.assert_allclose(oc[0, 0, 0, 0], s2 * 10, rtol=1e-15)       # key 1 hidden from query 0
+    np.testing.assert_allclose(oc[0, 0, 1, 0], 0.5 * 110, rtol=1e-15)     # diagonal kept
+
+
+def test_sequence_form_with_log_n_bias():
+    # Section 2, sequence equation: with b = -log n, weight = exp(s)/(exp(s)+n)
+    B, H, N, d = 1, 2, 19, 8
+    q, k, v = _rand(B, H, N, d), _rand(B, H, N, d), _rand(B, H, N, d)
+    s = np.einsum("bhid,bhjd->bhij", q, k) / math.sqrt(d)
+    w = np.exp(s) / (np.exp(s) + N)
+    np.testing.assert_allclose(orc.sigmoid_attn_fwd(q, k, v, -math.log(N)), w @ v, rtol=1e-12, atol=1e-13)
+
+
+# ------------------------------------------------------------------ identities and limits
+
+def test_reflection_symmetry():
+    # sigma(-x) = 1 - sigma(x): O(Q,b) + O(-Q,-b) = sum_j V_j (non-causal, no ALiBi)
+    B, H, N, d = 2, 2, 13, 6
+    q, k, v = _rand(B, H, N, d), _rand(B, H, N, d), _rand(B, H, N, d)
+    b = -0.8
+    tot = orc.sigmoid_attn_fwd(q, k, v, b) + orc.sigmoid_attn_fwd(-q, k, v, -b)
+    np.testing.assert_allclose(tot, np.broadcast_to(v.sum(2, keepdims=True), v.shape), rtol=1e-12, atol=1e-12)
+
+
+def test_heaviside_limit():
+    # Appendix C: sigmoid(lambda x) -> H(x).  Large lambda, b=0: O_i -> sum_{j: s_ij>0} V_j
+    B, H, N, d = 1, 1, 9, 4
+    q, k, v = _rand(B, H, N, d), _rand(B, H, N, d), _rand(B, H, N, d)
+    s = np.einsum("bhid,bhjd->bhij", q, k)
+    assert np.abs(s).min() > 1e-3
+    o = orc.sigmoid_attn_fwd(1e6 * q, k, v, 0.0)
+    np.testing.assert_allclose(o, (s > 0).astype(float) @ v, rtol=1e-12, atol=1e-12)
+    assert np.isfinite(o).all()
+
+
+def test_additive_over_key_halves_and_linear_in_v():
+    B, H, N, d = 1, 2, 16, 5
+    q, k, v = _rand(B, H, N, d), _rand(B, H, N, d), _rand(B, H, N, d)
+    b = -math.log(N)
+    full = orc.sigmoid_attn_fwd(q, k, v, b)
+    # no normaliser: zeroing V on one half of the keys and adding the two results gives the full one
+    v1, v2 = v.copy(), v.copy()
+    v1[:, :, N // 2:] = 0
+    v2[:, :, :N // 2] = 0
+    np.testing.assert_allclose(orc.sigmoid_attn_fwd(q, k, v1, b) + orc.sigmoid_attn_fwd(q, k, v2, b), full,
+                               rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(orc.sigmoid_attn_fwd(q, k, 3.0 * v, b), 3.0 * full, rtol=1e-12, atol=1e-14)
+
+
+def test_permutation_equivariance():
+    B, H, N, d = 1, 1, 12, 4
+    q, k, v = _rand(B, H, N, d), _rand(B, H, N, d), _rand(B, H, N, d)
+    perm = RNG.permutation(N)
+    o = orc.sigmoid_attn_fwd(q, k, v, -1.0)
+    op = orc.sigmoid_attn_fwd(q[:, :, perm], k[:, :, perm], v[:, :, perm], -1.0)
+    np.testing.assert_allclose(op, o[:, :, perm], rtol=1e-12, atol=1e-13)
+
+
+def test_alibi_closed_form_and_zero_slope():
+    # Q=0, causal: O_i = sum_{j<=i} sigma(b - m (i-j)) V_j  -- a 1-D correlation
+    B, H, N, d = 1, 3, 10, 4
+    v = _rand(B, H, N, d)
+    z = np.zeros_like(v)
+    slopes = _alibi_slopes(H)
+    b = -0.3
+    o = orc.sigmoid_attn_fwd(z, z, v, b, causal=True, alibi_slopes=slopes)
+    for h in range(H):
+        w = 1.0 / (1.0 + np.exp(-(b - slopes[h] * np.arange(N))))   # weight as a function of i-j
+        for i in range(N):
+            ref = sum(w[i - j] * v[0, h, j] for j in range(i + 1))
+            np.testing.assert_allclose(o[0, h, i], ref, rtol=1e-12)
+    # non-causal uses |i-j| (symmetric)
+    o2 = orc.sigmoid_attn_fwd(z, z, v, b, causal=False, alibi_slopes=slopes)
+    for h in range(H):
+        w = 1.0 / (1.0 + np.exp(-(b - slopes[h] * np.arange(N))))
+        ref = sum(w[abs(4 - j)] * v[0, h, j] for j in range(N))
+        np.testing.assert_allclose(o2[0, h, 4], ref, rtol=1e-12)
+    # slope 0 is bit-identical to no ALiBi
+    q, k = _rand(B, H, N, d), _rand(B, H, N, d)
+    assert np.array_equal(orc.sigmoid_attn_fwd(q, k, v, b, alibi_slopes=np.zeros(H)),
+                          orc.sigmoid_attn_fwd(q, k, v, b))
+
+
+# ------------------------------------------------------------------ library routine (torch fp64 + autograd)
+
+def _torch_ref(q, k, v, dout, bias, causal, slopes):
+    q, k, v, dout = (torch.tensor(x, dtype=torch.float64, requires_grad=True) for x in (q, k, v, dout))
+    B, H, N, d = q.shape
+    s = q @ k.transpose(-1, -2) / math.sqrt(d) + bias
+    idx = torch.arange(N)
+    if slopes is not None:
+        dist = (idx[:, None] - idx[None, :]).abs().double()
+        s = s - torch.tensor(slopes, dtype=torch.float64)[None, :, None, None] * dist
+    p = torch.sigmoid(s)
+    if causal:
+        p = p * (idx[None, :] <= idx[:, None]).double()
+    o = p @ v
+    (o * dout).sum().backward()
+    return o.detach().numpy(), q.grad.numpy(), k.grad.numpy(), v.grad.numpy()
+
+
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("alibi", [False, True])
+@pytest.mark.parametrize("shape", [(1, 2, 33, 8), (2, 3, 64, 16), (1, 1, 257, 64)])
+def test_against_torch_fp64_autograd(causal, alibi, shape):
+    B, H, N, d = shape
+    q, k, v, dout = (_rand(B, H, N, d) for _ in range(4))
+    slopes = _alibi_slopes(H) if alibi else None
+    bias = -math.log(N)
+    o, dq, dk, dv = _torch_ref(q, k, v, dout, bias, causal, slopes)
+    np.testing.assert_allclose(orc.sigmoid_attn_fwd(q, k, v, bias, causal, slopes), o, rtol=1e-11, atol=1e-13)
+    gq, gk, gv = orc.sigmoid_attn_bwd(q, k, v, dout, bias, causal, slopes)
+    np.testing.assert_allclose(gq, dq, rtol=1e-10, atol=1e-13)
+    np.testing.assert_allclose(gk, dk, rtol=1e-10, atol=1e-13)
+    np.testing.assert_allclose(gv, dv, rtol=1e-10, atol=1e-13)
+
+
+# ------------------------------------------------------------------ finite differences
+
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("alibi", [False, True])
+def test_backward_by_central_finite_differences(causal, alibi):
+    # L = sum(O * dO); dL/dx by central differences on every input element (N=5, d=3).
+    B, H, N, d = 1, 2, 5, 3
+    q, k, v, dout = (_rand(B, H, N, d) for _ in range(4))
+    slopes = _alibi_slopes(H) if alibi else None
+    bias = -0.4
+
+    def loss(q_, k_, v_):
+        return float((orc.sigmoid_attn_fwd(q_, k_, v_, bias, causal, slopes) * dout).sum())
+
+    dq, dk, dv = orc.sigmoid_attn_bwd(q, k, v, dout, bias, causal, slopes)
+    eps = 1e-5
+    for name, x, g in (("q", q, dq), ("k", k, dk), ("v", v, dv)):
+        num = np.zeros_like(x)
+        it = np.nditer(x, flags=["multi_index"])
+        for _ in it:
+            idx = it.multi_index
+            xp, xm = x.copy(), x.copy()
+            xp[idx] += eps
+            xm[idx] -= eps
+            args_p = {"q": (xp, k, v), "k": (q, xp, v), "v": (q, k, xp)}[name]
+            args_m = {"q": (xm, k, v), "k": (q, xm, v), "v": (q, k, xm)}[name]
+            num[idx] = (loss(*args_p) - loss(*args_m)) / (2 * eps)
+        np.testing.assert_allclose(g, num, rtol=2e-7, atol=1e-9, err_msg=name)
+
+
+def test_zero_logit_gradients_closed_form():
+    # Q=0: dV_j = sigma(b) sum_i dO_i ;  dQ_i = sigma(b)(1-sigma(b))/sqrt(d) sum_j (dO_i.V_j) K_j
+    B, H, N, d = 1, 1, 7, 4
+    k, v, dout = _rand(B, H, N, d), _rand(B, H, N, d), _rand(B, H, N, d)
+    q = np.zeros_like(k)
+    b = -1.2
+    sb = 1 / (1 + math.exp(-b))
+    dq, dk, dv = orc.sigmoid_attn_bwd(q, k, v, dout, b)
+    np.testing.assert_allclose(dv, np.broadcast_to(sb * dout.sum(2, keepdims=True), v.shape), rtol=1e-13)
+    dp = np.einsum("bhid,bhjd->bhij", dout, v)
+    np.testing.assert_allclose(dq, sb * (1 - sb) / math.sqrt(d) * (dp @ k), rtol=1e-12, atol=1e-14)
+    np.testing.assert_allclose(dk, 0.0, atol=1e-15)   # dK = dS^T Q / sqrt(d) and Q = 0
+
+
+# ------------------------------------------------------------------ sampled-row entry points
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_row_sampling_entry_points_match_full_pass(causal):
+    B, H, N, d = 1, 2, 50, 8
+    q, k, v, dout = (_rand(B, H, N, d) for _ in range(4))
+    slopes = _alibi_slopes(H)
+    bias = -math.log(N)
+    o = orc.sigmoid_attn_fwd(q, k, v, bias, causal, slopes)
+    dq, dk, dv = orc.sigmoid_attn_bwd(q, k, v, dout, bias, causal, slopes)
+    rows = [0, 1, 17, 49]
+    for h in range(H):
+        a = (q[0, h], k[0, h], v[0, h])
+        np.testing.assert_allclose(orc.sigmoid_attn_fwd_rows(*a, bias, causal, slopes[h], rows), o[0, h, rows],
+                                   rtol=1e-13, atol=1e-15)
+        np.testing.assert_allclose(orc.sigmoid_attn_dq_rows(*a, dout[0, h], bias, causal, slopes[h], rows),
+                                   dq[0, h, rows], rtol=1e-12, atol=1e-15)
+        rk, rv = orc.sigmoid_attn_dkdv_rows(*a, dout[0, h], bias, causal, slopes[h], rows)
+        np.testing.assert_allclose(rk, dk[0, h, rows], rtol=1e-12, atol=1e-15)
+        np.testing.assert_allclose(rv, dv[0, h, rows], rtol=1e-12, atol=1e-15)
+
+
+def test_planted_mistakes_are_caught_by_the_pins():
+    """The pins above are only useful if plausible mistakes break them.  Re-evaluate three
+    pins against deliberately wrong variants (written here, in torch) and check they fail."""
+    N, d = 6, 4
+    q, k, v = _rand(1, 1, N, d), _rand(1, 1, N, d), _rand(1, 1, N, d)
+    good = orc.sigmoid_attn_fwd(q, k, v, -0.5)
+
+    def variant(scale, bias_inside, transpose):
+        s = np.einsum("bhid,bhjd->bhij", q, k)
+        if transpose:
+            s = s.transpose(0, 1, 3, 2)
+        s = (s + (-0.5 if bias_inside else 0.0)) * scale + (0.0 if bias_inside else -0.5)
+        return (1 / (1 + np.exp(-s))) @ v
+
+    assert np.allclose(variant(1 / math.sqrt(d), False, False), good, rtol=1e-12)
+    assert not np.allclose(variant(1.0, False, False), good, rtol=1e-6)            # dropped scale
+    assert not np.allclose(variant(1 / math.sqrt(d), True, False), good, rtol=1e-6)  # bias before scale
+    assert not np.allclose(variant(1 / math.sqrt(d), False, True), good, rtol=1e-6)  # Q/K swapped
