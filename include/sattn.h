@@ -1,0 +1,127 @@
+/*
+ * sattn.h -- C ABI of the MI355X (gfx950) fused sigmoid-attention library.
+ *
+ * The library computes, per (batch, head), with Q, K, V of shape [N, d]:
+ *
+ *     S = Q K^T / sqrt(d)                     (paper: Appendix F.1 table, "Forward")
+ *     T = S + bias - slope_h * |i - j|        (bias: Section 2 boxed equation, b = -log n in
+ *                                              practice, Appendix E; ALiBi: Appendix F.4)
+ *     P = sigmoid(T), P_ij = 0 if causal and j > i   (mask keeps the diagonal, Appendix G.1)
+ *     O = P V                                 (Algorithm 1)
+ *
+ * and the recompute-based backward of Algorithm 2, which needs only Q, K, V, dO:
+ *
+ *     dV = P^T dO,  dP = dO V^T,  dS = P (1 - P) dP,
+ *     dQ = dS K / sqrt(d),  dK = dS^T Q / sqrt(d).
+ *
+ * (The paper's table prints sqrt(d) in the last two; with S scaled by 1/sqrt(d) the chain
+ * rule gives 1/sqrt(d), which is what is implemented.)  No row maximum, row sum or
+ * log-sum-exp is kept between the passes.  A softmax flash-attention pair built on the
+ * same tiling is exported for on-chip comparison (Appendix F.1 table, left half).
+ *
+ * Conventions for every entry point
+ *  - All tensor pointers are DEVICE pointers.  The caller owns every buffer; the library
+ *    never allocates, frees or keeps device memory.
+ *  - Tensors are [B, H, N, d] with the last dimension contiguous.  A NULL strides pointer
+ *    means fully contiguous [B, H, N, d]; otherwise strides are in ELEMENTS and must be
+ *    multiples of 8 (bf16) or 4 (f32) so that rows stay 16-byte aligned.  Base pointers
+ *    must be 16-byte aligned.
+ *  - d must be 64 or 128.  N >= 1 need not be a multiple of any tile size.
+ *  - SATTN_BF16: inputs/outputs bf16, logits, sigmoid and accumulation in fp32, P and dS
+ *    rounded to bf16 before the second matrix product.  SATTN_F32: everything fp32.
+ *  - bias is the scalar b in natural-log units (callers pass -log(N)); alibi_slopes is a
+ *    device pointer to H floats or NULL; causal is 0 or 1.
+ *  - Calls are asynchronous on `stream` (a hipStream_t; NULL = default stream).  No hidden
+ *    synchronisation, no global state; thread safe.
+ *  - Return 0 on success, a negative SATTN_ERR_* otherwise.  On error nothing is launched
+ *    and nothing is written.
+ */
+#ifndef SATTN_H_
+#define SATTN_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { SATTN_BF16 = 0, SATTN_F32 = 1 } sattn_dtype;
+
+typedef struct {
+  int64_t batch; /* elements between consecutive batches */
+  int64_t head;  /* elements between consecutive heads   */
+  int64_t seq;   /* elements between consecutive tokens  */
+} sattn_strides;
+
+enum {
+  SATTN_OK = 0,
+  SATTN_ERR_NULL = -1,        /* a required pointer is NULL */
+  SATTN_ERR_SHAPE = -2,       /* B, H or N not positive, or too large for 32-bit tile indexing */
+  SATTN_ERR_UNSUPPORTED = -3, /* d not in {64,128} or unknown dtype */
+  SATTN_ERR_ALIGN = -4,       /* pointer or stride breaks the 16-byte rule */
+  SATTN_ERR_WORKSPACE = -5,   /* workspace NULL or smaller than *_workspace_bytes() */
+  SATTN_ERR_LAUNCH = -6       /* the HIP runtime rejected the launch */
+};
+
+/* Forward pass of sigmoid attention (Algorithm 1): writes O only. */
+int sigmoid_attn_fwd(const void* q, const void* k, const void* v, void* o,
+                     int B, int H, int N, int d, sattn_dtype dtype,
+                     float bias, int causal, const float* alibi_slopes,
+                     const sattn_strides* sq, const sattn_strides* sk,
+                     const sattn_strides* sv, const sattn_strides* so,
+                     void* stream);
+
+/* Backward pass of sigmoid attention (Algorithm 2): reads Q, K, V, dO; writes dQ, dK, dV.
+ * P is recomputed on chip; neither O nor any per-row statistic is read.  No gradient is
+ * produced for bias or alibi_slopes.  `workspace` must hold at least
+ * sigmoid_attn_bwd_workspace_bytes() bytes (may be NULL when that is 0); its contents on
+ * entry are ignored. */
+int sigmoid_attn_bwd(const void* q, const void* k, const void* v, const void* dout,
+                     void* dq, void* dk, void* dv,
+                     int B, int H, int N, int d, sattn_dtype dtype,
+                     float bias, int causal, const float* alibi_slopes,
+                     const sattn_strides* sq, const sattn_strides* sk,
+                     const sattn_strides* sv, const sattn_strides* sdout,
+                     const sattn_strides* sdq, const sattn_strides* sdk,
+                     const sattn_strides* sdv,
+                     void* workspace, size_t workspace_bytes, void* stream);
+
+size_t sigmoid_attn_bwd_workspace_bytes(int B, int H, int N, int d, sattn_dtype dtype);
+
+/* Softmax flash attention with the same tiling, for comparison (Appendix F.1 table, left
+ * half).  lse is [B, H, N] fp32, contiguous, natural-log units: lse_i = log sum_j exp(T_ij)
+ * with T = S - slope_h |i-j| (no bias: a constant shift cancels). */
+int softmax_attn_fwd(const void* q, const void* k, const void* v, void* o, float* lse,
+                     int B, int H, int N, int d, sattn_dtype dtype,
+                     int causal, const float* alibi_slopes,
+                     const sattn_strides* sq, const sattn_strides* sk,
+                     const sattn_strides* sv, const sattn_strides* so,
+                     void* stream);
+
+/* Softmax backward: dS = P (dP - rowsum(dO o O)); reads O and lse from the forward.
+ * The workspace holds the rowsum vector D [B,H,N] fp32. */
+int softmax_attn_bwd(const void* q, const void* k, const void* v, const void* o,
+                     const float* lse, const void* dout,
+                     void* dq, void* dk, void* dv,
+                     int B, int H, int N, int d, sattn_dtype dtype,
+                     int causal, const float* alibi_slopes,
+                     const sattn_strides* sq, const sattn_strides* sk,
+                     const sattn_strides* sv, const sattn_strides* so,
+                     const sattn_strides* sdout,
+                     const sattn_strides* sdq, const sattn_strides* sdk,
+                     const sattn_strides* sdv,
+                     void* workspace, size_t workspace_bytes, void* stream);
+
+size_t softmax_attn_bwd_workspace_bytes(int B, int H, int N, int d, sattn_dtype dtype);
+
+/* Human-readable text for an SATTN_ERR_* code (static storage). */
+const char* sattn_strerror(int code);
+
+/* Library version: major*10000 + minor*100 + patch. */
+int sattn_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SATTN_H_ */

@@ -1,0 +1,19 @@
+"""MI355X-native fused sigmoid attention (forward + recompute backward) behind a C ABI.
+
+`binding` holds thin ctypes wrappers with the same names as the C entry points;
+`workloads` holds the seeded synthetic input recipes.  Importing this package does not
+load the HIP library; the first call does, and fails loudly if it is missing.
+"""
+from .binding import (  # noqa: F401
+    SattnError,
+    library_path,
+    load_library,
+    sigmoid_attn_bwd,
+    sigmoid_attn_bwd_workspace_bytes,
+    sigmoid_attn_fwd,
+    softmax_attn_bwd,
+    softmax_attn_bwd_workspace_bytes,
+    softmax_attn_fwd,
+    sattn_strerror,
+    sattn_version,
+)

@@ -1,0 +1,182 @@
+"""ctypes binding of libsattn.so: argument marshalling only.
+
+Every function mirrors the C entry point of the same name in include/sattn.h.  Tensors are
+torch CUDA tensors of shape [B, H, N, d] (any strides with a contiguous last dimension);
+PyTorch is used for device memory and the current stream, nothing else.  There is no CPU
+fallback: if the library cannot be loaded the call raises.
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libsattn.so")
+_lib = None
+
+SATTN_BF16, SATTN_F32 = 0, 1
+
+
+class SattnError(RuntimeError):
+    pass
+
+
+class _Strides(ctypes.Structure):
+    _fields_ = [("batch", ctypes.c_int64), ("head", ctypes.c_int64), ("seq", ctypes.c_int64)]
+
+
+_SP = ctypes.POINTER(_Strides)
+_vp = ctypes.c_void_p
+
+
+def library_path():
+    return _LIB_PATH
+
+
+def load_library():
+    """Load libsattn.so (built by paper_2409_04431_amd.build / __graft_entry__.build)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise SattnError(f"{_LIB_PATH} is missing: build it first (python -m paper_2409_04431_amd.build)")
+    lib = ctypes.CDLL(_LIB_PATH)
+    i, f, sz = ctypes.c_int, ctypes.c_float, ctypes.c_size_t
+    lib.sigmoid_attn_fwd.argtypes = [_vp, _vp, _vp, _vp, i, i, i, i, i, f, i, _vp, _SP, _SP, _SP, _SP, _vp]
+    lib.sigmoid_attn_fwd.restype = i
+    lib.sigmoid_attn_bwd.argtypes = [_vp] * 7 + [i, i, i, i, i, f, i, _vp] + [_SP] * 7 + [_vp, sz, _vp]
+    lib.sigmoid_attn_bwd.restype = i
+    lib.sigmoid_attn_bwd_workspace_bytes.argtypes = [i, i, i, i, i]
+    lib.sigmoid_attn_bwd_workspace_bytes.restype = sz
+    lib.softmax_attn_fwd.argtypes = [_vp, _vp, _vp, _vp, _vp, i, i, i, i, i, i, _vp, _SP, _SP, _SP, _SP, _vp]
+    lib.softmax_attn_fwd.restype = i
+    lib.softmax_attn_bwd.argtypes = [_vp] * 9 + [i, i, i, i, i, i, _vp] + [_SP] * 8 + [_vp, sz, _vp]
+    lib.softmax_attn_bwd.restype = i
+    lib.softmax_attn_bwd_workspace_bytes.argtypes = [i, i, i, i, i]
+    lib.softmax_attn_bwd_workspace_bytes.restype = sz
+    lib.sattn_strerror.argtypes = [i]
+    lib.sattn_strerror.restype = ctypes.c_char_p
+    lib.sattn_version.argtypes = []
+    lib.sattn_version.restype = i
+    _lib = lib
+    return lib
+
+
+def sattn_strerror(code):
+    return load_library().sattn_strerror(int(code)).decode()
+
+
+def sattn_version():
+    return int(load_library().sattn_version())
+
+
+def _dtype_code(t):
+    if t.dtype == torch.bfloat16:
+        return SATTN_BF16
+    if t.dtype == torch.float32:
+        return SATTN_F32
+    raise SattnError(f"unsupported dtype {t.dtype}")
+
+
+def _check(*ts):
+    t0 = ts[0]
+    for t in ts:
+        if not t.is_cuda:
+            raise SattnError("tensors must live on the GPU")
+        if t.dim() != 4 or t.shape != t0.shape or t.dtype != t0.dtype:
+            raise SattnError("tensors must share one [B,H,N,d] shape and dtype")
+        if t.stride(3) != 1:
+            raise SattnError("the last dimension must be contiguous")
+
+
+def _st(t):
+    return ctypes.byref(_Strides(t.stride(0), t.stride(1), t.stride(2)))
+
+
+def _stream():
+    return _vp(torch.cuda.current_stream().cuda_stream)
+
+
+def _slopes_ptr(alibi_slopes, H):
+    if alibi_slopes is None:
+        return None
+    if alibi_slopes.dtype != torch.float32 or not alibi_slopes.is_cuda or alibi_slopes.numel() != H \
+            or not alibi_slopes.is_contiguous():
+        raise SattnError("alibi_slopes must be a contiguous CUDA float32 tensor of H elements")
+    return _vp(alibi_slopes.data_ptr())
+
+
+def _raise(rc, what):
+    if rc != 0:
+        raise SattnError(f"{what} failed: {sattn_strerror(rc)} ({rc})")
+
+
+def sigmoid_attn_fwd(q, k, v, o, bias, causal=False, alibi_slopes=None):
+    """O = sigmoid(Q K^T/sqrt(d) + bias [- slope|i-j|], causal mask) V, written into `o`."""
+    lib = load_library()
+    _check(q, k, v, o)
+    B, H, N, d = q.shape
+    rc = lib.sigmoid_attn_fwd(q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(), B, H, N, d, _dtype_code(q),
+                              float(bias), int(bool(causal)), _slopes_ptr(alibi_slopes, H),
+                              _st(q), _st(k), _st(v), _st(o), _stream())
+    _raise(rc, "sigmoid_attn_fwd")
+    return o
+
+
+def sigmoid_attn_bwd_workspace_bytes(B, H, N, d, dtype=torch.bfloat16):
+    code = SATTN_BF16 if dtype == torch.bfloat16 else SATTN_F32
+    return int(load_library().sigmoid_attn_bwd_workspace_bytes(B, H, N, d, code))
+
+
+def sigmoid_attn_bwd(q, k, v, dout, dq, dk, dv, bias, causal=False, alibi_slopes=None, workspace=None):
+    """dQ, dK, dV of sigmoid attention from Q, K, V, dO (P is recomputed), written in place."""
+    lib = load_library()
+    _check(q, k, v, dout, dq, dk, dv)
+    B, H, N, d = q.shape
+    need = sigmoid_attn_bwd_workspace_bytes(B, H, N, d, q.dtype)
+    if workspace is None and need:
+        workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+    wp = _vp(workspace.data_ptr()) if workspace is not None else None
+    wb = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    rc = lib.sigmoid_attn_bwd(q.data_ptr(), k.data_ptr(), v.data_ptr(), dout.data_ptr(), dq.data_ptr(),
+                              dk.data_ptr(), dv.data_ptr(), B, H, N, d, _dtype_code(q), float(bias),
+                              int(bool(causal)), _slopes_ptr(alibi_slopes, H), _st(q), _st(k), _st(v), _st(dout),
+                              _st(dq), _st(dk), _st(dv), wp, wb, _stream())
+    _raise(rc, "sigmoid_attn_bwd")
+    return dq, dk, dv
+
+
+def softmax_attn_fwd(q, k, v, o, lse, causal=False, alibi_slopes=None):
+    """Softmax flash attention forward (comparison kernel); lse is [B,H,N] float32."""
+    lib = load_library()
+    _check(q, k, v, o)
+    B, H, N, d = q.shape
+    if lse.dtype != torch.float32 or not lse.is_cuda or tuple(lse.shape) != (B, H, N) or not lse.is_contiguous():
+        raise SattnError("lse must be a contiguous CUDA float32 tensor [B,H,N]")
+    rc = lib.softmax_attn_fwd(q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(), lse.data_ptr(), B, H, N, d,
+                              _dtype_code(q), int(bool(causal)), _slopes_ptr(alibi_slopes, H),
+                              _st(q), _st(k), _st(v), _st(o), _stream())
+    _raise(rc, "softmax_attn_fwd")
+    return o, lse
+
+
+def softmax_attn_bwd_workspace_bytes(B, H, N, d, dtype=torch.bfloat16):
+    code = SATTN_BF16 if dtype == torch.bfloat16 else SATTN_F32
+    return int(load_library().softmax_attn_bwd_workspace_bytes(B, H, N, d, code))
+
+
+def softmax_attn_bwd(q, k, v, o, lse, dout, dq, dk, dv, causal=False, alibi_slopes=None, workspace=None):
+    lib = load_library()
+    _check(q, k, v, o, dout, dq, dk, dv)
+    B, H, N, d = q.shape
+    need = softmax_attn_bwd_workspace_bytes(B, H, N, d, q.dtype)
+    if workspace is None and need:
+        workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+    wp = _vp(workspace.data_ptr()) if workspace is not None else None
+    wb = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    rc = lib.softmax_attn_bwd(q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(), lse.data_ptr(),
+                              dout.data_ptr(), dq.data_ptr(), dk.data_ptr(), dv.data_ptr(), B, H, N, d,
+                              _dtype_code(q), int(bool(causal)), _slopes_ptr(alibi_slopes, H),
+                              _st(q), _st(k), _st(v), _st(o), _st(dout), _st(dq), _st(dk), _st(dv), wp, wb, _stream())
+    _raise(rc, "softmax_attn_bwd")
+    return dq, dk, dv

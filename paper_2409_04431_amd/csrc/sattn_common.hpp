@@ -1,0 +1,86 @@
+// Device-side building blocks shared by the gfx950 attention kernels: vector types, MFMA
+// wrappers, fragment/LDS index maps.  HIP for CDNA4 only.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace sattn {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+#define SATTN_LDS(T) __attribute__((address_space(3))) T
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+// One tensor as the kernels see it: base pointer plus element strides (d contiguous).
+struct TensorRef {
+  void* ptr;
+  int64_t sb, sh, ss;
+};
+
+// ---- MFMA 32x32x16 bf16 (D = A*B + C).  Fragment maps for lane l (l32 = l%32, h = l/32):
+//   A (32 x 16): row l32, k = 8h + slot            (8 bf16 per lane)
+//   B (16 x 32): col l32, k = 8h + slot
+//   C (32 x 32): col l32, row = 8*(r/4) + 4h + r%4 (16 fp32 per lane, r = register)
+// The contraction index may be permuted freely as long as A and B use the same map.
+__device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
+__device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
+
+// fp32 pair -> packed bf16 (round to nearest even), low half = a.
+__device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
+  bf16x2 v = {(__bf16)a, (__bf16)b};
+  return __builtin_bit_cast(uint32_t, v);
+}
+
+// Row permutation that makes the accumulator of S^T = K Q^T directly usable as the B
+// operand of the next product.  A-row m of the S^T MFMA is fed with key kappa(m) (bits 2
+// and 3 of m swapped); then register r = 4g + t of lane half h holds key
+// 16*(g/2) + 8h + 4*(g%2) + t, i.e. registers 8ks..8ks+7 are eight consecutive keys
+// 16ks + 8h + (0..7): exactly the k-slots of B for contraction step ks.
+__device__ __forceinline__ int kappa(int m) { return (m & 0x13) | ((m & 4) << 1) | ((m & 8) >> 1); }
+// key offset (inside a 32-key chunk, without the 8h lane-half term) held by register r
+__host__ __device__ constexpr int key_of_reg(int r) { return 16 * (r >> 3) + (r & 7); }
+
+// Transposing LDS read (ds_read_b64_tr_b16).  Within each block of 16 lanes, lane i
+// receives 16-bit element (i % 4) of the 8 bytes addressed by lane 4j + i/4, for j = 0..3.
+// Pointing lanes 4j..4j+3 at 16 contiguous elements of row j therefore hands lane i the
+// four rows' element i: a 4 (k) x 16 (m) block read in "k-major per lane" order.
+__device__ __forceinline__ s16x4 lds_read_tr16(uint32_t lds_byte_addr) {
+  return __builtin_amdgcn_ds_read_tr16_b64_v4i16((SATTN_LDS(s16x4)*)(uintptr_t)lds_byte_addr);
+}
+
+__device__ __forceinline__ bf16x8 join_tr(s16x4 lo, s16x4 hi) {
+  typedef short s16x8 __attribute__((ext_vector_type(8)));
+  s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+  return __builtin_bit_cast(bf16x8, v);
+}
+
+__device__ __forceinline__ u32x4 lds_read_b128(uint32_t lds_byte_addr) {
+  return *(SATTN_LDS(u32x4)*)(uintptr_t)lds_byte_addr;
+}
+__device__ __forceinline__ void lds_write_b128(uint32_t lds_byte_addr, u32x4 v) {
+  *(SATTN_LDS(u32x4)*)(uintptr_t)lds_byte_addr = v;
+}
+
+// Workgroup id -> logical tile id so that consecutive logical ids (which share a head's
+// K/V) land on the same XCD and hence the same L2: hardware deals workgroup ids round-robin
+// over the 8 XCDs.
+__device__ __forceinline__ int xcd_remap(int bid, int total) {
+  constexpr int kXcd = 8;
+  int xcd = bid % kXcd, slot = bid / kXcd;
+  int c = total / kXcd, r = total % kXcd;
+  return xcd * c + (xcd < r ? xcd : r) + slot;
+}
+
+}  // namespace sattn
