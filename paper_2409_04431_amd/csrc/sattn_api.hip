@@ -5,6 +5,7 @@
 #include <hip/hip_runtime.h>
 #include <math.h>
 
+#include "sattn_bwd.hpp"
 #include "sattn_fwd.hpp"
 
 using namespace sattn;
@@ -39,8 +40,8 @@ int check_shape(int B, int H, int N, int d, sattn_dtype dt) {
   return SATTN_OK;
 }
 
-template <typename K>
-int launch(K kernel, dim3 grid, dim3 block, size_t lds, hipStream_t st, const FwdParams& p) {
+template <typename K, typename P>
+int launch(K kernel, dim3 grid, dim3 block, size_t lds, hipStream_t st, const P& p) {
   if (hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
     (void)hipGetLastError();
     return SATTN_ERR_LAUNCH;
@@ -59,6 +60,29 @@ int launch_sigmoid_fwd(const FwdParams& p, int causal, bool alibi, hipStream_t s
   }
   if (alibi) return launch(sigmoid_fwd_kernel<D, BC, NW, false, true>, grid, block, lds, st, p);
   return launch(sigmoid_fwd_kernel<D, BC, NW, false, false>, grid, block, lds, st, p);
+}
+
+template <int D, int BC, int NW>
+int launch_sigmoid_bwd(BwdParams p, int causal, bool alibi, hipStream_t st) {
+  constexpr size_t lds = 4 * BC * D * 2;
+  const int nblk = (p.N + 32 * NW - 1) / (32 * NW);
+  p.n_blocks = nblk;
+  dim3 grid(nblk * p.B * p.H), block(64 * NW);
+  int rc;
+  if (causal) {
+    if (alibi) {
+      if ((rc = launch(sigmoid_bwd_dkdv_kernel<D, BC, NW, true, true>, grid, block, lds, st, p))) return rc;
+      return launch(sigmoid_bwd_dq_kernel<D, BC, NW, true, true>, grid, block, lds, st, p);
+    }
+    if ((rc = launch(sigmoid_bwd_dkdv_kernel<D, BC, NW, true, false>, grid, block, lds, st, p))) return rc;
+    return launch(sigmoid_bwd_dq_kernel<D, BC, NW, true, false>, grid, block, lds, st, p);
+  }
+  if (alibi) {
+    if ((rc = launch(sigmoid_bwd_dkdv_kernel<D, BC, NW, false, true>, grid, block, lds, st, p))) return rc;
+    return launch(sigmoid_bwd_dq_kernel<D, BC, NW, false, true>, grid, block, lds, st, p);
+  }
+  if ((rc = launch(sigmoid_bwd_dkdv_kernel<D, BC, NW, false, false>, grid, block, lds, st, p))) return rc;
+  return launch(sigmoid_bwd_dq_kernel<D, BC, NW, false, false>, grid, block, lds, st, p);
 }
 
 }  // namespace
@@ -88,12 +112,37 @@ int sigmoid_attn_fwd(const void* q, const void* k, const void* v, void* o, int B
   return launch_sigmoid_fwd<64, 64, NW>(p, causal, alibi_slopes != nullptr, st);
 }
 
-// ---- not built yet: report it instead of pretending
-int sigmoid_attn_bwd(const void*, const void*, const void*, const void*, void*, void*, void*, int, int, int, int,
-                     sattn_dtype, float, int, const float*, const sattn_strides*, const sattn_strides*,
-                     const sattn_strides*, const sattn_strides*, const sattn_strides*, const sattn_strides*,
-                     const sattn_strides*, void*, size_t, void*) { return SATTN_ERR_UNSUPPORTED; }
+int sigmoid_attn_bwd(const void* q, const void* k, const void* v, const void* dout, void* dq, void* dk, void* dv,
+                     int B, int H, int N, int d, sattn_dtype dtype, float bias, int causal,
+                     const float* alibi_slopes, const sattn_strides* sq, const sattn_strides* sk,
+                     const sattn_strides* sv, const sattn_strides* sdout, const sattn_strides* sdq,
+                     const sattn_strides* sdk, const sattn_strides* sdv, void* workspace, size_t workspace_bytes,
+                     void* stream) {
+  (void)workspace; (void)workspace_bytes;  // the two-kernel split needs none
+  int rc = check_shape(B, H, N, d, dtype);
+  if (rc) return rc;
+  BwdParams p{};
+  if ((rc = make_ref(q, sq, H, N, d, dtype, &p.q))) return rc;
+  if ((rc = make_ref(k, sk, H, N, d, dtype, &p.k))) return rc;
+  if ((rc = make_ref(v, sv, H, N, d, dtype, &p.v))) return rc;
+  if ((rc = make_ref(dout, sdout, H, N, d, dtype, &p.dout))) return rc;
+  if ((rc = make_ref(dq, sdq, H, N, d, dtype, &p.dq))) return rc;
+  if ((rc = make_ref(dk, sdk, H, N, d, dtype, &p.dk))) return rc;
+  if ((rc = make_ref(dv, sdv, H, N, d, dtype, &p.dv))) return rc;
+  p.slopes = alibi_slopes;
+  p.B = B; p.H = H; p.N = N;
+  p.inv_sqrt_d = 1.0f / sqrtf((float)d);
+  p.nscale_log2 = -kLog2e * p.inv_sqrt_d;
+  p.nbias_log2 = -bias * kLog2e;
+  hipStream_t st = (hipStream_t)stream;
+  if (dtype == SATTN_F32) return SATTN_ERR_UNSUPPORTED;
+  if (d == 128) return launch_sigmoid_bwd<128, 64, 4>(p, causal, alibi_slopes != nullptr, st);
+  return launch_sigmoid_bwd<64, 64, 4>(p, causal, alibi_slopes != nullptr, st);
+}
+
 size_t sigmoid_attn_bwd_workspace_bytes(int, int, int, int, sattn_dtype) { return 0; }
+
+// ---- not built yet: report it instead of pretending
 int softmax_attn_fwd(const void*, const void*, const void*, void*, float*, int, int, int, int, sattn_dtype, int,
                      const float*, const sattn_strides*, const sattn_strides*, const sattn_strides*,
                      const sattn_strides*, void*) { return SATTN_ERR_UNSUPPORTED; }
