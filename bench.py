@@ -1,0 +1,180 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused sigmoid-attention hot path on one MI355X.
+
+A step = one forward + one backward (dK/dV kernel, dQ kernel) of sigmoid attention on the
+headline workload (B=8, H=16, N=4096, d=128, bf16, causal, b = -log N).  Inputs are
+synthetic, seeded, and already resident in HBM when timing starts.  Prints ONE JSON line.
+
+FLOP convention (Table 1 of the paper): forward 4*B*H*N^2*d, backward 10*B*H*N^2*d,
+halved when causal; recomputation is never counted.
+"""
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 matrix peak
+
+# HBM bytes per launch of the dominant kernel, from `rocprofv3 --pmc FETCH_SIZE` and
+# `--pmc WRITE_SIZE` runs of this script (summaries under profiles/); None until measured.
+MEASURED_TRAFFIC_BYTES = None
+
+
+def _events(n):
+    import torch
+    return [torch.cuda.Event(enable_timing=True) for _ in range(n)]
+
+
+def cpu_baseline(cfg, seconds_hint=20.0):
+    """Time the fp64 CPU oracle (as it stands) on a bounded sample of the same workload:
+    one forward + backward over `threads` heads of the headline shape (one head per core)."""
+    import torch
+    from oracle import sattn_oracle as orc
+    threads = orc.num_threads()
+    heads = 2 * max(1, threads)
+    N, d = cfg.N, cfg.d
+    # keep the sample near seconds_hint: two heads per core, ~14*N^2*d/2 flops each at roughly 2 GFLOP/s/core
+    while N > 512 and 2 * 14.0 * N * N * d / 2 / 2.0e9 > seconds_hint:
+        N //= 2
+    g = torch.Generator().manual_seed(4242)
+    q, k, v, do = (torch.randn(1, heads, N, d, generator=g).bfloat16() for _ in range(4))
+    bias = -math.log(N)
+    t0 = time.perf_counter()
+    orc.sigmoid_attn_fwd(q, k, v, bias, cfg.causal)
+    orc.sigmoid_attn_bwd(q, k, v, do, bias, cfg.causal)
+    dt = time.perf_counter() - t0
+    flops = 14.0 * heads * N * N * d * (0.5 if cfg.causal else 1.0)
+    return {
+        "value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": threads, "kind": "oracle",
+        "sample": f"fwd+bwd of {heads} heads, N={N}, d={d}, causal={cfg.causal}, fp64 C/OpenMP oracle, {dt:.1f} s",
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--cfg", type=int, default=3, help="workload id (1-5); the headline metric is quoted on 3")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--softmax", action="store_true", help="also time the softmax comparison kernels")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build is single-GPU; the path shards over (batch, head) with no exchange, "
+                 "so only --gpus 1 is measured here")
+
+    import torch
+    import paper_2409_04431_amd as sa
+    from paper_2409_04431_amd import workloads as W
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    sa.load_library()
+    cfg = W.CONFIGS[args.cfg]
+    dev = torch.device("cuda:0")
+    torch.manual_seed(1000 + cfg.cfg)
+    shape = (cfg.B, cfg.H, cfg.N, cfg.d)
+    q, k, dout = ((torch.randn(shape, device=dev) * s).to(cfg.dtype) for s in (cfg.qkv_scale, cfg.qkv_scale, 1.0))
+    if cfg.v_uniform:
+        v = (torch.rand(shape, device=dev) * 2 - 1).to(cfg.dtype)
+    else:
+        v = (torch.randn(shape, device=dev) * cfg.qkv_scale).to(cfg.dtype)
+    slopes = W.alibi_slopes(cfg.H).to(dev) if cfg.alibi else None
+    o, dq, dk, dv = (torch.empty_like(q) for _ in range(4))
+    bias = cfg.bias
+
+    def step(ev=None):
+        if ev: ev[0].record()
+        sa.sigmoid_attn_fwd(q, k, v, o, bias, cfg.causal, slopes)
+        if ev: ev[1].record()
+        if cfg.backward:
+            sa.sigmoid_attn_bwd_dkdv(q, k, v, dout, dk, dv, bias, cfg.causal, slopes)
+            if ev: ev[2].record()
+            sa.sigmoid_attn_bwd_dq(q, k, v, dout, dq, bias, cfg.causal, slopes)
+            if ev: ev[3].record()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    evs = [_events(4) for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(evs[i])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_step = wall * 1e3 / args.steps
+
+    fwd_ms = sum(e[0].elapsed_time(e[1]) for e in evs) / args.steps
+    flops_f, flops_b = cfg.fwd_flops(), cfg.bwd_flops()
+    out = {
+        "metric": "sigmoid-attn fwd+bwd TFLOP/s (N=4096,d=128)" if cfg.cfg == 3 else
+                  f"sigmoid-attn {'fwd+bwd' if cfg.backward else 'fwd'} TFLOP/s",
+        "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if cfg.dtype == torch.bfloat16 else "f32", "data": "synthetic",
+        "config": {"workload": cfg.name, "B": cfg.B, "H": cfg.H, "N": cfg.N, "d": cfg.d, "causal": cfg.causal,
+                   "alibi": cfg.alibi, "bias": bias, "flop_convention": "fwd 4BHN^2d, bwd 10BHN^2d, x0.5 causal"},
+        "fwd_ms": fwd_ms, "fwd_tflops": flops_f / fwd_ms / 1e9,
+        "fwd_frac_of_bf16_mfma_peak": flops_f / fwd_ms / 1e9 / MFMA_BF16_PEAK_TFLOPS,
+    }
+    if cfg.backward:
+        dkdv_ms = sum(e[1].elapsed_time(e[2]) for e in evs) / args.steps
+        dq_ms = sum(e[2].elapsed_time(e[3]) for e in evs) / args.steps
+        total = flops_f + flops_b
+        out["value"] = total / ms_step / 1e9
+        out["frac_of_bf16_mfma_peak"] = out["value"] / MFMA_BF16_PEAK_TFLOPS
+        out.update({"bwd_dkdv_ms": dkdv_ms, "bwd_dq_ms": dq_ms,
+                    "bwd_tflops": flops_b / (dkdv_ms + dq_ms) / 1e9})
+        # dominant kernel: dK/dV.  Algorithmic work attributed to it: S, dP, dV, dK = 4 of the
+        # 5 backward products (8*B*H*N^2*d, halved when causal); dQ's recompute is not counted.
+        algo = 0.8 * flops_b
+        ach = algo / dkdv_ms / 1e9
+        out["roofline"] = {"kernel": "sigmoid_bwd_dkdv_kernel", "bound": "mfma", "achieved": ach,
+                           "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": ach / MFMA_BF16_PEAK_TFLOPS,
+                           "traffic": MEASURED_TRAFFIC_BYTES, "avg_launch_ms": dkdv_ms}
+    else:
+        out["value"] = flops_f / ms_step / 1e9
+        out["frac_of_bf16_mfma_peak"] = out["value"] / MFMA_BF16_PEAK_TFLOPS
+        ach = flops_f / fwd_ms / 1e9
+        out["roofline"] = {"kernel": "sigmoid_fwd_kernel", "bound": "mfma", "achieved": ach,
+                           "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": ach / MFMA_BF16_PEAK_TFLOPS,
+                           "traffic": MEASURED_TRAFFIC_BYTES, "avg_launch_ms": fwd_ms}
+
+    if args.softmax:
+        lse = torch.empty(cfg.B, cfg.H, cfg.N, dtype=torch.float32, device=dev)
+        for _ in range(args.warmup):
+            sa.softmax_attn_fwd(q, k, v, o, lse, cfg.causal, slopes)
+        e = _events(2)
+        e[0].record()
+        for _ in range(args.steps):
+            sa.softmax_attn_fwd(q, k, v, o, lse, cfg.causal, slopes)
+        e[1].record()
+        torch.cuda.synchronize()
+        sm_ms = e[0].elapsed_time(e[1]) / args.steps
+        out["softmax_fwd_ms"] = sm_ms
+        out["softmax_fwd_tflops"] = flops_f / sm_ms / 1e9
+        if cfg.backward:
+            for _ in range(args.warmup):
+                sa.softmax_attn_bwd(q, k, v, o, lse, dout, dq, dk, dv, cfg.causal, slopes)
+            e = _events(2)
+            e[0].record()
+            for _ in range(args.steps):
+                sa.softmax_attn_bwd(q, k, v, o, lse, dout, dq, dk, dv, cfg.causal, slopes)
+            e[1].record()
+            torch.cuda.synchronize()
+            sb_ms = e[0].elapsed_time(e[1]) / args.steps
+            out["softmax_bwd_ms"] = sb_ms
+            out["softmax_bwd_tflops"] = flops_b / sb_ms / 1e9
+
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -89,6 +89,27 @@ int sigmoid_attn_bwd(const void* q, const void* k, const void* v, const void* do
 
 size_t sigmoid_attn_bwd_workspace_bytes(int B, int H, int N, int d, sattn_dtype dtype);
 
+/* The two halves of sigmoid_attn_bwd as separate launches (Algorithm 2 split by output
+ * owner): *_dkdv keeps a key block on chip and streams query blocks (dK_j, dV_j of
+ * Algorithm 2's outer loop); *_dq keeps a query block on chip and streams key blocks, so
+ * dQ_i never round-trips through HBM.  Calling both equals sigmoid_attn_bwd. */
+int sigmoid_attn_bwd_dkdv(const void* q, const void* k, const void* v, const void* dout,
+                          void* dk, void* dv,
+                          int B, int H, int N, int d, sattn_dtype dtype,
+                          float bias, int causal, const float* alibi_slopes,
+                          const sattn_strides* sq, const sattn_strides* sk,
+                          const sattn_strides* sv, const sattn_strides* sdout,
+                          const sattn_strides* sdk, const sattn_strides* sdv,
+                          void* stream);
+int sigmoid_attn_bwd_dq(const void* q, const void* k, const void* v, const void* dout,
+                        void* dq,
+                        int B, int H, int N, int d, sattn_dtype dtype,
+                        float bias, int causal, const float* alibi_slopes,
+                        const sattn_strides* sq, const sattn_strides* sk,
+                        const sattn_strides* sv, const sattn_strides* sdout,
+                        const sattn_strides* sdq,
+                        void* stream);
+
 /* Softmax flash attention with the same tiling, for comparison (Appendix F.1 table, left
  * half).  lse is [B, H, N] fp32, contiguous, natural-log units: lse_i = log sum_j exp(T_ij)
  * with T = S - slope_h |i-j| (no bias: a constant shift cancels). */

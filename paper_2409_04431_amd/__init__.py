@@ -9,6 +9,8 @@ from .binding import (  # noqa: F401
     library_path,
     load_library,
     sigmoid_attn_bwd,
+    sigmoid_attn_bwd_dkdv,
+    sigmoid_attn_bwd_dq,
     sigmoid_attn_bwd_workspace_bytes,
     sigmoid_attn_fwd,
     softmax_attn_bwd,

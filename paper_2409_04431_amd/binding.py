@@ -46,6 +46,10 @@ def load_library():
     lib.sigmoid_attn_fwd.restype = i
     lib.sigmoid_attn_bwd.argtypes = [_vp] * 7 + [i, i, i, i, i, f, i, _vp] + [_SP] * 7 + [_vp, sz, _vp]
     lib.sigmoid_attn_bwd.restype = i
+    lib.sigmoid_attn_bwd_dkdv.argtypes = [_vp] * 6 + [i, i, i, i, i, f, i, _vp] + [_SP] * 6 + [_vp]
+    lib.sigmoid_attn_bwd_dkdv.restype = i
+    lib.sigmoid_attn_bwd_dq.argtypes = [_vp] * 5 + [i, i, i, i, i, f, i, _vp] + [_SP] * 5 + [_vp]
+    lib.sigmoid_attn_bwd_dq.restype = i
     lib.sigmoid_attn_bwd_workspace_bytes.argtypes = [i, i, i, i, i]
     lib.sigmoid_attn_bwd_workspace_bytes.restype = sz
     lib.softmax_attn_fwd.argtypes = [_vp, _vp, _vp, _vp, _vp, i, i, i, i, i, i, _vp, _SP, _SP, _SP, _SP, _vp]
@@ -144,6 +148,31 @@ def sigmoid_attn_bwd(q, k, v, dout, dq, dk, dv, bias, causal=False, alibi_slopes
                               _st(dq), _st(dk), _st(dv), wp, wb, _stream())
     _raise(rc, "sigmoid_attn_bwd")
     return dq, dk, dv
+
+
+def sigmoid_attn_bwd_dkdv(q, k, v, dout, dk, dv, bias, causal=False, alibi_slopes=None):
+    """Key-block-stationary half of the backward: dK and dV only."""
+    lib = load_library()
+    _check(q, k, v, dout, dk, dv)
+    B, H, N, d = q.shape
+    rc = lib.sigmoid_attn_bwd_dkdv(q.data_ptr(), k.data_ptr(), v.data_ptr(), dout.data_ptr(), dk.data_ptr(),
+                                   dv.data_ptr(), B, H, N, d, _dtype_code(q), float(bias), int(bool(causal)),
+                                   _slopes_ptr(alibi_slopes, H), _st(q), _st(k), _st(v), _st(dout), _st(dk),
+                                   _st(dv), _stream())
+    _raise(rc, "sigmoid_attn_bwd_dkdv")
+    return dk, dv
+
+
+def sigmoid_attn_bwd_dq(q, k, v, dout, dq, bias, causal=False, alibi_slopes=None):
+    """Query-block-stationary half of the backward: dQ only."""
+    lib = load_library()
+    _check(q, k, v, dout, dq)
+    B, H, N, d = q.shape
+    rc = lib.sigmoid_attn_bwd_dq(q.data_ptr(), k.data_ptr(), v.data_ptr(), dout.data_ptr(), dq.data_ptr(), B, H, N,
+                                 d, _dtype_code(q), float(bias), int(bool(causal)), _slopes_ptr(alibi_slopes, H),
+                                 _st(q), _st(k), _st(v), _st(dout), _st(dq), _stream())
+    _raise(rc, "sigmoid_attn_bwd_dq")
+    return dq
 
 
 def softmax_attn_fwd(q, k, v, o, lse, causal=False, alibi_slopes=None):

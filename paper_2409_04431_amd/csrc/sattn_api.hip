@@ -62,27 +62,54 @@ int launch_sigmoid_fwd(const FwdParams& p, int causal, bool alibi, hipStream_t s
   return launch(sigmoid_fwd_kernel<D, BC, NW, false, false>, grid, block, lds, st, p);
 }
 
-template <int D, int BC, int NW>
-int launch_sigmoid_bwd(BwdParams p, int causal, bool alibi, hipStream_t st) {
+enum BwdPart { kBwdDkDv = 1, kBwdDq = 2 };
+
+template <int D, int BC, int NW, bool CAUSAL, bool ALIBI>
+int launch_sigmoid_bwd_t(const BwdParams& p, int parts, hipStream_t st) {
   constexpr size_t lds = 4 * BC * D * 2;
-  const int nblk = (p.N + 32 * NW - 1) / (32 * NW);
-  p.n_blocks = nblk;
-  dim3 grid(nblk * p.B * p.H), block(64 * NW);
-  int rc;
+  dim3 grid(p.n_blocks * p.B * p.H), block(64 * NW);
+  int rc = SATTN_OK;
+  if (parts & kBwdDkDv) rc = launch(sigmoid_bwd_dkdv_kernel<D, BC, NW, CAUSAL, ALIBI>, grid, block, lds, st, p);
+  if (rc == SATTN_OK && (parts & kBwdDq))
+    rc = launch(sigmoid_bwd_dq_kernel<D, BC, NW, CAUSAL, ALIBI>, grid, block, lds, st, p);
+  return rc;
+}
+
+template <int D, int BC, int NW>
+int launch_sigmoid_bwd(BwdParams p, int causal, bool alibi, int parts, hipStream_t st) {
+  p.n_blocks = (p.N + 32 * NW - 1) / (32 * NW);
   if (causal) {
-    if (alibi) {
-      if ((rc = launch(sigmoid_bwd_dkdv_kernel<D, BC, NW, true, true>, grid, block, lds, st, p))) return rc;
-      return launch(sigmoid_bwd_dq_kernel<D, BC, NW, true, true>, grid, block, lds, st, p);
-    }
-    if ((rc = launch(sigmoid_bwd_dkdv_kernel<D, BC, NW, true, false>, grid, block, lds, st, p))) return rc;
-    return launch(sigmoid_bwd_dq_kernel<D, BC, NW, true, false>, grid, block, lds, st, p);
+    if (alibi) return launch_sigmoid_bwd_t<D, BC, NW, true, true>(p, parts, st);
+    return launch_sigmoid_bwd_t<D, BC, NW, true, false>(p, parts, st);
   }
-  if (alibi) {
-    if ((rc = launch(sigmoid_bwd_dkdv_kernel<D, BC, NW, false, true>, grid, block, lds, st, p))) return rc;
-    return launch(sigmoid_bwd_dq_kernel<D, BC, NW, false, true>, grid, block, lds, st, p);
-  }
-  if ((rc = launch(sigmoid_bwd_dkdv_kernel<D, BC, NW, false, false>, grid, block, lds, st, p))) return rc;
-  return launch(sigmoid_bwd_dq_kernel<D, BC, NW, false, false>, grid, block, lds, st, p);
+  if (alibi) return launch_sigmoid_bwd_t<D, BC, NW, false, true>(p, parts, st);
+  return launch_sigmoid_bwd_t<D, BC, NW, false, false>(p, parts, st);
+}
+
+int sigmoid_bwd_impl(const void* q, const void* k, const void* v, const void* dout, void* dq, void* dk, void* dv,
+                     int B, int H, int N, int d, sattn_dtype dtype, float bias, int causal,
+                     const float* alibi_slopes, const sattn_strides* sq, const sattn_strides* sk,
+                     const sattn_strides* sv, const sattn_strides* sdout, const sattn_strides* sdq,
+                     const sattn_strides* sdk, const sattn_strides* sdv, int parts, void* stream) {
+  int rc = check_shape(B, H, N, d, dtype);
+  if (rc) return rc;
+  BwdParams p{};
+  if ((rc = make_ref(q, sq, H, N, d, dtype, &p.q))) return rc;
+  if ((rc = make_ref(k, sk, H, N, d, dtype, &p.k))) return rc;
+  if ((rc = make_ref(v, sv, H, N, d, dtype, &p.v))) return rc;
+  if ((rc = make_ref(dout, sdout, H, N, d, dtype, &p.dout))) return rc;
+  if ((parts & kBwdDq) && (rc = make_ref(dq, sdq, H, N, d, dtype, &p.dq))) return rc;
+  if ((parts & kBwdDkDv) && (rc = make_ref(dk, sdk, H, N, d, dtype, &p.dk))) return rc;
+  if ((parts & kBwdDkDv) && (rc = make_ref(dv, sdv, H, N, d, dtype, &p.dv))) return rc;
+  p.slopes = alibi_slopes;
+  p.B = B; p.H = H; p.N = N;
+  p.inv_sqrt_d = 1.0f / sqrtf((float)d);
+  p.nscale_log2 = -kLog2e * p.inv_sqrt_d;
+  p.nbias_log2 = -bias * kLog2e;
+  hipStream_t st = (hipStream_t)stream;
+  if (dtype == SATTN_F32) return SATTN_ERR_UNSUPPORTED;
+  if (d == 128) return launch_sigmoid_bwd<128, 64, 4>(p, causal, alibi_slopes != nullptr, parts, st);
+  return launch_sigmoid_bwd<64, 64, 4>(p, causal, alibi_slopes != nullptr, parts, st);
 }
 
 }  // namespace
@@ -119,25 +146,25 @@ int sigmoid_attn_bwd(const void* q, const void* k, const void* v, const void* do
                      const sattn_strides* sdk, const sattn_strides* sdv, void* workspace, size_t workspace_bytes,
                      void* stream) {
   (void)workspace; (void)workspace_bytes;  // the two-kernel split needs none
-  int rc = check_shape(B, H, N, d, dtype);
-  if (rc) return rc;
-  BwdParams p{};
-  if ((rc = make_ref(q, sq, H, N, d, dtype, &p.q))) return rc;
-  if ((rc = make_ref(k, sk, H, N, d, dtype, &p.k))) return rc;
-  if ((rc = make_ref(v, sv, H, N, d, dtype, &p.v))) return rc;
-  if ((rc = make_ref(dout, sdout, H, N, d, dtype, &p.dout))) return rc;
-  if ((rc = make_ref(dq, sdq, H, N, d, dtype, &p.dq))) return rc;
-  if ((rc = make_ref(dk, sdk, H, N, d, dtype, &p.dk))) return rc;
-  if ((rc = make_ref(dv, sdv, H, N, d, dtype, &p.dv))) return rc;
-  p.slopes = alibi_slopes;
-  p.B = B; p.H = H; p.N = N;
-  p.inv_sqrt_d = 1.0f / sqrtf((float)d);
-  p.nscale_log2 = -kLog2e * p.inv_sqrt_d;
-  p.nbias_log2 = -bias * kLog2e;
-  hipStream_t st = (hipStream_t)stream;
-  if (dtype == SATTN_F32) return SATTN_ERR_UNSUPPORTED;
-  if (d == 128) return launch_sigmoid_bwd<128, 64, 4>(p, causal, alibi_slopes != nullptr, st);
-  return launch_sigmoid_bwd<64, 64, 4>(p, causal, alibi_slopes != nullptr, st);
+  return sigmoid_bwd_impl(q, k, v, dout, dq, dk, dv, B, H, N, d, dtype, bias, causal, alibi_slopes, sq, sk, sv,
+                          sdout, sdq, sdk, sdv, kBwdDkDv | kBwdDq, stream);
+}
+
+int sigmoid_attn_bwd_dkdv(const void* q, const void* k, const void* v, const void* dout, void* dk, void* dv,
+                          int B, int H, int N, int d, sattn_dtype dtype, float bias, int causal,
+                          const float* alibi_slopes, const sattn_strides* sq, const sattn_strides* sk,
+                          const sattn_strides* sv, const sattn_strides* sdout, const sattn_strides* sdk,
+                          const sattn_strides* sdv, void* stream) {
+  return sigmoid_bwd_impl(q, k, v, dout, nullptr, dk, dv, B, H, N, d, dtype, bias, causal, alibi_slopes, sq, sk,
+                          sv, sdout, nullptr, sdk, sdv, kBwdDkDv, stream);
+}
+
+int sigmoid_attn_bwd_dq(const void* q, const void* k, const void* v, const void* dout, void* dq, int B, int H,
+                        int N, int d, sattn_dtype dtype, float bias, int causal, const float* alibi_slopes,
+                        const sattn_strides* sq, const sattn_strides* sk, const sattn_strides* sv,
+                        const sattn_strides* sdout, const sattn_strides* sdq, void* stream) {
+  return sigmoid_bwd_impl(q, k, v, dout, dq, nullptr, nullptr, B, H, N, d, dtype, bias, causal, alibi_slopes, sq,
+                          sk, sv, sdout, sdq, nullptr, nullptr, kBwdDq, stream);
 }
 
 size_t sigmoid_attn_bwd_workspace_bytes(int, int, int, int, sattn_dtype) { return 0; }

@@ -1,0 +1,78 @@
+"""Host-side checks of the C ABI: the library loads, exports every symbol the header
+declares, and rejects bad arguments before anything is launched (no GPU needed)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2409_04431_amd as sa
+from paper_2409_04431_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "sattn.h")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(sa.library_path()):
+        from paper_2409_04431_amd.build import build_library
+        build_library()
+    return sa.load_library()
+
+
+def _declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b((?:sigmoid|softmax)_attn_\w+|sattn_\w+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported(lib):
+    names = _declared_functions()
+    assert {"sigmoid_attn_fwd", "sigmoid_attn_bwd", "softmax_attn_fwd", "softmax_attn_bwd", "sattn_strerror",
+            "sattn_version"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), f"{n} declared in sattn.h but not exported"
+
+
+def test_version_and_error_strings(lib):
+    assert sa.sattn_version() >= 100
+    for code in range(0, -7, -1):
+        assert sa.sattn_strerror(code) and "unknown" not in sa.sattn_strerror(code)
+    assert "unknown" in sa.sattn_strerror(-99)
+
+
+def _fwd(lib, q=0x1000, k=0x2000, v=0x3000, o=0x4000, B=1, H=1, N=16, d=64, dtype=0, strides=None):
+    sp = ctypes.byref(binding._Strides(*strides)) if strides else None
+    return lib.sigmoid_attn_fwd(q, k, v, o, B, H, N, d, dtype, 0.0, 0, None, sp, None, None, None, None)
+
+
+def test_bad_arguments_are_rejected_without_launch(lib):
+    # the pointers are fake: every call must fail validation before touching the device
+    assert _fwd(lib, q=None) == -1                      # SATTN_ERR_NULL
+    assert _fwd(lib, o=None) == -1
+    assert _fwd(lib, N=0) == -2                         # SATTN_ERR_SHAPE
+    assert _fwd(lib, B=-1) == -2
+    assert _fwd(lib, d=96) == -3                        # SATTN_ERR_UNSUPPORTED
+    assert _fwd(lib, dtype=7) == -3
+    assert _fwd(lib, q=0x1004) == -4                    # SATTN_ERR_ALIGN (pointer)
+    assert _fwd(lib, strides=(1024, 1024, 60)) == -4    # seq stride < d
+    assert _fwd(lib, strides=(1027, 1024, 64)) == -4    # rows not 16-byte aligned
+    assert _fwd(lib, N=(1 << 24) + 1) == -2
+
+
+def test_backward_rejects_bad_arguments(lib):
+    args = [0x1000, 0x2000, 0x3000, 0x4000, 0x5000, 0x6000, None]      # dv NULL
+    rc = lib.sigmoid_attn_bwd(*args, 1, 1, 16, 64, 0, 0.0, 0, None, *([None] * 7), None, 0, None)
+    assert rc == -1
+    args[6] = 0x7000
+    rc = lib.sigmoid_attn_bwd(*args, 1, 1, 16, 100, 0, 0.0, 0, None, *([None] * 7), None, 0, None)
+    assert rc == -3
+    assert sa.sigmoid_attn_bwd_workspace_bytes(8, 16, 4096, 128) == 0
+
+
+def test_binding_refuses_cpu_tensors():
+    import torch
+    t = torch.zeros(1, 1, 8, 64, dtype=torch.bfloat16)
+    with pytest.raises(sa.SattnError):
+        sa.sigmoid_attn_fwd(t, t, t, t, 0.0)
