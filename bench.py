@@ -31,16 +31,16 @@ def _events(n):
     return [torch.cuda.Event(enable_timing=True) for _ in range(n)]
 
 
-def cpu_baseline(cfg, seconds_hint=20.0):
+def cpu_baseline(cfg, seconds_hint=30.0):
     """Time the fp64 CPU oracle (as it stands) on a bounded sample of the same workload:
     one forward + backward over `threads` heads of the headline shape (one head per core)."""
     import torch
     from oracle import sattn_oracle as orc
     threads = orc.num_threads()
-    heads = 2 * max(1, threads)
+    heads = 4 * max(1, threads)
     N, d = cfg.N, cfg.d
-    # keep the sample near seconds_hint: two heads per core, ~14*N^2*d/2 flops each at roughly 2 GFLOP/s/core
-    while N > 512 and 2 * 14.0 * N * N * d / 2 / 2.0e9 > seconds_hint:
+    # keep the sample near seconds_hint: four heads per core, ~14*N^2*d/2 flops each at roughly 2 GFLOP/s/core
+    while N > 512 and 4 * 14.0 * N * N * d / 2 / 2.0e9 > seconds_hint:
         N //= 2
     g = torch.Generator().manual_seed(4242)
     q, k, v, do = (torch.randn(1, heads, N, d, generator=g).bfloat16() for _ in range(4))
@@ -64,6 +64,8 @@ def main():
     ap.add_argument("--cfg", type=int, default=3, help="workload id (1-5); the headline metric is quoted on 3")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--softmax", action="store_true", help="also time the softmax comparison kernels")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="only run a plain 256 MiB -> 256 MiB elementwise copy kernel (scales the HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build is single-GPU; the path shards over (batch, head) with no exchange, "
@@ -74,6 +76,14 @@ def main():
     from paper_2409_04431_amd import workloads as W
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
+    if args.calibrate_copy:
+        a = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device="cuda:0")
+        b = torch.empty_like(a)
+        for _ in range(3):
+            torch.mul(a, 1.0, out=b)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy_bytes_read": a.numel() * 4, "calibrate_copy_bytes_written": b.numel() * 4}))
+        return
     sa.load_library()
     cfg = W.CONFIGS[args.cfg]
     dev = torch.device("cuda:0")

@@ -6,6 +6,7 @@
 #include <math.h>
 
 #include "sattn_bwd.hpp"
+#include "sattn_f32.hpp"
 #include "sattn_fwd.hpp"
 
 using namespace sattn;
@@ -40,76 +41,177 @@ int check_shape(int B, int H, int N, int d, sattn_dtype dt) {
   return SATTN_OK;
 }
 
-template <typename K, typename P>
-int launch(K kernel, dim3 grid, dim3 block, size_t lds, hipStream_t st, const P& p) {
-  if (hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
+template <typename K, typename... Args>
+int launch(K kernel, dim3 grid, dim3 block, size_t lds, hipStream_t st, Args... args) {
+  if (lds > 0 &&
+      hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
     (void)hipGetLastError();
     return SATTN_ERR_LAUNCH;
   }
-  hipLaunchKernelGGL(kernel, grid, block, lds, st, p);
+  hipLaunchKernelGGL(kernel, grid, block, lds, st, args...);
   return hipGetLastError() == hipSuccess ? SATTN_OK : SATTN_ERR_LAUNCH;
 }
 
-template <int D, int BC, int NW>
-int launch_sigmoid_fwd(const FwdParams& p, int causal, bool alibi, hipStream_t st) {
-  constexpr size_t lds = 4 * BC * D * 2;
-  dim3 grid(p.n_qblocks * p.B * p.H), block(64 * NW);
-  if (causal) {
-    if (alibi) return launch(sigmoid_fwd_kernel<D, BC, NW, true, true>, grid, block, lds, st, p);
-    return launch(sigmoid_fwd_kernel<D, BC, NW, true, false>, grid, block, lds, st, p);
-  }
-  if (alibi) return launch(sigmoid_fwd_kernel<D, BC, NW, false, true>, grid, block, lds, st, p);
-  return launch(sigmoid_fwd_kernel<D, BC, NW, false, false>, grid, block, lds, st, p);
-}
+// Expand two runtime flags into the constexpr bools A and B2 visible to CALL.
+#define SATTN_DISPATCH2(F1, F2, CALL)                          \
+  do {                                                         \
+    if (F1) {                                                  \
+      if (F2) { constexpr bool A = true, B2 = true; CALL; }    \
+      else { constexpr bool A = true, B2 = false; CALL; }      \
+    } else {                                                   \
+      if (F2) { constexpr bool A = false, B2 = true; CALL; }   \
+      else { constexpr bool A = false, B2 = false; CALL; }     \
+    }                                                          \
+  } while (0)
 
-enum BwdPart { kBwdDkDv = 1, kBwdDq = 2 };
-
-template <int D, int BC, int NW, bool CAUSAL, bool ALIBI>
-int launch_sigmoid_bwd_t(const BwdParams& p, int parts, hipStream_t st) {
-  constexpr size_t lds = 4 * BC * D * 2;
-  dim3 grid(p.n_blocks * p.B * p.H), block(64 * NW);
+// ---------------------------------------------------------------- forward
+template <int D, bool SOFTMAX>
+int launch_fwd_bf16(const FwdParams& p, int causal, bool alibi, hipStream_t st) {
+  constexpr size_t lds = 6 * 64 * D * 2;  // 3 K slots + 3 V slots of 64 keys
+  dim3 grid(p.n_qblocks * p.B * p.H), block(512);
   int rc = SATTN_OK;
-  if (parts & kBwdDkDv) rc = launch(sigmoid_bwd_dkdv_kernel<D, BC, NW, CAUSAL, ALIBI>, grid, block, lds, st, p);
-  if (rc == SATTN_OK && (parts & kBwdDq))
-    rc = launch(sigmoid_bwd_dq_kernel<D, BC, NW, CAUSAL, ALIBI>, grid, block, lds, st, p);
+  SATTN_DISPATCH2(causal, alibi, rc = launch(attn_fwd_kernel<D, A, B2, SOFTMAX>, grid, block, lds, st, p));
   return rc;
 }
 
-template <int D, int BC, int NW>
-int launch_sigmoid_bwd(BwdParams p, int causal, bool alibi, int parts, hipStream_t st) {
-  p.n_blocks = (p.N + 32 * NW - 1) / (32 * NW);
-  if (causal) {
-    if (alibi) return launch_sigmoid_bwd_t<D, BC, NW, true, true>(p, parts, st);
-    return launch_sigmoid_bwd_t<D, BC, NW, true, false>(p, parts, st);
-  }
-  if (alibi) return launch_sigmoid_bwd_t<D, BC, NW, false, true>(p, parts, st);
-  return launch_sigmoid_bwd_t<D, BC, NW, false, false>(p, parts, st);
+template <int D>
+int launch_fwd_f32(const F32Params& p, int causal, bool alibi, hipStream_t st) {
+  dim3 grid(p.n_blocks * p.B * p.H), block(256);
+  int rc = SATTN_OK;
+  SATTN_DISPATCH2(causal, alibi, rc = launch(sigmoid_f32_kernel<D, F32_FWD, A, B2>, grid, block, 0, st, p));
+  return rc;
 }
 
-int sigmoid_bwd_impl(const void* q, const void* k, const void* v, const void* dout, void* dq, void* dk, void* dv,
-                     int B, int H, int N, int d, sattn_dtype dtype, float bias, int causal,
-                     const float* alibi_slopes, const sattn_strides* sq, const sattn_strides* sk,
-                     const sattn_strides* sv, const sattn_strides* sdout, const sattn_strides* sdq,
-                     const sattn_strides* sdk, const sattn_strides* sdv, int parts, void* stream) {
-  int rc = check_shape(B, H, N, d, dtype);
+struct FwdArgs {
+  const void *q, *k, *v; void* o; float* lse;
+  int B, H, N, d; sattn_dtype dtype; float bias; int causal; const float* slopes;
+  const sattn_strides *sq, *sk, *sv, *so; void* stream;
+};
+
+template <bool SOFTMAX>
+int fwd_impl(const FwdArgs& a) {
+  int rc = check_shape(a.B, a.H, a.N, a.d, a.dtype);
   if (rc) return rc;
+  TensorRef q, k, v, o;
+  if ((rc = make_ref(a.q, a.sq, a.H, a.N, a.d, a.dtype, &q))) return rc;
+  if ((rc = make_ref(a.k, a.sk, a.H, a.N, a.d, a.dtype, &k))) return rc;
+  if ((rc = make_ref(a.v, a.sv, a.H, a.N, a.d, a.dtype, &v))) return rc;
+  if ((rc = make_ref(a.o, a.so, a.H, a.N, a.d, a.dtype, &o))) return rc;
+  if (SOFTMAX && !a.lse) return SATTN_ERR_NULL;
+  hipStream_t st = (hipStream_t)a.stream;
+  const bool alibi = a.slopes != nullptr;
+  const float inv_sqrt_d = 1.0f / sqrtf((float)a.d);
+  if (a.dtype == SATTN_F32) {
+    if (SOFTMAX) return SATTN_ERR_UNSUPPORTED;  // the comparison kernels exist for bf16 only
+    F32Params p{};
+    p.q = q; p.k = k; p.v = v; p.out0 = o;
+    p.slopes = a.slopes; p.B = a.B; p.H = a.H; p.N = a.N;
+    p.n_blocks = (a.N + 127) / 128;
+    p.scale = inv_sqrt_d; p.bias = a.bias;
+    if (a.d == 128) return launch_fwd_f32<128>(p, a.causal, alibi, st);
+    return launch_fwd_f32<64>(p, a.causal, alibi, st);
+  }
+  FwdParams p{};
+  p.q = q; p.k = k; p.v = v; p.o = o;
+  p.slopes = a.slopes; p.lse = a.lse;
+  p.B = a.B; p.H = a.H; p.N = a.N;
+  p.n_qblocks = (a.N + 255) / 256;
+  p.nscale_log2 = (SOFTMAX ? kLog2e : -kLog2e) * inv_sqrt_d;
+  p.nbias_log2 = -a.bias * kLog2e;
+  if (a.d == 128) return launch_fwd_bf16<128, SOFTMAX>(p, a.causal, alibi, st);
+  return launch_fwd_bf16<64, SOFTMAX>(p, a.causal, alibi, st);
+}
+
+// ---------------------------------------------------------------- backward
+enum BwdPart { kBwdDkDv = 1, kBwdDq = 2 };
+
+template <int D, bool SOFTMAX>
+int launch_bwd_bf16(BwdParams p, int causal, bool alibi, int parts, hipStream_t st) {
+  constexpr int BC = 64, NW = 4;
+  constexpr size_t lds = 4 * BC * D * 2;
+  constexpr size_t lds_stat = SOFTMAX ? 2 * 2 * BC * sizeof(float) : 0;
+  p.n_blocks = (p.N + 32 * NW - 1) / (32 * NW);
+  dim3 grid(p.n_blocks * p.B * p.H), block(64 * NW);
+  int rc = SATTN_OK;
+  if (parts & kBwdDkDv)
+    SATTN_DISPATCH2(causal, alibi,
+                    rc = launch(attn_bwd_dkdv_kernel<D, BC, NW, A, B2, SOFTMAX>, grid, block, lds + lds_stat, st, p));
+  if (rc == SATTN_OK && (parts & kBwdDq))
+    SATTN_DISPATCH2(causal, alibi, rc = launch(attn_bwd_dq_kernel<D, BC, NW, A, B2, SOFTMAX>, grid, block, lds, st, p));
+  return rc;
+}
+
+template <int D>
+int launch_bwd_f32(F32Params p, int causal, bool alibi, int parts, TensorRef dq, TensorRef dk, TensorRef dv,
+                   hipStream_t st) {
+  p.n_blocks = (p.N + 127) / 128;
+  dim3 grid(p.n_blocks * p.B * p.H), block(256);
+  int rc = SATTN_OK;
+  if (parts & kBwdDkDv) {
+    p.out0 = dk; p.out1 = dv;
+    SATTN_DISPATCH2(causal, alibi, rc = launch(sigmoid_f32_kernel<D, F32_DKDV, A, B2>, grid, block, 0, st, p));
+  }
+  if (rc == SATTN_OK && (parts & kBwdDq)) {
+    p.out0 = dq; p.out1 = TensorRef{};
+    SATTN_DISPATCH2(causal, alibi, rc = launch(sigmoid_f32_kernel<D, F32_DQ, A, B2>, grid, block, 0, st, p));
+  }
+  return rc;
+}
+
+struct BwdArgs {
+  const void *q, *k, *v, *o; const float* lse; const void* dout; void *dq, *dk, *dv;
+  int B, H, N, d; sattn_dtype dtype; float bias; int causal; const float* slopes;
+  const sattn_strides *sq, *sk, *sv, *so, *sdout, *sdq, *sdk, *sdv;
+  void* workspace; size_t workspace_bytes; int parts; void* stream;
+};
+
+template <bool SOFTMAX>
+int bwd_impl(const BwdArgs& a) {
+  int rc = check_shape(a.B, a.H, a.N, a.d, a.dtype);
+  if (rc) return rc;
+  TensorRef q, k, v, dout, dq{}, dk{}, dv{}, o{};
+  if ((rc = make_ref(a.q, a.sq, a.H, a.N, a.d, a.dtype, &q))) return rc;
+  if ((rc = make_ref(a.k, a.sk, a.H, a.N, a.d, a.dtype, &k))) return rc;
+  if ((rc = make_ref(a.v, a.sv, a.H, a.N, a.d, a.dtype, &v))) return rc;
+  if ((rc = make_ref(a.dout, a.sdout, a.H, a.N, a.d, a.dtype, &dout))) return rc;
+  if ((a.parts & kBwdDq) && (rc = make_ref(a.dq, a.sdq, a.H, a.N, a.d, a.dtype, &dq))) return rc;
+  if ((a.parts & kBwdDkDv) && (rc = make_ref(a.dk, a.sdk, a.H, a.N, a.d, a.dtype, &dk))) return rc;
+  if ((a.parts & kBwdDkDv) && (rc = make_ref(a.dv, a.sdv, a.H, a.N, a.d, a.dtype, &dv))) return rc;
+  hipStream_t st = (hipStream_t)a.stream;
+  const bool alibi = a.slopes != nullptr;
+  const float inv_sqrt_d = 1.0f / sqrtf((float)a.d);
+  if (a.dtype == SATTN_F32) {
+    if (SOFTMAX) return SATTN_ERR_UNSUPPORTED;
+    F32Params p{};
+    p.q = q; p.k = k; p.v = v; p.dout = dout;
+    p.slopes = a.slopes; p.B = a.B; p.H = a.H; p.N = a.N;
+    p.scale = inv_sqrt_d; p.bias = a.bias;
+    if (a.d == 128) return launch_bwd_f32<128>(p, a.causal, alibi, a.parts, dq, dk, dv, st);
+    return launch_bwd_f32<64>(p, a.causal, alibi, a.parts, dq, dk, dv, st);
+  }
   BwdParams p{};
-  if ((rc = make_ref(q, sq, H, N, d, dtype, &p.q))) return rc;
-  if ((rc = make_ref(k, sk, H, N, d, dtype, &p.k))) return rc;
-  if ((rc = make_ref(v, sv, H, N, d, dtype, &p.v))) return rc;
-  if ((rc = make_ref(dout, sdout, H, N, d, dtype, &p.dout))) return rc;
-  if ((parts & kBwdDq) && (rc = make_ref(dq, sdq, H, N, d, dtype, &p.dq))) return rc;
-  if ((parts & kBwdDkDv) && (rc = make_ref(dk, sdk, H, N, d, dtype, &p.dk))) return rc;
-  if ((parts & kBwdDkDv) && (rc = make_ref(dv, sdv, H, N, d, dtype, &p.dv))) return rc;
-  p.slopes = alibi_slopes;
-  p.B = B; p.H = H; p.N = N;
-  p.inv_sqrt_d = 1.0f / sqrtf((float)d);
-  p.nscale_log2 = -kLog2e * p.inv_sqrt_d;
-  p.nbias_log2 = -bias * kLog2e;
-  hipStream_t st = (hipStream_t)stream;
-  if (dtype == SATTN_F32) return SATTN_ERR_UNSUPPORTED;
-  if (d == 128) return launch_sigmoid_bwd<128, 64, 4>(p, causal, alibi_slopes != nullptr, parts, st);
-  return launch_sigmoid_bwd<64, 64, 4>(p, causal, alibi_slopes != nullptr, parts, st);
+  p.q = q; p.k = k; p.v = v; p.dout = dout; p.dq = dq; p.dk = dk; p.dv = dv;
+  p.slopes = a.slopes;
+  p.B = a.B; p.H = a.H; p.N = a.N;
+  p.inv_sqrt_d = inv_sqrt_d;
+  p.nscale_log2 = -kLog2e * inv_sqrt_d;
+  p.nbias_log2 = -a.bias * kLog2e;
+  if (SOFTMAX) {
+    if (!a.lse) return SATTN_ERR_NULL;
+    if ((rc = make_ref(a.o, a.so, a.H, a.N, a.d, a.dtype, &o))) return rc;
+    const size_t need = (size_t)a.B * a.H * a.N * sizeof(float);
+    if (!a.workspace || a.workspace_bytes < need) return SATTN_ERR_WORKSPACE;
+    if (((uintptr_t)a.workspace & 15) != 0) return SATTN_ERR_ALIGN;
+    float* dvec = (float*)a.workspace;
+    const int64_t rows = (int64_t)a.B * a.H * a.N;
+    dim3 grid((unsigned)((rows + 15) / 16)), block(256);
+    if (a.d == 128) rc = launch(rowsum_do_o_kernel<128>, grid, block, 0, st, o, dout, dvec, a.B, a.H, a.N);
+    else rc = launch(rowsum_do_o_kernel<64>, grid, block, 0, st, o, dout, dvec, a.B, a.H, a.N);
+    if (rc) return rc;
+    p.lse = a.lse; p.dvec = dvec;
+  }
+  if (a.d == 128) return launch_bwd_bf16<128, SOFTMAX>(p, a.causal, alibi, a.parts, st);
+  return launch_bwd_bf16<64, SOFTMAX>(p, a.causal, alibi, a.parts, st);
 }
 
 }  // namespace
@@ -119,24 +221,8 @@ extern "C" {
 int sigmoid_attn_fwd(const void* q, const void* k, const void* v, void* o, int B, int H, int N, int d,
                      sattn_dtype dtype, float bias, int causal, const float* alibi_slopes, const sattn_strides* sq,
                      const sattn_strides* sk, const sattn_strides* sv, const sattn_strides* so, void* stream) {
-  int rc = check_shape(B, H, N, d, dtype);
-  if (rc) return rc;
-  FwdParams p{};
-  if ((rc = make_ref(q, sq, H, N, d, dtype, &p.q))) return rc;
-  if ((rc = make_ref(k, sk, H, N, d, dtype, &p.k))) return rc;
-  if ((rc = make_ref(v, sv, H, N, d, dtype, &p.v))) return rc;
-  if ((rc = make_ref(o, so, H, N, d, dtype, &p.o))) return rc;
-  p.slopes = alibi_slopes;
-  p.lse = nullptr;
-  p.B = B; p.H = H; p.N = N;
-  p.nscale_log2 = -kLog2e / sqrtf((float)d);
-  p.nbias_log2 = -bias * kLog2e;
-  hipStream_t st = (hipStream_t)stream;
-  if (dtype == SATTN_F32) return SATTN_ERR_UNSUPPORTED;
-  constexpr int NW = 4;
-  p.n_qblocks = (N + 32 * NW - 1) / (32 * NW);
-  if (d == 128) return launch_sigmoid_fwd<128, 64, NW>(p, causal, alibi_slopes != nullptr, st);
-  return launch_sigmoid_fwd<64, 64, NW>(p, causal, alibi_slopes != nullptr, st);
+  FwdArgs a{q, k, v, o, nullptr, B, H, N, d, dtype, bias, causal, alibi_slopes, sq, sk, sv, so, stream};
+  return fwd_impl<false>(a);
 }
 
 int sigmoid_attn_bwd(const void* q, const void* k, const void* v, const void* dout, void* dq, void* dk, void* dv,
@@ -145,9 +231,10 @@ int sigmoid_attn_bwd(const void* q, const void* k, const void* v, const void* do
                      const sattn_strides* sv, const sattn_strides* sdout, const sattn_strides* sdq,
                      const sattn_strides* sdk, const sattn_strides* sdv, void* workspace, size_t workspace_bytes,
                      void* stream) {
-  (void)workspace; (void)workspace_bytes;  // the two-kernel split needs none
-  return sigmoid_bwd_impl(q, k, v, dout, dq, dk, dv, B, H, N, d, dtype, bias, causal, alibi_slopes, sq, sk, sv,
-                          sdout, sdq, sdk, sdv, kBwdDkDv | kBwdDq, stream);
+  // the split by output owner needs no workspace
+  BwdArgs a{q, k, v, nullptr, nullptr, dout, dq, dk, dv, B, H, N, d, dtype, bias, causal, alibi_slopes,
+            sq, sk, sv, nullptr, sdout, sdq, sdk, sdv, workspace, workspace_bytes, kBwdDkDv | kBwdDq, stream};
+  return bwd_impl<false>(a);
 }
 
 int sigmoid_attn_bwd_dkdv(const void* q, const void* k, const void* v, const void* dout, void* dk, void* dv,
@@ -155,38 +242,51 @@ int sigmoid_attn_bwd_dkdv(const void* q, const void* k, const void* v, const voi
                           const float* alibi_slopes, const sattn_strides* sq, const sattn_strides* sk,
                           const sattn_strides* sv, const sattn_strides* sdout, const sattn_strides* sdk,
                           const sattn_strides* sdv, void* stream) {
-  return sigmoid_bwd_impl(q, k, v, dout, nullptr, dk, dv, B, H, N, d, dtype, bias, causal, alibi_slopes, sq, sk,
-                          sv, sdout, nullptr, sdk, sdv, kBwdDkDv, stream);
+  BwdArgs a{q, k, v, nullptr, nullptr, dout, nullptr, dk, dv, B, H, N, d, dtype, bias, causal, alibi_slopes,
+            sq, sk, sv, nullptr, sdout, nullptr, sdk, sdv, nullptr, 0, kBwdDkDv, stream};
+  return bwd_impl<false>(a);
 }
 
 int sigmoid_attn_bwd_dq(const void* q, const void* k, const void* v, const void* dout, void* dq, int B, int H,
                         int N, int d, sattn_dtype dtype, float bias, int causal, const float* alibi_slopes,
                         const sattn_strides* sq, const sattn_strides* sk, const sattn_strides* sv,
                         const sattn_strides* sdout, const sattn_strides* sdq, void* stream) {
-  return sigmoid_bwd_impl(q, k, v, dout, dq, nullptr, nullptr, B, H, N, d, dtype, bias, causal, alibi_slopes, sq,
-                          sk, sv, sdout, sdq, nullptr, nullptr, kBwdDq, stream);
+  BwdArgs a{q, k, v, nullptr, nullptr, dout, dq, nullptr, nullptr, B, H, N, d, dtype, bias, causal, alibi_slopes,
+            sq, sk, sv, nullptr, sdout, sdq, nullptr, nullptr, nullptr, 0, kBwdDq, stream};
+  return bwd_impl<false>(a);
 }
 
 size_t sigmoid_attn_bwd_workspace_bytes(int, int, int, int, sattn_dtype) { return 0; }
 
-// ---- not built yet: report it instead of pretending
-int softmax_attn_fwd(const void*, const void*, const void*, void*, float*, int, int, int, int, sattn_dtype, int,
-                     const float*, const sattn_strides*, const sattn_strides*, const sattn_strides*,
-                     const sattn_strides*, void*) { return SATTN_ERR_UNSUPPORTED; }
-int softmax_attn_bwd(const void*, const void*, const void*, const void*, const float*, const void*, void*, void*,
-                     void*, int, int, int, int, sattn_dtype, int, const float*, const sattn_strides*,
-                     const sattn_strides*, const sattn_strides*, const sattn_strides*, const sattn_strides*,
-                     const sattn_strides*, const sattn_strides*, const sattn_strides*, void*, size_t, void*) {
-  return SATTN_ERR_UNSUPPORTED;
+int softmax_attn_fwd(const void* q, const void* k, const void* v, void* o, float* lse, int B, int H, int N, int d,
+                     sattn_dtype dtype, int causal, const float* alibi_slopes, const sattn_strides* sq,
+                     const sattn_strides* sk, const sattn_strides* sv, const sattn_strides* so, void* stream) {
+  FwdArgs a{q, k, v, o, lse, B, H, N, d, dtype, 0.0f, causal, alibi_slopes, sq, sk, sv, so, stream};
+  return fwd_impl<true>(a);
 }
-size_t softmax_attn_bwd_workspace_bytes(int, int, int, int, sattn_dtype) { return 0; }
+
+int softmax_attn_bwd(const void* q, const void* k, const void* v, const void* o, const float* lse, const void* dout,
+                     void* dq, void* dk, void* dv, int B, int H, int N, int d, sattn_dtype dtype, int causal,
+                     const float* alibi_slopes, const sattn_strides* sq, const sattn_strides* sk,
+                     const sattn_strides* sv, const sattn_strides* so, const sattn_strides* sdout,
+                     const sattn_strides* sdq, const sattn_strides* sdk, const sattn_strides* sdv, void* workspace,
+                     size_t workspace_bytes, void* stream) {
+  BwdArgs a{q, k, v, o, lse, dout, dq, dk, dv, B, H, N, d, dtype, 0.0f, causal, alibi_slopes,
+            sq, sk, sv, so, sdout, sdq, sdk, sdv, workspace, workspace_bytes, kBwdDkDv | kBwdDq, stream};
+  return bwd_impl<true>(a);
+}
+
+size_t softmax_attn_bwd_workspace_bytes(int B, int H, int N, int d, sattn_dtype dtype) {
+  if (check_shape(B, H, N, d, dtype) != SATTN_OK) return 0;
+  return (size_t)B * H * N * sizeof(float);  // rowsum(dO o O), one fp32 per query row
+}
 
 const char* sattn_strerror(int code) {
   switch (code) {
     case SATTN_OK: return "success";
     case SATTN_ERR_NULL: return "a required pointer is NULL";
     case SATTN_ERR_SHAPE: return "B, H and N must be positive and within the supported range";
-    case SATTN_ERR_UNSUPPORTED: return "unsupported head dimension or dtype (d must be 64 or 128)";
+    case SATTN_ERR_UNSUPPORTED: return "unsupported head dimension or dtype (d must be 64 or 128; softmax is bf16 only)";
     case SATTN_ERR_ALIGN: return "pointers and strides must keep rows 16-byte aligned";
     case SATTN_ERR_WORKSPACE: return "workspace missing or too small";
     case SATTN_ERR_LAUNCH: return "the HIP runtime rejected the kernel launch";

@@ -19,6 +19,8 @@ namespace sattn {
 struct BwdParams {
   TensorRef q, k, v, dout, dq, dk, dv;
   const float* slopes;
+  const float* lse;    // softmax only: [B,H,N] natural-log row log-sum-exp from the forward
+  const float* dvec;   // softmax only: [B,H,N] rowsum(dO o O)
   int B, H, N;
   int n_blocks;        // query blocks (dq kernel) or key blocks (dkdv kernel)
   float nscale_log2;   // -log2(e)/sqrt(d)
@@ -110,6 +112,22 @@ __device__ __forceinline__ void sigmoid16(const f32x16& s, float* pr, float nsca
   for (int r = 0; r < 16; ++r) pr[r] = __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(pr[r]));
 }
 
+// softmax probabilities from saved row statistics: p = 2^(s*scale_log2 - slope|i-j|log2e - lse*log2e).
+// `nlse` holds -lse*log2(e) per register (dkdv kernel) or one value for the lane (dq kernel).
+template <bool ALIBI, bool PER_REG>
+__device__ __forceinline__ void softmax16(const f32x16& s, float* pr, float scale_log2, float sl2, float dist0,
+                                          float dstep, const float* nlse) {
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    float w = PER_REG ? nlse[r] : nlse[0];
+    if (ALIBI) {
+      float dist = dist0 + dstep * (float)key_of_reg(r);
+      w = __builtin_fmaf(-sl2, __builtin_fabsf(dist), w);
+    }
+    pr[r] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], scale_log2, w));
+  }
+}
+
 __device__ __forceinline__ bf16x8 pack8(const float* x) {
   u32x4 w;
 #pragma unroll
@@ -118,9 +136,9 @@ __device__ __forceinline__ bf16x8 pack8(const float* x) {
 }
 
 // ------------------------------------------------------------------ dQ kernel
-template <int D, int BC, int NW, bool CAUSAL, bool ALIBI>
+template <int D, int BC, int NW, bool CAUSAL, bool ALIBI, bool SOFTMAX>
 __global__ void __launch_bounds__(64 * NW, 2)
-sigmoid_bwd_dq_kernel(const BwdParams p) {
+attn_bwd_dq_kernel(const BwdParams p) {
   constexpr int NT = 64 * NW, BR = 32 * NW, KD = D / 16, DT = D / 32, NCK = BC / 32;
   constexpr int TILE = BC * D * 2;
   extern __shared__ __attribute__((aligned(1024))) char smem[];
@@ -156,6 +174,11 @@ sigmoid_bwd_dq_kernel(const BwdParams p) {
   off.init(lane);
   float sl2 = 0.f;
   if (ALIBI) sl2 = p.slopes[hd] * kLog2e;
+  float nlse_q = 0.f, d_q = 0.f;  // softmax: this lane's query statistics
+  if (SOFTMAX) {
+    nlse_q = -p.lse[(int64_t)bh * N + qi_ld] * kLog2e;
+    d_q = p.dvec[(int64_t)bh * N + qi_ld];
+  }
 
   const int q_hi = (qb * BR + BR < N ? qb * BR + BR : N) - 1;
   const int kv_len = CAUSAL ? (q_hi + 1) : N;
@@ -164,6 +187,7 @@ sigmoid_bwd_dq_kernel(const BwdParams p) {
   PairStager<D, BC, NT> st;
   st.load(kbase, vbase, p.k.ss, p.v.ss, 0, N, tid);
   st.store(lds0, lds0 + TILE, tid);
+  __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): stationary fragments are in registers before the loop
   __syncthreads();
 
   for (int jt = 0; jt < n_tiles; ++jt) {
@@ -187,10 +211,16 @@ sigmoid_bwd_dq_kernel(const BwdParams p) {
       }
       const int jl = jc + 8 * h;
       float pr[16];
-      sigmoid16<ALIBI>(s, pr, p.nscale_log2, p.nbias_log2, sl2, (float)(qi - jl), -1.0f);
       float ds[16];
+      if (SOFTMAX) {
+        softmax16<ALIBI, false>(s, pr, -p.nscale_log2, sl2, (float)(qi - jl), -1.0f, &nlse_q);
 #pragma unroll
-      for (int r = 0; r < 16; ++r) ds[r] = pr[r] * (1.0f - pr[r]) * dp[r];
+        for (int r = 0; r < 16; ++r) ds[r] = pr[r] * (dp[r] - d_q);
+      } else {
+        sigmoid16<ALIBI>(s, pr, p.nscale_log2, p.nbias_log2, sl2, (float)(qi - jl), -1.0f);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) ds[r] = pr[r] * (1.0f - pr[r]) * dp[r];
+      }
       if ((jc + 31 >= N) || (CAUSAL && jc + 31 > q_wave0)) {
         int lim = N - 1 - jl;
         if (CAUSAL) lim = lim < qi - jl ? lim : qi - jl;
@@ -226,13 +256,16 @@ sigmoid_bwd_dq_kernel(const BwdParams p) {
 }
 
 // ------------------------------------------------------------------ dK/dV kernel
-template <int D, int BQ, int NW, bool CAUSAL, bool ALIBI>
+template <int D, int BQ, int NW, bool CAUSAL, bool ALIBI, bool SOFTMAX>
 __global__ void __launch_bounds__(64 * NW, 1)
-sigmoid_bwd_dkdv_kernel(const BwdParams p) {
+attn_bwd_dkdv_kernel(const BwdParams p) {
   constexpr int NT = 64 * NW, BK = 32 * NW, KD = D / 16, DT = D / 32, NCK = BQ / 32;
   constexpr int TILE = BQ * D * 2;
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   const uint32_t lds0 = (uint32_t)(uintptr_t)(SATTN_LDS(char)*)smem;
+  // softmax: per-query statistics of the staged tile, [stage][0: -lse*log2e | 1: D][BQ]
+  SATTN_LDS(float)* stat = (SATTN_LDS(float)*)(smem + 4 * TILE);
+  static_assert(NT >= 2 * BQ, "statistics are staged by the first 2*BQ threads");
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, h = lane >> 5;
   const int total = p.n_blocks * p.B * p.H;
@@ -271,17 +304,34 @@ sigmoid_bwd_dkdv_kernel(const BwdParams p) {
   const int n_tiles = (N + BQ - 1) / BQ;
 
   PairStager<D, BQ, NT> st;
+  float statreg = 0.f;
+  auto load_stat = [&](int i0) {
+    if (SOFTMAX && tid < 2 * BQ) {
+      int row = i0 + (tid & (BQ - 1));
+      row = row < N ? row : N - 1;
+      statreg = tid < BQ ? -p.lse[(int64_t)bh * N + row] * kLog2e : p.dvec[(int64_t)bh * N + row];
+    }
+  };
+  auto store_stat = [&](int stage) {
+    if (SOFTMAX && tid < 2 * BQ) stat[stage * 2 * BQ + tid] = statreg;
+  };
   if (it0 < n_tiles) {
     st.load(qbase, dobase, p.q.ss, p.dout.ss, it0 * BQ, N, tid);
+    load_stat(it0 * BQ);
     st.store(lds0 + (it0 & 1) * (2 * TILE), lds0 + (it0 & 1) * (2 * TILE) + TILE, tid);
+    store_stat(it0 & 1);
   }
+  __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): stationary fragments are in registers before the loop
   __syncthreads();
 
   for (int it = it0; it < n_tiles; ++it) {
     const int i0 = it * BQ;
     const uint32_t qs = lds0 + (it & 1) * (2 * TILE), dos = qs + TILE;
     const bool more = it + 1 < n_tiles;
-    if (more) st.load(qbase, dobase, p.q.ss, p.dout.ss, i0 + BQ, N, tid);
+    if (more) {
+      st.load(qbase, dobase, p.q.ss, p.dout.ss, i0 + BQ, N, tid);
+      load_stat(i0 + BQ);
+    }
 #pragma unroll
     for (int ck = 0; ck < NCK; ++ck) {
       const int ic = i0 + 32 * ck;  // first query row of the chunk
@@ -298,7 +348,19 @@ sigmoid_bwd_dkdv_kernel(const BwdParams p) {
       }
       const int il = ic + 8 * h;  // query row of register 0 for this lane half
       float pr[16];
-      sigmoid16<ALIBI>(s, pr, p.nscale_log2, p.nbias_log2, sl2, (float)(il - kj), 1.0f);
+      float dq_r[16];  // softmax: D of the query held by register r
+      if (SOFTMAX) {
+        float nl[16];
+        const SATTN_LDS(float)* sl = stat + (it & 1) * 2 * BQ + 32 * ck + 8 * h;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          nl[r] = sl[key_of_reg(r)];
+          dq_r[r] = sl[BQ + key_of_reg(r)];
+        }
+        softmax16<ALIBI, true>(s, pr, -p.nscale_log2, sl2, (float)(il - kj), 1.0f, nl);
+      } else {
+        sigmoid16<ALIBI>(s, pr, p.nscale_log2, p.nbias_log2, sl2, (float)(il - kj), 1.0f);
+      }
       if ((ic + 31 >= N) || (CAUSAL && ic < k_wave0 + 31)) {
         // keep rows il + key_of_reg(r) in [max(kj, .), N-1]
         const int hi = N - 1 - il;
@@ -308,7 +370,7 @@ sigmoid_bwd_dkdv_kernel(const BwdParams p) {
       }
       float ds[16];
 #pragma unroll
-      for (int r = 0; r < 16; ++r) ds[r] = pr[r] * (1.0f - pr[r]) * dp[r];
+      for (int r = 0; r < 16; ++r) ds[r] = SOFTMAX ? pr[r] * (dp[r] - dq_r[r]) : pr[r] * (1.0f - pr[r]) * dp[r];
 #pragma unroll
       for (int ks2 = 0; ks2 < 2; ++ks2) {
         bf16x8 pb = pack8(pr + 8 * ks2), dsb = pack8(ds + 8 * ks2);
@@ -322,7 +384,10 @@ sigmoid_bwd_dkdv_kernel(const BwdParams p) {
         }
       }
     }
-    if (more) st.store(lds0 + ((it + 1) & 1) * (2 * TILE), lds0 + ((it + 1) & 1) * (2 * TILE) + TILE, tid);
+    if (more) {
+      st.store(lds0 + ((it + 1) & 1) * (2 * TILE), lds0 + ((it + 1) & 1) * (2 * TILE) + TILE, tid);
+      store_stat((it + 1) & 1);
+    }
     __syncthreads();
   }
   if (kj < N) {
@@ -341,6 +406,34 @@ sigmoid_bwd_dkdv_kernel(const BwdParams p) {
         *(u32x2*)(vrow + 32 * dt + 8 * g + 4 * h) = w;
       }
   }
+}
+
+// D_i = sum_t dO[i][t] * O[i][t] (fp32), the row term of the softmax backward.  16 lanes per
+// row, 8 elements per lane and pass.
+template <int D>
+__global__ void __launch_bounds__(256)
+rowsum_do_o_kernel(TensorRef o, TensorRef dout, float* dvec, int B, int H, int N) {
+  const int64_t row = (int64_t)blockIdx.x * 16 + (threadIdx.x >> 4);
+  const int sub = threadIdx.x & 15;
+  const int64_t rows = (int64_t)B * H * N;
+  float acc = 0.f;
+  if (row < rows) {
+    const int64_t bh = row / N;
+    const int i = (int)(row % N);
+    const int b = (int)(bh / H), hd = (int)(bh % H);
+    const __bf16* op = (const __bf16*)o.ptr + b * o.sb + hd * o.sh + (int64_t)i * o.ss;
+    const __bf16* dp = (const __bf16*)dout.ptr + b * dout.sb + hd * dout.sh + (int64_t)i * dout.ss;
+#pragma unroll
+    for (int c = sub * 8; c < D; c += 128) {
+      bf16x8 a = as_bf16x8(*(const u32x4*)(op + c));
+      bf16x8 g = as_bf16x8(*(const u32x4*)(dp + c));
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc += (float)a[e] * (float)g[e];
+    }
+  }
+#pragma unroll
+  for (int m = 8; m >= 1; m >>= 1) acc += __shfl_xor(acc, m, 16);
+  if (row < rows && sub == 0) dvec[row] = acc;
 }
 
 }  // namespace sattn

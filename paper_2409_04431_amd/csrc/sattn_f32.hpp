@@ -1,0 +1,182 @@
+// fp32 sigmoid attention for gfx950: forward and the two backward kernels in one template.
+// Everything (operands, logits, sigmoid, accumulation, outputs) is fp32; the matrix
+// products run on the fp32 MFMA (32x32x2), exp and the division are the accurate ones.
+// This is the precision path (agreement with the fp64 oracle to ~1e-6); the bf16 kernels
+// are the throughput path.
+//
+// One workgroup = 4 waves; each wave owns 32 rows of the stationary side and keeps their
+// operand fragments in registers; 32-row tiles of the streaming side pass through LDS.
+//   FWD  : stationary Q          | stream K,V  : S^T = K Q^T, P^T, O^T += V^T P^T
+//   DQ   : stationary Q, dO      | stream K,V  : S^T, dP^T = V dO^T, dS^T, dQ^T += K^T dS^T
+//   DKDV : stationary K, V       | stream Q,dO : S = Q K^T, dP = dO V^T, dV^T += dO^T P, dK^T += Q^T dS
+// (Algorithms 1 and 2 of the paper's Appendix F.1; the backward is split by output owner.)
+//
+// MFMA 32x32x2 fp32 fragment maps, lane l (l32 = l%32, h = l/32):
+//   A (32x2): row l32, k = h;  B (2x32): col l32, k = h;  C: col l32, row 8*(r/4)+4h+r%4.
+// With the streaming rows on C's rows, accumulator register r is directly the B operand
+// (k-slot h <-> streaming row 8*(r/4)+4h+r%4) of the second product.
+#pragma once
+#include "sattn_common.hpp"
+
+namespace sattn {
+
+enum F32Mode { F32_FWD = 0, F32_DQ = 1, F32_DKDV = 2 };
+
+struct F32Params {
+  TensorRef q, k, v, dout;   // inputs (dout unused by FWD)
+  TensorRef out0, out1;      // FWD: O ; DQ: dQ ; DKDV: dK, dV
+  const float* slopes;
+  int B, H, N, n_blocks;
+  float scale;   // 1/sqrt(d)
+  float bias;
+};
+
+__device__ __forceinline__ f32x16 mfma_f32(float a, float b, f32x16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, c, 0, 0, 0);
+}
+
+template <int D, int MODE, bool CAUSAL, bool ALIBI>
+__global__ void __launch_bounds__(256, 1)
+sigmoid_f32_kernel(const F32Params p) {
+  constexpr int NW = 4, NT = 256, BS = 32 * NW;  // stationary rows per workgroup
+  constexpr int LD = D + 2;                        // LDS row stride (floats): 32 rows -> 32 distinct even banks
+  constexpr int DT = D / 32;
+  constexpr bool TWO = MODE != F32_FWD;           // second stationary operand / dP product
+  __shared__ float t1[32 * LD];
+  __shared__ float t2[32 * LD];
+
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, h = lane >> 5;
+  const int bh = blockIdx.x / p.n_blocks, blk = blockIdx.x % p.n_blocks;
+  const int b = bh / p.H, hd = bh % p.H, N = p.N;
+
+  const float* qb = (const float*)p.q.ptr + b * p.q.sb + hd * p.q.sh;
+  const float* kb = (const float*)p.k.ptr + b * p.k.sb + hd * p.k.sh;
+  const float* vb = (const float*)p.v.ptr + b * p.v.sb + hd * p.v.sh;
+  const float* dob = TWO ? (const float*)p.dout.ptr + b * p.dout.sb + hd * p.dout.sh : nullptr;
+
+  // stationary side: x1 (and x2); streaming side: y1, y2
+  const float* x1 = MODE == F32_DKDV ? kb : qb;
+  const int64_t x1s = MODE == F32_DKDV ? p.k.ss : p.q.ss;
+  const float* x2 = MODE == F32_DKDV ? vb : dob;
+  const int64_t x2s = MODE == F32_DKDV ? p.v.ss : p.dout.ss;
+  const float* y1 = MODE == F32_DKDV ? qb : kb;
+  const int64_t y1s = MODE == F32_DKDV ? p.q.ss : p.k.ss;
+  const float* y2 = MODE == F32_DKDV ? dob : vb;
+  const int64_t y2s = MODE == F32_DKDV ? p.dout.ss : p.v.ss;
+
+  const int a_wave0 = blk * BS + wave * 32;  // first stationary row of the wave
+  const int ai = a_wave0 + l32;              // this lane's stationary row (query, or key for DKDV)
+  const int ai_ld = ai < N ? ai : N - 1;
+
+  float xf1[D / 2], xf2[TWO ? D / 2 : 1];
+#pragma unroll
+  for (int kk = 0; kk < D / 2; ++kk) {
+    xf1[kk] = x1[(int64_t)ai_ld * x1s + 2 * kk + h];
+    if (TWO) xf2[kk] = x2[(int64_t)ai_ld * x2s + 2 * kk + h];
+  }
+  f32x16 acc0[DT], acc1[MODE == F32_DKDV ? DT : 1];
+#pragma unroll
+  for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      acc0[dt][r] = 0.f;
+      if (MODE == F32_DKDV) acc1[dt][r] = 0.f;
+    }
+  const float slope = ALIBI ? p.slopes[hd] : 0.f;
+
+  // range of streaming tiles (32 rows each)
+  const int a_hi = (blk * BS + BS < N ? blk * BS + BS : N) - 1;
+  int t_lo = 0, t_hi = (N + 31) / 32;
+  if (CAUSAL) {
+    if (MODE == F32_DKDV) t_lo = (blk * BS) / 32;  // queries before the first key see nothing
+    else t_hi = a_hi / 32 + 1;                      // keys after the last query are masked
+  }
+
+  for (int t = t_lo; t < t_hi; ++t) {
+    const int b0 = t * 32;  // first streaming row of the tile
+    __syncthreads();        // previous tile fully consumed
+    for (int idx = tid; idx < 32 * (D / 4); idx += NT) {
+      int r = idx / (D / 4), c = idx % (D / 4);
+      int row = b0 + r;
+      row = row < N ? row : N - 1;
+      f32x4 u = *(const f32x4*)(y1 + (int64_t)row * y1s + 4 * c);
+      f32x4 w = *(const f32x4*)(y2 + (int64_t)row * y2s + 4 * c);
+      float* d1 = &t1[r * LD + 4 * c];
+      float* d2 = &t2[r * LD + 4 * c];
+      d1[0] = u[0]; d1[1] = u[1]; d1[2] = u[2]; d1[3] = u[3];
+      d2[0] = w[0]; d2[1] = w[1]; d2[2] = w[2]; d2[3] = w[3];
+    }
+    __syncthreads();
+
+    // wave-uniform skip of tiles that are entirely masked for this wave
+    bool live = a_wave0 < N;
+    if (CAUSAL) {
+      if (MODE == F32_DKDV) live = live && (b0 + 31 >= a_wave0);  // some query >= some key
+      else live = live && (b0 <= a_wave0 + 31);                   // some key <= some query
+    }
+    if (!live) continue;
+
+    f32x16 s, dp;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
+#pragma unroll
+    for (int kk = 0; kk < D / 2; ++kk) {
+      s = mfma_f32(t1[l32 * LD + 2 * kk + h], xf1[kk], s);
+      if (MODE == F32_DQ) dp = mfma_f32(t2[l32 * LD + 2 * kk + h], xf2[kk], dp);
+      if (MODE == F32_DKDV) dp = mfma_f32(t2[l32 * LD + 2 * kk + h], xf2[kk], dp);
+    }
+    // element (register r, this lane): streaming row bi = b0 + 8g + 4h + t, stationary row ai
+    float pr[16], ds[16];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int bi = b0 + 8 * (r >> 2) + 4 * h + (r & 3);
+      const int qrow = MODE == F32_DKDV ? bi : ai;
+      const int krow = MODE == F32_DKDV ? ai : bi;
+      float tt = s[r] * p.scale + p.bias;
+      if (ALIBI) tt -= slope * fabsf((float)(qrow - krow));
+      float pv = 1.0f / (1.0f + expf(-tt));
+      bool keep = bi < N && (!CAUSAL || krow <= qrow);
+      pv = keep ? pv : 0.f;
+      pr[r] = pv;
+      if (TWO) ds[r] = pv * (1.0f - pv) * dp[r];
+    }
+    // second products: acc^T[d][a] += Y^T[d][bi] * W[bi][a]
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int br = 8 * (r >> 2) + 4 * h + (r & 3);
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt) {
+        if (MODE == F32_FWD) acc0[dt] = mfma_f32(t2[br * LD + 32 * dt + l32], pr[r], acc0[dt]);
+        if (MODE == F32_DQ) acc0[dt] = mfma_f32(t1[br * LD + 32 * dt + l32], ds[r], acc0[dt]);
+        if (MODE == F32_DKDV) {
+          acc0[dt] = mfma_f32(t1[br * LD + 32 * dt + l32], ds[r], acc0[dt]);  // dK^T += Q^T dS
+          acc1[dt] = mfma_f32(t2[br * LD + 32 * dt + l32], pr[r], acc1[dt]);  // dV^T += dO^T P
+        }
+      }
+    }
+  }
+
+  if (ai < N) {
+    const float osc = MODE == F32_FWD ? 1.0f : p.scale;  // dQ, dK carry the 1/sqrt(d) of the logits
+    float* o0 = (float*)p.out0.ptr + b * p.out0.sb + hd * p.out0.sh + (int64_t)ai * p.out0.ss;
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        f32x4 w = {acc0[dt][4 * g] * osc, acc0[dt][4 * g + 1] * osc, acc0[dt][4 * g + 2] * osc, acc0[dt][4 * g + 3] * osc};
+        *(f32x4*)(o0 + 32 * dt + 8 * g + 4 * h) = w;
+      }
+    if (MODE == F32_DKDV) {
+      float* o1 = (float*)p.out1.ptr + b * p.out1.sb + hd * p.out1.sh + (int64_t)ai * p.out1.ss;
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          f32x4 w = {acc1[dt][4 * g], acc1[dt][4 * g + 1], acc1[dt][4 * g + 2], acc1[dt][4 * g + 3]};
+          *(f32x4*)(o1 + 32 * dt + 8 * g + 4 * h) = w;
+        }
+    }
+  }
+}
+
+}  // namespace sattn

@@ -22,8 +22,12 @@ TOL_F32 = 1e-5
 
 
 def nerr(x, ref):
+    """max|x - ref| / max|ref|; an all-zero reference demands an all-zero result."""
     x = x.detach().float().cpu().numpy().astype(np.float64) if hasattr(x, "detach") else x
-    return float(np.abs(x - ref).max() / max(np.abs(ref).max(), 1e-300))
+    den = np.abs(ref).max()
+    if den == 0.0:
+        return 0.0 if np.abs(x).max() == 0.0 else float("inf")
+    return float(np.abs(x - ref).max() / den)
 
 
 def _dev(x):
@@ -165,9 +169,98 @@ def test_split_backward_entry_points_equal_the_fused_call():
     assert torch.equal(dq, dq2) and torch.equal(dk, dk2) and torch.equal(dv, dv2)
 
 
+# ------------------------------------------------------------------ fp32 path
+
+def test_config1_fp32_full_tensor():
+    # B1 H2 N256 d64 fp32 non-causal b=-ln 256: everything fp32, bar 1e-5
+    c = W.CONFIGS[1]
+    inp = W.make_inputs(c)
+    got = _run_fwd_bwd(inp, c.bias, c.causal, None)
+    ro = orc.sigmoid_attn_fwd(inp["q"], inp["k"], inp["v"], c.bias, c.causal)
+    rq, rk, rv = orc.sigmoid_attn_bwd(inp["q"], inp["k"], inp["v"], inp["dout"], c.bias, c.causal)
+    for name, ref in (("o", ro), ("dq", rq), ("dk", rk), ("dv", rv)):
+        e = nerr(got[name], ref)
+        assert e <= TOL_F32, f"{name}: {e:.3e}"
+
+
+@pytest.mark.parametrize("B,H,N,d,causal,alibi", [
+    (1, 2, 256, 64, True, True), (2, 2, 200, 128, True, False), (1, 1, 77, 128, False, True),
+    (1, 1, 1, 64, False, False), (1, 3, 300, 64, True, False), (1, 1, 129, 128, False, False),
+])
+def test_fp32_forward_backward_match_oracle(B, H, N, d, causal, alibi):
+    inp = _rand_inputs(B, H, N, d, seed=N + d, dtype=torch.float32)
+    slopes = W.alibi_slopes(H) if alibi else None
+    bias = -math.log(N)
+    got = _run_fwd_bwd(inp, bias, causal, slopes)
+    sl = slopes.numpy() if alibi else None
+    ro = orc.sigmoid_attn_fwd(inp["q"], inp["k"], inp["v"], bias, causal, sl)
+    rq, rk, rv = orc.sigmoid_attn_bwd(inp["q"], inp["k"], inp["v"], inp["dout"], bias, causal, sl)
+    for name, ref in (("o", ro), ("dq", rq), ("dk", rk), ("dv", rv)):
+        assert not torch.isnan(got[name]).any()
+        e = nerr(got[name], ref)
+        assert e <= TOL_F32, f"{name}: {e:.3e}"
+
+
+# ------------------------------------------------------------------ softmax comparison kernels
+
+def _run_softmax(inp, causal, slopes):
+    q, k, v, do = (_dev(inp[n]) for n in ("q", "k", "v", "dout"))
+    sl = _dev(slopes) if slopes is not None else None
+    B, H, N, d = q.shape
+    o = torch.full_like(q, float("nan"))
+    lse = torch.full((B, H, N), float("nan"), device="cuda")
+    dq, dk, dv = (torch.full_like(q, float("nan")) for _ in range(3))
+    sa.softmax_attn_fwd(q, k, v, o, lse, causal, sl)
+    sa.softmax_attn_bwd(q, k, v, o, lse, do, dq, dk, dv, causal, sl)
+    torch.cuda.synchronize()
+    return dict(o=o, lse=lse, dq=dq, dk=dk, dv=dv)
+
+
+@pytest.mark.parametrize("B,H,N,d,causal,alibi", [
+    (1, 2, 256, 128, False, False), (1, 2, 256, 128, True, False), (2, 2, 200, 128, True, True),
+    (1, 2, 333, 64, False, True), (1, 1, 1, 64, False, False), (1, 2, 1000, 64, True, False),
+    (1, 1, 17, 128, True, False), (1, 1, 513, 128, True, False),
+])
+def test_softmax_comparison_kernels_match_oracle(B, H, N, d, causal, alibi):
+    inp = _rand_inputs(B, H, N, d, seed=N + 1)
+    slopes = W.alibi_slopes(H) if alibi else None
+    got = _run_softmax(inp, causal, slopes)
+    sl = slopes.numpy() if alibi else None
+    ro, rl = orc.softmax_attn_fwd(inp["q"], inp["k"], inp["v"], causal, sl)
+    rq, rk, rv = orc.softmax_attn_bwd(inp["q"], inp["k"], inp["v"], inp["dout"], causal, sl)
+    assert float(np.abs(got["lse"].cpu().numpy() - rl).max()) <= 1e-3
+    for name, ref in (("o", ro), ("dq", rq), ("dk", rk), ("dv", rv)):
+        assert not torch.isnan(got[name]).any()
+        e = nerr(got[name], ref)
+        assert e <= TOL_BF16, f"{name}: {e:.3e}"
+    # rows of P sum to one: with V = 1 the output is 1
+    ones = {**inp, "v": torch.ones_like(inp["v"])}
+    o1 = _run_softmax(ones, causal, slopes)["o"].float()
+    assert float((o1 - 1).abs().max()) <= 1e-2
+
+
+def test_softmax_full_size_config3_sampled_rows():
+    c = W.CONFIGS[3]
+    inp = W.make_inputs(c)
+    got = {n: t.cpu() for n, t in _run_softmax(inp, c.causal, None).items()}
+    rng = np.random.default_rng(33)
+    for (b, h) in [(0, 0), (7, 15)]:
+        rows = _sample_rows(c.N, 64, rng)
+        ro, rl = orc.softmax_attn_fwd_rows(inp["q"][b, h], inp["k"][b, h], inp["v"][b, h], c.causal, 0.0, rows)
+        assert nerr(got["o"][b, h][rows], ro) <= TOL_BF16
+        assert float(np.abs(got["lse"][b, h][rows].numpy() - rl).max()) <= 1e-3
+    # backward at full size: one head against the full fp64 oracle pass of that head
+    b, h = 3, 5
+    sl = (slice(b, b + 1), slice(h, h + 1))
+    rq, rk, rv = orc.softmax_attn_bwd(inp["q"][sl], inp["k"][sl], inp["v"][sl], inp["dout"][sl], c.causal)
+    for name, ref in (("dq", rq), ("dk", rk), ("dv", rv)):
+        e = nerr(got[name][sl], ref)
+        assert e <= TOL_BF16, f"{name}: {e:.3e}"
+
+
 # ------------------------------------------------------------------ full benchmark sizes, sampled rows
 
-def _sample_rows(N, n, rng, extra=()):
+def _sample_rows(N, n, rng, extra=()):  # noqa: E302
     rows = set(int(r) for r in rng.integers(0, N, size=n))
     rows.update(r for r in (0, 1, 31, 32, 127, 128, N // 2, N - 129, N - 2, N - 1) if 0 <= r < N)
     rows.update(extra)
