@@ -65,12 +65,14 @@ int launch(K kernel, dim3 grid, dim3 block, size_t lds, hipStream_t st, Args... 
   } while (0)
 
 // ---------------------------------------------------------------- forward
+constexpr int kFwdWaves = 8;  // waves per forward workgroup, 32 query rows each
+
 template <int D, bool SOFTMAX>
 int launch_fwd_bf16(const FwdParams& p, int causal, bool alibi, hipStream_t st) {
   constexpr size_t lds = 6 * 64 * D * 2;  // 3 K slots + 3 V slots of 64 keys
-  dim3 grid(p.n_qblocks * p.B * p.H), block(512);
+  dim3 grid(p.n_qblocks * p.B * p.H), block(64 * kFwdWaves);
   int rc = SATTN_OK;
-  SATTN_DISPATCH2(causal, alibi, rc = launch(attn_fwd_kernel<D, A, B2, SOFTMAX>, grid, block, lds, st, p));
+  SATTN_DISPATCH2(causal, alibi, rc = launch(attn_fwd_kernel<D, kFwdWaves, A, B2, SOFTMAX>, grid, block, lds, st, p));
   return rc;
 }
 
@@ -115,7 +117,7 @@ int fwd_impl(const FwdArgs& a) {
   p.q = q; p.k = k; p.v = v; p.o = o;
   p.slopes = a.slopes; p.lse = a.lse;
   p.B = a.B; p.H = a.H; p.N = a.N;
-  p.n_qblocks = (a.N + 255) / 256;
+  p.n_qblocks = (a.N + 32 * kFwdWaves - 1) / (32 * kFwdWaves);
   p.nscale_log2 = (SOFTMAX ? kLog2e : -kLog2e) * inv_sqrt_d;
   p.nbias_log2 = -a.bias * kLog2e;
   if (a.d == 128) return launch_fwd_bf16<128, SOFTMAX>(p, a.causal, alibi, st);

@@ -1,8 +1,9 @@
 // Fused sigmoid-attention forward for gfx950 (Algorithm 1 of the paper's Appendix F.1),
 // bf16 operands, fp32 logits / sigmoid / accumulation.
 //
-// Work split: one workgroup = 8 waves (two per SIMD), each wave owns 32 query rows
-// (B_r = 256); the workgroup streams K/V tiles of 64 keys through a 3-slot LDS ring.
+// Work split: one workgroup = NW waves, each wave owns 32 query rows (B_r = 32*NW); the
+// workgroup streams K/V tiles of 64 keys through LDS (three K slots, three V slots) with
+// direct-to-LDS loads issued two tiles ahead.
 // Per 32-key chunk c a wave computes
 //     S^T (32 keys x 32 queries) = K_c Q_i^T               8 (d=128) MFMA 32x32x16
 //     P^T = sigmoid(S^T / sqrt(d) + b [+ ALiBi])            fp32 VALU, no row max / row sum
@@ -12,8 +13,10 @@
 // bf16 round, as the B operand of the second product with no cross-lane traffic.
 //
 // The three stages are software-pipelined inside each wave: step c issues the MFMAs of
-// S^T(c+1) and of the O^T update with P^T(c-1) while the VALU evaluates sigmoid(c), so
-// that matrix and vector pipes are both fed from one instruction stream.
+// S^T(c+1) and of the O^T update with P^T(c-1) while the VALU evaluates sigmoid(c), and
+// refills each operand fragment from LDS (K(c+2), V(c)) right after the MFMA that consumed
+// it, a full step before its next use.  Matrix and vector pipes are fed from one
+// instruction stream whose order is pinned with scheduling barriers.
 #pragma once
 #include "sattn_common.hpp"
 
@@ -39,44 +42,51 @@ struct Swz {
   __device__ static __forceinline__ int v(int row) { return D == 128 ? ((row & 3) << 2) : (((row >> 1) & 1) << 2); }
 };
 
-// Stage one tile (ROWS x D bf16) global -> registers -> LDS.
-template <int D, int ROWS, int NT, bool IS_V>
-struct TileStager {
-  static constexpr int CPR = D / 8;
-  static constexpr int NCH = (ROWS * CPR) / NT;
-  static_assert((ROWS * CPR) % NT == 0, "tile must split evenly over the workgroup");
-  u32x4 reg[NCH];
+// Stage one tile (BC x D bf16) global -> LDS with the direct-to-LDS load: no staging
+// registers, no LDS write instructions.  One wave-level instruction moves 64 x 16 bytes to
+// 1 KB of LDS at M0 + 16*lane, so the XOR swizzle is applied on the global side: the lane
+// that fills physical chunk pc of row r fetches logical chunk pc ^ swz(r).  Completion is
+// tracked by hand (vmcnt), the compiler never sees these loads.
+template <int D, int BC, int NW, bool IS_V>
+struct DmaStager {
+  static constexpr int CPR = D / 8;               // 16-byte chunks per row
+  static constexpr int RPI = 64 / CPR;            // rows filled by one instruction
+  static constexpr int NI = (BC * CPR) / (64 * NW);  // instructions per wave per tile
+  static_assert((BC * CPR) % (64 * NW) == 0, "tile must split evenly over the waves");
+  const char* ptr[NI];   // this lane's source for the next tile to stage (unclamped)
+  const char* last[NI];  // this lane's source inside the last row N-1
+  int row[NI];           // tile-relative row this lane fills
+  int64_t tile_bytes;    // BC * seq stride in bytes
 
-  __device__ __forceinline__ void load(const __bf16* base, int64_t ss, int j0, int N, int tid) {
+  __device__ __forceinline__ void init(const __bf16* base, int64_t ss, int N, int wave, int lane) {
 #pragma unroll
-    for (int n = 0; n < NCH; ++n) {
-      int idx = tid + n * NT;
-      int r = idx / CPR, c = idx % CPR;
-      int key = j0 + r;
-      key = key < N ? key : N - 1;  // rows past the end are clamped here and masked in the epilogue
-      reg[n] = *(const u32x4*)(base + (int64_t)key * ss + c * 8);
+    for (int n = 0; n < NI; ++n) {
+      const int r = (wave * NI + n) * RPI + lane / CPR, pc = lane % CPR;
+      const int c = pc ^ (IS_V ? Swz<D>::v(r) : Swz<D>::k(r));
+      row[n] = r;
+      ptr[n] = (const char*)(base + (int64_t)r * ss + c * 8);
+      last[n] = (const char*)(base + (int64_t)(N - 1) * ss + c * 8);
     }
+    tile_bytes = (int64_t)BC * ss * 2;
   }
-  __device__ __forceinline__ void store(uint32_t lds, int tid) const {
+  // Issue the loads of the tile starting at key j0 into the LDS tile at byte address `lds`
+  // (wave-uniform) and advance to the next tile.  Rows past the end re-read row N-1.
+  __device__ __forceinline__ void issue(uint32_t lds, int j0, int N, int wave) {
 #pragma unroll
-    for (int n = 0; n < NCH; ++n) {
-      int idx = tid + n * NT;
-      int r = idx / CPR, c = idx % CPR;
-      int sw = IS_V ? Swz<D>::v(r) : Swz<D>::k(r);
-      lds_write_b128(lds + r * (D * 2) + ((c ^ sw) << 4), reg[n]);
+    for (int n = 0; n < NI; ++n) {
+      const char* src = ptr[n];
+      if (j0 + BC > N) src = (j0 + row[n] < N) ? src : last[n];
+      const uint32_t m0v = lds + (wave * NI + n) * 1024;
+      asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(src), "s"(m0v) : "memory");
+#ifndef SATTN_EXP_SAMETILE
+      ptr[n] += tile_bytes;
+#endif
     }
   }
 };
 
-// Per-wave constants of the forward pipeline.
-template <int D>
-struct FwdLane {
-  static constexpr int KD = D / 16, DT = D / 32;
-  uint32_t koff[KD];  // K row-wise read: row kappa(l32), chunk 2kk+h
-  uint32_t voff[DT];  // V transposing read: rows 8h + i16/4, 64-byte group dt
-  int qi, h;
-  float nscale, nbias, sl2;
-};
+// s_waitcnt vmcnt(n), other counters untouched (gfx9 encoding, n < 16).
+#define SATTN_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(0x0F70 | (n))
 
 // Running row statistics of the softmax comparison kernel (log2 units), one query per lane.
 struct SoftmaxState {
@@ -84,114 +94,135 @@ struct SoftmaxState {
   float l;  // this lane half's partial sum of 2^(x - m)
 };
 
-// One pipeline step.  QK: start S^T(c+1) into s_nxt.  SIG: p_cur = bf16(sigmoid(s_cur)).
-// PV: oacc += V(c-1)^T p_prv.  kbase/vbase are LDS byte addresses of the 32-key chunks.
-// SOFTMAX replaces the sigmoid by the online-softmax update: row maximum (across the two
-// lane halves), p = 2^(x - m), running sum, and a rescale of O^T when a maximum moved.
-template <int D, bool ALIBI, bool SOFTMAX, bool QK, bool SIG, bool PV>
-__device__ __forceinline__ void fwd_step(const FwdLane<D>& L, const bf16x8* qf, f32x16* oacc, f32x16& s_cur,
-                                         f32x16& s_nxt, bf16x8* p_cur, const bf16x8* p_prv, uint32_t kbase,
-                                         uint32_t vbase, int jc, bool mask, int N, bool causal,
-                                         SoftmaxState& sm) {
+// Per-wave state of the forward pipeline.
+template <int D>
+struct FwdWave {
+  static constexpr int KD = D / 16, DT = D / 32;
+  uint32_t koff[KD];   // LDS byte address of this lane's K fragment kk in (slot 0, chunk 0)
+  uint32_t voff[DT];   // LDS byte address of this lane's V fragment dt in (slot 0, chunk 0, ks 0, rd 0)
+  bf16x8 qf[KD];       // Q fragment (B operand of S^T)
+  bf16x8 kf[KD];       // K fragments of the chunk whose S^T is computed next
+  bf16x8 vf[2 * DT];   // V fragments of the chunk whose P^T is consumed next
+  f32x16 oacc[DT];     // O^T accumulator
+  f32x16 s[2];         // S^T of chunk c in s[c&1]
+  bf16x8 p[2][2];      // bf16 P^T of chunk c in p[c&1][ks]
+  SoftmaxState sm;
+  int qi, h;
+  float nscale, nbias, sl2;
+};
+
+enum StepKind { STEP_FULL = 0, STEP_LAST = 1, STEP_TAIL = 2 };
+
+// One pipeline step for chunk c (PAR = c & 1).
+//   FULL: S^T(c+1) MFMAs + refill kf with K(c+2); sigmoid(c); O^T += V(c-1)^T P^T(c-1) + refill vf with V(c)
+//   LAST: the wave's last chunk (diagonal / ragged end): no S^T; masked sigmoid(c); O^T update; refill vf
+//   TAIL: only the O^T update with P^T(c-1)
+// kaddr: byte offset (compile-time) of K chunk c+2 inside LDS; vaddr: of V chunk c.
+template <int D, bool ALIBI, bool SOFTMAX, int KIND, int PAR>
+__device__ __forceinline__ void fwd_step(FwdWave<D>& W, uint32_t kaddr, uint32_t vaddr, int jc, int N, bool causal) {
   constexpr int KD = D / 16, DT = D / 32;
-  bf16x8 kf[KD];
-  bf16x8 vf[2 * DT];
-  if (QK) {
-#pragma unroll
-    for (int kk = 0; kk < KD; ++kk) kf[kk] = as_bf16x8(lds_read_b128(kbase + L.koff[kk]));
-  }
-  if (PV) {
-#pragma unroll
-    for (int ks2 = 0; ks2 < 2; ++ks2)
-#pragma unroll
-      for (int dt = 0; dt < DT; ++dt) {
-        uint32_t a0 = vbase + ks2 * 16 * (D * 2) + L.voff[dt];
-        vf[ks2 * DT + dt] = join_tr(lds_read_tr16(a0), lds_read_tr16(a0 + 4 * (D * 2)));
-      }
-  }
+  constexpr int NM = KD;  // == 2*DT
+  static_assert(KD == 2 * DT, "one S^T MFMA pairs with one O^T MFMA");
+  constexpr int EPS = 16 / NM;  // sigmoid elements evaluated per MFMA pair
+  constexpr bool QK = KIND == STEP_FULL, SIG = KIND != STEP_TAIL;
+  f32x16& s_cur = W.s[PAR];
+  f32x16& s_nxt = W.s[PAR ^ 1];
+  bf16x8* p_cur = W.p[PAR];
+  const bf16x8* p_prv = W.p[PAR ^ 1];
+
   float pr[16];
   float alpha = 1.0f;
+  const int jl = jc + 8 * W.h;  // key held by register 0 of this lane half
   if (SIG && SOFTMAX) {
     // x = (s/sqrt(d) - slope|i-j|) log2(e); masked keys -> -inf
-    const int jl = jc + 8 * L.h;
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
-      float x = s_cur[r] * L.nscale;
-      if (ALIBI) x = __builtin_fmaf(-L.sl2, __builtin_fabsf((float)(L.qi - jl) - (float)key_of_reg(r)), x);
+      float x = s_cur[r] * W.nscale;
+      if (ALIBI) x = __builtin_fmaf(-W.sl2, __builtin_fabsf((float)(W.qi - jl) - (float)key_of_reg(r)), x);
       pr[r] = x;
     }
-    if (mask) {
-      int lim = N - 1 - jl;
-      if (causal) lim = lim < L.qi - jl ? lim : L.qi - jl;
+    if (KIND == STEP_LAST) {
+      int lim2 = N - 1 - jl;
+      if (causal) lim2 = lim2 < W.qi - jl ? lim2 : W.qi - jl;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) pr[r] = key_of_reg(r) <= lim ? pr[r] : -__builtin_inff();
+      for (int r = 0; r < 16; ++r) pr[r] = key_of_reg(r) <= lim2 ? pr[r] : -__builtin_inff();
     }
     float mx = pr[0];
 #pragma unroll
     for (int r = 1; r < 16; ++r) mx = __builtin_fmaxf(mx, pr[r]);
     mx = __builtin_fmaxf(mx, __shfl_xor(mx, 32));  // the other half of this query's keys
-    const float m_new = __builtin_fmaxf(sm.m, mx);
-    alpha = __builtin_amdgcn_exp2f(sm.m - m_new);
-    sm.m = m_new;
+    const float m_new = __builtin_fmaxf(W.sm.m, mx);
+    alpha = __builtin_amdgcn_exp2f(W.sm.m - m_new);
+    W.sm.m = m_new;
 #pragma unroll
     for (int r = 0; r < 16; ++r) pr[r] -= m_new;
   }
-  if (SIG && !SOFTMAX) {
-    // p = 1 / (1 + 2^u), u = -(s/sqrt(d) + b - slope|i-j|) log2(e)
-    const int jl = jc + 8 * L.h;  // key held by register 0 of this lane half
-    if (ALIBI) {
-      const float dist0 = (float)(L.qi - jl);
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        float dist = dist0 - (float)key_of_reg(r);
-        float w = __builtin_fmaf(L.sl2, __builtin_fabsf(dist), L.nbias);
-        pr[r] = __builtin_fmaf(s_cur[r], L.nscale, w);
-      }
-    } else {
-#pragma unroll
-      for (int r = 0; r < 16; ++r) pr[r] = __builtin_fmaf(s_cur[r], L.nscale, L.nbias);
-    }
-  }
+  float dist0 = 0.f;
+  if (SIG && !SOFTMAX && ALIBI) dist0 = (float)(W.qi - jl);
+  int lim = N - 1 - jl;  // STEP_LAST: registers whose key offset exceeds lim are masked
+  if (causal) lim = lim < W.qi - jl ? lim : W.qi - jl;
+  u32x4 pw = {0, 0, 0, 0};
+
   if (QK) {
 #pragma unroll
     for (int r = 0; r < 16; ++r) s_nxt[r] = 0.f;
   }
-  // interleave: one MFMA of each product, then a slice of the sigmoid
-  constexpr int NM = KD > 2 * DT ? KD : 2 * DT;
 #pragma unroll
   for (int m = 0; m < NM; ++m) {
-    if (QK && m < KD) s_nxt = mfma32(kf[m], qf[m], s_nxt);
-    if (PV && m < 2 * DT) oacc[m % DT] = mfma32(vf[m], p_prv[m / DT], oacc[m % DT]);
-    if (SIG) {
-#pragma unroll
-      for (int r = (16 * m) / NM; r < (16 * (m + 1)) / NM; ++r)
-        pr[r] = SOFTMAX ? __builtin_amdgcn_exp2f(pr[r]) : __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(pr[r]));
+    // ---- sub-slot A: S^T MFMA, refill its K fragment, first half of two sigmoids
+    if (QK) {
+      s_nxt = mfma32(W.kf[m], W.qf[m], s_nxt);
+      W.kf[m] = as_bf16x8(lds_read_b128(W.koff[m] + kaddr));
     }
+    if (SIG && !SOFTMAX) {
+      // p = 1 / (1 + 2^u), u = -(s/sqrt(d) + b - slope|i-j|) log2(e)
+#pragma unroll
+      for (int r = EPS * m; r < EPS * m + EPS; ++r) {
+        float w = W.nbias;
+        if (ALIBI) w = __builtin_fmaf(W.sl2, __builtin_fabsf(dist0 - (float)key_of_reg(r)), W.nbias);
+        pr[r] = __builtin_amdgcn_exp2f(__builtin_fmaf(s_cur[r], W.nscale, w));
+      }
+    }
+    if (SIG && SOFTMAX) {
+#pragma unroll
+      for (int r = EPS * m; r < EPS * m + EPS; ++r) pr[r] = __builtin_amdgcn_exp2f(pr[r]);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    // ---- sub-slot B: O^T MFMA, refill its V fragment, second half of the two sigmoids
+    W.oacc[m % DT] = mfma32(W.vf[m], p_prv[m / DT], W.oacc[m % DT]);
+    if (SIG) {
+      const uint32_t a0 = W.voff[m % DT] + vaddr + (m / DT) * 16 * (D * 2);
+      W.vf[m] = join_tr(lds_read_tr16(a0), lds_read_tr16(a0 + 4 * (D * 2)));
+    }
+    if (SIG && !SOFTMAX) {
+#pragma unroll
+      for (int r = EPS * m; r < EPS * m + EPS; ++r) {
+        pr[r] = __builtin_amdgcn_rcpf(1.0f + pr[r]);
+        if (KIND == STEP_LAST) pr[r] = key_of_reg(r) <= lim ? pr[r] : 0.f;
+      }
+      // registers 8ks..8ks+7 form the P^T operand of contraction step ks
+#pragma unroll
+      for (int r = EPS * m; r < EPS * m + EPS; r += 2) {
+        pw[(r & 7) >> 1] = pack_bf16(pr[r], pr[r + 1]);
+        if ((r & 7) == 6) p_cur[r >> 3] = as_bf16x8(pw);
+      }
+    }
+    __builtin_amdgcn_sched_barrier(0);
   }
   if (SIG && SOFTMAX) {
     float sum = 0.f;
 #pragma unroll
     for (int r = 0; r < 16; ++r) sum += pr[r];
-    sm.l = __builtin_fmaf(sm.l, alpha, sum);
+    W.sm.l = __builtin_fmaf(W.sm.l, alpha, sum);
     // O^T holds sums relative to the previous maximum: rescale only when some maximum moved
     if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
 #pragma unroll
       for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) oacc[dt][r] *= alpha;
-    }
-  }
-  if (SIG) {
-    if (mask && !SOFTMAX) {
-      const int jl = jc + 8 * L.h;
-      int lim = N - 1 - jl;
-      if (causal) lim = lim < L.qi - jl ? lim : L.qi - jl;
-#pragma unroll
-      for (int r = 0; r < 16; ++r) pr[r] = key_of_reg(r) <= lim ? pr[r] : 0.f;
+        for (int r = 0; r < 16; ++r) W.oacc[dt][r] *= alpha;
     }
 #pragma unroll
     for (int ks2 = 0; ks2 < 2; ++ks2) {
-      u32x4 pw;
 #pragma unroll
       for (int w = 0; w < 4; ++w) pw[w] = pack_bf16(pr[8 * ks2 + 2 * w], pr[8 * ks2 + 2 * w + 1]);
       p_cur[ks2] = as_bf16x8(pw);
@@ -199,10 +230,19 @@ __device__ __forceinline__ void fwd_step(const FwdLane<D>& L, const bf16x8* qf, 
   }
 }
 
-template <int D, bool CAUSAL, bool ALIBI, bool SOFTMAX>
-__global__ void __launch_bounds__(512, 1)
+// Dispatch one step of chunk c for a wave that owns chunks 0..cw-1.
+template <int D, bool ALIBI, bool SOFTMAX, int PAR>
+__device__ __forceinline__ void fwd_step_any(FwdWave<D>& W, int c, int cw, uint32_t kaddr, uint32_t vaddr, int N,
+                                             bool causal) {
+  if (c + 1 < cw) fwd_step<D, ALIBI, SOFTMAX, STEP_FULL, PAR>(W, kaddr, vaddr, 32 * c, N, causal);
+  else if (c + 1 == cw) fwd_step<D, ALIBI, SOFTMAX, STEP_LAST, PAR>(W, kaddr, vaddr, 32 * c, N, causal);
+  else if (c == cw) fwd_step<D, ALIBI, SOFTMAX, STEP_TAIL, PAR>(W, kaddr, vaddr, 32 * c, N, causal);
+}
+
+template <int D, int NW, bool CAUSAL, bool ALIBI, bool SOFTMAX>
+__global__ void __launch_bounds__(64 * NW, 8 / NW)
 attn_fwd_kernel(const FwdParams p) {
-  constexpr int NW = 8, NT = 64 * NW, BR = 32 * NW, BC = 64;
+  constexpr int BR = 32 * NW, BC = 64;
   constexpr int KD = D / 16, DT = D / 32;
   constexpr int TILE = BC * D * 2;    // bytes of one K or V tile
   constexpr int CHUNK = 32 * D * 2;   // bytes of a 32-key chunk
@@ -232,32 +272,36 @@ attn_fwd_kernel(const FwdParams p) {
   const int qi = q_wave0 + l32;             // this lane's query row
   const int qi_ld = qi < N ? qi : N - 1;
 
+  FwdWave<D> W;
   // Q fragment: B operand of S^T = K Q^T, column = query, k = d
-  bf16x8 qf[KD];
 #pragma unroll
-  for (int kk = 0; kk < KD; ++kk) qf[kk] = as_bf16x8(*(const u32x4*)(qbase + (int64_t)qi_ld * p.q.ss + 16 * kk + 8 * h));
-
-  f32x16 oacc[DT];
+  for (int kk = 0; kk < KD; ++kk)
+    W.qf[kk] = as_bf16x8(*(const u32x4*)(qbase + (int64_t)qi_ld * p.q.ss + 16 * kk + 8 * h));
 #pragma unroll
   for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-    for (int r = 0; r < 16; ++r) oacc[dt][r] = 0.f;
-
-  FwdLane<D> L;
+    for (int r = 0; r < 16; ++r) W.oacc[dt][r] = 0.f;
   {
     const int kap = kappa(l32);
 #pragma unroll
-    for (int kk = 0; kk < KD; ++kk) L.koff[kk] = kap * (D * 2) + (((2 * kk + h) ^ Swz<D>::k(kap)) << 4);
+    for (int kk = 0; kk < KD; ++kk) W.koff[kk] = kring + kap * (D * 2) + (((2 * kk + h) ^ Swz<D>::k(kap)) << 4);
     const int i16 = lane & 15, blk1 = (lane >> 4) & 1;
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt) {
       int row = 8 * h + (i16 >> 2);
       int c = 4 * dt + 2 * blk1 + ((i16 & 3) >> 1);
-      L.voff[dt] = row * (D * 2) + ((c ^ Swz<D>::v(row)) << 4) + ((i16 & 1) << 3);
+      W.voff[dt] = vring + row * (D * 2) + ((c ^ Swz<D>::v(row)) << 4) + ((i16 & 1) << 3);
     }
-    L.qi = qi; L.h = h;
-    L.nscale = p.nscale_log2; L.nbias = p.nbias_log2;
-    L.sl2 = ALIBI ? p.slopes[hd] * kLog2e : 0.f;
+    W.qi = qi; W.h = h;
+    W.nscale = p.nscale_log2; W.nbias = p.nbias_log2;
+    W.sl2 = ALIBI ? p.slopes[hd] * kLog2e : 0.f;
+    W.sm = SoftmaxState{-__builtin_inff(), 0.f};
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { W.s[0][r] = 0.f; W.s[1][r] = 0.f; }
+    const bf16x8 z = as_bf16x8(u32x4{0, 0, 0, 0});
+    W.p[0][0] = W.p[0][1] = W.p[1][0] = W.p[1][1] = z;
+#pragma unroll
+    for (int m = 0; m < 2 * DT; ++m) W.vf[m] = z;  // step 0 multiplies these by P^T(-1) = 0
   }
 
   // keys this workgroup must visit, and chunks this wave must visit
@@ -268,100 +312,127 @@ attn_fwd_kernel(const FwdParams p) {
   if (CAUSAL) kv_wave = q_wave0 + 32 < N ? q_wave0 + 32 : N;
   const int cw = q_wave0 < N ? (kv_wave + 31) / 32 : 0;  // chunks 0..cw-1; waves past the end idle
 
-  TileStager<D, BC, NT, false> kst;
-  TileStager<D, BC, NT, true> vst;
-  // prologue: K(0), V(0), K(1) visible before the first step
-  kst.load(kbase, p.k.ss, 0, N, tid);
-  vst.load(vbase, p.v.ss, 0, N, tid);
-  kst.store(kring, tid);
-  vst.store(vring, tid);
-  if (n_tiles > 1) {
-    kst.load(kbase, p.k.ss, BC, N, tid);
-    kst.store(kring + TILE, tid);
-  }
-  __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): the Q fragment is in registers before the loop starts
+  // LDS rings: K tile t in K slot t%3, V tile t in V slot t%3.  At the start of tile t the
+  // loads of K(t+3) and V(t+2) are issued; they must have landed by the end of tile t+1.
+  // K(t+3) overwrites K(t), whose last reads happened during tile t-1; V(t+2) overwrites
+  // V(t-1), ditto: the barrier that ends tile t-1 orders both.
+  DmaStager<D, BC, NW, false> kst;
+  DmaStager<D, BC, NW, true> vst;
+  constexpr int NIK = DmaStager<D, BC, NW, false>::NI, NIV = DmaStager<D, BC, NW, true>::NI;
+  const int uwave = __builtin_amdgcn_readfirstlane(wave);
+  kst.init(kbase, p.k.ss, N, uwave, lane);
+  vst.init(vbase, p.v.ss, N, uwave, lane);
+  kst.issue(kring, 0, N, uwave);
+  vst.issue(vring, 0, N, uwave);
+  if (n_tiles > 1) { kst.issue(kring + TILE, BC, N, uwave); vst.issue(vring + TILE, BC, N, uwave); }
+  if (n_tiles > 2) kst.issue(kring + 2 * TILE, 2 * BC, N, uwave);
+  SATTN_WAIT_VMCNT(0);  // prologue tiles landed; the Q fragment is in registers
   __syncthreads();
 
-  f32x16 s_cur, s_nxt;
-  bf16x8 p_cur[2], p_prv[2];
-#pragma unroll
-  for (int r = 0; r < 16; ++r) { s_cur[r] = 0.f; s_nxt[r] = 0.f; }
-  p_cur[0] = p_cur[1] = p_prv[0] = p_prv[1] = as_bf16x8(u32x4{0, 0, 0, 0});
-  SoftmaxState sm{-__builtin_inff(), 0.f};
-
-  // step -1: S^T(0)
+  // step -1: S^T(0) into s[0], then fetch K(1)
   if (cw > 0) {
-    fwd_step<D, ALIBI, SOFTMAX, true, false, false>(L, qf, oacc, s_cur, s_nxt, p_cur, p_prv, kring, 0, 0, false, N, CAUSAL, sm);
-    s_cur = s_nxt;
-  }
-
-  int kslot = 0, vslot = 0;  // ring slot of tile t (K) and of tile t (V)
-  for (int t = 0; t < n_tiles; ++t) {
-    const bool k_more = t + 2 < n_tiles, v_more = t + 1 < n_tiles;
-    if (k_more) kst.load(kbase, p.k.ss, (t + 2) * BC, N, tid);
-    if (v_more) vst.load(vbase, p.v.ss, (t + 1) * BC, N, tid);
-    const int kslot1 = kslot == 2 ? 0 : kslot + 1, kslot2 = kslot1 == 2 ? 0 : kslot1 + 1;
-    const int vslot1 = vslot == 2 ? 0 : vslot + 1, vslotm = vslot == 0 ? 2 : vslot - 1;
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      const int c = 2 * t + i;
-      // K(c+1): chunk (c+1)%2 of tile (c+1)/2 ; V(c-1): chunk (c-1)%2 of tile (c-1)/2
-      const uint32_t ka = kring + (i == 0 ? kslot * TILE + CHUNK : kslot1 * TILE);
-      const uint32_t va = vring + (i == 0 ? vslotm * TILE + CHUNK : vslot * TILE);
-      if (c + 1 < cw) {
-        if (c == 0)
-          fwd_step<D, ALIBI, SOFTMAX, true, true, false>(L, qf, oacc, s_cur, s_nxt, p_cur, p_prv, ka, va, 32 * c, false, N, CAUSAL, sm);
-        else
-          fwd_step<D, ALIBI, SOFTMAX, true, true, true>(L, qf, oacc, s_cur, s_nxt, p_cur, p_prv, ka, va, 32 * c, false, N, CAUSAL, sm);
-        s_cur = s_nxt;
-        p_prv[0] = p_cur[0]; p_prv[1] = p_cur[1];
-      } else if (c + 1 == cw) {
-        // last chunk of this wave: the only one that can touch the diagonal or the ragged end
-        if (c == 0)
-          fwd_step<D, ALIBI, SOFTMAX, false, true, false>(L, qf, oacc, s_cur, s_nxt, p_cur, p_prv, ka, va, 32 * c, true, N, CAUSAL, sm);
-        else
-          fwd_step<D, ALIBI, SOFTMAX, false, true, true>(L, qf, oacc, s_cur, s_nxt, p_cur, p_prv, ka, va, 32 * c, true, N, CAUSAL, sm);
-        p_prv[0] = p_cur[0]; p_prv[1] = p_cur[1];
-      } else if (c == cw) {
-        fwd_step<D, ALIBI, SOFTMAX, false, false, true>(L, qf, oacc, s_cur, s_nxt, p_cur, p_prv, ka, va, 32 * c, false, N, CAUSAL, sm);
-      }
-    }
-    if (k_more) kst.store(kring + kslot2 * TILE, tid);
-    if (v_more) vst.store(vring + vslot1 * TILE, tid);
-    kslot = kslot1;
-    vslot = vslot1;
+    for (int kk = 0; kk < KD; ++kk) W.kf[kk] = as_bf16x8(lds_read_b128(W.koff[kk]));
+#pragma unroll
+    for (int kk = 0; kk < KD; ++kk) W.s[0] = mfma32(W.kf[kk], W.qf[kk], W.s[0]);
+#pragma unroll
+    for (int kk = 0; kk < KD; ++kk) W.kf[kk] = as_bf16x8(lds_read_b128(W.koff[kk] + CHUNK));
+  }
+  __syncthreads();  // every wave has read K tile 0 before tile 0 lets K(3) overwrite it
+
+  // Tile t: steps 2t, 2t+1.  Step c refills kf from K chunk c+2 (tile t+1, slot (t+1)%3) and
+  // vf from V chunk c (tile t, slot t%3).  The per-lane LDS addresses rotate with the rings.
+#pragma unroll
+  for (int kk = 0; kk < KD; ++kk) W.koff[kk] += TILE;  // K reads now point at tile 1
+#ifdef SATTN_EXP_TIMING
+  uint64_t tacc[5] = {0, 0, 0, 0, 0};
+  const uint64_t tstart = __builtin_amdgcn_s_memtime();
+#endif
+  int kslot = 0;  // ring slot of K tile t == slot that K(t+3) will overwrite; V tile t is in the same slot index
+  for (int t = 0; t < n_tiles; ++t) {
+#ifdef SATTN_EXP_NOLOAD
+    const bool k_more = false, v_more = false;
+#else
+    const bool k_more = t + 3 < n_tiles, v_more = t + 2 < n_tiles;
+#endif
+    const int vslot2 = kslot == 0 ? 2 : kslot - 1;  // (t+2)%3
+#ifdef SATTN_EXP_TIMING
+    __builtin_amdgcn_sched_barrier(0); const uint64_t tm0 = __builtin_amdgcn_s_memtime(); __builtin_amdgcn_s_waitcnt(0xC07F); __builtin_amdgcn_sched_barrier(0);
+#endif
+    if (k_more) kst.issue(kring + kslot * TILE, (t + 3) * BC, N, uwave);
+    if (v_more) vst.issue(vring + vslot2 * TILE, (t + 2) * BC, N, uwave);
+#ifdef SATTN_EXP_TIMING
+    __builtin_amdgcn_sched_barrier(0); const uint64_t tm1 = __builtin_amdgcn_s_memtime(); __builtin_amdgcn_s_waitcnt(0xC07F); __builtin_amdgcn_sched_barrier(0);
+#endif
+    fwd_step_any<D, ALIBI, SOFTMAX, 0>(W, 2 * t, cw, 0, 0, N, CAUSAL);
+#ifdef SATTN_EXP_TIMING
+    __builtin_amdgcn_sched_barrier(0); const uint64_t tm2 = __builtin_amdgcn_s_memtime(); __builtin_amdgcn_s_waitcnt(0xC07F); __builtin_amdgcn_sched_barrier(0);
+#endif
+    fwd_step_any<D, ALIBI, SOFTMAX, 1>(W, 2 * t + 1, cw, CHUNK, CHUNK, N, CAUSAL);
+#ifdef SATTN_EXP_TIMING
+    __builtin_amdgcn_sched_barrier(0); const uint64_t tm3 = __builtin_amdgcn_s_memtime(); __builtin_amdgcn_s_waitcnt(0xC07F); __builtin_amdgcn_sched_barrier(0);
+#endif
+    // advance the read addresses by one ring slot: K reads are at slot (t+1)%3, V reads at t%3
+    const int kadv = kslot == 1 ? -2 * TILE : TILE;  // slot (t+1)%3 == 2 wraps to 0
+    const int vadv = kslot == 2 ? -2 * TILE : TILE;
+#pragma unroll
+    for (int kk = 0; kk < KD; ++kk) W.koff[kk] += kadv;
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) W.voff[dt] += vadv;
+    kslot = kslot == 2 ? 0 : kslot + 1;
+    // everything issued before this tile must have landed; this tile's own loads may fly on
+    if (k_more) SATTN_WAIT_VMCNT(NIK + NIV);
+    else if (v_more) SATTN_WAIT_VMCNT(NIV);
+    else SATTN_WAIT_VMCNT(0);
+#ifdef SATTN_EXP_TIMING
+    __builtin_amdgcn_sched_barrier(0); const uint64_t tm4 = __builtin_amdgcn_s_memtime(); __builtin_amdgcn_s_waitcnt(0xC07F); __builtin_amdgcn_sched_barrier(0);
+#endif
+#ifndef SATTN_EXP_NOBARRIER
     __syncthreads();
+#endif
+#ifdef SATTN_EXP_TIMING
+    __builtin_amdgcn_sched_barrier(0); const uint64_t tm5 = __builtin_amdgcn_s_memtime(); __builtin_amdgcn_s_waitcnt(0xC07F); __builtin_amdgcn_sched_barrier(0);
+    tacc[0] += tm1 - tm0; tacc[1] += tm2 - tm1; tacc[2] += tm3 - tm2; tacc[3] += tm4 - tm3; tacc[4] += tm5 - tm4;
+#endif
   }
   // flush: O^T update of the last chunk when it fell on the last step of the loop
-  if (cw == 2 * n_tiles && cw > 0) {
-    const int vlast = vslot == 0 ? 2 : vslot - 1;  // slot of tile n_tiles-1
-    fwd_step<D, ALIBI, SOFTMAX, false, false, true>(L, qf, oacc, s_cur, s_nxt, p_cur, p_prv, 0, vring + vlast * TILE + CHUNK, 0,
-                                           false, N, CAUSAL, sm);
-  }
+  if (cw == 2 * n_tiles && cw > 0) fwd_step<D, ALIBI, SOFTMAX, STEP_TAIL, 0>(W, 0, 0, 0, N, CAUSAL);
 
   if (SOFTMAX) {
     // normalise by the row sum (both lane halves) and write the natural-log row log-sum-exp
-    const float l_tot = sm.l + __shfl_xor(sm.l, 32);
+    const float l_tot = W.sm.l + __shfl_xor(W.sm.l, 32);
     const float inv = 1.0f / l_tot;
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) oacc[dt][r] *= inv;
-    if (qi < N && h == 0) p.lse[(int64_t)bh * N + qi] = (sm.m + __builtin_amdgcn_logf(l_tot)) * kLn2;
+      for (int r = 0; r < 16; ++r) W.oacc[dt][r] *= inv;
+    if (qi < N && h == 0) p.lse[(int64_t)bh * N + qi] = (W.sm.m + __builtin_amdgcn_logf(l_tot)) * kLn2;
   }
+#ifdef SATTN_EXP_TIMING_NEVER
+#else
   // ---- store O (bf16): register 4g+t of tile dt is O[qi][32dt + 8g + 4h + t]
   if (qi < N) {
+#endif
     __bf16* orow = obase + (int64_t)qi * p.o.ss;
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
         u32x2 w;
-        w[0] = pack_bf16(oacc[dt][4 * g], oacc[dt][4 * g + 1]);
-        w[1] = pack_bf16(oacc[dt][4 * g + 2], oacc[dt][4 * g + 3]);
+        w[0] = pack_bf16(W.oacc[dt][4 * g], W.oacc[dt][4 * g + 1]);
+        w[1] = pack_bf16(W.oacc[dt][4 * g + 2], W.oacc[dt][4 * g + 3]);
         *(u32x2*)(orow + 32 * dt + 8 * g + 4 * h) = w;
       }
   }
+#ifdef SATTN_EXP_TIMING
+  __syncthreads();
+  if (lane == 0 && qi < N) {
+    uint64_t* dbg = (uint64_t*)(obase + (int64_t)qi * p.o.ss);
+    for (int i = 0; i < 5; ++i) dbg[i] = tacc[i];
+    dbg[5] = __builtin_amdgcn_s_memtime() - tstart;
+    dbg[6] = n_tiles;
+  }
+#endif
 }
 
 }  // namespace sattn
