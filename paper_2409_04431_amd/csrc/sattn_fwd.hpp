@@ -230,11 +230,94 @@ __device__ __forceinline__ void fwd_step(FwdWave<D>& W, uint32_t kaddr, uint32_t
   }
 }
 
+// ---- The steady-state step with a hand-pinned instruction order.
+// Every instruction below is a volatile asm statement, which the compiler neither reorders
+// nor drops, so the stream that reaches the SIMD is exactly: one MFMA, one fragment refill
+// from LDS, then a slice of the sigmoid whose dependent operations sit a full slice apart.
+// (The compiler still allocates registers and inserts the LDS wait counts: the refills are
+// ordinary loads.)  The MFMA asm carries a memory clobber to keep those loads in place.
+__device__ __forceinline__ void a_mfma(f32x16& c, const bf16x8& a, const bf16x8& b) {
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(c) : "v"(a), "v"(b) : "memory");
+}
+__device__ __forceinline__ void a_mfma_zero(f32x16& c, const bf16x8& a, const bf16x8& b) {
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(c) : "v"(a), "v"(b) : "memory");
+}
+
+// Sigmoid of the 16 accumulator registers as 4 groups x 18 operations.  Inside a group of
+// four elements the order is F F F F  X X X X  A A A A  R R R R  C C (scale+bias fma, exp2,
+// 1+e, reciprocal, bf16 pack), so a result is consumed four instructions after it was issued.
+template <int D, bool ALIBI, int I>
+__device__ __forceinline__ void sig_op(const FwdWave<D>& W, const f32x16& s, float (&u)[16], uint32_t (&wp)[8],
+                                       float nbias_v, float sl2_v, float dist0) {
+  constexpr int G = I / 18, i = I % 18, e = 4 * G + (i & 3);
+  if constexpr (i < 4) {
+    if constexpr (ALIBI) {
+      float t, w;
+      const float keyf = (float)key_of_reg(e);
+      asm volatile("v_sub_f32 %0, %1, %2" : "=v"(t) : "v"(dist0), "v"(keyf));
+      asm volatile("v_fma_f32 %0, %1, |%2|, %3" : "=v"(w) : "v"(sl2_v), "v"(t), "v"(nbias_v));
+      asm volatile("v_fma_f32 %0, %1, %2, %3" : "=v"(u[e]) : "v"(s[e]), "s"(W.nscale), "v"(w));
+    } else {
+      asm volatile("v_fma_f32 %0, %1, %2, %3" : "=v"(u[e]) : "v"(s[e]), "s"(W.nscale), "v"(nbias_v));
+    }
+  } else if constexpr (i < 8) {
+    asm volatile("v_exp_f32 %0, %0" : "+v"(u[e]));
+  } else if constexpr (i < 12) {
+    asm volatile("v_add_f32 %0, 1.0, %0" : "+v"(u[e]));
+  } else if constexpr (i < 16) {
+    asm volatile("v_rcp_f32 %0, %0" : "+v"(u[e]));
+  } else {
+    constexpr int j = 2 * G + (i - 16);  // word j packs elements 2j, 2j+1
+    asm volatile("v_cvt_pk_bf16_f32 %0, %1, %2" : "=v"(wp[j]) : "v"(u[2 * j]), "v"(u[2 * j + 1]));
+  }
+}
+template <int D, bool ALIBI, int LO, int HI>
+__device__ __forceinline__ void sig_ops(const FwdWave<D>& W, const f32x16& s, float (&u)[16], uint32_t (&wp)[8],
+                                        float nbias_v, float sl2_v, float dist0) {
+  if constexpr (LO < HI) {
+    sig_op<D, ALIBI, LO>(W, s, u, wp, nbias_v, sl2_v, dist0);
+    sig_ops<D, ALIBI, LO + 1, HI>(W, s, u, wp, nbias_v, sl2_v, dist0);
+  }
+}
+
+template <int D, bool ALIBI, int PAR, int K>
+__device__ __forceinline__ void full_subslots(FwdWave<D>& W, uint32_t kaddr, uint32_t vaddr, float (&u)[16],
+                                              uint32_t (&wp)[8], float nbias_v, float sl2_v, float dist0) {
+  constexpr int KD = D / 16, DT = D / 32, NSUB = 2 * KD, NOPS = 72;
+  if constexpr (K < NSUB) {
+    constexpr int m = K / 2;
+    if constexpr ((K & 1) == 0) {
+      if constexpr (m == 0) a_mfma_zero(W.s[PAR ^ 1], W.kf[m], W.qf[m]);
+      else a_mfma(W.s[PAR ^ 1], W.kf[m], W.qf[m]);
+      W.kf[m] = as_bf16x8(lds_read_b128(W.koff[m] + kaddr));
+    } else {
+      a_mfma(W.oacc[m % DT], W.vf[m], W.p[PAR ^ 1][m / DT]);
+      const uint32_t a0 = W.voff[m % DT] + vaddr + (m / DT) * 16 * (D * 2);
+      W.vf[m] = join_tr(lds_read_tr16(a0), lds_read_tr16(a0 + 4 * (D * 2)));
+    }
+    sig_ops<D, ALIBI, (K * NOPS) / NSUB, ((K + 1) * NOPS) / NSUB>(W, W.s[PAR], u, wp, nbias_v, sl2_v, dist0);
+    full_subslots<D, ALIBI, PAR, K + 1>(W, kaddr, vaddr, u, wp, nbias_v, sl2_v, dist0);
+  }
+}
+
+template <int D, bool ALIBI, int PAR>
+__device__ __forceinline__ void fwd_step_full_pinned(FwdWave<D>& W, uint32_t kaddr, uint32_t vaddr, int jc) {
+  float u[16];
+  uint32_t wp[8];
+  const float dist0 = (float)(W.qi - (jc + 8 * W.h));
+  full_subslots<D, ALIBI, PAR, 0>(W, kaddr, vaddr, u, wp, W.nbias, W.sl2, dist0);
+  W.p[PAR][0] = as_bf16x8(u32x4{wp[0], wp[1], wp[2], wp[3]});
+  W.p[PAR][1] = as_bf16x8(u32x4{wp[4], wp[5], wp[6], wp[7]});
+}
+
 // Dispatch one step of chunk c for a wave that owns chunks 0..cw-1.
 template <int D, bool ALIBI, bool SOFTMAX, int PAR>
 __device__ __forceinline__ void fwd_step_any(FwdWave<D>& W, int c, int cw, uint32_t kaddr, uint32_t vaddr, int N,
                                              bool causal) {
-  if (c + 1 < cw) fwd_step<D, ALIBI, SOFTMAX, STEP_FULL, PAR>(W, kaddr, vaddr, 32 * c, N, causal);
+  if (c + 1 < cw) {
+    if constexpr (SOFTMAX) fwd_step<D, ALIBI, SOFTMAX, STEP_FULL, PAR>(W, kaddr, vaddr, 32 * c, N, causal);
+    else fwd_step_full_pinned<D, ALIBI, PAR>(W, kaddr, vaddr, 32 * c);
+  }
   else if (c + 1 == cw) fwd_step<D, ALIBI, SOFTMAX, STEP_LAST, PAR>(W, kaddr, vaddr, 32 * c, N, causal);
   else if (c == cw) fwd_step<D, ALIBI, SOFTMAX, STEP_TAIL, PAR>(W, kaddr, vaddr, 32 * c, N, causal);
 }
