@@ -21,9 +21,10 @@ if ROOT not in sys.path:
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 matrix peak
 
-# HBM bytes per launch of the dominant kernel, from `rocprofv3 --pmc FETCH_SIZE` and
-# `--pmc WRITE_SIZE` runs of this script (summaries under profiles/); None until measured.
-MEASURED_TRAFFIC_BYTES = None
+# HBM bytes per launch of the dominant kernel (dK/dV on the headline workload), from
+# `rocprofv3 --pmc FETCH_SIZE` and `--pmc WRITE_SIZE` runs of this script scaled by a plain
+# copy kernel: 2 x 262 199 KiB read + 262 144 KiB written (profiles/attn_kernels_cfg3_pmc.txt).
+MEASURED_TRAFFIC_BYTES = {3: (2 * 262199 + 262144) * 1024}
 
 
 def _events(n):
@@ -144,16 +145,16 @@ def main():
         # 5 backward products (8*B*H*N^2*d, halved when causal); dQ's recompute is not counted.
         algo = 0.8 * flops_b
         ach = algo / dkdv_ms / 1e9
-        out["roofline"] = {"kernel": "sigmoid_bwd_dkdv_kernel", "bound": "mfma", "achieved": ach,
+        out["roofline"] = {"kernel": "attn_bwd_dkdv_kernel", "bound": "mfma", "achieved": ach,
                            "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": ach / MFMA_BF16_PEAK_TFLOPS,
-                           "traffic": MEASURED_TRAFFIC_BYTES, "avg_launch_ms": dkdv_ms}
+                           "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.cfg), "avg_launch_ms": dkdv_ms}
     else:
         out["value"] = flops_f / ms_step / 1e9
         out["frac_of_bf16_mfma_peak"] = out["value"] / MFMA_BF16_PEAK_TFLOPS
         ach = flops_f / fwd_ms / 1e9
-        out["roofline"] = {"kernel": "sigmoid_fwd_kernel", "bound": "mfma", "achieved": ach,
+        out["roofline"] = {"kernel": "attn_fwd_kernel", "bound": "mfma", "achieved": ach,
                            "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": ach / MFMA_BF16_PEAK_TFLOPS,
-                           "traffic": MEASURED_TRAFFIC_BYTES, "avg_launch_ms": fwd_ms}
+                           "traffic": None, "avg_launch_ms": fwd_ms}
 
     if args.softmax:
         lse = torch.empty(cfg.B, cfg.H, cfg.N, dtype=torch.float32, device=dev)
