@@ -129,17 +129,16 @@ enum BwdPart { kBwdDkDv = 1, kBwdDq = 2 };
 
 template <int D, bool SOFTMAX>
 int launch_bwd_bf16(BwdParams p, int causal, bool alibi, int parts, hipStream_t st) {
-  constexpr int BC = 64, NW = 4;
-  constexpr size_t lds = 4 * BC * D * 2;
-  constexpr size_t lds_stat = SOFTMAX ? 2 * 2 * BC * sizeof(float) : 0;
-  p.n_blocks = (p.N + 32 * NW - 1) / (32 * NW);
-  dim3 grid(p.n_blocks * p.B * p.H), block(64 * NW);
+  constexpr size_t lds = 4 * 2 * 64 * D * 2;                    // 4 ring slots of two 64-row tiles
+  constexpr size_t lds_stat = SOFTMAX ? 4 * 128 * sizeof(float) : 0;  // per-slot lse and D of the query tile
+  p.n_blocks = (p.N + 127) / 128;
+  dim3 grid(p.n_blocks * p.B * p.H), block(256);
   int rc = SATTN_OK;
   if (parts & kBwdDkDv)
     SATTN_DISPATCH2(causal, alibi,
-                    rc = launch(attn_bwd_dkdv_kernel<D, BC, NW, A, B2, SOFTMAX>, grid, block, lds + lds_stat, st, p));
+                    rc = launch(attn_bwd_kernel<D, BWD_DKDV, A, B2, SOFTMAX>, grid, block, lds + lds_stat, st, p));
   if (rc == SATTN_OK && (parts & kBwdDq))
-    SATTN_DISPATCH2(causal, alibi, rc = launch(attn_bwd_dq_kernel<D, BC, NW, A, B2, SOFTMAX>, grid, block, lds, st, p));
+    SATTN_DISPATCH2(causal, alibi, rc = launch(attn_bwd_kernel<D, BWD_DQ, A, B2, SOFTMAX>, grid, block, lds, st, p));
   return rc;
 }
 

@@ -3,18 +3,27 @@
 // but Q, K, V, dO is read.
 //
 // Algorithm 2 keeps dK_j, dV_j on chip and read-modify-writes dQ_i in HBM.  Here the pass
-// is split in two kernels so that every output tile has exactly one owner and no atomics or
-// fp32 dQ workspace are needed (results are bit-reproducible):
-//   dq kernel   : query block stationary, streams K/V tiles (S^T orientation, as forward)
-//                 S^T = K Q^T, dP^T = V dO^T, dS^T = P^T(1-P^T)dP^T, dQ^T += K^T dS^T
-//   dkdv kernel : key block stationary, streams Q/dO tiles (S orientation)
-//                 S = Q K^T, dP = dO V^T, dS = P(1-P)dP, dV^T += dO^T P, dK^T += Q^T dS
-// In both, the accumulator of the first product is, after the bf16 round, the B operand of
-// the second; the A operand of the second is a transposing LDS read of a row-major tile.
+// is split in two launches of one kernel template so that every output tile has exactly
+// one owner and no atomics or fp32 dQ workspace are needed (results are bit-reproducible):
+//   DQ   : query block stationary (Q, dO fragments in registers), streams K/V tiles
+//          S^T = K Q^T, dP^T = V dO^T, dS^T = P^T(1-P^T)dP^T, dQ^T += K^T dS^T
+//   DKDV : key block stationary (K, V fragments in registers), streams Q/dO tiles
+//          S = Q K^T, dP = dO V^T, dS = P(1-P)dP, dV^T += dO^T P, dK^T += Q^T dS
+// In both, the streamed rows land on the rows of the first products' accumulators, so after
+// the bf16 round those registers are the B operand of the second products; the A operand
+// of the second products is a transposing LDS read of the same row-major tiles.
+//
+// One workgroup = 4 waves (one per SIMD, up to 512 registers each), 32 stationary rows per
+// wave, 64-row streamed tiles in a 4-slot LDS ring filled by direct-to-LDS loads one tile
+// ahead.  Work is software pipelined over 32-row chunks: step s issues the first products
+// of chunk s, evaluates the sigmoid / dS of chunk s-1 and issues the second products of
+// chunk s-2.
 #pragma once
 #include "sattn_common.hpp"
 
 namespace sattn {
+
+enum BwdMode { BWD_DQ = 0, BWD_DKDV = 1 };
 
 struct BwdParams {
   TensorRef q, k, v, dout, dq, dk, dv;
@@ -22,7 +31,7 @@ struct BwdParams {
   const float* lse;    // softmax only: [B,H,N] natural-log row log-sum-exp from the forward
   const float* dvec;   // softmax only: [B,H,N] rowsum(dO o O)
   int B, H, N;
-  int n_blocks;        // query blocks (dq kernel) or key blocks (dkdv kernel)
+  int n_blocks;        // blocks of 128 stationary rows
   float nscale_log2;   // -log2(e)/sqrt(d)
   float nbias_log2;    // -b*log2(e)
   float inv_sqrt_d;
@@ -37,96 +46,38 @@ struct SwzX {
   }
 };
 
-// Stage two row-major tiles (ROWS x D bf16 each) global -> registers -> LDS, both with SwzX.
-template <int D, int ROWS, int NT>
-struct PairStager {
-  static constexpr int CPR = D / 8;
-  static constexpr int NCH = (ROWS * CPR) / NT;
-  static_assert((ROWS * CPR) % NT == 0, "tile must split evenly over the workgroup");
-  u32x4 areg[NCH], breg[NCH];
-
-  __device__ __forceinline__ void load(const __bf16* a, const __bf16* b, int64_t ass, int64_t bss, int r0, int N,
-                                       int tid) {
+// Direct-to-LDS staging of one 64-row tile: one wave-level global_load_lds_dwordx4 moves
+// 64 x 16 bytes to 1 KB of LDS at M0 + 16*lane; the XOR swizzle is applied on the global
+// side.  Completion is tracked by hand (vmcnt), the compiler never sees these loads.
+template <int D, int NW>
+struct DmaStagerX {
+  static constexpr int BC = 64, CPR = D / 8, RPI = 64 / CPR, NI = (BC * CPR) / (64 * NW);
+  const char* ptr[NI];   // this lane's source for the next tile to stage (unclamped)
+  const char* last[NI];  // this lane's source inside the last row N-1
+  int row[NI];           // tile-relative row this lane fills
+  int64_t tile_bytes;
+  __device__ __forceinline__ void init(const __bf16* base, int64_t ss, int N, int j0, int wave, int lane) {
 #pragma unroll
-    for (int n = 0; n < NCH; ++n) {
-      int idx = tid + n * NT;
-      int r = idx / CPR, c = idx % CPR;
-      int row = r0 + r;
-      row = row < N ? row : N - 1;  // clamped; the epilogue masks rows past the end
-      areg[n] = *(const u32x4*)(a + (int64_t)row * ass + c * 8);
-      breg[n] = *(const u32x4*)(b + (int64_t)row * bss + c * 8);
+    for (int n = 0; n < NI; ++n) {
+      const int r = (wave * NI + n) * RPI + lane / CPR, pc = lane % CPR;
+      const int c = pc ^ SwzX<D>::f(r);
+      row[n] = r;
+      ptr[n] = (const char*)(base + (int64_t)(j0 + r) * ss + c * 8);
+      last[n] = (const char*)(base + (int64_t)(N - 1) * ss + c * 8);
     }
+    tile_bytes = (int64_t)BC * ss * 2;
   }
-  __device__ __forceinline__ void store(uint32_t as, uint32_t bs, int tid) const {
+  __device__ __forceinline__ void issue(uint32_t lds, int j0, int N, int wave) {
 #pragma unroll
-    for (int n = 0; n < NCH; ++n) {
-      int idx = tid + n * NT;
-      int r = idx / CPR, c = idx % CPR;
-      uint32_t off = r * (D * 2) + ((c ^ SwzX<D>::f(r)) << 4);
-      lds_write_b128(as + off, areg[n]);
-      lds_write_b128(bs + off, breg[n]);
+    for (int n = 0; n < NI; ++n) {
+      const char* src = ptr[n];
+      if (j0 + BC > N) src = (j0 + row[n] < N) ? src : last[n];  // rows past the end re-read row N-1
+      const uint32_t m0v = lds + (wave * NI + n) * 1024;
+      asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(src), "s"(m0v) : "memory");
+      ptr[n] += tile_bytes;
     }
   }
 };
-
-// Per-lane LDS byte offsets into a SwzX tile.
-template <int D>
-struct TileOffsets {
-  static constexpr int KD = D / 16, DT = D / 32;
-  uint32_t row[KD];     // row-wise A operand: row kappa(l32), chunk 2kk+h
-  uint32_t tr[DT][2];   // transposing read: rows 8h + 4rd + i16/4 (+16ks +32ck), cols 32dt + ...
-  __device__ __forceinline__ void init(int lane) {
-    const int l32 = lane & 31, h = lane >> 5, i16 = lane & 15, blk1 = (lane >> 4) & 1;
-    const int kap = kappa(l32);
-#pragma unroll
-    for (int kk = 0; kk < KD; ++kk) row[kk] = kap * (D * 2) + (((2 * kk + h) ^ SwzX<D>::f(kap)) << 4);
-#pragma unroll
-    for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-      for (int rd = 0; rd < 2; ++rd) {
-        int r = 8 * h + 4 * rd + (i16 >> 2);
-        int c = 4 * dt + 2 * blk1 + ((i16 & 3) >> 1);
-        tr[dt][rd] = r * (D * 2) + ((c ^ SwzX<D>::f(r)) << 4) + ((i16 & 1) << 3);
-      }
-  }
-};
-
-// sigmoid(t) and t-derivative factor for 16 accumulator registers.
-//   u = -(t) log2 e, e = 2^u, p = 1/(1+e)
-// `dist0` / `dstep` give |i-j| for ALiBi: distance of register r is |dist0 + dstep*key_of_reg(r)|.
-template <bool ALIBI>
-__device__ __forceinline__ void sigmoid16(const f32x16& s, float* pr, float nscale, float nbias, float sl2, float dist0,
-                                          float dstep) {
-  if (ALIBI) {
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      float dist = dist0 + dstep * (float)key_of_reg(r);
-      float w = __builtin_fmaf(sl2, __builtin_fabsf(dist), nbias);
-      pr[r] = __builtin_fmaf(s[r], nscale, w);
-    }
-  } else {
-#pragma unroll
-    for (int r = 0; r < 16; ++r) pr[r] = __builtin_fmaf(s[r], nscale, nbias);
-  }
-#pragma unroll
-  for (int r = 0; r < 16; ++r) pr[r] = __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(pr[r]));
-}
-
-// softmax probabilities from saved row statistics: p = 2^(s*scale_log2 - slope|i-j|log2e - lse*log2e).
-// `nlse` holds -lse*log2(e) per register (dkdv kernel) or one value for the lane (dq kernel).
-template <bool ALIBI, bool PER_REG>
-__device__ __forceinline__ void softmax16(const f32x16& s, float* pr, float scale_log2, float sl2, float dist0,
-                                          float dstep, const float* nlse) {
-#pragma unroll
-  for (int r = 0; r < 16; ++r) {
-    float w = PER_REG ? nlse[r] : nlse[0];
-    if (ALIBI) {
-      float dist = dist0 + dstep * (float)key_of_reg(r);
-      w = __builtin_fmaf(-sl2, __builtin_fabsf(dist), w);
-    }
-    pr[r] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], scale_log2, w));
-  }
-}
 
 __device__ __forceinline__ bf16x8 pack8(const float* x) {
   u32x4 w;
@@ -135,276 +86,466 @@ __device__ __forceinline__ bf16x8 pack8(const float* x) {
   return as_bf16x8(w);
 }
 
-// ------------------------------------------------------------------ dQ kernel
-template <int D, int BC, int NW, bool CAUSAL, bool ALIBI, bool SOFTMAX>
-__global__ void __launch_bounds__(64 * NW, 2)
-attn_bwd_dq_kernel(const BwdParams p) {
-  constexpr int NT = 64 * NW, BR = 32 * NW, KD = D / 16, DT = D / 32, NCK = BC / 32;
-  constexpr int TILE = BC * D * 2;
-  extern __shared__ __attribute__((aligned(1024))) char smem[];
-  const uint32_t lds0 = (uint32_t)(uintptr_t)(SATTN_LDS(char)*)smem;
+// Per-wave pipeline state.
+template <int D, int MODE>
+struct BwdWave {
+  static constexpr int KD = D / 16, DT = D / 32;
+  uint32_t row0[KD];    // LDS address (streamed tensor 1) of row fragment kk in tile t (t = current tile)
+  uint32_t row1[KD];    // same in tile t+1
+  uint32_t tr[DT][2];   // LDS address of the transposed-read pair for d-tile dt in tile t-1 (tensor 1)
+  bf16x8 x1[KD], x2[KD];  // stationary B operands of the first products
+  bf16x8 F[2 * KD];       // streamed row fragments: F[2kk] from tensor 1, F[2kk+1] from tensor 2
+  f32x16 acc0[DT];        // DQ: dQ^T ; DKDV: dK^T
+  f32x16 acc1[MODE == BWD_DKDV ? DT : 1];  // DKDV: dV^T
+  f32x16 s[2], dp[2];     // first products of chunk c in [c&1]
+  bf16x8 pb[2][2];        // bf16 P of chunk c in [c&1][ks]   (DKDV only)
+  bf16x8 dsb[2][2];       // bf16 dS of chunk c in [c&1][ks]
+  int ai, h;              // this lane's stationary row, lane half
+  float nscale, nbias, sl2;
+  float nlse, dstat;      // softmax DQ: this lane's -lse*log2e and D
+};
 
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, h = lane >> 5;
-  const int total = p.n_blocks * p.B * p.H;
-  const int logical = xcd_remap(blockIdx.x, total);
-  const int bh = logical / p.n_blocks;
-  const int qb = CAUSAL ? (p.n_blocks - 1 - logical % p.n_blocks) : (logical % p.n_blocks);
-  const int b = bh / p.H, hd = bh % p.H, N = p.N;
+// Every MFMA of the backward kernel is a volatile asm statement with fixed register classes:
+// stationary fragments and output accumulators are AGPR operands, streamed fragments and the
+// first products VGPR operands.  The compiler does not see these as MFMAs, so the code below
+// covers the read-after-MFMA hazards itself (mfma_settle).
+__device__ __forceinline__ void b_mfma_v(f32x16& c, const bf16x8& a, const bf16x8& b_agpr) {
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(c) : "v"(a), "a"(b_agpr) : "memory");
+}
+__device__ __forceinline__ void b_mfma_v0(f32x16& c, const bf16x8& a, const bf16x8& b_agpr) {
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(c) : "v"(a), "a"(b_agpr) : "memory");
+}
+__device__ __forceinline__ void b_mfma_a(f32x16& c_agpr, const bf16x8& a, const bf16x8& b) {
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(c_agpr) : "v"(a), "v"(b) : "memory");
+}
+// Wait until the MFMAs issued so far have written their results, and keep the named first
+// products in their registers up to this point (a register copy placed earlier would read
+// them before the matrix pipeline has written them).
+__device__ __forceinline__ void mfma_settle(f32x16& a, f32x16& b) {
+  asm volatile("s_nop 15\n\ts_nop 3" : "+v"(a), "+v"(b) : : "memory");
+}
+__device__ __forceinline__ void mfma_settle() { asm volatile("s_nop 15\n\ts_nop 3" ::: "memory"); }
+// Same pin without the wait, for places where enough independent MFMAs have issued since.
+__device__ __forceinline__ void mfma_pin(f32x16& a, f32x16& b) { asm volatile("" : "+v"(a), "+v"(b) : : "memory"); }
 
-  const __bf16* qbase = (const __bf16*)p.q.ptr + b * p.q.sb + hd * p.q.sh;
-  const __bf16* kbase = (const __bf16*)p.k.ptr + b * p.k.sb + hd * p.k.sh;
-  const __bf16* vbase = (const __bf16*)p.v.ptr + b * p.v.sb + hd * p.v.sh;
-  const __bf16* dobase = (const __bf16*)p.dout.ptr + b * p.dout.sb + hd * p.dout.sh;
-  __bf16* dqbase = (__bf16*)p.dq.ptr + b * p.dq.sb + hd * p.dq.sh;
-
-  const int q_wave0 = qb * BR + wave * 32, qi = q_wave0 + l32, qi_ld = qi < N ? qi : N - 1;
-  bf16x8 qf[KD], dof[KD];
+// One pipeline step s (PAR = s & 1), compiler-scheduled:
+//   A : first products of chunk s (fragments F, loaded by the previous step)
+//   SG: p / dS of chunk s-1 (first row cs), masked when `mask`
+//   B : second products of chunk s-2 (transposed reads at tr + trimm)
+// then F is refilled with the rows of chunk s+1 (nextrow + nextimm).
+template <int D, int MODE, bool CAUSAL, bool ALIBI, bool SOFTMAX, int PAR>
+__device__ __forceinline__ void bwd_step(BwdWave<D, MODE>& W, bool doA, bool doS, bool doB, bool mask, uint32_t trimm,
+                                         const uint32_t* nextrow, uint32_t nextimm, int cs, int N,
+                                         const SATTN_LDS(float)* stat) {
+  constexpr int KD = D / 16, DT = D / 32;
+  constexpr uint32_t T2OFF = 64 * D * 2;  // tensor 2's tile follows tensor 1's inside a ring slot
+  if (doA) {
+    b_mfma_v0(W.s[PAR], W.F[0], W.x1[0]);
+    b_mfma_v0(W.dp[PAR], W.F[1], W.x2[0]);
 #pragma unroll
-  for (int kk = 0; kk < KD; ++kk) {
-    qf[kk] = as_bf16x8(*(const u32x4*)(qbase + (int64_t)qi_ld * p.q.ss + 16 * kk + 8 * h));
-    dof[kk] = as_bf16x8(*(const u32x4*)(dobase + (int64_t)qi_ld * p.dout.ss + 16 * kk + 8 * h));
+    for (int kk = 1; kk < KD; ++kk) {
+      b_mfma_v(W.s[PAR], W.F[2 * kk], W.x1[kk]);
+      b_mfma_v(W.dp[PAR], W.F[2 * kk + 1], W.x2[kk]);
+    }
+    mfma_settle(W.s[PAR], W.dp[PAR]);
   }
-  f32x16 acc[DT];
+  if (doS) {
+    // chunk s-1 lives in buffers [PAR^1]; streamed index of register r: b = cs + 8h + key_of_reg(r)
+    const int bl = cs + 8 * W.h;
+    float pr[16], ds[16];
 #pragma unroll
-  for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) acc[dt][r] = 0.f;
-
-  TileOffsets<D> off;
-  off.init(lane);
-  float sl2 = 0.f;
-  if (ALIBI) sl2 = p.slopes[hd] * kLog2e;
-  float nlse_q = 0.f, d_q = 0.f;  // softmax: this lane's query statistics
-  if (SOFTMAX) {
-    nlse_q = -p.lse[(int64_t)bh * N + qi_ld] * kLog2e;
-    d_q = p.dvec[(int64_t)bh * N + qi_ld];
-  }
-
-  const int q_hi = (qb * BR + BR < N ? qb * BR + BR : N) - 1;
-  const int kv_len = CAUSAL ? (q_hi + 1) : N;
-  const int n_tiles = (kv_len + BC - 1) / BC;
-
-  PairStager<D, BC, NT> st;
-  st.load(kbase, vbase, p.k.ss, p.v.ss, 0, N, tid);
-  st.store(lds0, lds0 + TILE, tid);
-  __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): stationary fragments are in registers before the loop
-  __syncthreads();
-
-  for (int jt = 0; jt < n_tiles; ++jt) {
-    const int j0 = jt * BC;
-    const uint32_t ks = lds0 + (jt & 1) * (2 * TILE), vs = ks + TILE;
-    const bool more = jt + 1 < n_tiles;
-    if (more) st.load(kbase, vbase, p.k.ss, p.v.ss, j0 + BC, N, tid);
-#pragma unroll
-    for (int ck = 0; ck < NCK; ++ck) {
-      const int jc = j0 + 32 * ck;
-      if (jc >= N) break;
-      if (CAUSAL && jc > q_wave0 + 31) break;
-      const uint32_t cko = ck * 32 * (D * 2);
-      f32x16 s, dp;
-#pragma unroll
-      for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
-#pragma unroll
-      for (int kk = 0; kk < KD; ++kk) {
-        s = mfma32(as_bf16x8(lds_read_b128(ks + cko + off.row[kk])), qf[kk], s);
-        dp = mfma32(as_bf16x8(lds_read_b128(vs + cko + off.row[kk])), dof[kk], dp);
-      }
-      const int jl = jc + 8 * h;
-      float pr[16];
-      float ds[16];
+    for (int r = 0; r < 16; ++r) {
+      const int b = bl + key_of_reg(r);
+      const int qrow = MODE == BWD_DKDV ? b : W.ai, krow = MODE == BWD_DKDV ? W.ai : b;
       if (SOFTMAX) {
-        softmax16<ALIBI, false>(s, pr, -p.nscale_log2, sl2, (float)(qi - jl), -1.0f, &nlse_q);
-#pragma unroll
-        for (int r = 0; r < 16; ++r) ds[r] = pr[r] * (dp[r] - d_q);
+        // p = 2^(s*log2e/sqrt(d) - slope|i-j|log2e - lse*log2e), dS = p (dP - D)
+        float w = MODE == BWD_DKDV ? stat[key_of_reg(r)] : W.nlse;
+        if (ALIBI) w = __builtin_fmaf(-W.sl2, __builtin_fabsf((float)(qrow - krow)), w);
+        pr[r] = __builtin_amdgcn_exp2f(__builtin_fmaf(W.s[PAR ^ 1][r], -W.nscale, w));
+        const float dd = MODE == BWD_DKDV ? stat[64 + key_of_reg(r)] : W.dstat;
+        ds[r] = pr[r] * (W.dp[PAR ^ 1][r] - dd);
       } else {
-        sigmoid16<ALIBI>(s, pr, p.nscale_log2, p.nbias_log2, sl2, (float)(qi - jl), -1.0f);
-#pragma unroll
-        for (int r = 0; r < 16; ++r) ds[r] = pr[r] * (1.0f - pr[r]) * dp[r];
+        // p = 1/(1 + 2^u), dS = (p - p^2) dP
+        float w = W.nbias;
+        if (ALIBI) w = __builtin_fmaf(W.sl2, __builtin_fabsf((float)(qrow - krow)), w);
+        const float e = __builtin_amdgcn_exp2f(__builtin_fmaf(W.s[PAR ^ 1][r], W.nscale, w));
+        pr[r] = __builtin_amdgcn_rcpf(1.0f + e);
+        ds[r] = __builtin_fmaf(-pr[r], pr[r], pr[r]) * W.dp[PAR ^ 1][r];
       }
-      if ((jc + 31 >= N) || (CAUSAL && jc + 31 > q_wave0)) {
-        int lim = N - 1 - jl;
-        if (CAUSAL) lim = lim < qi - jl ? lim : qi - jl;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) ds[r] = key_of_reg(r) <= lim ? ds[r] : 0.f;
-      }
-#pragma unroll
-      for (int ks2 = 0; ks2 < 2; ++ks2) {
-        bf16x8 dsb = pack8(ds + 8 * ks2);
-#pragma unroll
-        for (int dt = 0; dt < DT; ++dt) {
-          uint32_t a0 = ks + cko + ks2 * 16 * (D * 2);
-          bf16x8 a = join_tr(lds_read_tr16(a0 + off.tr[dt][0]), lds_read_tr16(a0 + off.tr[dt][1]));
-          acc[dt] = mfma32(a, dsb, acc[dt]);
-        }
+      if (mask) {
+        const bool keep = b < N && (!CAUSAL || krow <= qrow);
+        pr[r] = keep ? pr[r] : 0.f;
+        ds[r] = keep ? ds[r] : 0.f;
       }
     }
-    if (more) st.store(lds0 + ((jt + 1) & 1) * (2 * TILE), lds0 + ((jt + 1) & 1) * (2 * TILE) + TILE, tid);
-    __syncthreads();
+    if (MODE == BWD_DKDV) { W.pb[PAR ^ 1][0] = pack8(pr); W.pb[PAR ^ 1][1] = pack8(pr + 8); }
+    W.dsb[PAR ^ 1][0] = pack8(ds);
+    W.dsb[PAR ^ 1][1] = pack8(ds + 8);
   }
-  if (qi < N) {
-    __bf16* row = dqbase + (int64_t)qi * p.dq.ss;
+  if (doB) {
+    // chunk s-2 lives in buffers [PAR]
 #pragma unroll
-    for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        u32x2 w;
-        w[0] = pack_bf16(acc[dt][4 * g] * p.inv_sqrt_d, acc[dt][4 * g + 1] * p.inv_sqrt_d);
-        w[1] = pack_bf16(acc[dt][4 * g + 2] * p.inv_sqrt_d, acc[dt][4 * g + 3] * p.inv_sqrt_d);
-        *(u32x2*)(row + 32 * dt + 8 * g + 4 * h) = w;
+    for (int j = 0; j < 2 * DT; ++j) {
+      const uint32_t a0 = W.tr[j % DT][0] + trimm + (j / DT) * 16 * (D * 2);
+      const uint32_t a1 = W.tr[j % DT][1] + trimm + (j / DT) * 16 * (D * 2);
+      if (MODE == BWD_DKDV) {
+        bf16x8 ado = join_tr(lds_read_tr16(a0 + T2OFF), lds_read_tr16(a1 + T2OFF));
+        b_mfma_a(W.acc1[j % DT], ado, W.pb[PAR][j / DT]);
       }
+      bf16x8 a1t = join_tr(lds_read_tr16(a0), lds_read_tr16(a1));
+      b_mfma_a(W.acc0[j % DT], a1t, W.dsb[PAR][j / DT]);
+    }
+    mfma_settle();
+  }
+#pragma unroll
+  for (int kk = 0; kk < KD; ++kk) {
+    W.F[2 * kk] = as_bf16x8(lds_read_b128(nextrow[kk] + nextimm));
+    W.F[2 * kk + 1] = as_bf16x8(lds_read_b128(nextrow[kk] + nextimm + T2OFF));
   }
 }
 
-// ------------------------------------------------------------------ dK/dV kernel
-template <int D, int BQ, int NW, bool CAUSAL, bool ALIBI, bool SOFTMAX>
-__global__ void __launch_bounds__(64 * NW, 1)
-attn_bwd_dkdv_kernel(const BwdParams p) {
-  constexpr int NT = 64 * NW, BK = 32 * NW, KD = D / 16, DT = D / 32, NCK = BQ / 32;
-  constexpr int TILE = BQ * D * 2;
+// ---- The steady-state step (all three stages active, no mask) with a hand-pinned
+// instruction order: every instruction is a volatile asm statement, so the stream is exactly
+// one MFMA, the LDS refill of the fragment it consumed, then a slice of the sigmoid / dS
+// arithmetic whose dependent operations sit four instructions apart.  Stationary fragments
+// and output accumulators are AGPR operands, which keeps the VALU-visible registers < 256.
+// One fragment buffer serves both kinds of LDS operand: a slot is refilled with the
+// transposed fragment right after the first-product MFMA that used it, and with the next
+// chunk's row fragment right after the second-product MFMA that used that.
+
+// Arithmetic of one chunk as 4 groups of four elements.  Per group:
+//   F x4 (u = s*scale + bias[+alibi])  X x4 (2^u)  A x4 (1+e)  R x4 (p = 1/.)  Q x4 (p - p^2)
+//   M x4 (dS = . * dP)  [CP x2 pack P]  CD x2 pack dS
+template <int D, int MODE, bool ALIBI, int I>
+__device__ __forceinline__ void bsig_op(const BwdWave<D, MODE>& W, const f32x16& s, const f32x16& dp, float (&u)[16],
+                                        float (&v)[16], uint32_t (&wp)[8], uint32_t (&wd)[8], float nbias_v,
+                                        float sl2_v, float dist0, float dstep) {
+  constexpr int OPG = MODE == BWD_DKDV ? 28 : 26;
+  constexpr int G = I / OPG, i = I % OPG, e = 4 * G + (i & 3);
+  if constexpr (i < 4) {
+    if constexpr (ALIBI) {
+      float t, w;
+      const float keyf = (float)key_of_reg(e);
+      asm volatile("v_fma_f32 %0, %1, %2, %3" : "=v"(t) : "v"(dstep), "v"(keyf), "v"(dist0));
+      asm volatile("v_fma_f32 %0, %1, |%2|, %3" : "=v"(w) : "v"(sl2_v), "v"(t), "v"(nbias_v));
+      asm volatile("v_fma_f32 %0, %1, %2, %3" : "=v"(u[e]) : "v"(s[e]), "s"(W.nscale), "v"(w));
+    } else {
+      asm volatile("v_fma_f32 %0, %1, %2, %3" : "=v"(u[e]) : "v"(s[e]), "s"(W.nscale), "v"(nbias_v));
+    }
+  } else if constexpr (i < 8) {
+    asm volatile("v_exp_f32 %0, %0" : "+v"(u[e]));
+  } else if constexpr (i < 12) {
+    asm volatile("v_add_f32 %0, 1.0, %0" : "+v"(u[e]));
+  } else if constexpr (i < 16) {
+    asm volatile("v_rcp_f32 %0, %0" : "+v"(u[e]));
+  } else if constexpr (i < 20) {
+    asm volatile("v_fma_f32 %0, -%1, %1, %1" : "=v"(v[e]) : "v"(u[e]));
+  } else if constexpr (i < 24) {
+    asm volatile("v_mul_f32 %0, %0, %1" : "+v"(v[e]) : "v"(dp[e]));
+  } else if constexpr (MODE == BWD_DKDV && i < 26) {
+    constexpr int j = 2 * G + (i - 24);
+    asm volatile("v_cvt_pk_bf16_f32 %0, %1, %2" : "=v"(wp[j]) : "v"(u[2 * j]), "v"(u[2 * j + 1]));
+  } else {
+    constexpr int j = 2 * G + (i - (MODE == BWD_DKDV ? 26 : 24));
+    asm volatile("v_cvt_pk_bf16_f32 %0, %1, %2" : "=v"(wd[j]) : "v"(v[2 * j]), "v"(v[2 * j + 1]));
+  }
+}
+template <int D, int MODE, bool ALIBI, int LO, int HI>
+__device__ __forceinline__ void bsig_ops(const BwdWave<D, MODE>& W, const f32x16& s, const f32x16& dp, float (&u)[16],
+                                         float (&v)[16], uint32_t (&wp)[8], uint32_t (&wd)[8], float nbias_v,
+                                         float sl2_v, float dist0, float dstep) {
+  if constexpr (LO < HI) {
+    bsig_op<D, MODE, ALIBI, LO>(W, s, dp, u, v, wp, wd, nbias_v, sl2_v, dist0, dstep);
+    bsig_ops<D, MODE, ALIBI, LO + 1, HI>(W, s, dp, u, v, wp, wd, nbias_v, sl2_v, dist0, dstep);
+  }
+}
+
+template <int D, int MODE, bool ALIBI, int PAR, int K>
+__device__ __forceinline__ void bwd_full_subslots(BwdWave<D, MODE>& W, uint32_t trimm, const uint32_t* nextrow,
+                                                  uint32_t nextimm, float (&u)[16], float (&v)[16], uint32_t (&wp)[8],
+                                                  uint32_t (&wd)[8], float nbias_v, float sl2_v, float dist0,
+                                                  float dstep) {
+  constexpr int KD = D / 16, DT = D / 32;
+  constexpr uint32_t T2OFF = 64 * D * 2;
+  constexpr int NA = 2 * KD;                               // first-product MFMAs
+  constexpr int NB = MODE == BWD_DKDV ? 2 * KD : KD;       // second-product MFMAs
+  constexpr int NSUB = NA + NB;
+  constexpr int NOPS = 4 * (MODE == BWD_DKDV ? 28 : 26);
+  if constexpr (K < NSUB) {
+    if constexpr (K < NA) {
+      constexpr int kk = K / 2;
+      if constexpr ((K & 1) == 0) {
+        // S-type product from tensor 1, then fetch the transposed tensor-1 fragment kk
+        if constexpr (kk == 0) b_mfma_v0(W.s[PAR], W.F[K], W.x1[kk]);
+        else b_mfma_v(W.s[PAR], W.F[K], W.x1[kk]);
+        const uint32_t off = trimm + (kk / DT) * 16 * (D * 2);
+        W.F[K] = join_tr(lds_read_tr16(W.tr[kk % DT][0] + off), lds_read_tr16(W.tr[kk % DT][1] + off));
+      } else {
+        // dP-type product from tensor 2
+        if constexpr (kk == 0) b_mfma_v0(W.dp[PAR], W.F[K], W.x2[kk]);
+        else b_mfma_v(W.dp[PAR], W.F[K], W.x2[kk]);
+        if constexpr (MODE == BWD_DKDV) {
+          const uint32_t off = trimm + (kk / DT) * 16 * (D * 2) + T2OFF;
+          W.F[K] = join_tr(lds_read_tr16(W.tr[kk % DT][0] + off), lds_read_tr16(W.tr[kk % DT][1] + off));
+        } else {
+          W.F[K] = as_bf16x8(lds_read_b128(nextrow[kk] + nextimm + T2OFF));  // DQ: V is only read row-wise
+        }
+      }
+    } else {
+      constexpr int KB = K - NA;
+      if constexpr (KB == 2) mfma_pin(W.s[PAR], W.dp[PAR]);
+      if constexpr (MODE == BWD_DKDV) {
+        constexpr int j = KB / 2;
+        if constexpr ((KB & 1) == 0) {
+          b_mfma_a(W.acc0[j % DT], W.F[2 * j], W.dsb[PAR][j / DT]);      // dK^T += Q^T dS
+          W.F[2 * j] = as_bf16x8(lds_read_b128(nextrow[j] + nextimm));
+        } else {
+          b_mfma_a(W.acc1[j % DT], W.F[2 * j + 1], W.pb[PAR][j / DT]);   // dV^T += dO^T P
+          W.F[2 * j + 1] = as_bf16x8(lds_read_b128(nextrow[j] + nextimm + T2OFF));
+        }
+      } else {
+        constexpr int j = KB;
+        b_mfma_a(W.acc0[j % DT], W.F[2 * j], W.dsb[PAR][j / DT]);        // dQ^T += K^T dS^T
+        W.F[2 * j] = as_bf16x8(lds_read_b128(nextrow[j] + nextimm));
+      }
+    }
+    bsig_ops<D, MODE, ALIBI, (K * NOPS) / NSUB, ((K + 1) * NOPS) / NSUB>(W, W.s[PAR ^ 1], W.dp[PAR ^ 1], u, v, wp, wd,
+                                                                         nbias_v, sl2_v, dist0, dstep);
+    bwd_full_subslots<D, MODE, ALIBI, PAR, K + 1>(W, trimm, nextrow, nextimm, u, v, wp, wd, nbias_v, sl2_v, dist0,
+                                                  dstep);
+  }
+}
+
+template <int D, int MODE, bool ALIBI, int PAR>
+__device__ __forceinline__ void bwd_step_full_pinned(BwdWave<D, MODE>& W, uint32_t trimm, const uint32_t* nextrow,
+                                                     uint32_t nextimm, int cs) {
+  float u[16], v[16];
+  uint32_t wp[8], wd[8];
+  // |i-j| of register r: DKDV streams queries (b - a), DQ streams keys (a - b)
+  const int bl = cs + 8 * W.h;
+  const float dist0 = MODE == BWD_DKDV ? (float)(bl - W.ai) : (float)(W.ai - bl);
+  const float dstep = MODE == BWD_DKDV ? 1.0f : -1.0f;
+  bwd_full_subslots<D, MODE, ALIBI, PAR, 0>(W, trimm, nextrow, nextimm, u, v, wp, wd, W.nbias, W.sl2, dist0, dstep);
+  // The compiler does not know that the asm statements above are MFMAs: let the last ones
+  // retire before it may touch their accumulators (copies at the join with the other path).
+  mfma_settle();
+  if (MODE == BWD_DKDV) {
+    W.pb[PAR ^ 1][0] = as_bf16x8(u32x4{wp[0], wp[1], wp[2], wp[3]});
+    W.pb[PAR ^ 1][1] = as_bf16x8(u32x4{wp[4], wp[5], wp[6], wp[7]});
+  }
+  W.dsb[PAR ^ 1][0] = as_bf16x8(u32x4{wd[0], wd[1], wd[2], wd[3]});
+  W.dsb[PAR ^ 1][1] = as_bf16x8(u32x4{wd[4], wd[5], wd[6], wd[7]});
+}
+
+template <int D, int MODE, bool CAUSAL, bool ALIBI, bool SOFTMAX>
+__global__ void __launch_bounds__(256, 1)
+attn_bwd_kernel(const BwdParams p) {
+  constexpr int NW = 4, BS = 32 * NW, BC = 64, KD = D / 16, DT = D / 32;
+  constexpr int TILE = BC * D * 2, SLOT = 2 * TILE, CHUNK = 32 * D * 2, NSLOT = 4;
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   const uint32_t lds0 = (uint32_t)(uintptr_t)(SATTN_LDS(char)*)smem;
-  // softmax: per-query statistics of the staged tile, [stage][0: -lse*log2e | 1: D][BQ]
-  SATTN_LDS(float)* stat = (SATTN_LDS(float)*)(smem + 4 * TILE);
-  static_assert(NT >= 2 * BQ, "statistics are staged by the first 2*BQ threads");
+  // softmax DKDV: per-row statistics of the streamed query tiles, [slot][0: -lse*log2e | 1: D][64]
+  SATTN_LDS(float)* statbase = (SATTN_LDS(float)*)(smem + NSLOT * SLOT);
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, h = lane >> 5;
+  const int uwave = __builtin_amdgcn_readfirstlane(wave);
   const int total = p.n_blocks * p.B * p.H;
   const int logical = xcd_remap(blockIdx.x, total);
   const int bh = logical / p.n_blocks;
-  const int kb = logical % p.n_blocks;  // causal: early key blocks are the heavy ones and come first
+  // causal: heavy blocks first (late query blocks for DQ, early key blocks for DKDV)
+  const int blk = (CAUSAL && MODE == BWD_DQ) ? (p.n_blocks - 1 - logical % p.n_blocks) : (logical % p.n_blocks);
   const int b = bh / p.H, hd = bh % p.H, N = p.N;
 
   const __bf16* qbase = (const __bf16*)p.q.ptr + b * p.q.sb + hd * p.q.sh;
   const __bf16* kbase = (const __bf16*)p.k.ptr + b * p.k.sb + hd * p.k.sh;
   const __bf16* vbase = (const __bf16*)p.v.ptr + b * p.v.sb + hd * p.v.sh;
   const __bf16* dobase = (const __bf16*)p.dout.ptr + b * p.dout.sb + hd * p.dout.sh;
-  __bf16* dkbase = (__bf16*)p.dk.ptr + b * p.dk.sb + hd * p.dk.sh;
-  __bf16* dvbase = (__bf16*)p.dv.ptr + b * p.dv.sb + hd * p.dv.sh;
+  // stationary tensors x1, x2 and streamed tensors y1, y2
+  const __bf16* x1b = MODE == BWD_DKDV ? kbase : qbase;
+  const __bf16* x2b = MODE == BWD_DKDV ? vbase : dobase;
+  const int64_t x1s = MODE == BWD_DKDV ? p.k.ss : p.q.ss, x2s = MODE == BWD_DKDV ? p.v.ss : p.dout.ss;
+  const __bf16* y1b = MODE == BWD_DKDV ? qbase : kbase;
+  const __bf16* y2b = MODE == BWD_DKDV ? dobase : vbase;
+  const int64_t y1s = MODE == BWD_DKDV ? p.q.ss : p.k.ss, y2s = MODE == BWD_DKDV ? p.dout.ss : p.v.ss;
 
-  const int k_wave0 = kb * BK + wave * 32, kj = k_wave0 + l32, kj_ld = kj < N ? kj : N - 1;
-  // K and V fragments: B operands (column = key, k = d)
-  bf16x8 kf[KD], vf[KD];
+  const int a_wave0 = blk * BS + wave * 32, ai = a_wave0 + l32, ai_ld = ai < N ? ai : N - 1;
+
+  BwdWave<D, MODE> W;
 #pragma unroll
   for (int kk = 0; kk < KD; ++kk) {
-    kf[kk] = as_bf16x8(*(const u32x4*)(kbase + (int64_t)kj_ld * p.k.ss + 16 * kk + 8 * h));
-    vf[kk] = as_bf16x8(*(const u32x4*)(vbase + (int64_t)kj_ld * p.v.ss + 16 * kk + 8 * h));
+    W.x1[kk] = as_bf16x8(*(const u32x4*)(x1b + (int64_t)ai_ld * x1s + 16 * kk + 8 * h));
+    W.x2[kk] = as_bf16x8(*(const u32x4*)(x2b + (int64_t)ai_ld * x2s + 16 * kk + 8 * h));
   }
-  f32x16 dkacc[DT], dvacc[DT];
 #pragma unroll
   for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-    for (int r = 0; r < 16; ++r) { dkacc[dt][r] = 0.f; dvacc[dt][r] = 0.f; }
-
-  TileOffsets<D> off;
-  off.init(lane);
-  float sl2 = 0.f;
-  if (ALIBI) sl2 = p.slopes[hd] * kLog2e;
-
-  const int it0 = CAUSAL ? (kb * BK) / BQ : 0;  // first query tile that can see this key block
-  const int n_tiles = (N + BQ - 1) / BQ;
-
-  PairStager<D, BQ, NT> st;
-  float statreg = 0.f;
-  auto load_stat = [&](int i0) {
-    if (SOFTMAX && tid < 2 * BQ) {
-      int row = i0 + (tid & (BQ - 1));
-      row = row < N ? row : N - 1;
-      statreg = tid < BQ ? -p.lse[(int64_t)bh * N + row] * kLog2e : p.dvec[(int64_t)bh * N + row];
+    for (int r = 0; r < 16; ++r) {
+      W.acc0[dt][r] = 0.f;
+      if (MODE == BWD_DKDV) W.acc1[dt][r] = 0.f;
     }
-  };
-  auto store_stat = [&](int stage) {
-    if (SOFTMAX && tid < 2 * BQ) stat[stage * 2 * BQ + tid] = statreg;
-  };
-  if (it0 < n_tiles) {
-    st.load(qbase, dobase, p.q.ss, p.dout.ss, it0 * BQ, N, tid);
-    load_stat(it0 * BQ);
-    st.store(lds0 + (it0 & 1) * (2 * TILE), lds0 + (it0 & 1) * (2 * TILE) + TILE, tid);
-    store_stat(it0 & 1);
+  W.ai = ai; W.h = h;
+  W.nscale = p.nscale_log2; W.nbias = p.nbias_log2;
+  W.sl2 = ALIBI ? p.slopes[hd] * kLog2e : 0.f;
+  W.nlse = 0.f; W.dstat = 0.f;
+  if (SOFTMAX && MODE == BWD_DQ) {
+    W.nlse = -p.lse[(int64_t)bh * N + ai_ld] * kLog2e;
+    W.dstat = p.dvec[(int64_t)bh * N + ai_ld];
   }
-  __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): stationary fragments are in registers before the loop
-  __syncthreads();
+  {
+    const bf16x8 z = as_bf16x8(u32x4{0, 0, 0, 0});
+    W.pb[0][0] = W.pb[0][1] = W.pb[1][0] = W.pb[1][1] = z;
+    W.dsb[0][0] = W.dsb[0][1] = W.dsb[1][0] = W.dsb[1][1] = z;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { W.s[0][r] = W.s[1][r] = W.dp[0][r] = W.dp[1][r] = 0.f; }
+  }
 
-  for (int it = it0; it < n_tiles; ++it) {
-    const int i0 = it * BQ;
-    const uint32_t qs = lds0 + (it & 1) * (2 * TILE), dos = qs + TILE;
-    const bool more = it + 1 < n_tiles;
-    if (more) {
-      st.load(qbase, dobase, p.q.ss, p.dout.ss, i0 + BQ, N, tid);
-      load_stat(i0 + BQ);
+  // chunk range of the streamed side: workgroup [wg_lo, wg_hi], this wave [c_lo, c_hi]
+  const int n_chunks = (N + 31) / 32;
+  int wg_lo = 0, wg_hi = n_chunks - 1, c_lo = 0, c_hi = n_chunks - 1;
+  if (CAUSAL) {
+    if (MODE == BWD_DKDV) {
+      wg_lo = (blk * BS) / 32;  // queries before the block's first key see none of its keys
+      c_lo = a_wave0 / 32;
+    } else {
+      const int a_hi = (blk * BS + BS < N ? blk * BS + BS : N) - 1;
+      wg_hi = a_hi / 32;        // keys after the block's last query are masked
+      c_hi = (a_wave0 + 31 < N ? a_wave0 + 31 : N - 1) / 32;
+    }
+  }
+  if (a_wave0 >= N) { c_lo = 1; c_hi = 0; }  // wave past the end: no chunks
+  // step s handles chunks s, s-1, s-2; tile t holds chunks 2t, 2t+1 and runs steps 2t, 2t+1
+  const int t_lo = wg_lo / 2, t_hi = (wg_hi + 2) / 2;  // the last step is wg_hi + 2
+  const int t_data_hi = wg_hi / 2;                      // last tile that has to be staged
+
+  // per-lane LDS addresses (the ring slot of tile t is t % 4)
+  {
+    const int kap = kappa(l32), i16 = lane & 15, blk1 = (lane >> 4) & 1;
+#pragma unroll
+    for (int kk = 0; kk < KD; ++kk) {
+      const uint32_t o = lds0 + kap * (D * 2) + (((2 * kk + h) ^ SwzX<D>::f(kap)) << 4);
+      W.row0[kk] = o + (t_lo % NSLOT) * SLOT;
+      W.row1[kk] = o + ((t_lo + 1) % NSLOT) * SLOT;
     }
 #pragma unroll
-    for (int ck = 0; ck < NCK; ++ck) {
-      const int ic = i0 + 32 * ck;  // first query row of the chunk
-      if (ic >= N) break;
-      if (CAUSAL && ic + 31 < k_wave0) continue;  // every query of the chunk precedes every key of the wave
-      const uint32_t cko = ck * 32 * (D * 2);
-      f32x16 s, dp;
+    for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
-#pragma unroll
-      for (int kk = 0; kk < KD; ++kk) {
-        s = mfma32(as_bf16x8(lds_read_b128(qs + cko + off.row[kk])), kf[kk], s);
-        dp = mfma32(as_bf16x8(lds_read_b128(dos + cko + off.row[kk])), vf[kk], dp);
+      for (int rd = 0; rd < 2; ++rd) {
+        const int r = 8 * h + 4 * rd + (i16 >> 2);
+        const int c = 4 * dt + 2 * blk1 + ((i16 & 3) >> 1);
+        W.tr[dt][rd] = lds0 + ((t_lo + NSLOT - 1) % NSLOT) * SLOT + r * (D * 2) + ((c ^ SwzX<D>::f(r)) << 4) +
+                       ((i16 & 1) << 3);
       }
-      const int il = ic + 8 * h;  // query row of register 0 for this lane half
-      float pr[16];
-      float dq_r[16];  // softmax: D of the query held by register r
-      if (SOFTMAX) {
-        float nl[16];
-        const SATTN_LDS(float)* sl = stat + (it & 1) * 2 * BQ + 32 * ck + 8 * h;
+  }
+
+  DmaStagerX<D, NW> st1, st2;
+  st1.init(y1b, y1s, N, t_lo * BC, uwave, lane);
+  st2.init(y2b, y2s, N, t_lo * BC, uwave, lane);
+  float statreg = 0.f;
+  auto load_stat = [&](int t) {
+    if (SOFTMAX && MODE == BWD_DKDV && tid < 128) {
+      int row = t * BC + (tid & 63);
+      row = row < N ? row : N - 1;
+      statreg = tid < 64 ? -p.lse[(int64_t)bh * N + row] * kLog2e : p.dvec[(int64_t)bh * N + row];
+    }
+  };
+  auto store_stat = [&](int t) {
+    if (SOFTMAX && MODE == BWD_DKDV && tid < 128) statbase[(t % NSLOT) * 128 + tid] = statreg;
+  };
+  // prologue: tiles t_lo and t_lo+1
+  st1.issue(lds0 + (t_lo % NSLOT) * SLOT, t_lo * BC, N, uwave);
+  st2.issue(lds0 + (t_lo % NSLOT) * SLOT + TILE, t_lo * BC, N, uwave);
+  load_stat(t_lo);
+  store_stat(t_lo);
+  if (t_lo + 1 <= t_data_hi) {
+    st1.issue(lds0 + ((t_lo + 1) % NSLOT) * SLOT, (t_lo + 1) * BC, N, uwave);
+    st2.issue(lds0 + ((t_lo + 1) % NSLOT) * SLOT + TILE, (t_lo + 1) * BC, N, uwave);
+    load_stat(t_lo + 1);
+    store_stat(t_lo + 1);
+  }
+  __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): prologue tiles landed, stationary fragments in registers
+  __syncthreads();
+  // rows of chunk 2*t_lo for the first step
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          nl[r] = sl[key_of_reg(r)];
-          dq_r[r] = sl[BQ + key_of_reg(r)];
-        }
-        softmax16<ALIBI, true>(s, pr, -p.nscale_log2, sl2, (float)(il - kj), 1.0f, nl);
+  for (int kk = 0; kk < KD; ++kk) {
+    W.F[2 * kk] = as_bf16x8(lds_read_b128(W.row0[kk]));
+    W.F[2 * kk + 1] = as_bf16x8(lds_read_b128(W.row0[kk] + TILE));
+  }
+
+  for (int t = t_lo; t <= t_hi; ++t) {
+    // stage tile t+2 into the slot of tile t-2 (last read during tile t-1)
+    const bool more = t + 2 <= t_data_hi;
+    if (more) {
+      st1.issue(lds0 + ((t + 2) % NSLOT) * SLOT, (t + 2) * BC, N, uwave);
+      st2.issue(lds0 + ((t + 2) % NSLOT) * SLOT + TILE, (t + 2) * BC, N, uwave);
+      load_stat(t + 2);
+    }
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int s = 2 * t + i;
+      const bool doA = s >= c_lo && s <= c_hi;
+      const bool doS = s - 1 >= c_lo && s - 1 <= c_hi;
+      const bool doB = s - 2 >= c_lo && s - 2 <= c_hi;
+      const bool mask = (s - 1 == c_hi) || (CAUSAL && MODE == BWD_DKDV && s - 1 == c_lo);
+      // chunk s-1 sits in tile (s-1)/2
+      const SATTN_LDS(float)* stat = statbase + (((s - 1) >> 1) & (NSLOT - 1)) * 128 + ((s - 1) & 1) * 32 + 8 * h;
+      // rows of chunk s+1: step 2t refills from tile t (second half), step 2t+1 from tile t+1 (first half);
+      // transposed reads of chunk s-2: tile t-1, first half for step 2t, second half for step 2t+1
+#if defined(SATTN_EXP_NOPIN_DQ)
+      const bool full = MODE != BWD_DQ && !SOFTMAX && doA && doS && doB && !mask;
+#elif defined(SATTN_EXP_NOPIN_DKDV)
+      const bool full = MODE != BWD_DKDV && !SOFTMAX && doA && doS && doB && !mask;
+#else
+      const bool full = !SOFTMAX && doA && doS && doB && !mask;
+#endif
+      if (i == 0) {
+        if (full) bwd_step_full_pinned<D, MODE, ALIBI, 0>(W, 0, W.row0, CHUNK, 32 * (s - 1));
+        else bwd_step<D, MODE, CAUSAL, ALIBI, SOFTMAX, 0>(W, doA, doS, doB, mask, 0, W.row0, CHUNK, 32 * (s - 1), N, stat);
       } else {
-        sigmoid16<ALIBI>(s, pr, p.nscale_log2, p.nbias_log2, sl2, (float)(il - kj), 1.0f);
-      }
-      if ((ic + 31 >= N) || (CAUSAL && ic < k_wave0 + 31)) {
-        // keep rows il + key_of_reg(r) in [max(kj, .), N-1]
-        const int hi = N - 1 - il;
-        const int lo = CAUSAL ? kj - il : -1000000;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) pr[r] = (key_of_reg(r) <= hi && key_of_reg(r) >= lo) ? pr[r] : 0.f;
-      }
-      float ds[16];
-#pragma unroll
-      for (int r = 0; r < 16; ++r) ds[r] = SOFTMAX ? pr[r] * (dp[r] - dq_r[r]) : pr[r] * (1.0f - pr[r]) * dp[r];
-#pragma unroll
-      for (int ks2 = 0; ks2 < 2; ++ks2) {
-        bf16x8 pb = pack8(pr + 8 * ks2), dsb = pack8(ds + 8 * ks2);
-#pragma unroll
-        for (int dt = 0; dt < DT; ++dt) {
-          uint32_t a0 = cko + ks2 * 16 * (D * 2);
-          bf16x8 ado = join_tr(lds_read_tr16(dos + a0 + off.tr[dt][0]), lds_read_tr16(dos + a0 + off.tr[dt][1]));
-          dvacc[dt] = mfma32(ado, pb, dvacc[dt]);
-          bf16x8 aq = join_tr(lds_read_tr16(qs + a0 + off.tr[dt][0]), lds_read_tr16(qs + a0 + off.tr[dt][1]));
-          dkacc[dt] = mfma32(aq, dsb, dkacc[dt]);
-        }
+        if (full) bwd_step_full_pinned<D, MODE, ALIBI, 1>(W, CHUNK, W.row1, 0, 32 * (s - 1));
+        else bwd_step<D, MODE, CAUSAL, ALIBI, SOFTMAX, 1>(W, doA, doS, doB, mask, CHUNK, W.row1, 0, 32 * (s - 1), N, stat);
       }
     }
-    if (more) {
-      st.store(lds0 + ((it + 1) & 1) * (2 * TILE), lds0 + ((it + 1) & 1) * (2 * TILE) + TILE, tid);
-      store_stat((it + 1) & 1);
+    // rotate the per-lane addresses by one ring slot
+    {
+      const int s0 = t % NSLOT;  // row0 points at slot s0, row1 at s0+1, tr at s0-1 (mod 4)
+      const int adv0 = s0 == NSLOT - 1 ? -(NSLOT - 1) * SLOT : SLOT;
+      const int adv1 = s0 == NSLOT - 2 ? -(NSLOT - 1) * SLOT : SLOT;
+      const int advt = s0 == 0 ? -(NSLOT - 1) * SLOT : SLOT;
+#pragma unroll
+      for (int kk = 0; kk < KD; ++kk) { W.row0[kk] += adv0; W.row1[kk] += adv1; }
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt) { W.tr[dt][0] += advt; W.tr[dt][1] += advt; }
     }
+    if (more) store_stat(t + 2);
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): tile t+2 has landed (first read during tile t+1)
     __syncthreads();
   }
-  if (kj < N) {
-    __bf16* krow = dkbase + (int64_t)kj * p.dk.ss;
-    __bf16* vrow = dvbase + (int64_t)kj * p.dv.ss;
+
+  if (ai < N) {
+    const float sc = p.inv_sqrt_d;  // dQ and dK carry the 1/sqrt(d) of the logits
+    __bf16* o0 = (MODE == BWD_DKDV ? (__bf16*)p.dk.ptr + b * p.dk.sb + hd * p.dk.sh + (int64_t)ai * p.dk.ss
+                                   : (__bf16*)p.dq.ptr + b * p.dq.sb + hd * p.dq.sh + (int64_t)ai * p.dq.ss);
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
         u32x2 w;
-        w[0] = pack_bf16(dkacc[dt][4 * g] * p.inv_sqrt_d, dkacc[dt][4 * g + 1] * p.inv_sqrt_d);
-        w[1] = pack_bf16(dkacc[dt][4 * g + 2] * p.inv_sqrt_d, dkacc[dt][4 * g + 3] * p.inv_sqrt_d);
-        *(u32x2*)(krow + 32 * dt + 8 * g + 4 * h) = w;
-        w[0] = pack_bf16(dvacc[dt][4 * g], dvacc[dt][4 * g + 1]);
-        w[1] = pack_bf16(dvacc[dt][4 * g + 2], dvacc[dt][4 * g + 3]);
-        *(u32x2*)(vrow + 32 * dt + 8 * g + 4 * h) = w;
+        w[0] = pack_bf16(W.acc0[dt][4 * g] * sc, W.acc0[dt][4 * g + 1] * sc);
+        w[1] = pack_bf16(W.acc0[dt][4 * g + 2] * sc, W.acc0[dt][4 * g + 3] * sc);
+        *(u32x2*)(o0 + 32 * dt + 8 * g + 4 * h) = w;
       }
+    if (MODE == BWD_DKDV) {
+      __bf16* o1 = (__bf16*)p.dv.ptr + b * p.dv.sb + hd * p.dv.sh + (int64_t)ai * p.dv.ss;
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          u32x2 w;
+          w[0] = pack_bf16(W.acc1[dt][4 * g], W.acc1[dt][4 * g + 1]);
+          w[1] = pack_bf16(W.acc1[dt][4 * g + 2], W.acc1[dt][4 * g + 3]);
+          *(u32x2*)(o1 + 32 * dt + 8 * g + 4 * h) = w;
+        }
+    }
   }
 }
 
