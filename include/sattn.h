@@ -57,7 +57,8 @@ typedef struct {
 enum {
   SATTN_OK = 0,
   SATTN_ERR_NULL = -1,        /* a required pointer is NULL */
-  SATTN_ERR_SHAPE = -2,       /* B, H or N not positive, or too large for 32-bit tile indexing */
+  SATTN_ERR_SHAPE = -2,       /* B, H or N not positive, too large for 32-bit tile indexing, or
+                                 (N + 256) * seq stride * element size exceeds 4 GiB - 1 */
   SATTN_ERR_UNSUPPORTED = -3, /* d not in {64,128} or unknown dtype */
   SATTN_ERR_ALIGN = -4,       /* pointer or stride breaks the 16-byte rule */
   SATTN_ERR_WORKSPACE = -5,   /* workspace NULL or smaller than *_workspace_bytes() */

@@ -27,6 +27,8 @@ int make_ref(const void* ptr, const sattn_strides* s, int H, int N, int d, sattn
   }
   if (((uintptr_t)ptr & 15) != 0) return SATTN_ERR_ALIGN;
   if (sb % per16 || sh % per16 || ss % per16 || ss < d) return SATTN_ERR_ALIGN;
+  // the kernels address the rows of one (batch, head) slice with 32-bit byte offsets
+  if (((int64_t)N + 256) * ss * elem_size(dt) > 0xffffffffLL) return SATTN_ERR_SHAPE;
   out->ptr = const_cast<void*>(ptr);
   out->sb = sb; out->sh = sh; out->ss = ss;
   return SATTN_OK;

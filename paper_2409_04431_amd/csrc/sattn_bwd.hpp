@@ -52,32 +52,58 @@ struct SwzX {
 template <int D, int NW>
 struct DmaStagerX {
   static constexpr int BC = 64, CPR = D / 8, RPI = 64 / CPR, NI = (BC * CPR) / (64 * NW);
-  const char* ptr[NI];   // this lane's source for the next tile to stage (unclamped)
-  const char* last[NI];  // this lane's source inside the last row N-1
+  const char* base;      // (batch, head) slice of the tensor, wave-uniform
+  uint32_t off[NI];      // this lane's byte offset for the next tile to stage (unclamped)
+  uint32_t lastoff[NI];  // this lane's byte offset inside the last row N-1
   int row[NI];           // tile-relative row this lane fills
-  int64_t tile_bytes;
-  __device__ __forceinline__ void init(const __bf16* base, int64_t ss, int N, int j0, int wave, int lane) {
+  uint32_t tile_bytes;
+  // The host side guarantees (N + 256) * ss * 2 < 2^32, so the offsets never wrap.
+  __device__ __forceinline__ void init(const __bf16* b, int64_t ss, int N, int j0, int wave, int lane) {
+    base = (const char*)b;
 #pragma unroll
     for (int n = 0; n < NI; ++n) {
       const int r = (wave * NI + n) * RPI + lane / CPR, pc = lane % CPR;
       const int c = pc ^ SwzX<D>::f(r);
       row[n] = r;
-      ptr[n] = (const char*)(base + (int64_t)(j0 + r) * ss + c * 8);
-      last[n] = (const char*)(base + (int64_t)(N - 1) * ss + c * 8);
+      off[n] = (uint32_t)(((int64_t)(j0 + r) * ss + c * 8) * 2);
+      lastoff[n] = (uint32_t)(((int64_t)(N - 1) * ss + c * 8) * 2);
     }
-    tile_bytes = (int64_t)BC * ss * 2;
+    tile_bytes = (uint32_t)(BC * ss * 2);
+  }
+  __device__ __forceinline__ void load(uint32_t o, uint32_t m0v) const {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(o), "s"(base), "s"(m0v) : "memory");
   }
   __device__ __forceinline__ void issue(uint32_t lds, int j0, int N, int wave) {
 #pragma unroll
     for (int n = 0; n < NI; ++n) {
-      const char* src = ptr[n];
-      if (j0 + BC > N) src = (j0 + row[n] < N) ? src : last[n];  // rows past the end re-read row N-1
-      const uint32_t m0v = lds + (wave * NI + n) * 1024;
-      asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(src), "s"(m0v) : "memory");
-      ptr[n] += tile_bytes;
+      uint32_t o = off[n];
+      if (j0 + BC > N) o = (j0 + row[n] < N) ? o : lastoff[n];  // rows past the end re-read row N-1
+      load(o, lds + (wave * NI + n) * 1024);
+      off[n] += tile_bytes;
     }
   }
+  // The same staging split into single instructions (for interleaving with a pinned step):
+  // clamp_tail() first when the tile crosses the end, issue_one<0..NI-1>(), then advance().
+  __device__ __forceinline__ void clamp_tail(int j0, int N) {
+#pragma unroll
+    for (int n = 0; n < NI; ++n) off[n] = (j0 + row[n] < N) ? off[n] : lastoff[n];
+  }
+  template <int n>
+  __device__ __forceinline__ void issue_one(uint32_t lds, int wave) const {
+    load(off[n], lds + (wave * NI + n) * 1024);
+  }
+  __device__ __forceinline__ void advance() {
+#pragma unroll
+    for (int n = 0; n < NI; ++n) off[n] += tile_bytes;
+  }
 };
+
+// A wave-uniform flag as a per-lane value the compiler cannot prove uniform.
+__device__ __forceinline__ bool lane_flag(bool uniform) {
+  int x;
+  asm("v_mov_b32 %0, %1" : "=v"(x) : "s"((int)uniform));
+  return x != 0;
+}
 
 __device__ __forceinline__ bf16x8 pack8(const float* x) {
   u32x4 w;
@@ -103,20 +129,42 @@ struct BwdWave {
   int ai, h;              // this lane's stationary row, lane half
   float nscale, nbias, sl2;
   float nlse, dstat;      // softmax DQ: this lane's -lse*log2e and D
+#ifdef SATTN_EXPB_TIMING
+  uint64_t tpin;
+#endif
 };
 
 // Every MFMA of the backward kernel is a volatile asm statement with fixed register classes:
 // stationary fragments and output accumulators are AGPR operands, streamed fragments and the
 // first products VGPR operands.  The compiler does not see these as MFMAs, so the code below
 // covers the read-after-MFMA hazards itself (mfma_settle).
+// GUARD puts two wait states in front of the MFMA: a vector-ALU result has to be that old
+// before an MFMA may read it.  The compiler-scheduled step needs it (register copies and
+// packs may sit right in front of the statement); the pinned step orders its own
+// instructions and is verified on the generated assembly instead (isa_check.py).
+#ifdef SATTN_EXPB_NOMFMA
+#define SATTN_BWD_MFMA(PRE, ACC) "; skip"
+#else
+#define SATTN_BWD_MFMA(PRE, ACC) PRE "v_mfma_f32_32x32x16_bf16 %0, %1, %2, " ACC
+#endif
+template <bool GUARD>
 __device__ __forceinline__ void b_mfma_v(f32x16& c, const bf16x8& a, const bf16x8& b_agpr) {
-  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(c) : "v"(a), "a"(b_agpr) : "memory");
+  if constexpr (GUARD) asm volatile(SATTN_BWD_MFMA("s_nop 1\n\t", "%0") : "+v"(c) : "v"(a), "a"(b_agpr) : "memory");
+  else asm volatile(SATTN_BWD_MFMA("", "%0") : "+v"(c) : "v"(a), "a"(b_agpr) : "memory");
 }
+template <bool GUARD>
 __device__ __forceinline__ void b_mfma_v0(f32x16& c, const bf16x8& a, const bf16x8& b_agpr) {
-  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(c) : "v"(a), "a"(b_agpr) : "memory");
+#ifdef SATTN_EXPB_NOMFMA
+  asm volatile("; skip" : "+v"(c) : "v"(a), "a"(b_agpr) : "memory");
+#else
+  if constexpr (GUARD) asm volatile(SATTN_BWD_MFMA("s_nop 1\n\t", "0") : "=&v"(c) : "v"(a), "a"(b_agpr) : "memory");
+  else asm volatile(SATTN_BWD_MFMA("", "0") : "=&v"(c) : "v"(a), "a"(b_agpr) : "memory");
+#endif
 }
+template <bool GUARD>
 __device__ __forceinline__ void b_mfma_a(f32x16& c_agpr, const bf16x8& a, const bf16x8& b) {
-  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(c_agpr) : "v"(a), "v"(b) : "memory");
+  if constexpr (GUARD) asm volatile(SATTN_BWD_MFMA("s_nop 1\n\t", "%0") : "+a"(c_agpr) : "v"(a), "v"(b) : "memory");
+  else asm volatile(SATTN_BWD_MFMA("", "%0") : "+a"(c_agpr) : "v"(a), "v"(b) : "memory");
 }
 // Wait until the MFMAs issued so far have written their results, and keep the named first
 // products in their registers up to this point (a register copy placed earlier would read
@@ -140,12 +188,12 @@ __device__ __forceinline__ void bwd_step(BwdWave<D, MODE>& W, bool doA, bool doS
   constexpr int KD = D / 16, DT = D / 32;
   constexpr uint32_t T2OFF = 64 * D * 2;  // tensor 2's tile follows tensor 1's inside a ring slot
   if (doA) {
-    b_mfma_v0(W.s[PAR], W.F[0], W.x1[0]);
-    b_mfma_v0(W.dp[PAR], W.F[1], W.x2[0]);
+    b_mfma_v0<true>(W.s[PAR], W.F[0], W.x1[0]);
+    b_mfma_v0<true>(W.dp[PAR], W.F[1], W.x2[0]);
 #pragma unroll
     for (int kk = 1; kk < KD; ++kk) {
-      b_mfma_v(W.s[PAR], W.F[2 * kk], W.x1[kk]);
-      b_mfma_v(W.dp[PAR], W.F[2 * kk + 1], W.x2[kk]);
+      b_mfma_v<true>(W.s[PAR], W.F[2 * kk], W.x1[kk]);
+      b_mfma_v<true>(W.dp[PAR], W.F[2 * kk + 1], W.x2[kk]);
     }
     mfma_settle(W.s[PAR], W.dp[PAR]);
   }
@@ -190,10 +238,10 @@ __device__ __forceinline__ void bwd_step(BwdWave<D, MODE>& W, bool doA, bool doS
       const uint32_t a1 = W.tr[j % DT][1] + trimm + (j / DT) * 16 * (D * 2);
       if (MODE == BWD_DKDV) {
         bf16x8 ado = join_tr(lds_read_tr16(a0 + T2OFF), lds_read_tr16(a1 + T2OFF));
-        b_mfma_a(W.acc1[j % DT], ado, W.pb[PAR][j / DT]);
+        b_mfma_a<true>(W.acc1[j % DT], ado, W.pb[PAR][j / DT]);
       }
       bf16x8 a1t = join_tr(lds_read_tr16(a0), lds_read_tr16(a1));
-      b_mfma_a(W.acc0[j % DT], a1t, W.dsb[PAR][j / DT]);
+      b_mfma_a<true>(W.acc0[j % DT], a1t, W.dsb[PAR][j / DT]);
     }
     mfma_settle();
   }
@@ -260,11 +308,12 @@ __device__ __forceinline__ void bsig_ops(const BwdWave<D, MODE>& W, const f32x16
   }
 }
 
-template <int D, int MODE, bool ALIBI, int PAR, int K>
+template <int D, int MODE, bool ALIBI, int PAR, bool DMA, int K>
 __device__ __forceinline__ void bwd_full_subslots(BwdWave<D, MODE>& W, uint32_t trimm, const uint32_t* nextrow,
                                                   uint32_t nextimm, float (&u)[16], float (&v)[16], uint32_t (&wp)[8],
                                                   uint32_t (&wd)[8], float nbias_v, float sl2_v, float dist0,
-                                                  float dstep) {
+                                                  float dstep, const DmaStagerX<D, 4>& st1, const DmaStagerX<D, 4>& st2,
+                                                  uint32_t dma_lds, int uwave) {
   constexpr int KD = D / 16, DT = D / 32;
   constexpr uint32_t T2OFF = 64 * D * 2;
   constexpr int NA = 2 * KD;                               // first-product MFMAs
@@ -276,19 +325,25 @@ __device__ __forceinline__ void bwd_full_subslots(BwdWave<D, MODE>& W, uint32_t 
       constexpr int kk = K / 2;
       if constexpr ((K & 1) == 0) {
         // S-type product from tensor 1, then fetch the transposed tensor-1 fragment kk
-        if constexpr (kk == 0) b_mfma_v0(W.s[PAR], W.F[K], W.x1[kk]);
-        else b_mfma_v(W.s[PAR], W.F[K], W.x1[kk]);
+        if constexpr (kk == 0) b_mfma_v0<false>(W.s[PAR], W.F[K], W.x1[kk]);
+        else b_mfma_v<false>(W.s[PAR], W.F[K], W.x1[kk]);
         const uint32_t off = trimm + (kk / DT) * 16 * (D * 2);
+#ifndef SATTN_EXPB_NOLDS
         W.F[K] = join_tr(lds_read_tr16(W.tr[kk % DT][0] + off), lds_read_tr16(W.tr[kk % DT][1] + off));
+#endif
       } else {
         // dP-type product from tensor 2
-        if constexpr (kk == 0) b_mfma_v0(W.dp[PAR], W.F[K], W.x2[kk]);
-        else b_mfma_v(W.dp[PAR], W.F[K], W.x2[kk]);
+        if constexpr (kk == 0) b_mfma_v0<false>(W.dp[PAR], W.F[K], W.x2[kk]);
+        else b_mfma_v<false>(W.dp[PAR], W.F[K], W.x2[kk]);
         if constexpr (MODE == BWD_DKDV) {
           const uint32_t off = trimm + (kk / DT) * 16 * (D * 2) + T2OFF;
+#ifndef SATTN_EXPB_NOLDS
           W.F[K] = join_tr(lds_read_tr16(W.tr[kk % DT][0] + off), lds_read_tr16(W.tr[kk % DT][1] + off));
+#endif
         } else {
+#ifndef SATTN_EXPB_NOLDS
           W.F[K] = as_bf16x8(lds_read_b128(nextrow[kk] + nextimm + T2OFF));  // DQ: V is only read row-wise
+#endif
         }
       }
     } else {
@@ -297,38 +352,67 @@ __device__ __forceinline__ void bwd_full_subslots(BwdWave<D, MODE>& W, uint32_t 
       if constexpr (MODE == BWD_DKDV) {
         constexpr int j = KB / 2;
         if constexpr ((KB & 1) == 0) {
-          b_mfma_a(W.acc0[j % DT], W.F[2 * j], W.dsb[PAR][j / DT]);      // dK^T += Q^T dS
+          b_mfma_a<false>(W.acc0[j % DT], W.F[2 * j], W.dsb[PAR][j / DT]);      // dK^T += Q^T dS
+#ifndef SATTN_EXPB_NOLDS
           W.F[2 * j] = as_bf16x8(lds_read_b128(nextrow[j] + nextimm));
+#endif
         } else {
-          b_mfma_a(W.acc1[j % DT], W.F[2 * j + 1], W.pb[PAR][j / DT]);   // dV^T += dO^T P
+          b_mfma_a<false>(W.acc1[j % DT], W.F[2 * j + 1], W.pb[PAR][j / DT]);   // dV^T += dO^T P
+#ifndef SATTN_EXPB_NOLDS
           W.F[2 * j + 1] = as_bf16x8(lds_read_b128(nextrow[j] + nextimm + T2OFF));
+#endif
         }
       } else {
         constexpr int j = KB;
-        b_mfma_a(W.acc0[j % DT], W.F[2 * j], W.dsb[PAR][j / DT]);        // dQ^T += K^T dS^T
+        b_mfma_a<false>(W.acc0[j % DT], W.F[2 * j], W.dsb[PAR][j / DT]);        // dQ^T += K^T dS^T
+#ifndef SATTN_EXPB_NOLDS
         W.F[2 * j] = as_bf16x8(lds_read_b128(nextrow[j] + nextimm));
+#endif
       }
     }
+#ifndef SATTN_EXPB_NOSIG
     bsig_ops<D, MODE, ALIBI, (K * NOPS) / NSUB, ((K + 1) * NOPS) / NSUB>(W, W.s[PAR ^ 1], W.dp[PAR ^ 1], u, v, wp, wd,
                                                                          nbias_v, sl2_v, dist0, dstep);
-    bwd_full_subslots<D, MODE, ALIBI, PAR, K + 1>(W, trimm, nextrow, nextimm, u, v, wp, wd, nbias_v, sl2_v, dist0,
-                                                  dstep);
+#endif
+    if constexpr (DMA) {
+      // one staging instruction of the tile two ahead every DSTEP sub-slots
+      constexpr int NI = DmaStagerX<D, 4>::NI, DSTEP = NSUB / (2 * NI);
+      if constexpr (K % DSTEP == 1 && K / DSTEP < 2 * NI) {
+        constexpr int n = K / DSTEP;
+        if constexpr (n < NI) st1.template issue_one<n>(dma_lds, uwave);
+        else st2.template issue_one<n - NI>(dma_lds + 64 * D * 2, uwave);
+      }
+    }
+    bwd_full_subslots<D, MODE, ALIBI, PAR, DMA, K + 1>(W, trimm, nextrow, nextimm, u, v, wp, wd, nbias_v, sl2_v, dist0,
+                                                       dstep, st1, st2, dma_lds, uwave);
   }
 }
 
-template <int D, int MODE, bool ALIBI, int PAR>
+template <int D, int MODE, bool ALIBI, int PAR, bool DMA>
 __device__ __forceinline__ void bwd_step_full_pinned(BwdWave<D, MODE>& W, uint32_t trimm, const uint32_t* nextrow,
-                                                     uint32_t nextimm, int cs) {
+                                                     uint32_t nextimm, int cs, const DmaStagerX<D, 4>& st1,
+                                                     const DmaStagerX<D, 4>& st2, uint32_t dma_lds, int uwave) {
   float u[16], v[16];
   uint32_t wp[8], wd[8];
   // |i-j| of register r: DKDV streams queries (b - a), DQ streams keys (a - b)
   const int bl = cs + 8 * W.h;
   const float dist0 = MODE == BWD_DKDV ? (float)(bl - W.ai) : (float)(W.ai - bl);
   const float dstep = MODE == BWD_DKDV ? 1.0f : -1.0f;
-  bwd_full_subslots<D, MODE, ALIBI, PAR, 0>(W, trimm, nextrow, nextimm, u, v, wp, wd, W.nbias, W.sl2, dist0, dstep);
+#ifdef SATTN_EXPB_TIMING
+  __builtin_amdgcn_sched_barrier(0); const uint64_t tp0 = __builtin_amdgcn_s_memtime(); __builtin_amdgcn_s_waitcnt(0xC07F); __builtin_amdgcn_sched_barrier(0);
+#endif
+  bwd_full_subslots<D, MODE, ALIBI, PAR, DMA, 0>(W, trimm, nextrow, nextimm, u, v, wp, wd, W.nbias, W.sl2, dist0, dstep,
+                                                 st1, st2, dma_lds, uwave);
   // The compiler does not know that the asm statements above are MFMAs: let the last ones
   // retire before it may touch their accumulators (copies at the join with the other path).
   mfma_settle();
+#ifdef SATTN_EXPB_TIMING
+  __builtin_amdgcn_sched_barrier(0); const uint64_t tp1 = __builtin_amdgcn_s_memtime(); __builtin_amdgcn_s_waitcnt(0xC07F); __builtin_amdgcn_sched_barrier(0);
+  if (PAR == 0) W.tpin += tp1 - tp0;
+#endif
+#ifdef SATTN_EXPB_NOSIG
+  return;
+#endif
   if (MODE == BWD_DKDV) {
     W.pb[PAR ^ 1][0] = as_bf16x8(u32x4{wp[0], wp[1], wp[2], wp[3]});
     W.pb[PAR ^ 1][1] = as_bf16x8(u32x4{wp[4], wp[5], wp[6], wp[7]});
@@ -392,7 +476,11 @@ attn_bwd_kernel(const BwdParams p) {
     W.dstat = p.dvec[(int64_t)bh * N + ai_ld];
   }
   {
+#ifdef SATTN_EXPB_NOSIG
+    const bf16x8 z = as_bf16x8(u32x4{0x3c123d45u, 0xbc553b77u, 0x3d013c99u, 0xbd333c21u});
+#else
     const bf16x8 z = as_bf16x8(u32x4{0, 0, 0, 0});
+#endif
     W.pb[0][0] = W.pb[0][1] = W.pb[1][0] = W.pb[1][1] = z;
     W.dsb[0][0] = W.dsb[0][1] = W.dsb[1][0] = W.dsb[1][1] = z;
 #pragma unroll
@@ -413,6 +501,10 @@ attn_bwd_kernel(const BwdParams p) {
     }
   }
   if (a_wave0 >= N) { c_lo = 1; c_hi = 0; }  // wave past the end: no chunks
+  // The per-step flags are wave-uniform: evaluate them on the scalar unit.  The branch itself
+  // stays an exec-mask branch on an opaque VGPR copy of the flag (lane_flag), which keeps the
+  // two step variants in one linear region for the register allocator.
+  const int c_lo_s = __builtin_amdgcn_readfirstlane(c_lo), c_hi_s = __builtin_amdgcn_readfirstlane(c_hi);
   // step s handles chunks s, s-1, s-2; tile t holds chunks 2t, 2t+1 and runs steps 2t, 2t+1
   const int t_lo = wg_lo / 2, t_hi = (wg_hi + 2) / 2;  // the last step is wg_hi + 2
   const int t_data_hi = wg_hi / 2;                      // last tile that has to be staged
@@ -471,40 +563,94 @@ attn_bwd_kernel(const BwdParams p) {
     W.F[2 * kk + 1] = as_bf16x8(lds_read_b128(W.row0[kk] + TILE));
   }
 
+#ifdef SATTN_EXPB_TIMING
+  uint64_t tacc[6] = {0, 0, 0, 0, 0, 0};
+  W.tpin = 0;
+  const uint64_t tstart = __builtin_amdgcn_s_memtime();
+#endif
+  // Iteration t runs steps 2t and 2t+1 with one barrier between them.  Tile t+2 is staged
+  // during step 2t+1 (into the slot of tile t-2, whose last reads were in step 2t-1, before
+  // this iteration's barrier) and has landed before the next iteration's barrier, after which
+  // step 2t+3 reads its first rows.
+  auto flags = [&](int s, bool& doA, bool& doS, bool& doB, bool& mask) {
+    doA = s >= c_lo_s && s <= c_hi_s;
+    doS = s - 1 >= c_lo_s && s - 1 <= c_hi_s;
+    doB = s - 2 >= c_lo_s && s - 2 <= c_hi_s;
+    mask = (s - 1 == c_hi_s) || (CAUSAL && MODE == BWD_DKDV && s - 1 == c_lo_s);
+  };
   for (int t = t_lo; t <= t_hi; ++t) {
-    // stage tile t+2 into the slot of tile t-2 (last read during tile t-1)
-    const bool more = t + 2 <= t_data_hi;
-    if (more) {
-      st1.issue(lds0 + ((t + 2) % NSLOT) * SLOT, (t + 2) * BC, N, uwave);
-      st2.issue(lds0 + ((t + 2) % NSLOT) * SLOT + TILE, (t + 2) * BC, N, uwave);
-      load_stat(t + 2);
-    }
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      const int s = 2 * t + i;
-      const bool doA = s >= c_lo && s <= c_hi;
-      const bool doS = s - 1 >= c_lo && s - 1 <= c_hi;
-      const bool doB = s - 2 >= c_lo && s - 2 <= c_hi;
-      const bool mask = (s - 1 == c_hi) || (CAUSAL && MODE == BWD_DKDV && s - 1 == c_lo);
+#ifdef SATTN_EXPB_TIMING
+    __builtin_amdgcn_sched_barrier(0); const uint64_t tm0 = __builtin_amdgcn_s_memtime(); __builtin_amdgcn_s_waitcnt(0xC07F); __builtin_amdgcn_sched_barrier(0);
+#endif
+    {
+      const int s = 2 * t;
+      bool doA_s, doS_s, doB_s, mask_s;
+      flags(s, doA_s, doS_s, doB_s, mask_s);
       // chunk s-1 sits in tile (s-1)/2
       const SATTN_LDS(float)* stat = statbase + (((s - 1) >> 1) & (NSLOT - 1)) * 128 + ((s - 1) & 1) * 32 + 8 * h;
-      // rows of chunk s+1: step 2t refills from tile t (second half), step 2t+1 from tile t+1 (first half);
-      // transposed reads of chunk s-2: tile t-1, first half for step 2t, second half for step 2t+1
-#if defined(SATTN_EXP_NOPIN_DQ)
-      const bool full = MODE != BWD_DQ && !SOFTMAX && doA && doS && doB && !mask;
-#elif defined(SATTN_EXP_NOPIN_DKDV)
-      const bool full = MODE != BWD_DKDV && !SOFTMAX && doA && doS && doB && !mask;
-#else
-      const bool full = !SOFTMAX && doA && doS && doB && !mask;
-#endif
-      if (i == 0) {
-        if (full) bwd_step_full_pinned<D, MODE, ALIBI, 0>(W, 0, W.row0, CHUNK, 32 * (s - 1));
-        else bwd_step<D, MODE, CAUSAL, ALIBI, SOFTMAX, 0>(W, doA, doS, doB, mask, 0, W.row0, CHUNK, 32 * (s - 1), N, stat);
-      } else {
-        if (full) bwd_step_full_pinned<D, MODE, ALIBI, 1>(W, CHUNK, W.row1, 0, 32 * (s - 1));
-        else bwd_step<D, MODE, CAUSAL, ALIBI, SOFTMAX, 1>(W, doA, doS, doB, mask, CHUNK, W.row1, 0, 32 * (s - 1), N, stat);
-      }
+      // rows of chunk s+1 come from tile t (second half); transposed reads of chunk s-2 from tile t-1 (first half)
+      if (lane_flag(!SOFTMAX && doA_s && doS_s && doB_s && !mask_s))
+        bwd_step_full_pinned<D, MODE, ALIBI, 0, false>(W, 0, W.row0, CHUNK, 32 * (s - 1), st1, st2, 0, uwave);
+      else
+        bwd_step<D, MODE, CAUSAL, ALIBI, SOFTMAX, 0>(W, lane_flag(doA_s), lane_flag(doS_s), lane_flag(doB_s),
+                                                     lane_flag(mask_s), 0, W.row0, CHUNK, 32 * (s - 1), N, stat);
     }
+#ifdef SATTN_EXPB_TIMING
+    __builtin_amdgcn_sched_barrier(0); const uint64_t tm1 = __builtin_amdgcn_s_memtime(); __builtin_amdgcn_s_waitcnt(0xC07F); __builtin_amdgcn_sched_barrier(0);
+#endif
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): tile t+1 has landed
+#ifdef SATTN_EXPB_TIMING
+    __builtin_amdgcn_sched_barrier(0); const uint64_t tm2 = __builtin_amdgcn_s_memtime(); __builtin_amdgcn_s_waitcnt(0xC07F); __builtin_amdgcn_sched_barrier(0);
+#endif
+    // A bare barrier: fragment reads of the tiles that stay in the ring may remain in flight
+    // across it.  Only the softmax statistics are LDS writes that the other waves wait for.
+    if (SOFTMAX && MODE == BWD_DKDV) __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
+    __builtin_amdgcn_s_barrier();
+#ifdef SATTN_EXPB_TIMING
+    __builtin_amdgcn_sched_barrier(0); const uint64_t tm3 = __builtin_amdgcn_s_memtime(); __builtin_amdgcn_s_waitcnt(0xC07F); __builtin_amdgcn_sched_barrier(0);
+    uint64_t tm4 = 0;
+#endif
+    {
+      const int s = 2 * t + 1;
+      bool doA_s, doS_s, doB_s, mask_s;
+      flags(s, doA_s, doS_s, doB_s, mask_s);
+      const SATTN_LDS(float)* stat = statbase + (((s - 1) >> 1) & (NSLOT - 1)) * 128 + ((s - 1) & 1) * 32 + 8 * h;
+      const bool full_s = !SOFTMAX && doA_s && doS_s && doB_s && !mask_s;
+#ifdef SATTN_EXPB_NODMA
+      const bool more = false;
+#else
+      const bool more = t + 2 <= t_data_hi;
+#endif
+      const uint32_t dma_lds = lds0 + ((t + 2) % NSLOT) * SLOT;
+      if (!full_s) {
+        // compiler-scheduled step: stage the whole tile up front
+        if (more) {
+          st1.issue(dma_lds, (t + 2) * BC, N, uwave);
+          st2.issue(dma_lds + TILE, (t + 2) * BC, N, uwave);
+          load_stat(t + 2);
+        }
+      } else if ((t + 3) * BC > N) {
+        // the pinned step always stages (a tile past the data goes to the dead slot, from row N-1)
+        st1.clamp_tail((t + 2) * BC, N);
+        st2.clamp_tail((t + 2) * BC, N);
+      }
+#ifdef SATTN_EXPB_TIMING
+    __builtin_amdgcn_sched_barrier(0); tm4 = __builtin_amdgcn_s_memtime(); __builtin_amdgcn_s_waitcnt(0xC07F); __builtin_amdgcn_sched_barrier(0);
+#endif
+      // rows of chunk s+1 come from tile t+1 (first half); transposed reads of chunk s-2 from tile t-1 (second half)
+      if (lane_flag(full_s)) {
+        bwd_step_full_pinned<D, MODE, ALIBI, 1, true>(W, CHUNK, W.row1, 0, 32 * (s - 1), st1, st2, dma_lds, uwave);
+        st1.advance();
+        st2.advance();
+      } else {
+        bwd_step<D, MODE, CAUSAL, ALIBI, SOFTMAX, 1>(W, lane_flag(doA_s), lane_flag(doS_s), lane_flag(doB_s),
+                                                     lane_flag(mask_s), CHUNK, W.row1, 0, 32 * (s - 1), N, stat);
+      }
+      if (more) store_stat(t + 2);
+    }
+#ifdef SATTN_EXPB_TIMING
+    __builtin_amdgcn_sched_barrier(0); const uint64_t tm5 = __builtin_amdgcn_s_memtime(); __builtin_amdgcn_s_waitcnt(0xC07F); __builtin_amdgcn_sched_barrier(0);
+#endif
     // rotate the per-lane addresses by one ring slot
     {
       const int s0 = t % NSLOT;  // row0 points at slot s0, row1 at s0+1, tr at s0-1 (mod 4)
@@ -516,10 +662,12 @@ attn_bwd_kernel(const BwdParams p) {
 #pragma unroll
       for (int dt = 0; dt < DT; ++dt) { W.tr[dt][0] += advt; W.tr[dt][1] += advt; }
     }
-    if (more) store_stat(t + 2);
-    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): tile t+2 has landed (first read during tile t+1)
-    __syncthreads();
+#ifdef SATTN_EXPB_TIMING
+    __builtin_amdgcn_sched_barrier(0); const uint64_t tm6 = __builtin_amdgcn_s_memtime(); __builtin_amdgcn_s_waitcnt(0xC07F); __builtin_amdgcn_sched_barrier(0);
+    tacc[0] += tm1 - tm0; tacc[1] += tm2 - tm1; tacc[2] += tm3 - tm2; tacc[3] += tm4 - tm3; tacc[4] += tm5 - tm4; tacc[5] += tm6 - tm5;
+#endif
   }
+  __builtin_amdgcn_s_waitcnt(0x0F70);  // no staging may be in flight when the workgroup's LDS is released
 
   if (ai < N) {
     const float sc = p.inv_sqrt_d;  // dQ and dK carry the 1/sqrt(d) of the logits
@@ -547,6 +695,17 @@ attn_bwd_kernel(const BwdParams p) {
         }
     }
   }
+#ifdef SATTN_EXPB_TIMING
+  __syncthreads();
+  if (lane == 0 && ai < N) {
+    uint64_t* dbg = (MODE == BWD_DKDV ? (uint64_t*)((__bf16*)p.dk.ptr + b * p.dk.sb + hd * p.dk.sh + (int64_t)ai * p.dk.ss)
+                                      : (uint64_t*)((__bf16*)p.dq.ptr + b * p.dq.sb + hd * p.dq.sh + (int64_t)ai * p.dq.ss));
+    for (int i = 0; i < 6; ++i) dbg[i] = tacc[i];
+    dbg[6] = __builtin_amdgcn_s_memtime() - tstart;
+    dbg[7] = t_hi - t_lo + 1;
+    dbg[8] = W.tpin;
+  }
+#endif
 }
 
 // D_i = sum_t dO[i][t] * O[i][t] (fp32), the row term of the softmax backward.  16 lanes per
