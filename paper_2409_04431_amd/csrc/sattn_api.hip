@@ -131,11 +131,12 @@ enum BwdPart { kBwdDkDv = 1, kBwdDq = 2 };
 
 template <int D, bool SOFTMAX>
 int launch_bwd_bf16(BwdParams p, int causal, bool alibi, int parts, hipStream_t st) {
+  p.n_blocks = (p.N + 127) / 128;
+  dim3 grid(p.n_blocks * p.B * p.H);
+  int rc = SATTN_OK;
   constexpr size_t lds = 4 * 2 * 64 * D * 2;                    // 4 ring slots of two 64-row tiles
   constexpr size_t lds_stat = SOFTMAX ? 4 * 128 * sizeof(float) : 0;  // per-slot lse and D of the query tile
-  p.n_blocks = (p.N + 127) / 128;
-  dim3 grid(p.n_blocks * p.B * p.H), block(256);
-  int rc = SATTN_OK;
+  dim3 block(256);
   if (parts & kBwdDkDv)
     SATTN_DISPATCH2(causal, alibi,
                     rc = launch(attn_bwd_kernel<D, BWD_DKDV, A, B2, SOFTMAX>, grid, block, lds + lds_stat, st, p));

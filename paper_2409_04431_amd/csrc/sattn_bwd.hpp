@@ -52,49 +52,51 @@ struct SwzX {
 template <int D, int NW>
 struct DmaStagerX {
   static constexpr int BC = 64, CPR = D / 8, RPI = 64 / CPR, NI = (BC * CPR) / (64 * NW);
-  const char* base;      // (batch, head) slice of the tensor, wave-uniform
-  uint32_t off[NI];      // this lane's byte offset for the next tile to stage (unclamped)
-  uint32_t lastoff[NI];  // this lane's byte offset inside the last row N-1
-  int row[NI];           // tile-relative row this lane fills
-  uint32_t tile_bytes;
-  // The host side guarantees (N + 256) * ss * 2 < 2^32, so the offsets never wrap.
-  __device__ __forceinline__ void init(const __bf16* b, int64_t ss, int N, int j0, int wave, int lane) {
-    base = (const char*)b;
+  const char* base;       // first row of the next tile to stage (wave-uniform, advances per tile)
+  const char* base_last;  // row N-1 (wave-uniform)
+  uint32_t off[NI];       // this lane's byte offset inside a tile (constant)
+  uint32_t tile_bytes, row_bytes;
+  int j0;                 // first row of the next tile to stage
+  __device__ __forceinline__ static int row_of(int n, int wave, int lane) { return (wave * NI + n) * RPI + lane / CPR; }
+  __device__ __forceinline__ static uint32_t col_bytes(int n, int wave, int lane) {
+    return (uint32_t)(((lane % CPR) ^ SwzX<D>::f(row_of(n, wave, lane))) * 16);
+  }
+  __device__ __forceinline__ void init(const __bf16* b, int64_t ss, int N, int first_row, int wave, int lane) {
+    base = (const char*)(b + (int64_t)first_row * ss);
+    base_last = (const char*)(b + (int64_t)(N - 1) * ss);
+    row_bytes = (uint32_t)(ss * 2);
+    tile_bytes = BC * row_bytes;
+    j0 = first_row;
 #pragma unroll
-    for (int n = 0; n < NI; ++n) {
-      const int r = (wave * NI + n) * RPI + lane / CPR, pc = lane % CPR;
-      const int c = pc ^ SwzX<D>::f(r);
-      row[n] = r;
-      off[n] = (uint32_t)(((int64_t)(j0 + r) * ss + c * 8) * 2);
-      lastoff[n] = (uint32_t)(((int64_t)(N - 1) * ss + c * 8) * 2);
+    for (int n = 0; n < NI; ++n) off[n] = row_of(n, wave, lane) * row_bytes + col_bytes(n, wave, lane);
+  }
+  __device__ __forceinline__ static void load(uint32_t o, const char* sbase, uint32_t m0v) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(o), "s"(sbase), "s"(m0v) : "memory");
+  }
+  __device__ __forceinline__ void advance() { base += tile_bytes; j0 += BC; }
+  // Stage the whole next tile.  Rows past the end re-read row N-1.
+  __device__ __forceinline__ void issue(uint32_t lds, int N, int wave, int lane) {
+    if (j0 + BC <= N) {
+#pragma unroll
+      for (int n = 0; n < NI; ++n) load(off[n], base, lds + (wave * NI + n) * 1024);
+    } else if (j0 < N) {
+      const uint32_t to_last = (uint32_t)(N - 1 - j0) * row_bytes;
+#pragma unroll
+      for (int n = 0; n < NI; ++n) {
+        const uint32_t o = (j0 + row_of(n, wave, lane) < N) ? off[n] : to_last + col_bytes(n, wave, lane);
+        load(o, base, lds + (wave * NI + n) * 1024);
+      }
+    } else {
+#pragma unroll
+      for (int n = 0; n < NI; ++n) load(col_bytes(n, wave, lane), base_last, lds + (wave * NI + n) * 1024);
     }
-    tile_bytes = (uint32_t)(BC * ss * 2);
+    advance();
   }
-  __device__ __forceinline__ void load(uint32_t o, uint32_t m0v) const {
-    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(o), "s"(base), "s"(m0v) : "memory");
-  }
-  __device__ __forceinline__ void issue(uint32_t lds, int j0, int N, int wave) {
-#pragma unroll
-    for (int n = 0; n < NI; ++n) {
-      uint32_t o = off[n];
-      if (j0 + BC > N) o = (j0 + row[n] < N) ? o : lastoff[n];  // rows past the end re-read row N-1
-      load(o, lds + (wave * NI + n) * 1024);
-      off[n] += tile_bytes;
-    }
-  }
-  // The same staging split into single instructions (for interleaving with a pinned step):
-  // clamp_tail() first when the tile crosses the end, issue_one<0..NI-1>(), then advance().
-  __device__ __forceinline__ void clamp_tail(int j0, int N) {
-#pragma unroll
-    for (int n = 0; n < NI; ++n) off[n] = (j0 + row[n] < N) ? off[n] : lastoff[n];
-  }
+  // One instruction of the same staging for a tile that lies inside the tensor (for
+  // interleaving with a pinned step; the caller calls advance() after the last one).
   template <int n>
   __device__ __forceinline__ void issue_one(uint32_t lds, int wave) const {
-    load(off[n], lds + (wave * NI + n) * 1024);
-  }
-  __device__ __forceinline__ void advance() {
-#pragma unroll
-    for (int n = 0; n < NI; ++n) off[n] += tile_bytes;
+    load(off[n], base, lds + (wave * NI + n) * 1024);
   }
 };
 
@@ -129,9 +131,6 @@ struct BwdWave {
   int ai, h;              // this lane's stationary row, lane half
   float nscale, nbias, sl2;
   float nlse, dstat;      // softmax DQ: this lane's -lse*log2e and D
-#ifdef SATTN_EXPB_TIMING
-  uint64_t tpin;
-#endif
 };
 
 // Every MFMA of the backward kernel is a volatile asm statement with fixed register classes:
@@ -142,11 +141,7 @@ struct BwdWave {
 // before an MFMA may read it.  The compiler-scheduled step needs it (register copies and
 // packs may sit right in front of the statement); the pinned step orders its own
 // instructions and is verified on the generated assembly instead (isa_check.py).
-#ifdef SATTN_EXPB_NOMFMA
-#define SATTN_BWD_MFMA(PRE, ACC) "; skip"
-#else
 #define SATTN_BWD_MFMA(PRE, ACC) PRE "v_mfma_f32_32x32x16_bf16 %0, %1, %2, " ACC
-#endif
 template <bool GUARD>
 __device__ __forceinline__ void b_mfma_v(f32x16& c, const bf16x8& a, const bf16x8& b_agpr) {
   if constexpr (GUARD) asm volatile(SATTN_BWD_MFMA("s_nop 1\n\t", "%0") : "+v"(c) : "v"(a), "a"(b_agpr) : "memory");
@@ -154,12 +149,8 @@ __device__ __forceinline__ void b_mfma_v(f32x16& c, const bf16x8& a, const bf16x
 }
 template <bool GUARD>
 __device__ __forceinline__ void b_mfma_v0(f32x16& c, const bf16x8& a, const bf16x8& b_agpr) {
-#ifdef SATTN_EXPB_NOMFMA
-  asm volatile("; skip" : "+v"(c) : "v"(a), "a"(b_agpr) : "memory");
-#else
   if constexpr (GUARD) asm volatile(SATTN_BWD_MFMA("s_nop 1\n\t", "0") : "=&v"(c) : "v"(a), "a"(b_agpr) : "memory");
   else asm volatile(SATTN_BWD_MFMA("", "0") : "=&v"(c) : "v"(a), "a"(b_agpr) : "memory");
-#endif
 }
 template <bool GUARD>
 __device__ __forceinline__ void b_mfma_a(f32x16& c_agpr, const bf16x8& a, const bf16x8& b) {
@@ -308,6 +299,9 @@ __device__ __forceinline__ void bsig_ops(const BwdWave<D, MODE>& W, const f32x16
   }
 }
 
+#ifndef SATTN_PIN_GUARD
+#define SATTN_PIN_GUARD false
+#endif
 template <int D, int MODE, bool ALIBI, int PAR, bool DMA, int K>
 __device__ __forceinline__ void bwd_full_subslots(BwdWave<D, MODE>& W, uint32_t trimm, const uint32_t* nextrow,
                                                   uint32_t nextimm, float (&u)[16], float (&v)[16], uint32_t (&wp)[8],
@@ -325,25 +319,19 @@ __device__ __forceinline__ void bwd_full_subslots(BwdWave<D, MODE>& W, uint32_t 
       constexpr int kk = K / 2;
       if constexpr ((K & 1) == 0) {
         // S-type product from tensor 1, then fetch the transposed tensor-1 fragment kk
-        if constexpr (kk == 0) b_mfma_v0<false>(W.s[PAR], W.F[K], W.x1[kk]);
-        else b_mfma_v<false>(W.s[PAR], W.F[K], W.x1[kk]);
+        if constexpr (kk == 0) b_mfma_v0<SATTN_PIN_GUARD>(W.s[PAR], W.F[K], W.x1[kk]);
+        else b_mfma_v<SATTN_PIN_GUARD>(W.s[PAR], W.F[K], W.x1[kk]);
         const uint32_t off = trimm + (kk / DT) * 16 * (D * 2);
-#ifndef SATTN_EXPB_NOLDS
         W.F[K] = join_tr(lds_read_tr16(W.tr[kk % DT][0] + off), lds_read_tr16(W.tr[kk % DT][1] + off));
-#endif
       } else {
         // dP-type product from tensor 2
-        if constexpr (kk == 0) b_mfma_v0<false>(W.dp[PAR], W.F[K], W.x2[kk]);
-        else b_mfma_v<false>(W.dp[PAR], W.F[K], W.x2[kk]);
+        if constexpr (kk == 0) b_mfma_v0<SATTN_PIN_GUARD>(W.dp[PAR], W.F[K], W.x2[kk]);
+        else b_mfma_v<SATTN_PIN_GUARD>(W.dp[PAR], W.F[K], W.x2[kk]);
         if constexpr (MODE == BWD_DKDV) {
           const uint32_t off = trimm + (kk / DT) * 16 * (D * 2) + T2OFF;
-#ifndef SATTN_EXPB_NOLDS
           W.F[K] = join_tr(lds_read_tr16(W.tr[kk % DT][0] + off), lds_read_tr16(W.tr[kk % DT][1] + off));
-#endif
         } else {
-#ifndef SATTN_EXPB_NOLDS
           W.F[K] = as_bf16x8(lds_read_b128(nextrow[kk] + nextimm + T2OFF));  // DQ: V is only read row-wise
-#endif
         }
       }
     } else {
@@ -352,28 +340,20 @@ __device__ __forceinline__ void bwd_full_subslots(BwdWave<D, MODE>& W, uint32_t 
       if constexpr (MODE == BWD_DKDV) {
         constexpr int j = KB / 2;
         if constexpr ((KB & 1) == 0) {
-          b_mfma_a<false>(W.acc0[j % DT], W.F[2 * j], W.dsb[PAR][j / DT]);      // dK^T += Q^T dS
-#ifndef SATTN_EXPB_NOLDS
+          b_mfma_a<SATTN_PIN_GUARD>(W.acc0[j % DT], W.F[2 * j], W.dsb[PAR][j / DT]);      // dK^T += Q^T dS
           W.F[2 * j] = as_bf16x8(lds_read_b128(nextrow[j] + nextimm));
-#endif
         } else {
-          b_mfma_a<false>(W.acc1[j % DT], W.F[2 * j + 1], W.pb[PAR][j / DT]);   // dV^T += dO^T P
-#ifndef SATTN_EXPB_NOLDS
+          b_mfma_a<SATTN_PIN_GUARD>(W.acc1[j % DT], W.F[2 * j + 1], W.pb[PAR][j / DT]);   // dV^T += dO^T P
           W.F[2 * j + 1] = as_bf16x8(lds_read_b128(nextrow[j] + nextimm + T2OFF));
-#endif
         }
       } else {
         constexpr int j = KB;
-        b_mfma_a<false>(W.acc0[j % DT], W.F[2 * j], W.dsb[PAR][j / DT]);        // dQ^T += K^T dS^T
-#ifndef SATTN_EXPB_NOLDS
+        b_mfma_a<SATTN_PIN_GUARD>(W.acc0[j % DT], W.F[2 * j], W.dsb[PAR][j / DT]);        // dQ^T += K^T dS^T
         W.F[2 * j] = as_bf16x8(lds_read_b128(nextrow[j] + nextimm));
-#endif
       }
     }
-#ifndef SATTN_EXPB_NOSIG
     bsig_ops<D, MODE, ALIBI, (K * NOPS) / NSUB, ((K + 1) * NOPS) / NSUB>(W, W.s[PAR ^ 1], W.dp[PAR ^ 1], u, v, wp, wd,
                                                                          nbias_v, sl2_v, dist0, dstep);
-#endif
     if constexpr (DMA) {
       // one staging instruction of the tile two ahead every DSTEP sub-slots
       constexpr int NI = DmaStagerX<D, 4>::NI, DSTEP = NSUB / (2 * NI);
@@ -398,21 +378,11 @@ __device__ __forceinline__ void bwd_step_full_pinned(BwdWave<D, MODE>& W, uint32
   const int bl = cs + 8 * W.h;
   const float dist0 = MODE == BWD_DKDV ? (float)(bl - W.ai) : (float)(W.ai - bl);
   const float dstep = MODE == BWD_DKDV ? 1.0f : -1.0f;
-#ifdef SATTN_EXPB_TIMING
-  __builtin_amdgcn_sched_barrier(0); const uint64_t tp0 = __builtin_amdgcn_s_memtime(); __builtin_amdgcn_s_waitcnt(0xC07F); __builtin_amdgcn_sched_barrier(0);
-#endif
   bwd_full_subslots<D, MODE, ALIBI, PAR, DMA, 0>(W, trimm, nextrow, nextimm, u, v, wp, wd, W.nbias, W.sl2, dist0, dstep,
                                                  st1, st2, dma_lds, uwave);
   // The compiler does not know that the asm statements above are MFMAs: let the last ones
   // retire before it may touch their accumulators (copies at the join with the other path).
   mfma_settle();
-#ifdef SATTN_EXPB_TIMING
-  __builtin_amdgcn_sched_barrier(0); const uint64_t tp1 = __builtin_amdgcn_s_memtime(); __builtin_amdgcn_s_waitcnt(0xC07F); __builtin_amdgcn_sched_barrier(0);
-  if (PAR == 0) W.tpin += tp1 - tp0;
-#endif
-#ifdef SATTN_EXPB_NOSIG
-  return;
-#endif
   if (MODE == BWD_DKDV) {
     W.pb[PAR ^ 1][0] = as_bf16x8(u32x4{wp[0], wp[1], wp[2], wp[3]});
     W.pb[PAR ^ 1][1] = as_bf16x8(u32x4{wp[4], wp[5], wp[6], wp[7]});
@@ -476,11 +446,7 @@ attn_bwd_kernel(const BwdParams p) {
     W.dstat = p.dvec[(int64_t)bh * N + ai_ld];
   }
   {
-#ifdef SATTN_EXPB_NOSIG
-    const bf16x8 z = as_bf16x8(u32x4{0x3c123d45u, 0xbc553b77u, 0x3d013c99u, 0xbd333c21u});
-#else
     const bf16x8 z = as_bf16x8(u32x4{0, 0, 0, 0});
-#endif
     W.pb[0][0] = W.pb[0][1] = W.pb[1][0] = W.pb[1][1] = z;
     W.dsb[0][0] = W.dsb[0][1] = W.dsb[1][0] = W.dsb[1][1] = z;
 #pragma unroll
@@ -544,13 +510,13 @@ attn_bwd_kernel(const BwdParams p) {
     if (SOFTMAX && MODE == BWD_DKDV && tid < 128) statbase[(t % NSLOT) * 128 + tid] = statreg;
   };
   // prologue: tiles t_lo and t_lo+1
-  st1.issue(lds0 + (t_lo % NSLOT) * SLOT, t_lo * BC, N, uwave);
-  st2.issue(lds0 + (t_lo % NSLOT) * SLOT + TILE, t_lo * BC, N, uwave);
+  st1.issue(lds0 + (t_lo % NSLOT) * SLOT, N, uwave, lane);
+  st2.issue(lds0 + (t_lo % NSLOT) * SLOT + TILE, N, uwave, lane);
   load_stat(t_lo);
   store_stat(t_lo);
   if (t_lo + 1 <= t_data_hi) {
-    st1.issue(lds0 + ((t_lo + 1) % NSLOT) * SLOT, (t_lo + 1) * BC, N, uwave);
-    st2.issue(lds0 + ((t_lo + 1) % NSLOT) * SLOT + TILE, (t_lo + 1) * BC, N, uwave);
+    st1.issue(lds0 + ((t_lo + 1) % NSLOT) * SLOT, N, uwave, lane);
+    st2.issue(lds0 + ((t_lo + 1) % NSLOT) * SLOT + TILE, N, uwave, lane);
     load_stat(t_lo + 1);
     store_stat(t_lo + 1);
   }
@@ -563,11 +529,6 @@ attn_bwd_kernel(const BwdParams p) {
     W.F[2 * kk + 1] = as_bf16x8(lds_read_b128(W.row0[kk] + TILE));
   }
 
-#ifdef SATTN_EXPB_TIMING
-  uint64_t tacc[6] = {0, 0, 0, 0, 0, 0};
-  W.tpin = 0;
-  const uint64_t tstart = __builtin_amdgcn_s_memtime();
-#endif
   // Iteration t runs steps 2t and 2t+1 with one barrier between them.  Tile t+2 is staged
   // during step 2t+1 (into the slot of tile t-2, whose last reads were in step 2t-1, before
   // this iteration's barrier) and has landed before the next iteration's barrier, after which
@@ -578,96 +539,134 @@ attn_bwd_kernel(const BwdParams p) {
     doB = s - 2 >= c_lo_s && s - 2 <= c_hi_s;
     mask = (s - 1 == c_hi_s) || (CAUSAL && MODE == BWD_DKDV && s - 1 == c_lo_s);
   };
-  for (int t = t_lo; t <= t_hi; ++t) {
+  // A wave issues about one instruction every six cycles whatever the instruction, so the
+  // per-tile control flow is kept out of the steady state: tiles whose two steps are both
+  // full (chunks s, s-1, s-2 inside this wave's range, no mask: c_lo+2 <= s <= c_hi) run a
+  // loop of pinned steps only; the tiles before and after run the flag-driven general body.
+  // Every variant has its one barrier per tile at the same place, so waves of a workgroup
+  // may be in different loops.
+  const int t_s0 = SOFTMAX ? t_hi + 1 : (c_lo_s + 3) / 2;          // first tile with 2t >= c_lo+2
+  const int t_s1a = (c_hi_s + 1) / 2 - 1, t_s1b = N / BC - 3;      // last tile with 2t+1 <= c_hi / with tile t+2 inside the tensor
+  const int t_s1 = SOFTMAX ? t_lo - 1 : (t_s1a < t_s1b ? t_s1a : t_s1b);
+  auto rotate = [&](int t) {
+    // rotate the per-lane addresses by one ring slot
+    const int s0 = t % NSLOT;  // row0 points at slot s0, row1 at s0+1, tr at s0-1 (mod 4)
+    const int adv0 = s0 == NSLOT - 1 ? -(NSLOT - 1) * SLOT : SLOT;
+    const int adv1 = s0 == NSLOT - 2 ? -(NSLOT - 1) * SLOT : SLOT;
+    const int advt = s0 == 0 ? -(NSLOT - 1) * SLOT : SLOT;
+#pragma unroll
+    for (int kk = 0; kk < KD; ++kk) { W.row0[kk] += adv0; W.row1[kk] += adv1; }
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) { W.tr[dt][0] += advt; W.tr[dt][1] += advt; }
+  };
 #ifdef SATTN_EXPB_TIMING
-    __builtin_amdgcn_sched_barrier(0); const uint64_t tm0 = __builtin_amdgcn_s_memtime(); __builtin_amdgcn_s_waitcnt(0xC07F); __builtin_amdgcn_sched_barrier(0);
+  uint64_t tacc[7] = {0, 0, 0, 0, 0, 0, 0}, tlast = 0;
+  const uint64_t tstart = __builtin_amdgcn_s_memtime();
 #endif
-    {
-      const int s = 2 * t;
-      bool doA_s, doS_s, doB_s, mask_s;
-      flags(s, doA_s, doS_s, doB_s, mask_s);
-      // chunk s-1 sits in tile (s-1)/2
-      const SATTN_LDS(float)* stat = statbase + (((s - 1) >> 1) & (NSLOT - 1)) * 128 + ((s - 1) & 1) * 32 + 8 * h;
-      // rows of chunk s+1 come from tile t (second half); transposed reads of chunk s-2 from tile t-1 (first half)
-      if (lane_flag(!SOFTMAX && doA_s && doS_s && doB_s && !mask_s))
-        bwd_step_full_pinned<D, MODE, ALIBI, 0, false>(W, 0, W.row0, CHUNK, 32 * (s - 1), st1, st2, 0, uwave);
-      else
-        bwd_step<D, MODE, CAUSAL, ALIBI, SOFTMAX, 0>(W, lane_flag(doA_s), lane_flag(doS_s), lane_flag(doB_s),
-                                                     lane_flag(mask_s), 0, W.row0, CHUNK, 32 * (s - 1), N, stat);
-    }
-#ifdef SATTN_EXPB_TIMING
-    __builtin_amdgcn_sched_barrier(0); const uint64_t tm1 = __builtin_amdgcn_s_memtime(); __builtin_amdgcn_s_waitcnt(0xC07F); __builtin_amdgcn_sched_barrier(0);
-#endif
-    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): tile t+1 has landed
-#ifdef SATTN_EXPB_TIMING
-    __builtin_amdgcn_sched_barrier(0); const uint64_t tm2 = __builtin_amdgcn_s_memtime(); __builtin_amdgcn_s_waitcnt(0xC07F); __builtin_amdgcn_sched_barrier(0);
-#endif
-    // A bare barrier: fragment reads of the tiles that stay in the ring may remain in flight
-    // across it.  Only the softmax statistics are LDS writes that the other waves wait for.
-    if (SOFTMAX && MODE == BWD_DKDV) __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
-    __builtin_amdgcn_s_barrier();
-#ifdef SATTN_EXPB_TIMING
-    __builtin_amdgcn_sched_barrier(0); const uint64_t tm3 = __builtin_amdgcn_s_memtime(); __builtin_amdgcn_s_waitcnt(0xC07F); __builtin_amdgcn_sched_barrier(0);
-    uint64_t tm4 = 0;
-#endif
-    {
-      const int s = 2 * t + 1;
-      bool doA_s, doS_s, doB_s, mask_s;
-      flags(s, doA_s, doS_s, doB_s, mask_s);
-      const SATTN_LDS(float)* stat = statbase + (((s - 1) >> 1) & (NSLOT - 1)) * 128 + ((s - 1) & 1) * 32 + 8 * h;
-      const bool full_s = !SOFTMAX && doA_s && doS_s && doB_s && !mask_s;
-#ifdef SATTN_EXPB_NODMA
-      const bool more = false;
-#else
-      const bool more = t + 2 <= t_data_hi;
-#endif
-      const uint32_t dma_lds = lds0 + ((t + 2) % NSLOT) * SLOT;
-      if (!full_s) {
-        // compiler-scheduled step: stage the whole tile up front
-        if (more) {
-          st1.issue(dma_lds, (t + 2) * BC, N, uwave);
-          st2.issue(dma_lds + TILE, (t + 2) * BC, N, uwave);
-          load_stat(t + 2);
-        }
-      } else if ((t + 3) * BC > N) {
-        // the pinned step always stages (a tile past the data goes to the dead slot, from row N-1)
-        st1.clamp_tail((t + 2) * BC, N);
-        st2.clamp_tail((t + 2) * BC, N);
+  int t = t_lo;
+  int general_end = t_s0 < t_hi + 1 ? t_s0 : t_hi + 1;
+  for (int phase = 0; phase < 2; ++phase) {
+    for (; t < general_end; ++t) {
+      {
+        const int s = 2 * t;
+        bool doA_s, doS_s, doB_s, mask_s;
+        flags(s, doA_s, doS_s, doB_s, mask_s);
+        // chunk s-1 sits in tile (s-1)/2
+        const SATTN_LDS(float)* stat = statbase + (((s - 1) >> 1) & (NSLOT - 1)) * 128 + ((s - 1) & 1) * 32 + 8 * h;
+        // rows of chunk s+1 come from tile t (second half); transposed reads of chunk s-2 from tile t-1 (first half)
+        if (lane_flag(!SOFTMAX && doA_s && doS_s && doB_s && !mask_s))
+          bwd_step_full_pinned<D, MODE, ALIBI, 0, false>(W, 0, W.row0, CHUNK, 32 * (s - 1), st1, st2, 0, uwave);
+        else
+          bwd_step<D, MODE, CAUSAL, ALIBI, SOFTMAX, 0>(W, lane_flag(doA_s), lane_flag(doS_s), lane_flag(doB_s),
+                                                       lane_flag(mask_s), 0, W.row0, CHUNK, 32 * (s - 1), N, stat);
       }
+      __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): tile t+1 has landed
+      // A bare barrier: fragment reads of the tiles that stay in the ring may remain in flight
+      // across it.  Only the softmax statistics are LDS writes that the other waves wait for.
+      if (SOFTMAX && MODE == BWD_DKDV) __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
+      __builtin_amdgcn_s_barrier();
+      {
+        const int s = 2 * t + 1;
+        bool doA_s, doS_s, doB_s, mask_s;
+        flags(s, doA_s, doS_s, doB_s, mask_s);
+        const SATTN_LDS(float)* stat = statbase + (((s - 1) >> 1) & (NSLOT - 1)) * 128 + ((s - 1) & 1) * 32 + 8 * h;
+        // the pinned step stages tile t+2 without a tail clamp: that tile must lie inside the tensor
+        const bool full_s = !SOFTMAX && doA_s && doS_s && doB_s && !mask_s && (t + 3) * BC <= N;
+        const bool more = t + 2 <= t_data_hi;
+        const uint32_t dma_lds = lds0 + ((t + 2) % NSLOT) * SLOT;
+        if (!full_s) {
+          // compiler-scheduled step: stage the whole tile up front
+          if (more) {
+            st1.issue(dma_lds, N, uwave, lane);
+            st2.issue(dma_lds + TILE, N, uwave, lane);
+            load_stat(t + 2);
+          }
+        }
+        // rows of chunk s+1 come from tile t+1 (first half); transposed reads of chunk s-2 from tile t-1 (second half)
+        if (lane_flag(full_s)) {
+          bwd_step_full_pinned<D, MODE, ALIBI, 1, true>(W, CHUNK, W.row1, 0, 32 * (s - 1), st1, st2, dma_lds, uwave);
+        } else {
+          bwd_step<D, MODE, CAUSAL, ALIBI, SOFTMAX, 1>(W, lane_flag(doA_s), lane_flag(doS_s), lane_flag(doB_s),
+                                                       lane_flag(mask_s), CHUNK, W.row1, 0, 32 * (s - 1), N, stat);
+        }
+        if (full_s) {  // wave-uniform state: advanced outside the exec-masked branch
+          st1.advance();
+          st2.advance();
+        }
+        if (more) store_stat(t + 2);
+      }
+      rotate(t);
+    }
+    if (phase == 0) {
+      for (; t <= t_s1; ++t) {
 #ifdef SATTN_EXPB_TIMING
-    __builtin_amdgcn_sched_barrier(0); tm4 = __builtin_amdgcn_s_memtime(); __builtin_amdgcn_s_waitcnt(0xC07F); __builtin_amdgcn_sched_barrier(0);
+        __builtin_amdgcn_sched_barrier(0); const uint64_t q0 = __builtin_amdgcn_s_memtime(); __builtin_amdgcn_s_waitcnt(0xC07F); __builtin_amdgcn_sched_barrier(0);
 #endif
-      // rows of chunk s+1 come from tile t+1 (first half); transposed reads of chunk s-2 from tile t-1 (second half)
-      if (lane_flag(full_s)) {
-        bwd_step_full_pinned<D, MODE, ALIBI, 1, true>(W, CHUNK, W.row1, 0, 32 * (s - 1), st1, st2, dma_lds, uwave);
+        bwd_step_full_pinned<D, MODE, ALIBI, 0, false>(W, 0, W.row0, CHUNK, 32 * (2 * t - 1), st1, st2, 0, uwave);
+#ifdef SATTN_EXPB_TIMING
+        __builtin_amdgcn_sched_barrier(0); const uint64_t q1 = __builtin_amdgcn_s_memtime(); __builtin_amdgcn_s_waitcnt(0xC07F); __builtin_amdgcn_sched_barrier(0);
+#endif
+        __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): tile t+1 has landed
+#ifdef SATTN_EXPB_TIMING
+        __builtin_amdgcn_sched_barrier(0); const uint64_t q2 = __builtin_amdgcn_s_memtime(); __builtin_amdgcn_s_waitcnt(0xC07F); __builtin_amdgcn_sched_barrier(0);
+#endif
+        __builtin_amdgcn_s_barrier();
+#ifdef SATTN_EXPB_TIMING
+        __builtin_amdgcn_sched_barrier(0); const uint64_t q3 = __builtin_amdgcn_s_memtime(); __builtin_amdgcn_s_waitcnt(0xC07F); __builtin_amdgcn_sched_barrier(0);
+#endif
+        bwd_step_full_pinned<D, MODE, ALIBI, 1, true>(W, CHUNK, W.row1, 0, 32 * (2 * t), st1, st2,
+                                                      lds0 + ((t + 2) % NSLOT) * SLOT, uwave);
+#ifdef SATTN_EXPB_TIMING
+        __builtin_amdgcn_sched_barrier(0); const uint64_t q4 = __builtin_amdgcn_s_memtime(); __builtin_amdgcn_s_waitcnt(0xC07F); __builtin_amdgcn_sched_barrier(0);
+#endif
         st1.advance();
         st2.advance();
-      } else {
-        bwd_step<D, MODE, CAUSAL, ALIBI, SOFTMAX, 1>(W, lane_flag(doA_s), lane_flag(doS_s), lane_flag(doB_s),
-                                                     lane_flag(mask_s), CHUNK, W.row1, 0, 32 * (s - 1), N, stat);
+        rotate(t);
+#ifdef SATTN_EXPB_TIMING
+        __builtin_amdgcn_sched_barrier(0); const uint64_t q5 = __builtin_amdgcn_s_memtime(); __builtin_amdgcn_s_waitcnt(0xC07F); __builtin_amdgcn_sched_barrier(0);
+        tacc[0] += q1 - q0; tacc[1] += q2 - q1; tacc[2] += q3 - q2; tacc[3] += q4 - q3; tacc[4] += q5 - q4; tacc[5] += 1;
+        if (tlast) tacc[6] += q0 - tlast;
+        tlast = q5;
+#endif
       }
-      if (more) store_stat(t + 2);
     }
-#ifdef SATTN_EXPB_TIMING
-    __builtin_amdgcn_sched_barrier(0); const uint64_t tm5 = __builtin_amdgcn_s_memtime(); __builtin_amdgcn_s_waitcnt(0xC07F); __builtin_amdgcn_sched_barrier(0);
-#endif
-    // rotate the per-lane addresses by one ring slot
-    {
-      const int s0 = t % NSLOT;  // row0 points at slot s0, row1 at s0+1, tr at s0-1 (mod 4)
-      const int adv0 = s0 == NSLOT - 1 ? -(NSLOT - 1) * SLOT : SLOT;
-      const int adv1 = s0 == NSLOT - 2 ? -(NSLOT - 1) * SLOT : SLOT;
-      const int advt = s0 == 0 ? -(NSLOT - 1) * SLOT : SLOT;
-#pragma unroll
-      for (int kk = 0; kk < KD; ++kk) { W.row0[kk] += adv0; W.row1[kk] += adv1; }
-#pragma unroll
-      for (int dt = 0; dt < DT; ++dt) { W.tr[dt][0] += advt; W.tr[dt][1] += advt; }
-    }
-#ifdef SATTN_EXPB_TIMING
-    __builtin_amdgcn_sched_barrier(0); const uint64_t tm6 = __builtin_amdgcn_s_memtime(); __builtin_amdgcn_s_waitcnt(0xC07F); __builtin_amdgcn_sched_barrier(0);
-    tacc[0] += tm1 - tm0; tacc[1] += tm2 - tm1; tacc[2] += tm3 - tm2; tacc[3] += tm4 - tm3; tacc[4] += tm5 - tm4; tacc[5] += tm6 - tm5;
-#endif
+    general_end = t_hi + 1;
   }
   __builtin_amdgcn_s_waitcnt(0x0F70);  // no staging may be in flight when the workgroup's LDS is released
+#ifdef SATTN_EXPB_TIMING
+  {
+    const uint64_t tend = __builtin_amdgcn_s_memtime();
+    __syncthreads();
+    if (lane == 0 && ai < N) {
+      uint64_t* dbg = (MODE == BWD_DKDV ? (uint64_t*)((__bf16*)p.dk.ptr + b * p.dk.sb + hd * p.dk.sh + (int64_t)ai * p.dk.ss)
+                                        : (uint64_t*)((__bf16*)p.dq.ptr + b * p.dq.sb + hd * p.dq.sh + (int64_t)ai * p.dq.ss));
+      for (int i = 0; i < 7; ++i) dbg[i] = tacc[i];
+      dbg[7] = tend - tstart;
+      dbg[8] = t_hi - t_lo + 1;
+    }
+    return;
+  }
+#endif
 
   if (ai < N) {
     const float sc = p.inv_sqrt_d;  // dQ and dK carry the 1/sqrt(d) of the logits
@@ -695,17 +694,6 @@ attn_bwd_kernel(const BwdParams p) {
         }
     }
   }
-#ifdef SATTN_EXPB_TIMING
-  __syncthreads();
-  if (lane == 0 && ai < N) {
-    uint64_t* dbg = (MODE == BWD_DKDV ? (uint64_t*)((__bf16*)p.dk.ptr + b * p.dk.sb + hd * p.dk.sh + (int64_t)ai * p.dk.ss)
-                                      : (uint64_t*)((__bf16*)p.dq.ptr + b * p.dq.sb + hd * p.dq.sh + (int64_t)ai * p.dq.ss));
-    for (int i = 0; i < 6; ++i) dbg[i] = tacc[i];
-    dbg[6] = __builtin_amdgcn_s_memtime() - tstart;
-    dbg[7] = t_hi - t_lo + 1;
-    dbg[8] = W.tpin;
-  }
-#endif
 }
 
 // D_i = sum_t dO[i][t] * O[i][t] (fp32), the row term of the softmax backward.  16 lanes per
