@@ -14,10 +14,13 @@
 // of the second products is a transposing LDS read of the same row-major tiles.
 //
 // One workgroup = 4 waves (one per SIMD, up to 512 registers each), 32 stationary rows per
-// wave, 64-row streamed tiles in a 4-slot LDS ring filled by direct-to-LDS loads one tile
-// ahead.  Work is software pipelined over 32-row chunks: step s issues the first products
-// of chunk s, evaluates the sigmoid / dS of chunk s-1 and issues the second products of
-// chunk s-2.
+// wave, 64-row streamed tiles in a 4-slot LDS ring filled by direct-to-LDS loads two tiles
+// ahead (issued one instruction at a time inside the second step of a tile).  Work is
+// software pipelined over 32-row chunks: step s issues the first products of chunk s,
+// evaluates the sigmoid / dS of chunk s-1 and issues the second products of chunk s-2.
+// The steady-state step is a fixed instruction stream of asm statements (MFMA, LDS refill,
+// a slice of the sigmoid arithmetic); tiles at the ends of a wave's range, masked tiles and
+// the softmax variant run a compiler-scheduled step with the same data flow.
 #pragma once
 #include "sattn_common.hpp"
 
@@ -299,9 +302,6 @@ __device__ __forceinline__ void bsig_ops(const BwdWave<D, MODE>& W, const f32x16
   }
 }
 
-#ifndef SATTN_PIN_GUARD
-#define SATTN_PIN_GUARD false
-#endif
 template <int D, int MODE, bool ALIBI, int PAR, bool DMA, int K>
 __device__ __forceinline__ void bwd_full_subslots(BwdWave<D, MODE>& W, uint32_t trimm, const uint32_t* nextrow,
                                                   uint32_t nextimm, float (&u)[16], float (&v)[16], uint32_t (&wp)[8],
@@ -319,14 +319,14 @@ __device__ __forceinline__ void bwd_full_subslots(BwdWave<D, MODE>& W, uint32_t 
       constexpr int kk = K / 2;
       if constexpr ((K & 1) == 0) {
         // S-type product from tensor 1, then fetch the transposed tensor-1 fragment kk
-        if constexpr (kk == 0) b_mfma_v0<SATTN_PIN_GUARD>(W.s[PAR], W.F[K], W.x1[kk]);
-        else b_mfma_v<SATTN_PIN_GUARD>(W.s[PAR], W.F[K], W.x1[kk]);
+        if constexpr (kk == 0) b_mfma_v0<false>(W.s[PAR], W.F[K], W.x1[kk]);
+        else b_mfma_v<false>(W.s[PAR], W.F[K], W.x1[kk]);
         const uint32_t off = trimm + (kk / DT) * 16 * (D * 2);
         W.F[K] = join_tr(lds_read_tr16(W.tr[kk % DT][0] + off), lds_read_tr16(W.tr[kk % DT][1] + off));
       } else {
         // dP-type product from tensor 2
-        if constexpr (kk == 0) b_mfma_v0<SATTN_PIN_GUARD>(W.dp[PAR], W.F[K], W.x2[kk]);
-        else b_mfma_v<SATTN_PIN_GUARD>(W.dp[PAR], W.F[K], W.x2[kk]);
+        if constexpr (kk == 0) b_mfma_v0<false>(W.dp[PAR], W.F[K], W.x2[kk]);
+        else b_mfma_v<false>(W.dp[PAR], W.F[K], W.x2[kk]);
         if constexpr (MODE == BWD_DKDV) {
           const uint32_t off = trimm + (kk / DT) * 16 * (D * 2) + T2OFF;
           W.F[K] = join_tr(lds_read_tr16(W.tr[kk % DT][0] + off), lds_read_tr16(W.tr[kk % DT][1] + off));
@@ -340,15 +340,15 @@ __device__ __forceinline__ void bwd_full_subslots(BwdWave<D, MODE>& W, uint32_t 
       if constexpr (MODE == BWD_DKDV) {
         constexpr int j = KB / 2;
         if constexpr ((KB & 1) == 0) {
-          b_mfma_a<SATTN_PIN_GUARD>(W.acc0[j % DT], W.F[2 * j], W.dsb[PAR][j / DT]);      // dK^T += Q^T dS
+          b_mfma_a<false>(W.acc0[j % DT], W.F[2 * j], W.dsb[PAR][j / DT]);      // dK^T += Q^T dS
           W.F[2 * j] = as_bf16x8(lds_read_b128(nextrow[j] + nextimm));
         } else {
-          b_mfma_a<SATTN_PIN_GUARD>(W.acc1[j % DT], W.F[2 * j + 1], W.pb[PAR][j / DT]);   // dV^T += dO^T P
+          b_mfma_a<false>(W.acc1[j % DT], W.F[2 * j + 1], W.pb[PAR][j / DT]);   // dV^T += dO^T P
           W.F[2 * j + 1] = as_bf16x8(lds_read_b128(nextrow[j] + nextimm + T2OFF));
         }
       } else {
         constexpr int j = KB;
-        b_mfma_a<SATTN_PIN_GUARD>(W.acc0[j % DT], W.F[2 * j], W.dsb[PAR][j / DT]);        // dQ^T += K^T dS^T
+        b_mfma_a<false>(W.acc0[j % DT], W.F[2 * j], W.dsb[PAR][j / DT]);        // dQ^T += K^T dS^T
         W.F[2 * j] = as_bf16x8(lds_read_b128(nextrow[j] + nextimm));
       }
     }
@@ -559,10 +559,6 @@ attn_bwd_kernel(const BwdParams p) {
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt) { W.tr[dt][0] += advt; W.tr[dt][1] += advt; }
   };
-#ifdef SATTN_EXPB_TIMING
-  uint64_t tacc[7] = {0, 0, 0, 0, 0, 0, 0}, tlast = 0;
-  const uint64_t tstart = __builtin_amdgcn_s_memtime();
-#endif
   int t = t_lo;
   int general_end = t_s0 < t_hi + 1 ? t_s0 : t_hi + 1;
   for (int phase = 0; phase < 2; ++phase) {
@@ -619,54 +615,19 @@ attn_bwd_kernel(const BwdParams p) {
     }
     if (phase == 0) {
       for (; t <= t_s1; ++t) {
-#ifdef SATTN_EXPB_TIMING
-        __builtin_amdgcn_sched_barrier(0); const uint64_t q0 = __builtin_amdgcn_s_memtime(); __builtin_amdgcn_s_waitcnt(0xC07F); __builtin_amdgcn_sched_barrier(0);
-#endif
         bwd_step_full_pinned<D, MODE, ALIBI, 0, false>(W, 0, W.row0, CHUNK, 32 * (2 * t - 1), st1, st2, 0, uwave);
-#ifdef SATTN_EXPB_TIMING
-        __builtin_amdgcn_sched_barrier(0); const uint64_t q1 = __builtin_amdgcn_s_memtime(); __builtin_amdgcn_s_waitcnt(0xC07F); __builtin_amdgcn_sched_barrier(0);
-#endif
         __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): tile t+1 has landed
-#ifdef SATTN_EXPB_TIMING
-        __builtin_amdgcn_sched_barrier(0); const uint64_t q2 = __builtin_amdgcn_s_memtime(); __builtin_amdgcn_s_waitcnt(0xC07F); __builtin_amdgcn_sched_barrier(0);
-#endif
         __builtin_amdgcn_s_barrier();
-#ifdef SATTN_EXPB_TIMING
-        __builtin_amdgcn_sched_barrier(0); const uint64_t q3 = __builtin_amdgcn_s_memtime(); __builtin_amdgcn_s_waitcnt(0xC07F); __builtin_amdgcn_sched_barrier(0);
-#endif
         bwd_step_full_pinned<D, MODE, ALIBI, 1, true>(W, CHUNK, W.row1, 0, 32 * (2 * t), st1, st2,
                                                       lds0 + ((t + 2) % NSLOT) * SLOT, uwave);
-#ifdef SATTN_EXPB_TIMING
-        __builtin_amdgcn_sched_barrier(0); const uint64_t q4 = __builtin_amdgcn_s_memtime(); __builtin_amdgcn_s_waitcnt(0xC07F); __builtin_amdgcn_sched_barrier(0);
-#endif
         st1.advance();
         st2.advance();
         rotate(t);
-#ifdef SATTN_EXPB_TIMING
-        __builtin_amdgcn_sched_barrier(0); const uint64_t q5 = __builtin_amdgcn_s_memtime(); __builtin_amdgcn_s_waitcnt(0xC07F); __builtin_amdgcn_sched_barrier(0);
-        tacc[0] += q1 - q0; tacc[1] += q2 - q1; tacc[2] += q3 - q2; tacc[3] += q4 - q3; tacc[4] += q5 - q4; tacc[5] += 1;
-        if (tlast) tacc[6] += q0 - tlast;
-        tlast = q5;
-#endif
       }
     }
     general_end = t_hi + 1;
   }
   __builtin_amdgcn_s_waitcnt(0x0F70);  // no staging may be in flight when the workgroup's LDS is released
-#ifdef SATTN_EXPB_TIMING
-  {
-    const uint64_t tend = __builtin_amdgcn_s_memtime();
-    __syncthreads();
-    if (lane == 0 && ai < N) {
-      uint64_t* dbg = (MODE == BWD_DKDV ? (uint64_t*)((__bf16*)p.dk.ptr + b * p.dk.sb + hd * p.dk.sh + (int64_t)ai * p.dk.ss)
-                                        : (uint64_t*)((__bf16*)p.dq.ptr + b * p.dq.sb + hd * p.dq.sh + (int64_t)ai * p.dq.ss));
-      for (int i = 0; i < 7; ++i) dbg[i] = tacc[i];
-      dbg[7] = tend - tstart;
-      dbg[8] = t_hi - t_lo + 1;
-    }
-    return;
-  }
-#endif
 
   if (ai < N) {
     const float sc = p.inv_sqrt_d;  // dQ and dK carry the 1/sqrt(d) of the logits

@@ -78,9 +78,7 @@ struct DmaStager {
       if (j0 + BC > N) src = (j0 + row[n] < N) ? src : last[n];
       const uint32_t m0v = lds + (wave * NI + n) * 1024;
       asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(src), "s"(m0v) : "memory");
-#ifndef SATTN_EXP_SAMETILE
       ptr[n] += tile_bytes;
-#endif
     }
   }
 };
@@ -427,34 +425,14 @@ attn_fwd_kernel(const FwdParams p) {
   // vf from V chunk c (tile t, slot t%3).  The per-lane LDS addresses rotate with the rings.
 #pragma unroll
   for (int kk = 0; kk < KD; ++kk) W.koff[kk] += TILE;  // K reads now point at tile 1
-#ifdef SATTN_EXP_TIMING
-  uint64_t tacc[5] = {0, 0, 0, 0, 0};
-  const uint64_t tstart = __builtin_amdgcn_s_memtime();
-#endif
   int kslot = 0;  // ring slot of K tile t == slot that K(t+3) will overwrite; V tile t is in the same slot index
   for (int t = 0; t < n_tiles; ++t) {
-#ifdef SATTN_EXP_NOLOAD
-    const bool k_more = false, v_more = false;
-#else
     const bool k_more = t + 3 < n_tiles, v_more = t + 2 < n_tiles;
-#endif
     const int vslot2 = kslot == 0 ? 2 : kslot - 1;  // (t+2)%3
-#ifdef SATTN_EXP_TIMING
-    __builtin_amdgcn_sched_barrier(0); const uint64_t tm0 = __builtin_amdgcn_s_memtime(); __builtin_amdgcn_s_waitcnt(0xC07F); __builtin_amdgcn_sched_barrier(0);
-#endif
     if (k_more) kst.issue(kring + kslot * TILE, (t + 3) * BC, N, uwave);
     if (v_more) vst.issue(vring + vslot2 * TILE, (t + 2) * BC, N, uwave);
-#ifdef SATTN_EXP_TIMING
-    __builtin_amdgcn_sched_barrier(0); const uint64_t tm1 = __builtin_amdgcn_s_memtime(); __builtin_amdgcn_s_waitcnt(0xC07F); __builtin_amdgcn_sched_barrier(0);
-#endif
     fwd_step_any<D, ALIBI, SOFTMAX, 0>(W, 2 * t, cw, 0, 0, N, CAUSAL);
-#ifdef SATTN_EXP_TIMING
-    __builtin_amdgcn_sched_barrier(0); const uint64_t tm2 = __builtin_amdgcn_s_memtime(); __builtin_amdgcn_s_waitcnt(0xC07F); __builtin_amdgcn_sched_barrier(0);
-#endif
     fwd_step_any<D, ALIBI, SOFTMAX, 1>(W, 2 * t + 1, cw, CHUNK, CHUNK, N, CAUSAL);
-#ifdef SATTN_EXP_TIMING
-    __builtin_amdgcn_sched_barrier(0); const uint64_t tm3 = __builtin_amdgcn_s_memtime(); __builtin_amdgcn_s_waitcnt(0xC07F); __builtin_amdgcn_sched_barrier(0);
-#endif
     // advance the read addresses by one ring slot: K reads are at slot (t+1)%3, V reads at t%3
     const int kadv = kslot == 1 ? -2 * TILE : TILE;  // slot (t+1)%3 == 2 wraps to 0
     const int vadv = kslot == 2 ? -2 * TILE : TILE;
@@ -467,16 +445,7 @@ attn_fwd_kernel(const FwdParams p) {
     if (k_more) SATTN_WAIT_VMCNT(NIK + NIV);
     else if (v_more) SATTN_WAIT_VMCNT(NIV);
     else SATTN_WAIT_VMCNT(0);
-#ifdef SATTN_EXP_TIMING
-    __builtin_amdgcn_sched_barrier(0); const uint64_t tm4 = __builtin_amdgcn_s_memtime(); __builtin_amdgcn_s_waitcnt(0xC07F); __builtin_amdgcn_sched_barrier(0);
-#endif
-#ifndef SATTN_EXP_NOBARRIER
     __syncthreads();
-#endif
-#ifdef SATTN_EXP_TIMING
-    __builtin_amdgcn_sched_barrier(0); const uint64_t tm5 = __builtin_amdgcn_s_memtime(); __builtin_amdgcn_s_waitcnt(0xC07F); __builtin_amdgcn_sched_barrier(0);
-    tacc[0] += tm1 - tm0; tacc[1] += tm2 - tm1; tacc[2] += tm3 - tm2; tacc[3] += tm4 - tm3; tacc[4] += tm5 - tm4;
-#endif
   }
   // flush: O^T update of the last chunk when it fell on the last step of the loop
   if (cw == 2 * n_tiles && cw > 0) fwd_step<D, ALIBI, SOFTMAX, STEP_TAIL, 0>(W, 0, 0, 0, N, CAUSAL);
@@ -491,11 +460,8 @@ attn_fwd_kernel(const FwdParams p) {
       for (int r = 0; r < 16; ++r) W.oacc[dt][r] *= inv;
     if (qi < N && h == 0) p.lse[(int64_t)bh * N + qi] = (W.sm.m + __builtin_amdgcn_logf(l_tot)) * kLn2;
   }
-#ifdef SATTN_EXP_TIMING_NEVER
-#else
   // ---- store O (bf16): register 4g+t of tile dt is O[qi][32dt + 8g + 4h + t]
   if (qi < N) {
-#endif
     __bf16* orow = obase + (int64_t)qi * p.o.ss;
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt)
@@ -507,15 +473,6 @@ attn_fwd_kernel(const FwdParams p) {
         *(u32x2*)(orow + 32 * dt + 8 * g + 4 * h) = w;
       }
   }
-#ifdef SATTN_EXP_TIMING
-  __syncthreads();
-  if (lane == 0 && qi < N) {
-    uint64_t* dbg = (uint64_t*)(obase + (int64_t)qi * p.o.ss);
-    for (int i = 0; i < 5; ++i) dbg[i] = tacc[i];
-    dbg[5] = __builtin_amdgcn_s_memtime() - tstart;
-    dbg[6] = n_tiles;
-  }
-#endif
 }
 
 }  // namespace sattn
