@@ -23,8 +23,8 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 matrix peak
 
 # HBM bytes per launch of the dominant kernel (dK/dV on the headline workload), from
 # `rocprofv3 --pmc FETCH_SIZE` and `--pmc WRITE_SIZE` runs of this script scaled by a plain
-# copy kernel: 2 x 262 199 KiB read + 262 144 KiB written (profiles/attn_kernels_cfg3_pmc.txt).
-MEASURED_TRAFFIC_BYTES = {3: (2 * 262199 + 262144) * 1024}
+# copy kernel: 2 x 262 318 KiB read + 262 144 KiB written (profiles/attn_kernels_cfg3_pmc.txt).
+MEASURED_TRAFFIC_BYTES = {3: (2 * 262318 + 262144) * 1024}
 
 
 def _events(n):
@@ -109,6 +109,17 @@ def main():
             sa.sigmoid_attn_bwd_dq(q, k, v, dout, dq, bias, cfg.causal, slopes)
             if ev: ev[3].record()
 
+    # the matrix rate this device sustains at its actual clock (register-resident MFMA loop)
+    props = torch.cuda.get_device_properties(dev)
+    sink = torch.empty(props.multi_processor_count * 256, dtype=torch.float32, device=dev)
+    sa.sattn_mfma_bf16_probe(props.multi_processor_count, 2000, sink)
+    pe = _events(2)
+    pe[0].record()
+    probe_flops = sa.sattn_mfma_bf16_probe(props.multi_processor_count, 20000, sink)
+    pe[1].record()
+    torch.cuda.synchronize()
+    sustained_peak = probe_flops / pe[0].elapsed_time(pe[1]) / 1e9
+
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -130,6 +141,9 @@ def main():
         "dtype": "bf16" if cfg.dtype == torch.bfloat16 else "f32", "data": "synthetic",
         "config": {"workload": cfg.name, "B": cfg.B, "H": cfg.H, "N": cfg.N, "d": cfg.d, "causal": cfg.causal,
                    "alibi": cfg.alibi, "bias": bias, "flop_convention": "fwd 4BHN^2d, bwd 10BHN^2d, x0.5 causal"},
+        "device": {"name": props.name, "compute_units": props.multi_processor_count,
+                   "clock_mhz": getattr(props, "clock_rate", 0) / 1e3 or None,
+                   "sustained_mfma_bf16_tflops": sustained_peak},
         "fwd_ms": fwd_ms, "fwd_tflops": flops_f / fwd_ms / 1e9,
         "fwd_frac_of_bf16_mfma_peak": flops_f / fwd_ms / 1e9 / MFMA_BF16_PEAK_TFLOPS,
     }
@@ -145,7 +159,7 @@ def main():
         # 5 backward products (8*B*H*N^2*d, halved when causal); dQ's recompute is not counted.
         algo = 0.8 * flops_b
         ach = algo / dkdv_ms / 1e9
-        out["roofline"] = {"kernel": "attn_bwd_dkdv_kernel", "bound": "mfma", "achieved": ach,
+        out["roofline"] = {"kernel": "attn_bwd_kernel<BWD_DKDV>", "bound": "mfma", "achieved": ach,
                            "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": ach / MFMA_BF16_PEAK_TFLOPS,
                            "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.cfg), "avg_launch_ms": dkdv_ms}
     else:
@@ -156,7 +170,7 @@ def main():
                            "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": ach / MFMA_BF16_PEAK_TFLOPS,
                            "traffic": None, "avg_launch_ms": fwd_ms}
 
-    if args.softmax:
+    if args.softmax and cfg.dtype == torch.bfloat16:  # the comparison kernels exist for bf16 only
         lse = torch.empty(cfg.B, cfg.H, cfg.N, dtype=torch.float32, device=dev)
         for _ in range(args.warmup):
             sa.softmax_attn_fwd(q, k, v, o, lse, cfg.causal, slopes)

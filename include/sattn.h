@@ -140,6 +140,14 @@ size_t softmax_attn_bwd_workspace_bytes(int B, int H, int N, int d, sattn_dtype 
 /* Human-readable text for an SATTN_ERR_* code (static storage). */
 const char* sattn_strerror(int code);
 
+/* Measurement aid (Section 4.1 quotes kernel speed against the matrix-unit peak): launches
+ * `blocks` workgroups of 4 waves that each issue iters*8 independent register-resident
+ * 32x32x16 bf16 MFMAs (32768 flop each) and nothing else, asynchronously on `stream`.  The
+ * caller times the launch; blocks*4*iters*8*32768 flop / time is the matrix rate this device
+ * sustains at its actual clock.  `sink` is a device pointer to blocks*256 floats that
+ * receives one value per lane (keeps the loop alive).  Returns 0 or SATTN_ERR_*. */
+int sattn_mfma_bf16_probe(int blocks, int iters, float* sink, void* stream);
+
 /* Library version: major*10000 + minor*100 + patch. */
 int sattn_version(void);
 

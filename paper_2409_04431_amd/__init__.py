@@ -16,6 +16,7 @@ from .binding import (  # noqa: F401
     softmax_attn_bwd,
     softmax_attn_bwd_workspace_bytes,
     softmax_attn_fwd,
+    sattn_mfma_bf16_probe,
     sattn_strerror,
     sattn_version,
 )

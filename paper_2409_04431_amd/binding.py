@@ -60,6 +60,8 @@ def load_library():
     lib.softmax_attn_bwd_workspace_bytes.restype = sz
     lib.sattn_strerror.argtypes = [i]
     lib.sattn_strerror.restype = ctypes.c_char_p
+    lib.sattn_mfma_bf16_probe.argtypes = [i, i, _vp, _vp]
+    lib.sattn_mfma_bf16_probe.restype = i
     lib.sattn_version.argtypes = []
     lib.sattn_version.restype = i
     _lib = lib
@@ -68,6 +70,14 @@ def load_library():
 
 def sattn_strerror(code):
     return load_library().sattn_strerror(int(code)).decode()
+
+
+def sattn_mfma_bf16_probe(blocks, iters, sink):
+    """Launch the register-resident MFMA loop on torch's current stream; returns its flop count."""
+    assert sink.is_cuda and sink.dtype == torch.float32 and sink.numel() >= blocks * 256
+    rc = load_library().sattn_mfma_bf16_probe(int(blocks), int(iters), _vp(sink.data_ptr()), _stream())
+    _raise(rc, "sattn_mfma_bf16_probe")
+    return blocks * 4 * iters * 8 * 32768
 
 
 def sattn_version():

@@ -15,6 +15,31 @@ namespace {
 
 int elem_size(sattn_dtype t) { return t == SATTN_BF16 ? 2 : 4; }
 
+// Register-resident MFMA loop of the matrix-rate probe: 4 accumulators, 8 MFMAs per iteration.
+__global__ void __launch_bounds__(256) mfma_bf16_probe_kernel(float* sink, int iters) {
+  f32x16 acc[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
+  bf16x8 a, b;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    a[e] = (__bf16)(0.01f * (float)((threadIdx.x % 7) + e));
+    b[e] = (__bf16)(0.02f * (float)((threadIdx.x % 5) + e));
+  }
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int u = 0; u < 8; ++u) acc[u & 3] = mfma32(a, b, acc[u & 3]);
+  }
+  float s = 0.f;
+#pragma unroll
+  for (int j = 0; j < 4; ++j)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) s += acc[j][r];
+  sink[(size_t)blockIdx.x * 256 + threadIdx.x] = s;
+}
+
 // Validate one tensor and turn it into a TensorRef.  Strides are in elements.
 int make_ref(const void* ptr, const sattn_strides* s, int H, int N, int d, sattn_dtype dt, TensorRef* out) {
   if (!ptr) return SATTN_ERR_NULL;
@@ -296,6 +321,12 @@ const char* sattn_strerror(int code) {
     case SATTN_ERR_LAUNCH: return "the HIP runtime rejected the kernel launch";
     default: return "unknown error code";
   }
+}
+
+int sattn_mfma_bf16_probe(int blocks, int iters, float* sink, void* stream) {
+  if (!sink) return SATTN_ERR_NULL;
+  if (blocks <= 0 || iters <= 0) return SATTN_ERR_SHAPE;
+  return launch(mfma_bf16_probe_kernel, dim3(blocks), dim3(256), 0, (hipStream_t)stream, sink, iters);
 }
 
 int sattn_version(void) { return 100; }
