@@ -256,15 +256,24 @@ __device__ __forceinline__ void bwd_step(BwdWave<D, MODE>& W, bool doA, bool doS
 // chunk's row fragment right after the second-product MFMA that used that.
 
 // Arithmetic of one chunk as 4 groups of four elements.  Per group:
-//   F x4 (u = s*scale + bias[+alibi])  X x4 (2^u)  A x4 (1+e)  R x4 (p = 1/.)  Q x4 (p - p^2)
-//   M x4 (dS = . * dP)  [CP x2 pack P]  CD x2 pack dS
-template <int D, int MODE, bool ALIBI, int I>
+//   F x4 (u = s*scale + bias[+alibi])  X x4 (2^u)  A x4 (1+e)  R x4 (p = 1/.)  [C x4]
+//   Q x4 (p - p^2)  M x4 (dS = . * dP)  [D x4]  [CP x2 pack P]  CD x2 pack dS
+// MASK adds C (keep = key_of_reg(e) >= thr for DKDV, <= thr for DQ; p = keep ? p : 0) and
+// D (dS = keep ? dS : 0): selects, so that a masked element is exactly zero whatever the
+// logit and dP registers hold (they are not even finite in a dead pipeline stage).
+template <int MODE, bool MASK>
+struct BsigLayout {
+  static constexpr int nC = MASK ? 4 : 0, nP = MODE == BWD_DKDV ? 2 : 0;
+  static constexpr int oX = 4, oA = 8, oR = 12, oC = 16, oQ = 16 + nC, oM = oQ + 4, oD = oM + 4, oP = oD + nC,
+                       oS = oP + nP, OPG = oS + 2, NOPS = 4 * OPG;
+};
+template <int D, int MODE, bool ALIBI, bool MASK, int I>
 __device__ __forceinline__ void bsig_op(const BwdWave<D, MODE>& W, const f32x16& s, const f32x16& dp, float (&u)[16],
-                                        float (&v)[16], uint32_t (&wp)[8], uint32_t (&wd)[8], float nbias_v,
-                                        float sl2_v, float dist0, float dstep) {
-  constexpr int OPG = MODE == BWD_DKDV ? 28 : 26;
-  constexpr int G = I / OPG, i = I % OPG, e = 4 * G + (i & 3);
-  if constexpr (i < 4) {
+                                        float (&v)[16], uint32_t (&wp)[8], uint32_t (&wd)[8], uint64_t (&km)[16],
+                                        float nbias_v, float sl2_v, float dist0, float dstep, int thr) {
+  using L = BsigLayout<MODE, MASK>;
+  constexpr int G = I / L::OPG, i = I % L::OPG, e = 4 * G + (i & 3);
+  if constexpr (i < L::oX) {
     if constexpr (ALIBI) {
       float t, w;
       const float keyf = (float)key_of_reg(e);
@@ -274,46 +283,54 @@ __device__ __forceinline__ void bsig_op(const BwdWave<D, MODE>& W, const f32x16&
     } else {
       asm volatile("v_fma_f32 %0, %1, %2, %3" : "=v"(u[e]) : "v"(s[e]), "s"(W.nscale), "v"(nbias_v));
     }
-  } else if constexpr (i < 8) {
+  } else if constexpr (i < L::oA) {
     asm volatile("v_exp_f32 %0, %0" : "+v"(u[e]));
-  } else if constexpr (i < 12) {
+  } else if constexpr (i < L::oR) {
     asm volatile("v_add_f32 %0, 1.0, %0" : "+v"(u[e]));
-  } else if constexpr (i < 16) {
+  } else if constexpr (i < L::oC) {
     asm volatile("v_rcp_f32 %0, %0" : "+v"(u[e]));
-  } else if constexpr (i < 20) {
+  } else if constexpr (i < L::oQ) {
+    constexpr int kor = key_of_reg(e);
+    if constexpr (MODE == BWD_DKDV)
+      asm volatile("v_cmp_ge_i32_e64 %0, %2, %3\n\tv_cndmask_b32_e64 %1, 0, %1, %0" : "=&s"(km[e]), "+v"(u[e]) : "n"(kor), "v"(thr));
+    else
+      asm volatile("v_cmp_le_i32_e64 %0, %2, %3\n\tv_cndmask_b32_e64 %1, 0, %1, %0" : "=&s"(km[e]), "+v"(u[e]) : "n"(kor), "v"(thr));
+  } else if constexpr (i < L::oM) {
     asm volatile("v_fma_f32 %0, -%1, %1, %1" : "=v"(v[e]) : "v"(u[e]));
-  } else if constexpr (i < 24) {
+  } else if constexpr (i < L::oD) {
     asm volatile("v_mul_f32 %0, %0, %1" : "+v"(v[e]) : "v"(dp[e]));
-  } else if constexpr (MODE == BWD_DKDV && i < 26) {
-    constexpr int j = 2 * G + (i - 24);
+  } else if constexpr (i < L::oP) {
+    asm volatile("v_cndmask_b32_e64 %0, 0, %0, %1" : "+v"(v[e]) : "s"(km[e]));
+  } else if constexpr (i < L::oS) {
+    constexpr int j = 2 * G + (i - L::oP);
     asm volatile("v_cvt_pk_bf16_f32 %0, %1, %2" : "=v"(wp[j]) : "v"(u[2 * j]), "v"(u[2 * j + 1]));
   } else {
-    constexpr int j = 2 * G + (i - (MODE == BWD_DKDV ? 26 : 24));
+    constexpr int j = 2 * G + (i - L::oS);
     asm volatile("v_cvt_pk_bf16_f32 %0, %1, %2" : "=v"(wd[j]) : "v"(v[2 * j]), "v"(v[2 * j + 1]));
   }
 }
-template <int D, int MODE, bool ALIBI, int LO, int HI>
+template <int D, int MODE, bool ALIBI, bool MASK, int LO, int HI>
 __device__ __forceinline__ void bsig_ops(const BwdWave<D, MODE>& W, const f32x16& s, const f32x16& dp, float (&u)[16],
-                                         float (&v)[16], uint32_t (&wp)[8], uint32_t (&wd)[8], float nbias_v,
-                                         float sl2_v, float dist0, float dstep) {
+                                         float (&v)[16], uint32_t (&wp)[8], uint32_t (&wd)[8], uint64_t (&km)[16],
+                                         float nbias_v, float sl2_v, float dist0, float dstep, int thr) {
   if constexpr (LO < HI) {
-    bsig_op<D, MODE, ALIBI, LO>(W, s, dp, u, v, wp, wd, nbias_v, sl2_v, dist0, dstep);
-    bsig_ops<D, MODE, ALIBI, LO + 1, HI>(W, s, dp, u, v, wp, wd, nbias_v, sl2_v, dist0, dstep);
+    bsig_op<D, MODE, ALIBI, MASK, LO>(W, s, dp, u, v, wp, wd, km, nbias_v, sl2_v, dist0, dstep, thr);
+    bsig_ops<D, MODE, ALIBI, MASK, LO + 1, HI>(W, s, dp, u, v, wp, wd, km, nbias_v, sl2_v, dist0, dstep, thr);
   }
 }
 
-template <int D, int MODE, bool ALIBI, int PAR, bool DMA, int K>
+template <int D, int MODE, bool ALIBI, int PAR, bool DMA, bool MASK, int K>
 __device__ __forceinline__ void bwd_full_subslots(BwdWave<D, MODE>& W, uint32_t trimm, const uint32_t* nextrow,
                                                   uint32_t nextimm, float (&u)[16], float (&v)[16], uint32_t (&wp)[8],
-                                                  uint32_t (&wd)[8], float nbias_v, float sl2_v, float dist0,
-                                                  float dstep, const DmaStagerX<D, 4>& st1, const DmaStagerX<D, 4>& st2,
-                                                  uint32_t dma_lds, int uwave) {
+                                                  uint32_t (&wd)[8], uint64_t (&km)[16], float nbias_v, float sl2_v,
+                                                  float dist0, float dstep, int thr, const DmaStagerX<D, 4>& st1,
+                                                  const DmaStagerX<D, 4>& st2, uint32_t dma_lds, int uwave) {
   constexpr int KD = D / 16, DT = D / 32;
   constexpr uint32_t T2OFF = 64 * D * 2;
   constexpr int NA = 2 * KD;                               // first-product MFMAs
   constexpr int NB = MODE == BWD_DKDV ? 2 * KD : KD;       // second-product MFMAs
   constexpr int NSUB = NA + NB;
-  constexpr int NOPS = 4 * (MODE == BWD_DKDV ? 28 : 26);
+  constexpr int NOPS = BsigLayout<MODE, MASK>::NOPS;
   if constexpr (K < NSUB) {
     if constexpr (K < NA) {
       constexpr int kk = K / 2;
@@ -352,8 +369,8 @@ __device__ __forceinline__ void bwd_full_subslots(BwdWave<D, MODE>& W, uint32_t 
         W.F[2 * j] = as_bf16x8(lds_read_b128(nextrow[j] + nextimm));
       }
     }
-    bsig_ops<D, MODE, ALIBI, (K * NOPS) / NSUB, ((K + 1) * NOPS) / NSUB>(W, W.s[PAR ^ 1], W.dp[PAR ^ 1], u, v, wp, wd,
-                                                                         nbias_v, sl2_v, dist0, dstep);
+    bsig_ops<D, MODE, ALIBI, MASK, (K * NOPS) / NSUB, ((K + 1) * NOPS) / NSUB>(W, W.s[PAR ^ 1], W.dp[PAR ^ 1], u, v, wp, wd,
+                                                                               km, nbias_v, sl2_v, dist0, dstep, thr);
     if constexpr (DMA) {
       // one staging instruction of the tile two ahead every DSTEP sub-slots
       constexpr int NI = DmaStagerX<D, 4>::NI, DSTEP = NSUB / (2 * NI);
@@ -363,23 +380,26 @@ __device__ __forceinline__ void bwd_full_subslots(BwdWave<D, MODE>& W, uint32_t 
         else st2.template issue_one<n - NI>(dma_lds + 64 * D * 2, uwave);
       }
     }
-    bwd_full_subslots<D, MODE, ALIBI, PAR, DMA, K + 1>(W, trimm, nextrow, nextimm, u, v, wp, wd, nbias_v, sl2_v, dist0,
-                                                       dstep, st1, st2, dma_lds, uwave);
+    bwd_full_subslots<D, MODE, ALIBI, PAR, DMA, MASK, K + 1>(W, trimm, nextrow, nextimm, u, v, wp, wd, km, nbias_v, sl2_v,
+                                                             dist0, dstep, thr, st1, st2, dma_lds, uwave);
   }
 }
 
-template <int D, int MODE, bool ALIBI, int PAR, bool DMA>
+// thr (MASK only): elements with key_of_reg(e) >= thr (DKDV) / <= thr (DQ) are kept.
+template <int D, int MODE, bool ALIBI, int PAR, bool DMA, bool MASK = false>
 __device__ __forceinline__ void bwd_step_full_pinned(BwdWave<D, MODE>& W, uint32_t trimm, const uint32_t* nextrow,
                                                      uint32_t nextimm, int cs, const DmaStagerX<D, 4>& st1,
-                                                     const DmaStagerX<D, 4>& st2, uint32_t dma_lds, int uwave) {
+                                                     const DmaStagerX<D, 4>& st2, uint32_t dma_lds, int uwave,
+                                                     int thr = 0) {
   float u[16], v[16];
   uint32_t wp[8], wd[8];
+  uint64_t km[16];
   // |i-j| of register r: DKDV streams queries (b - a), DQ streams keys (a - b)
   const int bl = cs + 8 * W.h;
   const float dist0 = MODE == BWD_DKDV ? (float)(bl - W.ai) : (float)(W.ai - bl);
   const float dstep = MODE == BWD_DKDV ? 1.0f : -1.0f;
-  bwd_full_subslots<D, MODE, ALIBI, PAR, DMA, 0>(W, trimm, nextrow, nextimm, u, v, wp, wd, W.nbias, W.sl2, dist0, dstep,
-                                                 st1, st2, dma_lds, uwave);
+  bwd_full_subslots<D, MODE, ALIBI, PAR, DMA, MASK, 0>(W, trimm, nextrow, nextimm, u, v, wp, wd, km, W.nbias, W.sl2,
+                                                       dist0, dstep, thr, st1, st2, dma_lds, uwave);
   // The compiler does not know that the asm statements above are MFMAs: let the last ones
   // retire before it may touch their accumulators (copies at the join with the other path).
   mfma_settle();
@@ -509,7 +529,17 @@ attn_bwd_kernel(const BwdParams p) {
   auto store_stat = [&](int t) {
     if (SOFTMAX && MODE == BWD_DKDV && tid < 128) statbase[(t % NSLOT) * 128 + tid] = statreg;
   };
-  // prologue: tiles t_lo and t_lo+1
+  // prologue: tiles t_lo and t_lo+1, and tile t_lo-1 (tile 0 again for t_lo = 0): the pinned
+  // steps run their second-product stage from the first step on (with zero P / dS until the
+  // pipeline has filled), so the slot it reads must hold finite data
+  {
+    DmaStagerX<D, NW> p1, p2;
+    const int tp = t_lo > 0 ? t_lo - 1 : 0;
+    p1.init(y1b, y1s, N, tp * BC, uwave, lane);
+    p2.init(y2b, y2s, N, tp * BC, uwave, lane);
+    p1.issue(lds0 + ((t_lo + NSLOT - 1) % NSLOT) * SLOT, N, uwave, lane);
+    p2.issue(lds0 + ((t_lo + NSLOT - 1) % NSLOT) * SLOT + TILE, N, uwave, lane);
+  }
   st1.issue(lds0 + (t_lo % NSLOT) * SLOT, N, uwave, lane);
   st2.issue(lds0 + (t_lo % NSLOT) * SLOT + TILE, N, uwave, lane);
   load_stat(t_lo);
@@ -538,6 +568,22 @@ attn_bwd_kernel(const BwdParams p) {
     doS = s - 1 >= c_lo_s && s - 1 <= c_hi_s;
     doB = s - 2 >= c_lo_s && s - 2 <= c_hi_s;
     mask = (s - 1 == c_hi_s) || (CAUSAL && MODE == BWD_DKDV && s - 1 == c_lo_s);
+  };
+  // Outside the steady state the sigmoid passes still run the pinned step, in its masked
+  // form: a stage whose chunk lies outside this wave's range works on whatever finite data
+  // the ring and the registers hold and its P / dS are forced to zero (thr = keep nothing);
+  // the diagonal / ragged chunk gets its per-lane threshold.  Only the ragged last query
+  // chunk of the dK/dV pass (upper and lower bound at once) and the softmax variant take
+  // the compiler-scheduled step.
+  auto step_kind = [&](int s, bool& pin, int& thr) {
+    constexpr int NONE = MODE == BWD_DKDV ? 1000 : -1000, ALL = -NONE;
+    const bool doS = s - 1 >= c_lo_s && s - 1 <= c_hi_s;
+    const int cs = 32 * (s - 1), bl = cs + 8 * h;
+    const bool ragged = doS && s - 1 == c_hi_s && cs + 32 > N;
+    pin = !SOFTMAX && !(MODE == BWD_DKDV && ragged);
+    if (!doS) thr = NONE;
+    else if (MODE == BWD_DKDV) thr = (CAUSAL && s - 1 == c_lo_s) ? ai - bl : ALL;
+    else thr = (s - 1 == c_hi_s) ? ((CAUSAL && ai < N - 1 ? ai : N - 1) - bl) : ALL;
   };
   // A wave issues about one instruction every six cycles whatever the instruction, so the
   // per-tile control flow is kept out of the steady state: tiles whose two steps are both
@@ -570,8 +616,11 @@ attn_bwd_kernel(const BwdParams p) {
         // chunk s-1 sits in tile (s-1)/2
         const SATTN_LDS(float)* stat = statbase + (((s - 1) >> 1) & (NSLOT - 1)) * 128 + ((s - 1) & 1) * 32 + 8 * h;
         // rows of chunk s+1 come from tile t (second half); transposed reads of chunk s-2 from tile t-1 (first half)
-        if (lane_flag(!SOFTMAX && doA_s && doS_s && doB_s && !mask_s))
-          bwd_step_full_pinned<D, MODE, ALIBI, 0, false>(W, 0, W.row0, CHUNK, 32 * (s - 1), st1, st2, 0, uwave);
+        bool pin_s;
+        int thr;
+        step_kind(s, pin_s, thr);
+        if (lane_flag(pin_s))
+          bwd_step_full_pinned<D, MODE, ALIBI, 0, false, true>(W, 0, W.row0, CHUNK, 32 * (s - 1), st1, st2, 0, uwave, thr);
         else
           bwd_step<D, MODE, CAUSAL, ALIBI, SOFTMAX, 0>(W, lane_flag(doA_s), lane_flag(doS_s), lane_flag(doB_s),
                                                        lane_flag(mask_s), 0, W.row0, CHUNK, 32 * (s - 1), N, stat);
@@ -586,29 +635,22 @@ attn_bwd_kernel(const BwdParams p) {
         bool doA_s, doS_s, doB_s, mask_s;
         flags(s, doA_s, doS_s, doB_s, mask_s);
         const SATTN_LDS(float)* stat = statbase + (((s - 1) >> 1) & (NSLOT - 1)) * 128 + ((s - 1) & 1) * 32 + 8 * h;
-        // the pinned step stages tile t+2 without a tail clamp: that tile must lie inside the tensor
-        const bool full_s = !SOFTMAX && doA_s && doS_s && doB_s && !mask_s && (t + 3) * BC <= N;
+        bool pin_s;
+        int thr;
+        step_kind(s, pin_s, thr);
         const bool more = t + 2 <= t_data_hi;
-        const uint32_t dma_lds = lds0 + ((t + 2) % NSLOT) * SLOT;
-        if (!full_s) {
-          // compiler-scheduled step: stage the whole tile up front
-          if (more) {
-            st1.issue(dma_lds, N, uwave, lane);
-            st2.issue(dma_lds + TILE, N, uwave, lane);
-            load_stat(t + 2);
-          }
+        if (more) {  // stage tile t+2 up front (the steady-state loop interleaves it instead)
+          const uint32_t dma_lds = lds0 + ((t + 2) % NSLOT) * SLOT;
+          st1.issue(dma_lds, N, uwave, lane);
+          st2.issue(dma_lds + TILE, N, uwave, lane);
+          load_stat(t + 2);
         }
         // rows of chunk s+1 come from tile t+1 (first half); transposed reads of chunk s-2 from tile t-1 (second half)
-        if (lane_flag(full_s)) {
-          bwd_step_full_pinned<D, MODE, ALIBI, 1, true>(W, CHUNK, W.row1, 0, 32 * (s - 1), st1, st2, dma_lds, uwave);
-        } else {
+        if (lane_flag(pin_s))
+          bwd_step_full_pinned<D, MODE, ALIBI, 1, false, true>(W, CHUNK, W.row1, 0, 32 * (s - 1), st1, st2, 0, uwave, thr);
+        else
           bwd_step<D, MODE, CAUSAL, ALIBI, SOFTMAX, 1>(W, lane_flag(doA_s), lane_flag(doS_s), lane_flag(doB_s),
                                                        lane_flag(mask_s), CHUNK, W.row1, 0, 32 * (s - 1), N, stat);
-        }
-        if (full_s) {  // wave-uniform state: advanced outside the exec-masked branch
-          st1.advance();
-          st2.advance();
-        }
         if (more) store_stat(t + 2);
       }
       rotate(t);
