@@ -129,6 +129,7 @@ struct BwdWave {
   f32x16 acc0[DT];        // DQ: dQ^T ; DKDV: dK^T
   f32x16 acc1[MODE == BWD_DKDV ? DT : 1];  // DKDV: dV^T
   f32x16 s[2], dp[2];     // first products of chunk c in [c&1]
+  f32x16 cinit;           // FOLD: initial value of the S accumulators (register term of causal ALiBi)
   bf16x8 pb[2][2];        // bf16 P of chunk c in [c&1][ks]   (DKDV only)
   bf16x8 dsb[2][2];       // bf16 dS of chunk c in [c&1][ks]
   int ai, h;              // this lane's stationary row, lane half
@@ -154,6 +155,13 @@ template <bool GUARD>
 __device__ __forceinline__ void b_mfma_v0(f32x16& c, const bf16x8& a, const bf16x8& b_agpr) {
   if constexpr (GUARD) asm volatile(SATTN_BWD_MFMA("s_nop 1\n\t", "0") : "=&v"(c) : "v"(a), "a"(b_agpr) : "memory");
   else asm volatile(SATTN_BWD_MFMA("", "0") : "=&v"(c) : "v"(a), "a"(b_agpr) : "memory");
+}
+// First MFMA of an S product whose accumulator starts from `init` instead of zero.  C and D
+// of an MFMA share one register file, so `init` is a VGPR tuple like the result; under
+// register pressure the compiler parks it in AGPRs and copies it back right here, hence the
+// two wait states in front of the MFMA in every variant.
+__device__ __forceinline__ void b_mfma_vinit(f32x16& c, const bf16x8& a, const bf16x8& b_agpr, const f32x16& init) {
+  asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %3" : "=&v"(c) : "v"(a), "a"(b_agpr), "v"(init) : "memory");
 }
 template <bool GUARD>
 __device__ __forceinline__ void b_mfma_a(f32x16& c_agpr, const bf16x8& a, const bf16x8& b) {
@@ -181,8 +189,14 @@ __device__ __forceinline__ void bwd_step(BwdWave<D, MODE>& W, bool doA, bool doS
                                          const SATTN_LDS(float)* stat) {
   constexpr int KD = D / 16, DT = D / 32;
   constexpr uint32_t T2OFF = 64 * D * 2;  // tensor 2's tile follows tensor 1's inside a ring slot
+  // FOLD (sigmoid, causal, ALiBi): every unmasked pair has its key at or before its query, so
+  // slope*(i - j) splits into a per-lane, per-step part added to the bias and a per-register
+  // part that is a constant of the kernel and sits in the S accumulators from the start
+  // (W.cinit, already divided by the logit scale): no ALiBi arithmetic per element.
+  constexpr bool FOLD = !SOFTMAX && CAUSAL && ALIBI;
   if (doA) {
-    b_mfma_v0<true>(W.s[PAR], W.F[0], W.x1[0]);
+    if constexpr (FOLD) b_mfma_vinit(W.s[PAR], W.F[0], W.x1[0], W.cinit);
+    else b_mfma_v0<true>(W.s[PAR], W.F[0], W.x1[0]);
     b_mfma_v0<true>(W.dp[PAR], W.F[1], W.x2[0]);
 #pragma unroll
     for (int kk = 1; kk < KD; ++kk) {
@@ -209,7 +223,8 @@ __device__ __forceinline__ void bwd_step(BwdWave<D, MODE>& W, bool doA, bool doS
       } else {
         // p = 1/(1 + 2^u), dS = (p - p^2) dP
         float w = W.nbias;
-        if (ALIBI) w = __builtin_fmaf(W.sl2, __builtin_fabsf((float)(qrow - krow)), w);
+        if (FOLD) w = __builtin_fmaf(W.sl2, MODE == BWD_DKDV ? (float)(bl - W.ai) : (float)(W.ai - bl), w);
+        else if (ALIBI) w = __builtin_fmaf(W.sl2, __builtin_fabsf((float)(qrow - krow)), w);
         const float e = __builtin_amdgcn_exp2f(__builtin_fmaf(W.s[PAR ^ 1][r], W.nscale, w));
         pr[r] = __builtin_amdgcn_rcpf(1.0f + e);
         ds[r] = __builtin_fmaf(-pr[r], pr[r], pr[r]) * W.dp[PAR ^ 1][r];
@@ -319,7 +334,7 @@ __device__ __forceinline__ void bsig_ops(const BwdWave<D, MODE>& W, const f32x16
   }
 }
 
-template <int D, int MODE, bool ALIBI, int PAR, bool DMA, bool MASK, int K>
+template <int D, int MODE, bool ALIBI, int PAR, bool DMA, bool MASK, bool FOLD, int K>
 __device__ __forceinline__ void bwd_full_subslots(BwdWave<D, MODE>& W, uint32_t trimm, const uint32_t* nextrow,
                                                   uint32_t nextimm, float (&u)[16], float (&v)[16], uint32_t (&wp)[8],
                                                   uint32_t (&wd)[8], uint64_t (&km)[16], float nbias_v, float sl2_v,
@@ -336,7 +351,8 @@ __device__ __forceinline__ void bwd_full_subslots(BwdWave<D, MODE>& W, uint32_t 
       constexpr int kk = K / 2;
       if constexpr ((K & 1) == 0) {
         // S-type product from tensor 1, then fetch the transposed tensor-1 fragment kk
-        if constexpr (kk == 0) b_mfma_v0<false>(W.s[PAR], W.F[K], W.x1[kk]);
+        if constexpr (kk == 0 && FOLD) b_mfma_vinit(W.s[PAR], W.F[K], W.x1[kk], W.cinit);
+        else if constexpr (kk == 0) b_mfma_v0<false>(W.s[PAR], W.F[K], W.x1[kk]);
         else b_mfma_v<false>(W.s[PAR], W.F[K], W.x1[kk]);
         const uint32_t off = trimm + (kk / DT) * 16 * (D * 2);
         W.F[K] = join_tr(lds_read_tr16(W.tr[kk % DT][0] + off), lds_read_tr16(W.tr[kk % DT][1] + off));
@@ -380,13 +396,13 @@ __device__ __forceinline__ void bwd_full_subslots(BwdWave<D, MODE>& W, uint32_t 
         else st2.template issue_one<n - NI>(dma_lds + 64 * D * 2, uwave);
       }
     }
-    bwd_full_subslots<D, MODE, ALIBI, PAR, DMA, MASK, K + 1>(W, trimm, nextrow, nextimm, u, v, wp, wd, km, nbias_v, sl2_v,
+    bwd_full_subslots<D, MODE, ALIBI, PAR, DMA, MASK, FOLD, K + 1>(W, trimm, nextrow, nextimm, u, v, wp, wd, km, nbias_v, sl2_v,
                                                              dist0, dstep, thr, st1, st2, dma_lds, uwave);
   }
 }
 
 // thr (MASK only): elements with key_of_reg(e) >= thr (DKDV) / <= thr (DQ) are kept.
-template <int D, int MODE, bool ALIBI, int PAR, bool DMA, bool MASK = false>
+template <int D, int MODE, bool ALIBI, bool FOLD, int PAR, bool DMA, bool MASK = false>
 __device__ __forceinline__ void bwd_step_full_pinned(BwdWave<D, MODE>& W, uint32_t trimm, const uint32_t* nextrow,
                                                      uint32_t nextimm, int cs, const DmaStagerX<D, 4>& st1,
                                                      const DmaStagerX<D, 4>& st2, uint32_t dma_lds, int uwave,
@@ -398,8 +414,13 @@ __device__ __forceinline__ void bwd_step_full_pinned(BwdWave<D, MODE>& W, uint32
   const int bl = cs + 8 * W.h;
   const float dist0 = MODE == BWD_DKDV ? (float)(bl - W.ai) : (float)(W.ai - bl);
   const float dstep = MODE == BWD_DKDV ? 1.0f : -1.0f;
-  bwd_full_subslots<D, MODE, ALIBI, PAR, DMA, MASK, 0>(W, trimm, nextrow, nextimm, u, v, wp, wd, km, W.nbias, W.sl2,
-                                                       dist0, dstep, thr, st1, st2, dma_lds, uwave);
+  if constexpr (FOLD)  // the per-element arithmetic is the one without ALiBi, on a per-step bias
+    bwd_full_subslots<D, MODE, false, PAR, DMA, MASK, true, 0>(W, trimm, nextrow, nextimm, u, v, wp, wd, km,
+                                                               __builtin_fmaf(W.sl2, dist0, W.nbias), W.sl2, dist0, dstep,
+                                                               thr, st1, st2, dma_lds, uwave);
+  else
+    bwd_full_subslots<D, MODE, ALIBI, PAR, DMA, MASK, false, 0>(W, trimm, nextrow, nextimm, u, v, wp, wd, km, W.nbias, W.sl2,
+                                                                dist0, dstep, thr, st1, st2, dma_lds, uwave);
   // The compiler does not know that the asm statements above are MFMAs: let the last ones
   // retire before it may touch their accumulators (copies at the join with the other path).
   mfma_settle();
@@ -415,6 +436,7 @@ template <int D, int MODE, bool CAUSAL, bool ALIBI, bool SOFTMAX>
 __global__ void __launch_bounds__(256, 1)
 attn_bwd_kernel(const BwdParams p) {
   constexpr int NW = 4, BS = 32 * NW, BC = 64, KD = D / 16, DT = D / 32;
+  constexpr bool FOLD = !SOFTMAX && CAUSAL && ALIBI;  // see bwd_step
   constexpr int TILE = BC * D * 2, SLOT = 2 * TILE, CHUNK = 32 * D * 2, NSLOT = 4;
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   const uint32_t lds0 = (uint32_t)(uintptr_t)(SATTN_LDS(char)*)smem;
@@ -460,6 +482,9 @@ attn_bwd_kernel(const BwdParams p) {
   W.ai = ai; W.h = h;
   W.nscale = p.nscale_log2; W.nbias = p.nbias_log2;
   W.sl2 = ALIBI ? p.slopes[hd] * kLog2e : 0.f;
+#pragma unroll
+  for (int r = 0; r < 16; ++r)  // DKDV: |i-j| = (bl - ai) + key_of_reg(r); DQ: (ai - bl) - key_of_reg(r)
+    W.cinit[r] = FOLD ? (MODE == BWD_DKDV ? W.sl2 : -W.sl2) * (float)key_of_reg(r) / p.nscale_log2 : 0.f;
   W.nlse = 0.f; W.dstat = 0.f;
   if (SOFTMAX && MODE == BWD_DQ) {
     W.nlse = -p.lse[(int64_t)bh * N + ai_ld] * kLog2e;
@@ -620,7 +645,7 @@ attn_bwd_kernel(const BwdParams p) {
         int thr;
         step_kind(s, pin_s, thr);
         if (lane_flag(pin_s))
-          bwd_step_full_pinned<D, MODE, ALIBI, 0, false, true>(W, 0, W.row0, CHUNK, 32 * (s - 1), st1, st2, 0, uwave, thr);
+          bwd_step_full_pinned<D, MODE, ALIBI, FOLD, 0, false, true>(W, 0, W.row0, CHUNK, 32 * (s - 1), st1, st2, 0, uwave, thr);
         else
           bwd_step<D, MODE, CAUSAL, ALIBI, SOFTMAX, 0>(W, lane_flag(doA_s), lane_flag(doS_s), lane_flag(doB_s),
                                                        lane_flag(mask_s), 0, W.row0, CHUNK, 32 * (s - 1), N, stat);
@@ -647,7 +672,7 @@ attn_bwd_kernel(const BwdParams p) {
         }
         // rows of chunk s+1 come from tile t+1 (first half); transposed reads of chunk s-2 from tile t-1 (second half)
         if (lane_flag(pin_s))
-          bwd_step_full_pinned<D, MODE, ALIBI, 1, false, true>(W, CHUNK, W.row1, 0, 32 * (s - 1), st1, st2, 0, uwave, thr);
+          bwd_step_full_pinned<D, MODE, ALIBI, FOLD, 1, false, true>(W, CHUNK, W.row1, 0, 32 * (s - 1), st1, st2, 0, uwave, thr);
         else
           bwd_step<D, MODE, CAUSAL, ALIBI, SOFTMAX, 1>(W, lane_flag(doA_s), lane_flag(doS_s), lane_flag(doB_s),
                                                        lane_flag(mask_s), CHUNK, W.row1, 0, 32 * (s - 1), N, stat);
@@ -657,10 +682,10 @@ attn_bwd_kernel(const BwdParams p) {
     }
     if (phase == 0) {
       for (; t <= t_s1; ++t) {
-        bwd_step_full_pinned<D, MODE, ALIBI, 0, false>(W, 0, W.row0, CHUNK, 32 * (2 * t - 1), st1, st2, 0, uwave);
+        bwd_step_full_pinned<D, MODE, ALIBI, FOLD, 0, false>(W, 0, W.row0, CHUNK, 32 * (2 * t - 1), st1, st2, 0, uwave);
         __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): tile t+1 has landed
         __builtin_amdgcn_s_barrier();
-        bwd_step_full_pinned<D, MODE, ALIBI, 1, true>(W, CHUNK, W.row1, 0, 32 * (2 * t), st1, st2,
+        bwd_step_full_pinned<D, MODE, ALIBI, FOLD, 1, true>(W, CHUNK, W.row1, 0, 32 * (2 * t), st1, st2,
                                                       lds0 + ((t + 2) % NSLOT) * SLOT, uwave);
         st1.advance();
         st2.advance();

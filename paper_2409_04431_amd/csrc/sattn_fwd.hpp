@@ -53,33 +53,48 @@ struct DmaStager {
   static constexpr int RPI = 64 / CPR;            // rows filled by one instruction
   static constexpr int NI = (BC * CPR) / (64 * NW);  // instructions per wave per tile
   static_assert((BC * CPR) % (64 * NW) == 0, "tile must split evenly over the waves");
-  const char* ptr[NI];   // this lane's source for the next tile to stage (unclamped)
-  const char* last[NI];  // this lane's source inside the last row N-1
-  int row[NI];           // tile-relative row this lane fills
-  int64_t tile_bytes;    // BC * seq stride in bytes
-
-  __device__ __forceinline__ void init(const __bf16* base, int64_t ss, int N, int wave, int lane) {
-#pragma unroll
-    for (int n = 0; n < NI; ++n) {
-      const int r = (wave * NI + n) * RPI + lane / CPR, pc = lane % CPR;
-      const int c = pc ^ (IS_V ? Swz<D>::v(r) : Swz<D>::k(r));
-      row[n] = r;
-      ptr[n] = (const char*)(base + (int64_t)r * ss + c * 8);
-      last[n] = (const char*)(base + (int64_t)(N - 1) * ss + c * 8);
-    }
-    tile_bytes = (int64_t)BC * ss * 2;
+  const char* base;       // first row of the next tile to stage (wave-uniform, advances per tile)
+  const char* base_last;  // row N-1 (wave-uniform)
+  uint32_t off[NI];       // this lane's byte offset inside a tile (constant)
+  uint32_t tile_bytes, row_bytes;
+  int j0;                 // first key of the next tile to stage
+  __device__ __forceinline__ static int row_of(int n, int wave, int lane) { return (wave * NI + n) * RPI + lane / CPR; }
+  __device__ __forceinline__ static uint32_t col_bytes(int n, int wave, int lane) {
+    const int r = row_of(n, wave, lane);
+    return (uint32_t)(((lane % CPR) ^ (IS_V ? Swz<D>::v(r) : Swz<D>::k(r))) * 16);
   }
-  // Issue the loads of the tile starting at key j0 into the LDS tile at byte address `lds`
-  // (wave-uniform) and advance to the next tile.  Rows past the end re-read row N-1.
-  __device__ __forceinline__ void issue(uint32_t lds, int j0, int N, int wave) {
+  // The host side guarantees that one (batch, head) slice spans < 4 GiB.
+  __device__ __forceinline__ void init(const __bf16* b, int64_t ss, int N, int wave, int lane) {
+    base = (const char*)b;
+    base_last = (const char*)(b + (int64_t)(N - 1) * ss);
+    row_bytes = (uint32_t)(ss * 2);
+    tile_bytes = BC * row_bytes;
+    j0 = 0;
 #pragma unroll
-    for (int n = 0; n < NI; ++n) {
-      const char* src = ptr[n];
-      if (j0 + BC > N) src = (j0 + row[n] < N) ? src : last[n];
-      const uint32_t m0v = lds + (wave * NI + n) * 1024;
-      asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(src), "s"(m0v) : "memory");
-      ptr[n] += tile_bytes;
+    for (int n = 0; n < NI; ++n) off[n] = row_of(n, wave, lane) * row_bytes + col_bytes(n, wave, lane);
+  }
+  __device__ __forceinline__ static void load(uint32_t o, const char* sbase, uint32_t m0v) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(o), "s"(sbase), "s"(m0v) : "memory");
+  }
+  // Issue the loads of the next tile into the LDS tile at byte address `lds` (wave-uniform)
+  // and advance.  Rows past the end re-read row N-1.
+  __device__ __forceinline__ void issue(uint32_t lds, int N, int wave, int lane) {
+    if (j0 + BC <= N) {
+#pragma unroll
+      for (int n = 0; n < NI; ++n) load(off[n], base, lds + (wave * NI + n) * 1024);
+    } else if (j0 < N) {
+      const uint32_t to_last = (uint32_t)(N - 1 - j0) * row_bytes;
+#pragma unroll
+      for (int n = 0; n < NI; ++n) {
+        const uint32_t o = (j0 + row_of(n, wave, lane) < N) ? off[n] : to_last + col_bytes(n, wave, lane);
+        load(o, base, lds + (wave * NI + n) * 1024);
+      }
+    } else {
+#pragma unroll
+      for (int n = 0; n < NI; ++n) load(col_bytes(n, wave, lane), base_last, lds + (wave * NI + n) * 1024);
     }
+    base += tile_bytes;
+    j0 += BC;
   }
 };
 
@@ -103,6 +118,7 @@ struct FwdWave {
   bf16x8 vf[2 * DT];   // V fragments of the chunk whose P^T is consumed next
   f32x16 oacc[DT];     // O^T accumulator
   f32x16 s[2];         // S^T of chunk c in s[c&1]
+  f32x16 cinit;        // FOLD: initial value of every S^T accumulator (the key term of causal ALiBi)
   bf16x8 p[2][2];      // bf16 P^T of chunk c in p[c&1][ks]
   SoftmaxState sm;
   int qi, h;
@@ -116,7 +132,13 @@ enum StepKind { STEP_FULL = 0, STEP_LAST = 1, STEP_TAIL = 2 };
 //   LAST: the wave's last chunk (diagonal / ragged end): no S^T; masked sigmoid(c); O^T update; refill vf
 //   TAIL: only the O^T update with P^T(c-1)
 // kaddr: byte offset (compile-time) of K chunk c+2 inside LDS; vaddr: of V chunk c.
-template <int D, bool ALIBI, bool SOFTMAX, int KIND, int PAR>
+//
+// FOLD (sigmoid, causal, ALiBi): every unmasked key lies at or before its query, so the
+// ALiBi term slope*(i - j) splits into a per-lane, per-step part slope*(i - jc - 8h), added
+// to the bias with one fma per step, and a per-register part -slope*key_of_reg(r), which is
+// a constant of the kernel and goes into the accumulators as the initial value of S^T
+// (divided by the logit scale).  The sigmoid then costs what it costs without ALiBi.
+template <int D, bool ALIBI, bool SOFTMAX, int KIND, int PAR, bool FOLD = false>
 __device__ __forceinline__ void fwd_step(FwdWave<D>& W, uint32_t kaddr, uint32_t vaddr, int jc, int N, bool causal) {
   constexpr int KD = D / 16, DT = D / 32;
   constexpr int NM = KD;  // == 2*DT
@@ -157,13 +179,14 @@ __device__ __forceinline__ void fwd_step(FwdWave<D>& W, uint32_t kaddr, uint32_t
   }
   float dist0 = 0.f;
   if (SIG && !SOFTMAX && ALIBI) dist0 = (float)(W.qi - jl);
+  const float wfold = FOLD ? __builtin_fmaf(W.sl2, dist0, W.nbias) : W.nbias;
   int lim = N - 1 - jl;  // STEP_LAST: registers whose key offset exceeds lim are masked
   if (causal) lim = lim < W.qi - jl ? lim : W.qi - jl;
   u32x4 pw = {0, 0, 0, 0};
 
   if (QK) {
 #pragma unroll
-    for (int r = 0; r < 16; ++r) s_nxt[r] = 0.f;
+    for (int r = 0; r < 16; ++r) s_nxt[r] = FOLD ? W.cinit[r] : 0.f;
   }
 #pragma unroll
   for (int m = 0; m < NM; ++m) {
@@ -176,8 +199,8 @@ __device__ __forceinline__ void fwd_step(FwdWave<D>& W, uint32_t kaddr, uint32_t
       // p = 1 / (1 + 2^u), u = -(s/sqrt(d) + b - slope|i-j|) log2(e)
 #pragma unroll
       for (int r = EPS * m; r < EPS * m + EPS; ++r) {
-        float w = W.nbias;
-        if (ALIBI) w = __builtin_fmaf(W.sl2, __builtin_fabsf(dist0 - (float)key_of_reg(r)), W.nbias);
+        float w = wfold;
+        if (ALIBI && !FOLD) w = __builtin_fmaf(W.sl2, __builtin_fabsf(dist0 - (float)key_of_reg(r)), W.nbias);
         pr[r] = __builtin_amdgcn_exp2f(__builtin_fmaf(s_cur[r], W.nscale, w));
       }
     }
@@ -241,6 +264,10 @@ __device__ __forceinline__ void a_mfma_zero(f32x16& c, const bf16x8& a, const bf
   asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(c) : "v"(a), "v"(b) : "memory");
 }
 
+__device__ __forceinline__ void a_mfma_init(f32x16& c, const bf16x8& a, const bf16x8& b, const f32x16& init) {
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %3" : "=&v"(c) : "v"(a), "v"(b), "v"(init) : "memory");
+}
+
 // Sigmoid of the 16 accumulator registers as 4 groups x 18 operations.  Inside a group of
 // four elements the order is F F F F  X X X X  A A A A  R R R R  C C (scale+bias fma, exp2,
 // 1+e, reciprocal, bf16 pack), so a result is consumed four instructions after it was issued.
@@ -278,14 +305,15 @@ __device__ __forceinline__ void sig_ops(const FwdWave<D>& W, const f32x16& s, fl
   }
 }
 
-template <int D, bool ALIBI, int PAR, int K>
+template <int D, bool ALIBI, int PAR, bool FOLD, int K>
 __device__ __forceinline__ void full_subslots(FwdWave<D>& W, uint32_t kaddr, uint32_t vaddr, float (&u)[16],
                                               uint32_t (&wp)[8], float nbias_v, float sl2_v, float dist0) {
   constexpr int KD = D / 16, DT = D / 32, NSUB = 2 * KD, NOPS = 72;
   if constexpr (K < NSUB) {
     constexpr int m = K / 2;
     if constexpr ((K & 1) == 0) {
-      if constexpr (m == 0) a_mfma_zero(W.s[PAR ^ 1], W.kf[m], W.qf[m]);
+      if constexpr (m == 0 && FOLD) a_mfma_init(W.s[PAR ^ 1], W.kf[m], W.qf[m], W.cinit);
+      else if constexpr (m == 0) a_mfma_zero(W.s[PAR ^ 1], W.kf[m], W.qf[m]);
       else a_mfma(W.s[PAR ^ 1], W.kf[m], W.qf[m]);
       W.kf[m] = as_bf16x8(lds_read_b128(W.koff[m] + kaddr));
     } else {
@@ -294,30 +322,33 @@ __device__ __forceinline__ void full_subslots(FwdWave<D>& W, uint32_t kaddr, uin
       W.vf[m] = join_tr(lds_read_tr16(a0), lds_read_tr16(a0 + 4 * (D * 2)));
     }
     sig_ops<D, ALIBI, (K * NOPS) / NSUB, ((K + 1) * NOPS) / NSUB>(W, W.s[PAR], u, wp, nbias_v, sl2_v, dist0);
-    full_subslots<D, ALIBI, PAR, K + 1>(W, kaddr, vaddr, u, wp, nbias_v, sl2_v, dist0);
+    full_subslots<D, ALIBI, PAR, FOLD, K + 1>(W, kaddr, vaddr, u, wp, nbias_v, sl2_v, dist0);
   }
 }
 
-template <int D, bool ALIBI, int PAR>
+template <int D, bool ALIBI, int PAR, bool FOLD>
 __device__ __forceinline__ void fwd_step_full_pinned(FwdWave<D>& W, uint32_t kaddr, uint32_t vaddr, int jc) {
   float u[16];
   uint32_t wp[8];
   const float dist0 = (float)(W.qi - (jc + 8 * W.h));
-  full_subslots<D, ALIBI, PAR, 0>(W, kaddr, vaddr, u, wp, W.nbias, W.sl2, dist0);
+  if constexpr (FOLD)  // the per-element arithmetic is the one without ALiBi, on a per-step bias
+    full_subslots<D, false, PAR, true, 0>(W, kaddr, vaddr, u, wp, __builtin_fmaf(W.sl2, dist0, W.nbias), W.sl2, dist0);
+  else
+    full_subslots<D, ALIBI, PAR, false, 0>(W, kaddr, vaddr, u, wp, W.nbias, W.sl2, dist0);
   W.p[PAR][0] = as_bf16x8(u32x4{wp[0], wp[1], wp[2], wp[3]});
   W.p[PAR][1] = as_bf16x8(u32x4{wp[4], wp[5], wp[6], wp[7]});
 }
 
 // Dispatch one step of chunk c for a wave that owns chunks 0..cw-1.
-template <int D, bool ALIBI, bool SOFTMAX, int PAR>
+template <int D, bool ALIBI, bool SOFTMAX, int PAR, bool FOLD>
 __device__ __forceinline__ void fwd_step_any(FwdWave<D>& W, int c, int cw, uint32_t kaddr, uint32_t vaddr, int N,
                                              bool causal) {
   if (c + 1 < cw) {
     if constexpr (SOFTMAX) fwd_step<D, ALIBI, SOFTMAX, STEP_FULL, PAR>(W, kaddr, vaddr, 32 * c, N, causal);
-    else fwd_step_full_pinned<D, ALIBI, PAR>(W, kaddr, vaddr, 32 * c);
+    else fwd_step_full_pinned<D, ALIBI, PAR, FOLD>(W, kaddr, vaddr, 32 * c);
   }
-  else if (c + 1 == cw) fwd_step<D, ALIBI, SOFTMAX, STEP_LAST, PAR>(W, kaddr, vaddr, 32 * c, N, causal);
-  else if (c == cw) fwd_step<D, ALIBI, SOFTMAX, STEP_TAIL, PAR>(W, kaddr, vaddr, 32 * c, N, causal);
+  else if (c + 1 == cw) fwd_step<D, ALIBI, SOFTMAX, STEP_LAST, PAR, FOLD>(W, kaddr, vaddr, 32 * c, N, causal);
+  else if (c == cw) fwd_step<D, ALIBI, SOFTMAX, STEP_TAIL, PAR, FOLD>(W, kaddr, vaddr, 32 * c, N, causal);
 }
 
 template <int D, int NW, bool CAUSAL, bool ALIBI, bool SOFTMAX>
@@ -325,6 +356,7 @@ __global__ void __launch_bounds__(64 * NW, 8 / NW)
 attn_fwd_kernel(const FwdParams p) {
   constexpr int BR = 32 * NW, BC = 64;
   constexpr int KD = D / 16, DT = D / 32;
+  constexpr bool FOLD = !SOFTMAX && CAUSAL && ALIBI;  // see fwd_step
   constexpr int TILE = BC * D * 2;    // bytes of one K or V tile
   constexpr int CHUNK = 32 * D * 2;   // bytes of a 32-key chunk
 
@@ -378,7 +410,11 @@ attn_fwd_kernel(const FwdParams p) {
     W.sl2 = ALIBI ? p.slopes[hd] * kLog2e : 0.f;
     W.sm = SoftmaxState{-__builtin_inff(), 0.f};
 #pragma unroll
-    for (int r = 0; r < 16; ++r) { W.s[0][r] = 0.f; W.s[1][r] = 0.f; }
+    for (int r = 0; r < 16; ++r) {
+      W.cinit[r] = FOLD ? -W.sl2 * (float)key_of_reg(r) / W.nscale : 0.f;
+      W.s[0][r] = W.cinit[r];  // step -1 accumulates S^T(0) on top of it
+      W.s[1][r] = 0.f;
+    }
     const bf16x8 z = as_bf16x8(u32x4{0, 0, 0, 0});
     W.p[0][0] = W.p[0][1] = W.p[1][0] = W.p[1][1] = z;
 #pragma unroll
@@ -403,10 +439,10 @@ attn_fwd_kernel(const FwdParams p) {
   const int uwave = __builtin_amdgcn_readfirstlane(wave);
   kst.init(kbase, p.k.ss, N, uwave, lane);
   vst.init(vbase, p.v.ss, N, uwave, lane);
-  kst.issue(kring, 0, N, uwave);
-  vst.issue(vring, 0, N, uwave);
-  if (n_tiles > 1) { kst.issue(kring + TILE, BC, N, uwave); vst.issue(vring + TILE, BC, N, uwave); }
-  if (n_tiles > 2) kst.issue(kring + 2 * TILE, 2 * BC, N, uwave);
+  kst.issue(kring, N, uwave, lane);
+  vst.issue(vring, N, uwave, lane);
+  if (n_tiles > 1) { kst.issue(kring + TILE, N, uwave, lane); vst.issue(vring + TILE, N, uwave, lane); }
+  if (n_tiles > 2) kst.issue(kring + 2 * TILE, N, uwave, lane);
   SATTN_WAIT_VMCNT(0);  // prologue tiles landed; the Q fragment is in registers
   __syncthreads();
 
@@ -429,10 +465,10 @@ attn_fwd_kernel(const FwdParams p) {
   for (int t = 0; t < n_tiles; ++t) {
     const bool k_more = t + 3 < n_tiles, v_more = t + 2 < n_tiles;
     const int vslot2 = kslot == 0 ? 2 : kslot - 1;  // (t+2)%3
-    if (k_more) kst.issue(kring + kslot * TILE, (t + 3) * BC, N, uwave);
-    if (v_more) vst.issue(vring + vslot2 * TILE, (t + 2) * BC, N, uwave);
-    fwd_step_any<D, ALIBI, SOFTMAX, 0>(W, 2 * t, cw, 0, 0, N, CAUSAL);
-    fwd_step_any<D, ALIBI, SOFTMAX, 1>(W, 2 * t + 1, cw, CHUNK, CHUNK, N, CAUSAL);
+    if (k_more) kst.issue(kring + kslot * TILE, N, uwave, lane);
+    if (v_more) vst.issue(vring + vslot2 * TILE, N, uwave, lane);
+    fwd_step_any<D, ALIBI, SOFTMAX, 0, FOLD>(W, 2 * t, cw, 0, 0, N, CAUSAL);
+    fwd_step_any<D, ALIBI, SOFTMAX, 1, FOLD>(W, 2 * t + 1, cw, CHUNK, CHUNK, N, CAUSAL);
     // advance the read addresses by one ring slot: K reads are at slot (t+1)%3, V reads at t%3
     const int kadv = kslot == 1 ? -2 * TILE : TILE;  // slot (t+1)%3 == 2 wraps to 0
     const int vadv = kslot == 2 ? -2 * TILE : TILE;
@@ -448,7 +484,7 @@ attn_fwd_kernel(const FwdParams p) {
     __syncthreads();
   }
   // flush: O^T update of the last chunk when it fell on the last step of the loop
-  if (cw == 2 * n_tiles && cw > 0) fwd_step<D, ALIBI, SOFTMAX, STEP_TAIL, 0>(W, 0, 0, 0, N, CAUSAL);
+  if (cw == 2 * n_tiles && cw > 0) fwd_step<D, ALIBI, SOFTMAX, STEP_TAIL, 0, FOLD>(W, 0, 0, 0, N, CAUSAL);
 
   if (SOFTMAX) {
     // normalise by the row sum (both lane halves) and write the natural-log row log-sum-exp
