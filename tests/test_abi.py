@@ -59,6 +59,10 @@ def test_bad_arguments_are_rejected_without_launch(lib):
     assert _fwd(lib, strides=(1024, 1024, 60)) == -4    # seq stride < d
     assert _fwd(lib, strides=(1027, 1024, 64)) == -4    # rows not 16-byte aligned
     assert _fwd(lib, N=(1 << 24) + 1) == -2
+    # one (batch, head) slice must span < 4 GiB: its rows are addressed with 32-bit byte offsets
+    assert _fwd(lib, N=1 << 20, d=64, strides=(1 << 40, 1 << 40, 4096)) == -2
+    assert lib.sattn_mfma_bf16_probe(0, 10, ctypes.c_void_p(0x1000), None) == -2
+    assert lib.sattn_mfma_bf16_probe(4, 10, None, None) == -1
 
 
 def test_backward_rejects_bad_arguments(lib):

@@ -319,3 +319,17 @@ def test_full_size_additivity_over_key_halves():
     torch.cuda.synchronize()
     ref = o.float().cpu().numpy().astype(np.float64)
     assert nerr((o1.float() + o2.float()), ref) <= TOL_BF16
+
+
+def test_matrix_rate_probe_runs_and_reports_a_plausible_rate():
+    sink = torch.zeros(64 * 256, dtype=torch.float32, device="cuda")
+    sa.sattn_mfma_bf16_probe(64, 100, sink)          # warm-up
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    flops = sa.sattn_mfma_bf16_probe(64, 4000, sink)
+    e1.record()
+    torch.cuda.synchronize()
+    assert flops == 64 * 4 * 4000 * 8 * 32768
+    assert torch.isfinite(sink).all()
+    per_cu = flops / (e0.elapsed_time(e1) * 1e-3) / 64 / 1e12   # TFLOP/s per compute unit
+    assert 2.0 < per_cu < 2.5e3 / 256 * 1.05                    # below the nominal 9.8 TFLOP/s per CU
