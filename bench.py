@@ -183,6 +183,23 @@ def main():
         sm_ms = e[0].elapsed_time(e[1]) / args.steps
         out["softmax_fwd_ms"] = sm_ms
         out["softmax_fwd_tflops"] = flops_f / sm_ms / 1e9
+
+        def timed(fn):
+            for _ in range(args.warmup):
+                fn()
+            ev = _events(2)
+            ev[0].record()
+            for _ in range(args.steps):
+                fn()
+            ev[1].record()
+            torch.cuda.synchronize()
+            return ev[0].elapsed_time(ev[1]) / args.steps
+        # the sigmoid kernels with the same compiler-scheduled step the softmax kernels use
+        out["sigmoid_fwd_compiler_scheduled_ms"] = timed(
+            lambda: sa.sigmoid_attn_fwd_compiler_scheduled(q, k, v, o, bias, cfg.causal, slopes))
+        if cfg.backward:
+            out["sigmoid_bwd_compiler_scheduled_ms"] = timed(
+                lambda: sa.sigmoid_attn_bwd_compiler_scheduled(q, k, v, dout, dq, dk, dv, bias, cfg.causal, slopes))
         if cfg.backward:
             for _ in range(args.warmup):
                 sa.softmax_attn_bwd(q, k, v, o, lse, dout, dq, dk, dv, cfg.causal, slopes)

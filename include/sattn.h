@@ -140,6 +140,27 @@ size_t softmax_attn_bwd_workspace_bytes(int B, int H, int N, int d, sattn_dtype 
 /* Human-readable text for an SATTN_ERR_* code (static storage). */
 const char* sattn_strerror(int code);
 
+/* Comparison aids (Section 4.1 / Appendix F.2 compare the sigmoid kernels with softmax kernels
+ * built the same way).  Same arguments, results and error behaviour as sigmoid_attn_fwd /
+ * sigmoid_attn_bwd; the kernels run every pipeline step in the compiler-scheduled form that
+ * the softmax comparison kernels use, instead of the hand-pinned instruction stream.  They
+ * exist so that sigmoid and softmax can be timed like for like; not meant for production. */
+int sigmoid_attn_fwd_compiler_scheduled(const void* q, const void* k, const void* v, void* o,
+                                        int B, int H, int N, int d, sattn_dtype dtype,
+                                        float bias, int causal, const float* alibi_slopes,
+                                        const sattn_strides* sq, const sattn_strides* sk,
+                                        const sattn_strides* sv, const sattn_strides* so,
+                                        void* stream);
+int sigmoid_attn_bwd_compiler_scheduled(const void* q, const void* k, const void* v, const void* dout,
+                                        void* dq, void* dk, void* dv,
+                                        int B, int H, int N, int d, sattn_dtype dtype,
+                                        float bias, int causal, const float* alibi_slopes,
+                                        const sattn_strides* sq, const sattn_strides* sk,
+                                        const sattn_strides* sv, const sattn_strides* sdout,
+                                        const sattn_strides* sdq, const sattn_strides* sdk,
+                                        const sattn_strides* sdv,
+                                        void* workspace, size_t workspace_bytes, void* stream);
+
 /* Measurement aid (Section 4.1 quotes kernel speed against the matrix-unit peak): launches
  * `blocks` workgroups of 4 waves that each issue iters*8 independent register-resident
  * 32x32x16 bf16 MFMAs (32768 flop each) and nothing else, asynchronously on `stream`.  The

@@ -9,10 +9,12 @@ from .binding import (  # noqa: F401
     library_path,
     load_library,
     sigmoid_attn_bwd,
+    sigmoid_attn_bwd_compiler_scheduled,
     sigmoid_attn_bwd_dkdv,
     sigmoid_attn_bwd_dq,
     sigmoid_attn_bwd_workspace_bytes,
     sigmoid_attn_fwd,
+    sigmoid_attn_fwd_compiler_scheduled,
     softmax_attn_bwd,
     softmax_attn_bwd_workspace_bytes,
     softmax_attn_fwd,

@@ -46,6 +46,10 @@ def load_library():
     lib.sigmoid_attn_fwd.restype = i
     lib.sigmoid_attn_bwd.argtypes = [_vp] * 7 + [i, i, i, i, i, f, i, _vp] + [_SP] * 7 + [_vp, sz, _vp]
     lib.sigmoid_attn_bwd.restype = i
+    lib.sigmoid_attn_fwd_compiler_scheduled.argtypes = lib.sigmoid_attn_fwd.argtypes
+    lib.sigmoid_attn_fwd_compiler_scheduled.restype = i
+    lib.sigmoid_attn_bwd_compiler_scheduled.argtypes = lib.sigmoid_attn_bwd.argtypes
+    lib.sigmoid_attn_bwd_compiler_scheduled.restype = i
     lib.sigmoid_attn_bwd_dkdv.argtypes = [_vp] * 6 + [i, i, i, i, i, f, i, _vp] + [_SP] * 6 + [_vp]
     lib.sigmoid_attn_bwd_dkdv.restype = i
     lib.sigmoid_attn_bwd_dq.argtypes = [_vp] * 5 + [i, i, i, i, i, f, i, _vp] + [_SP] * 5 + [_vp]
@@ -125,16 +129,21 @@ def _raise(rc, what):
         raise SattnError(f"{what} failed: {sattn_strerror(rc)} ({rc})")
 
 
-def sigmoid_attn_fwd(q, k, v, o, bias, causal=False, alibi_slopes=None):
+def sigmoid_attn_fwd(q, k, v, o, bias, causal=False, alibi_slopes=None, _entry="sigmoid_attn_fwd"):
     """O = sigmoid(Q K^T/sqrt(d) + bias [- slope|i-j|], causal mask) V, written into `o`."""
     lib = load_library()
     _check(q, k, v, o)
     B, H, N, d = q.shape
-    rc = lib.sigmoid_attn_fwd(q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(), B, H, N, d, _dtype_code(q),
+    rc = getattr(lib, _entry)(q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(), B, H, N, d, _dtype_code(q),
                               float(bias), int(bool(causal)), _slopes_ptr(alibi_slopes, H),
                               _st(q), _st(k), _st(v), _st(o), _stream())
-    _raise(rc, "sigmoid_attn_fwd")
+    _raise(rc, _entry)
     return o
+
+
+def sigmoid_attn_fwd_compiler_scheduled(q, k, v, o, bias, causal=False, alibi_slopes=None):
+    """Same result as sigmoid_attn_fwd from the compiler-scheduled pipeline step (comparison aid)."""
+    return sigmoid_attn_fwd(q, k, v, o, bias, causal, alibi_slopes, _entry="sigmoid_attn_fwd_compiler_scheduled")
 
 
 def sigmoid_attn_bwd_workspace_bytes(B, H, N, d, dtype=torch.bfloat16):
@@ -142,7 +151,8 @@ def sigmoid_attn_bwd_workspace_bytes(B, H, N, d, dtype=torch.bfloat16):
     return int(load_library().sigmoid_attn_bwd_workspace_bytes(B, H, N, d, code))
 
 
-def sigmoid_attn_bwd(q, k, v, dout, dq, dk, dv, bias, causal=False, alibi_slopes=None, workspace=None):
+def sigmoid_attn_bwd(q, k, v, dout, dq, dk, dv, bias, causal=False, alibi_slopes=None, workspace=None,
+                     _entry="sigmoid_attn_bwd"):
     """dQ, dK, dV of sigmoid attention from Q, K, V, dO (P is recomputed), written in place."""
     lib = load_library()
     _check(q, k, v, dout, dq, dk, dv)
@@ -152,12 +162,18 @@ def sigmoid_attn_bwd(q, k, v, dout, dq, dk, dv, bias, causal=False, alibi_slopes
         workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
     wp = _vp(workspace.data_ptr()) if workspace is not None else None
     wb = workspace.numel() * workspace.element_size() if workspace is not None else 0
-    rc = lib.sigmoid_attn_bwd(q.data_ptr(), k.data_ptr(), v.data_ptr(), dout.data_ptr(), dq.data_ptr(),
+    rc = getattr(lib, _entry)(q.data_ptr(), k.data_ptr(), v.data_ptr(), dout.data_ptr(), dq.data_ptr(),
                               dk.data_ptr(), dv.data_ptr(), B, H, N, d, _dtype_code(q), float(bias),
                               int(bool(causal)), _slopes_ptr(alibi_slopes, H), _st(q), _st(k), _st(v), _st(dout),
                               _st(dq), _st(dk), _st(dv), wp, wb, _stream())
-    _raise(rc, "sigmoid_attn_bwd")
+    _raise(rc, _entry)
     return dq, dk, dv
+
+
+def sigmoid_attn_bwd_compiler_scheduled(q, k, v, dout, dq, dk, dv, bias, causal=False, alibi_slopes=None):
+    """Same result as sigmoid_attn_bwd from the compiler-scheduled pipeline step (comparison aid)."""
+    return sigmoid_attn_bwd(q, k, v, dout, dq, dk, dv, bias, causal, alibi_slopes,
+                            _entry="sigmoid_attn_bwd_compiler_scheduled")
 
 
 def sigmoid_attn_bwd_dkdv(q, k, v, dout, dk, dv, bias, causal=False, alibi_slopes=None):

@@ -94,12 +94,13 @@ int launch(K kernel, dim3 grid, dim3 block, size_t lds, hipStream_t st, Args... 
 // ---------------------------------------------------------------- forward
 constexpr int kFwdWaves = 8;  // waves per forward workgroup, 32 query rows each
 
-template <int D, bool SOFTMAX>
+template <int D, bool SOFTMAX, bool PIN>
 int launch_fwd_bf16(const FwdParams& p, int causal, bool alibi, hipStream_t st) {
   constexpr size_t lds = 6 * 64 * D * 2;  // 3 K slots + 3 V slots of 64 keys
   dim3 grid(p.n_qblocks * p.B * p.H), block(64 * kFwdWaves);
   int rc = SATTN_OK;
-  SATTN_DISPATCH2(causal, alibi, rc = launch(attn_fwd_kernel<D, kFwdWaves, A, B2, SOFTMAX>, grid, block, lds, st, p));
+  SATTN_DISPATCH2(causal, alibi,
+                  rc = launch(attn_fwd_kernel<D, kFwdWaves, A, B2, SOFTMAX, PIN>, grid, block, lds, st, p));
   return rc;
 }
 
@@ -117,7 +118,7 @@ struct FwdArgs {
   const sattn_strides *sq, *sk, *sv, *so; void* stream;
 };
 
-template <bool SOFTMAX>
+template <bool SOFTMAX, bool PIN = true>
 int fwd_impl(const FwdArgs& a) {
   int rc = check_shape(a.B, a.H, a.N, a.d, a.dtype);
   if (rc) return rc;
@@ -147,14 +148,14 @@ int fwd_impl(const FwdArgs& a) {
   p.n_qblocks = (a.N + 32 * kFwdWaves - 1) / (32 * kFwdWaves);
   p.nscale_log2 = (SOFTMAX ? kLog2e : -kLog2e) * inv_sqrt_d;
   p.nbias_log2 = -a.bias * kLog2e;
-  if (a.d == 128) return launch_fwd_bf16<128, SOFTMAX>(p, a.causal, alibi, st);
-  return launch_fwd_bf16<64, SOFTMAX>(p, a.causal, alibi, st);
+  if (a.d == 128) return launch_fwd_bf16<128, SOFTMAX, PIN>(p, a.causal, alibi, st);
+  return launch_fwd_bf16<64, SOFTMAX, PIN>(p, a.causal, alibi, st);
 }
 
 // ---------------------------------------------------------------- backward
 enum BwdPart { kBwdDkDv = 1, kBwdDq = 2 };
 
-template <int D, bool SOFTMAX>
+template <int D, bool SOFTMAX, bool PIN>
 int launch_bwd_bf16(BwdParams p, int causal, bool alibi, int parts, hipStream_t st) {
   p.n_blocks = (p.N + 127) / 128;
   dim3 grid(p.n_blocks * p.B * p.H);
@@ -164,9 +165,9 @@ int launch_bwd_bf16(BwdParams p, int causal, bool alibi, int parts, hipStream_t 
   dim3 block(256);
   if (parts & kBwdDkDv)
     SATTN_DISPATCH2(causal, alibi,
-                    rc = launch(attn_bwd_kernel<D, BWD_DKDV, A, B2, SOFTMAX>, grid, block, lds + lds_stat, st, p));
+                    rc = launch(attn_bwd_kernel<D, BWD_DKDV, A, B2, SOFTMAX, PIN>, grid, block, lds + lds_stat, st, p));
   if (rc == SATTN_OK && (parts & kBwdDq))
-    SATTN_DISPATCH2(causal, alibi, rc = launch(attn_bwd_kernel<D, BWD_DQ, A, B2, SOFTMAX>, grid, block, lds, st, p));
+    SATTN_DISPATCH2(causal, alibi, rc = launch(attn_bwd_kernel<D, BWD_DQ, A, B2, SOFTMAX, PIN>, grid, block, lds, st, p));
   return rc;
 }
 
@@ -194,7 +195,7 @@ struct BwdArgs {
   void* workspace; size_t workspace_bytes; int parts; void* stream;
 };
 
-template <bool SOFTMAX>
+template <bool SOFTMAX, bool PIN = true>
 int bwd_impl(const BwdArgs& a) {
   int rc = check_shape(a.B, a.H, a.N, a.d, a.dtype);
   if (rc) return rc;
@@ -239,8 +240,8 @@ int bwd_impl(const BwdArgs& a) {
     if (rc) return rc;
     p.lse = a.lse; p.dvec = dvec;
   }
-  if (a.d == 128) return launch_bwd_bf16<128, SOFTMAX>(p, a.causal, alibi, a.parts, st);
-  return launch_bwd_bf16<64, SOFTMAX>(p, a.causal, alibi, a.parts, st);
+  if (a.d == 128) return launch_bwd_bf16<128, SOFTMAX, PIN>(p, a.causal, alibi, a.parts, st);
+  return launch_bwd_bf16<64, SOFTMAX, PIN>(p, a.causal, alibi, a.parts, st);
 }
 
 }  // namespace
@@ -286,6 +287,25 @@ int sigmoid_attn_bwd_dq(const void* q, const void* k, const void* v, const void*
 }
 
 size_t sigmoid_attn_bwd_workspace_bytes(int, int, int, int, sattn_dtype) { return 0; }
+
+int sigmoid_attn_fwd_compiler_scheduled(const void* q, const void* k, const void* v, void* o, int B, int H, int N,
+                                        int d, sattn_dtype dtype, float bias, int causal, const float* alibi_slopes,
+                                        const sattn_strides* sq, const sattn_strides* sk, const sattn_strides* sv,
+                                        const sattn_strides* so, void* stream) {
+  FwdArgs a{q, k, v, o, nullptr, B, H, N, d, dtype, bias, causal, alibi_slopes, sq, sk, sv, so, stream};
+  return fwd_impl<false, false>(a);
+}
+
+int sigmoid_attn_bwd_compiler_scheduled(const void* q, const void* k, const void* v, const void* dout, void* dq,
+                                        void* dk, void* dv, int B, int H, int N, int d, sattn_dtype dtype, float bias,
+                                        int causal, const float* alibi_slopes, const sattn_strides* sq,
+                                        const sattn_strides* sk, const sattn_strides* sv, const sattn_strides* sdout,
+                                        const sattn_strides* sdq, const sattn_strides* sdk, const sattn_strides* sdv,
+                                        void* workspace, size_t workspace_bytes, void* stream) {
+  BwdArgs a{q, k, v, nullptr, nullptr, dout, dq, dk, dv, B, H, N, d, dtype, bias, causal, alibi_slopes,
+            sq, sk, sv, nullptr, sdout, sdq, sdk, sdv, workspace, workspace_bytes, kBwdDkDv | kBwdDq, stream};
+  return bwd_impl<false, false>(a);
+}
 
 int softmax_attn_fwd(const void* q, const void* k, const void* v, void* o, float* lse, int B, int H, int N, int d,
                      sattn_dtype dtype, int causal, const float* alibi_slopes, const sattn_strides* sq,

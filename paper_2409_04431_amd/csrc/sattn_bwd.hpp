@@ -432,7 +432,9 @@ __device__ __forceinline__ void bwd_step_full_pinned(BwdWave<D, MODE>& W, uint32
   W.dsb[PAR ^ 1][1] = as_bf16x8(u32x4{wd[4], wd[5], wd[6], wd[7]});
 }
 
-template <int D, int MODE, bool CAUSAL, bool ALIBI, bool SOFTMAX>
+// PIN = false runs every step in its compiler-scheduled form (the form the softmax variant
+// always uses): the like-for-like counterpart for comparisons.
+template <int D, int MODE, bool CAUSAL, bool ALIBI, bool SOFTMAX, bool PIN = true>
 __global__ void __launch_bounds__(256, 1)
 attn_bwd_kernel(const BwdParams p) {
   constexpr int NW = 4, BS = 32 * NW, BC = 64, KD = D / 16, DT = D / 32;
@@ -605,7 +607,7 @@ attn_bwd_kernel(const BwdParams p) {
     const bool doS = s - 1 >= c_lo_s && s - 1 <= c_hi_s;
     const int cs = 32 * (s - 1), bl = cs + 8 * h;
     const bool ragged = doS && s - 1 == c_hi_s && cs + 32 > N;
-    pin = !SOFTMAX && !(MODE == BWD_DKDV && ragged);
+    pin = PIN && !SOFTMAX && !(MODE == BWD_DKDV && ragged);
     if (!doS) thr = NONE;
     else if (MODE == BWD_DKDV) thr = (CAUSAL && s - 1 == c_lo_s) ? ai - bl : ALL;
     else thr = (s - 1 == c_hi_s) ? ((CAUSAL && ai < N - 1 ? ai : N - 1) - bl) : ALL;
@@ -616,9 +618,9 @@ attn_bwd_kernel(const BwdParams p) {
   // loop of pinned steps only; the tiles before and after run the flag-driven general body.
   // Every variant has its one barrier per tile at the same place, so waves of a workgroup
   // may be in different loops.
-  const int t_s0 = SOFTMAX ? t_hi + 1 : (c_lo_s + 3) / 2;          // first tile with 2t >= c_lo+2
+  const int t_s0 = (SOFTMAX || !PIN) ? t_hi + 1 : (c_lo_s + 3) / 2;          // first tile with 2t >= c_lo+2
   const int t_s1a = (c_hi_s + 1) / 2 - 1, t_s1b = N / BC - 3;      // last tile with 2t+1 <= c_hi / with tile t+2 inside the tensor
-  const int t_s1 = SOFTMAX ? t_lo - 1 : (t_s1a < t_s1b ? t_s1a : t_s1b);
+  const int t_s1 = (SOFTMAX || !PIN) ? t_lo - 1 : (t_s1a < t_s1b ? t_s1a : t_s1b);
   auto rotate = [&](int t) {
     // rotate the per-lane addresses by one ring slot
     const int s0 = t % NSLOT;  // row0 points at slot s0, row1 at s0+1, tr at s0-1 (mod 4)

@@ -340,18 +340,20 @@ __device__ __forceinline__ void fwd_step_full_pinned(FwdWave<D>& W, uint32_t kad
 }
 
 // Dispatch one step of chunk c for a wave that owns chunks 0..cw-1.
-template <int D, bool ALIBI, bool SOFTMAX, int PAR, bool FOLD>
+template <int D, bool ALIBI, bool SOFTMAX, int PAR, bool FOLD, bool PIN>
 __device__ __forceinline__ void fwd_step_any(FwdWave<D>& W, int c, int cw, uint32_t kaddr, uint32_t vaddr, int N,
                                              bool causal) {
   if (c + 1 < cw) {
-    if constexpr (SOFTMAX) fwd_step<D, ALIBI, SOFTMAX, STEP_FULL, PAR>(W, kaddr, vaddr, 32 * c, N, causal);
+    if constexpr (SOFTMAX || !PIN) fwd_step<D, ALIBI, SOFTMAX, STEP_FULL, PAR, FOLD>(W, kaddr, vaddr, 32 * c, N, causal);
     else fwd_step_full_pinned<D, ALIBI, PAR, FOLD>(W, kaddr, vaddr, 32 * c);
   }
   else if (c + 1 == cw) fwd_step<D, ALIBI, SOFTMAX, STEP_LAST, PAR, FOLD>(W, kaddr, vaddr, 32 * c, N, causal);
   else if (c == cw) fwd_step<D, ALIBI, SOFTMAX, STEP_TAIL, PAR, FOLD>(W, kaddr, vaddr, 32 * c, N, causal);
 }
 
-template <int D, int NW, bool CAUSAL, bool ALIBI, bool SOFTMAX>
+// PIN = false runs the steady-state step in its compiler-scheduled form as well (the form the
+// softmax variant always uses): the like-for-like counterpart for comparisons.
+template <int D, int NW, bool CAUSAL, bool ALIBI, bool SOFTMAX, bool PIN = true>
 __global__ void __launch_bounds__(64 * NW, 8 / NW)
 attn_fwd_kernel(const FwdParams p) {
   constexpr int BR = 32 * NW, BC = 64;
@@ -467,8 +469,8 @@ attn_fwd_kernel(const FwdParams p) {
     const int vslot2 = kslot == 0 ? 2 : kslot - 1;  // (t+2)%3
     if (k_more) kst.issue(kring + kslot * TILE, N, uwave, lane);
     if (v_more) vst.issue(vring + vslot2 * TILE, N, uwave, lane);
-    fwd_step_any<D, ALIBI, SOFTMAX, 0, FOLD>(W, 2 * t, cw, 0, 0, N, CAUSAL);
-    fwd_step_any<D, ALIBI, SOFTMAX, 1, FOLD>(W, 2 * t + 1, cw, CHUNK, CHUNK, N, CAUSAL);
+    fwd_step_any<D, ALIBI, SOFTMAX, 0, FOLD, PIN>(W, 2 * t, cw, 0, 0, N, CAUSAL);
+    fwd_step_any<D, ALIBI, SOFTMAX, 1, FOLD, PIN>(W, 2 * t + 1, cw, CHUNK, CHUNK, N, CAUSAL);
     // advance the read addresses by one ring slot: K reads are at slot (t+1)%3, V reads at t%3
     const int kadv = kslot == 1 ? -2 * TILE : TILE;  // slot (t+1)%3 == 2 wraps to 0
     const int vadv = kslot == 2 ? -2 * TILE : TILE;

@@ -333,3 +333,21 @@ def test_matrix_rate_probe_runs_and_reports_a_plausible_rate():
     assert torch.isfinite(sink).all()
     per_cu = flops / (e0.elapsed_time(e1) * 1e-3) / 64 / 1e12   # TFLOP/s per compute unit
     assert 2.0 < per_cu < 2.5e3 / 256 * 1.05                    # below the nominal 9.8 TFLOP/s per CU
+
+
+@pytest.mark.parametrize("B,H,N,d,causal,alibi", [(1, 2, 333, 128, True, False), (2, 2, 200, 64, True, True),
+                                                  (1, 1, 640, 128, False, True)])
+def test_compiler_scheduled_entry_points_match_oracle(B, H, N, d, causal, alibi):
+    inp = _rand_inputs(B, H, N, d, seed=77)
+    slopes = W.alibi_slopes(H) if alibi else None
+    bias = -float(np.log(N))
+    q, k, v, do = (_dev(inp[n]) for n in ("q", "k", "v", "dout"))
+    sl = _dev(slopes) if slopes is not None else None
+    o, dq, dk, dv = (torch.full_like(q, float("nan")) for _ in range(4))
+    sa.sigmoid_attn_fwd_compiler_scheduled(q, k, v, o, bias, causal, sl)
+    sa.sigmoid_attn_bwd_compiler_scheduled(q, k, v, do, dq, dk, dv, bias, causal, sl)
+    torch.cuda.synchronize()
+    ro = orc.sigmoid_attn_fwd(inp["q"], inp["k"], inp["v"], bias, causal, slopes)
+    rdq, rdk, rdv = orc.sigmoid_attn_bwd(inp["q"], inp["k"], inp["v"], inp["dout"], bias, causal, slopes)
+    for name, got, ref in (("o", o, ro), ("dq", dq, rdq), ("dk", dk, rdk), ("dv", dv, rdv)):
+        assert nerr(got, ref) <= TOL_BF16, name
