@@ -305,6 +305,23 @@ __device__ __forceinline__ void sig_ops(const FwdWave<D>& W, const f32x16& s, fl
   }
 }
 
+// First sigmoid operation of sub-slot K.  The 72 operations are cut so that every group of
+// transcendental instructions (X x4, R x4) ends a slice, i.e. is followed by the next
+// sub-slot's MFMA: a plain VALU instruction right behind a transcendental one costs a wait
+// state (an s_nop from the compiler, one more issue slot).  Per group of 18 operations the
+// cuts are  [C2 of the previous group, F4] [X4] [A4] [R4]  with 4 sub-slots per group, or
+// [C2, F4, X4] [A4, R4] with 2; the last C2 joins the last slice.
+template <int NSUB>
+__device__ constexpr int sig_lo(int K) {
+  if (K <= 0) return 0;
+  if (K >= NSUB) return 72;
+  constexpr int PER = NSUB / 4;  // sub-slots per group
+  const int g = K / PER, ph = K % PER;
+  if (PER == 4) return ph == 0 ? 18 * g - 2 : 18 * g + 4 * ph;
+  if (PER == 2) return ph == 0 ? 18 * g - 2 : 18 * g + 8;
+  return (K * 72) / NSUB;
+}
+
 template <int D, bool ALIBI, int PAR, bool FOLD, int K>
 __device__ __forceinline__ void full_subslots(FwdWave<D>& W, uint32_t kaddr, uint32_t vaddr, float (&u)[16],
                                               uint32_t (&wp)[8], float nbias_v, float sl2_v, float dist0) {
@@ -321,7 +338,7 @@ __device__ __forceinline__ void full_subslots(FwdWave<D>& W, uint32_t kaddr, uin
       const uint32_t a0 = W.voff[m % DT] + vaddr + (m / DT) * 16 * (D * 2);
       W.vf[m] = join_tr(lds_read_tr16(a0), lds_read_tr16(a0 + 4 * (D * 2)));
     }
-    sig_ops<D, ALIBI, (K * NOPS) / NSUB, ((K + 1) * NOPS) / NSUB>(W, W.s[PAR], u, wp, nbias_v, sl2_v, dist0);
+    sig_ops<D, ALIBI, sig_lo<NSUB>(K), sig_lo<NSUB>(K + 1)>(W, W.s[PAR], u, wp, nbias_v, sl2_v, dist0);
     full_subslots<D, ALIBI, PAR, FOLD, K + 1>(W, kaddr, vaddr, u, wp, nbias_v, sl2_v, dist0);
   }
 }
