@@ -140,6 +140,33 @@ size_t softmax_attn_bwd_workspace_bytes(int B, int H, int N, int d, sattn_dtype 
 /* Human-readable text for an SATTN_ERR_* code (static storage). */
 const char* sattn_strerror(int code);
 
+/* Variable-length batches (Appendix G.4, training details of the speech models: dynamic
+ * batching, and every sample's own length gives its bias b = -ln(n), a non-trainable bias
+ * vector for the minibatch): the B
+ * sequences are packed along the token axis of [tokens, H, d] tensors; sequence s owns tokens
+ * cu_seqlens[s] .. cu_seqlens[s+1]-1 (device pointer to B+1 non-decreasing int32 offsets,
+ * cu_seqlens[0] >= 0) and attends only to itself.  max_seqlen bounds every length (tokens of
+ * a longer sequence beyond it are not written).  bias_per_seq is a device pointer to B floats
+ * or NULL (then `bias` applies to every sequence).  Strides: `batch` is ignored, `head` and
+ * `seq` (token) as usual; NULL = contiguous [tokens, H, d].  bf16 only.  Same error codes and
+ * stream semantics as the dense entry points; the offsets themselves are not validated. */
+int sigmoid_attn_varlen_fwd(const void* q, const void* k, const void* v, void* o,
+                            const int32_t* cu_seqlens, const float* bias_per_seq,
+                            int B, int H, int max_seqlen, int d, sattn_dtype dtype,
+                            float bias, int causal, const float* alibi_slopes,
+                            const sattn_strides* sq, const sattn_strides* sk,
+                            const sattn_strides* sv, const sattn_strides* so,
+                            void* stream);
+int sigmoid_attn_varlen_bwd(const void* q, const void* k, const void* v, const void* dout,
+                            void* dq, void* dk, void* dv,
+                            const int32_t* cu_seqlens, const float* bias_per_seq,
+                            int B, int H, int max_seqlen, int d, sattn_dtype dtype,
+                            float bias, int causal, const float* alibi_slopes,
+                            const sattn_strides* sq, const sattn_strides* sk,
+                            const sattn_strides* sv, const sattn_strides* sdout,
+                            const sattn_strides* sdq, const sattn_strides* sdk,
+                            const sattn_strides* sdv, void* stream);
+
 /* Comparison aids (Section 4.1 / Appendix F.2 compare the sigmoid kernels with softmax kernels
  * built the same way).  Same arguments, results and error behaviour as sigmoid_attn_fwd /
  * sigmoid_attn_bwd; the kernels run every pipeline step in the compiler-scheduled form that

@@ -50,6 +50,11 @@ def load_library():
     lib.sigmoid_attn_fwd_compiler_scheduled.restype = i
     lib.sigmoid_attn_bwd_compiler_scheduled.argtypes = lib.sigmoid_attn_bwd.argtypes
     lib.sigmoid_attn_bwd_compiler_scheduled.restype = i
+    ip = ctypes.c_void_p
+    lib.sigmoid_attn_varlen_fwd.argtypes = [_vp, _vp, _vp, _vp, ip, _vp, i, i, i, i, i, f, i, _vp, _SP, _SP, _SP, _SP, _vp]
+    lib.sigmoid_attn_varlen_fwd.restype = i
+    lib.sigmoid_attn_varlen_bwd.argtypes = [_vp] * 7 + [ip, _vp, i, i, i, i, i, f, i, _vp] + [_SP] * 7 + [_vp]
+    lib.sigmoid_attn_varlen_bwd.restype = i
     lib.sigmoid_attn_bwd_dkdv.argtypes = [_vp] * 6 + [i, i, i, i, i, f, i, _vp] + [_SP] * 6 + [_vp]
     lib.sigmoid_attn_bwd_dkdv.restype = i
     lib.sigmoid_attn_bwd_dq.argtypes = [_vp] * 5 + [i, i, i, i, i, f, i, _vp] + [_SP] * 5 + [_vp]
@@ -74,6 +79,55 @@ def load_library():
 
 def sattn_strerror(code):
     return load_library().sattn_strerror(int(code)).decode()
+
+
+def _check_varlen(cu_seqlens, bias_per_seq, *ts):
+    t0 = ts[0]
+    for t in ts:
+        if not t.is_cuda or t.dim() != 3 or t.shape != t0.shape or t.dtype != torch.bfloat16 or t.stride(2) != 1:
+            raise SattnError("varlen tensors must be CUDA bf16 [tokens, H, d] with a contiguous last dimension")
+    if not cu_seqlens.is_cuda or cu_seqlens.dtype != torch.int32 or cu_seqlens.dim() != 1 or not cu_seqlens.is_contiguous():
+        raise SattnError("cu_seqlens must be a contiguous CUDA int32 vector of B+1 offsets")
+    B = cu_seqlens.numel() - 1
+    if bias_per_seq is not None and (not bias_per_seq.is_cuda or bias_per_seq.dtype != torch.float32
+                                     or bias_per_seq.numel() != B or not bias_per_seq.is_contiguous()):
+        raise SattnError("bias_per_seq must be a contiguous CUDA float32 vector of B elements")
+    return B
+
+
+def _st3(t):
+    return ctypes.byref(_Strides(0, t.stride(1), t.stride(0)))
+
+
+def sigmoid_attn_varlen_fwd(q, k, v, o, cu_seqlens, max_seqlen, bias, causal=False, alibi_slopes=None,
+                            bias_per_seq=None):
+    """Forward over B packed sequences ([tokens, H, d] tensors, offsets in cu_seqlens)."""
+    lib = load_library()
+    B = _check_varlen(cu_seqlens, bias_per_seq, q, k, v, o)
+    _, H, d = q.shape
+    bp = _vp(bias_per_seq.data_ptr()) if bias_per_seq is not None else None
+    rc = lib.sigmoid_attn_varlen_fwd(q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(),
+                                     _vp(cu_seqlens.data_ptr()), bp, B, H, int(max_seqlen), d, SATTN_BF16,
+                                     float(bias), int(bool(causal)), _slopes_ptr(alibi_slopes, H),
+                                     _st3(q), _st3(k), _st3(v), _st3(o), _stream())
+    _raise(rc, "sigmoid_attn_varlen_fwd")
+    return o
+
+
+def sigmoid_attn_varlen_bwd(q, k, v, dout, dq, dk, dv, cu_seqlens, max_seqlen, bias, causal=False,
+                            alibi_slopes=None, bias_per_seq=None):
+    """Backward over B packed sequences ([tokens, H, d] tensors, offsets in cu_seqlens)."""
+    lib = load_library()
+    B = _check_varlen(cu_seqlens, bias_per_seq, q, k, v, dout, dq, dk, dv)
+    _, H, d = q.shape
+    bp = _vp(bias_per_seq.data_ptr()) if bias_per_seq is not None else None
+    rc = lib.sigmoid_attn_varlen_bwd(q.data_ptr(), k.data_ptr(), v.data_ptr(), dout.data_ptr(), dq.data_ptr(),
+                                     dk.data_ptr(), dv.data_ptr(), _vp(cu_seqlens.data_ptr()), bp, B, H,
+                                     int(max_seqlen), d, SATTN_BF16, float(bias), int(bool(causal)),
+                                     _slopes_ptr(alibi_slopes, H), _st3(q), _st3(k), _st3(v), _st3(dout),
+                                     _st3(dq), _st3(dk), _st3(dv), _stream())
+    _raise(rc, "sigmoid_attn_varlen_bwd")
+    return dq, dk, dv
 
 
 def sattn_mfma_bf16_probe(blocks, iters, sink):

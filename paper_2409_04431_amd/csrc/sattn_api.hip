@@ -116,6 +116,7 @@ struct FwdArgs {
   const void *q, *k, *v; void* o; float* lse;
   int B, H, N, d; sattn_dtype dtype; float bias; int causal; const float* slopes;
   const sattn_strides *sq, *sk, *sv, *so; void* stream;
+  const int* cu_seqlens = nullptr; const float* bias_vec = nullptr;  // variable-length batches
 };
 
 template <bool SOFTMAX, bool PIN = true>
@@ -132,7 +133,7 @@ int fwd_impl(const FwdArgs& a) {
   const bool alibi = a.slopes != nullptr;
   const float inv_sqrt_d = 1.0f / sqrtf((float)a.d);
   if (a.dtype == SATTN_F32) {
-    if (SOFTMAX) return SATTN_ERR_UNSUPPORTED;  // the comparison kernels exist for bf16 only
+    if (SOFTMAX || a.cu_seqlens) return SATTN_ERR_UNSUPPORTED;  // comparison and varlen kernels: bf16 only
     F32Params p{};
     p.q = q; p.k = k; p.v = v; p.out0 = o;
     p.slopes = a.slopes; p.B = a.B; p.H = a.H; p.N = a.N;
@@ -148,6 +149,7 @@ int fwd_impl(const FwdArgs& a) {
   p.n_qblocks = (a.N + 32 * kFwdWaves - 1) / (32 * kFwdWaves);
   p.nscale_log2 = (SOFTMAX ? kLog2e : -kLog2e) * inv_sqrt_d;
   p.nbias_log2 = -a.bias * kLog2e;
+  p.cu_seqlens = a.cu_seqlens; p.bias_vec = a.bias_vec;
   if (a.d == 128) return launch_fwd_bf16<128, SOFTMAX, PIN>(p, a.causal, alibi, st);
   return launch_fwd_bf16<64, SOFTMAX, PIN>(p, a.causal, alibi, st);
 }
@@ -193,6 +195,7 @@ struct BwdArgs {
   int B, H, N, d; sattn_dtype dtype; float bias; int causal; const float* slopes;
   const sattn_strides *sq, *sk, *sv, *so, *sdout, *sdq, *sdk, *sdv;
   void* workspace; size_t workspace_bytes; int parts; void* stream;
+  const int* cu_seqlens = nullptr; const float* bias_vec = nullptr;  // variable-length batches
 };
 
 template <bool SOFTMAX, bool PIN = true>
@@ -211,7 +214,7 @@ int bwd_impl(const BwdArgs& a) {
   const bool alibi = a.slopes != nullptr;
   const float inv_sqrt_d = 1.0f / sqrtf((float)a.d);
   if (a.dtype == SATTN_F32) {
-    if (SOFTMAX) return SATTN_ERR_UNSUPPORTED;
+    if (SOFTMAX || a.cu_seqlens) return SATTN_ERR_UNSUPPORTED;
     F32Params p{};
     p.q = q; p.k = k; p.v = v; p.dout = dout;
     p.slopes = a.slopes; p.B = a.B; p.H = a.H; p.N = a.N;
@@ -226,6 +229,7 @@ int bwd_impl(const BwdArgs& a) {
   p.inv_sqrt_d = inv_sqrt_d;
   p.nscale_log2 = -kLog2e * inv_sqrt_d;
   p.nbias_log2 = -a.bias * kLog2e;
+  p.cu_seqlens = a.cu_seqlens; p.bias_vec = a.bias_vec;
   if (SOFTMAX) {
     if (!a.lse) return SATTN_ERR_NULL;
     if ((rc = make_ref(a.o, a.so, a.H, a.N, a.d, a.dtype, &o))) return rc;
@@ -341,6 +345,45 @@ const char* sattn_strerror(int code) {
     case SATTN_ERR_LAUNCH: return "the HIP runtime rejected the kernel launch";
     default: return "unknown error code";
   }
+}
+
+// Packed [tokens, H, d] strides for a variable-length call: batch stride 0; head and token
+// strides from the caller, or contiguous.
+static sattn_strides varlen_strides(const sattn_strides* s, int H, int d) {
+  sattn_strides r;
+  r.batch = 0;
+  r.head = s ? s->head : d;
+  r.seq = s ? s->seq : (int64_t)H * d;
+  return r;
+}
+
+int sigmoid_attn_varlen_fwd(const void* q, const void* k, const void* v, void* o, const int32_t* cu_seqlens,
+                            const float* bias_per_seq, int B, int H, int max_seqlen, int d, sattn_dtype dtype,
+                            float bias, int causal, const float* alibi_slopes, const sattn_strides* sq,
+                            const sattn_strides* sk, const sattn_strides* sv, const sattn_strides* so,
+                            void* stream) {
+  if (!cu_seqlens) return SATTN_ERR_NULL;
+  const sattn_strides tq = varlen_strides(sq, H, d), tk = varlen_strides(sk, H, d), tv = varlen_strides(sv, H, d),
+                      to = varlen_strides(so, H, d);
+  FwdArgs a{q, k, v, o, nullptr, B, H, max_seqlen, d, dtype, bias, causal, alibi_slopes, &tq, &tk, &tv, &to, stream};
+  a.cu_seqlens = cu_seqlens; a.bias_vec = bias_per_seq;
+  return fwd_impl<false>(a);
+}
+
+int sigmoid_attn_varlen_bwd(const void* q, const void* k, const void* v, const void* dout, void* dq, void* dk,
+                            void* dv, const int32_t* cu_seqlens, const float* bias_per_seq, int B, int H,
+                            int max_seqlen, int d, sattn_dtype dtype, float bias, int causal,
+                            const float* alibi_slopes, const sattn_strides* sq, const sattn_strides* sk,
+                            const sattn_strides* sv, const sattn_strides* sdout, const sattn_strides* sdq,
+                            const sattn_strides* sdk, const sattn_strides* sdv, void* stream) {
+  if (!cu_seqlens) return SATTN_ERR_NULL;
+  const sattn_strides tq = varlen_strides(sq, H, d), tk = varlen_strides(sk, H, d), tv = varlen_strides(sv, H, d),
+                      tdo = varlen_strides(sdout, H, d), tdq = varlen_strides(sdq, H, d),
+                      tdk = varlen_strides(sdk, H, d), tdv = varlen_strides(sdv, H, d);
+  BwdArgs a{q, k, v, nullptr, nullptr, dout, dq, dk, dv, B, H, max_seqlen, d, dtype, bias, causal, alibi_slopes,
+            &tq, &tk, &tv, nullptr, &tdo, &tdq, &tdk, &tdv, nullptr, 0, kBwdDkDv | kBwdDq, stream};
+  a.cu_seqlens = cu_seqlens; a.bias_vec = bias_per_seq;
+  return bwd_impl<false>(a);
 }
 
 int sattn_mfma_bf16_probe(int blocks, int iters, float* sink, void* stream) {

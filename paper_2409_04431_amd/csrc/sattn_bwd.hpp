@@ -38,6 +38,9 @@ struct BwdParams {
   float nscale_log2;   // -log2(e)/sqrt(d)
   float nbias_log2;    // -b*log2(e)
   float inv_sqrt_d;
+  // variable-length batches (nullptr otherwise), as in the forward parameters
+  const int* cu_seqlens;
+  const float* bias_vec;
 };
 
 // One swizzle for tiles that are read both row-wise (ds_read_b128, 32 rows at one logical
@@ -452,12 +455,21 @@ attn_bwd_kernel(const BwdParams p) {
   const int bh = logical / p.n_blocks;
   // causal: heavy blocks first (late query blocks for DQ, early key blocks for DKDV)
   const int blk = (CAUSAL && MODE == BWD_DQ) ? (p.n_blocks - 1 - logical % p.n_blocks) : (logical % p.n_blocks);
-  const int b = bh / p.H, hd = bh % p.H, N = p.N;
+  const int b = bh / p.H, hd = bh % p.H;
+  int N = p.N;
+  int64_t tok0 = 0;
+  float nbias_log2 = p.nbias_log2;
+  if (p.cu_seqlens) {
+    tok0 = p.cu_seqlens[b];
+    N = min(p.cu_seqlens[b + 1] - (int)tok0, p.N);  // never beyond the span the host checked
+    if (p.bias_vec) nbias_log2 = -p.bias_vec[b] * kLog2e;
+    if (blk * BS >= N) return;  // this sequence has no such block (whole workgroup)
+  }
 
-  const __bf16* qbase = (const __bf16*)p.q.ptr + b * p.q.sb + hd * p.q.sh;
-  const __bf16* kbase = (const __bf16*)p.k.ptr + b * p.k.sb + hd * p.k.sh;
-  const __bf16* vbase = (const __bf16*)p.v.ptr + b * p.v.sb + hd * p.v.sh;
-  const __bf16* dobase = (const __bf16*)p.dout.ptr + b * p.dout.sb + hd * p.dout.sh;
+  const __bf16* qbase = (const __bf16*)p.q.ptr + b * p.q.sb + hd * p.q.sh + tok0 * p.q.ss;
+  const __bf16* kbase = (const __bf16*)p.k.ptr + b * p.k.sb + hd * p.k.sh + tok0 * p.k.ss;
+  const __bf16* vbase = (const __bf16*)p.v.ptr + b * p.v.sb + hd * p.v.sh + tok0 * p.v.ss;
+  const __bf16* dobase = (const __bf16*)p.dout.ptr + b * p.dout.sb + hd * p.dout.sh + tok0 * p.dout.ss;
   // stationary tensors x1, x2 and streamed tensors y1, y2
   const __bf16* x1b = MODE == BWD_DKDV ? kbase : qbase;
   const __bf16* x2b = MODE == BWD_DKDV ? vbase : dobase;
@@ -482,7 +494,7 @@ attn_bwd_kernel(const BwdParams p) {
       if (MODE == BWD_DKDV) W.acc1[dt][r] = 0.f;
     }
   W.ai = ai; W.h = h;
-  W.nscale = p.nscale_log2; W.nbias = p.nbias_log2;
+  W.nscale = p.nscale_log2; W.nbias = nbias_log2;
   W.sl2 = ALIBI ? p.slopes[hd] * kLog2e : 0.f;
 #pragma unroll
   for (int r = 0; r < 16; ++r)  // DKDV: |i-j| = (bl - ai) + key_of_reg(r); DQ: (ai - bl) - key_of_reg(r)
@@ -700,8 +712,8 @@ attn_bwd_kernel(const BwdParams p) {
 
   if (ai < N) {
     const float sc = p.inv_sqrt_d;  // dQ and dK carry the 1/sqrt(d) of the logits
-    __bf16* o0 = (MODE == BWD_DKDV ? (__bf16*)p.dk.ptr + b * p.dk.sb + hd * p.dk.sh + (int64_t)ai * p.dk.ss
-                                   : (__bf16*)p.dq.ptr + b * p.dq.sb + hd * p.dq.sh + (int64_t)ai * p.dq.ss);
+    __bf16* o0 = (MODE == BWD_DKDV ? (__bf16*)p.dk.ptr + b * p.dk.sb + hd * p.dk.sh + (tok0 + ai) * p.dk.ss
+                                   : (__bf16*)p.dq.ptr + b * p.dq.sb + hd * p.dq.sh + (tok0 + ai) * p.dq.ss);
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
@@ -712,7 +724,7 @@ attn_bwd_kernel(const BwdParams p) {
         *(u32x2*)(o0 + 32 * dt + 8 * g + 4 * h) = w;
       }
     if (MODE == BWD_DKDV) {
-      __bf16* o1 = (__bf16*)p.dv.ptr + b * p.dv.sb + hd * p.dv.sh + (int64_t)ai * p.dv.ss;
+      __bf16* o1 = (__bf16*)p.dv.ptr + b * p.dv.sb + hd * p.dv.sh + (tok0 + ai) * p.dv.ss;
 #pragma unroll
       for (int dt = 0; dt < DT; ++dt)
 #pragma unroll

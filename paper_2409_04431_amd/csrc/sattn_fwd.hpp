@@ -30,6 +30,11 @@ struct FwdParams {
   int n_qblocks;
   float nscale_log2;  // -log2(e)/sqrt(d)   (softmax: +log2(e)/sqrt(d))
   float nbias_log2;   // -b*log2(e)
+  // variable-length batches (nullptr otherwise): sequence b owns tokens cu_seqlens[b] ..
+  // cu_seqlens[b+1]-1 of the packed [tokens, H, d] tensors (batch stride 0); N is then the
+  // longest length the grid covers; bias_vec, if given, holds one bias per sequence
+  const int* cu_seqlens;
+  const float* bias_vec;
 };
 
 // LDS swizzles (XOR on the 16-byte chunk index within a row).
@@ -393,12 +398,20 @@ attn_fwd_kernel(const FwdParams p) {
   // causal: heavy (late) query blocks first
   const int qb = CAUSAL ? (p.n_qblocks - 1 - logical % p.n_qblocks) : (logical % p.n_qblocks);
   const int b = bh / p.H, hd = bh % p.H;
-  const int N = p.N;
+  int N = p.N;
+  int64_t tok0 = 0;
+  float nbias_log2 = p.nbias_log2;
+  if (p.cu_seqlens) {
+    tok0 = p.cu_seqlens[b];
+    N = min(p.cu_seqlens[b + 1] - (int)tok0, p.N);  // never beyond the span the host checked
+    if (p.bias_vec) nbias_log2 = -p.bias_vec[b] * kLog2e;
+    if (qb * BR >= N) return;  // this sequence has no such query block (whole workgroup)
+  }
 
-  const __bf16* qbase = (const __bf16*)p.q.ptr + b * p.q.sb + hd * p.q.sh;
-  const __bf16* kbase = (const __bf16*)p.k.ptr + b * p.k.sb + hd * p.k.sh;
-  const __bf16* vbase = (const __bf16*)p.v.ptr + b * p.v.sb + hd * p.v.sh;
-  __bf16* obase = (__bf16*)p.o.ptr + b * p.o.sb + hd * p.o.sh;
+  const __bf16* qbase = (const __bf16*)p.q.ptr + b * p.q.sb + hd * p.q.sh + tok0 * p.q.ss;
+  const __bf16* kbase = (const __bf16*)p.k.ptr + b * p.k.sb + hd * p.k.sh + tok0 * p.k.ss;
+  const __bf16* vbase = (const __bf16*)p.v.ptr + b * p.v.sb + hd * p.v.sh + tok0 * p.v.ss;
+  __bf16* obase = (__bf16*)p.o.ptr + b * p.o.sb + hd * p.o.sh + tok0 * p.o.ss;
 
   const int q_wave0 = qb * BR + wave * 32;  // first query row of this wave
   const int qi = q_wave0 + l32;             // this lane's query row
@@ -425,7 +438,7 @@ attn_fwd_kernel(const FwdParams p) {
       W.voff[dt] = vring + row * (D * 2) + ((c ^ Swz<D>::v(row)) << 4) + ((i16 & 1) << 3);
     }
     W.qi = qi; W.h = h;
-    W.nscale = p.nscale_log2; W.nbias = p.nbias_log2;
+    W.nscale = p.nscale_log2; W.nbias = nbias_log2;
     W.sl2 = ALIBI ? p.slopes[hd] * kLog2e : 0.f;
     W.sm = SoftmaxState{-__builtin_inff(), 0.f};
 #pragma unroll

@@ -75,6 +75,21 @@ def test_backward_rejects_bad_arguments(lib):
     assert sa.sigmoid_attn_bwd_workspace_bytes(8, 16, 4096, 128) == 0
 
 
+def test_varlen_entry_points_reject_bad_arguments(lib):
+    ptrs = [0x1000, 0x2000, 0x3000, 0x4000]
+    tail = [2, 4, 512, 128, 0, 0.0, 1, None, None, None, None, None, None]       # B H max_seqlen d dtype bias causal ...
+    assert lib.sigmoid_attn_varlen_fwd(*ptrs, None, None, *tail) == -1          # cu_seqlens NULL
+    assert lib.sigmoid_attn_varlen_fwd(*ptrs, 0x5000, None, 2, 4, 512, 128, 1, 0.0, 1, None, None, None, None,
+                                       None, None) == -3                        # fp32: no varlen kernels
+    assert lib.sigmoid_attn_varlen_fwd(*ptrs, 0x5000, None, 2, 4, 512, 96, 0, 0.0, 1, None, None, None, None,
+                                       None, None) == -3                        # head dimension
+    assert lib.sigmoid_attn_varlen_fwd(*ptrs, 0x5000, None, 2, 4, 0, 128, 0, 0.0, 1, None, None, None, None,
+                                       None, None) == -2                        # max_seqlen
+    bptrs = [0x1000, 0x2000, 0x3000, 0x4000, 0x5000, 0x6000, 0x7000]
+    assert lib.sigmoid_attn_varlen_bwd(*bptrs, None, None, 2, 4, 512, 128, 0, 0.0, 1, None, *([None] * 7), None) == -1
+    assert lib.sigmoid_attn_varlen_bwd(*bptrs, 0x8000, None, 2, 4, 512, 128, 1, 0.0, 1, None, *([None] * 7), None) == -3
+
+
 def test_binding_refuses_cpu_tensors():
     import torch
     t = torch.zeros(1, 1, 8, 64, dtype=torch.bfloat16)

@@ -351,3 +351,45 @@ def test_compiler_scheduled_entry_points_match_oracle(B, H, N, d, causal, alibi)
     rdq, rdk, rdv = orc.sigmoid_attn_bwd(inp["q"], inp["k"], inp["v"], inp["dout"], bias, causal, slopes)
     for name, got, ref in (("o", o, ro), ("dq", dq, rdq), ("dk", dk, rdk), ("dv", dv, rdv)):
         assert nerr(got, ref) <= TOL_BF16, name
+
+
+# ------------------------------------------------------------------ variable-length batches
+
+@pytest.mark.parametrize("d,causal,alibi,per_seq_bias", [(128, True, False, True), (64, False, True, True),
+                                                         (128, True, True, False)])
+def test_varlen_batches_match_per_sequence_calls_and_oracle(d, causal, alibi, per_seq_bias):
+    H = 2
+    lens = [200, 1, 0, 333, 64, 129]                      # ragged, a single token, an empty sequence
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    total = int(cu[-1])
+    g = torch.Generator().manual_seed(4321)
+    q, k, v, do = (torch.randn(total, H, d, generator=g).bfloat16() for _ in range(4))
+    slopes = W.alibi_slopes(H) if alibi else None
+    biases = torch.tensor([-float(np.log(max(n, 2))) for n in lens], dtype=torch.float32)
+    bias = -float(np.log(max(lens)))
+    Q, K, V, DO = (_dev(t) for t in (q, k, v, do))
+    sl = _dev(slopes) if slopes is not None else None
+    o, dq, dk, dv = (torch.full_like(Q, float("nan")) for _ in range(4))
+    cu_d = torch.from_numpy(cu).cuda()
+    bp = biases.cuda() if per_seq_bias else None
+    sa.sigmoid_attn_varlen_fwd(Q, K, V, o, cu_d, max(lens), bias, causal, sl, bp)
+    sa.sigmoid_attn_varlen_bwd(Q, K, V, DO, dq, dk, dv, cu_d, max(lens), bias, causal, sl, bp)
+    torch.cuda.synchronize()
+    for s_, n in enumerate(lens):
+        if n == 0:
+            continue
+        a, b_ = int(cu[s_]), int(cu[s_ + 1])
+        bs = float(biases[s_]) if per_seq_bias else bias
+        # dense call on this sequence alone: [1, H, n, d] views of the packed tensors
+        dense = lambda t: t[a:b_].permute(1, 0, 2).unsqueeze(0)
+        o1, dq1, dk1, dv1 = (torch.full((1, H, n, d), float("nan"), dtype=torch.bfloat16, device="cuda") for _ in range(4))
+        sa.sigmoid_attn_fwd(dense(Q), dense(K), dense(V), o1, bs, causal, sl)
+        sa.sigmoid_attn_bwd(dense(Q), dense(K), dense(V), dense(DO), dq1, dk1, dv1, bs, causal, sl)
+        torch.cuda.synchronize()
+        for name, packed, alone in (("o", o, o1), ("dq", dq, dq1), ("dk", dk, dk1), ("dv", dv, dv1)):
+            assert torch.equal(dense(packed), alone), f"{name} of sequence {s_} differs from the dense call"
+        qs, ks, vs, ds = (t[a:b_].permute(1, 0, 2).unsqueeze(0) for t in (q, k, v, do))
+        ro = orc.sigmoid_attn_fwd(qs, ks, vs, bs, causal, slopes)
+        rdq, rdk, rdv = orc.sigmoid_attn_bwd(qs, ks, vs, ds, bs, causal, slopes)
+        for name, got, ref in (("o", o1, ro), ("dq", dq1, rdq), ("dk", dk1, rdk), ("dv", dv1, rdv)):
+            assert nerr(got, ref) <= TOL_BF16, f"{name} of sequence {s_}"
