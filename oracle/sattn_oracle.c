@@ -15,6 +15,9 @@
  *   O = P V
  *   dV = P^T dO,  dP = dO V^T,  dS = P (1-P) dP (0 where masked)
  *   dQ = dS K / sqrt(d),  dK = dS^T Q / sqrt(d)
+ *   db_i = sum_j dS_ij                          gradient of a bias added to row i of T; a
+ *                                               scalar learnable b (Section 5.4, Appendix G.4:
+ *                                               one per layer) gets the sum over its rows
  *
  * The table in Appendix F.1 and Algorithm 2 print the last two with a factor sqrt(d);
  * since S = Q K^T / sqrt(d) the chain rule gives 1/sqrt(d), which the finite-difference
@@ -31,7 +34,7 @@
  * Parity pins (tests/test_oracle_*.py): closed forms for zero logits, the N=1 scalar case,
  * the exp(s)/(exp(s)+n) form of Section 2 (sequence equation), sigma(-x)=1-sigma(x)
  * symmetry, the Heaviside limit of Appendix C, additivity over key halves, central finite
- * differences, and PyTorch's fp64 CPU sigmoid/softmax/scaled_dot_product_attention with
+ * differences (also in b, for the bias gradient), and PyTorch's fp64 CPU sigmoid/softmax/scaled_dot_product_attention with
  * autograd.  No function here is "parity unpinned".
  */
 #include <math.h>
@@ -127,6 +130,30 @@ void oracle_sigmoid_attn_bwd(const double* q, const double* k, const double* v, 
     double slope = alibi_slopes ? alibi_slopes[bh % H] : 0.0;
     sig_head_bwd(q + bh * hs, k + bh * hs, v + bh * hs, dout + bh * hs, dq + bh * hs, dk + bh * hs, dv + bh * hs,
                  N, d, bias, causal, slope);
+  }
+}
+
+/* Row sums of dS: T_ij = S_ij + b, so dL/db collects dL/dT_ij = dS_ij over every unmasked
+ * pair the bias enters; db_rows[bh][i] = sum_j dS_ij keeps the rows apart. */
+void oracle_sigmoid_attn_bias_grad(const double* q, const double* k, const double* v, const double* dout,
+                                   double* db_rows, int B, int H, int N, int d, double bias, int causal,
+                                   const double* alibi_slopes) {
+  const size_t hs = (size_t)N * d;
+#pragma omp parallel for schedule(dynamic, 1)
+  for (int bh = 0; bh < B * H; ++bh) {
+    double slope = alibi_slopes ? alibi_slopes[bh % H] : 0.0;
+    double* p = (double*)malloc(sizeof(double) * (size_t)N);
+    for (int i = 0; i < N; ++i) {
+      sig_row_probs(q + bh * hs, k + bh * hs, N, d, bias, causal, slope, i, p);
+      double acc = 0.0;
+      for (int j = 0; j < N; ++j) {
+        if (causal && j > i) continue;
+        double dp = dot(dout + bh * hs + (size_t)i * d, v + bh * hs + (size_t)j * d, d);
+        acc += p[j] * (1.0 - p[j]) * dp;
+      }
+      db_rows[(size_t)bh * N + i] = acc;
+    }
+    free(p);
   }
 }
 

@@ -89,6 +89,18 @@ def sigmoid_attn_bwd(q, k, v, dout, bias, causal=False, alibi_slopes=None):
     return dq, dk, dv
 
 
+def sigmoid_attn_bias_grad(q, k, v, dout, bias, causal=False, alibi_slopes=None):
+    """Row sums of dS, [B, H, N]: the gradient of a bias added to each query row's logits."""
+    q, k, v, dout = _f64(q), _f64(k), _f64(v), _f64(dout)
+    B, H, N, d = q.shape
+    assert k.shape == q.shape and v.shape == q.shape and dout.shape == q.shape
+    db = np.empty((B, H, N), dtype=np.float64)
+    s, sp = _slopes(alibi_slopes, H)
+    _load().oracle_sigmoid_attn_bias_grad(_ptr(q), _ptr(k), _ptr(v), _ptr(dout), _ptr(db), B, H, N, d,
+                                          ctypes.c_double(bias), int(bool(causal)), sp)
+    return db
+
+
 def softmax_attn_fwd(q, k, v, causal=False, alibi_slopes=None):
     """Returns (O, LSE) with LSE [B,H,N] in natural-log units."""
     q, k, v = _f64(q), _f64(k), _f64(v)

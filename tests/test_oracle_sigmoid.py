@@ -256,6 +256,53 @@ def test_zero_logit_gradients_closed_form():
     np.testing.assert_allclose(dk, 0.0, atol=1e-15)   # dK = dS^T Q / sqrt(d) and Q = 0
 
 
+# ------------------------------------------------------------------ bias gradient (row sums of dS)
+
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("alibi", [False, True])
+def test_bias_gradient_by_central_differences_in_b(causal, alibi):
+    # Row i of O depends on b only through row i of T, so d/db of sum_t O_it dO_it is the
+    # gradient of a bias on row i alone: the row sum of dS.  The forward oracle gives it by
+    # central differences without any backward formula.
+    B, H, N, d = 2, 2, 9, 4
+    q, k, v, dout = (_rand(B, H, N, d) for _ in range(4))
+    slopes = _alibi_slopes(H) if alibi else None
+    bias, eps = -0.7, 1e-5
+    lp = (orc.sigmoid_attn_fwd(q, k, v, bias + eps, causal, slopes) * dout).sum(-1)
+    lm = (orc.sigmoid_attn_fwd(q, k, v, bias - eps, causal, slopes) * dout).sum(-1)
+    db = orc.sigmoid_attn_bias_grad(q, k, v, dout, bias, causal, slopes)
+    assert db.shape == (B, H, N)
+    np.testing.assert_allclose(db, (lp - lm) / (2 * eps), rtol=2e-7, atol=1e-9)
+
+
+def test_bias_gradient_against_torch_autograd_and_closed_form():
+    B, H, N, d = 1, 3, 40, 8
+    q, k, v, dout = (_rand(B, H, N, d) for _ in range(4))
+    slopes = _alibi_slopes(H)
+    b = torch.tensor(-math.log(N), dtype=torch.float64, requires_grad=True)
+    tq, tk, tv, tdo = (torch.tensor(x, dtype=torch.float64) for x in (q, k, v, dout))
+    idx = torch.arange(N)
+    t = tq @ tk.transpose(-1, -2) / math.sqrt(d) + b \
+        - torch.tensor(slopes)[None, :, None, None] * (idx[:, None] - idx[None, :]).abs().double()
+    p = torch.sigmoid(t) * (idx[None, :] <= idx[:, None]).double()
+    ((p @ tv) * tdo).sum().backward()
+    db = orc.sigmoid_attn_bias_grad(q, k, v, dout, -math.log(N), True, slopes)
+    np.testing.assert_allclose(db.sum(), b.grad.item(), rtol=1e-11)
+    # Q = 0, no ALiBi: every P is sigma(b), so db_i = sigma(b)(1 - sigma(b)) dO_i . sum_{j visible} V_j
+    z = np.zeros_like(q)
+    sb = 1 / (1 + math.exp(0.9))
+    got = orc.sigmoid_attn_bias_grad(z, k, v, dout, -0.9, True)
+    ref = sb * (1 - sb) * np.einsum("bhid,bhid->bhi", dout, np.cumsum(v, axis=2))
+    np.testing.assert_allclose(got, ref, rtol=1e-12, atol=1e-14)
+    # consistent with the backward pass: dQ_i = (1/sqrt d) sum_j dS_ij K_j, so with every K_j = c
+    # (the same vector), dQ_i = db_i c / sqrt(d)
+    c = RNG.standard_normal(d)
+    kc = np.broadcast_to(c, k.shape).copy()
+    dq, _, _ = orc.sigmoid_attn_bwd(q, kc, v, dout, -0.3, False)
+    dbc = orc.sigmoid_attn_bias_grad(q, kc, v, dout, -0.3, False)
+    np.testing.assert_allclose(dq, dbc[..., None] * c / math.sqrt(d), rtol=1e-11, atol=1e-14)
+
+
 # ------------------------------------------------------------------ sampled-row entry points
 
 @pytest.mark.parametrize("causal", [False, True])
