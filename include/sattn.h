@@ -140,6 +140,23 @@ size_t softmax_attn_bwd_workspace_bytes(int B, int H, int N, int d, sattn_dtype 
 /* Human-readable text for an SATTN_ERR_* code (static storage). */
 const char* sattn_strerror(int code);
 
+/* Backward with the gradient of a learnable bias (Section 5.4 and Appendix G.4 train with a
+ * learnable scalar b, one per layer; Appendix F.1 backward table: T = S + b, so dL/db is the
+ * sum of dS over the pairs the bias enters).  Same as sigmoid_attn_bwd (bf16 or fp32), and the
+ * dQ pass also writes db_rows[b][h][i] = sum_j dS_ij (device pointer, contiguous [B,H,N] fp32,
+ * required: the gradient of a bias per query row).  If db is not NULL (device pointer, B*H
+ * fp32), a second small kernel sums each head's rows in a fixed order into db[b*H+h]; the
+ * scalar gradient of a bias shared by a layer is the sum of those B*H numbers.  Errors as
+ * sigmoid_attn_bwd; SATTN_ERR_NULL for db_rows == NULL. */
+int sigmoid_attn_bwd_bias_grad(const void* q, const void* k, const void* v, const void* dout,
+                               void* dq, void* dk, void* dv, float* db_rows, float* db,
+                               int B, int H, int N, int d, sattn_dtype dtype,
+                               float bias, int causal, const float* alibi_slopes,
+                               const sattn_strides* sq, const sattn_strides* sk,
+                               const sattn_strides* sv, const sattn_strides* sdout,
+                               const sattn_strides* sdq, const sattn_strides* sdk,
+                               const sattn_strides* sdv, void* stream);
+
 /* Variable-length batches (Appendix G.4, training details of the speech models: dynamic
  * batching, and every sample's own length gives its bias b = -ln(n), a non-trainable bias
  * vector for the minibatch): the B

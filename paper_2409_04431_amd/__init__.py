@@ -9,6 +9,7 @@ from .binding import (  # noqa: F401
     library_path,
     load_library,
     sigmoid_attn_bwd,
+    sigmoid_attn_bwd_bias_grad,
     sigmoid_attn_bwd_compiler_scheduled,
     sigmoid_attn_bwd_dkdv,
     sigmoid_attn_bwd_dq,

@@ -50,6 +50,8 @@ def load_library():
     lib.sigmoid_attn_fwd_compiler_scheduled.restype = i
     lib.sigmoid_attn_bwd_compiler_scheduled.argtypes = lib.sigmoid_attn_bwd.argtypes
     lib.sigmoid_attn_bwd_compiler_scheduled.restype = i
+    lib.sigmoid_attn_bwd_bias_grad.argtypes = [_vp] * 9 + [i, i, i, i, i, f, i, _vp] + [_SP] * 7 + [_vp]
+    lib.sigmoid_attn_bwd_bias_grad.restype = i
     ip = ctypes.c_void_p
     lib.sigmoid_attn_varlen_fwd.argtypes = [_vp, _vp, _vp, _vp, ip, _vp, i, i, i, i, i, f, i, _vp, _SP, _SP, _SP, _SP, _vp]
     lib.sigmoid_attn_varlen_fwd.restype = i
@@ -222,6 +224,25 @@ def sigmoid_attn_bwd(q, k, v, dout, dq, dk, dv, bias, causal=False, alibi_slopes
                               _st(dq), _st(dk), _st(dv), wp, wb, _stream())
     _raise(rc, _entry)
     return dq, dk, dv
+
+
+def sigmoid_attn_bwd_bias_grad(q, k, v, dout, dq, dk, dv, db_rows, bias, causal=False, alibi_slopes=None, db=None):
+    """sigmoid_attn_bwd plus db_rows[b,h,i] = sum_j dS_ij (fp32 [B,H,N]) and, if given, db[b,h] = sum_i db_rows."""
+    lib = load_library()
+    _check(q, k, v, dout, dq, dk, dv)
+    B, H, N, d = q.shape
+    for t, shape, what in ((db_rows, (B, H, N), "db_rows"), (db, (B, H), "db")):
+        if t is None and what == "db":
+            continue
+        if t is None or not t.is_cuda or t.dtype != torch.float32 or tuple(t.shape) != shape or not t.is_contiguous():
+            raise SattnError(f"{what} must be a contiguous CUDA float32 tensor of shape {shape}")
+    rc = lib.sigmoid_attn_bwd_bias_grad(q.data_ptr(), k.data_ptr(), v.data_ptr(), dout.data_ptr(), dq.data_ptr(),
+                                        dk.data_ptr(), dv.data_ptr(), _vp(db_rows.data_ptr()),
+                                        _vp(db.data_ptr()) if db is not None else None, B, H, N, d, _dtype_code(q),
+                                        float(bias), int(bool(causal)), _slopes_ptr(alibi_slopes, H), _st(q), _st(k),
+                                        _st(v), _st(dout), _st(dq), _st(dk), _st(dv), _stream())
+    _raise(rc, "sigmoid_attn_bwd_bias_grad")
+    return dq, dk, dv, db_rows, db
 
 
 def sigmoid_attn_bwd_compiler_scheduled(q, k, v, dout, dq, dk, dv, bias, causal=False, alibi_slopes=None):

@@ -168,8 +168,16 @@ int launch_bwd_bf16(BwdParams p, int causal, bool alibi, int parts, hipStream_t 
   if (parts & kBwdDkDv)
     SATTN_DISPATCH2(causal, alibi,
                     rc = launch(attn_bwd_kernel<D, BWD_DKDV, A, B2, SOFTMAX, PIN>, grid, block, lds + lds_stat, st, p));
-  if (rc == SATTN_OK && (parts & kBwdDq))
+  if (rc == SATTN_OK && (parts & kBwdDq)) {
+    if constexpr (!SOFTMAX && PIN) {
+      if (p.db_rows) {  // the dQ pass that also writes the row sums of dS
+        SATTN_DISPATCH2(causal, alibi,
+                        rc = launch(attn_bwd_kernel<D, BWD_DQ_DB, A, B2, false, true>, grid, block, lds, st, p));
+        return rc;
+      }
+    }
     SATTN_DISPATCH2(causal, alibi, rc = launch(attn_bwd_kernel<D, BWD_DQ, A, B2, SOFTMAX, PIN>, grid, block, lds, st, p));
+  }
   return rc;
 }
 
@@ -196,6 +204,7 @@ struct BwdArgs {
   const sattn_strides *sq, *sk, *sv, *so, *sdout, *sdq, *sdk, *sdv;
   void* workspace; size_t workspace_bytes; int parts; void* stream;
   const int* cu_seqlens = nullptr; const float* bias_vec = nullptr;  // variable-length batches
+  float* db_rows = nullptr; float* db = nullptr;                     // bias gradient (dense sigmoid only)
 };
 
 template <bool SOFTMAX, bool PIN = true>
@@ -219,8 +228,13 @@ int bwd_impl(const BwdArgs& a) {
     p.q = q; p.k = k; p.v = v; p.dout = dout;
     p.slopes = a.slopes; p.B = a.B; p.H = a.H; p.N = a.N;
     p.scale = inv_sqrt_d; p.bias = a.bias;
-    if (a.d == 128) return launch_bwd_f32<128>(p, a.causal, alibi, a.parts, dq, dk, dv, st);
-    return launch_bwd_f32<64>(p, a.causal, alibi, a.parts, dq, dk, dv, st);
+    p.db_rows = a.db_rows; p.db_sb = (int64_t)a.H * a.N; p.db_sh = a.N;
+    if (a.d == 128) rc = launch_bwd_f32<128>(p, a.causal, alibi, a.parts, dq, dk, dv, st);
+    else rc = launch_bwd_f32<64>(p, a.causal, alibi, a.parts, dq, dk, dv, st);
+    if (rc == SATTN_OK && a.db)
+      rc = launch(rowsum_reduce_kernel, dim3(a.B * a.H), dim3(256), 0, st, (const float*)a.db_rows, a.db, a.H, a.N,
+                  p.db_sb, p.db_sh);
+    return rc;
   }
   BwdParams p{};
   p.q = q; p.k = k; p.v = v; p.dout = dout; p.dq = dq; p.dk = dk; p.dv = dv;
@@ -230,6 +244,7 @@ int bwd_impl(const BwdArgs& a) {
   p.nscale_log2 = -kLog2e * inv_sqrt_d;
   p.nbias_log2 = -a.bias * kLog2e;
   p.cu_seqlens = a.cu_seqlens; p.bias_vec = a.bias_vec;
+  p.db_rows = a.db_rows; p.db_sb = (int64_t)a.H * a.N; p.db_sh = a.N;
   if (SOFTMAX) {
     if (!a.lse) return SATTN_ERR_NULL;
     if ((rc = make_ref(a.o, a.so, a.H, a.N, a.d, a.dtype, &o))) return rc;
@@ -244,8 +259,12 @@ int bwd_impl(const BwdArgs& a) {
     if (rc) return rc;
     p.lse = a.lse; p.dvec = dvec;
   }
-  if (a.d == 128) return launch_bwd_bf16<128, SOFTMAX, PIN>(p, a.causal, alibi, a.parts, st);
-  return launch_bwd_bf16<64, SOFTMAX, PIN>(p, a.causal, alibi, a.parts, st);
+  if (a.d == 128) rc = launch_bwd_bf16<128, SOFTMAX, PIN>(p, a.causal, alibi, a.parts, st);
+  else rc = launch_bwd_bf16<64, SOFTMAX, PIN>(p, a.causal, alibi, a.parts, st);
+  if (rc == SATTN_OK && a.db)
+    rc = launch(rowsum_reduce_kernel, dim3(a.B * a.H), dim3(256), 0, st, (const float*)a.db_rows, a.db, a.H, a.N,
+                p.db_sb, p.db_sh);
+  return rc;
 }
 
 }  // namespace
@@ -287,6 +306,20 @@ int sigmoid_attn_bwd_dq(const void* q, const void* k, const void* v, const void*
                         const sattn_strides* sdout, const sattn_strides* sdq, void* stream) {
   BwdArgs a{q, k, v, nullptr, nullptr, dout, dq, nullptr, nullptr, B, H, N, d, dtype, bias, causal, alibi_slopes,
             sq, sk, sv, nullptr, sdout, sdq, nullptr, nullptr, nullptr, 0, kBwdDq, stream};
+  return bwd_impl<false>(a);
+}
+
+int sigmoid_attn_bwd_bias_grad(const void* q, const void* k, const void* v, const void* dout, void* dq, void* dk,
+                               void* dv, float* db_rows, float* db, int B, int H, int N, int d, sattn_dtype dtype,
+                               float bias, int causal, const float* alibi_slopes, const sattn_strides* sq,
+                               const sattn_strides* sk, const sattn_strides* sv, const sattn_strides* sdout,
+                               const sattn_strides* sdq, const sattn_strides* sdk, const sattn_strides* sdv,
+                               void* stream) {
+  if (!db_rows) return SATTN_ERR_NULL;
+  if (((uintptr_t)db_rows & 3) != 0 || ((uintptr_t)db & 3) != 0) return SATTN_ERR_ALIGN;
+  BwdArgs a{q, k, v, nullptr, nullptr, dout, dq, dk, dv, B, H, N, d, dtype, bias, causal, alibi_slopes,
+            sq, sk, sv, nullptr, sdout, sdq, sdk, sdv, nullptr, 0, kBwdDkDv | kBwdDq, stream};
+  a.db_rows = db_rows; a.db = db;
   return bwd_impl<false>(a);
 }
 

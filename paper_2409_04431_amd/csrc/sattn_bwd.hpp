@@ -26,7 +26,9 @@
 
 namespace sattn {
 
-enum BwdMode { BWD_DQ = 0, BWD_DKDV = 1 };
+// BWD_DQ_DB is the dQ pass that also sums dS along every query row (the gradient of a bias
+// added to that row's logits); everything that is not BWD_DKDV is a dQ pass.
+enum BwdMode { BWD_DQ = 0, BWD_DKDV = 1, BWD_DQ_DB = 2 };
 
 struct BwdParams {
   TensorRef q, k, v, dout, dq, dk, dv;
@@ -41,6 +43,9 @@ struct BwdParams {
   // variable-length batches (nullptr otherwise), as in the forward parameters
   const int* cu_seqlens;
   const float* bias_vec;
+  // BWD_DQ_DB: row sums of dS, element (b, h, i) at b*db_sb + h*db_sh + i
+  float* db_rows;
+  int64_t db_sb, db_sh;
 };
 
 // One swizzle for tiles that are read both row-wise (ds_read_b128, 32 rows at one logical
@@ -138,6 +143,7 @@ struct BwdWave {
   int ai, h;              // this lane's stationary row, lane half
   float nscale, nbias, sl2;
   float nlse, dstat;      // softmax DQ: this lane's -lse*log2e and D
+  float dbs[4];           // BWD_DQ_DB: partial sums of this lane's dS elements (element e in [e & 3])
 };
 
 // Every MFMA of the backward kernel is a volatile asm statement with fixed register classes:
@@ -237,6 +243,7 @@ __device__ __forceinline__ void bwd_step(BwdWave<D, MODE>& W, bool doA, bool doS
         pr[r] = keep ? pr[r] : 0.f;
         ds[r] = keep ? ds[r] : 0.f;
       }
+      if (MODE == BWD_DQ_DB) W.dbs[r & 3] += ds[r];
     }
     if (MODE == BWD_DKDV) { W.pb[PAR ^ 1][0] = pack8(pr); W.pb[PAR ^ 1][1] = pack8(pr + 8); }
     W.dsb[PAR ^ 1][0] = pack8(ds);
@@ -275,18 +282,18 @@ __device__ __forceinline__ void bwd_step(BwdWave<D, MODE>& W, bool doA, bool doS
 
 // Arithmetic of one chunk as 4 groups of four elements.  Per group:
 //   F x4 (u = s*scale + bias[+alibi])  X x4 (2^u)  A x4 (1+e)  R x4 (p = 1/.)  [C x4]
-//   Q x4 (p - p^2)  M x4 (dS = . * dP)  [D x4]  [CP x2 pack P]  CD x2 pack dS
+//   Q x4 (p - p^2)  M x4 (dS = . * dP)  [D x4]  [B x4 row sum]  [CP x2 pack P]  CD x2 pack dS
 // MASK adds C (keep = key_of_reg(e) >= thr for DKDV, <= thr for DQ; p = keep ? p : 0) and
 // D (dS = keep ? dS : 0): selects, so that a masked element is exactly zero whatever the
 // logit and dP registers hold (they are not even finite in a dead pipeline stage).
 template <int MODE, bool MASK>
 struct BsigLayout {
-  static constexpr int nC = MASK ? 4 : 0, nP = MODE == BWD_DKDV ? 2 : 0;
-  static constexpr int oX = 4, oA = 8, oR = 12, oC = 16, oQ = 16 + nC, oM = oQ + 4, oD = oM + 4, oP = oD + nC,
-                       oS = oP + nP, OPG = oS + 2, NOPS = 4 * OPG;
+  static constexpr int nC = MASK ? 4 : 0, nP = MODE == BWD_DKDV ? 2 : 0, nB = MODE == BWD_DQ_DB ? 4 : 0;
+  static constexpr int oX = 4, oA = 8, oR = 12, oC = 16, oQ = 16 + nC, oM = oQ + 4, oD = oM + 4, oB = oD + nC,
+                       oP = oB + nB, oS = oP + nP, OPG = oS + 2, NOPS = 4 * OPG;
 };
 template <int D, int MODE, bool ALIBI, bool MASK, int I>
-__device__ __forceinline__ void bsig_op(const BwdWave<D, MODE>& W, const f32x16& s, const f32x16& dp, float (&u)[16],
+__device__ __forceinline__ void bsig_op(BwdWave<D, MODE>& W, const f32x16& s, const f32x16& dp, float (&u)[16],
                                         float (&v)[16], uint32_t (&wp)[8], uint32_t (&wd)[8], uint64_t (&km)[16],
                                         float nbias_v, float sl2_v, float dist0, float dstep, int thr) {
   using L = BsigLayout<MODE, MASK>;
@@ -317,8 +324,10 @@ __device__ __forceinline__ void bsig_op(const BwdWave<D, MODE>& W, const f32x16&
     asm volatile("v_fma_f32 %0, -%1, %1, %1" : "=v"(v[e]) : "v"(u[e]));
   } else if constexpr (i < L::oD) {
     asm volatile("v_mul_f32 %0, %0, %1" : "+v"(v[e]) : "v"(dp[e]));
-  } else if constexpr (i < L::oP) {
+  } else if constexpr (i < L::oB) {
     asm volatile("v_cndmask_b32_e64 %0, 0, %0, %1" : "+v"(v[e]) : "s"(km[e]));
+  } else if constexpr (i < L::oP) {
+    asm volatile("v_add_f32 %0, %0, %1" : "+v"(W.dbs[i - L::oB]) : "v"(v[e]));
   } else if constexpr (i < L::oS) {
     constexpr int j = 2 * G + (i - L::oP);
     asm volatile("v_cvt_pk_bf16_f32 %0, %1, %2" : "=v"(wp[j]) : "v"(u[2 * j]), "v"(u[2 * j + 1]));
@@ -328,7 +337,7 @@ __device__ __forceinline__ void bsig_op(const BwdWave<D, MODE>& W, const f32x16&
   }
 }
 template <int D, int MODE, bool ALIBI, bool MASK, int LO, int HI>
-__device__ __forceinline__ void bsig_ops(const BwdWave<D, MODE>& W, const f32x16& s, const f32x16& dp, float (&u)[16],
+__device__ __forceinline__ void bsig_ops(BwdWave<D, MODE>& W, const f32x16& s, const f32x16& dp, float (&u)[16],
                                          float (&v)[16], uint32_t (&wp)[8], uint32_t (&wd)[8], uint64_t (&km)[16],
                                          float nbias_v, float sl2_v, float dist0, float dstep, int thr) {
   if constexpr (LO < HI) {
@@ -454,7 +463,7 @@ attn_bwd_kernel(const BwdParams p) {
   const int logical = xcd_remap(blockIdx.x, total);
   const int bh = logical / p.n_blocks;
   // causal: heavy blocks first (late query blocks for DQ, early key blocks for DKDV)
-  const int blk = (CAUSAL && MODE == BWD_DQ) ? (p.n_blocks - 1 - logical % p.n_blocks) : (logical % p.n_blocks);
+  const int blk = (CAUSAL && MODE != BWD_DKDV) ? (p.n_blocks - 1 - logical % p.n_blocks) : (logical % p.n_blocks);
   const int b = bh / p.H, hd = bh % p.H;
   int N = p.N;
   int64_t tok0 = 0;
@@ -500,7 +509,8 @@ attn_bwd_kernel(const BwdParams p) {
   for (int r = 0; r < 16; ++r)  // DKDV: |i-j| = (bl - ai) + key_of_reg(r); DQ: (ai - bl) - key_of_reg(r)
     W.cinit[r] = FOLD ? (MODE == BWD_DKDV ? W.sl2 : -W.sl2) * (float)key_of_reg(r) / p.nscale_log2 : 0.f;
   W.nlse = 0.f; W.dstat = 0.f;
-  if (SOFTMAX && MODE == BWD_DQ) {
+  W.dbs[0] = W.dbs[1] = W.dbs[2] = W.dbs[3] = 0.f;
+  if (SOFTMAX && MODE != BWD_DKDV) {
     W.nlse = -p.lse[(int64_t)bh * N + ai_ld] * kLog2e;
     W.dstat = p.dvec[(int64_t)bh * N + ai_ld];
   }
@@ -710,6 +720,12 @@ attn_bwd_kernel(const BwdParams p) {
   }
   __builtin_amdgcn_s_waitcnt(0x0F70);  // no staging may be in flight when the workgroup's LDS is released
 
+  if (MODE == BWD_DQ_DB) {
+    // the two halves of the wave hold the sums over different keys of the same query row
+    float rs = (W.dbs[0] + W.dbs[1]) + (W.dbs[2] + W.dbs[3]);
+    rs += __shfl_xor(rs, 32);
+    if (h == 0 && ai < N) p.db_rows[b * p.db_sb + hd * p.db_sh + tok0 + ai] = rs;
+  }
   if (ai < N) {
     const float sc = p.inv_sqrt_d;  // dQ and dK carry the 1/sqrt(d) of the logits
     __bf16* o0 = (MODE == BWD_DKDV ? (__bf16*)p.dk.ptr + b * p.dk.sb + hd * p.dk.sh + (tok0 + ai) * p.dk.ss
@@ -764,6 +780,24 @@ rowsum_do_o_kernel(TensorRef o, TensorRef dout, float* dvec, int B, int H, int N
 #pragma unroll
   for (int m = 8; m >= 1; m >>= 1) acc += __shfl_xor(acc, m, 16);
   if (row < rows && sub == 0) dvec[row] = acc;
+}
+
+// out[bh] = sum over i < N of rows[b*sb + h*sh + i], in a fixed order (deterministic).
+__global__ void __launch_bounds__(256)
+rowsum_reduce_kernel(const float* rows, float* out, int H, int N, int64_t sb, int64_t sh) {
+  __shared__ float part[256];
+  const int bh = blockIdx.x, tid = threadIdx.x;
+  const float* r = rows + (bh / H) * sb + (bh % H) * sh;
+  float acc = 0.f;
+  for (int i = tid; i < N; i += 256) acc += r[i];
+  part[tid] = acc;
+  __syncthreads();
+#pragma unroll
+  for (int m = 128; m >= 1; m >>= 1) {
+    if (tid < m) part[tid] += part[tid + m];
+    __syncthreads();
+  }
+  if (tid == 0) out[bh] = part[0];
 }
 
 }  // namespace sattn

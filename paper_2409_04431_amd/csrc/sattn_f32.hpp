@@ -29,6 +29,9 @@ struct F32Params {
   int B, H, N, n_blocks;
   float scale;   // 1/sqrt(d)
   float bias;
+  // DQ only, optional: row sums of dS, element (b, h, i) at b*db_sb + h*db_sh + i
+  float* db_rows;
+  int64_t db_sb, db_sh;
 };
 
 __device__ __forceinline__ f32x16 mfma_f32(float a, float b, f32x16 c) {
@@ -83,6 +86,7 @@ sigmoid_f32_kernel(const F32Params p) {
       if (MODE == F32_DKDV) acc1[dt][r] = 0.f;
     }
   const float slope = ALIBI ? p.slopes[hd] : 0.f;
+  float dbsum = 0.f;  // DQ: sum of this lane's dS elements
 
   // range of streaming tiles (32 rows each)
   const int a_hi = (blk * BS + BS < N ? blk * BS + BS : N) - 1;
@@ -139,6 +143,7 @@ sigmoid_f32_kernel(const F32Params p) {
       pv = keep ? pv : 0.f;
       pr[r] = pv;
       if (TWO) ds[r] = pv * (1.0f - pv) * dp[r];
+      if (MODE == F32_DQ) dbsum += ds[r];
     }
     // second products: acc^T[d][a] += Y^T[d][bi] * W[bi][a]
 #pragma unroll
@@ -156,6 +161,11 @@ sigmoid_f32_kernel(const F32Params p) {
     }
   }
 
+  if (MODE == F32_DQ) {
+    // the two halves of the wave hold the sums over different keys of the same query row
+    dbsum += __shfl_xor(dbsum, 32);
+    if (p.db_rows && h == 0 && ai < N) p.db_rows[b * p.db_sb + hd * p.db_sh + ai] = dbsum;
+  }
   if (ai < N) {
     const float osc = MODE == F32_FWD ? 1.0f : p.scale;  // dQ, dK carry the 1/sqrt(d) of the logits
     float* o0 = (float*)p.out0.ptr + b * p.out0.sb + hd * p.out0.sh + (int64_t)ai * p.out0.ss;

@@ -90,6 +90,16 @@ def test_varlen_entry_points_reject_bad_arguments(lib):
     assert lib.sigmoid_attn_varlen_bwd(*bptrs, 0x8000, None, 2, 4, 512, 128, 1, 0.0, 1, None, *([None] * 7), None) == -3
 
 
+def test_bias_gradient_entry_point_rejects_bad_arguments(lib):
+    ptrs = [0x1000, 0x2000, 0x3000, 0x4000, 0x5000, 0x6000, 0x7000]
+    tail = [1, 1, 16, 64, 0, 0.0, 0, None, *([None] * 7), None]
+    assert lib.sigmoid_attn_bwd_bias_grad(*ptrs, None, None, *tail) == -1            # db_rows is required
+    assert lib.sigmoid_attn_bwd_bias_grad(*ptrs, 0x8002, None, *tail) == -4          # fp32 alignment
+    assert lib.sigmoid_attn_bwd_bias_grad(*ptrs, 0x8000, 0x9001, *tail) == -4
+    tail[3] = 100
+    assert lib.sigmoid_attn_bwd_bias_grad(*ptrs, 0x8000, None, *tail) == -3          # head dimension
+
+
 def test_binding_refuses_cpu_tensors():
     import torch
     t = torch.zeros(1, 1, 8, 64, dtype=torch.bfloat16)

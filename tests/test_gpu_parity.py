@@ -393,3 +393,42 @@ def test_varlen_batches_match_per_sequence_calls_and_oracle(d, causal, alibi, pe
         rdq, rdk, rdv = orc.sigmoid_attn_bwd(qs, ks, vs, ds, bs, causal, slopes)
         for name, got, ref in (("o", o1, ro), ("dq", dq1, rdq), ("dk", dk1, rdk), ("dv", dv1, rdv)):
             assert nerr(got, ref) <= TOL_BF16, f"{name} of sequence {s_}"
+
+
+# ------------------------------------------------------------------ learnable-bias gradient
+
+@pytest.mark.parametrize("B,H,N,d,causal,alibi,dtype", [
+    (1, 2, 1024, 128, True, False, torch.bfloat16),     # steady-state loop, diagonal, fill and drain
+    (2, 2, 1000, 128, False, True, torch.bfloat16),     # ragged last chunk
+    (1, 3, 333, 64, True, True, torch.bfloat16),
+    (2, 1, 1, 64, False, False, torch.bfloat16),
+    (1, 2, 200, 128, True, True, torch.float32),
+    (1, 2, 130, 64, False, False, torch.float32),
+])
+def test_bias_gradient_rows_match_oracle_and_leave_the_other_gradients_unchanged(B, H, N, d, causal, alibi, dtype):
+    inp = _rand_inputs(B, H, N, d, seed=977 + N, dtype=dtype)
+    slopes = W.alibi_slopes(H) if alibi else None
+    bias = -math.log(max(N, 2))
+    q, k, v, do = (_dev(inp[n]) for n in ("q", "k", "v", "dout"))
+    sl = _dev(slopes) if slopes is not None else None
+    dq, dk, dv, dq0, dk0, dv0 = (torch.full_like(q, float("nan")) for _ in range(6))
+    rows = torch.full((B, H, N), float("nan"), dtype=torch.float32, device="cuda")
+    db = torch.full((B, H), float("nan"), dtype=torch.float32, device="cuda")
+    sa.sigmoid_attn_bwd_bias_grad(q, k, v, do, dq, dk, dv, rows, bias, causal, sl, db=db)
+    sa.sigmoid_attn_bwd(q, k, v, do, dq0, dk0, dv0, bias, causal, sl)
+    torch.cuda.synchronize()
+    # the same arithmetic produces dQ, dK, dV with or without the row sums
+    assert torch.equal(dq, dq0) and torch.equal(dk, dk0) and torch.equal(dv, dv0)
+    f = lambda t: inp[t].double().numpy()
+    ref = orc.sigmoid_attn_bias_grad(f("q"), f("k"), f("v"), f("dout"), bias, causal, slopes)
+    # dS is formed in fp32 from exact products of the stored inputs and summed in fp32 in both
+    # paths, so the row sums carry fp32-level error, far below the bf16 bar of the outputs
+    tol = 2e-4 if dtype == torch.bfloat16 else TOL_F32
+    assert nerr(rows, ref) <= tol
+    assert nerr(db, ref.sum(-1)) <= tol
+    np.testing.assert_allclose(db.cpu().numpy(), rows.double().sum(-1).cpu().numpy(), rtol=1e-5, atol=1e-6 * np.abs(ref).max() * N)
+    # without db only the rows are written
+    rows2 = torch.full_like(rows, float("nan"))
+    sa.sigmoid_attn_bwd_bias_grad(q, k, v, do, dq, dk, dv, rows2, bias, causal, sl)
+    torch.cuda.synchronize()
+    assert torch.equal(rows2, rows)
