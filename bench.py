@@ -144,6 +144,8 @@ def main():
         "device": {"name": props.name, "compute_units": props.multi_processor_count,
                    "clock_mhz": getattr(props, "clock_rate", 0) / 1e3 or None,
                    "sustained_mfma_bf16_tflops": sustained_peak},
+        "fwd_waves_per_workgroup": (sa.sattn_fwd_waves(cfg.B, cfg.H, cfg.N, cfg.d, cfg.causal)
+                                    if cfg.dtype == torch.bfloat16 else None),
         "fwd_ms": fwd_ms, "fwd_tflops": flops_f / fwd_ms / 1e9,
         "fwd_frac_of_bf16_mfma_peak": flops_f / fwd_ms / 1e9 / MFMA_BF16_PEAK_TFLOPS,
     }

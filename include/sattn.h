@@ -137,6 +137,17 @@ int softmax_attn_bwd(const void* q, const void* k, const void* v, const void* o,
 
 size_t softmax_attn_bwd_workspace_bytes(int B, int H, int N, int d, sattn_dtype dtype);
 
+/* Forward tile shape (Appendix F.5: the block shape of the forward kernel is a tuning
+ * parameter; the paper's second variant halves B_c for d = 64).  Here the tuned quantity is
+ * B_r = 32 * waves query rows per workgroup, waves in {4, 8}; the bf16 forward entry points
+ * (sigmoid, softmax, variable-length) choose it per problem from d, B*H*N, the mask and the
+ * number of compute units.  sattn_fwd_waves returns that choice (or a negative error code);
+ * sattn_set_fwd_waves forces it process-wide for measurements (0 = back to automatic; not
+ * thread-safe against concurrent launches).  The outputs are bit-identical for both shapes:
+ * the arithmetic of a query row does not depend on which rows share its workgroup. */
+int sattn_fwd_waves(int B, int H, int N, int d, int causal);
+int sattn_set_fwd_waves(int waves);
+
 /* Human-readable text for an SATTN_ERR_* code (static storage). */
 const char* sattn_strerror(int code);
 

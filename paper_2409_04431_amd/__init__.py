@@ -21,7 +21,9 @@ from .binding import (  # noqa: F401
     softmax_attn_bwd,
     softmax_attn_bwd_workspace_bytes,
     softmax_attn_fwd,
+    sattn_fwd_waves,
     sattn_mfma_bf16_probe,
+    sattn_set_fwd_waves,
     sattn_strerror,
     sattn_version,
 )

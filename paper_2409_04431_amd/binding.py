@@ -73,6 +73,10 @@ def load_library():
     lib.sattn_strerror.restype = ctypes.c_char_p
     lib.sattn_mfma_bf16_probe.argtypes = [i, i, _vp, _vp]
     lib.sattn_mfma_bf16_probe.restype = i
+    lib.sattn_fwd_waves.argtypes = [i, i, i, i, i]
+    lib.sattn_fwd_waves.restype = i
+    lib.sattn_set_fwd_waves.argtypes = [i]
+    lib.sattn_set_fwd_waves.restype = i
     lib.sattn_version.argtypes = []
     lib.sattn_version.restype = i
     _lib = lib
@@ -130,6 +134,19 @@ def sigmoid_attn_varlen_bwd(q, k, v, dout, dq, dk, dv, cu_seqlens, max_seqlen, b
                                      _st3(dq), _st3(dk), _st3(dv), _stream())
     _raise(rc, "sigmoid_attn_varlen_bwd")
     return dq, dk, dv
+
+
+def sattn_fwd_waves(B, H, N, d, causal=False):
+    """Waves (32 query rows each) per workgroup the bf16 forward kernels use for this problem."""
+    rc = load_library().sattn_fwd_waves(B, H, N, d, int(bool(causal)))
+    if rc < 0:
+        _raise(rc, "sattn_fwd_waves")
+    return rc
+
+
+def sattn_set_fwd_waves(waves):
+    """Force 4 or 8 forward waves per workgroup for measurements; 0 restores the automatic choice."""
+    _raise(load_library().sattn_set_fwd_waves(int(waves)), "sattn_set_fwd_waves")
 
 
 def sattn_mfma_bf16_probe(blocks, iters, sink):

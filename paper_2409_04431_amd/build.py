@@ -1,11 +1,14 @@
 """Compile the HIP library for gfx950 with hipcc (cross-compiles without a GPU)."""
 import os
 import subprocess
+from concurrent.futures import ThreadPoolExecutor
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
+OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libsattn.so")
-SOURCES = ["sattn_api.hip"]
+# one translation unit per head dimension and direction, so the kernels compile in parallel
+SOURCES = ["sattn_api.hip", "sattn_fwd_d64.hip", "sattn_fwd_d128.hip", "sattn_bwd_d64.hip", "sattn_bwd_d128.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
@@ -14,16 +17,27 @@ HIPCC_FLAGS = [
 ]
 
 
-def build_library(verbose=False):
-    """(Re)build libsattn.so in-tree.  Always compiles."""
-    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc] + HIPCC_FLAGS + ["-o", LIB] + [os.path.join(CSRC, s) for s in SOURCES]
+def _run(cmd):
     res = subprocess.run(cmd, capture_output=True, text=True)
     err = "\n".join(l for l in res.stderr.splitlines() if "is not a recognized feature" not in l)
     if res.returncode != 0:
-        raise RuntimeError("hipcc failed:\n" + err)
-    if verbose and err.strip():
-        print(err)
+        raise RuntimeError("hipcc failed:\n" + " ".join(cmd) + "\n" + err)
+    return err
+
+
+def build_library(verbose=False, jobs=None):
+    """(Re)build libsattn.so in-tree.  Always compiles every source."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    os.makedirs(OBJ, exist_ok=True)
+    compile_flags = [f for f in HIPCC_FLAGS if f != "-shared"]
+    objs = [os.path.join(OBJ, s + ".o") for s in SOURCES]
+    cmds = [[hipcc] + compile_flags + ["-c", "-o", o, os.path.join(CSRC, s)] for s, o in zip(SOURCES, objs)]
+    jobs = jobs or min(len(cmds), os.cpu_count() or 1, 16)
+    with ThreadPoolExecutor(max_workers=jobs) as pool:
+        msgs = list(pool.map(_run, cmds))
+    msgs.append(_run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs))
+    if verbose and any(m.strip() for m in msgs):
+        print("\n".join(m for m in msgs if m.strip()))
     return LIB
 
 

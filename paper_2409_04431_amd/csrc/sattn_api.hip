@@ -5,9 +5,8 @@
 #include <hip/hip_runtime.h>
 #include <math.h>
 
-#include "sattn_bwd.hpp"
 #include "sattn_f32.hpp"
-#include "sattn_fwd.hpp"
+#include "sattn_launch.hpp"
 
 using namespace sattn;
 
@@ -40,6 +39,24 @@ __global__ void __launch_bounds__(256) mfma_bf16_probe_kernel(float* sink, int i
   sink[(size_t)blockIdx.x * 256 + threadIdx.x] = s;
 }
 
+// out[bh] = sum over i < N of rows[b*sb + h*sh + i], in a fixed order (deterministic).
+__global__ void __launch_bounds__(256)
+rowsum_reduce_kernel(const float* rows, float* out, int H, int N, int64_t sb, int64_t sh) {
+  __shared__ float part[256];
+  const int bh = blockIdx.x, tid = threadIdx.x;
+  const float* r = rows + (bh / H) * sb + (bh % H) * sh;
+  float acc = 0.f;
+  for (int i = tid; i < N; i += 256) acc += r[i];
+  part[tid] = acc;
+  __syncthreads();
+#pragma unroll
+  for (int m = 128; m >= 1; m >>= 1) {
+    if (tid < m) part[tid] += part[tid + m];
+    __syncthreads();
+  }
+  if (tid == 0) out[bh] = part[0];
+}
+
 // Validate one tensor and turn it into a TensorRef.  Strides are in elements.
 int make_ref(const void* ptr, const sattn_strides* s, int H, int N, int d, sattn_dtype dt, TensorRef* out) {
   if (!ptr) return SATTN_ERR_NULL;
@@ -59,6 +76,33 @@ int make_ref(const void* ptr, const sattn_strides* s, int H, int N, int d, sattn
   return SATTN_OK;
 }
 
+// Waves (32 query rows each) per forward workgroup.  Head dimension 64: two 4-wave workgroups
+// share a compute unit (their LDS rings both fit) and overlap each other's barriers, which
+// measured faster than one 8-wave workgroup at every size.  Head dimension 128: the ring of an
+// 8-wave workgroup fills the LDS either way, so 4-wave workgroups halve the waves per compute
+// unit; they only pay when the problem is too small to give every compute unit an 8-wave one
+// (causal problems a little longer: their workgroups run heavy-first, so a second, light round
+// of workgroups costs less than idle compute units in the first).
+int g_fwd_waves = 0;  // 0: choose per problem; 4 or 8: forced (sattn_set_fwd_waves)
+
+int compute_units() {
+  int dev = 0, n = 0;
+  if (hipGetDevice(&dev) != hipSuccess ||
+      hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) {
+    (void)hipGetLastError();
+    return 256;
+  }
+  return n;
+}
+
+int pick_fwd_waves(int B, int H, int N, int d, int causal) {
+  if (g_fwd_waves) return g_fwd_waves;
+  if (d == 64) return 4;
+  const int64_t wg4 = (int64_t)B * H * ((N + 127) / 128);
+  const int64_t cus = compute_units();
+  return wg4 <= (causal ? cus + cus / 2 : cus) ? 4 : 8;
+}
+
 int check_shape(int B, int H, int N, int d, sattn_dtype dt) {
   if (dt != SATTN_BF16 && dt != SATTN_F32) return SATTN_ERR_UNSUPPORTED;
   if (d != 64 && d != 128) return SATTN_ERR_UNSUPPORTED;
@@ -68,42 +112,7 @@ int check_shape(int B, int H, int N, int d, sattn_dtype dt) {
   return SATTN_OK;
 }
 
-template <typename K, typename... Args>
-int launch(K kernel, dim3 grid, dim3 block, size_t lds, hipStream_t st, Args... args) {
-  if (lds > 0 &&
-      hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
-    (void)hipGetLastError();
-    return SATTN_ERR_LAUNCH;
-  }
-  hipLaunchKernelGGL(kernel, grid, block, lds, st, args...);
-  return hipGetLastError() == hipSuccess ? SATTN_OK : SATTN_ERR_LAUNCH;
-}
-
-// Expand two runtime flags into the constexpr bools A and B2 visible to CALL.
-#define SATTN_DISPATCH2(F1, F2, CALL)                          \
-  do {                                                         \
-    if (F1) {                                                  \
-      if (F2) { constexpr bool A = true, B2 = true; CALL; }    \
-      else { constexpr bool A = true, B2 = false; CALL; }      \
-    } else {                                                   \
-      if (F2) { constexpr bool A = false, B2 = true; CALL; }   \
-      else { constexpr bool A = false, B2 = false; CALL; }     \
-    }                                                          \
-  } while (0)
-
 // ---------------------------------------------------------------- forward
-constexpr int kFwdWaves = 8;  // waves per forward workgroup, 32 query rows each
-
-template <int D, bool SOFTMAX, bool PIN>
-int launch_fwd_bf16(const FwdParams& p, int causal, bool alibi, hipStream_t st) {
-  constexpr size_t lds = 6 * 64 * D * 2;  // 3 K slots + 3 V slots of 64 keys
-  dim3 grid(p.n_qblocks * p.B * p.H), block(64 * kFwdWaves);
-  int rc = SATTN_OK;
-  SATTN_DISPATCH2(causal, alibi,
-                  rc = launch(attn_fwd_kernel<D, kFwdWaves, A, B2, SOFTMAX, PIN>, grid, block, lds, st, p));
-  return rc;
-}
-
 template <int D>
 int launch_fwd_f32(const F32Params& p, int causal, bool alibi, hipStream_t st) {
   dim3 grid(p.n_blocks * p.B * p.H), block(256);
@@ -146,41 +155,15 @@ int fwd_impl(const FwdArgs& a) {
   p.q = q; p.k = k; p.v = v; p.o = o;
   p.slopes = a.slopes; p.lse = a.lse;
   p.B = a.B; p.H = a.H; p.N = a.N;
-  p.n_qblocks = (a.N + 32 * kFwdWaves - 1) / (32 * kFwdWaves);
   p.nscale_log2 = (SOFTMAX ? kLog2e : -kLog2e) * inv_sqrt_d;
   p.nbias_log2 = -a.bias * kLog2e;
   p.cu_seqlens = a.cu_seqlens; p.bias_vec = a.bias_vec;
-  if (a.d == 128) return launch_fwd_bf16<128, SOFTMAX, PIN>(p, a.causal, alibi, st);
-  return launch_fwd_bf16<64, SOFTMAX, PIN>(p, a.causal, alibi, st);
+  const int waves = pick_fwd_waves(a.B, a.H, a.N, a.d, a.causal);
+  if (a.d == 128) return launch_fwd_bf16<128>(p, waves, SOFTMAX, PIN, a.causal, alibi, st);
+  return launch_fwd_bf16<64>(p, waves, SOFTMAX, PIN, a.causal, alibi, st);
 }
 
 // ---------------------------------------------------------------- backward
-enum BwdPart { kBwdDkDv = 1, kBwdDq = 2 };
-
-template <int D, bool SOFTMAX, bool PIN>
-int launch_bwd_bf16(BwdParams p, int causal, bool alibi, int parts, hipStream_t st) {
-  p.n_blocks = (p.N + 127) / 128;
-  dim3 grid(p.n_blocks * p.B * p.H);
-  int rc = SATTN_OK;
-  constexpr size_t lds = 4 * 2 * 64 * D * 2;                    // 4 ring slots of two 64-row tiles
-  constexpr size_t lds_stat = SOFTMAX ? 4 * 128 * sizeof(float) : 0;  // per-slot lse and D of the query tile
-  dim3 block(256);
-  if (parts & kBwdDkDv)
-    SATTN_DISPATCH2(causal, alibi,
-                    rc = launch(attn_bwd_kernel<D, BWD_DKDV, A, B2, SOFTMAX, PIN>, grid, block, lds + lds_stat, st, p));
-  if (rc == SATTN_OK && (parts & kBwdDq)) {
-    if constexpr (!SOFTMAX && PIN) {
-      if (p.db_rows) {  // the dQ pass that also writes the row sums of dS
-        SATTN_DISPATCH2(causal, alibi,
-                        rc = launch(attn_bwd_kernel<D, BWD_DQ_DB, A, B2, false, true>, grid, block, lds, st, p));
-        return rc;
-      }
-    }
-    SATTN_DISPATCH2(causal, alibi, rc = launch(attn_bwd_kernel<D, BWD_DQ, A, B2, SOFTMAX, PIN>, grid, block, lds, st, p));
-  }
-  return rc;
-}
-
 template <int D>
 int launch_bwd_f32(F32Params p, int causal, bool alibi, int parts, TensorRef dq, TensorRef dk, TensorRef dv,
                    hipStream_t st) {
@@ -259,8 +242,8 @@ int bwd_impl(const BwdArgs& a) {
     if (rc) return rc;
     p.lse = a.lse; p.dvec = dvec;
   }
-  if (a.d == 128) rc = launch_bwd_bf16<128, SOFTMAX, PIN>(p, a.causal, alibi, a.parts, st);
-  else rc = launch_bwd_bf16<64, SOFTMAX, PIN>(p, a.causal, alibi, a.parts, st);
+  if (a.d == 128) rc = launch_bwd_bf16<128>(p, SOFTMAX, PIN, a.causal, alibi, a.parts, st);
+  else rc = launch_bwd_bf16<64>(p, SOFTMAX, PIN, a.causal, alibi, a.parts, st);
   if (rc == SATTN_OK && a.db)
     rc = launch(rowsum_reduce_kernel, dim3(a.B * a.H), dim3(256), 0, st, (const float*)a.db_rows, a.db, a.H, a.N,
                 p.db_sb, p.db_sh);
@@ -425,6 +408,18 @@ int sattn_mfma_bf16_probe(int blocks, int iters, float* sink, void* stream) {
   return launch(mfma_bf16_probe_kernel, dim3(blocks), dim3(256), 0, (hipStream_t)stream, sink, iters);
 }
 
-int sattn_version(void) { return 100; }
+int sattn_set_fwd_waves(int waves) {
+  if (waves != 0 && waves != 4 && waves != 8) return SATTN_ERR_UNSUPPORTED;
+  g_fwd_waves = waves;
+  return SATTN_OK;
+}
+
+int sattn_fwd_waves(int B, int H, int N, int d, int causal) {
+  if (B <= 0 || H <= 0 || N <= 0) return SATTN_ERR_SHAPE;
+  if (d != 64 && d != 128) return SATTN_ERR_UNSUPPORTED;
+  return pick_fwd_waves(B, H, N, d, causal);
+}
+
+int sattn_version(void) { return 101; }
 
 }  // extern "C"

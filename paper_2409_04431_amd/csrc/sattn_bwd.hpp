@@ -782,22 +782,4 @@ rowsum_do_o_kernel(TensorRef o, TensorRef dout, float* dvec, int B, int H, int N
   if (row < rows && sub == 0) dvec[row] = acc;
 }
 
-// out[bh] = sum over i < N of rows[b*sb + h*sh + i], in a fixed order (deterministic).
-__global__ void __launch_bounds__(256)
-rowsum_reduce_kernel(const float* rows, float* out, int H, int N, int64_t sb, int64_t sh) {
-  __shared__ float part[256];
-  const int bh = blockIdx.x, tid = threadIdx.x;
-  const float* r = rows + (bh / H) * sb + (bh % H) * sh;
-  float acc = 0.f;
-  for (int i = tid; i < N; i += 256) acc += r[i];
-  part[tid] = acc;
-  __syncthreads();
-#pragma unroll
-  for (int m = 128; m >= 1; m >>= 1) {
-    if (tid < m) part[tid] += part[tid + m];
-    __syncthreads();
-  }
-  if (tid == 0) out[bh] = part[0];
-}
-
 }  // namespace sattn

@@ -1,0 +1,38 @@
+// Definition of launch_bwd_bf16<D>; included by the one translation unit that instantiates it.
+#pragma once
+#include "sattn_launch.hpp"
+
+namespace sattn {
+
+template <int D, bool SOFTMAX, bool PIN>
+int launch_bwd_variant(BwdParams p, int causal, bool alibi, int parts, hipStream_t st) {
+  p.n_blocks = (p.N + 127) / 128;
+  dim3 grid(p.n_blocks * p.B * p.H);
+  int rc = SATTN_OK;
+  constexpr size_t lds = 4 * 2 * 64 * D * 2;                    // 4 ring slots of two 64-row tiles
+  constexpr size_t lds_stat = SOFTMAX ? 4 * 128 * sizeof(float) : 0;  // per-slot lse and D of the query tile
+  dim3 block(256);
+  if (parts & kBwdDkDv)
+    SATTN_DISPATCH2(causal, alibi,
+                    rc = launch(attn_bwd_kernel<D, BWD_DKDV, A, B2, SOFTMAX, PIN>, grid, block, lds + lds_stat, st, p));
+  if (rc == SATTN_OK && (parts & kBwdDq)) {
+    if constexpr (!SOFTMAX && PIN) {
+      if (p.db_rows) {  // the dQ pass that also writes the row sums of dS
+        SATTN_DISPATCH2(causal, alibi,
+                        rc = launch(attn_bwd_kernel<D, BWD_DQ_DB, A, B2, false, true>, grid, block, lds, st, p));
+        return rc;
+      }
+    }
+    SATTN_DISPATCH2(causal, alibi, rc = launch(attn_bwd_kernel<D, BWD_DQ, A, B2, SOFTMAX, PIN>, grid, block, lds, st, p));
+  }
+  return rc;
+}
+
+template <int D>
+int launch_bwd_bf16(BwdParams p, bool softmax, bool pin, int causal, bool alibi, int parts, hipStream_t st) {
+  if (softmax) return launch_bwd_variant<D, true, false>(p, causal, alibi, parts, st);
+  if (pin) return launch_bwd_variant<D, false, true>(p, causal, alibi, parts, st);
+  return launch_bwd_variant<D, false, false>(p, causal, alibi, parts, st);
+}
+
+}  // namespace sattn

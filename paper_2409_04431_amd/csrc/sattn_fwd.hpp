@@ -60,7 +60,12 @@ struct DmaStager {
   static_assert((BC * CPR) % (64 * NW) == 0, "tile must split evenly over the waves");
   const char* base;       // first row of the next tile to stage (wave-uniform, advances per tile)
   const char* base_last;  // row N-1 (wave-uniform)
-  uint32_t off[NI];       // this lane's byte offset inside a tile (constant)
+  // This lane's byte offset inside a tile for instruction n is
+  //   row_of(n) * row_bytes + col_bytes(n) = (rowoff0 + n * RPI * row_bytes) + (col0 ^ XCOL * n'):
+  // successive instructions of a wave move RPI rows down, which flips swizzle bits that no
+  // lane-dependent term touches, so two registers describe all NI offsets; the row step goes
+  // into the scalar base.
+  uint32_t rowoff0, col0;
   uint32_t tile_bytes, row_bytes;
   int j0;                 // first key of the next tile to stage
   __device__ __forceinline__ static int row_of(int n, int wave, int lane) { return (wave * NI + n) * RPI + lane / CPR; }
@@ -68,6 +73,12 @@ struct DmaStager {
     const int r = row_of(n, wave, lane);
     return (uint32_t)(((lane % CPR) ^ (IS_V ? Swz<D>::v(r) : Swz<D>::k(r))) * 16);
   }
+  // col_bytes(n) ^ col_bytes(0): the K swizzle takes row bits 0..3 (D = 128) or 1..3 (D = 64),
+  // instruction n adds n * RPI = 4n (8n) to the row; the V swizzle only takes bits the lane sets.
+  __host__ __device__ static constexpr uint32_t xcol(int n) {
+    return IS_V ? 0u : (uint32_t)((D == 128 ? (4 * n) & 15 : (4 * n) & 7) << 4);
+  }
+  static_assert(IS_V || (D == 128 ? 4 * (NI - 1) < 16 && (NI * RPI) % 8 == 0 : NI <= 2), "row step must stay inside the swizzle field");
   // The host side guarantees that one (batch, head) slice spans < 4 GiB.
   __device__ __forceinline__ void init(const __bf16* b, int64_t ss, int N, int wave, int lane) {
     base = (const char*)b;
@@ -75,23 +86,38 @@ struct DmaStager {
     row_bytes = (uint32_t)(ss * 2);
     tile_bytes = BC * row_bytes;
     j0 = 0;
-#pragma unroll
-    for (int n = 0; n < NI; ++n) off[n] = row_of(n, wave, lane) * row_bytes + col_bytes(n, wave, lane);
+    rowoff0 = row_of(0, wave, lane) * row_bytes;
+    col0 = col_bytes(0, wave, lane);
   }
   __device__ __forceinline__ static void load(uint32_t o, const char* sbase, uint32_t m0v) {
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(o), "s"(sbase), "s"(m0v) : "memory");
+  }
+  // Same with the lane offset (c ^ X) + r formed in place, so that it never occupies a register
+  // between tiles.
+  template <uint32_t X>
+  __device__ __forceinline__ static void load_xad(uint32_t c, uint32_t r, const char* sbase, uint32_t m0v) {
+    uint32_t t;
+    asm volatile("v_xad_u32 %0, %1, %2, %3\n\ts_mov_b32 m0, %5\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %4"
+                 : "=&v"(t) : "v"(c), "s"(X), "v"(r), "s"(sbase), "s"(m0v) : "memory");
+  }
+  template <int n>
+  __device__ __forceinline__ void issue_full(uint32_t lds, int wave) const {
+    if constexpr (n < NI) {
+      load_xad<xcol(n)>(col0, rowoff0, base + (uint32_t)(n * RPI) * row_bytes, lds + (wave * NI + n) * 1024);
+      issue_full<n + 1>(lds, wave);
+    }
   }
   // Issue the loads of the next tile into the LDS tile at byte address `lds` (wave-uniform)
   // and advance.  Rows past the end re-read row N-1.
   __device__ __forceinline__ void issue(uint32_t lds, int N, int wave, int lane) {
     if (j0 + BC <= N) {
-#pragma unroll
-      for (int n = 0; n < NI; ++n) load(off[n], base, lds + (wave * NI + n) * 1024);
+      issue_full<0>(lds, wave);
     } else if (j0 < N) {
       const uint32_t to_last = (uint32_t)(N - 1 - j0) * row_bytes;
 #pragma unroll
       for (int n = 0; n < NI; ++n) {
-        const uint32_t o = (j0 + row_of(n, wave, lane) < N) ? off[n] : to_last + col_bytes(n, wave, lane);
+        const int r = row_of(n, wave, lane);
+        const uint32_t o = (j0 + r < N ? r * row_bytes : to_last) + col_bytes(n, wave, lane);
         load(o, base, lds + (wave * NI + n) * 1024);
       }
     } else {

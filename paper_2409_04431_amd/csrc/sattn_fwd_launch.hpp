@@ -1,0 +1,29 @@
+// Definition of launch_fwd_bf16<D>; included by the one translation unit that instantiates it.
+#pragma once
+#include "sattn_launch.hpp"
+
+namespace sattn {
+
+template <int D, int NW, bool SOFTMAX, bool PIN>
+int launch_fwd_variant(FwdParams p, int causal, bool alibi, hipStream_t st) {
+  constexpr size_t lds = 6 * 64 * D * 2;  // 3 K slots + 3 V slots of 64 keys
+  p.n_qblocks = (p.N + 32 * NW - 1) / (32 * NW);
+  dim3 grid(p.n_qblocks * p.B * p.H), block(64 * NW);
+  int rc = SATTN_OK;
+  SATTN_DISPATCH2(causal, alibi, rc = launch(attn_fwd_kernel<D, NW, A, B2, SOFTMAX, PIN>, grid, block, lds, st, p));
+  return rc;
+}
+
+template <int D>
+int launch_fwd_bf16(FwdParams p, int waves, bool softmax, bool pin, int causal, bool alibi, hipStream_t st) {
+  if (waves == 4) {
+    if (softmax) return launch_fwd_variant<D, 4, true, false>(p, causal, alibi, st);
+    if (pin) return launch_fwd_variant<D, 4, false, true>(p, causal, alibi, st);
+    return launch_fwd_variant<D, 4, false, false>(p, causal, alibi, st);
+  }
+  if (softmax) return launch_fwd_variant<D, 8, true, false>(p, causal, alibi, st);
+  if (pin) return launch_fwd_variant<D, 8, false, true>(p, causal, alibi, st);
+  return launch_fwd_variant<D, 8, false, false>(p, causal, alibi, st);
+}
+
+}  // namespace sattn

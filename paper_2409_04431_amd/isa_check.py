@@ -22,6 +22,7 @@ import re
 import subprocess
 import sys
 import tempfile
+from concurrent.futures import ThreadPoolExecutor
 
 from .build import CSRC, HIPCC_FLAGS, SOURCES
 
@@ -151,16 +152,17 @@ def compile_to_asm(extra_flags=()):
     """Device-only assembly of the library sources with the product's flags."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     flags = [f for f in HIPCC_FLAGS if f not in ("-fPIC", "-shared")]
-    texts = []
     with tempfile.TemporaryDirectory() as td:
-        for s in SOURCES:
+        def one(s):
             out = os.path.join(td, s + ".s")
             cmd = [hipcc] + flags + list(extra_flags) + ["--cuda-device-only", "-S", "-o", out, os.path.join(CSRC, s)]
             res = subprocess.run(cmd, capture_output=True, text=True)
             if res.returncode != 0:
                 raise RuntimeError("hipcc failed:\n" + res.stderr)
             with open(out) as f:
-                texts.append(f.read())
+                return f.read()
+        with ThreadPoolExecutor(max_workers=min(len(SOURCES), os.cpu_count() or 1, 16)) as pool:
+            texts = list(pool.map(one, SOURCES))
     return "\n".join(texts)
 
 

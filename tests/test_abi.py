@@ -100,6 +100,22 @@ def test_bias_gradient_entry_point_rejects_bad_arguments(lib):
     assert lib.sigmoid_attn_bwd_bias_grad(*ptrs, 0x8000, None, *tail) == -3          # head dimension
 
 
+def test_forward_wave_choice(lib):
+    # d = 64 always takes 4-wave workgroups; d = 128 only while the problem is small
+    assert sa.sattn_fwd_waves(32, 12, 4096, 64) == 4
+    assert sa.sattn_fwd_waves(8, 16, 4096, 128, True) == 8
+    assert sa.sattn_fwd_waves(1, 2, 512, 128) == 4
+    assert lib.sattn_fwd_waves(1, 1, 16, 100, 0) == -3
+    assert lib.sattn_fwd_waves(0, 1, 16, 64, 0) == -2
+    assert lib.sattn_set_fwd_waves(3) == -3
+    try:
+        sa.sattn_set_fwd_waves(8)
+        assert sa.sattn_fwd_waves(1, 2, 512, 128) == 8 and sa.sattn_fwd_waves(1, 2, 512, 64) == 8
+    finally:
+        sa.sattn_set_fwd_waves(0)
+    assert sa.sattn_fwd_waves(1, 2, 512, 64) == 4
+
+
 def test_binding_refuses_cpu_tensors():
     import torch
     t = torch.zeros(1, 1, 8, 64, dtype=torch.bfloat16)

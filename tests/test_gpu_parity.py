@@ -432,3 +432,35 @@ def test_bias_gradient_rows_match_oracle_and_leave_the_other_gradients_unchanged
     sa.sigmoid_attn_bwd_bias_grad(q, k, v, do, dq, dk, dv, rows2, bias, causal, sl)
     torch.cuda.synchronize()
     assert torch.equal(rows2, rows)
+
+
+# ------------------------------------------------------------------ forward tile shape
+
+@pytest.mark.parametrize("B,H,N,d,causal,alibi", [(1, 2, 700, 128, True, True), (2, 2, 333, 64, False, True),
+                                                  (1, 1, 1025, 128, False, False), (1, 3, 96, 64, True, False)])
+def test_forward_tile_shapes_agree_bit_for_bit_and_with_the_oracle(B, H, N, d, causal, alibi):
+    inp = _rand_inputs(B, H, N, d, seed=31 + N)
+    slopes = W.alibi_slopes(H) if alibi else None
+    sl = _dev(slopes) if slopes is not None else None
+    bias = -math.log(N)
+    q, k, v = (_dev(inp[n]) for n in ("q", "k", "v"))
+    outs, souts = {}, {}
+    try:
+        for waves in (4, 8):
+            sa.sattn_set_fwd_waves(waves)
+            o = torch.full_like(q, float("nan"))
+            so = torch.full_like(q, float("nan"))
+            lse = torch.full((B, H, N), float("nan"), dtype=torch.float32, device="cuda")
+            sa.sigmoid_attn_fwd(q, k, v, o, bias, causal, sl)
+            sa.softmax_attn_fwd(q, k, v, so, lse, causal, sl)
+            torch.cuda.synchronize()
+            outs[waves], souts[waves] = o, (so, lse)
+    finally:
+        sa.sattn_set_fwd_waves(0)
+    assert torch.equal(outs[4], outs[8])
+    assert torch.equal(souts[4][0], souts[8][0]) and torch.equal(souts[4][1], souts[8][1])
+    f = lambda t: inp[t].double().numpy()
+    assert nerr(outs[4], orc.sigmoid_attn_fwd(f("q"), f("k"), f("v"), bias, causal, slopes)) <= TOL_BF16
+    ro, rl = orc.softmax_attn_fwd(f("q"), f("k"), f("v"), causal, slopes)
+    assert nerr(souts[4][0], ro) <= TOL_BF16
+    assert np.abs(souts[4][1].cpu().numpy() - rl).max() <= 1e-3
