@@ -101,6 +101,34 @@ def sigmoid_attn_bias_grad(q, k, v, dout, bias, causal=False, alibi_slopes=None)
     return db
 
 
+# ---- shared key/value heads (multi-query attention, Section 5.1: one K/V head for all query
+# heads; grouped in general).  Query head h reads K/V head h // (H / Hkv).  By definition this
+# is dense attention on the K/V heads repeated over their groups, and a shared head's gradient
+# is the sum of the gradients of its copies.
+
+def _expand_kv(x, H):
+    x = _f64(x)
+    Hkv = x.shape[1]
+    assert H % Hkv == 0
+    return np.ascontiguousarray(np.repeat(x, H // Hkv, axis=1)), Hkv
+
+
+def sigmoid_attn_mqa_fwd(q, k, v, bias, causal=False, alibi_slopes=None):
+    H = np.shape(q)[1]
+    ke, _ = _expand_kv(k, H)
+    ve, _ = _expand_kv(v, H)
+    return sigmoid_attn_fwd(q, ke, ve, bias, causal, alibi_slopes)
+
+
+def sigmoid_attn_mqa_bwd(q, k, v, dout, bias, causal=False, alibi_slopes=None):
+    B, H, N, d = np.shape(q)
+    ke, Hkv = _expand_kv(k, H)
+    ve, _ = _expand_kv(v, H)
+    dq, dke, dve = sigmoid_attn_bwd(q, ke, ve, dout, bias, causal, alibi_slopes)
+    fold = lambda g: g.reshape(B, Hkv, H // Hkv, N, d).sum(axis=2)
+    return dq, fold(dke), fold(dve)
+
+
 def softmax_attn_fwd(q, k, v, causal=False, alibi_slopes=None):
     """Returns (O, LSE) with LSE [B,H,N] in natural-log units."""
     q, k, v = _f64(q), _f64(k), _f64(v)

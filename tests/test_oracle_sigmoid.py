@@ -303,6 +303,50 @@ def test_bias_gradient_against_torch_autograd_and_closed_form():
     np.testing.assert_allclose(dq, dbc[..., None] * c / math.sqrt(d), rtol=1e-11, atol=1e-14)
 
 
+# ------------------------------------------------------------------ shared key/value heads
+
+@pytest.mark.parametrize("Hkv", [1, 2, 4])
+def test_shared_kv_heads_against_torch_autograd(Hkv):
+    B, H, N, d = 2, 4, 19, 8
+    q, dout = _rand(B, H, N, d), _rand(B, H, N, d)
+    k, v = _rand(B, Hkv, N, d), _rand(B, Hkv, N, d)
+    slopes = _alibi_slopes(H)
+    bias = -math.log(N)
+    tq, tk, tv = (torch.tensor(x, dtype=torch.float64, requires_grad=True) for x in (q, k, v))
+    idx = torch.arange(N)
+    g = H // Hkv
+    # head h of Q against head h // g of K, V, written with an explicit index (no repeat)
+    kv_of = torch.arange(H) // g
+    t = torch.einsum("bhid,bhjd->bhij", tq, tk[:, kv_of]) / math.sqrt(d) + bias \
+        - torch.tensor(slopes)[None, :, None, None] * (idx[:, None] - idx[None, :]).abs().double()
+    p = torch.sigmoid(t) * (idx[None, :] <= idx[:, None]).double()
+    o = torch.einsum("bhij,bhjd->bhid", p, tv[:, kv_of])
+    (o * torch.tensor(dout)).sum().backward()
+    np.testing.assert_allclose(orc.sigmoid_attn_mqa_fwd(q, k, v, bias, True, slopes), o.detach().numpy(),
+                               rtol=1e-11, atol=1e-13)
+    dq, dk, dv = orc.sigmoid_attn_mqa_bwd(q, k, v, dout, bias, True, slopes)
+    assert dk.shape == k.shape and dv.shape == v.shape
+    np.testing.assert_allclose(dq, tq.grad.numpy(), rtol=1e-10, atol=1e-13)
+    np.testing.assert_allclose(dk, tk.grad.numpy(), rtol=1e-10, atol=1e-13)
+    np.testing.assert_allclose(dv, tv.grad.numpy(), rtol=1e-10, atol=1e-13)
+    if Hkv == H:   # one K/V head per query head is plain attention
+        assert np.array_equal(orc.sigmoid_attn_mqa_fwd(q, k, v, bias, True, slopes),
+                              orc.sigmoid_attn_fwd(q, k, v, bias, True, slopes))
+
+
+def test_multi_query_zero_logit_closed_form():
+    # Q = 0, one K/V head: every query head outputs sigma(b) * sum_j V_j, and dV_j collects
+    # sigma(b) * dO_i over every query head and row
+    B, H, N, d = 1, 3, 6, 4
+    k, v, dout = _rand(B, 1, N, d), _rand(B, 1, N, d), _rand(B, H, N, d)
+    q = np.zeros((B, H, N, d))
+    sb = 1 / (1 + math.exp(0.8))
+    o = orc.sigmoid_attn_mqa_fwd(q, k, v, -0.8)
+    np.testing.assert_allclose(o, np.broadcast_to(sb * v.sum(2, keepdims=True), o.shape), rtol=1e-13)
+    _, _, dv = orc.sigmoid_attn_mqa_bwd(q, k, v, dout, -0.8)
+    np.testing.assert_allclose(dv, np.broadcast_to(sb * dout.sum((1, 2), keepdims=True), dv.shape), rtol=1e-12)
+
+
 # ------------------------------------------------------------------ sampled-row entry points
 
 @pytest.mark.parametrize("causal", [False, True])
