@@ -151,6 +151,27 @@ int sattn_set_fwd_waves(int waves);
 /* Human-readable text for an SATTN_ERR_* code (static storage). */
 const char* sattn_strerror(int code);
 
+/* Shared key/value heads (Section 5.1, multi-query attention: one K/V head for all query
+ * heads; any Hkv that divides H is accepted).  Query head h attends to K/V head
+ * h / (H / Hkv).  q, o, dout, dq are [B, H, N, d]; k, v, dk, dv are [B, Hkv, N, d] (strides as
+ * usual, NULL = contiguous with that head count).  dK/dV of a shared head is the sum over its
+ * query heads, accumulated in fp32 inside one workgroup (no atomics, no workspace).  bf16
+ * only (SATTN_ERR_UNSUPPORTED for fp32 unless Hkv == H); SATTN_ERR_SHAPE if Hkv does not
+ * divide H.  Otherwise as sigmoid_attn_fwd / sigmoid_attn_bwd. */
+int sigmoid_attn_mqa_fwd(const void* q, const void* k, const void* v, void* o,
+                         int B, int H, int Hkv, int N, int d, sattn_dtype dtype,
+                         float bias, int causal, const float* alibi_slopes,
+                         const sattn_strides* sq, const sattn_strides* sk,
+                         const sattn_strides* sv, const sattn_strides* so, void* stream);
+int sigmoid_attn_mqa_bwd(const void* q, const void* k, const void* v, const void* dout,
+                         void* dq, void* dk, void* dv,
+                         int B, int H, int Hkv, int N, int d, sattn_dtype dtype,
+                         float bias, int causal, const float* alibi_slopes,
+                         const sattn_strides* sq, const sattn_strides* sk,
+                         const sattn_strides* sv, const sattn_strides* sdout,
+                         const sattn_strides* sdq, const sattn_strides* sdk,
+                         const sattn_strides* sdv, void* stream);
+
 /* Backward with the gradient of a learnable bias (Section 5.4 and Appendix G.4 train with a
  * learnable scalar b, one per layer; Appendix F.1 backward table: T = S + b, so dL/db is the
  * sum of dS over the pairs the bias enters).  Same as sigmoid_attn_bwd (bf16 or fp32), and the

@@ -16,6 +16,8 @@ from .binding import (  # noqa: F401
     sigmoid_attn_bwd_workspace_bytes,
     sigmoid_attn_fwd,
     sigmoid_attn_fwd_compiler_scheduled,
+    sigmoid_attn_mqa_bwd,
+    sigmoid_attn_mqa_fwd,
     sigmoid_attn_varlen_bwd,
     sigmoid_attn_varlen_fwd,
     softmax_attn_bwd,

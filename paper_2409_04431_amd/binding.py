@@ -50,6 +50,10 @@ def load_library():
     lib.sigmoid_attn_fwd_compiler_scheduled.restype = i
     lib.sigmoid_attn_bwd_compiler_scheduled.argtypes = lib.sigmoid_attn_bwd.argtypes
     lib.sigmoid_attn_bwd_compiler_scheduled.restype = i
+    lib.sigmoid_attn_mqa_fwd.argtypes = [_vp, _vp, _vp, _vp, i, i, i, i, i, i, f, i, _vp, _SP, _SP, _SP, _SP, _vp]
+    lib.sigmoid_attn_mqa_fwd.restype = i
+    lib.sigmoid_attn_mqa_bwd.argtypes = [_vp] * 7 + [i, i, i, i, i, i, f, i, _vp] + [_SP] * 7 + [_vp]
+    lib.sigmoid_attn_mqa_bwd.restype = i
     lib.sigmoid_attn_bwd_bias_grad.argtypes = [_vp] * 9 + [i, i, i, i, i, f, i, _vp] + [_SP] * 7 + [_vp]
     lib.sigmoid_attn_bwd_bias_grad.restype = i
     ip = ctypes.c_void_p
@@ -133,6 +137,39 @@ def sigmoid_attn_varlen_bwd(q, k, v, dout, dq, dk, dv, cu_seqlens, max_seqlen, b
                                      _slopes_ptr(alibi_slopes, H), _st3(q), _st3(k), _st3(v), _st3(dout),
                                      _st3(dq), _st3(dk), _st3(dv), _stream())
     _raise(rc, "sigmoid_attn_varlen_bwd")
+    return dq, dk, dv
+
+
+def _check_mqa(q, kv, *qlike):
+    _check(q, *qlike)
+    _check(*kv)
+    B, H, N, d = q.shape
+    Bk, Hkv, Nk, dk = kv[0].shape
+    if (Bk, Nk, dk) != (B, N, d) or Hkv <= 0 or H % Hkv:
+        raise SattnError(f"K/V shape {tuple(kv[0].shape)} does not match Q {tuple(q.shape)} with shared heads")
+    return B, H, Hkv, N, d
+
+
+def sigmoid_attn_mqa_fwd(q, k, v, o, bias, causal=False, alibi_slopes=None):
+    """Forward with shared K/V heads: q, o [B,H,N,d]; k, v [B,Hkv,N,d], Hkv divides H."""
+    lib = load_library()
+    B, H, Hkv, N, d = _check_mqa(q, (k, v), o)
+    rc = lib.sigmoid_attn_mqa_fwd(q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(), B, H, Hkv, N, d,
+                                  _dtype_code(q), float(bias), int(bool(causal)), _slopes_ptr(alibi_slopes, H),
+                                  _st(q), _st(k), _st(v), _st(o), _stream())
+    _raise(rc, "sigmoid_attn_mqa_fwd")
+    return o
+
+
+def sigmoid_attn_mqa_bwd(q, k, v, dout, dq, dk, dv, bias, causal=False, alibi_slopes=None):
+    """Backward with shared K/V heads: dk, dv [B,Hkv,N,d] are summed over each head's query group."""
+    lib = load_library()
+    B, H, Hkv, N, d = _check_mqa(q, (k, v, dk, dv), dout, dq)
+    rc = lib.sigmoid_attn_mqa_bwd(q.data_ptr(), k.data_ptr(), v.data_ptr(), dout.data_ptr(), dq.data_ptr(),
+                                  dk.data_ptr(), dv.data_ptr(), B, H, Hkv, N, d, _dtype_code(q), float(bias),
+                                  int(bool(causal)), _slopes_ptr(alibi_slopes, H), _st(q), _st(k), _st(v),
+                                  _st(dout), _st(dq), _st(dk), _st(dv), _stream())
+    _raise(rc, "sigmoid_attn_mqa_bwd")
     return dq, dk, dv
 
 

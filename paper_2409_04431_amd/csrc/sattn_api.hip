@@ -126,16 +126,20 @@ struct FwdArgs {
   int B, H, N, d; sattn_dtype dtype; float bias; int causal; const float* slopes;
   const sattn_strides *sq, *sk, *sv, *so; void* stream;
   const int* cu_seqlens = nullptr; const float* bias_vec = nullptr;  // variable-length batches
+  int Hkv = 0;                                                       // K/V heads (0: one per query head)
 };
 
 template <bool SOFTMAX, bool PIN = true>
 int fwd_impl(const FwdArgs& a) {
   int rc = check_shape(a.B, a.H, a.N, a.d, a.dtype);
   if (rc) return rc;
+  const int Hkv = a.Hkv ? a.Hkv : a.H;
+  if (Hkv <= 0 || a.H % Hkv) return SATTN_ERR_SHAPE;
+  if (Hkv != a.H && (SOFTMAX || !PIN || a.dtype != SATTN_BF16)) return SATTN_ERR_UNSUPPORTED;
   TensorRef q, k, v, o;
   if ((rc = make_ref(a.q, a.sq, a.H, a.N, a.d, a.dtype, &q))) return rc;
-  if ((rc = make_ref(a.k, a.sk, a.H, a.N, a.d, a.dtype, &k))) return rc;
-  if ((rc = make_ref(a.v, a.sv, a.H, a.N, a.d, a.dtype, &v))) return rc;
+  if ((rc = make_ref(a.k, a.sk, Hkv, a.N, a.d, a.dtype, &k))) return rc;
+  if ((rc = make_ref(a.v, a.sv, Hkv, a.N, a.d, a.dtype, &v))) return rc;
   if ((rc = make_ref(a.o, a.so, a.H, a.N, a.d, a.dtype, &o))) return rc;
   if (SOFTMAX && !a.lse) return SATTN_ERR_NULL;
   hipStream_t st = (hipStream_t)a.stream;
@@ -158,6 +162,7 @@ int fwd_impl(const FwdArgs& a) {
   p.nscale_log2 = (SOFTMAX ? kLog2e : -kLog2e) * inv_sqrt_d;
   p.nbias_log2 = -a.bias * kLog2e;
   p.cu_seqlens = a.cu_seqlens; p.bias_vec = a.bias_vec;
+  p.kv_group = a.H / Hkv;
   const int waves = pick_fwd_waves(a.B, a.H, a.N, a.d, a.causal);
   if (a.d == 128) return launch_fwd_bf16<128>(p, waves, SOFTMAX, PIN, a.causal, alibi, st);
   return launch_fwd_bf16<64>(p, waves, SOFTMAX, PIN, a.causal, alibi, st);
@@ -188,20 +193,24 @@ struct BwdArgs {
   void* workspace; size_t workspace_bytes; int parts; void* stream;
   const int* cu_seqlens = nullptr; const float* bias_vec = nullptr;  // variable-length batches
   float* db_rows = nullptr; float* db = nullptr;                     // bias gradient (dense sigmoid only)
+  int Hkv = 0;                                                       // K/V heads (0: one per query head)
 };
 
 template <bool SOFTMAX, bool PIN = true>
 int bwd_impl(const BwdArgs& a) {
   int rc = check_shape(a.B, a.H, a.N, a.d, a.dtype);
   if (rc) return rc;
+  const int Hkv = a.Hkv ? a.Hkv : a.H;
+  if (Hkv <= 0 || a.H % Hkv) return SATTN_ERR_SHAPE;
+  if (Hkv != a.H && (SOFTMAX || !PIN || a.dtype != SATTN_BF16)) return SATTN_ERR_UNSUPPORTED;
   TensorRef q, k, v, dout, dq{}, dk{}, dv{}, o{};
   if ((rc = make_ref(a.q, a.sq, a.H, a.N, a.d, a.dtype, &q))) return rc;
-  if ((rc = make_ref(a.k, a.sk, a.H, a.N, a.d, a.dtype, &k))) return rc;
-  if ((rc = make_ref(a.v, a.sv, a.H, a.N, a.d, a.dtype, &v))) return rc;
+  if ((rc = make_ref(a.k, a.sk, Hkv, a.N, a.d, a.dtype, &k))) return rc;
+  if ((rc = make_ref(a.v, a.sv, Hkv, a.N, a.d, a.dtype, &v))) return rc;
   if ((rc = make_ref(a.dout, a.sdout, a.H, a.N, a.d, a.dtype, &dout))) return rc;
   if ((a.parts & kBwdDq) && (rc = make_ref(a.dq, a.sdq, a.H, a.N, a.d, a.dtype, &dq))) return rc;
-  if ((a.parts & kBwdDkDv) && (rc = make_ref(a.dk, a.sdk, a.H, a.N, a.d, a.dtype, &dk))) return rc;
-  if ((a.parts & kBwdDkDv) && (rc = make_ref(a.dv, a.sdv, a.H, a.N, a.d, a.dtype, &dv))) return rc;
+  if ((a.parts & kBwdDkDv) && (rc = make_ref(a.dk, a.sdk, Hkv, a.N, a.d, a.dtype, &dk))) return rc;
+  if ((a.parts & kBwdDkDv) && (rc = make_ref(a.dv, a.sdv, Hkv, a.N, a.d, a.dtype, &dv))) return rc;
   hipStream_t st = (hipStream_t)a.stream;
   const bool alibi = a.slopes != nullptr;
   const float inv_sqrt_d = 1.0f / sqrtf((float)a.d);
@@ -228,6 +237,7 @@ int bwd_impl(const BwdArgs& a) {
   p.nbias_log2 = -a.bias * kLog2e;
   p.cu_seqlens = a.cu_seqlens; p.bias_vec = a.bias_vec;
   p.db_rows = a.db_rows; p.db_sb = (int64_t)a.H * a.N; p.db_sh = a.N;
+  p.kv_group = a.H / Hkv;
   if (SOFTMAX) {
     if (!a.lse) return SATTN_ERR_NULL;
     if ((rc = make_ref(a.o, a.so, a.H, a.N, a.d, a.dtype, &o))) return rc;
@@ -399,6 +409,28 @@ int sigmoid_attn_varlen_bwd(const void* q, const void* k, const void* v, const v
   BwdArgs a{q, k, v, nullptr, nullptr, dout, dq, dk, dv, B, H, max_seqlen, d, dtype, bias, causal, alibi_slopes,
             &tq, &tk, &tv, nullptr, &tdo, &tdq, &tdk, &tdv, nullptr, 0, kBwdDkDv | kBwdDq, stream};
   a.cu_seqlens = cu_seqlens; a.bias_vec = bias_per_seq;
+  return bwd_impl<false>(a);
+}
+
+int sigmoid_attn_mqa_fwd(const void* q, const void* k, const void* v, void* o, int B, int H, int Hkv, int N, int d,
+                         sattn_dtype dtype, float bias, int causal, const float* alibi_slopes,
+                         const sattn_strides* sq, const sattn_strides* sk, const sattn_strides* sv,
+                         const sattn_strides* so, void* stream) {
+  if (Hkv <= 0) return SATTN_ERR_SHAPE;
+  FwdArgs a{q, k, v, o, nullptr, B, H, N, d, dtype, bias, causal, alibi_slopes, sq, sk, sv, so, stream};
+  a.Hkv = Hkv;
+  return fwd_impl<false>(a);
+}
+
+int sigmoid_attn_mqa_bwd(const void* q, const void* k, const void* v, const void* dout, void* dq, void* dk,
+                         void* dv, int B, int H, int Hkv, int N, int d, sattn_dtype dtype, float bias, int causal,
+                         const float* alibi_slopes, const sattn_strides* sq, const sattn_strides* sk,
+                         const sattn_strides* sv, const sattn_strides* sdout, const sattn_strides* sdq,
+                         const sattn_strides* sdk, const sattn_strides* sdv, void* stream) {
+  if (Hkv <= 0) return SATTN_ERR_SHAPE;
+  BwdArgs a{q, k, v, nullptr, nullptr, dout, dq, dk, dv, B, H, N, d, dtype, bias, causal, alibi_slopes,
+            sq, sk, sv, nullptr, sdout, sdq, sdk, sdv, nullptr, 0, kBwdDkDv | kBwdDq, stream};
+  a.Hkv = Hkv;
   return bwd_impl<false>(a);
 }
 

@@ -46,6 +46,9 @@ struct BwdParams {
   // BWD_DQ_DB: row sums of dS, element (b, h, i) at b*db_sb + h*db_sh + i
   float* db_rows;
   int64_t db_sb, db_sh;
+  // shared key/value heads: query head h reads K/V head h / kv_group (1 = one per query head);
+  // k, v, dk, dv then have H / kv_group heads
+  int kv_group;
 };
 
 // One swizzle for tiles that are read both row-wise (ds_read_b128, 32 rows at one logical
@@ -446,9 +449,12 @@ __device__ __forceinline__ void bwd_step_full_pinned(BwdWave<D, MODE>& W, uint32
 
 // PIN = false runs every step in its compiler-scheduled form (the form the softmax variant
 // always uses): the like-for-like counterpart for comparisons.
-template <int D, int MODE, bool CAUSAL, bool ALIBI, bool SOFTMAX, bool PIN = true>
+// GROUPS (dK/dV pass only) compiles the loop over the query heads that share a K/V head; without
+// it the pass handles exactly one query head per K/V head and p.kv_group must be 1.
+template <int D, int MODE, bool CAUSAL, bool ALIBI, bool SOFTMAX, bool PIN = true, bool GROUPS = false>
 __global__ void __launch_bounds__(256, 1)
 attn_bwd_kernel(const BwdParams p) {
+  static_assert(!GROUPS || MODE == BWD_DKDV, "only the dK/dV pass iterates over query heads");
   constexpr int NW = 4, BS = 32 * NW, BC = 64, KD = D / 16, DT = D / 32;
   constexpr bool FOLD = !SOFTMAX && CAUSAL && ALIBI;  // see bwd_step
   constexpr int TILE = BC * D * 2, SLOT = 2 * TILE, CHUNK = 32 * D * 2, NSLOT = 4;
@@ -459,12 +465,18 @@ attn_bwd_kernel(const BwdParams p) {
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, h = lane >> 5;
   const int uwave = __builtin_amdgcn_readfirstlane(wave);
-  const int total = p.n_blocks * p.B * p.H;
+  // the dK/dV pass runs one workgroup per K/V head and key block and streams the query heads
+  // of that head's group one after the other; the dQ pass runs per query head
+  const int kv_group = (MODE == BWD_DKDV && !GROUPS) ? 1 : p.kv_group;
+  const int heads = MODE == BWD_DKDV ? p.H / kv_group : p.H;
+  const int total = p.n_blocks * p.B * heads;
   const int logical = xcd_remap(blockIdx.x, total);
   const int bh = logical / p.n_blocks;
   // causal: heavy blocks first (late query blocks for DQ, early key blocks for DKDV)
   const int blk = (CAUSAL && MODE != BWD_DKDV) ? (p.n_blocks - 1 - logical % p.n_blocks) : (logical % p.n_blocks);
-  const int b = bh / p.H, hd = bh % p.H;
+  const int b = bh / heads, hd = bh % heads;  // hd: K/V head (dK/dV pass) or query head (dQ pass)
+  const int hkv = MODE == BWD_DKDV ? hd : hd / kv_group;
+  const int hq0 = MODE == BWD_DKDV ? hd * kv_group : hd, n_hq = MODE == BWD_DKDV ? kv_group : 1;
   int N = p.N;
   int64_t tok0 = 0;
   float nbias_log2 = p.nbias_log2;
@@ -475,16 +487,15 @@ attn_bwd_kernel(const BwdParams p) {
     if (blk * BS >= N) return;  // this sequence has no such block (whole workgroup)
   }
 
-  const __bf16* qbase = (const __bf16*)p.q.ptr + b * p.q.sb + hd * p.q.sh + tok0 * p.q.ss;
-  const __bf16* kbase = (const __bf16*)p.k.ptr + b * p.k.sb + hd * p.k.sh + tok0 * p.k.ss;
-  const __bf16* vbase = (const __bf16*)p.v.ptr + b * p.v.sb + hd * p.v.sh + tok0 * p.v.ss;
-  const __bf16* dobase = (const __bf16*)p.dout.ptr + b * p.dout.sb + hd * p.dout.sh + tok0 * p.dout.ss;
-  // stationary tensors x1, x2 and streamed tensors y1, y2
-  const __bf16* x1b = MODE == BWD_DKDV ? kbase : qbase;
-  const __bf16* x2b = MODE == BWD_DKDV ? vbase : dobase;
+  const __bf16* kbase = (const __bf16*)p.k.ptr + b * p.k.sb + hkv * p.k.sh + tok0 * p.k.ss;
+  const __bf16* vbase = (const __bf16*)p.v.ptr + b * p.v.sb + hkv * p.v.sh + tok0 * p.v.ss;
+  // query-side tensors of query head hq
+  auto qhead = [&](int hq) { return (const __bf16*)p.q.ptr + b * p.q.sb + hq * p.q.sh + tok0 * p.q.ss; };
+  auto dohead = [&](int hq) { return (const __bf16*)p.dout.ptr + b * p.dout.sb + hq * p.dout.sh + tok0 * p.dout.ss; };
+  // stationary tensors x1, x2 and streamed tensors y1, y2 (per query head in the dK/dV pass)
+  const __bf16* x1b = MODE == BWD_DKDV ? kbase : qhead(hq0);
+  const __bf16* x2b = MODE == BWD_DKDV ? vbase : dohead(hq0);
   const int64_t x1s = MODE == BWD_DKDV ? p.k.ss : p.q.ss, x2s = MODE == BWD_DKDV ? p.v.ss : p.dout.ss;
-  const __bf16* y1b = MODE == BWD_DKDV ? qbase : kbase;
-  const __bf16* y2b = MODE == BWD_DKDV ? dobase : vbase;
   const int64_t y1s = MODE == BWD_DKDV ? p.q.ss : p.k.ss, y2s = MODE == BWD_DKDV ? p.dout.ss : p.v.ss;
 
   const int a_wave0 = blk * BS + wave * 32, ai = a_wave0 + l32, ai_ld = ai < N ? ai : N - 1;
@@ -504,22 +515,11 @@ attn_bwd_kernel(const BwdParams p) {
     }
   W.ai = ai; W.h = h;
   W.nscale = p.nscale_log2; W.nbias = nbias_log2;
-  W.sl2 = ALIBI ? p.slopes[hd] * kLog2e : 0.f;
-#pragma unroll
-  for (int r = 0; r < 16; ++r)  // DKDV: |i-j| = (bl - ai) + key_of_reg(r); DQ: (ai - bl) - key_of_reg(r)
-    W.cinit[r] = FOLD ? (MODE == BWD_DKDV ? W.sl2 : -W.sl2) * (float)key_of_reg(r) / p.nscale_log2 : 0.f;
   W.nlse = 0.f; W.dstat = 0.f;
   W.dbs[0] = W.dbs[1] = W.dbs[2] = W.dbs[3] = 0.f;
   if (SOFTMAX && MODE != BWD_DKDV) {
-    W.nlse = -p.lse[(int64_t)bh * N + ai_ld] * kLog2e;
-    W.dstat = p.dvec[(int64_t)bh * N + ai_ld];
-  }
-  {
-    const bf16x8 z = as_bf16x8(u32x4{0, 0, 0, 0});
-    W.pb[0][0] = W.pb[0][1] = W.pb[1][0] = W.pb[1][1] = z;
-    W.dsb[0][0] = W.dsb[0][1] = W.dsb[1][0] = W.dsb[1][1] = z;
-#pragma unroll
-    for (int r = 0; r < 16; ++r) { W.s[0][r] = W.s[1][r] = W.dp[0][r] = W.dp[1][r] = 0.f; }
+    W.nlse = -p.lse[((int64_t)b * p.H + hq0) * N + ai_ld] * kLog2e;
+    W.dstat = p.dvec[((int64_t)b * p.H + hq0) * N + ai_ld];
   }
 
   // chunk range of the streamed side: workgroup [wg_lo, wg_hi], this wave [c_lo, c_hi]
@@ -544,6 +544,22 @@ attn_bwd_kernel(const BwdParams p) {
   const int t_lo = wg_lo / 2, t_hi = (wg_hi + 2) / 2;  // the last step is wg_hi + 2
   const int t_data_hi = wg_hi / 2;                      // last tile that has to be staged
 
+  for (int hq = hq0; hq < hq0 + n_hq; ++hq) {  // one pass of the pipeline per query head
+  const __bf16* y1b = MODE == BWD_DKDV ? qhead(hq) : kbase;
+  const __bf16* y2b = MODE == BWD_DKDV ? dohead(hq) : vbase;
+  const int64_t stat_row0 = ((int64_t)b * p.H + hq) * N;  // softmax statistics of query head hq
+  W.sl2 = ALIBI ? p.slopes[hq] * kLog2e : 0.f;
+  // the pipeline starts empty: the second-product stage of the first steps must add zeros
+  {
+    const bf16x8 z = as_bf16x8(u32x4{0, 0, 0, 0});
+    W.pb[0][0] = W.pb[0][1] = W.pb[1][0] = W.pb[1][1] = z;
+    W.dsb[0][0] = W.dsb[0][1] = W.dsb[1][0] = W.dsb[1][1] = z;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { W.s[0][r] = W.s[1][r] = W.dp[0][r] = W.dp[1][r] = 0.f; }
+  }
+#pragma unroll
+  for (int r = 0; r < 16; ++r)  // DKDV: |i-j| = (bl - ai) + key_of_reg(r); DQ: (ai - bl) - key_of_reg(r)
+    W.cinit[r] = FOLD ? (MODE == BWD_DKDV ? W.sl2 : -W.sl2) * (float)key_of_reg(r) / p.nscale_log2 : 0.f;
   // per-lane LDS addresses (the ring slot of tile t is t % 4)
   {
     const int kap = kappa(l32), i16 = lane & 15, blk1 = (lane >> 4) & 1;
@@ -572,7 +588,7 @@ attn_bwd_kernel(const BwdParams p) {
     if (SOFTMAX && MODE == BWD_DKDV && tid < 128) {
       int row = t * BC + (tid & 63);
       row = row < N ? row : N - 1;
-      statreg = tid < 64 ? -p.lse[(int64_t)bh * N + row] * kLog2e : p.dvec[(int64_t)bh * N + row];
+      statreg = tid < 64 ? -p.lse[stat_row0 + row] * kLog2e : p.dvec[stat_row0 + row];
     }
   };
   auto store_stat = [&](int t) {
@@ -719,17 +735,20 @@ attn_bwd_kernel(const BwdParams p) {
     general_end = t_hi + 1;
   }
   __builtin_amdgcn_s_waitcnt(0x0F70);  // no staging may be in flight when the workgroup's LDS is released
+  // the next query head refills the ring: every wave must have finished reading it
+  if (hq + 1 < hq0 + n_hq) __syncthreads();
+  }  // query heads
 
   if (MODE == BWD_DQ_DB) {
     // the two halves of the wave hold the sums over different keys of the same query row
     float rs = (W.dbs[0] + W.dbs[1]) + (W.dbs[2] + W.dbs[3]);
     rs += __shfl_xor(rs, 32);
-    if (h == 0 && ai < N) p.db_rows[b * p.db_sb + hd * p.db_sh + tok0 + ai] = rs;
+    if (h == 0 && ai < N) p.db_rows[b * p.db_sb + hq0 * p.db_sh + tok0 + ai] = rs;
   }
   if (ai < N) {
     const float sc = p.inv_sqrt_d;  // dQ and dK carry the 1/sqrt(d) of the logits
-    __bf16* o0 = (MODE == BWD_DKDV ? (__bf16*)p.dk.ptr + b * p.dk.sb + hd * p.dk.sh + (tok0 + ai) * p.dk.ss
-                                   : (__bf16*)p.dq.ptr + b * p.dq.sb + hd * p.dq.sh + (tok0 + ai) * p.dq.ss);
+    __bf16* o0 = (MODE == BWD_DKDV ? (__bf16*)p.dk.ptr + b * p.dk.sb + hkv * p.dk.sh + (tok0 + ai) * p.dk.ss
+                                   : (__bf16*)p.dq.ptr + b * p.dq.sb + hq0 * p.dq.sh + (tok0 + ai) * p.dq.ss);
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
@@ -740,7 +759,7 @@ attn_bwd_kernel(const BwdParams p) {
         *(u32x2*)(o0 + 32 * dt + 8 * g + 4 * h) = w;
       }
     if (MODE == BWD_DKDV) {
-      __bf16* o1 = (__bf16*)p.dv.ptr + b * p.dv.sb + hd * p.dv.sh + (tok0 + ai) * p.dv.ss;
+      __bf16* o1 = (__bf16*)p.dv.ptr + b * p.dv.sb + hkv * p.dv.sh + (tok0 + ai) * p.dv.ss;
 #pragma unroll
       for (int dt = 0; dt < DT; ++dt)
 #pragma unroll

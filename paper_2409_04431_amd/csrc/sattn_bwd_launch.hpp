@@ -7,14 +7,21 @@ namespace sattn {
 template <int D, bool SOFTMAX, bool PIN>
 int launch_bwd_variant(BwdParams p, int causal, bool alibi, int parts, hipStream_t st) {
   p.n_blocks = (p.N + 127) / 128;
-  dim3 grid(p.n_blocks * p.B * p.H);
+  dim3 grid(p.n_blocks * p.B * p.H), grid_kv(p.n_blocks * p.B * (p.H / p.kv_group));
   int rc = SATTN_OK;
   constexpr size_t lds = 4 * 2 * 64 * D * 2;                    // 4 ring slots of two 64-row tiles
   constexpr size_t lds_stat = SOFTMAX ? 4 * 128 * sizeof(float) : 0;  // per-slot lse and D of the query tile
   dim3 block(256);
-  if (parts & kBwdDkDv)
-    SATTN_DISPATCH2(causal, alibi,
-                    rc = launch(attn_bwd_kernel<D, BWD_DKDV, A, B2, SOFTMAX, PIN>, grid, block, lds + lds_stat, st, p));
+  if (parts & kBwdDkDv) {
+    if constexpr (!SOFTMAX && PIN) {
+      if (p.kv_group > 1)  // one workgroup per K/V head streams the query heads of its group
+        SATTN_DISPATCH2(causal, alibi,
+                        rc = launch(attn_bwd_kernel<D, BWD_DKDV, A, B2, false, true, true>, grid_kv, block, lds, st, p));
+    }
+    if (p.kv_group == 1)
+      SATTN_DISPATCH2(causal, alibi,
+                      rc = launch(attn_bwd_kernel<D, BWD_DKDV, A, B2, SOFTMAX, PIN>, grid, block, lds + lds_stat, st, p));
+  }
   if (rc == SATTN_OK && (parts & kBwdDq)) {
     if constexpr (!SOFTMAX && PIN) {
       if (p.db_rows) {  // the dQ pass that also writes the row sums of dS

@@ -35,6 +35,8 @@ struct FwdParams {
   // longest length the grid covers; bias_vec, if given, holds one bias per sequence
   const int* cu_seqlens;
   const float* bias_vec;
+  // shared key/value heads: query head h reads K/V head h / kv_group (1 = one per query head)
+  int kv_group;
 };
 
 // LDS swizzles (XOR on the 16-byte chunk index within a row).
@@ -435,8 +437,9 @@ attn_fwd_kernel(const FwdParams p) {
   }
 
   const __bf16* qbase = (const __bf16*)p.q.ptr + b * p.q.sb + hd * p.q.sh + tok0 * p.q.ss;
-  const __bf16* kbase = (const __bf16*)p.k.ptr + b * p.k.sb + hd * p.k.sh + tok0 * p.k.ss;
-  const __bf16* vbase = (const __bf16*)p.v.ptr + b * p.v.sb + hd * p.v.sh + tok0 * p.v.ss;
+  const int hkv = hd / p.kv_group;
+  const __bf16* kbase = (const __bf16*)p.k.ptr + b * p.k.sb + hkv * p.k.sh + tok0 * p.k.ss;
+  const __bf16* vbase = (const __bf16*)p.v.ptr + b * p.v.sb + hkv * p.v.sh + tok0 * p.v.ss;
   __bf16* obase = (__bf16*)p.o.ptr + b * p.o.sb + hd * p.o.sh + tok0 * p.o.ss;
 
   const int q_wave0 = qb * BR + wave * 32;  // first query row of this wave

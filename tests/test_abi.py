@@ -116,6 +116,20 @@ def test_forward_wave_choice(lib):
     assert sa.sattn_fwd_waves(1, 2, 512, 64) == 4
 
 
+def test_shared_kv_head_entry_points_reject_bad_arguments(lib):
+    ptrs = [0x1000, 0x2000, 0x3000, 0x4000]
+    args = lambda H, Hkv, dtype=0: [*ptrs, 1, H, Hkv, 64, 64, dtype, 0.0, 0, None, None, None, None, None, None]
+    assert lib.sigmoid_attn_mqa_fwd(*args(6, 4)) == -2          # Hkv must divide H
+    assert lib.sigmoid_attn_mqa_fwd(*args(6, 0)) == -2
+    assert lib.sigmoid_attn_mqa_fwd(*args(6, 2, 1)) == -3       # fp32 has no shared-head kernels
+    bptrs = [0x1000, 0x2000, 0x3000, 0x4000, 0x5000, 0x6000, 0x7000]
+    bargs = lambda H, Hkv, dtype=0: [*bptrs, 1, H, Hkv, 64, 64, dtype, 0.0, 0, None, *([None] * 7), None]
+    assert lib.sigmoid_attn_mqa_bwd(*bargs(8, 3)) == -2
+    assert lib.sigmoid_attn_mqa_bwd(*bargs(8, 2, 1)) == -3
+    bptrs[5] = None
+    assert lib.sigmoid_attn_mqa_bwd(*bargs(8, 2)) == -1         # dk NULL
+
+
 def test_binding_refuses_cpu_tensors():
     import torch
     t = torch.zeros(1, 1, 8, 64, dtype=torch.bfloat16)

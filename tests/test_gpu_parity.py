@@ -464,3 +464,42 @@ def test_forward_tile_shapes_agree_bit_for_bit_and_with_the_oracle(B, H, N, d, c
     ro, rl = orc.softmax_attn_fwd(f("q"), f("k"), f("v"), causal, slopes)
     assert nerr(souts[4][0], ro) <= TOL_BF16
     assert np.abs(souts[4][1].cpu().numpy() - rl).max() <= 1e-3
+
+
+# ------------------------------------------------------------------ shared key/value heads
+
+@pytest.mark.parametrize("B,H,Hkv,N,d,causal,alibi", [
+    (1, 4, 1, 1024, 128, True, True),      # multi-query, several tiles per head, steady-state loop
+    (2, 4, 2, 333, 128, False, False),     # two groups, ragged
+    (1, 6, 2, 200, 64, True, False),
+    (1, 3, 1, 700, 64, False, True),
+    (1, 2, 2, 160, 128, True, False),      # one K/V head per query head: the plain kernels' results
+])
+def test_shared_kv_heads_match_oracle_and_the_expanded_dense_call(B, H, Hkv, N, d, causal, alibi):
+    g = torch.Generator().manual_seed(5150 + N)
+    q, do = (torch.randn(B, H, N, d, generator=g).bfloat16() for _ in range(2))
+    k, v = (torch.randn(B, Hkv, N, d, generator=g).bfloat16() for _ in range(2))
+    slopes = W.alibi_slopes(H) if alibi else None
+    sl = _dev(slopes) if slopes is not None else None
+    bias = -math.log(N)
+    Q, K, V, DO = (_dev(t) for t in (q, k, v, do))
+    o, dq = (torch.full_like(Q, float("nan")) for _ in range(2))
+    dk, dv = (torch.full_like(K, float("nan")) for _ in range(2))
+    sa.sigmoid_attn_mqa_fwd(Q, K, V, o, bias, causal, sl)
+    sa.sigmoid_attn_mqa_bwd(Q, K, V, DO, dq, dk, dv, bias, causal, sl)
+    torch.cuda.synchronize()
+    f = lambda t: t.double().numpy()
+    ro = orc.sigmoid_attn_mqa_fwd(f(q), f(k), f(v), bias, causal, slopes)
+    rdq, rdk, rdv = orc.sigmoid_attn_mqa_bwd(f(q), f(k), f(v), f(do), bias, causal, slopes)
+    for name, got, ref in (("o", o, ro), ("dq", dq, rdq), ("dk", dk, rdk), ("dv", dv, rdv)):
+        assert not torch.isnan(got).any(), name
+        assert nerr(got, ref) <= TOL_BF16, f"{name}: {nerr(got, ref):.3e}"
+    # the query side is the dense computation on K/V heads repeated over their groups, bit for bit
+    Ke, Ve = (t.repeat_interleave(H // Hkv, dim=1).contiguous() for t in (K, V))
+    o2, dq2, dk2, dv2 = (torch.full_like(Q, float("nan")) for _ in range(4))
+    sa.sigmoid_attn_fwd(Q, Ke, Ve, o2, bias, causal, sl)
+    sa.sigmoid_attn_bwd(Q, Ke, Ve, DO, dq2, dk2, dv2, bias, causal, sl)
+    torch.cuda.synchronize()
+    assert torch.equal(o, o2) and torch.equal(dq, dq2)
+    if Hkv == H:
+        assert torch.equal(dk, dk2) and torch.equal(dv, dv2)
