@@ -40,8 +40,8 @@ def cpu_baseline(cfg, seconds_hint=30.0):
     threads = orc.num_threads()
     heads = 4 * max(1, threads)
     N, d = cfg.N, cfg.d
-    # keep the sample near seconds_hint: four heads per core, ~14*N^2*d/2 flops each at roughly 2 GFLOP/s/core
-    while N > 512 and 4 * 14.0 * N * N * d / 2 / 2.0e9 > seconds_hint:
+    # keep the sample near 10-30 s: four heads per core, ~14*N^2*d/2 flops each at roughly 4 GFLOP/s/core
+    while N > 512 and 4 * 14.0 * N * N * d / 2 / 4.0e9 > seconds_hint:
         N //= 2
     g = torch.Generator().manual_seed(4242)
     q, k, v, do = (torch.randn(1, heads, N, d, generator=g).bfloat16() for _ in range(4))
@@ -109,17 +109,6 @@ def main():
             sa.sigmoid_attn_bwd_dq(q, k, v, dout, dq, bias, cfg.causal, slopes)
             if ev: ev[3].record()
 
-    # the matrix rate this device sustains at its actual clock (register-resident MFMA loop)
-    props = torch.cuda.get_device_properties(dev)
-    sink = torch.empty(props.multi_processor_count * 256, dtype=torch.float32, device=dev)
-    sa.sattn_mfma_bf16_probe(props.multi_processor_count, 2000, sink)
-    pe = _events(2)
-    pe[0].record()
-    probe_flops = sa.sattn_mfma_bf16_probe(props.multi_processor_count, 20000, sink)
-    pe[1].record()
-    torch.cuda.synchronize()
-    sustained_peak = probe_flops / pe[0].elapsed_time(pe[1]) / 1e9
-
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -130,6 +119,20 @@ def main():
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     ms_step = wall * 1e3 / args.steps
+
+    # the matrix rate this device sustains at its actual clock (register-resident MFMA loop)
+    props = torch.cuda.get_device_properties(dev)
+    sink = torch.empty(props.multi_processor_count * 256, dtype=torch.float32, device=dev)
+    # (measured after the timed steps, so that it does not disturb them; the clock takes some tens
+    # of milliseconds of matrix work to settle, hence the untimed launches first)
+    for _ in range(12):
+        sa.sattn_mfma_bf16_probe(props.multi_processor_count, 20000, sink)
+    pe = _events(2)
+    pe[0].record()
+    probe_flops = sum(sa.sattn_mfma_bf16_probe(props.multi_processor_count, 20000, sink) for _ in range(5))
+    pe[1].record()
+    torch.cuda.synchronize()
+    sustained_peak = probe_flops / pe[0].elapsed_time(pe[1]) / 1e9
 
     fwd_ms = sum(e[0].elapsed_time(e[1]) for e in evs) / args.steps
     flops_f, flops_b = cfg.fwd_flops(), cfg.bwd_flops()
