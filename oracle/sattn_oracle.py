@@ -198,3 +198,43 @@ def softmax_attn_fwd_rows(q, k, v, causal, slope, rows):
     _load().oracle_softmax_attn_fwd_rows(_ptr(q), _ptr(k), _ptr(v), N, d, int(bool(causal)), ctypes.c_double(slope),
                                          rp, len(r), _ptr(out), _ptr(lse))
     return out, lse
+
+
+# ---- hybrid-norm: normalisation of the attention output over the concatenated heads
+# (Section 5.5 and Appendix G.6: x + norm(sigmoid-attention), LayerNorm without learnable
+# affine parameters; RMSNorm is the other norm the paper's models use).  o is [B, H, N, d];
+# token (b, n) is normalised over its H*d features.  LayerNorm: (x - mean) / sqrt(var + eps)
+# with the population variance; RMSNorm: x / sqrt(mean(x^2) + eps).
+
+def headconcat_norm_fwd(o, kind="layer", eps=1e-5):
+    """Returns (y [B,H,N,d], mean [B,N], rstd [B,N]); mean is zero for kind == 'rms'."""
+    x = _f64(o)
+    B, H, N, d = x.shape
+    F = H * d
+    mean = np.zeros((B, N))
+    if kind == "layer":
+        for h in range(H):
+            mean += x[:, h].sum(axis=-1)
+        mean /= F
+    else:
+        assert kind == "rms"
+    var = np.zeros((B, N))
+    for h in range(H):
+        var += ((x[:, h] - mean[..., None]) ** 2).sum(axis=-1)
+    var /= F
+    rstd = 1.0 / np.sqrt(var + eps)
+    y = (x - mean[:, None, :, None]) * rstd[:, None, :, None]
+    return y, mean, rstd
+
+
+def headconcat_norm_bwd(o, dy, kind="layer", eps=1e-5):
+    """dL/do for L = sum(y * dy), from the chain rule through mean and variance."""
+    x, g = _f64(o), _f64(dy)
+    B, H, N, d = x.shape
+    F = H * d
+    y, mean, rstd = headconcat_norm_fwd(x, kind, eps)
+    gy = (g * y).sum(axis=(1, 3)) / F            # mean over features of dy * y
+    dx = g - y * gy[:, None, :, None]
+    if kind == "layer":
+        dx = dx - (g.sum(axis=(1, 3)) / F)[:, None, :, None]
+    return dx * rstd[:, None, :, None]

@@ -347,6 +347,42 @@ def test_multi_query_zero_logit_closed_form():
     np.testing.assert_allclose(dv, np.broadcast_to(sb * dout.sum((1, 2), keepdims=True), dv.shape), rtol=1e-12)
 
 
+# ------------------------------------------------------------------ hybrid-norm
+
+@pytest.mark.parametrize("kind", ["layer", "rms"])
+def test_headconcat_norm_against_torch_and_invariants(kind):
+    B, H, N, d = 2, 3, 7, 8
+    x, dy = _rand(B, H, N, d) * 3 + 0.7, _rand(B, H, N, d)
+    eps = 1e-5
+    y, mean, rstd = orc.headconcat_norm_fwd(x, kind, eps)
+    # library routine on the token-major layout [B, N, H*d]
+    t = torch.tensor(x.transpose(0, 2, 1, 3).reshape(B, N, H * d), dtype=torch.float64, requires_grad=True)
+    if kind == "layer":
+        ref = torch.nn.functional.layer_norm(t, (H * d,), eps=eps)
+    else:
+        ref = t * torch.rsqrt(t.pow(2).mean(-1, keepdim=True) + eps)
+    back = lambda a: a.reshape(B, N, H, d).transpose(0, 2, 1, 3)
+    np.testing.assert_allclose(y, back(ref.detach().numpy()), rtol=1e-12, atol=1e-13)
+    (ref * torch.tensor(dy.transpose(0, 2, 1, 3).reshape(B, N, H * d))).sum().backward()
+    np.testing.assert_allclose(orc.headconcat_norm_bwd(x, dy, kind, eps), back(t.grad.numpy()), rtol=1e-10, atol=1e-12)
+    # invariants: unit second moment per token (up to eps), zero mean for LayerNorm, scale invariance
+    tok = y.transpose(0, 2, 1, 3).reshape(B, N, -1)
+    np.testing.assert_allclose((tok ** 2).mean(-1), 1.0, rtol=1e-4)
+    if kind == "layer":
+        np.testing.assert_allclose(tok.mean(-1), 0.0, atol=1e-13)
+        assert np.abs(mean).max() > 0.1
+    else:
+        assert np.all(mean == 0.0)
+    # exact only without the eps term: scale invariance, and a gradient orthogonal to y
+    y0, _, _ = orc.headconcat_norm_fwd(x, kind, 0.0)
+    y2, _, _ = orc.headconcat_norm_fwd(1000.0 * x, kind, 0.0)
+    np.testing.assert_allclose(y2, y0, rtol=1e-12)
+    dx = orc.headconcat_norm_bwd(x, dy, kind, 0.0)
+    np.testing.assert_allclose((dx * y0).sum(axis=(1, 3)), 0.0, atol=1e-12)
+    if kind == "layer":
+        np.testing.assert_allclose(dx.sum(axis=(1, 3)), 0.0, atol=1e-12)
+
+
 # ------------------------------------------------------------------ sampled-row entry points
 
 @pytest.mark.parametrize("causal", [False, True])
