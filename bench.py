@@ -65,6 +65,8 @@ def main():
     ap.add_argument("--cfg", type=int, default=3, help="workload id (1-5); the headline metric is quoted on 3")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--softmax", action="store_true", help="also time the softmax comparison kernels")
+    ap.add_argument("--norm", action="store_true",
+                    help="also time the hybrid-norm kernels (LayerNorm over the concatenated heads) on this workload's O")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain 256 MiB -> 256 MiB elementwise copy kernel (scales the HBM byte counters)")
     args = ap.parse_args()
@@ -217,6 +219,30 @@ def main():
             sb_ms = e[0].elapsed_time(e[1]) / args.steps
             out["softmax_bwd_ms"] = sb_ms
             out["softmax_bwd_tflops"] = flops_b / sb_ms / 1e9
+
+    if args.norm and cfg.dtype == torch.bfloat16:
+        # HBM-bound: algorithmic bytes = one read + one write of O (forward), two reads + one write (backward)
+        y = torch.empty_like(o)
+        stats = torch.empty(cfg.B, cfg.N, 2, dtype=torch.float32, device=dev)
+
+        def timed_norm(fn):
+            for _ in range(args.warmup):
+                fn()
+            ev = _events(2)
+            ev[0].record()
+            for _ in range(args.steps):
+                fn()
+            ev[1].record()
+            torch.cuda.synchronize()
+            return ev[0].elapsed_time(ev[1]) / args.steps
+        nbytes = o.numel() * 2
+        f_ms = timed_norm(lambda: sa.sattn_headconcat_norm_fwd(o, y, stats, "layer"))
+        b_ms = timed_norm(lambda: sa.sattn_headconcat_norm_bwd(o, dout, stats, y, "layer"))
+        out["hybrid_norm"] = {"kind": "layer", "fwd_ms": f_ms, "bwd_ms": b_ms,
+                              "roofline": {"kernel": "headconcat_norm_kernel (forward)", "bound": "hbm",
+                                           "achieved": 2 * nbytes / f_ms / 1e6, "peak": 8000.0, "unit": "GB/s",
+                                           "frac": 2 * nbytes / f_ms / 1e6 / 8000.0, "traffic": None},
+                              "bwd_gbps": 3 * nbytes / b_ms / 1e6}
 
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg)

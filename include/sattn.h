@@ -137,6 +137,25 @@ int softmax_attn_bwd(const void* q, const void* k, const void* v, const void* o,
 
 size_t softmax_attn_bwd_workspace_bytes(int B, int H, int N, int d, sattn_dtype dtype);
 
+/* Hybrid-norm (Section 5.5, Appendix G.6: x + norm(attention output), a LayerNorm without
+ * learnable affine parameters; RMSNorm is the other norm the paper's models use).  Token (b, n)
+ * of a [B,H,N,d] bf16 tensor (any batch/head/token strides, NULL = contiguous) is normalised
+ * over its H*d features:  LayerNorm  y = (x - mean) / sqrt(var + eps)  (population variance),
+ * RMSNorm  y = x / sqrt(mean(x^2) + eps).  Statistics are fp32; `stats` (device, [B,N,2] fp32,
+ * 8-byte aligned) receives mean (0 for RMSNorm) and 1/sqrt(. + eps) per token in the forward
+ * call and is read by the backward call, which returns dx for L = sum(y * dy) from x, dy and
+ * those statistics.  One read and one write of the tensor (two reads in the backward).  bf16
+ * only, d in {64,128}, H*d <= 8192 (SATTN_ERR_SHAPE beyond).  The residual add and any affine
+ * parameters are the caller's. */
+typedef enum { SATTN_NORM_LAYER = 0, SATTN_NORM_RMS = 1 } sattn_norm_kind;
+int sattn_headconcat_norm_fwd(const void* x, void* y, float* stats, int B, int H, int N, int d,
+                              sattn_dtype dtype, int kind, float eps,
+                              const sattn_strides* sx, const sattn_strides* sy, void* stream);
+int sattn_headconcat_norm_bwd(const void* x, const void* dy, const float* stats, void* dx,
+                              int B, int H, int N, int d, sattn_dtype dtype, int kind,
+                              const sattn_strides* sx, const sattn_strides* sdy,
+                              const sattn_strides* sdx, void* stream);
+
 /* Forward tile shape (Appendix F.5: the block shape of the forward kernel is a tuning
  * parameter; the paper's second variant halves B_c for d = 64).  Here the tuned quantity is
  * B_r = 32 * waves query rows per workgroup, waves in {4, 8}; the bf16 forward entry points

@@ -77,6 +77,10 @@ def load_library():
     lib.sattn_strerror.restype = ctypes.c_char_p
     lib.sattn_mfma_bf16_probe.argtypes = [i, i, _vp, _vp]
     lib.sattn_mfma_bf16_probe.restype = i
+    lib.sattn_headconcat_norm_fwd.argtypes = [_vp, _vp, _vp, i, i, i, i, i, i, f, _SP, _SP, _vp]
+    lib.sattn_headconcat_norm_fwd.restype = i
+    lib.sattn_headconcat_norm_bwd.argtypes = [_vp, _vp, _vp, _vp, i, i, i, i, i, i, _SP, _SP, _SP, _vp]
+    lib.sattn_headconcat_norm_bwd.restype = i
     lib.sattn_fwd_waves.argtypes = [i, i, i, i, i]
     lib.sattn_fwd_waves.restype = i
     lib.sattn_set_fwd_waves.argtypes = [i]
@@ -171,6 +175,38 @@ def sigmoid_attn_mqa_bwd(q, k, v, dout, dq, dk, dv, bias, causal=False, alibi_sl
                                   _st(dout), _st(dq), _st(dk), _st(dv), _stream())
     _raise(rc, "sigmoid_attn_mqa_bwd")
     return dq, dk, dv
+
+
+_NORM_KINDS = {"layer": 0, "rms": 1}
+
+
+def _check_stats(stats, B, N):
+    if not stats.is_cuda or stats.dtype != torch.float32 or tuple(stats.shape) != (B, N, 2) or not stats.is_contiguous():
+        raise SattnError(f"stats must be a contiguous CUDA float32 tensor of shape {(B, N, 2)}")
+
+
+def sattn_headconcat_norm_fwd(x, y, stats, kind="layer", eps=1e-5):
+    """LayerNorm / RMSNorm of a [B,H,N,d] bf16 tensor over each token's H*d features; fills stats [B,N,2]."""
+    lib = load_library()
+    _check(x, y)
+    B, H, N, d = x.shape
+    _check_stats(stats, B, N)
+    rc = lib.sattn_headconcat_norm_fwd(x.data_ptr(), y.data_ptr(), _vp(stats.data_ptr()), B, H, N, d, _dtype_code(x),
+                                       _NORM_KINDS[kind], float(eps), _st(x), _st(y), _stream())
+    _raise(rc, "sattn_headconcat_norm_fwd")
+    return y, stats
+
+
+def sattn_headconcat_norm_bwd(x, dy, stats, dx, kind="layer"):
+    """Gradient of sattn_headconcat_norm_fwd with respect to x, from x, dy and the forward statistics."""
+    lib = load_library()
+    _check(x, dy, dx)
+    B, H, N, d = x.shape
+    _check_stats(stats, B, N)
+    rc = lib.sattn_headconcat_norm_bwd(x.data_ptr(), dy.data_ptr(), _vp(stats.data_ptr()), dx.data_ptr(), B, H, N, d,
+                                       _dtype_code(x), _NORM_KINDS[kind], _st(x), _st(dy), _st(dx), _stream())
+    _raise(rc, "sattn_headconcat_norm_bwd")
+    return dx
 
 
 def sattn_fwd_waves(B, H, N, d, causal=False):

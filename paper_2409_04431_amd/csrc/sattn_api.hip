@@ -7,6 +7,7 @@
 
 #include "sattn_f32.hpp"
 #include "sattn_launch.hpp"
+#include "sattn_norm.hpp"
 
 using namespace sattn;
 
@@ -260,6 +261,38 @@ int bwd_impl(const BwdArgs& a) {
   return rc;
 }
 
+template <bool RMS, bool BACKWARD>
+int launch_norm(const NormParams& p, hipStream_t st) {
+  const int nchunks = p.H * (p.d / 8);
+  const int64_t tokens = (int64_t)p.B * p.N;
+  dim3 grid((unsigned)((tokens + 3) / 4)), block(256);
+  if (nchunks <= 64) return launch(headconcat_norm_kernel<1, RMS, BACKWARD>, grid, block, 0, st, p);
+  if (nchunks <= 128) return launch(headconcat_norm_kernel<2, RMS, BACKWARD>, grid, block, 0, st, p);
+  if (nchunks <= 256) return launch(headconcat_norm_kernel<4, RMS, BACKWARD>, grid, block, 0, st, p);
+  if (nchunks <= 512) return launch(headconcat_norm_kernel<8, RMS, BACKWARD>, grid, block, 0, st, p);
+  return launch(headconcat_norm_kernel<16, RMS, BACKWARD>, grid, block, 0, st, p);
+}
+
+int norm_impl(bool backward, const void* x, const void* dy, void* out, float* stats, int B, int H, int N, int d,
+              sattn_dtype dtype, int kind, float eps, const sattn_strides* sx, const sattn_strides* sdy,
+              const sattn_strides* sout, void* stream) {
+  int rc = check_shape(B, H, N, d, dtype);
+  if (rc) return rc;
+  if (dtype != SATTN_BF16 || (kind != SATTN_NORM_LAYER && kind != SATTN_NORM_RMS)) return SATTN_ERR_UNSUPPORTED;
+  if ((int64_t)H * d > 8192) return SATTN_ERR_SHAPE;  // a wave keeps one token's features in registers
+  if (!(eps >= 0.f)) return SATTN_ERR_SHAPE;
+  if (!stats) return SATTN_ERR_NULL;
+  if (((uintptr_t)stats & 7) != 0) return SATTN_ERR_ALIGN;
+  NormParams p{};
+  if ((rc = make_ref(x, sx, H, N, d, dtype, &p.x))) return rc;
+  if ((rc = make_ref(out, sout, H, N, d, dtype, &p.y))) return rc;
+  if (backward && (rc = make_ref(dy, sdy, H, N, d, dtype, &p.dy))) return rc;
+  p.stats = stats; p.B = B; p.H = H; p.N = N; p.d = d; p.eps = eps;
+  hipStream_t st = (hipStream_t)stream;
+  if (kind == SATTN_NORM_RMS) return backward ? launch_norm<true, true>(p, st) : launch_norm<true, false>(p, st);
+  return backward ? launch_norm<false, true>(p, st) : launch_norm<false, false>(p, st);
+}
+
 }  // namespace
 
 extern "C" {
@@ -438,6 +471,17 @@ int sattn_mfma_bf16_probe(int blocks, int iters, float* sink, void* stream) {
   if (!sink) return SATTN_ERR_NULL;
   if (blocks <= 0 || iters <= 0) return SATTN_ERR_SHAPE;
   return launch(mfma_bf16_probe_kernel, dim3(blocks), dim3(256), 0, (hipStream_t)stream, sink, iters);
+}
+
+int sattn_headconcat_norm_fwd(const void* x, void* y, float* stats, int B, int H, int N, int d, sattn_dtype dtype,
+                              int kind, float eps, const sattn_strides* sx, const sattn_strides* sy, void* stream) {
+  return norm_impl(false, x, nullptr, y, stats, B, H, N, d, dtype, kind, eps, sx, nullptr, sy, stream);
+}
+
+int sattn_headconcat_norm_bwd(const void* x, const void* dy, const float* stats, void* dx, int B, int H, int N, int d,
+                              sattn_dtype dtype, int kind, const sattn_strides* sx, const sattn_strides* sdy,
+                              const sattn_strides* sdx, void* stream) {
+  return norm_impl(true, x, dy, dx, const_cast<float*>(stats), B, H, N, d, dtype, kind, 0.f, sx, sdy, sdx, stream);
 }
 
 int sattn_set_fwd_waves(int waves) {

@@ -130,6 +130,17 @@ def test_shared_kv_head_entry_points_reject_bad_arguments(lib):
     assert lib.sigmoid_attn_mqa_bwd(*bargs(8, 2)) == -1         # dk NULL
 
 
+def test_norm_entry_points_reject_bad_arguments(lib):
+    fwd = lambda H=16, d=128, dtype=0, kind=0, stats=0x3000, eps=1e-5: lib.sattn_headconcat_norm_fwd(
+        0x1000, 0x2000, stats, 1, H, 32, d, dtype, kind, eps, None, None, None)
+    assert fwd(stats=None) == -1
+    assert fwd(stats=0x3004) == -4
+    assert fwd(dtype=1) == -3 and fwd(kind=2) == -3
+    assert fwd(H=128) == -2                       # H*d beyond what one wave holds
+    assert fwd(eps=-1.0) == -2
+    assert lib.sattn_headconcat_norm_bwd(0x1000, None, 0x3000, 0x4000, 1, 16, 32, 128, 0, 0, None, None, None, None) == -1
+
+
 def test_binding_refuses_cpu_tensors():
     import torch
     t = torch.zeros(1, 1, 8, 64, dtype=torch.bfloat16)

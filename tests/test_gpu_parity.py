@@ -503,3 +503,32 @@ def test_shared_kv_heads_match_oracle_and_the_expanded_dense_call(B, H, Hkv, N, 
     assert torch.equal(o, o2) and torch.equal(dq, dq2)
     if Hkv == H:
         assert torch.equal(dk, dk2) and torch.equal(dv, dv2)
+
+
+# ------------------------------------------------------------------ hybrid-norm
+
+@pytest.mark.parametrize("B,H,N,d,kind,bnhd", [
+    (2, 16, 300, 128, "layer", False), (1, 12, 257, 64, "layer", True), (2, 3, 65, 64, "rms", False),
+    (1, 32, 130, 128, "rms", True), (1, 64, 9, 128, "layer", False), (3, 1, 5, 64, "layer", False),
+])
+def test_headconcat_norm_matches_oracle(B, H, N, d, kind, bnhd):
+    g = torch.Generator().manual_seed(88 + H)
+    x = (torch.randn(B, H, N, d, generator=g) * 2.0 + 0.5).bfloat16()
+    dy = torch.randn(B, H, N, d, generator=g).bfloat16()
+
+    def dev(t):   # optionally token-major storage viewed as [B,H,N,d]
+        if not bnhd:
+            return t.cuda()
+        return t.permute(0, 2, 1, 3).contiguous().cuda().permute(0, 2, 1, 3)
+    X, DY = dev(x), dev(dy)
+    Y, DX = (torch.full_like(X, float("nan")) for _ in range(2))
+    stats = torch.full((B, N, 2), float("nan"), dtype=torch.float32, device="cuda")
+    sa.sattn_headconcat_norm_fwd(X, Y, stats, kind, 1e-5)
+    sa.sattn_headconcat_norm_bwd(X, DY, stats, DX, kind)
+    torch.cuda.synchronize()
+    ry, rmean, rrstd = orc.headconcat_norm_fwd(x.double().numpy(), kind, 1e-5)
+    rdx = orc.headconcat_norm_bwd(x.double().numpy(), dy.double().numpy(), kind, 1e-5)
+    # fp32 statistics of exactly representable inputs; outputs rounded once to bf16 (2^-9 relative)
+    np.testing.assert_allclose(stats[..., 0].cpu().numpy(), rmean, rtol=1e-5, atol=1e-6)
+    np.testing.assert_allclose(stats[..., 1].cpu().numpy(), rrstd, rtol=1e-5)
+    assert nerr(Y, ry) <= 4e-3 and nerr(DX, rdx) <= 4e-3
