@@ -280,6 +280,7 @@ int norm_impl(bool backward, const void* x, const void* dy, void* out, float* st
   if (rc) return rc;
   if (dtype != SATTN_BF16 || (kind != SATTN_NORM_LAYER && kind != SATTN_NORM_RMS)) return SATTN_ERR_UNSUPPORTED;
   if ((int64_t)H * d > 8192) return SATTN_ERR_SHAPE;  // a wave keeps one token's features in registers
+  if (((int64_t)B * N + 3) / 4 > 0x7fffffffLL) return SATTN_ERR_SHAPE;  // 1-D grid, four tokens per workgroup
   if (!(eps >= 0.f)) return SATTN_ERR_SHAPE;
   if (!stats) return SATTN_ERR_NULL;
   if (((uintptr_t)stats & 7) != 0) return SATTN_ERR_ALIGN;

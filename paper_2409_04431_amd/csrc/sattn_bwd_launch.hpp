@@ -12,6 +12,8 @@ int launch_bwd_variant(BwdParams p, int causal, bool alibi, int parts, hipStream
   constexpr size_t lds = 4 * 2 * 64 * D * 2;                    // 4 ring slots of two 64-row tiles
   constexpr size_t lds_stat = SOFTMAX ? 4 * 128 * sizeof(float) : 0;  // per-slot lse and D of the query tile
   dim3 block(256);
+  if (p.kv_group < 1 || p.H % p.kv_group) return SATTN_ERR_SHAPE;
+  if (p.kv_group > 1 && (SOFTMAX || !PIN)) return SATTN_ERR_UNSUPPORTED;  // only the product kernels share K/V heads
   if (parts & kBwdDkDv) {
     if constexpr (!SOFTMAX && PIN) {
       if (p.kv_group > 1)  // one workgroup per K/V head streams the query heads of its group

@@ -16,6 +16,7 @@ int launch_fwd_variant(FwdParams p, int causal, bool alibi, hipStream_t st) {
 
 template <int D>
 int launch_fwd_bf16(FwdParams p, int waves, bool softmax, bool pin, int causal, bool alibi, hipStream_t st) {
+  if (p.kv_group < 1 || p.H % p.kv_group) return SATTN_ERR_SHAPE;
   if (waves == 4) {
     if (softmax) return launch_fwd_variant<D, 4, true, false>(p, causal, alibi, st);
     if (pin) return launch_fwd_variant<D, 4, false, true>(p, causal, alibi, st);
