@@ -532,3 +532,64 @@ def test_headconcat_norm_matches_oracle(B, H, N, d, kind, bnhd):
     np.testing.assert_allclose(stats[..., 0].cpu().numpy(), rmean, rtol=1e-5, atol=1e-6)
     np.testing.assert_allclose(stats[..., 1].cpu().numpy(), rrstd, rtol=1e-5)
     assert nerr(Y, ry) <= 4e-3 and nerr(DX, rdx) <= 4e-3
+
+
+# ------------------------------------------------------------------ the added entry points at config-3 size
+
+def test_full_size_variable_length_bias_gradient_and_shared_heads():
+    c = W.CONFIGS[3]
+    H, d = c.H, c.d
+    g = torch.Generator().manual_seed(303)
+    # variable length: eight sequences filling config 3's token count of one batch row pair
+    lens = [4096, 1000, 3333, 64, 2048, 1, 4095, 1747]
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    total = int(cu[-1])
+    q, k, v, do = (torch.randn(total, H, d, generator=g).bfloat16().cuda() for _ in range(4))
+    o, dq, dk, dv = (torch.full_like(q, float("nan")) for _ in range(4))
+    cu_d = torch.from_numpy(cu).cuda()
+    bs = torch.tensor([-math.log(max(n, 2)) for n in lens], dtype=torch.float32).cuda()
+    sa.sigmoid_attn_varlen_fwd(q, k, v, o, cu_d, max(lens), 0.0, True, None, bs)
+    sa.sigmoid_attn_varlen_bwd(q, k, v, do, dq, dk, dv, cu_d, max(lens), 0.0, True, None, bs)
+    torch.cuda.synchronize()
+    for t in (o, dq, dk, dv):
+        assert torch.isfinite(t.float()).all()
+    for s_ in (0, 2, 5, 7):
+        a, b_ = int(cu[s_]), int(cu[s_ + 1])
+        n = b_ - a
+        dense = lambda t: t[a:b_].permute(1, 0, 2).unsqueeze(0)
+        o1, dq1, dk1, dv1 = (torch.empty(1, H, n, d, dtype=torch.bfloat16, device="cuda") for _ in range(4))
+        sa.sigmoid_attn_fwd(dense(q), dense(k), dense(v), o1, float(bs[s_]), True)
+        sa.sigmoid_attn_bwd(dense(q), dense(k), dense(v), dense(do), dq1, dk1, dv1, float(bs[s_]), True)
+        torch.cuda.synchronize()
+        for packed, alone in ((o, o1), (dq, dq1), (dk, dk1), (dv, dv1)):
+            assert torch.equal(dense(packed), alone)
+    # bias gradient on config 3 itself: one head against the oracle, every head against dQ's twin
+    inp = W.make_inputs(c)
+    Q, K, V, DO = (_dev(inp[n]) for n in ("q", "k", "v", "dout"))
+    dq, dk, dv, dq0, dk0, dv0 = (torch.empty_like(Q) for _ in range(6))
+    rows = torch.full((c.B, c.H, c.N), float("nan"), dtype=torch.float32, device="cuda")
+    db = torch.empty(c.B, c.H, dtype=torch.float32, device="cuda")
+    sa.sigmoid_attn_bwd_bias_grad(Q, K, V, DO, dq, dk, dv, rows, c.bias, c.causal, None, db=db)
+    sa.sigmoid_attn_bwd(Q, K, V, DO, dq0, dk0, dv0, c.bias, c.causal)
+    torch.cuda.synchronize()
+    assert torch.equal(dq, dq0) and torch.equal(dk, dk0) and torch.equal(dv, dv0)
+    f = lambda n, b, h: inp[n][b:b + 1, h:h + 1].double().numpy()
+    ref = orc.sigmoid_attn_bias_grad(f("q", 5, 9), f("k", 5, 9), f("v", 5, 9), f("dout", 5, 9), c.bias, c.causal)
+    assert nerr(rows[5:6, 9:10], ref) <= 2e-4
+    np.testing.assert_allclose(db.cpu().numpy(), rows.double().sum(-1).cpu().numpy(), rtol=1e-4, atol=1e-4)
+    # shared K/V heads at config-3 size: the query side equals the dense call on repeated heads
+    Hkv = 4
+    Kg, Vg = K[:, :Hkv].contiguous(), V[:, :Hkv].contiguous()
+    o, dq = torch.empty_like(Q), torch.empty_like(Q)
+    dkg, dvg = torch.empty_like(Kg), torch.empty_like(Vg)
+    sa.sigmoid_attn_mqa_fwd(Q, Kg, Vg, o, c.bias, c.causal)
+    sa.sigmoid_attn_mqa_bwd(Q, Kg, Vg, DO, dq, dkg, dvg, c.bias, c.causal)
+    Ke, Ve = (t.repeat_interleave(c.H // Hkv, dim=1).contiguous() for t in (Kg, Vg))
+    o2, dq2, dk2, dv2 = (torch.empty_like(Q) for _ in range(4))
+    sa.sigmoid_attn_fwd(Q, Ke, Ve, o2, c.bias, c.causal)
+    sa.sigmoid_attn_bwd(Q, Ke, Ve, DO, dq2, dk2, dv2, c.bias, c.causal)
+    torch.cuda.synchronize()
+    assert torch.equal(o, o2) and torch.equal(dq, dq2)
+    # dK/dV: fp32 sum inside one workgroup against the sum of the dense call's bf16 per-head results
+    fold = lambda t: t.float().reshape(c.B, Hkv, c.H // Hkv, c.N, c.d).sum(2).cpu().numpy().astype(np.float64)
+    assert nerr(dkg, fold(dk2)) <= TOL_BF16 and nerr(dvg, fold(dv2)) <= TOL_BF16
