@@ -61,16 +61,21 @@ struct SwzX {
 };
 
 // Direct-to-LDS staging of one 64-row tile: one wave-level global_load_lds_dwordx4 moves
-// 64 x 16 bytes to 1 KB of LDS at M0 + 16*lane; the XOR swizzle is applied on the global
-// side.  Completion is tracked by hand (vmcnt), the compiler never sees these loads.
+// 64 x 16 bytes to 1 KB of LDS at M0 + offset + 16*lane; the XOR swizzle is applied on the
+// global side.  Completion is tracked by hand (vmcnt), the compiler never sees these loads.
+// The instruction offset moves the LDS target and the global address alike, so the NI loads
+// of a wave (consecutive 1 KB pieces of the tile) share one M0 value and differ in their
+// offset field; the per-lane global offsets are stored with that offset taken out.  M0 is
+// not otherwise used in these kernels (checked on the generated assembly by isa_check.py).
 template <int D, int NW>
 struct DmaStagerX {
   static constexpr int BC = 64, CPR = D / 8, RPI = 64 / CPR, NI = (BC * CPR) / (64 * NW);
   const char* base;       // first row of the next tile to stage (wave-uniform, advances per tile)
   const char* base_last;  // row N-1 (wave-uniform)
-  uint32_t off[NI];       // this lane's byte offset inside a tile (constant)
+  uint32_t off[NI];       // this lane's byte offset inside a tile, minus 1024 * n (constant)
   uint32_t tile_bytes, row_bytes;
   int j0;                 // first row of the next tile to stage
+  static_assert(RPI * D * 2 >= 1024 && NI * 1024 <= 4096, "offset field of the load: 0 .. 4095, never below the row step");
   __device__ __forceinline__ static int row_of(int n, int wave, int lane) { return (wave * NI + n) * RPI + lane / CPR; }
   __device__ __forceinline__ static uint32_t col_bytes(int n, int wave, int lane) {
     return (uint32_t)(((lane % CPR) ^ SwzX<D>::f(row_of(n, wave, lane))) * 16);
@@ -82,22 +87,36 @@ struct DmaStagerX {
     tile_bytes = BC * row_bytes;
     j0 = first_row;
 #pragma unroll
-    for (int n = 0; n < NI; ++n) off[n] = row_of(n, wave, lane) * row_bytes + col_bytes(n, wave, lane);
+    for (int n = 0; n < NI; ++n) off[n] = row_of(n, wave, lane) * row_bytes + col_bytes(n, wave, lane) - 1024 * n;
   }
   __device__ __forceinline__ static void load(uint32_t o, const char* sbase, uint32_t m0v) {
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(o), "s"(sbase), "s"(m0v) : "memory");
+  }
+  // Load n of a wave's NI: the first one sets M0 to the wave's first piece, the others reuse it.
+  template <int n>
+  __device__ __forceinline__ static void load_nth(uint32_t o, const char* sbase, uint32_t m0v) {
+    if constexpr (n == 0)
+      asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(o), "s"(sbase), "s"(m0v) : "memory");
+    else
+      asm volatile("global_load_lds_dwordx4 %0, %1 offset:%2" : : "v"(o), "s"(sbase), "n"(1024 * n) : "memory");
+  }
+  template <int n>
+  __device__ __forceinline__ void issue_rest(uint32_t lds_wave) const {
+    if constexpr (n < NI) {
+      load_nth<n>(off[n], base, lds_wave);
+      issue_rest<n + 1>(lds_wave);
+    }
   }
   __device__ __forceinline__ void advance() { base += tile_bytes; j0 += BC; }
   // Stage the whole next tile.  Rows past the end re-read row N-1.
   __device__ __forceinline__ void issue(uint32_t lds, int N, int wave, int lane) {
     if (j0 + BC <= N) {
-#pragma unroll
-      for (int n = 0; n < NI; ++n) load(off[n], base, lds + (wave * NI + n) * 1024);
+      issue_rest<0>(lds + wave * NI * 1024);
     } else if (j0 < N) {
       const uint32_t to_last = (uint32_t)(N - 1 - j0) * row_bytes;
 #pragma unroll
       for (int n = 0; n < NI; ++n) {
-        const uint32_t o = (j0 + row_of(n, wave, lane) < N) ? off[n] : to_last + col_bytes(n, wave, lane);
+        const uint32_t o = (j0 + row_of(n, wave, lane) < N) ? off[n] + 1024 * n : to_last + col_bytes(n, wave, lane);
         load(o, base, lds + (wave * NI + n) * 1024);
       }
     } else {
@@ -110,7 +129,7 @@ struct DmaStagerX {
   // interleaving with a pinned step; the caller calls advance() after the last one).
   template <int n>
   __device__ __forceinline__ void issue_one(uint32_t lds, int wave) const {
-    load(off[n], base, lds + (wave * NI + n) * 1024);
+    load_nth<n>(off[n], base, lds + wave * NI * 1024);
   }
 };
 

@@ -95,17 +95,25 @@ struct DmaStager {
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(o), "s"(sbase), "s"(m0v) : "memory");
   }
   // Same with the lane offset (c ^ X) + r formed in place, so that it never occupies a register
-  // between tiles.
-  template <uint32_t X>
+  // between tiles.  The instruction offset moves the LDS target and the global address alike:
+  // the NI loads of a wave (consecutive 1 KB pieces) share the M0 value set by the first one
+  // and carry 1024 * n in their offset field, which the scalar base takes out again.  M0 is
+  // not otherwise used in these kernels (checked on the generated assembly by isa_check.py).
+  template <uint32_t X, int n>
   __device__ __forceinline__ static void load_xad(uint32_t c, uint32_t r, const char* sbase, uint32_t m0v) {
     uint32_t t;
-    asm volatile("v_xad_u32 %0, %1, %2, %3\n\ts_mov_b32 m0, %5\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %4"
-                 : "=&v"(t) : "v"(c), "s"(X), "v"(r), "s"(sbase), "s"(m0v) : "memory");
+    if constexpr (n == 0)
+      asm volatile("v_xad_u32 %0, %1, %2, %3\n\ts_mov_b32 m0, %5\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %4"
+                   : "=&v"(t) : "v"(c), "s"(X), "v"(r), "s"(sbase), "s"(m0v) : "memory");
+    else
+      asm volatile("v_xad_u32 %0, %1, %2, %3\n\tglobal_load_lds_dwordx4 %0, %4 offset:%5"
+                   : "=&v"(t) : "v"(c), "s"(X), "v"(r), "s"(sbase), "n"(1024 * n) : "memory");
   }
+  static_assert(NI * 1024 <= 4096 && RPI * D * 2 >= 1024, "offset field of the load: 0 .. 4095, never below the row step");
   template <int n>
   __device__ __forceinline__ void issue_full(uint32_t lds, int wave) const {
     if constexpr (n < NI) {
-      load_xad<xcol(n)>(col0, rowoff0, base + (uint32_t)(n * RPI) * row_bytes, lds + (wave * NI + n) * 1024);
+      load_xad<xcol(n), n>(col0, rowoff0, base + (uint32_t)n * (RPI * row_bytes - 1024), lds + wave * NI * 1024);
       issue_full<n + 1>(lds, wave);
     }
   }

@@ -9,6 +9,12 @@ enforce with s_nop are therefore checked here on the generated gfx950 assembly:
   B. the result of an 8-pass MFMA (32x32x16 bf16) must be at least 11 wait states old when
      any instruction other than an MFMA touches it (16-pass 32x32x2 f32: 19).
 
+The direct-to-LDS loads (asm as well) take their LDS target from M0, and several of them share
+one M0 value set by an asm statement the compiler knows nothing about:
+
+  C. in a function that contains such loads, no instruction outside the asm statements may
+     write M0.
+
 Wait states are counted like the compiler does: one per instruction, N+1 for `s_nop N`;
 an intervening MFMA counts as its own pass count because it occupies the matrix pipe that
 long.  Only hazards with an asm MFMA on one side are reported (compiler-emitted MFMAs are
@@ -137,6 +143,11 @@ def check_function(insts):
                     break
                 ws += n.wait_states()
                 j += 1
+    # Rule C
+    if any(i.in_asm and i.op.startswith("global_load_lds") for i in insts):
+        for ins in insts:
+            if not ins.in_asm and re.match(r"^s_\w+\s+m0\b", ins.text):
+                bad.append(("C", f"line {ins.line}: '{ins.text}' writes M0 outside the asm statements"))
     return bad
 
 

@@ -35,6 +35,16 @@ def test_scanner_ignores_compiler_emitted_mfma():
     assert isa_check.check_text(txt) == []
 
 
+def test_scanner_flags_m0_write_outside_asm_next_to_lds_dma():
+    dma = "\t;;#ASMSTART\n\ts_mov_b32 m0, s5\n\ts_nop 0\n\tglobal_load_lds_dwordx4 v3, s[8:9]\n\t;;#ASMEND\n"
+    more = "\t;;#ASMSTART\n\tglobal_load_lds_dwordx4 v4, s[8:9] offset:1024\n\t;;#ASMEND\n"
+    assert isa_check.check_text(_HEAD + dma + "\tv_add_u32_e32 v40, v41, v42\n" + more + "\ts_endpgm\n") == []
+    msgs = isa_check.check_text(_HEAD + dma + "\ts_mov_b32 m0, -1\n" + more + "\ts_endpgm\n")
+    assert len(msgs) == 1 and "rule C" in msgs[0]
+    # without such loads in the function the compiler may use M0 as it likes
+    assert isa_check.check_text(_HEAD + "\ts_mov_b32 m0, -1\n\ts_endpgm\n") == []
+
+
 def test_library_kernels_have_no_mfma_hazard():
     asm = isa_check.compile_to_asm()
     n_asm_mfma = sum(1 for _, insts in isa_check.parse_functions(asm) for i in insts if i.is_mfma and i.in_asm)
