@@ -60,8 +60,8 @@ def cpu_baseline(cfg, seconds_hint=30.0):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--cfg", type=int, default=3, help="workload id (1-5); the headline metric is quoted on 3")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--softmax", action="store_true", help="also time the softmax comparison kernels")
@@ -136,8 +136,20 @@ def main():
     torch.cuda.synchronize()
     sustained_peak = probe_flops / pe[0].elapsed_time(pe[1]) / 1e9
 
-    fwd_ms = sum(e[0].elapsed_time(e[1]) for e in evs) / args.steps
+    def stats(i):   # mean / median / min of kernel i's HIP-event durations over the timed steps
+        ts = sorted(e[i].elapsed_time(e[i + 1]) for e in evs)
+        return {"mean": sum(ts) / len(ts), "median": ts[len(ts) // 2], "min": ts[0]}
+    fwd_ms = stats(0)["mean"]
     flops_f, flops_b = cfg.fwd_flops(), cfg.bwd_flops()
+    cus, clock_khz = sa.sattn_device_info()
+    # Per-config bounds of the forward (nominal clock): time on the matrix pipe alone, and time on
+    # the vector/transcendental units alone for the sigmoid (fma, exp2, add, rcp and half a pack per
+    # logit: about 3.3 + 8 + 3.3 + 8 + 2.5 issue cycles per 64 logits and SIMD, measured rates)
+    logits = cfg.B * cfg.H * cfg.N * cfg.N * (0.5 if cfg.causal else 1.0)
+    simd_hz = cus * 4 * clock_khz * 1e3
+    bounds = {"fwd_mfma_ms_at_nominal_peak": flops_f / (MFMA_BF16_PEAK_TFLOPS * 1e9),
+              "fwd_mfma_ms_at_sustained_rate": flops_f / (sustained_peak * 1e9),
+              "fwd_sigmoid_valu_ms": logits / 64 * 25.1 / simd_hz * 1e3}
     out = {
         "metric": "sigmoid-attn fwd+bwd TFLOP/s (N=4096,d=128)" if cfg.cfg == 3 else
                   f"sigmoid-attn {'fwd+bwd' if cfg.backward else 'fwd'} TFLOP/s",
@@ -146,17 +158,17 @@ def main():
         "dtype": "bf16" if cfg.dtype == torch.bfloat16 else "f32", "data": "synthetic",
         "config": {"workload": cfg.name, "B": cfg.B, "H": cfg.H, "N": cfg.N, "d": cfg.d, "causal": cfg.causal,
                    "alibi": cfg.alibi, "bias": bias, "flop_convention": "fwd 4BHN^2d, bwd 10BHN^2d, x0.5 causal"},
-        "device": {"name": props.name, "compute_units": props.multi_processor_count,
-                   "clock_mhz": getattr(props, "clock_rate", 0) / 1e3 or None,
+        "device": {"name": props.name, "compute_units": cus, "clock_mhz": clock_khz / 1e3,
                    "sustained_mfma_bf16_tflops": sustained_peak},
+        "bounds": bounds, "fwd_ms_stats": stats(0),
         "fwd_waves_per_workgroup": (sa.sattn_fwd_waves(cfg.B, cfg.H, cfg.N, cfg.d, cfg.causal)
                                     if cfg.dtype == torch.bfloat16 else None),
         "fwd_ms": fwd_ms, "fwd_tflops": flops_f / fwd_ms / 1e9,
         "fwd_frac_of_bf16_mfma_peak": flops_f / fwd_ms / 1e9 / MFMA_BF16_PEAK_TFLOPS,
     }
     if cfg.backward:
-        dkdv_ms = sum(e[1].elapsed_time(e[2]) for e in evs) / args.steps
-        dq_ms = sum(e[2].elapsed_time(e[3]) for e in evs) / args.steps
+        dkdv_ms, dq_ms = stats(1)["mean"], stats(2)["mean"]
+        out["bwd_dkdv_ms_stats"], out["bwd_dq_ms_stats"] = stats(1), stats(2)
         total = flops_f + flops_b
         out["value"] = total / ms_step / 1e9
         out["frac_of_bf16_mfma_peak"] = out["value"] / MFMA_BF16_PEAK_TFLOPS

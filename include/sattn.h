@@ -264,6 +264,10 @@ int sigmoid_attn_bwd_compiler_scheduled(const void* q, const void* k, const void
  * receives one value per lane (keeps the loop alive).  Returns 0 or SATTN_ERR_*. */
 int sattn_mfma_bf16_probe(int blocks, int iters, float* sink, void* stream);
 
+/* Measurement aid: compute units and nominal peak engine clock (kHz) of the current device, as
+ * the runtime reports them (host pointers).  SATTN_ERR_LAUNCH if there is no usable device. */
+int sattn_device_info(int* compute_units, int* clock_khz);
+
 /* Library version: major*10000 + minor*100 + patch. */
 int sattn_version(void);
 

@@ -23,6 +23,7 @@ from .binding import (  # noqa: F401
     softmax_attn_bwd,
     softmax_attn_bwd_workspace_bytes,
     softmax_attn_fwd,
+    sattn_device_info,
     sattn_fwd_waves,
     sattn_headconcat_norm_bwd,
     sattn_headconcat_norm_fwd,

@@ -85,6 +85,8 @@ def load_library():
     lib.sattn_fwd_waves.restype = i
     lib.sattn_set_fwd_waves.argtypes = [i]
     lib.sattn_set_fwd_waves.restype = i
+    lib.sattn_device_info.argtypes = [ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_int)]
+    lib.sattn_device_info.restype = i
     lib.sattn_version.argtypes = []
     lib.sattn_version.restype = i
     _lib = lib
@@ -228,6 +230,13 @@ def sattn_mfma_bf16_probe(blocks, iters, sink):
     rc = load_library().sattn_mfma_bf16_probe(int(blocks), int(iters), _vp(sink.data_ptr()), _stream())
     _raise(rc, "sattn_mfma_bf16_probe")
     return blocks * 4 * iters * 8 * 32768
+
+
+def sattn_device_info():
+    """(compute units, nominal peak engine clock in kHz) of the current device."""
+    cus, khz = ctypes.c_int(0), ctypes.c_int(0)
+    _raise(load_library().sattn_device_info(ctypes.byref(cus), ctypes.byref(khz)), "sattn_device_info")
+    return cus.value, khz.value
 
 
 def sattn_version():

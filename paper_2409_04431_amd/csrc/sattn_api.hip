@@ -497,6 +497,18 @@ int sattn_fwd_waves(int B, int H, int N, int d, int causal) {
   return pick_fwd_waves(B, H, N, d, causal);
 }
 
+int sattn_device_info(int* compute_units, int* clock_khz) {
+  if (!compute_units || !clock_khz) return SATTN_ERR_NULL;
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess ||
+      hipDeviceGetAttribute(compute_units, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+      hipDeviceGetAttribute(clock_khz, hipDeviceAttributeClockRate, dev) != hipSuccess) {
+    (void)hipGetLastError();
+    return SATTN_ERR_LAUNCH;
+  }
+  return SATTN_OK;
+}
+
 int sattn_version(void) { return 101; }
 
 }  // extern "C"
