@@ -9,6 +9,7 @@ sigmoid-attention equation in Section 2; `alibi_slopes` is an optional length-H 
 `causal` keeps keys j <= i.
 """
 import ctypes
+import math
 import os
 import subprocess
 
@@ -238,3 +239,28 @@ def headconcat_norm_bwd(o, dy, kind="layer", eps=1e-5):
     if kind == "layer":
         dx = dx - (g.sum(axis=(1, 3)) / F)[:, None, :, None]
     return dx * rstd[:, None, :, None]
+
+
+# ---- different numbers of queries and keys: the definition of Section 2 with Q of n_q rows and
+# K, V of n_k rows (no mask, no ALiBi), written with fp64 matrix products.
+#   P = sigmoid(Q K^T / sqrt(d) + b)  [n_q x n_k],  O = P V
+#   dV = P^T dO,  dP = dO V^T,  dS = P (1 - P) dP,  dQ = dS K / sqrt(d),  dK = dS^T Q / sqrt(d)
+
+def _cross_probs(q, k, bias):
+    d = q.shape[-1]
+    t = np.einsum("bhid,bhjd->bhij", q, k) / math.sqrt(d) + bias
+    return np.where(t >= 0, 1.0 / (1.0 + np.exp(-np.abs(t))), np.exp(-np.abs(t)) / (1.0 + np.exp(-np.abs(t))))
+
+
+def sigmoid_attn_cross_fwd(q, k, v, bias):
+    q, k, v = _f64(q), _f64(k), _f64(v)
+    return np.einsum("bhij,bhjd->bhid", _cross_probs(q, k, bias), v)
+
+
+def sigmoid_attn_cross_bwd(q, k, v, dout, bias):
+    q, k, v, dout = _f64(q), _f64(k), _f64(v), _f64(dout)
+    inv = 1.0 / math.sqrt(q.shape[-1])
+    p = _cross_probs(q, k, bias)
+    dv = np.einsum("bhij,bhid->bhjd", p, dout)
+    ds = p * (1.0 - p) * np.einsum("bhid,bhjd->bhij", dout, v)
+    return np.einsum("bhij,bhjd->bhid", ds, k) * inv, np.einsum("bhij,bhid->bhjd", ds, q) * inv, dv

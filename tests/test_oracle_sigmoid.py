@@ -347,6 +347,41 @@ def test_multi_query_zero_logit_closed_form():
     np.testing.assert_allclose(dv, np.broadcast_to(sb * dout.sum((1, 2), keepdims=True), dv.shape), rtol=1e-12)
 
 
+# ------------------------------------------------------------------ different numbers of queries and keys
+
+def test_cross_attention_pins():
+    B, H, Nq, Nk, d = 2, 2, 7, 12, 8
+    q, dout = _rand(B, H, Nq, d), _rand(B, H, Nq, d)
+    k, v = _rand(B, H, Nk, d), _rand(B, H, Nk, d)
+    b = -math.log(Nk)
+    o = orc.sigmoid_attn_cross_fwd(q, k, v, b)
+    dq, dk, dv = orc.sigmoid_attn_cross_bwd(q, k, v, dout, b)
+    # (1) square attention (the C oracle) on inputs padded to 12 rows: queries beyond the 7th do
+    # not influence the first 7 outputs, and with zero upstream gradient they add nothing to dK, dV
+    pad = lambda x: np.concatenate([x, np.zeros((B, H, Nk - Nq, d))], axis=2)
+    np.testing.assert_allclose(orc.sigmoid_attn_fwd(pad(q), k, v, b)[:, :, :Nq], o, rtol=1e-12, atol=1e-14)
+    sq, sk, sv = orc.sigmoid_attn_bwd(pad(q), k, v, pad(dout), b)
+    np.testing.assert_allclose(sq[:, :, :Nq], dq, rtol=1e-11, atol=1e-14)
+    np.testing.assert_allclose(sk, dk, rtol=1e-11, atol=1e-14)
+    np.testing.assert_allclose(sv, dv, rtol=1e-11, atol=1e-14)
+    # (2) more queries than keys: pad the keys with V = 0 rows, which contribute sigma(.) * 0
+    q2, d2 = _rand(B, H, Nk, d), _rand(B, H, Nk, d)
+    k2, v2 = _rand(B, H, Nq, d), _rand(B, H, Nq, d)
+    np.testing.assert_allclose(orc.sigmoid_attn_fwd(q2, pad(k2), pad(v2), b),
+                               orc.sigmoid_attn_cross_fwd(q2, k2, v2, b), rtol=1e-12, atol=1e-14)
+    # (3) torch autograd
+    tq, tk, tv = (torch.tensor(x, dtype=torch.float64, requires_grad=True) for x in (q, k, v))
+    to = torch.sigmoid(tq @ tk.transpose(-1, -2) / math.sqrt(d) + b) @ tv
+    (to * torch.tensor(dout)).sum().backward()
+    np.testing.assert_allclose(o, to.detach().numpy(), rtol=1e-12, atol=1e-14)
+    for got, ref in ((dq, tq.grad), (dk, tk.grad), (dv, tv.grad)):
+        np.testing.assert_allclose(got, ref.numpy(), rtol=1e-10, atol=1e-13)
+    # (4) Q = 0: O_i = sigma(b) * sum of all Nk values
+    z = np.zeros_like(q)
+    np.testing.assert_allclose(orc.sigmoid_attn_cross_fwd(z, k, v, -0.4),
+                               np.broadcast_to(v.sum(2, keepdims=True) / (1 + math.exp(0.4)), o.shape), rtol=1e-13)
+
+
 # ------------------------------------------------------------------ hybrid-norm
 
 @pytest.mark.parametrize("kind", ["layer", "rms"])
