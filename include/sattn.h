@@ -191,6 +191,24 @@ int sigmoid_attn_mqa_bwd(const void* q, const void* k, const void* v, const void
                          const sattn_strides* sdq, const sattn_strides* sdk,
                          const sattn_strides* sdv, void* stream);
 
+/* Different numbers of queries and keys (the definition of Section 2 with Q of n_q rows and
+ * K, V of n_k rows; the paper's models only use n_q = n_k).  q, o, dout, dq are [B,H,Nq,d];
+ * k, v, dk, dv are [B,H,Nk,d].  Plain sigmoid attention only: bf16, no causal mask, no ALiBi
+ * (both are defined by positions that the two sides would have to share), one K/V head per
+ * query head; `bias` is the caller's (the paper's rule gives -ln(Nk)).  Otherwise as
+ * sigmoid_attn_fwd / sigmoid_attn_bwd. */
+int sigmoid_attn_cross_fwd(const void* q, const void* k, const void* v, void* o,
+                           int B, int H, int Nq, int Nk, int d, sattn_dtype dtype, float bias,
+                           const sattn_strides* sq, const sattn_strides* sk,
+                           const sattn_strides* sv, const sattn_strides* so, void* stream);
+int sigmoid_attn_cross_bwd(const void* q, const void* k, const void* v, const void* dout,
+                           void* dq, void* dk, void* dv,
+                           int B, int H, int Nq, int Nk, int d, sattn_dtype dtype, float bias,
+                           const sattn_strides* sq, const sattn_strides* sk,
+                           const sattn_strides* sv, const sattn_strides* sdout,
+                           const sattn_strides* sdq, const sattn_strides* sdk,
+                           const sattn_strides* sdv, void* stream);
+
 /* Backward with the gradient of a learnable bias (Section 5.4 and Appendix G.4 train with a
  * learnable scalar b, one per layer; Appendix F.1 backward table: T = S + b, so dL/db is the
  * sum of dS over the pairs the bias enters).  Same as sigmoid_attn_bwd (bf16 or fp32), and the

@@ -14,6 +14,8 @@ from .binding import (  # noqa: F401
     sigmoid_attn_bwd_dkdv,
     sigmoid_attn_bwd_dq,
     sigmoid_attn_bwd_workspace_bytes,
+    sigmoid_attn_cross_bwd,
+    sigmoid_attn_cross_fwd,
     sigmoid_attn_fwd,
     sigmoid_attn_fwd_compiler_scheduled,
     sigmoid_attn_mqa_bwd,

@@ -54,6 +54,10 @@ def load_library():
     lib.sigmoid_attn_mqa_fwd.restype = i
     lib.sigmoid_attn_mqa_bwd.argtypes = [_vp] * 7 + [i, i, i, i, i, i, f, i, _vp] + [_SP] * 7 + [_vp]
     lib.sigmoid_attn_mqa_bwd.restype = i
+    lib.sigmoid_attn_cross_fwd.argtypes = [_vp, _vp, _vp, _vp, i, i, i, i, i, i, f, _SP, _SP, _SP, _SP, _vp]
+    lib.sigmoid_attn_cross_fwd.restype = i
+    lib.sigmoid_attn_cross_bwd.argtypes = [_vp] * 7 + [i, i, i, i, i, i, f] + [_SP] * 7 + [_vp]
+    lib.sigmoid_attn_cross_bwd.restype = i
     lib.sigmoid_attn_bwd_bias_grad.argtypes = [_vp] * 9 + [i, i, i, i, i, f, i, _vp] + [_SP] * 7 + [_vp]
     lib.sigmoid_attn_bwd_bias_grad.restype = i
     ip = ctypes.c_void_p
@@ -209,6 +213,37 @@ def sattn_headconcat_norm_bwd(x, dy, stats, dx, kind="layer"):
                                        _dtype_code(x), _NORM_KINDS[kind], _st(x), _st(dy), _st(dx), _stream())
     _raise(rc, "sattn_headconcat_norm_bwd")
     return dx
+
+
+def _check_cross(q, kv, *qlike):
+    _check(q, *qlike)
+    _check(*kv)
+    B, H, Nq, d = q.shape
+    Bk, Hk, Nk, dk = kv[0].shape
+    if (Bk, Hk, dk) != (B, H, d) or Nk <= 0:
+        raise SattnError(f"K/V shape {tuple(kv[0].shape)} does not match Q {tuple(q.shape)}")
+    return B, H, Nq, Nk, d
+
+
+def sigmoid_attn_cross_fwd(q, k, v, o, bias):
+    """Plain sigmoid attention with Nq queries and Nk keys: q, o [B,H,Nq,d]; k, v [B,H,Nk,d]."""
+    lib = load_library()
+    B, H, Nq, Nk, d = _check_cross(q, (k, v), o)
+    rc = lib.sigmoid_attn_cross_fwd(q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(), B, H, Nq, Nk, d,
+                                    _dtype_code(q), float(bias), _st(q), _st(k), _st(v), _st(o), _stream())
+    _raise(rc, "sigmoid_attn_cross_fwd")
+    return o
+
+
+def sigmoid_attn_cross_bwd(q, k, v, dout, dq, dk, dv, bias):
+    """Backward of sigmoid_attn_cross_fwd: dq [B,H,Nq,d]; dk, dv [B,H,Nk,d]."""
+    lib = load_library()
+    B, H, Nq, Nk, d = _check_cross(q, (k, v, dk, dv), dout, dq)
+    rc = lib.sigmoid_attn_cross_bwd(q.data_ptr(), k.data_ptr(), v.data_ptr(), dout.data_ptr(), dq.data_ptr(),
+                                    dk.data_ptr(), dv.data_ptr(), B, H, Nq, Nk, d, _dtype_code(q), float(bias),
+                                    _st(q), _st(k), _st(v), _st(dout), _st(dq), _st(dk), _st(dv), _stream())
+    _raise(rc, "sigmoid_attn_cross_bwd")
+    return dq, dk, dv
 
 
 def sattn_fwd_waves(B, H, N, d, causal=False):

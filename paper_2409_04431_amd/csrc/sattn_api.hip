@@ -128,7 +128,19 @@ struct FwdArgs {
   const sattn_strides *sq, *sk, *sv, *so; void* stream;
   const int* cu_seqlens = nullptr; const float* bias_vec = nullptr;  // variable-length batches
   int Hkv = 0;                                                       // K/V heads (0: one per query head)
+  int Nk = 0;                                                        // keys (0: as many as queries)
 };
+
+// A key count that differs from the query count: plain (non-causal, no ALiBi) bf16 sigmoid
+// attention with one K/V head per query head only.
+template <typename Args>
+int check_cross(const Args& a, bool softmax, bool pin, int Hkv, int* Nk) {
+  *Nk = a.Nk > 0 ? a.Nk : a.N;
+  if (*Nk == a.N) return SATTN_OK;
+  if (softmax || !pin || a.dtype != SATTN_BF16 || a.causal || a.slopes || a.cu_seqlens || Hkv != a.H)
+    return SATTN_ERR_UNSUPPORTED;
+  return check_shape(a.B, a.H, *Nk, a.d, a.dtype);
+}
 
 template <bool SOFTMAX, bool PIN = true>
 int fwd_impl(const FwdArgs& a) {
@@ -137,10 +149,12 @@ int fwd_impl(const FwdArgs& a) {
   const int Hkv = a.Hkv ? a.Hkv : a.H;
   if (Hkv <= 0 || a.H % Hkv) return SATTN_ERR_SHAPE;
   if (Hkv != a.H && (SOFTMAX || !PIN || a.dtype != SATTN_BF16)) return SATTN_ERR_UNSUPPORTED;
+  int Nk;
+  if ((rc = check_cross(a, SOFTMAX, PIN, Hkv, &Nk))) return rc;
   TensorRef q, k, v, o;
   if ((rc = make_ref(a.q, a.sq, a.H, a.N, a.d, a.dtype, &q))) return rc;
-  if ((rc = make_ref(a.k, a.sk, Hkv, a.N, a.d, a.dtype, &k))) return rc;
-  if ((rc = make_ref(a.v, a.sv, Hkv, a.N, a.d, a.dtype, &v))) return rc;
+  if ((rc = make_ref(a.k, a.sk, Hkv, Nk, a.d, a.dtype, &k))) return rc;
+  if ((rc = make_ref(a.v, a.sv, Hkv, Nk, a.d, a.dtype, &v))) return rc;
   if ((rc = make_ref(a.o, a.so, a.H, a.N, a.d, a.dtype, &o))) return rc;
   if (SOFTMAX && !a.lse) return SATTN_ERR_NULL;
   hipStream_t st = (hipStream_t)a.stream;
@@ -164,6 +178,7 @@ int fwd_impl(const FwdArgs& a) {
   p.nbias_log2 = -a.bias * kLog2e;
   p.cu_seqlens = a.cu_seqlens; p.bias_vec = a.bias_vec;
   p.kv_group = a.H / Hkv;
+  p.Nk = Nk == a.N ? 0 : Nk;
   const int waves = pick_fwd_waves(a.B, a.H, a.N, a.d, a.causal);
   if (a.d == 128) return launch_fwd_bf16<128>(p, waves, SOFTMAX, PIN, a.causal, alibi, st);
   return launch_fwd_bf16<64>(p, waves, SOFTMAX, PIN, a.causal, alibi, st);
@@ -195,6 +210,7 @@ struct BwdArgs {
   const int* cu_seqlens = nullptr; const float* bias_vec = nullptr;  // variable-length batches
   float* db_rows = nullptr; float* db = nullptr;                     // bias gradient (dense sigmoid only)
   int Hkv = 0;                                                       // K/V heads (0: one per query head)
+  int Nk = 0;                                                        // keys (0: as many as queries)
 };
 
 template <bool SOFTMAX, bool PIN = true>
@@ -204,14 +220,17 @@ int bwd_impl(const BwdArgs& a) {
   const int Hkv = a.Hkv ? a.Hkv : a.H;
   if (Hkv <= 0 || a.H % Hkv) return SATTN_ERR_SHAPE;
   if (Hkv != a.H && (SOFTMAX || !PIN || a.dtype != SATTN_BF16)) return SATTN_ERR_UNSUPPORTED;
+  int Nk;
+  if ((rc = check_cross(a, SOFTMAX, PIN, Hkv, &Nk))) return rc;
+  if (Nk != a.N && a.db_rows) return SATTN_ERR_UNSUPPORTED;
   TensorRef q, k, v, dout, dq{}, dk{}, dv{}, o{};
   if ((rc = make_ref(a.q, a.sq, a.H, a.N, a.d, a.dtype, &q))) return rc;
-  if ((rc = make_ref(a.k, a.sk, Hkv, a.N, a.d, a.dtype, &k))) return rc;
-  if ((rc = make_ref(a.v, a.sv, Hkv, a.N, a.d, a.dtype, &v))) return rc;
+  if ((rc = make_ref(a.k, a.sk, Hkv, Nk, a.d, a.dtype, &k))) return rc;
+  if ((rc = make_ref(a.v, a.sv, Hkv, Nk, a.d, a.dtype, &v))) return rc;
   if ((rc = make_ref(a.dout, a.sdout, a.H, a.N, a.d, a.dtype, &dout))) return rc;
   if ((a.parts & kBwdDq) && (rc = make_ref(a.dq, a.sdq, a.H, a.N, a.d, a.dtype, &dq))) return rc;
-  if ((a.parts & kBwdDkDv) && (rc = make_ref(a.dk, a.sdk, Hkv, a.N, a.d, a.dtype, &dk))) return rc;
-  if ((a.parts & kBwdDkDv) && (rc = make_ref(a.dv, a.sdv, Hkv, a.N, a.d, a.dtype, &dv))) return rc;
+  if ((a.parts & kBwdDkDv) && (rc = make_ref(a.dk, a.sdk, Hkv, Nk, a.d, a.dtype, &dk))) return rc;
+  if ((a.parts & kBwdDkDv) && (rc = make_ref(a.dv, a.sdv, Hkv, Nk, a.d, a.dtype, &dv))) return rc;
   hipStream_t st = (hipStream_t)a.stream;
   const bool alibi = a.slopes != nullptr;
   const float inv_sqrt_d = 1.0f / sqrtf((float)a.d);
@@ -239,6 +258,7 @@ int bwd_impl(const BwdArgs& a) {
   p.cu_seqlens = a.cu_seqlens; p.bias_vec = a.bias_vec;
   p.db_rows = a.db_rows; p.db_sb = (int64_t)a.H * a.N; p.db_sh = a.N;
   p.kv_group = a.H / Hkv;
+  p.Nk = Nk == a.N ? 0 : Nk;
   if (SOFTMAX) {
     if (!a.lse) return SATTN_ERR_NULL;
     if ((rc = make_ref(a.o, a.so, a.H, a.N, a.d, a.dtype, &o))) return rc;
@@ -465,6 +485,27 @@ int sigmoid_attn_mqa_bwd(const void* q, const void* k, const void* v, const void
   BwdArgs a{q, k, v, nullptr, nullptr, dout, dq, dk, dv, B, H, N, d, dtype, bias, causal, alibi_slopes,
             sq, sk, sv, nullptr, sdout, sdq, sdk, sdv, nullptr, 0, kBwdDkDv | kBwdDq, stream};
   a.Hkv = Hkv;
+  return bwd_impl<false>(a);
+}
+
+int sigmoid_attn_cross_fwd(const void* q, const void* k, const void* v, void* o, int B, int H, int Nq, int Nk, int d,
+                           sattn_dtype dtype, float bias, const sattn_strides* sq, const sattn_strides* sk,
+                           const sattn_strides* sv, const sattn_strides* so, void* stream) {
+  if (Nk <= 0) return SATTN_ERR_SHAPE;
+  FwdArgs a{q, k, v, o, nullptr, B, H, Nq, d, dtype, bias, 0, nullptr, sq, sk, sv, so, stream};
+  a.Nk = Nk;
+  return fwd_impl<false>(a);
+}
+
+int sigmoid_attn_cross_bwd(const void* q, const void* k, const void* v, const void* dout, void* dq, void* dk,
+                           void* dv, int B, int H, int Nq, int Nk, int d, sattn_dtype dtype, float bias,
+                           const sattn_strides* sq, const sattn_strides* sk, const sattn_strides* sv,
+                           const sattn_strides* sdout, const sattn_strides* sdq, const sattn_strides* sdk,
+                           const sattn_strides* sdv, void* stream) {
+  if (Nk <= 0) return SATTN_ERR_SHAPE;
+  BwdArgs a{q, k, v, nullptr, nullptr, dout, dq, dk, dv, B, H, Nq, d, dtype, bias, 0, nullptr,
+            sq, sk, sv, nullptr, sdout, sdq, sdk, sdv, nullptr, 0, kBwdDkDv | kBwdDq, stream};
+  a.Nk = Nk;
   return bwd_impl<false>(a);
 }
 

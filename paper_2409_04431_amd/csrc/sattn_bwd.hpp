@@ -49,6 +49,8 @@ struct BwdParams {
   // shared key/value heads: query head h reads K/V head h / kv_group (1 = one per query head);
   // k, v, dk, dv then have H / kv_group heads
   int kv_group;
+  // number of keys when it differs from the number of queries N (0: same); non-causal only
+  int Nk;
 };
 
 // One swizzle for tiles that are read both row-wise (ds_read_b128, 32 rows at one logical
@@ -505,6 +507,10 @@ attn_bwd_kernel(const BwdParams p) {
     if (p.bias_vec) nbias_log2 = -p.bias_vec[b] * kLog2e;
     if (blk * BS >= N) return;  // this sequence has no such block (whole workgroup)
   }
+  // keys may differ in number from queries (cross attention, non-causal only): N counts the
+  // queries, Nk the keys; Ns / Nt are the row counts of this pass's stationary / streamed side
+  const int Nk = p.Nk > 0 ? p.Nk : N;
+  const int Ns = MODE == BWD_DKDV ? Nk : N, Nt = MODE == BWD_DKDV ? N : Nk;
 
   const __bf16* kbase = (const __bf16*)p.k.ptr + b * p.k.sb + hkv * p.k.sh + tok0 * p.k.ss;
   const __bf16* vbase = (const __bf16*)p.v.ptr + b * p.v.sb + hkv * p.v.sh + tok0 * p.v.ss;
@@ -517,7 +523,7 @@ attn_bwd_kernel(const BwdParams p) {
   const int64_t x1s = MODE == BWD_DKDV ? p.k.ss : p.q.ss, x2s = MODE == BWD_DKDV ? p.v.ss : p.dout.ss;
   const int64_t y1s = MODE == BWD_DKDV ? p.q.ss : p.k.ss, y2s = MODE == BWD_DKDV ? p.dout.ss : p.v.ss;
 
-  const int a_wave0 = blk * BS + wave * 32, ai = a_wave0 + l32, ai_ld = ai < N ? ai : N - 1;
+  const int a_wave0 = blk * BS + wave * 32, ai = a_wave0 + l32, ai_ld = ai < Ns ? ai : Ns - 1;
 
   BwdWave<D, MODE> W;
 #pragma unroll
@@ -542,19 +548,19 @@ attn_bwd_kernel(const BwdParams p) {
   }
 
   // chunk range of the streamed side: workgroup [wg_lo, wg_hi], this wave [c_lo, c_hi]
-  const int n_chunks = (N + 31) / 32;
+  const int n_chunks = (Nt + 31) / 32;
   int wg_lo = 0, wg_hi = n_chunks - 1, c_lo = 0, c_hi = n_chunks - 1;
   if (CAUSAL) {
     if (MODE == BWD_DKDV) {
       wg_lo = (blk * BS) / 32;  // queries before the block's first key see none of its keys
       c_lo = a_wave0 / 32;
     } else {
-      const int a_hi = (blk * BS + BS < N ? blk * BS + BS : N) - 1;
+      const int a_hi = (blk * BS + BS < Nt ? blk * BS + BS : Nt) - 1;
       wg_hi = a_hi / 32;        // keys after the block's last query are masked
-      c_hi = (a_wave0 + 31 < N ? a_wave0 + 31 : N - 1) / 32;
+      c_hi = (a_wave0 + 31 < Nt ? a_wave0 + 31 : Nt - 1) / 32;
     }
   }
-  if (a_wave0 >= N) { c_lo = 1; c_hi = 0; }  // wave past the end: no chunks
+  if (a_wave0 >= Ns) { c_lo = 1; c_hi = 0; }  // wave past the end: no chunks
   // The per-step flags are wave-uniform: evaluate them on the scalar unit.  The branch itself
   // stays an exec-mask branch on an opaque VGPR copy of the flag (lane_flag), which keeps the
   // two step variants in one linear region for the register allocator.
@@ -600,8 +606,8 @@ attn_bwd_kernel(const BwdParams p) {
   }
 
   DmaStagerX<D, NW> st1, st2;
-  st1.init(y1b, y1s, N, t_lo * BC, uwave, lane);
-  st2.init(y2b, y2s, N, t_lo * BC, uwave, lane);
+  st1.init(y1b, y1s, Nt, t_lo * BC, uwave, lane);
+  st2.init(y2b, y2s, Nt, t_lo * BC, uwave, lane);
   float statreg = 0.f;
   auto load_stat = [&](int t) {
     if (SOFTMAX && MODE == BWD_DKDV && tid < 128) {
@@ -619,18 +625,18 @@ attn_bwd_kernel(const BwdParams p) {
   {
     DmaStagerX<D, NW> p1, p2;
     const int tp = t_lo > 0 ? t_lo - 1 : 0;
-    p1.init(y1b, y1s, N, tp * BC, uwave, lane);
-    p2.init(y2b, y2s, N, tp * BC, uwave, lane);
-    p1.issue(lds0 + ((t_lo + NSLOT - 1) % NSLOT) * SLOT, N, uwave, lane);
-    p2.issue(lds0 + ((t_lo + NSLOT - 1) % NSLOT) * SLOT + TILE, N, uwave, lane);
+    p1.init(y1b, y1s, Nt, tp * BC, uwave, lane);
+    p2.init(y2b, y2s, Nt, tp * BC, uwave, lane);
+    p1.issue(lds0 + ((t_lo + NSLOT - 1) % NSLOT) * SLOT, Nt, uwave, lane);
+    p2.issue(lds0 + ((t_lo + NSLOT - 1) % NSLOT) * SLOT + TILE, Nt, uwave, lane);
   }
-  st1.issue(lds0 + (t_lo % NSLOT) * SLOT, N, uwave, lane);
-  st2.issue(lds0 + (t_lo % NSLOT) * SLOT + TILE, N, uwave, lane);
+  st1.issue(lds0 + (t_lo % NSLOT) * SLOT, Nt, uwave, lane);
+  st2.issue(lds0 + (t_lo % NSLOT) * SLOT + TILE, Nt, uwave, lane);
   load_stat(t_lo);
   store_stat(t_lo);
   if (t_lo + 1 <= t_data_hi) {
-    st1.issue(lds0 + ((t_lo + 1) % NSLOT) * SLOT, N, uwave, lane);
-    st2.issue(lds0 + ((t_lo + 1) % NSLOT) * SLOT + TILE, N, uwave, lane);
+    st1.issue(lds0 + ((t_lo + 1) % NSLOT) * SLOT, Nt, uwave, lane);
+    st2.issue(lds0 + ((t_lo + 1) % NSLOT) * SLOT + TILE, Nt, uwave, lane);
     load_stat(t_lo + 1);
     store_stat(t_lo + 1);
   }
@@ -663,11 +669,11 @@ attn_bwd_kernel(const BwdParams p) {
     constexpr int NONE = MODE == BWD_DKDV ? 1000 : -1000, ALL = -NONE;
     const bool doS = s - 1 >= c_lo_s && s - 1 <= c_hi_s;
     const int cs = 32 * (s - 1), bl = cs + 8 * h;
-    const bool ragged = doS && s - 1 == c_hi_s && cs + 32 > N;
+    const bool ragged = doS && s - 1 == c_hi_s && cs + 32 > Nt;
     pin = PIN && !SOFTMAX && !(MODE == BWD_DKDV && ragged);
     if (!doS) thr = NONE;
     else if (MODE == BWD_DKDV) thr = (CAUSAL && s - 1 == c_lo_s) ? ai - bl : ALL;
-    else thr = (s - 1 == c_hi_s) ? ((CAUSAL && ai < N - 1 ? ai : N - 1) - bl) : ALL;
+    else thr = (s - 1 == c_hi_s) ? ((CAUSAL && ai < Nt - 1 ? ai : Nt - 1) - bl) : ALL;
   };
   // A wave issues about one instruction every six cycles whatever the instruction, so the
   // per-tile control flow is kept out of the steady state: tiles whose two steps are both
@@ -676,7 +682,7 @@ attn_bwd_kernel(const BwdParams p) {
   // Every variant has its one barrier per tile at the same place, so waves of a workgroup
   // may be in different loops.
   const int t_s0 = (SOFTMAX || !PIN) ? t_hi + 1 : (c_lo_s + 3) / 2;          // first tile with 2t >= c_lo+2
-  const int t_s1a = (c_hi_s + 1) / 2 - 1, t_s1b = N / BC - 3;      // last tile with 2t+1 <= c_hi / with tile t+2 inside the tensor
+  const int t_s1a = (c_hi_s + 1) / 2 - 1, t_s1b = Nt / BC - 3;      // last tile with 2t+1 <= c_hi / with tile t+2 inside the tensor
   const int t_s1 = (SOFTMAX || !PIN) ? t_lo - 1 : (t_s1a < t_s1b ? t_s1a : t_s1b);
   auto rotate = [&](int t) {
     // rotate the per-lane addresses by one ring slot
@@ -707,7 +713,7 @@ attn_bwd_kernel(const BwdParams p) {
           bwd_step_full_pinned<D, MODE, ALIBI, FOLD, 0, false, true>(W, 0, W.row0, CHUNK, 32 * (s - 1), st1, st2, 0, uwave, thr);
         else
           bwd_step<D, MODE, CAUSAL, ALIBI, SOFTMAX, 0>(W, lane_flag(doA_s), lane_flag(doS_s), lane_flag(doB_s),
-                                                       lane_flag(mask_s), 0, W.row0, CHUNK, 32 * (s - 1), N, stat);
+                                                       lane_flag(mask_s), 0, W.row0, CHUNK, 32 * (s - 1), Nt, stat);
       }
       __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): tile t+1 has landed
       // A bare barrier: fragment reads of the tiles that stay in the ring may remain in flight
@@ -725,8 +731,8 @@ attn_bwd_kernel(const BwdParams p) {
         const bool more = t + 2 <= t_data_hi;
         if (more) {  // stage tile t+2 up front (the steady-state loop interleaves it instead)
           const uint32_t dma_lds = lds0 + ((t + 2) % NSLOT) * SLOT;
-          st1.issue(dma_lds, N, uwave, lane);
-          st2.issue(dma_lds + TILE, N, uwave, lane);
+          st1.issue(dma_lds, Nt, uwave, lane);
+          st2.issue(dma_lds + TILE, Nt, uwave, lane);
           load_stat(t + 2);
         }
         // rows of chunk s+1 come from tile t+1 (first half); transposed reads of chunk s-2 from tile t-1 (second half)
@@ -734,7 +740,7 @@ attn_bwd_kernel(const BwdParams p) {
           bwd_step_full_pinned<D, MODE, ALIBI, FOLD, 1, false, true>(W, CHUNK, W.row1, 0, 32 * (s - 1), st1, st2, 0, uwave, thr);
         else
           bwd_step<D, MODE, CAUSAL, ALIBI, SOFTMAX, 1>(W, lane_flag(doA_s), lane_flag(doS_s), lane_flag(doB_s),
-                                                       lane_flag(mask_s), CHUNK, W.row1, 0, 32 * (s - 1), N, stat);
+                                                       lane_flag(mask_s), CHUNK, W.row1, 0, 32 * (s - 1), Nt, stat);
         if (more) store_stat(t + 2);
       }
       rotate(t);
@@ -762,9 +768,9 @@ attn_bwd_kernel(const BwdParams p) {
     // the two halves of the wave hold the sums over different keys of the same query row
     float rs = (W.dbs[0] + W.dbs[1]) + (W.dbs[2] + W.dbs[3]);
     rs += __shfl_xor(rs, 32);
-    if (h == 0 && ai < N) p.db_rows[b * p.db_sb + hq0 * p.db_sh + tok0 + ai] = rs;
+    if (h == 0 && ai < Ns) p.db_rows[b * p.db_sb + hq0 * p.db_sh + tok0 + ai] = rs;
   }
-  if (ai < N) {
+  if (ai < Ns) {
     const float sc = p.inv_sqrt_d;  // dQ and dK carry the 1/sqrt(d) of the logits
     __bf16* o0 = (MODE == BWD_DKDV ? (__bf16*)p.dk.ptr + b * p.dk.sb + hkv * p.dk.sh + (tok0 + ai) * p.dk.ss
                                    : (__bf16*)p.dq.ptr + b * p.dq.sb + hq0 * p.dq.sh + (tok0 + ai) * p.dq.ss);

@@ -6,8 +6,9 @@ namespace sattn {
 
 template <int D, bool SOFTMAX, bool PIN>
 int launch_bwd_variant(BwdParams p, int causal, bool alibi, int parts, hipStream_t st) {
-  p.n_blocks = (p.N + 127) / 128;
-  dim3 grid(p.n_blocks * p.B * p.H), grid_kv(p.n_blocks * p.B * (p.H / p.kv_group));
+  // the dQ pass runs one workgroup per 128 queries, the dK/dV pass one per 128 keys
+  const int nb_q = (p.N + 127) / 128, nb_k = ((p.Nk > 0 ? p.Nk : p.N) + 127) / 128;
+  dim3 grid(nb_q * p.B * p.H), grid_k(nb_k * p.B * p.H), grid_kv(nb_k * p.B * (p.H / p.kv_group));
   int rc = SATTN_OK;
   constexpr size_t lds = 4 * 2 * 64 * D * 2;                    // 4 ring slots of two 64-row tiles
   constexpr size_t lds_stat = SOFTMAX ? 4 * 128 * sizeof(float) : 0;  // per-slot lse and D of the query tile
@@ -15,6 +16,7 @@ int launch_bwd_variant(BwdParams p, int causal, bool alibi, int parts, hipStream
   if (p.kv_group < 1 || p.H % p.kv_group) return SATTN_ERR_SHAPE;
   if (p.kv_group > 1 && (SOFTMAX || !PIN)) return SATTN_ERR_UNSUPPORTED;  // only the product kernels share K/V heads
   if (parts & kBwdDkDv) {
+    p.n_blocks = nb_k;
     if constexpr (!SOFTMAX && PIN) {
       if (p.kv_group > 1)  // one workgroup per K/V head streams the query heads of its group
         SATTN_DISPATCH2(causal, alibi,
@@ -22,8 +24,9 @@ int launch_bwd_variant(BwdParams p, int causal, bool alibi, int parts, hipStream
     }
     if (p.kv_group == 1)
       SATTN_DISPATCH2(causal, alibi,
-                      rc = launch(attn_bwd_kernel<D, BWD_DKDV, A, B2, SOFTMAX, PIN>, grid, block, lds + lds_stat, st, p));
+                      rc = launch(attn_bwd_kernel<D, BWD_DKDV, A, B2, SOFTMAX, PIN>, grid_k, block, lds + lds_stat, st, p));
   }
+  p.n_blocks = nb_q;
   if (rc == SATTN_OK && (parts & kBwdDq)) {
     if constexpr (!SOFTMAX && PIN) {
       if (p.db_rows) {  // the dQ pass that also writes the row sums of dS

@@ -37,6 +37,8 @@ struct FwdParams {
   const float* bias_vec;
   // shared key/value heads: query head h reads K/V head h / kv_group (1 = one per query head)
   int kv_group;
+  // number of keys when it differs from the number of queries N (0: same); non-causal only
+  int Nk;
 };
 
 // LDS swizzles (XOR on the 16-byte chunk index within a row).
@@ -492,9 +494,10 @@ attn_fwd_kernel(const FwdParams p) {
 
   // keys this workgroup must visit, and chunks this wave must visit
   const int q_hi = (qb * BR + BR < N ? qb * BR + BR : N) - 1;  // last valid query row of the block
-  const int kv_len = CAUSAL ? (q_hi + 1) : N;
+  const int Nk = p.Nk > 0 ? p.Nk : N;  // keys (N counts the queries)
+  const int kv_len = CAUSAL ? (q_hi + 1) : Nk;
   const int n_tiles = (kv_len + BC - 1) / BC;
-  int kv_wave = N;
+  int kv_wave = Nk;
   if (CAUSAL) kv_wave = q_wave0 + 32 < N ? q_wave0 + 32 : N;
   const int cw = q_wave0 < N ? (kv_wave + 31) / 32 : 0;  // chunks 0..cw-1; waves past the end idle
 
@@ -506,12 +509,12 @@ attn_fwd_kernel(const FwdParams p) {
   DmaStager<D, BC, NW, true> vst;
   constexpr int NIK = DmaStager<D, BC, NW, false>::NI, NIV = DmaStager<D, BC, NW, true>::NI;
   const int uwave = __builtin_amdgcn_readfirstlane(wave);
-  kst.init(kbase, p.k.ss, N, uwave, lane);
-  vst.init(vbase, p.v.ss, N, uwave, lane);
-  kst.issue(kring, N, uwave, lane);
-  vst.issue(vring, N, uwave, lane);
-  if (n_tiles > 1) { kst.issue(kring + TILE, N, uwave, lane); vst.issue(vring + TILE, N, uwave, lane); }
-  if (n_tiles > 2) kst.issue(kring + 2 * TILE, N, uwave, lane);
+  kst.init(kbase, p.k.ss, Nk, uwave, lane);
+  vst.init(vbase, p.v.ss, Nk, uwave, lane);
+  kst.issue(kring, Nk, uwave, lane);
+  vst.issue(vring, Nk, uwave, lane);
+  if (n_tiles > 1) { kst.issue(kring + TILE, Nk, uwave, lane); vst.issue(vring + TILE, Nk, uwave, lane); }
+  if (n_tiles > 2) kst.issue(kring + 2 * TILE, Nk, uwave, lane);
   SATTN_WAIT_VMCNT(0);  // prologue tiles landed; the Q fragment is in registers
   __syncthreads();
 
@@ -534,10 +537,10 @@ attn_fwd_kernel(const FwdParams p) {
   for (int t = 0; t < n_tiles; ++t) {
     const bool k_more = t + 3 < n_tiles, v_more = t + 2 < n_tiles;
     const int vslot2 = kslot == 0 ? 2 : kslot - 1;  // (t+2)%3
-    if (k_more) kst.issue(kring + kslot * TILE, N, uwave, lane);
-    if (v_more) vst.issue(vring + vslot2 * TILE, N, uwave, lane);
-    fwd_step_any<D, ALIBI, SOFTMAX, 0, FOLD, PIN>(W, 2 * t, cw, 0, 0, N, CAUSAL);
-    fwd_step_any<D, ALIBI, SOFTMAX, 1, FOLD, PIN>(W, 2 * t + 1, cw, CHUNK, CHUNK, N, CAUSAL);
+    if (k_more) kst.issue(kring + kslot * TILE, Nk, uwave, lane);
+    if (v_more) vst.issue(vring + vslot2 * TILE, Nk, uwave, lane);
+    fwd_step_any<D, ALIBI, SOFTMAX, 0, FOLD, PIN>(W, 2 * t, cw, 0, 0, Nk, CAUSAL);
+    fwd_step_any<D, ALIBI, SOFTMAX, 1, FOLD, PIN>(W, 2 * t + 1, cw, CHUNK, CHUNK, Nk, CAUSAL);
     // advance the read addresses by one ring slot: K reads are at slot (t+1)%3, V reads at t%3
     const int kadv = kslot == 1 ? -2 * TILE : TILE;  // slot (t+1)%3 == 2 wraps to 0
     const int vadv = kslot == 2 ? -2 * TILE : TILE;
@@ -553,7 +556,7 @@ attn_fwd_kernel(const FwdParams p) {
     __syncthreads();
   }
   // flush: O^T update of the last chunk when it fell on the last step of the loop
-  if (cw == 2 * n_tiles && cw > 0) fwd_step<D, ALIBI, SOFTMAX, STEP_TAIL, 0, FOLD>(W, 0, 0, 0, N, CAUSAL);
+  if (cw == 2 * n_tiles && cw > 0) fwd_step<D, ALIBI, SOFTMAX, STEP_TAIL, 0, FOLD>(W, 0, 0, 0, Nk, CAUSAL);
 
   if (SOFTMAX) {
     // normalise by the row sum (both lane halves) and write the natural-log row log-sum-exp

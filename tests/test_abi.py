@@ -141,6 +141,17 @@ def test_norm_entry_points_reject_bad_arguments(lib):
     assert lib.sattn_headconcat_norm_bwd(0x1000, None, 0x3000, 0x4000, 1, 16, 32, 128, 0, 0, None, None, None, None) == -1
 
 
+def test_cross_attention_entry_points_reject_bad_arguments(lib):
+    ptrs = [0x1000, 0x2000, 0x3000, 0x4000]
+    f = lambda Nq=64, Nk=96, d=64, dtype=0: lib.sigmoid_attn_cross_fwd(*ptrs, 1, 2, Nq, Nk, d, dtype, 0.0,
+                                                                       None, None, None, None, None)
+    assert f(Nk=0) == -2 and f(Nq=0) == -2
+    assert f(dtype=1) == -3                         # fp32 has no such kernels
+    assert f(d=96) == -3
+    bptrs = [0x1000, 0x2000, 0x3000, 0x4000, 0x5000, None, 0x7000]
+    assert lib.sigmoid_attn_cross_bwd(*bptrs, 1, 2, 64, 96, 64, 0, 0.0, *([None] * 7), None) == -1
+
+
 def test_binding_refuses_cpu_tensors():
     import torch
     t = torch.zeros(1, 1, 8, 64, dtype=torch.bfloat16)

@@ -593,3 +593,34 @@ def test_full_size_variable_length_bias_gradient_and_shared_heads():
     # dK/dV: fp32 sum inside one workgroup against the sum of the dense call's bf16 per-head results
     fold = lambda t: t.float().reshape(c.B, Hkv, c.H // Hkv, c.N, c.d).sum(2).cpu().numpy().astype(np.float64)
     assert nerr(dkg, fold(dk2)) <= TOL_BF16 and nerr(dvg, fold(dv2)) <= TOL_BF16
+
+
+# ------------------------------------------------------------------ different numbers of queries and keys
+
+@pytest.mark.parametrize("B,H,Nq,Nk,d", [
+    (1, 2, 300, 1100, 128), (2, 1, 1024, 257, 128), (1, 3, 1, 700, 64), (1, 2, 640, 1, 64),
+    (1, 1, 129, 2048, 64), (1, 2, 777, 777, 128),
+])
+def test_cross_attention_matches_oracle(B, H, Nq, Nk, d):
+    g = torch.Generator().manual_seed(7000 + Nq + Nk)
+    q, do = (torch.randn(B, H, Nq, d, generator=g).bfloat16() for _ in range(2))
+    k, v = (torch.randn(B, H, Nk, d, generator=g).bfloat16() for _ in range(2))
+    bias = -math.log(max(Nk, 2))
+    Q, K, V, DO = (_dev(t) for t in (q, k, v, do))
+    o, dq = (torch.full_like(Q, float("nan")) for _ in range(2))
+    dk, dv = (torch.full_like(K, float("nan")) for _ in range(2))
+    sa.sigmoid_attn_cross_fwd(Q, K, V, o, bias)
+    sa.sigmoid_attn_cross_bwd(Q, K, V, DO, dq, dk, dv, bias)
+    torch.cuda.synchronize()
+    f = lambda t: t.double().numpy()
+    ro = orc.sigmoid_attn_cross_fwd(f(q), f(k), f(v), bias)
+    rdq, rdk, rdv = orc.sigmoid_attn_cross_bwd(f(q), f(k), f(v), f(do), bias)
+    for name, got, ref in (("o", o, ro), ("dq", dq, rdq), ("dk", dk, rdk), ("dv", dv, rdv)):
+        assert not torch.isnan(got).any(), name
+        assert nerr(got, ref) <= TOL_BF16, f"{name}: {nerr(got, ref):.3e}"
+    if Nq == Nk:   # the square entry points run the same kernels
+        o2, dq2, dk2, dv2 = (torch.empty_like(Q) for _ in range(4))
+        sa.sigmoid_attn_fwd(Q, K, V, o2, bias)
+        sa.sigmoid_attn_bwd(Q, K, V, DO, dq2, dk2, dv2, bias)
+        torch.cuda.synchronize()
+        assert torch.equal(o, o2) and torch.equal(dq, dq2) and torch.equal(dk, dk2) and torch.equal(dv, dv2)
