@@ -157,15 +157,19 @@ int sattn_headconcat_norm_bwd(const void* x, const void* dy, const float* stats,
                               const sattn_strides* sdx, void* stream);
 
 /* Forward tile shape (Appendix F.5: the block shape of the forward kernel is a tuning
- * parameter; the paper's second variant halves B_c for d = 64).  Here the tuned quantity is
- * B_r = 32 * waves query rows per workgroup, waves in {4, 8}; the bf16 forward entry points
- * (sigmoid, softmax, variable-length) choose it per problem from d, B*H*N, the mask and the
- * number of compute units.  sattn_fwd_waves returns that choice (or a negative error code);
- * sattn_set_fwd_waves forces it process-wide for measurements (0 = back to automatic; not
- * thread-safe against concurrent launches).  The outputs are bit-identical for both shapes:
+ * parameter; the paper's second variant halves B_c for d = 64).  Here the tuned quantities are
+ * B_r = 32 * waves query rows per workgroup, waves in {4, 8}, and, for 4-wave workgroups at
+ * d = 128, the depth of the V ring in LDS (3 slots: one workgroup per compute unit; 2 slots: two).
+ * The bf16 forward entry points (sigmoid, softmax, variable-length, ...) choose them per problem
+ * from d, B*H*N, the mask and the number of compute units.  sattn_fwd_waves / sattn_fwd_v_slots
+ * return that choice (or a negative error code); the setters force a value process-wide for
+ * measurements (0 = back to automatic; a forced v_slots only applies where that shape exists;
+ * not thread-safe against concurrent launches).  The outputs are bit-identical for all shapes:
  * the arithmetic of a query row does not depend on which rows share its workgroup. */
 int sattn_fwd_waves(int B, int H, int N, int d, int causal);
+int sattn_fwd_v_slots(int B, int H, int N, int d, int causal);
 int sattn_set_fwd_waves(int waves);
+int sattn_set_fwd_v_slots(int v_slots);
 
 /* Human-readable text for an SATTN_ERR_* code (static storage). */
 const char* sattn_strerror(int code);

@@ -26,10 +26,12 @@ from .binding import (  # noqa: F401
     softmax_attn_bwd_workspace_bytes,
     softmax_attn_fwd,
     sattn_device_info,
+    sattn_fwd_v_slots,
     sattn_fwd_waves,
     sattn_headconcat_norm_bwd,
     sattn_headconcat_norm_fwd,
     sattn_mfma_bf16_probe,
+    sattn_set_fwd_v_slots,
     sattn_set_fwd_waves,
     sattn_strerror,
     sattn_version,

@@ -89,6 +89,10 @@ def load_library():
     lib.sattn_fwd_waves.restype = i
     lib.sattn_set_fwd_waves.argtypes = [i]
     lib.sattn_set_fwd_waves.restype = i
+    lib.sattn_fwd_v_slots.argtypes = [i, i, i, i, i]
+    lib.sattn_fwd_v_slots.restype = i
+    lib.sattn_set_fwd_v_slots.argtypes = [i]
+    lib.sattn_set_fwd_v_slots.restype = i
     lib.sattn_device_info.argtypes = [ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_int)]
     lib.sattn_device_info.restype = i
     lib.sattn_version.argtypes = []
@@ -252,6 +256,19 @@ def sattn_fwd_waves(B, H, N, d, causal=False):
     if rc < 0:
         _raise(rc, "sattn_fwd_waves")
     return rc
+
+
+def sattn_fwd_v_slots(B, H, N, d, causal=False):
+    """Depth of the V ring (2 or 3 tiles) the bf16 forward kernels use for this problem."""
+    rc = load_library().sattn_fwd_v_slots(B, H, N, d, int(bool(causal)))
+    if rc < 0:
+        _raise(rc, "sattn_fwd_v_slots")
+    return rc
+
+
+def sattn_set_fwd_v_slots(v_slots):
+    """Force a V ring of 2 or 3 tiles where that shape exists (4 waves, d = 128); 0 = automatic."""
+    _raise(load_library().sattn_set_fwd_v_slots(int(v_slots)), "sattn_set_fwd_v_slots")
 
 
 def sattn_set_fwd_waves(waves):

@@ -77,14 +77,18 @@ int make_ref(const void* ptr, const sattn_strides* s, int H, int N, int d, sattn
   return SATTN_OK;
 }
 
-// Waves (32 query rows each) per forward workgroup.  Head dimension 64: two 4-wave workgroups
-// share a compute unit (their LDS rings both fit) and overlap each other's barriers, which
-// measured faster than one 8-wave workgroup at every size.  Head dimension 128: the ring of an
-// 8-wave workgroup fills the LDS either way, so 4-wave workgroups halve the waves per compute
-// unit; they only pay when the problem is too small to give every compute unit an 8-wave one
-// (causal problems a little longer: their workgroups run heavy-first, so a second, light round
-// of workgroups costs less than idle compute units in the first).
-int g_fwd_waves = 0;  // 0: choose per problem; 4 or 8: forced (sattn_set_fwd_waves)
+// Shape of a forward workgroup: waves (32 query rows each) and depth of the V ring.
+// Head dimension 64: two 4-wave workgroups share a compute unit (their LDS rings both fit) and
+// overlap each other's barriers, which measured faster than one 8-wave workgroup at every size.
+// Head dimension 128: the 96 KB ring of the three-slot V ring admits one workgroup per compute
+// unit, so 4 waves halve the occupancy; that only pays while the problem is too small to give
+// every compute unit an 8-wave workgroup (causal problems a little longer: their workgroups run
+// heavy-first, so a second, light round costs less than idle compute units in the first).  With a
+// two-slot V ring (80 KB) two 4-wave workgroups fit again; they win while a workgroup's key loop
+// is short (per-workgroup prologue, diagonal and barrier waits overlap with the neighbour) and
+// lose a few percent on long loops, where V is staged only one tile ahead.
+int g_fwd_waves = 0;   // 0: choose per problem; 4 or 8: forced (sattn_set_fwd_waves)
+int g_fwd_vslots = 0;  // 0: choose per problem; 2 or 3: forced (sattn_set_fwd_v_slots)
 
 int compute_units() {
   int dev = 0, n = 0;
@@ -96,12 +100,26 @@ int compute_units() {
   return n;
 }
 
-int pick_fwd_waves(int B, int H, int N, int d, int causal) {
-  if (g_fwd_waves) return g_fwd_waves;
-  if (d == 64) return 4;
-  const int64_t wg4 = (int64_t)B * H * ((N + 127) / 128);
-  const int64_t cus = compute_units();
-  return wg4 <= (causal ? cus + cus / 2 : cus) ? 4 : 8;
+struct FwdShape { int waves, v_slots; };
+
+FwdShape pick_fwd_shape(int B, int H, int N, int d, int causal) {
+  FwdShape s{8, 3};
+  if (d == 64) {
+    s.waves = 4;
+  } else {
+    const int64_t wg4 = (int64_t)B * H * ((N + 127) / 128);
+    const int64_t cus = compute_units();
+    const int64_t avg_tiles = (causal ? (N + 1) / 2 : N) / 64;  // 64-key tiles a workgroup visits on average
+    if (wg4 <= (causal ? cus + cus / 2 : cus)) s = FwdShape{4, 3};
+    else if (avg_tiles <= 48) s = FwdShape{4, 2};
+  }
+  if (g_fwd_waves) {
+    if (g_fwd_waves != s.waves) s.v_slots = 3;
+    s.waves = g_fwd_waves;
+  }
+  if (g_fwd_vslots) s.v_slots = g_fwd_vslots;
+  if (s.waves != 4 || d != 128) s.v_slots = 3;  // the only shape with a two-slot V ring
+  return s;
 }
 
 int check_shape(int B, int H, int N, int d, sattn_dtype dt) {
@@ -179,9 +197,9 @@ int fwd_impl(const FwdArgs& a) {
   p.cu_seqlens = a.cu_seqlens; p.bias_vec = a.bias_vec;
   p.kv_group = a.H / Hkv;
   p.Nk = Nk == a.N ? 0 : Nk;
-  const int waves = pick_fwd_waves(a.B, a.H, a.N, a.d, a.causal);
-  if (a.d == 128) return launch_fwd_bf16<128>(p, waves, SOFTMAX, PIN, a.causal, alibi, st);
-  return launch_fwd_bf16<64>(p, waves, SOFTMAX, PIN, a.causal, alibi, st);
+  const FwdShape shape = pick_fwd_shape(a.B, a.H, a.N, a.d, a.causal);
+  if (a.d == 128) return launch_fwd_bf16<128>(p, shape.waves, shape.v_slots, SOFTMAX, PIN, a.causal, alibi, st);
+  return launch_fwd_bf16<64>(p, shape.waves, shape.v_slots, SOFTMAX, PIN, a.causal, alibi, st);
 }
 
 // ---------------------------------------------------------------- backward
@@ -532,10 +550,22 @@ int sattn_set_fwd_waves(int waves) {
   return SATTN_OK;
 }
 
+int sattn_set_fwd_v_slots(int v_slots) {
+  if (v_slots != 0 && v_slots != 2 && v_slots != 3) return SATTN_ERR_UNSUPPORTED;
+  g_fwd_vslots = v_slots;
+  return SATTN_OK;
+}
+
 int sattn_fwd_waves(int B, int H, int N, int d, int causal) {
   if (B <= 0 || H <= 0 || N <= 0) return SATTN_ERR_SHAPE;
   if (d != 64 && d != 128) return SATTN_ERR_UNSUPPORTED;
-  return pick_fwd_waves(B, H, N, d, causal);
+  return pick_fwd_shape(B, H, N, d, causal).waves;
+}
+
+int sattn_fwd_v_slots(int B, int H, int N, int d, int causal) {
+  if (B <= 0 || H <= 0 || N <= 0) return SATTN_ERR_SHAPE;
+  if (d != 64 && d != 128) return SATTN_ERR_UNSUPPORTED;
+  return pick_fwd_shape(B, H, N, d, causal).v_slots;
 }
 
 int sattn_device_info(int* compute_units, int* clock_khz) {

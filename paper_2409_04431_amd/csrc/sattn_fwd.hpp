@@ -413,9 +413,12 @@ __device__ __forceinline__ void fwd_step_any(FwdWave<D>& W, int c, int cw, uint3
 
 // PIN = false runs the steady-state step in its compiler-scheduled form as well (the form the
 // softmax variant always uses): the like-for-like counterpart for comparisons.
-template <int D, int NW, bool CAUSAL, bool ALIBI, bool SOFTMAX, bool PIN = true>
+// VS = V ring slots (3, or 2: the V tile is then staged one tile ahead instead of two, which
+// brings the ring of D = 128 down to 80 KB so that two 4-wave workgroups share a compute unit).
+template <int D, int NW, bool CAUSAL, bool ALIBI, bool SOFTMAX, bool PIN = true, int VS = 3>
 __global__ void __launch_bounds__(64 * NW, 8 / NW)
 attn_fwd_kernel(const FwdParams p) {
+  static_assert(VS == 2 || VS == 3, "V ring of two or three slots");
   constexpr int BR = 32 * NW, BC = 64;
   constexpr int KD = D / 16, DT = D / 32;
   constexpr bool FOLD = !SOFTMAX && CAUSAL && ALIBI;  // see fwd_step
@@ -424,7 +427,7 @@ attn_fwd_kernel(const FwdParams p) {
 
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   const uint32_t lds0 = (uint32_t)(uintptr_t)(SATTN_LDS(char)*)smem;
-  const uint32_t kring = lds0, vring = lds0 + 3 * TILE;  // 3 K slots, then 3 V slots
+  const uint32_t kring = lds0, vring = lds0 + 3 * TILE;  // 3 K slots, then VS V slots
 
   const int tid = threadIdx.x;
   const int wave = tid >> 6, lane = tid & 63;
@@ -501,10 +504,12 @@ attn_fwd_kernel(const FwdParams p) {
   if (CAUSAL) kv_wave = q_wave0 + 32 < N ? q_wave0 + 32 : N;
   const int cw = q_wave0 < N ? (kv_wave + 31) / 32 : 0;  // chunks 0..cw-1; waves past the end idle
 
-  // LDS rings: K tile t in K slot t%3, V tile t in V slot t%3.  At the start of tile t the
+  // LDS rings: K tile t in K slot t%3, V tile t in V slot t%VS.  At the start of tile t the
   // loads of K(t+3) and V(t+2) are issued; they must have landed by the end of tile t+1.
   // K(t+3) overwrites K(t), whose last reads happened during tile t-1; V(t+2) overwrites
-  // V(t-1), ditto: the barrier that ends tile t-1 orders both.
+  // V(t-1), ditto: the barrier that ends tile t-1 orders both.  With VS = 2 it is V(t+1) that
+  // is issued at the start of tile t (first, so that the wait at the end of the tile can leave
+  // K(t+3) in flight), again into the slot of V(t-1).
   DmaStager<D, BC, NW, false> kst;
   DmaStager<D, BC, NW, true> vst;
   constexpr int NIK = DmaStager<D, BC, NW, false>::NI, NIV = DmaStager<D, BC, NW, true>::NI;
@@ -513,7 +518,10 @@ attn_fwd_kernel(const FwdParams p) {
   vst.init(vbase, p.v.ss, Nk, uwave, lane);
   kst.issue(kring, Nk, uwave, lane);
   vst.issue(vring, Nk, uwave, lane);
-  if (n_tiles > 1) { kst.issue(kring + TILE, Nk, uwave, lane); vst.issue(vring + TILE, Nk, uwave, lane); }
+  if (n_tiles > 1) {
+    kst.issue(kring + TILE, Nk, uwave, lane);
+    if (VS == 3) vst.issue(vring + TILE, Nk, uwave, lane);
+  }
   if (n_tiles > 2) kst.issue(kring + 2 * TILE, Nk, uwave, lane);
   SATTN_WAIT_VMCNT(0);  // prologue tiles landed; the Q fragment is in registers
   __syncthreads();
@@ -533,26 +541,36 @@ attn_fwd_kernel(const FwdParams p) {
   // vf from V chunk c (tile t, slot t%3).  The per-lane LDS addresses rotate with the rings.
 #pragma unroll
   for (int kk = 0; kk < KD; ++kk) W.koff[kk] += TILE;  // K reads now point at tile 1
-  int kslot = 0;  // ring slot of K tile t == slot that K(t+3) will overwrite; V tile t is in the same slot index
+  int kslot = 0;  // ring slot of K tile t == slot that K(t+3) will overwrite; with VS = 3 V tile t is in the same slot index
   for (int t = 0; t < n_tiles; ++t) {
-    const bool k_more = t + 3 < n_tiles, v_more = t + 2 < n_tiles;
-    const int vslot2 = kslot == 0 ? 2 : kslot - 1;  // (t+2)%3
-    if (k_more) kst.issue(kring + kslot * TILE, Nk, uwave, lane);
-    if (v_more) vst.issue(vring + vslot2 * TILE, Nk, uwave, lane);
+    const bool k_more = t + 3 < n_tiles, v_more = t + (VS == 3 ? 2 : 1) < n_tiles;
+    if (VS == 3) {
+      const int vslot2 = kslot == 0 ? 2 : kslot - 1;  // (t+2)%3
+      if (k_more) kst.issue(kring + kslot * TILE, Nk, uwave, lane);
+      if (v_more) vst.issue(vring + vslot2 * TILE, Nk, uwave, lane);
+    } else {
+      if (v_more) vst.issue(vring + ((t + 1) & 1) * TILE, Nk, uwave, lane);
+      if (k_more) kst.issue(kring + kslot * TILE, Nk, uwave, lane);
+    }
     fwd_step_any<D, ALIBI, SOFTMAX, 0, FOLD, PIN>(W, 2 * t, cw, 0, 0, Nk, CAUSAL);
     fwd_step_any<D, ALIBI, SOFTMAX, 1, FOLD, PIN>(W, 2 * t + 1, cw, CHUNK, CHUNK, Nk, CAUSAL);
     // advance the read addresses by one ring slot: K reads are at slot (t+1)%3, V reads at t%3
     const int kadv = kslot == 1 ? -2 * TILE : TILE;  // slot (t+1)%3 == 2 wraps to 0
-    const int vadv = kslot == 2 ? -2 * TILE : TILE;
+    const int vadv = VS == 3 ? (kslot == 2 ? -2 * TILE : TILE) : ((t & 1) ? -TILE : TILE);
 #pragma unroll
     for (int kk = 0; kk < KD; ++kk) W.koff[kk] += kadv;
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt) W.voff[dt] += vadv;
     kslot = kslot == 2 ? 0 : kslot + 1;
     // everything issued before this tile must have landed; this tile's own loads may fly on
-    if (k_more) SATTN_WAIT_VMCNT(NIK + NIV);
-    else if (v_more) SATTN_WAIT_VMCNT(NIV);
-    else SATTN_WAIT_VMCNT(0);
+    if (VS == 3) {
+      if (k_more) SATTN_WAIT_VMCNT(NIK + NIV);
+      else if (v_more) SATTN_WAIT_VMCNT(NIV);
+      else SATTN_WAIT_VMCNT(0);
+    } else {
+      if (k_more) SATTN_WAIT_VMCNT(NIK);  // V(t+1) was issued first and has landed
+      else SATTN_WAIT_VMCNT(0);
+    }
     __syncthreads();
   }
   // flush: O^T update of the last chunk when it fell on the last step of the loop

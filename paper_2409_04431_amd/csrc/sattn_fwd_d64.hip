@@ -1,4 +1,4 @@
 // Forward bf16 kernels for head dimension 64.
 #include "sattn_fwd_launch.hpp"
 
-template int sattn::launch_fwd_bf16<64>(sattn::FwdParams, int, bool, bool, int, bool, hipStream_t);
+template int sattn::launch_fwd_bf16<64>(sattn::FwdParams, int, int, bool, bool, int, bool, hipStream_t);

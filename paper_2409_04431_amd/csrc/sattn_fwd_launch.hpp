@@ -4,27 +4,35 @@
 
 namespace sattn {
 
-template <int D, int NW, bool SOFTMAX, bool PIN>
+template <int D, int NW, int VS, bool SOFTMAX, bool PIN>
 int launch_fwd_variant(FwdParams p, int causal, bool alibi, hipStream_t st) {
-  constexpr size_t lds = 6 * 64 * D * 2;  // 3 K slots + 3 V slots of 64 keys
+  constexpr size_t lds = (3 + VS) * 64 * D * 2;  // 3 K slots + VS V slots of 64 keys
   p.n_qblocks = (p.N + 32 * NW - 1) / (32 * NW);
   dim3 grid(p.n_qblocks * p.B * p.H), block(64 * NW);
   int rc = SATTN_OK;
-  SATTN_DISPATCH2(causal, alibi, rc = launch(attn_fwd_kernel<D, NW, A, B2, SOFTMAX, PIN>, grid, block, lds, st, p));
+  SATTN_DISPATCH2(causal, alibi, rc = launch(attn_fwd_kernel<D, NW, A, B2, SOFTMAX, PIN, VS>, grid, block, lds, st, p));
   return rc;
 }
 
+template <int D, int NW, int VS>
+int launch_fwd_shape(const FwdParams& p, bool softmax, bool pin, int causal, bool alibi, hipStream_t st) {
+  if (softmax) return launch_fwd_variant<D, NW, VS, true, false>(p, causal, alibi, st);
+  if (pin) return launch_fwd_variant<D, NW, VS, false, true>(p, causal, alibi, st);
+  return launch_fwd_variant<D, NW, VS, false, false>(p, causal, alibi, st);
+}
+
 template <int D>
-int launch_fwd_bf16(FwdParams p, int waves, bool softmax, bool pin, int causal, bool alibi, hipStream_t st) {
+int launch_fwd_bf16(FwdParams p, int waves, int v_slots, bool softmax, bool pin, int causal, bool alibi,
+                    hipStream_t st) {
   if (p.kv_group < 1 || p.H % p.kv_group) return SATTN_ERR_SHAPE;
   if (waves == 4) {
-    if (softmax) return launch_fwd_variant<D, 4, true, false>(p, causal, alibi, st);
-    if (pin) return launch_fwd_variant<D, 4, false, true>(p, causal, alibi, st);
-    return launch_fwd_variant<D, 4, false, false>(p, causal, alibi, st);
+    // the two-slot V ring only matters at D = 128, where it lets two workgroups share a compute unit
+    if constexpr (D == 128) {
+      if (v_slots == 2) return launch_fwd_shape<D, 4, 2>(p, softmax, pin, causal, alibi, st);
+    }
+    return launch_fwd_shape<D, 4, 3>(p, softmax, pin, causal, alibi, st);
   }
-  if (softmax) return launch_fwd_variant<D, 8, true, false>(p, causal, alibi, st);
-  if (pin) return launch_fwd_variant<D, 8, false, true>(p, causal, alibi, st);
-  return launch_fwd_variant<D, 8, false, false>(p, causal, alibi, st);
+  return launch_fwd_shape<D, 8, 3>(p, softmax, pin, causal, alibi, st);
 }
 
 }  // namespace sattn

@@ -37,10 +37,12 @@ int launch(K kernel, dim3 grid, dim3 block, size_t lds, hipStream_t st, Args... 
 
 enum BwdPart { kBwdDkDv = 1, kBwdDq = 2 };
 
-// Forward: `waves` (4 or 8) is the number of 32-query-row waves per workgroup; sets
-// p.n_qblocks accordingly.  softmax selects the comparison kernel, pin the hand-ordered step.
+// Forward: `waves` (4 or 8) is the number of 32-query-row waves per workgroup (sets
+// p.n_qblocks accordingly), `v_slots` (2 or 3) the depth of the V ring of 4-wave workgroups
+// at D = 128.  softmax selects the comparison kernel, pin the hand-ordered step.
 template <int D>
-int launch_fwd_bf16(FwdParams p, int waves, bool softmax, bool pin, int causal, bool alibi, hipStream_t st);
+int launch_fwd_bf16(FwdParams p, int waves, int v_slots, bool softmax, bool pin, int causal, bool alibi,
+                    hipStream_t st);
 
 // Backward: `parts` is a mask of BwdPart; p.db_rows selects the dQ pass with row sums.
 template <int D>

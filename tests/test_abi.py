@@ -100,19 +100,26 @@ def test_bias_gradient_entry_point_rejects_bad_arguments(lib):
     assert lib.sigmoid_attn_bwd_bias_grad(*ptrs, 0x8000, None, *tail) == -3          # head dimension
 
 
-def test_forward_wave_choice(lib):
-    # d = 64 always takes 4-wave workgroups; d = 128 only while the problem is small
-    assert sa.sattn_fwd_waves(32, 12, 4096, 64) == 4
-    assert sa.sattn_fwd_waves(8, 16, 4096, 128, True) == 8
-    assert sa.sattn_fwd_waves(1, 2, 512, 128) == 4
-    assert lib.sattn_fwd_waves(1, 1, 16, 100, 0) == -3
+def test_forward_shape_choice(lib):
+    # d = 64 always takes 4-wave workgroups; d = 128 while the grid is small (one per compute unit,
+    # three-slot V ring) or the key loop short (two per compute unit, two-slot V ring)
+    assert sa.sattn_fwd_waves(32, 12, 4096, 64) == 4 and sa.sattn_fwd_v_slots(32, 12, 4096, 64) == 3
+    assert (sa.sattn_fwd_waves(8, 16, 4096, 128, True), sa.sattn_fwd_v_slots(8, 16, 4096, 128, True)) == (4, 2)
+    assert (sa.sattn_fwd_waves(1, 32, 16384, 128, True), sa.sattn_fwd_v_slots(1, 32, 16384, 128, True)) == (8, 3)
+    assert (sa.sattn_fwd_waves(1, 2, 512, 128), sa.sattn_fwd_v_slots(1, 2, 512, 128)) == (4, 3)
+    assert lib.sattn_fwd_waves(1, 1, 16, 100, 0) == -3 and lib.sattn_fwd_v_slots(1, 1, 16, 100, 0) == -3
     assert lib.sattn_fwd_waves(0, 1, 16, 64, 0) == -2
-    assert lib.sattn_set_fwd_waves(3) == -3
+    assert lib.sattn_set_fwd_waves(3) == -3 and lib.sattn_set_fwd_v_slots(4) == -3
     try:
         sa.sattn_set_fwd_waves(8)
         assert sa.sattn_fwd_waves(1, 2, 512, 128) == 8 and sa.sattn_fwd_waves(1, 2, 512, 64) == 8
+        assert sa.sattn_fwd_v_slots(8, 16, 4096, 128, True) == 3      # no two-slot ring with 8 waves
+        sa.sattn_set_fwd_waves(4)
+        sa.sattn_set_fwd_v_slots(2)
+        assert sa.sattn_fwd_v_slots(1, 32, 16384, 128, True) == 2 and sa.sattn_fwd_v_slots(1, 2, 512, 64) == 3
     finally:
         sa.sattn_set_fwd_waves(0)
+        sa.sattn_set_fwd_v_slots(0)
     assert sa.sattn_fwd_waves(1, 2, 512, 64) == 4
 
 

@@ -446,8 +446,9 @@ def test_forward_tile_shapes_agree_bit_for_bit_and_with_the_oracle(B, H, N, d, c
     q, k, v = (_dev(inp[n]) for n in ("q", "k", "v"))
     outs, souts = {}, {}
     try:
-        for waves in (4, 8):
-            sa.sattn_set_fwd_waves(waves)
+        for waves, vs in ((4, 3), (8, 3), (42, 2)):     # 42: 4 waves with the two-slot V ring
+            sa.sattn_set_fwd_waves(4 if waves == 42 else waves)
+            sa.sattn_set_fwd_v_slots(vs)
             o = torch.full_like(q, float("nan"))
             so = torch.full_like(q, float("nan"))
             lse = torch.full((B, H, N), float("nan"), dtype=torch.float32, device="cuda")
@@ -457,8 +458,10 @@ def test_forward_tile_shapes_agree_bit_for_bit_and_with_the_oracle(B, H, N, d, c
             outs[waves], souts[waves] = o, (so, lse)
     finally:
         sa.sattn_set_fwd_waves(0)
-    assert torch.equal(outs[4], outs[8])
-    assert torch.equal(souts[4][0], souts[8][0]) and torch.equal(souts[4][1], souts[8][1])
+        sa.sattn_set_fwd_v_slots(0)
+    for other in (8, 42):
+        assert torch.equal(outs[4], outs[other])
+        assert torch.equal(souts[4][0], souts[other][0]) and torch.equal(souts[4][1], souts[other][1])
     f = lambda t: inp[t].double().numpy()
     assert nerr(outs[4], orc.sigmoid_attn_fwd(f("q"), f("k"), f("v"), bias, causal, slopes)) <= TOL_BF16
     ro, rl = orc.softmax_attn_fwd(f("q"), f("k"), f("v"), causal, slopes)
