@@ -667,10 +667,14 @@ attn_bwd_kernel(const BwdParams p) {
   // the compiler-scheduled step.
   auto step_kind = [&](int s, bool& pin, int& thr) {
     constexpr int NONE = MODE == BWD_DKDV ? 1000 : -1000, ALL = -NONE;
+    const bool doA = s >= c_lo_s && s <= c_hi_s;
     const bool doS = s - 1 >= c_lo_s && s - 1 <= c_hi_s;
+    const bool doB = s - 2 >= c_lo_s && s - 2 <= c_hi_s;
     const int cs = 32 * (s - 1), bl = cs + 8 * h;
     const bool ragged = doS && s - 1 == c_hi_s && cs + 32 > Nt;
-    pin = PIN && !SOFTMAX && !(MODE == BWD_DKDV && ragged);
+    // a step with at most one live stage (first and last step of the wave's range, steps
+    // outside it) is cheaper in the flag-driven form, which skips the dead stages
+    pin = PIN && !SOFTMAX && !(MODE == BWD_DKDV && ragged) && (int)doA + (int)doS + (int)doB >= 2;
     if (!doS) thr = NONE;
     else if (MODE == BWD_DKDV) thr = (CAUSAL && s - 1 == c_lo_s) ? ai - bl : ALL;
     else thr = (s - 1 == c_hi_s) ? ((CAUSAL && ai < Nt - 1 ? ai : Nt - 1) - bl) : ALL;
