@@ -713,9 +713,11 @@ attn_bwd_kernel(const BwdParams p) {
         bool pin_s;
         int thr;
         step_kind(s, pin_s, thr);
-        if (lane_flag(pin_s))
-          bwd_step_full_pinned<D, MODE, ALIBI, FOLD, 0, false, true>(W, 0, W.row0, CHUNK, 32 * (s - 1), st1, st2, 0, uwave, thr);
-        else
+        constexpr bool kPinned = PIN && !SOFTMAX;  // the other kernels do not carry the pinned code at all
+        if (kPinned && lane_flag(pin_s)) {
+          if constexpr (kPinned)
+            bwd_step_full_pinned<D, MODE, ALIBI, FOLD, 0, false, true>(W, 0, W.row0, CHUNK, 32 * (s - 1), st1, st2, 0, uwave, thr);
+        } else
           bwd_step<D, MODE, CAUSAL, ALIBI, SOFTMAX, 0>(W, lane_flag(doA_s), lane_flag(doS_s), lane_flag(doB_s),
                                                        lane_flag(mask_s), 0, W.row0, CHUNK, 32 * (s - 1), Nt, stat);
       }
@@ -740,16 +742,18 @@ attn_bwd_kernel(const BwdParams p) {
           load_stat(t + 2);
         }
         // rows of chunk s+1 come from tile t+1 (first half); transposed reads of chunk s-2 from tile t-1 (second half)
-        if (lane_flag(pin_s))
-          bwd_step_full_pinned<D, MODE, ALIBI, FOLD, 1, false, true>(W, CHUNK, W.row1, 0, 32 * (s - 1), st1, st2, 0, uwave, thr);
-        else
+        constexpr bool kPinned = PIN && !SOFTMAX;  // the other kernels do not carry the pinned code at all
+        if (kPinned && lane_flag(pin_s)) {
+          if constexpr (kPinned)
+            bwd_step_full_pinned<D, MODE, ALIBI, FOLD, 1, false, true>(W, CHUNK, W.row1, 0, 32 * (s - 1), st1, st2, 0, uwave, thr);
+        } else
           bwd_step<D, MODE, CAUSAL, ALIBI, SOFTMAX, 1>(W, lane_flag(doA_s), lane_flag(doS_s), lane_flag(doB_s),
                                                        lane_flag(mask_s), CHUNK, W.row1, 0, 32 * (s - 1), Nt, stat);
         if (more) store_stat(t + 2);
       }
       rotate(t);
     }
-    if (phase == 0) {
+    if constexpr (PIN && !SOFTMAX) if (phase == 0) {
       for (; t <= t_s1; ++t) {
         bwd_step_full_pinned<D, MODE, ALIBI, FOLD, 0, false>(W, 0, W.row0, CHUNK, 32 * (2 * t - 1), st1, st2, 0, uwave);
         __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): tile t+1 has landed
