@@ -122,7 +122,8 @@ int softmax_attn_fwd(const void* q, const void* k, const void* v, void* o, float
                      void* stream);
 
 /* Softmax backward: dS = P (dP - rowsum(dO o O)); reads O and lse from the forward.
- * The workspace holds the rowsum vector D [B,H,N] fp32. */
+ * The workspace holds two fp32 vectors per query row (the rowsum D and the rescaled log-sum-exp),
+ * rows padded to a multiple of 64: softmax_attn_bwd_workspace_bytes() says how much. */
 int softmax_attn_bwd(const void* q, const void* k, const void* v, const void* o,
                      const float* lse, const void* dout,
                      void* dq, void* dk, void* dv,

@@ -280,16 +280,21 @@ int bwd_impl(const BwdArgs& a) {
   if (SOFTMAX) {
     if (!a.lse) return SATTN_ERR_NULL;
     if ((rc = make_ref(a.o, a.so, a.H, a.N, a.d, a.dtype, &o))) return rc;
-    const size_t need = (size_t)a.B * a.H * a.N * sizeof(float);
+    const int npad = (a.N + 63) / 64 * 64;
+    const int64_t prows = (int64_t)a.B * a.H * npad;
+    const size_t need = 2 * (size_t)prows * sizeof(float);
     if (!a.workspace || a.workspace_bytes < need) return SATTN_ERR_WORKSPACE;
     if (((uintptr_t)a.workspace & 15) != 0) return SATTN_ERR_ALIGN;
-    float* dvec = (float*)a.workspace;
-    const int64_t rows = (int64_t)a.B * a.H * a.N;
-    dim3 grid((unsigned)((rows + 15) / 16)), block(256);
-    if (a.d == 128) rc = launch(rowsum_do_o_kernel<128>, grid, block, 0, st, o, dout, dvec, a.B, a.H, a.N);
-    else rc = launch(rowsum_do_o_kernel<64>, grid, block, 0, st, o, dout, dvec, a.B, a.H, a.N);
+    if ((prows + 15) / 16 > 0x7fffffffLL) return SATTN_ERR_SHAPE;
+    float* nlse2 = (float*)a.workspace;
+    float* dvec = nlse2 + prows;
+    dim3 grid((unsigned)((prows + 15) / 16)), block(256);
+    if (a.d == 128)
+      rc = launch(softmax_bwd_prepass_kernel<128>, grid, block, 0, st, o, dout, a.lse, nlse2, dvec, a.B, a.H, a.N, npad);
+    else
+      rc = launch(softmax_bwd_prepass_kernel<64>, grid, block, 0, st, o, dout, a.lse, nlse2, dvec, a.B, a.H, a.N, npad);
     if (rc) return rc;
-    p.lse = a.lse; p.dvec = dvec;
+    p.nlse2 = nlse2; p.dvec = dvec; p.npad = npad;
   }
   if (a.d == 128) rc = launch_bwd_bf16<128>(p, SOFTMAX, PIN, a.causal, alibi, a.parts, st);
   else rc = launch_bwd_bf16<64>(p, SOFTMAX, PIN, a.causal, alibi, a.parts, st);
@@ -429,7 +434,8 @@ int softmax_attn_bwd(const void* q, const void* k, const void* v, const void* o,
 
 size_t softmax_attn_bwd_workspace_bytes(int B, int H, int N, int d, sattn_dtype dtype) {
   if (check_shape(B, H, N, d, dtype) != SATTN_OK) return 0;
-  return (size_t)B * H * N * sizeof(float);  // rowsum(dO o O), one fp32 per query row
+  // rowsum(dO o O) and the rescaled log-sum-exp: two fp32 per query row, rows padded to 64
+  return 2 * (size_t)B * H * ((N + 63) / 64 * 64) * sizeof(float);
 }
 
 const char* sattn_strerror(int code) {

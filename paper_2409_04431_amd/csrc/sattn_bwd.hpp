@@ -33,8 +33,11 @@ enum BwdMode { BWD_DQ = 0, BWD_DKDV = 1, BWD_DQ_DB = 2 };
 struct BwdParams {
   TensorRef q, k, v, dout, dq, dk, dv;
   const float* slopes;
-  const float* lse;    // softmax only: [B,H,N] natural-log row log-sum-exp from the forward
-  const float* dvec;   // softmax only: [B,H,N] rowsum(dO o O)
+  // softmax only, written by the pre-pass: per query row -lse*log2(e) and rowsum(dO o O), each
+  // [B*H, npad] with rows padded to a multiple of 64 (pad entries are zero)
+  const float* nlse2;
+  const float* dvec;
+  int npad;
   int B, H, N;
   int n_blocks;        // blocks of 128 stationary rows
   float nscale_log2;   // -log2(e)/sqrt(d)
@@ -219,7 +222,7 @@ __device__ __forceinline__ void mfma_pin(f32x16& a, f32x16& b) { asm volatile(""
 template <int D, int MODE, bool CAUSAL, bool ALIBI, bool SOFTMAX, int PAR>
 __device__ __forceinline__ void bwd_step(BwdWave<D, MODE>& W, bool doA, bool doS, bool doB, bool mask, uint32_t trimm,
                                          const uint32_t* nextrow, uint32_t nextimm, int cs, int N,
-                                         const SATTN_LDS(float)* stat) {
+                                         const float* stat_l, const float* stat_d) {
   constexpr int KD = D / 16, DT = D / 32;
   constexpr uint32_t T2OFF = 64 * D * 2;  // tensor 2's tile follows tensor 1's inside a ring slot
   // FOLD (sigmoid, causal, ALiBi): every unmasked pair has its key at or before its query, so
@@ -242,16 +245,27 @@ __device__ __forceinline__ void bwd_step(BwdWave<D, MODE>& W, bool doA, bool doS
     // chunk s-1 lives in buffers [PAR^1]; streamed index of register r: b = cs + 8h + key_of_reg(r)
     const int bl = cs + 8 * W.h;
     float pr[16], ds[16];
+    // softmax dK/dV: the statistics of the 16 streamed queries this lane's registers belong to
+    // (queries bl .. bl+7 and bl+16 .. bl+23), straight from global memory: every lane of a wave
+    // half reads the same 2 x 32 bytes, which the vector cache serves as one request
+    f32x4 sl[4], sd[4];
+    if (SOFTMAX && MODE == BWD_DKDV) {
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        sl[g] = *(const f32x4*)(stat_l + bl + 16 * (g >> 1) + 4 * (g & 1));
+        sd[g] = *(const f32x4*)(stat_d + bl + 16 * (g >> 1) + 4 * (g & 1));
+      }
+    }
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
       const int b = bl + key_of_reg(r);
       const int qrow = MODE == BWD_DKDV ? b : W.ai, krow = MODE == BWD_DKDV ? W.ai : b;
       if (SOFTMAX) {
         // p = 2^(s*log2e/sqrt(d) - slope|i-j|log2e - lse*log2e), dS = p (dP - D)
-        float w = MODE == BWD_DKDV ? stat[key_of_reg(r)] : W.nlse;
+        float w = MODE == BWD_DKDV ? sl[r >> 2][r & 3] : W.nlse;
         if (ALIBI) w = __builtin_fmaf(-W.sl2, __builtin_fabsf((float)(qrow - krow)), w);
         pr[r] = __builtin_amdgcn_exp2f(__builtin_fmaf(W.s[PAR ^ 1][r], -W.nscale, w));
-        const float dd = MODE == BWD_DKDV ? stat[64 + key_of_reg(r)] : W.dstat;
+        const float dd = MODE == BWD_DKDV ? sd[r >> 2][r & 3] : W.dstat;
         ds[r] = pr[r] * (W.dp[PAR ^ 1][r] - dd);
       } else {
         // p = 1/(1 + 2^u), dS = (p - p^2) dP
@@ -481,8 +495,6 @@ attn_bwd_kernel(const BwdParams p) {
   constexpr int TILE = BC * D * 2, SLOT = 2 * TILE, CHUNK = 32 * D * 2, NSLOT = 4;
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   const uint32_t lds0 = (uint32_t)(uintptr_t)(SATTN_LDS(char)*)smem;
-  // softmax DKDV: per-row statistics of the streamed query tiles, [slot][0: -lse*log2e | 1: D][64]
-  SATTN_LDS(float)* statbase = (SATTN_LDS(float)*)(smem + NSLOT * SLOT);
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, h = lane >> 5;
   const int uwave = __builtin_amdgcn_readfirstlane(wave);
@@ -543,8 +555,8 @@ attn_bwd_kernel(const BwdParams p) {
   W.nlse = 0.f; W.dstat = 0.f;
   W.dbs[0] = W.dbs[1] = W.dbs[2] = W.dbs[3] = 0.f;
   if (SOFTMAX && MODE != BWD_DKDV) {
-    W.nlse = -p.lse[((int64_t)b * p.H + hq0) * N + ai_ld] * kLog2e;
-    W.dstat = p.dvec[((int64_t)b * p.H + hq0) * N + ai_ld];
+    W.nlse = p.nlse2[((int64_t)b * p.H + hq0) * p.npad + ai_ld];
+    W.dstat = p.dvec[((int64_t)b * p.H + hq0) * p.npad + ai_ld];
   }
 
   // chunk range of the streamed side: workgroup [wg_lo, wg_hi], this wave [c_lo, c_hi]
@@ -572,7 +584,9 @@ attn_bwd_kernel(const BwdParams p) {
   for (int hq = hq0; hq < hq0 + n_hq; ++hq) {  // one pass of the pipeline per query head
   const __bf16* y1b = MODE == BWD_DKDV ? qhead(hq) : kbase;
   const __bf16* y2b = MODE == BWD_DKDV ? dohead(hq) : vbase;
-  const int64_t stat_row0 = ((int64_t)b * p.H + hq) * N;  // softmax statistics of query head hq
+  // softmax statistics of query head hq
+  const float* stat_l = SOFTMAX ? p.nlse2 + ((int64_t)b * p.H + hq) * p.npad : nullptr;
+  const float* stat_d = SOFTMAX ? p.dvec + ((int64_t)b * p.H + hq) * p.npad : nullptr;
   W.sl2 = ALIBI ? p.slopes[hq] * kLog2e : 0.f;
   // the pipeline starts empty: the second-product stage of the first steps must add zeros
   {
@@ -608,17 +622,6 @@ attn_bwd_kernel(const BwdParams p) {
   DmaStagerX<D, NW> st1, st2;
   st1.init(y1b, y1s, Nt, t_lo * BC, uwave, lane);
   st2.init(y2b, y2s, Nt, t_lo * BC, uwave, lane);
-  float statreg = 0.f;
-  auto load_stat = [&](int t) {
-    if (SOFTMAX && MODE == BWD_DKDV && tid < 128) {
-      int row = t * BC + (tid & 63);
-      row = row < N ? row : N - 1;
-      statreg = tid < 64 ? -p.lse[stat_row0 + row] * kLog2e : p.dvec[stat_row0 + row];
-    }
-  };
-  auto store_stat = [&](int t) {
-    if (SOFTMAX && MODE == BWD_DKDV && tid < 128) statbase[(t % NSLOT) * 128 + tid] = statreg;
-  };
   // prologue: tiles t_lo and t_lo+1, and tile t_lo-1 (tile 0 again for t_lo = 0): the pinned
   // steps run their second-product stage from the first step on (with zero P / dS until the
   // pipeline has filled), so the slot it reads must hold finite data
@@ -632,13 +635,9 @@ attn_bwd_kernel(const BwdParams p) {
   }
   st1.issue(lds0 + (t_lo % NSLOT) * SLOT, Nt, uwave, lane);
   st2.issue(lds0 + (t_lo % NSLOT) * SLOT + TILE, Nt, uwave, lane);
-  load_stat(t_lo);
-  store_stat(t_lo);
   if (t_lo + 1 <= t_data_hi) {
     st1.issue(lds0 + ((t_lo + 1) % NSLOT) * SLOT, Nt, uwave, lane);
     st2.issue(lds0 + ((t_lo + 1) % NSLOT) * SLOT + TILE, Nt, uwave, lane);
-    load_stat(t_lo + 1);
-    store_stat(t_lo + 1);
   }
   __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): prologue tiles landed, stationary fragments in registers
   __syncthreads();
@@ -707,8 +706,6 @@ attn_bwd_kernel(const BwdParams p) {
         const int s = 2 * t;
         bool doA_s, doS_s, doB_s, mask_s;
         flags(s, doA_s, doS_s, doB_s, mask_s);
-        // chunk s-1 sits in tile (s-1)/2
-        const SATTN_LDS(float)* stat = statbase + (((s - 1) >> 1) & (NSLOT - 1)) * 128 + ((s - 1) & 1) * 32 + 8 * h;
         // rows of chunk s+1 come from tile t (second half); transposed reads of chunk s-2 from tile t-1 (first half)
         bool pin_s;
         int thr;
@@ -719,18 +716,16 @@ attn_bwd_kernel(const BwdParams p) {
             bwd_step_full_pinned<D, MODE, ALIBI, FOLD, 0, false, true>(W, 0, W.row0, CHUNK, 32 * (s - 1), st1, st2, 0, uwave, thr);
         } else
           bwd_step<D, MODE, CAUSAL, ALIBI, SOFTMAX, 0>(W, lane_flag(doA_s), lane_flag(doS_s), lane_flag(doB_s),
-                                                       lane_flag(mask_s), 0, W.row0, CHUNK, 32 * (s - 1), Nt, stat);
+                                                       lane_flag(mask_s), 0, W.row0, CHUNK, 32 * (s - 1), Nt, stat_l, stat_d);
       }
       __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): tile t+1 has landed
       // A bare barrier: fragment reads of the tiles that stay in the ring may remain in flight
-      // across it.  Only the softmax statistics are LDS writes that the other waves wait for.
-      if (SOFTMAX && MODE == BWD_DKDV) __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
+      // across it.
       __builtin_amdgcn_s_barrier();
       {
         const int s = 2 * t + 1;
         bool doA_s, doS_s, doB_s, mask_s;
         flags(s, doA_s, doS_s, doB_s, mask_s);
-        const SATTN_LDS(float)* stat = statbase + (((s - 1) >> 1) & (NSLOT - 1)) * 128 + ((s - 1) & 1) * 32 + 8 * h;
         bool pin_s;
         int thr;
         step_kind(s, pin_s, thr);
@@ -739,7 +734,6 @@ attn_bwd_kernel(const BwdParams p) {
           const uint32_t dma_lds = lds0 + ((t + 2) % NSLOT) * SLOT;
           st1.issue(dma_lds, Nt, uwave, lane);
           st2.issue(dma_lds + TILE, Nt, uwave, lane);
-          load_stat(t + 2);
         }
         // rows of chunk s+1 come from tile t+1 (first half); transposed reads of chunk s-2 from tile t-1 (second half)
         constexpr bool kPinned = PIN && !SOFTMAX;  // the other kernels do not carry the pinned code at all
@@ -748,8 +742,7 @@ attn_bwd_kernel(const BwdParams p) {
             bwd_step_full_pinned<D, MODE, ALIBI, FOLD, 1, false, true>(W, CHUNK, W.row1, 0, 32 * (s - 1), st1, st2, 0, uwave, thr);
         } else
           bwd_step<D, MODE, CAUSAL, ALIBI, SOFTMAX, 1>(W, lane_flag(doA_s), lane_flag(doS_s), lane_flag(doB_s),
-                                                       lane_flag(mask_s), CHUNK, W.row1, 0, 32 * (s - 1), Nt, stat);
-        if (more) store_stat(t + 2);
+                                                       lane_flag(mask_s), CHUNK, W.row1, 0, 32 * (s - 1), Nt, stat_l, stat_d);
       }
       rotate(t);
     }
@@ -806,18 +799,21 @@ attn_bwd_kernel(const BwdParams p) {
   }
 }
 
-// D_i = sum_t dO[i][t] * O[i][t] (fp32), the row term of the softmax backward.  16 lanes per
-// row, 8 elements per lane and pass.
+// Pre-pass of the softmax backward: per query row D_i = sum_t dO[i][t] * O[i][t] (fp32) and
+// -lse_i * log2(e), written to [B*H, npad] vectors (npad = N rounded up to 64; pad entries 0 so
+// that the kernels may read whole chunks).  16 lanes per row, 8 elements per lane and pass.
 template <int D>
 __global__ void __launch_bounds__(256)
-rowsum_do_o_kernel(TensorRef o, TensorRef dout, float* dvec, int B, int H, int N) {
-  const int64_t row = (int64_t)blockIdx.x * 16 + (threadIdx.x >> 4);
+softmax_bwd_prepass_kernel(TensorRef o, TensorRef dout, const float* lse, float* nlse2, float* dvec, int B, int H,
+                           int N, int npad) {
+  const int64_t prow = (int64_t)blockIdx.x * 16 + (threadIdx.x >> 4);  // padded row index
   const int sub = threadIdx.x & 15;
-  const int64_t rows = (int64_t)B * H * N;
+  const int64_t prows = (int64_t)B * H * npad;
+  if (prow >= prows) return;  // whole 16-lane group
+  const int64_t bh = prow / npad;
+  const int i = (int)(prow % npad);
   float acc = 0.f;
-  if (row < rows) {
-    const int64_t bh = row / N;
-    const int i = (int)(row % N);
+  if (i < N) {
     const int b = (int)(bh / H), hd = (int)(bh % H);
     const __bf16* op = (const __bf16*)o.ptr + b * o.sb + hd * o.sh + (int64_t)i * o.ss;
     const __bf16* dp = (const __bf16*)dout.ptr + b * dout.sb + hd * dout.sh + (int64_t)i * dout.ss;
@@ -831,7 +827,10 @@ rowsum_do_o_kernel(TensorRef o, TensorRef dout, float* dvec, int B, int H, int N
   }
 #pragma unroll
   for (int m = 8; m >= 1; m >>= 1) acc += __shfl_xor(acc, m, 16);
-  if (row < rows && sub == 0) dvec[row] = acc;
+  if (sub == 0) {
+    dvec[prow] = acc;
+    nlse2[prow] = i < N ? -lse[bh * N + i] * kLog2e : 0.f;
+  }
 }
 
 }  // namespace sattn

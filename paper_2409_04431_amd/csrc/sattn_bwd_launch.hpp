@@ -11,7 +11,6 @@ int launch_bwd_variant(BwdParams p, int causal, bool alibi, int parts, hipStream
   dim3 grid(nb_q * p.B * p.H), grid_k(nb_k * p.B * p.H), grid_kv(nb_k * p.B * (p.H / p.kv_group));
   int rc = SATTN_OK;
   constexpr size_t lds = 4 * 2 * 64 * D * 2;                    // 4 ring slots of two 64-row tiles
-  constexpr size_t lds_stat = SOFTMAX ? 4 * 128 * sizeof(float) : 0;  // per-slot lse and D of the query tile
   dim3 block(256);
   if (p.kv_group < 1 || p.H % p.kv_group) return SATTN_ERR_SHAPE;
   if (p.kv_group > 1 && (SOFTMAX || !PIN)) return SATTN_ERR_UNSUPPORTED;  // only the product kernels share K/V heads
@@ -24,7 +23,7 @@ int launch_bwd_variant(BwdParams p, int causal, bool alibi, int parts, hipStream
     }
     if (p.kv_group == 1)
       SATTN_DISPATCH2(causal, alibi,
-                      rc = launch(attn_bwd_kernel<D, BWD_DKDV, A, B2, SOFTMAX, PIN>, grid_k, block, lds + lds_stat, st, p));
+                      rc = launch(attn_bwd_kernel<D, BWD_DKDV, A, B2, SOFTMAX, PIN>, grid_k, block, lds, st, p));
   }
   p.n_blocks = nb_q;
   if (rc == SATTN_OK && (parts & kBwdDq)) {
