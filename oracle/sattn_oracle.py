@@ -40,8 +40,6 @@ def _load():
     if _lib is None:
         build()
         _lib = ctypes.CDLL(_LIB)
-        for name in dir(_lib):
-            pass
         _lib.oracle_num_threads.restype = ctypes.c_int
     return _lib
 

@@ -440,21 +440,101 @@ def test_row_sampling_entry_points_match_full_pass(causal):
         np.testing.assert_allclose(rv, dv[0, h, rows], rtol=1e-12, atol=1e-15)
 
 
-def test_planted_mistakes_are_caught_by_the_pins():
-    """The pins above are only useful if plausible mistakes break them.  Re-evaluate three
-    pins against deliberately wrong variants (written here, in torch) and check they fail."""
-    N, d = 6, 4
-    q, k, v = _rand(1, 1, N, d), _rand(1, 1, N, d), _rand(1, 1, N, d)
-    good = orc.sigmoid_attn_fwd(q, k, v, -0.5)
+# ------------------------------------------------------------------ the pins catch planted mistakes
 
-    def variant(scale, bias_inside, transpose):
+def _mutant(kind):
+    """A numpy sigmoid attention (forward, backward) with one deliberate mistake `kind`
+    (None: no mistake).  Lives here, on the CPU, only to show that the pins above fail on it."""
+
+    def probs(q, k, bias, causal, slopes):
+        B, H, N, d = q.shape
+        scale = 1.0 if kind == "dropped_scale" else math.sqrt(d) if kind == "sqrt_d_scale" else 1.0 / math.sqrt(d)
         s = np.einsum("bhid,bhjd->bhij", q, k)
-        if transpose:
+        if kind == "qk_swapped":
             s = s.transpose(0, 1, 3, 2)
-        s = (s + (-0.5 if bias_inside else 0.0)) * scale + (0.0 if bias_inside else -0.5)
-        return (1 / (1 + np.exp(-s))) @ v
+        t = (s + bias) * scale if kind == "bias_before_scale" else s * scale + bias
+        idx = np.arange(N)
+        if slopes is not None:
+            dist = np.abs(idx[:, None] - idx[None, :]).astype(np.float64)
+            sgn = 1.0 if kind == "alibi_sign" else -1.0
+            t = t + sgn * np.asarray(slopes, dtype=np.float64)[None, :, None, None] * dist
+        p = 1.0 / (1.0 + np.exp(-t))
+        if causal:
+            keep = idx[None, :] < idx[:, None] if kind == "diagonal_masked" else idx[None, :] <= idx[:, None]
+            if kind == "mask_flipped":
+                keep = idx[None, :] >= idx[:, None]
+            p = p * keep
+        return p
 
-    assert np.allclose(variant(1 / math.sqrt(d), False, False), good, rtol=1e-12)
-    assert not np.allclose(variant(1.0, False, False), good, rtol=1e-6)            # dropped scale
-    assert not np.allclose(variant(1 / math.sqrt(d), True, False), good, rtol=1e-6)  # bias before scale
-    assert not np.allclose(variant(1 / math.sqrt(d), False, True), good, rtol=1e-6)  # Q/K swapped
+    def fwd(q, k, v, bias, causal=False, alibi_slopes=None):
+        q, k, v = (np.asarray(x, dtype=np.float64) for x in (q, k, v))
+        return probs(q, k, bias, causal, alibi_slopes) @ v
+
+    def bwd(q, k, v, dout, bias, causal=False, alibi_slopes=None):
+        q, k, v, dout = (np.asarray(x, dtype=np.float64) for x in (q, k, v, dout))
+        d = q.shape[-1]
+        p = probs(q, k, bias, causal, alibi_slopes)
+        dv = np.einsum("bhij,bhid->bhjd", p, dout)
+        if kind == "dv_not_transposed":
+            dv = np.einsum("bhij,bhjd->bhid", p, dout)
+        dp = np.einsum("bhid,bhjd->bhij", dout, v)
+        ds = p * dp if kind == "dropped_one_minus_p" else p * (1.0 - p) * dp
+        g = math.sqrt(d) if kind == "bwd_sqrt_d" else 1.0 / math.sqrt(d)   # the factor the paper's table prints
+        dq = np.einsum("bhij,bhjd->bhid", ds, k) * g
+        dk = np.einsum("bhij,bhid->bhjd", ds, q) * g
+        if kind == "dq_dk_swapped":
+            dq, dk = dk, dq
+        return dq, dk, dv
+
+    return fwd, bwd
+
+
+_FWD_PINS = [
+    lambda: test_zero_logits_give_sigma_b_times_sum_of_visible_v(True, 3),
+    test_paper_bias_values,
+    test_single_token_scalar_case_fixes_scale_and_bias_order,
+    test_two_token_hand_example_fixes_operand_roles,
+    test_sequence_form_with_log_n_bias,
+    test_reflection_symmetry,
+    test_alibi_closed_form_and_zero_slope,
+]
+_BWD_PINS = [
+    lambda: test_backward_by_central_finite_differences(True, True),
+    test_zero_logit_gradients_closed_form,
+    lambda: test_against_torch_fp64_autograd(True, True, (1, 2, 33, 8)),
+]
+
+
+def _failing_pins(pins):
+    failed = 0
+    for pin in pins:
+        try:
+            pin()
+        except AssertionError:
+            failed += 1
+    return failed
+
+
+def test_the_unmutated_twin_passes_every_pin(monkeypatch):
+    # the harness itself: without a planted mistake the numpy twin satisfies all the pins, so a
+    # failure below is caused by the mistake and not by the twin
+    fwd, bwd = _mutant(None)
+    monkeypatch.setattr(orc, "sigmoid_attn_fwd", fwd)
+    monkeypatch.setattr(orc, "sigmoid_attn_bwd", bwd)
+    assert _failing_pins(_FWD_PINS + _BWD_PINS) == 0
+
+
+@pytest.mark.parametrize("kind,pins", [
+    ("dropped_scale", _FWD_PINS), ("sqrt_d_scale", _FWD_PINS), ("bias_before_scale", _FWD_PINS),
+    ("qk_swapped", _FWD_PINS), ("alibi_sign", _FWD_PINS), ("diagonal_masked", _FWD_PINS),
+    ("mask_flipped", _FWD_PINS),
+    ("dv_not_transposed", _BWD_PINS), ("dropped_one_minus_p", _BWD_PINS), ("bwd_sqrt_d", _BWD_PINS),
+    ("dq_dk_swapped", _BWD_PINS),
+])
+def test_planted_mistakes_are_caught_by_the_pins(monkeypatch, kind, pins):
+    """Run the pins themselves against an implementation with one planted mistake: at least one
+    pin of the relevant group must fail (backward mistakes leave the forward pins green)."""
+    fwd, bwd = _mutant(kind)
+    monkeypatch.setattr(orc, "sigmoid_attn_fwd", fwd)
+    monkeypatch.setattr(orc, "sigmoid_attn_bwd", bwd)
+    assert _failing_pins(pins) >= 1, f"no pin notices the mistake '{kind}'"

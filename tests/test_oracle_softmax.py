@@ -62,6 +62,31 @@ def test_alibi_matches_additive_mask_in_sdpa():
     np.testing.assert_allclose(o, to.numpy(), rtol=1e-11, atol=1e-13)
 
 
+@pytest.mark.parametrize("causal", [False, True])
+def test_backward_with_alibi_against_sdpa_autograd(causal):
+    # the gradients with ALiBi slopes: autograd through SDPA with the additive mask
+    # -m_h |i - j| (plus -inf above the diagonal when causal)
+    B, H, N, d = 2, 3, 37, 8
+    q, k, v, dout = (_rand(B, H, N, d) for _ in range(4))
+    slopes = np.array([2.0 ** (-8.0 * (h + 1) / H) for h in range(H)])
+    idx = torch.arange(N)
+    mask = -torch.tensor(slopes)[None, :, None, None] * (idx[:, None] - idx[None, :]).abs().double()
+    if causal:
+        mask = mask.masked_fill(idx[None, :] > idx[:, None], float("-inf"))
+    tq, tk, tv = (torch.tensor(x, dtype=torch.float64, requires_grad=True) for x in (q, k, v))
+    to = F.scaled_dot_product_attention(tq, tk, tv, attn_mask=mask.expand(B, H, N, N))
+    (to * torch.tensor(dout)).sum().backward()
+    o, _ = orc.softmax_attn_fwd(q, k, v, causal, slopes)
+    np.testing.assert_allclose(o, to.detach().numpy(), rtol=1e-11, atol=1e-13)
+    dq, dk, dv = orc.softmax_attn_bwd(q, k, v, dout, causal, slopes)
+    np.testing.assert_allclose(dq, tq.grad.numpy(), rtol=1e-10, atol=1e-13)
+    np.testing.assert_allclose(dk, tk.grad.numpy(), rtol=1e-10, atol=1e-13)
+    np.testing.assert_allclose(dv, tv.grad.numpy(), rtol=1e-10, atol=1e-13)
+    # and the slopes matter: without them the gradients differ
+    dq0, _, _ = orc.softmax_attn_bwd(q, k, v, dout, causal)
+    assert np.abs(dq0 - dq).max() > 1e-3
+
+
 def test_shift_invariance_and_rows_entry_point():
     B, H, N, d = 1, 1, 40, 8
     q, k, v = _rand(B, H, N, d), _rand(B, H, N, d), _rand(B, H, N, d)
