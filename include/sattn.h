@@ -31,10 +31,20 @@
  *    rounded to bf16 before the second matrix product.  SATTN_F32: everything fp32.
  *  - bias is the scalar b in natural-log units (callers pass -log(N)); alibi_slopes is a
  *    device pointer to H floats or NULL; causal is 0 or 1.
- *  - Calls are asynchronous on `stream` (a hipStream_t; NULL = default stream).  No hidden
- *    synchronisation, no global state; thread safe.
- *  - Return 0 on success, a negative SATTN_ERR_* otherwise.  On error nothing is launched
- *    and nothing is written.
+ *  - Calls are asynchronous on `stream` (a hipStream_t; NULL = default stream) and launch on
+ *    the calling thread's current device, which must be the device of the stream and of the
+ *    buffers.  No hidden synchronisation.  The entry points of this header may be called
+ *    from several threads at once; the only process-wide state they read is the forced tile
+ *    shape of sattn_bench.h (measurements only, see there).
+ *  - Return 0 on success, a negative SATTN_ERR_* otherwise.  Argument errors (every code but
+ *    SATTN_ERR_LAUNCH) are found before anything is launched: nothing is written.  An entry
+ *    point that launches several kernels (the backward passes, the softmax backward with its
+ *    pre-pass, the bias gradient) returns SATTN_ERR_LAUNCH as soon as the runtime rejects one
+ *    of them; kernels launched before that one have run, so outputs may be partly written.
+ *
+ * Measurement and comparison aids (compiler-scheduled twins of the sigmoid kernels, the
+ * matrix-rate probe, the tile-shape setters, device information) are declared in
+ * sattn_bench.h, not here.
  */
 #ifndef SATTN_H_
 #define SATTN_H_
@@ -163,14 +173,10 @@ int sattn_headconcat_norm_bwd(const void* x, const void* dy, const float* stats,
  * d = 128, the depth of the V ring in LDS (3 slots: one workgroup per compute unit; 2 slots: two).
  * The bf16 forward entry points (sigmoid, softmax, variable-length, ...) choose them per problem
  * from d, B*H*N, the mask and the number of compute units.  sattn_fwd_waves / sattn_fwd_v_slots
- * return that choice (or a negative error code); the setters force a value process-wide for
- * measurements (0 = back to automatic; a forced v_slots only applies where that shape exists;
- * not thread-safe against concurrent launches).  The outputs are bit-identical for all shapes:
- * the arithmetic of a query row does not depend on which rows share its workgroup. */
+ * return that choice (or a negative error code).  The outputs are bit-identical for all
+ * shapes: the arithmetic of a query row does not depend on which rows share its workgroup. */
 int sattn_fwd_waves(int B, int H, int N, int d, int causal);
 int sattn_fwd_v_slots(int B, int H, int N, int d, int causal);
-int sattn_set_fwd_waves(int waves);
-int sattn_set_fwd_v_slots(int v_slots);
 
 /* Human-readable text for an SATTN_ERR_* code (static storage). */
 const char* sattn_strerror(int code);
@@ -257,39 +263,6 @@ int sigmoid_attn_varlen_bwd(const void* q, const void* k, const void* v, const v
                             const sattn_strides* sv, const sattn_strides* sdout,
                             const sattn_strides* sdq, const sattn_strides* sdk,
                             const sattn_strides* sdv, void* stream);
-
-/* Comparison aids (Section 4.1 / Appendix F.2 compare the sigmoid kernels with softmax kernels
- * built the same way).  Same arguments, results and error behaviour as sigmoid_attn_fwd /
- * sigmoid_attn_bwd; the kernels run every pipeline step in the compiler-scheduled form that
- * the softmax comparison kernels use, instead of the hand-pinned instruction stream.  They
- * exist so that sigmoid and softmax can be timed like for like; not meant for production. */
-int sigmoid_attn_fwd_compiler_scheduled(const void* q, const void* k, const void* v, void* o,
-                                        int B, int H, int N, int d, sattn_dtype dtype,
-                                        float bias, int causal, const float* alibi_slopes,
-                                        const sattn_strides* sq, const sattn_strides* sk,
-                                        const sattn_strides* sv, const sattn_strides* so,
-                                        void* stream);
-int sigmoid_attn_bwd_compiler_scheduled(const void* q, const void* k, const void* v, const void* dout,
-                                        void* dq, void* dk, void* dv,
-                                        int B, int H, int N, int d, sattn_dtype dtype,
-                                        float bias, int causal, const float* alibi_slopes,
-                                        const sattn_strides* sq, const sattn_strides* sk,
-                                        const sattn_strides* sv, const sattn_strides* sdout,
-                                        const sattn_strides* sdq, const sattn_strides* sdk,
-                                        const sattn_strides* sdv,
-                                        void* workspace, size_t workspace_bytes, void* stream);
-
-/* Measurement aid (Section 4.1 quotes kernel speed against the matrix-unit peak): launches
- * `blocks` workgroups of 4 waves that each issue iters*8 independent register-resident
- * 32x32x16 bf16 MFMAs (32768 flop each) and nothing else, asynchronously on `stream`.  The
- * caller times the launch; blocks*4*iters*8*32768 flop / time is the matrix rate this device
- * sustains at its actual clock.  `sink` is a device pointer to blocks*256 floats that
- * receives one value per lane (keeps the loop alive).  Returns 0 or SATTN_ERR_*. */
-int sattn_mfma_bf16_probe(int blocks, int iters, float* sink, void* stream);
-
-/* Measurement aid: compute units and nominal peak engine clock (kHz) of the current device, as
- * the runtime reports them (host pointers).  SATTN_ERR_LAUNCH if there is no usable device. */
-int sattn_device_info(int* compute_units, int* clock_khz);
 
 /* Library version: major*10000 + minor*100 + patch. */
 int sattn_version(void);

@@ -1,0 +1,64 @@
+/*
+ * sattn_bench.h -- measurement and comparison aids of the sigmoid-attention library.
+ *
+ * Nothing here is part of the product contract of sattn.h: these entry points exist so that
+ * the kernels can be timed like for like against the softmax comparison kernels, so that
+ * the benchmark can report the matrix rate the device sustains, and so that a tile shape
+ * can be forced for a sweep.  Same conventions as sattn.h (device pointers, element
+ * strides, asynchronous on `stream`, negative SATTN_ERR_* on error).
+ */
+#ifndef SATTN_BENCH_H_
+#define SATTN_BENCH_H_
+
+#include "sattn.h"
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Force the forward tile shape for measurements (Appendix F.5: the block shape is a tuning
+ * parameter): waves in {4, 8}, v_slots in {2, 3}; 0 = back to the automatic choice; a forced
+ * v_slots only applies where that shape exists.  The value is process-wide (an atomic that
+ * every forward launch reads): set it from one thread while no other thread launches, or
+ * launches in flight on other threads may take either shape.  Results do not depend on it. */
+int sattn_set_fwd_waves(int waves);
+int sattn_set_fwd_v_slots(int v_slots);
+
+/* Comparison aids (Section 4 and Appendix F.2 compare the sigmoid kernels with softmax kernels
+ * built the same way).  Same arguments, results and error behaviour as sigmoid_attn_fwd /
+ * sigmoid_attn_bwd; the kernels run every pipeline step in the compiler-scheduled form that
+ * the softmax comparison kernels use, instead of the hand-pinned instruction stream.  They
+ * exist so that sigmoid and softmax can be timed like for like; not meant for production. */
+int sigmoid_attn_fwd_compiler_scheduled(const void* q, const void* k, const void* v, void* o,
+                                        int B, int H, int N, int d, sattn_dtype dtype,
+                                        float bias, int causal, const float* alibi_slopes,
+                                        const sattn_strides* sq, const sattn_strides* sk,
+                                        const sattn_strides* sv, const sattn_strides* so,
+                                        void* stream);
+int sigmoid_attn_bwd_compiler_scheduled(const void* q, const void* k, const void* v, const void* dout,
+                                        void* dq, void* dk, void* dv,
+                                        int B, int H, int N, int d, sattn_dtype dtype,
+                                        float bias, int causal, const float* alibi_slopes,
+                                        const sattn_strides* sq, const sattn_strides* sk,
+                                        const sattn_strides* sv, const sattn_strides* sdout,
+                                        const sattn_strides* sdq, const sattn_strides* sdk,
+                                        const sattn_strides* sdv,
+                                        void* workspace, size_t workspace_bytes, void* stream);
+
+/* Measurement aid (Appendix F.2 reports kernel times; here they are also quoted as a fraction
+ * of the matrix-unit rate): launches `blocks` workgroups of 4 waves that each issue iters*8
+ * independent register-resident 32x32x16 bf16 MFMAs (32768 flop each) and nothing else,
+ * asynchronously on `stream`.  The
+ * caller times the launch; blocks*4*iters*8*32768 flop / time is the matrix rate this device
+ * sustains at its actual clock.  `sink` is a device pointer to blocks*256 floats that
+ * receives one value per lane (keeps the loop alive).  Returns 0 or SATTN_ERR_*. */
+int sattn_mfma_bf16_probe(int blocks, int iters, float* sink, void* stream);
+
+/* Measurement aid: compute units and nominal peak engine clock (kHz) of the current device, as
+ * the runtime reports them (host pointers).  SATTN_ERR_LAUNCH if there is no usable device. */
+int sattn_device_info(int* compute_units, int* clock_khz);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SATTN_BENCH_H_ */

@@ -1,15 +1,37 @@
 // C ABI of the sigmoid-attention library: argument validation and kernel dispatch.
-// See include/sattn.h for the contract of every entry point.
+// See include/sattn.h (product contract) and include/sattn_bench.h (measurement aids).
 #include "../../include/sattn.h"
+#include "../../include/sattn_bench.h"
 
 #include <hip/hip_runtime.h>
 #include <math.h>
+
+#include <atomic>
+#include <mutex>
+#include <map>
+#include <utility>
 
 #include "sattn_f32.hpp"
 #include "sattn_launch.hpp"
 #include "sattn_norm.hpp"
 
 using namespace sattn;
+
+namespace sattn {
+
+bool ensure_dynamic_lds(const void* kernel, int dev, size_t lds) {
+  static std::mutex mu;
+  static std::map<std::pair<const void*, int>, size_t> granted;  // (kernel, device) -> largest size set so far
+  const std::pair<const void*, int> key(kernel, dev);
+  std::lock_guard<std::mutex> lock(mu);
+  auto it = granted.find(key);
+  if (it != granted.end() && it->second >= lds) return true;
+  if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) return false;
+  granted[key] = lds;
+  return true;
+}
+
+}  // namespace sattn
 
 namespace {
 
@@ -87,8 +109,8 @@ int make_ref(const void* ptr, const sattn_strides* s, int H, int N, int d, sattn
 // two-slot V ring (80 KB) two 4-wave workgroups fit again; they win while a workgroup's key loop
 // is short (per-workgroup prologue, diagonal and barrier waits overlap with the neighbour) and
 // lose a few percent on long loops, where V is staged only one tile ahead.
-int g_fwd_waves = 0;   // 0: choose per problem; 4 or 8: forced (sattn_set_fwd_waves)
-int g_fwd_vslots = 0;  // 0: choose per problem; 2 or 3: forced (sattn_set_fwd_v_slots)
+std::atomic<int> g_fwd_waves{0};   // 0: choose per problem; 4 or 8: forced (sattn_set_fwd_waves)
+std::atomic<int> g_fwd_vslots{0};  // 0: choose per problem; 2 or 3: forced (sattn_set_fwd_v_slots)
 
 int compute_units() {
   int dev = 0, n = 0;
@@ -113,11 +135,13 @@ FwdShape pick_fwd_shape(int B, int H, int N, int d, int causal) {
     if (wg4 <= (causal ? cus + cus / 2 : cus)) s = FwdShape{4, 3};
     else if (avg_tiles <= 48) s = FwdShape{4, 2};
   }
-  if (g_fwd_waves) {
-    if (g_fwd_waves != s.waves) s.v_slots = 3;
-    s.waves = g_fwd_waves;
+  const int forced_waves = g_fwd_waves.load(std::memory_order_relaxed);
+  const int forced_vslots = g_fwd_vslots.load(std::memory_order_relaxed);
+  if (forced_waves) {
+    if (forced_waves != s.waves) s.v_slots = 3;
+    s.waves = forced_waves;
   }
-  if (g_fwd_vslots) s.v_slots = g_fwd_vslots;
+  if (forced_vslots) s.v_slots = forced_vslots;
   if (s.waves != 4 || d != 128) s.v_slots = 3;  // the only shape with a two-slot V ring
   return s;
 }
@@ -552,13 +576,13 @@ int sattn_headconcat_norm_bwd(const void* x, const void* dy, const float* stats,
 
 int sattn_set_fwd_waves(int waves) {
   if (waves != 0 && waves != 4 && waves != 8) return SATTN_ERR_UNSUPPORTED;
-  g_fwd_waves = waves;
+  g_fwd_waves.store(waves, std::memory_order_relaxed);
   return SATTN_OK;
 }
 
 int sattn_set_fwd_v_slots(int v_slots) {
   if (v_slots != 0 && v_slots != 2 && v_slots != 3) return SATTN_ERR_UNSUPPORTED;
-  g_fwd_vslots = v_slots;
+  g_fwd_vslots.store(v_slots, std::memory_order_relaxed);
   return SATTN_OK;
 }
 

@@ -12,15 +12,27 @@
 
 namespace sattn {
 
+// Raises the dynamic-LDS limit of `kernel` on device `dev` to `lds` bytes unless an earlier
+// launch already did (the attribute is a property of the loaded function per device, and the
+// small problems are launch-latency bound, so the runtime call is made once, not per launch).
+bool ensure_dynamic_lds(const void* kernel, int dev, size_t lds);
+
 template <typename K, typename... Args>
 int launch(K kernel, dim3 grid, dim3 block, size_t lds, hipStream_t st, Args... args) {
-  if (lds > 0 &&
-      hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
+  if (lds > 0) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || !ensure_dynamic_lds((const void*)kernel, dev, lds)) {
+      (void)hipGetLastError();
+      return SATTN_ERR_LAUNCH;
+    }
+  }
+  // the launch's own status, not whatever error an earlier, unrelated call left behind
+  void* argv[] = {(void*)&args...};
+  if (hipLaunchKernel((const void*)kernel, grid, block, argv, lds, st) != hipSuccess) {
     (void)hipGetLastError();
     return SATTN_ERR_LAUNCH;
   }
-  hipLaunchKernelGGL(kernel, grid, block, lds, st, args...);
-  return hipGetLastError() == hipSuccess ? SATTN_OK : SATTN_ERR_LAUNCH;
+  return SATTN_OK;
 }
 
 // Expand two runtime flags into the constexpr bools A and B2 visible to CALL.

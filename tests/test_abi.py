@@ -10,7 +10,7 @@ import paper_2409_04431_amd as sa
 from paper_2409_04431_amd import binding
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-HEADER = os.path.join(ROOT, "include", "sattn.h")
+HEADERS = [os.path.join(ROOT, "include", n) for n in sorted(os.listdir(os.path.join(ROOT, "include"))) if n.endswith(".h")]
 
 
 @pytest.fixture(scope="module")
@@ -22,7 +22,7 @@ def lib():
 
 
 def _declared_functions():
-    text = open(HEADER).read()
+    text = "\n".join(open(h).read() for h in HEADERS)
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b((?:sigmoid|softmax)_attn_\w+|sattn_\w+)\s*\(", text)))
 
@@ -32,7 +32,7 @@ def test_header_symbols_are_exported(lib):
     assert {"sigmoid_attn_fwd", "sigmoid_attn_bwd", "softmax_attn_fwd", "softmax_attn_bwd", "sattn_strerror",
             "sattn_version"} <= set(names)
     for n in names:
-        assert hasattr(lib, n), f"{n} declared in sattn.h but not exported"
+        assert hasattr(lib, n), f"{n} declared in include/*.h but not exported"
 
 
 def test_version_and_error_strings(lib):
