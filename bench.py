@@ -21,10 +21,28 @@ if ROOT not in sys.path:
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 matrix peak
 
-# HBM bytes per launch of the dominant kernel (dK/dV on the headline workload), from
-# `rocprofv3 --pmc FETCH_SIZE` and `--pmc WRITE_SIZE` runs of this script scaled by a plain
-# copy kernel: 2 x 262 318 KiB read + 262 144 KiB written (profiles/attn_kernels_cfg3_pmc.txt).
-MEASURED_TRAFFIC_BYTES = {3: (2 * 262318 + 262144) * 1024}
+PROFILES = os.path.join(ROOT, "profiles")
+
+
+def measured_traffic_bytes(cfg_id, kernel_prefix):
+    """HBM bytes per launch of `kernel_prefix` on workload `cfg_id`, from the tracked rocprofv3
+    summary profiles/attn_kernels_cfg<id>_pmc.txt: 2 x FETCH_SIZE + WRITE_SIZE KiB (the factors
+    a plain copy kernel of known size gives; the summary holds that calibration).  None if the
+    summary or the kernel's block is not there."""
+    path = os.path.join(PROFILES, f"attn_kernels_cfg{cfg_id}_pmc.txt")
+    if not os.path.exists(path):
+        return None
+    vals, inside = {}, False
+    for line in open(path):
+        if not line.startswith(" "):
+            inside = line.startswith(kernel_prefix)
+            continue
+        parts = line.split()
+        if inside and len(parts) == 2 and parts[0] in ("FETCH_SIZE", "WRITE_SIZE") and parts[0] not in vals:
+            vals[parts[0]] = float(parts[1])
+    if len(vals) != 2:
+        return None
+    return int((2 * vals["FETCH_SIZE"] + vals["WRITE_SIZE"]) * 1024)
 
 
 def _events(n):
@@ -64,7 +82,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--cfg", type=int, default=3, help="workload id (1-5); the headline metric is quoted on 3")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--softmax", action="store_true", help="also time the softmax comparison kernels")
+    ap.add_argument("--no-softmax", action="store_true",
+                    help="skip the comparison region (softmax kernels and compiler-scheduled sigmoid twins)")
+    ap.add_argument("--softmax", action="store_true", help="accepted for compatibility: the comparison is on by default")
     ap.add_argument("--norm", action="store_true",
                     help="also time the hybrid-norm kernels (LayerNorm over the concatenated heads) on this workload's O")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -142,14 +162,23 @@ def main():
     fwd_ms = stats(0)["mean"]
     flops_f, flops_b = cfg.fwd_flops(), cfg.bwd_flops()
     cus, clock_khz = sa.sattn_device_info()
-    # Per-config bounds of the forward (nominal clock): time on the matrix pipe alone, and time on
-    # the vector/transcendental units alone for the sigmoid (fma, exp2, add, rcp and half a pack per
-    # logit: about 3.3 + 8 + 3.3 + 8 + 2.5 issue cycles per 64 logits and SIMD, measured rates)
+    # Per-config, per-kernel bounds: time on the matrix pipe alone for the products the kernel
+    # EXECUTES (forward 2, dK/dV 4, dQ pass 3 of which 2 are recomputed; nominal peak and the
+    # rate the probe sustains), and time on the vector / transcendental units alone for its
+    # per-logit arithmetic at the nominal clock (measured issue costs per 64 logits and SIMD:
+    # fma 3.3, exp2 8, add 3.3, rcp 8, pack 2.5 = 25.1 cycles for the sigmoid; the backward adds
+    # p - p^2, the product with dP and a second pack, and the dK/dV pass packs P as well).
     logits = cfg.B * cfg.H * cfg.N * cfg.N * (0.5 if cfg.causal else 1.0)
     simd_hz = cus * 4 * clock_khz * 1e3
-    bounds = {"fwd_mfma_ms_at_nominal_peak": flops_f / (MFMA_BF16_PEAK_TFLOPS * 1e9),
-              "fwd_mfma_ms_at_sustained_rate": flops_f / (sustained_peak * 1e9),
-              "fwd_sigmoid_valu_ms": logits / 64 * 25.1 / simd_hz * 1e3}
+    prod = flops_f / 2.0                       # flops of one N x N x d product
+
+    def kbounds(n_products, valu_cycles):
+        return {"mfma_ms_at_nominal_peak": n_products * prod / (MFMA_BF16_PEAK_TFLOPS * 1e9),
+                "mfma_ms_at_sustained_rate": n_products * prod / (sustained_peak * 1e9),
+                "valu_ms_at_nominal_clock": logits / 64 * valu_cycles / simd_hz * 1e3}
+    bounds = {"fwd": kbounds(2, 25.1), "bwd_dkdv": kbounds(4, 25.1 + 3.3 + 3.3 + 2.5 + 2.5),
+              "bwd_dq": kbounds(3, 25.1 + 3.3 + 3.3 + 2.5)}
+    bounds["fwd_mfma_ms_at_nominal_peak"] = bounds["fwd"]["mfma_ms_at_nominal_peak"]
     out = {
         "metric": "sigmoid-attn fwd+bwd TFLOP/s (N=4096,d=128)" if cfg.cfg == 3 else
                   f"sigmoid-attn {'fwd+bwd' if cfg.backward else 'fwd'} TFLOP/s",
@@ -180,57 +209,70 @@ def main():
         ach = algo / dkdv_ms / 1e9
         out["roofline"] = {"kernel": "attn_bwd_kernel<BWD_DKDV>", "bound": "mfma", "achieved": ach,
                            "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": ach / MFMA_BF16_PEAK_TFLOPS,
-                           "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.cfg), "avg_launch_ms": dkdv_ms}
+                           "traffic": measured_traffic_bytes(cfg.cfg, f"attn_bwd_kernel<{cfg.d}, 1,"),
+                           "avg_launch_ms": dkdv_ms}
+        out["bounds"]["bwd_dkdv"]["achieved_ms"] = dkdv_ms
+        out["bounds"]["bwd_dq"]["achieved_ms"] = dq_ms
     else:
         out["value"] = flops_f / ms_step / 1e9
         out["frac_of_bf16_mfma_peak"] = out["value"] / MFMA_BF16_PEAK_TFLOPS
         ach = flops_f / fwd_ms / 1e9
         out["roofline"] = {"kernel": "attn_fwd_kernel", "bound": "mfma", "achieved": ach,
                            "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": ach / MFMA_BF16_PEAK_TFLOPS,
-                           "traffic": None, "avg_launch_ms": fwd_ms}
+                           "traffic": measured_traffic_bytes(cfg.cfg, f"attn_fwd_kernel<{cfg.d},"),
+                           "avg_launch_ms": fwd_ms}
 
-    if args.softmax and cfg.dtype == torch.bfloat16:  # the comparison kernels exist for bf16 only
+    out["bounds"]["fwd"]["achieved_ms"] = fwd_ms
+    if not args.no_softmax and cfg.dtype == torch.bfloat16:  # the comparison kernels exist for bf16 only
+        # Comparison region (Appendix F.1 table, left half; Appendix F.2): the softmax kernels
+        # and the sigmoid kernels take turns on the same buffers, every launch between its own
+        # pair of events, so that clock and temperature drift hit both alike.  "cs" = the sigmoid
+        # kernels with the compiler-scheduled step (no hand-pinned stream anywhere).
         lse = torch.empty(cfg.B, cfg.H, cfg.N, dtype=torch.float32, device=dev)
-        for _ in range(args.warmup):
-            sa.softmax_attn_fwd(q, k, v, o, lse, cfg.causal, slopes)
-        e = _events(2)
-        e[0].record()
-        for _ in range(args.steps):
-            sa.softmax_attn_fwd(q, k, v, o, lse, cfg.causal, slopes)
-        e[1].record()
+        o2 = torch.empty_like(o)
+        ws = torch.empty(max(sa.softmax_attn_bwd_workspace_bytes(cfg.B, cfg.H, cfg.N, cfg.d), 16),
+                         dtype=torch.uint8, device=dev)
+        sa.softmax_attn_fwd(q, k, v, o2, lse, cfg.causal, slopes)   # O and LSE for the softmax backward
+        calls = [("sigmoid_fwd", lambda: sa.sigmoid_attn_fwd(q, k, v, o, bias, cfg.causal, slopes)),
+                 ("softmax_fwd", lambda: sa.softmax_attn_fwd(q, k, v, o2, lse, cfg.causal, slopes)),
+                 ("sigmoid_cs_fwd", lambda: sa.sigmoid_attn_fwd_compiler_scheduled(q, k, v, o, bias, cfg.causal, slopes))]
+        if cfg.backward:
+            calls += [("sigmoid_bwd", lambda: sa.sigmoid_attn_bwd(q, k, v, dout, dq, dk, dv, bias, cfg.causal, slopes)),
+                      ("softmax_bwd", lambda: sa.softmax_attn_bwd(q, k, v, o2, lse, dout, dq, dk, dv, cfg.causal,
+                                                                  slopes, workspace=ws)),
+                      ("sigmoid_cs_bwd", lambda: sa.sigmoid_attn_bwd_compiler_scheduled(q, k, v, dout, dq, dk, dv, bias,
+                                                                                        cfg.causal, slopes))]
+        rounds = max(3, min(args.steps, 20))
+        for _ in range(2):
+            for _, fn in calls:
+                fn()
+        cev = [[_events(2) for _ in calls] for _ in range(rounds)]
+        for r in range(rounds):
+            for c, (_, fn) in enumerate(calls):
+                cev[r][c][0].record()
+                fn()
+                cev[r][c][1].record()
         torch.cuda.synchronize()
-        sm_ms = e[0].elapsed_time(e[1]) / args.steps
-        out["softmax_fwd_ms"] = sm_ms
-        out["softmax_fwd_tflops"] = flops_f / sm_ms / 1e9
-
-        def timed(fn):
-            for _ in range(args.warmup):
-                fn()
-            ev = _events(2)
-            ev[0].record()
-            for _ in range(args.steps):
-                fn()
-            ev[1].record()
-            torch.cuda.synchronize()
-            return ev[0].elapsed_time(ev[1]) / args.steps
-        # the sigmoid kernels with the same compiler-scheduled step the softmax kernels use
-        out["sigmoid_fwd_compiler_scheduled_ms"] = timed(
-            lambda: sa.sigmoid_attn_fwd_compiler_scheduled(q, k, v, o, bias, cfg.causal, slopes))
+        cmp_ms = {}
+        for c, (name, _) in enumerate(calls):
+            ts = sorted(cev[r][c][0].elapsed_time(cev[r][c][1]) for r in range(rounds))
+            cmp_ms[name] = {"mean": sum(ts) / len(ts), "median": ts[len(ts) // 2], "min": ts[0]}
+        out["comparison"] = {"rounds": rounds, "method": "interleaved launches, one event pair per launch, same buffers",
+                             "ms": cmp_ms}
+        out["softmax_fwd_ms"] = cmp_ms["softmax_fwd"]["mean"]
+        out["softmax_fwd_tflops"] = flops_f / out["softmax_fwd_ms"] / 1e9
+        out["sigmoid_fwd_ms_interleaved"] = cmp_ms["sigmoid_fwd"]["mean"]
+        out["sigmoid_fwd_compiler_scheduled_ms"] = cmp_ms["sigmoid_cs_fwd"]["mean"]
+        out["fwd_time_ratio_sigmoid_over_softmax"] = cmp_ms["sigmoid_fwd"]["mean"] / cmp_ms["softmax_fwd"]["mean"]
         if cfg.backward:
-            out["sigmoid_bwd_compiler_scheduled_ms"] = timed(
-                lambda: sa.sigmoid_attn_bwd_compiler_scheduled(q, k, v, dout, dq, dk, dv, bias, cfg.causal, slopes))
-        if cfg.backward:
-            for _ in range(args.warmup):
-                sa.softmax_attn_bwd(q, k, v, o, lse, dout, dq, dk, dv, cfg.causal, slopes)
-            e = _events(2)
-            e[0].record()
-            for _ in range(args.steps):
-                sa.softmax_attn_bwd(q, k, v, o, lse, dout, dq, dk, dv, cfg.causal, slopes)
-            e[1].record()
-            torch.cuda.synchronize()
-            sb_ms = e[0].elapsed_time(e[1]) / args.steps
-            out["softmax_bwd_ms"] = sb_ms
-            out["softmax_bwd_tflops"] = flops_b / sb_ms / 1e9
+            out["softmax_bwd_ms"] = cmp_ms["softmax_bwd"]["mean"]
+            out["softmax_bwd_tflops"] = flops_b / out["softmax_bwd_ms"] / 1e9
+            out["sigmoid_bwd_ms_interleaved"] = cmp_ms["sigmoid_bwd"]["mean"]
+            out["sigmoid_bwd_compiler_scheduled_ms"] = cmp_ms["sigmoid_cs_bwd"]["mean"]
+            out["bwd_time_ratio_sigmoid_over_softmax"] = cmp_ms["sigmoid_bwd"]["mean"] / cmp_ms["softmax_bwd"]["mean"]
+            out["fwd_bwd_time_ratio_sigmoid_over_softmax"] = (
+                (cmp_ms["sigmoid_fwd"]["mean"] + cmp_ms["sigmoid_bwd"]["mean"])
+                / (cmp_ms["softmax_fwd"]["mean"] + cmp_ms["softmax_bwd"]["mean"]))
 
     if args.norm and cfg.dtype == torch.bfloat16:
         # HBM-bound: algorithmic bytes = one read + one write of O (forward), two reads + one write (backward)
