@@ -72,7 +72,8 @@ enum {
   SATTN_ERR_UNSUPPORTED = -3, /* d not in {64,128} or unknown dtype */
   SATTN_ERR_ALIGN = -4,       /* pointer or stride breaks the 16-byte rule */
   SATTN_ERR_WORKSPACE = -5,   /* workspace NULL or smaller than *_workspace_bytes() */
-  SATTN_ERR_LAUNCH = -6       /* the HIP runtime rejected the launch */
+  SATTN_ERR_LAUNCH = -6,      /* the HIP runtime rejected the launch */
+  SATTN_ERR_TOO_LARGE = -7    /* softmax_attn_bwd_noalloc: more padded query rows than its scratch holds */
 };
 
 /* Forward pass of sigmoid attention (Algorithm 1): writes O only. */
@@ -147,6 +148,29 @@ int softmax_attn_bwd(const void* q, const void* k, const void* v, const void* o,
                      void* workspace, size_t workspace_bytes, void* stream);
 
 size_t softmax_attn_bwd_workspace_bytes(int B, int H, int N, int d, sattn_dtype dtype);
+
+/* softmax_attn_bwd for callers that cannot allocate device memory or pass a workspace (code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): same
+ * arguments, results and errors as softmax_attn_bwd without `workspace`; the two fp32 per
+ * padded query row live in a fixed 8 MiB array inside the library's device image (one copy per
+ * GPU, held until the process ends) whose address is looked up on the first call on each device.
+ * Limit: B * H * roundup(N, 64) <= softmax_attn_bwd_noalloc_max_rows() (2^20), else
+ * SATTN_ERR_TOO_LARGE and nothing is launched.  No hipMalloc / hipFree / allocating library
+ * routine is called.  All calls on one GPU share that GPU's array: calls that may overlap on one
+ * GPU (different streams or threads) race on it and must be ordered by the caller; calls on
+ * one stream are ordered by the stream.  Nothing needs clearing between calls (the pre-pass
+ * rewrites every entry that the call reads). */
+int softmax_attn_bwd_noalloc(const void* q, const void* k, const void* v, const void* o,
+                             const float* lse, const void* dout,
+                             void* dq, void* dk, void* dv,
+                             int B, int H, int N, int d, sattn_dtype dtype,
+                             int causal, const float* alibi_slopes,
+                             const sattn_strides* sq, const sattn_strides* sk,
+                             const sattn_strides* sv, const sattn_strides* so,
+                             const sattn_strides* sdout,
+                             const sattn_strides* sdq, const sattn_strides* sdk,
+                             const sattn_strides* sdv, void* stream);
+size_t softmax_attn_bwd_noalloc_max_rows(void);
 
 /* Hybrid-norm (Section 5.5, Appendix G.6: x + norm(attention output), a LayerNorm without
  * learnable affine parameters; RMSNorm is the other norm the paper's models use).  Token (b, n)

@@ -23,6 +23,8 @@ from .binding import (  # noqa: F401
     sigmoid_attn_varlen_bwd,
     sigmoid_attn_varlen_fwd,
     softmax_attn_bwd,
+    softmax_attn_bwd_noalloc,
+    softmax_attn_bwd_noalloc_max_rows,
     softmax_attn_bwd_workspace_bytes,
     softmax_attn_fwd,
     sattn_device_info,

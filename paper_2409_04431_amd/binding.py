@@ -77,6 +77,10 @@ def load_library():
     lib.softmax_attn_bwd.restype = i
     lib.softmax_attn_bwd_workspace_bytes.argtypes = [i, i, i, i, i]
     lib.softmax_attn_bwd_workspace_bytes.restype = sz
+    lib.softmax_attn_bwd_noalloc.argtypes = [_vp] * 9 + [i, i, i, i, i, i, _vp] + [_SP] * 8 + [_vp]
+    lib.softmax_attn_bwd_noalloc.restype = i
+    lib.softmax_attn_bwd_noalloc_max_rows.argtypes = []
+    lib.softmax_attn_bwd_noalloc_max_rows.restype = sz
     lib.sattn_strerror.argtypes = [i]
     lib.sattn_strerror.restype = ctypes.c_char_p
     lib.sattn_mfma_bf16_probe.argtypes = [i, i, _vp, _vp]
@@ -460,4 +464,21 @@ def softmax_attn_bwd(q, k, v, o, lse, dout, dq, dk, dv, causal=False, alibi_slop
                               _dtype_code(q), int(bool(causal)), _slopes_ptr(alibi_slopes, H),
                               _st(q), _st(k), _st(v), _st(o), _st(dout), _st(dq), _st(dk), _st(dv), wp, wb, _stream())
     _raise(rc, "softmax_attn_bwd")
+    return dq, dk, dv
+
+
+def softmax_attn_bwd_noalloc_max_rows():
+    return int(load_library().softmax_attn_bwd_noalloc_max_rows())
+
+
+def softmax_attn_bwd_noalloc(q, k, v, o, lse, dout, dq, dk, dv, causal=False, alibi_slopes=None):
+    """softmax_attn_bwd on the library's own fixed scratch: no workspace, no allocation."""
+    lib = load_library()
+    _check(q, k, v, o, dout, dq, dk, dv)
+    B, H, N, d = q.shape
+    rc = lib.softmax_attn_bwd_noalloc(q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(), lse.data_ptr(),
+                                      dout.data_ptr(), dq.data_ptr(), dk.data_ptr(), dv.data_ptr(), B, H, N, d,
+                                      _dtype_code(q), int(bool(causal)), _slopes_ptr(alibi_slopes, H),
+                                      _st(q), _st(k), _st(v), _st(o), _st(dout), _st(dq), _st(dk), _st(dv), _stream())
+    _raise(rc, "softmax_attn_bwd_noalloc")
     return dq, dk, dv

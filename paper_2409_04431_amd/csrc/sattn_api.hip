@@ -33,7 +33,38 @@ bool ensure_dynamic_lds(const void* kernel, int dev, size_t lds) {
 
 }  // namespace sattn
 
+// Scratch of softmax_attn_bwd_noalloc: what softmax_attn_bwd takes as its workspace (two fp32
+// per padded query row), held in the library's own device image so that the call allocates
+// nothing.  Every GPU the library runs on holds its own copy until the process ends.
+constexpr size_t kNoAllocRows = (size_t)1 << 20;  // padded query rows B*H*roundup(N, 64)
+static __device__ __align__(256) float scratch[2 * kNoAllocRows];  // 8 MiB
+
 namespace {
+
+// Device address of `scratch` on the current device.  In host code the array's name is only
+// a handle; the address kernels can use comes from the runtime, once per device.
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+float* g_scratch_ptr[kMaxDevices] = {};
+
+int scratch_on_current_device(float** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+    (void)hipGetLastError();
+    return SATTN_ERR_LAUNCH;
+  }
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) {
+      (void)hipGetLastError();
+      return SATTN_ERR_LAUNCH;
+    }
+    g_scratch_ptr[dev] = (float*)ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return SATTN_OK;
+}
 
 int elem_size(sattn_dtype t) { return t == SATTN_BF16 ? 2 : 4; }
 
@@ -462,6 +493,26 @@ size_t softmax_attn_bwd_workspace_bytes(int B, int H, int N, int d, sattn_dtype 
   return 2 * (size_t)B * H * ((N + 63) / 64 * 64) * sizeof(float);
 }
 
+size_t softmax_attn_bwd_noalloc_max_rows(void) { return kNoAllocRows; }
+
+int softmax_attn_bwd_noalloc(const void* q, const void* k, const void* v, const void* o, const float* lse,
+                             const void* dout, void* dq, void* dk, void* dv, int B, int H, int N, int d,
+                             sattn_dtype dtype, int causal, const float* alibi_slopes, const sattn_strides* sq,
+                             const sattn_strides* sk, const sattn_strides* sv, const sattn_strides* so,
+                             const sattn_strides* sdout, const sattn_strides* sdq, const sattn_strides* sdk,
+                             const sattn_strides* sdv, void* stream) {
+  int rc = check_shape(B, H, N, d, dtype);
+  if (rc) return rc;
+  // the pre-pass writes every padded row it later reads, so the last call's contents need no clearing
+  const size_t rows = (size_t)B * H * ((size_t)(N + 63) / 64 * 64);
+  if (rows > kNoAllocRows) return SATTN_ERR_TOO_LARGE;
+  float* ws = nullptr;
+  if ((rc = scratch_on_current_device(&ws))) return rc;
+  BwdArgs a{q, k, v, o, lse, dout, dq, dk, dv, B, H, N, d, dtype, 0.0f, causal, alibi_slopes,
+            sq, sk, sv, so, sdout, sdq, sdk, sdv, ws, 2 * kNoAllocRows * sizeof(float), kBwdDkDv | kBwdDq, stream};
+  return bwd_impl<true>(a);
+}
+
 const char* sattn_strerror(int code) {
   switch (code) {
     case SATTN_OK: return "success";
@@ -471,6 +522,7 @@ const char* sattn_strerror(int code) {
     case SATTN_ERR_ALIGN: return "pointers and strides must keep rows 16-byte aligned";
     case SATTN_ERR_WORKSPACE: return "workspace missing or too small";
     case SATTN_ERR_LAUNCH: return "the HIP runtime rejected the kernel launch";
+    case SATTN_ERR_TOO_LARGE: return "problem exceeds the fixed scratch of the allocation-free entry point";
     default: return "unknown error code";
   }
 }

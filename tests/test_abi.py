@@ -37,7 +37,7 @@ def test_header_symbols_are_exported(lib):
 
 def test_version_and_error_strings(lib):
     assert sa.sattn_version() >= 100
-    for code in range(0, -7, -1):
+    for code in range(0, -8, -1):
         assert sa.sattn_strerror(code) and "unknown" not in sa.sattn_strerror(code)
     assert "unknown" in sa.sattn_strerror(-99)
 
