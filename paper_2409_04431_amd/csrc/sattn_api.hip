@@ -252,7 +252,9 @@ int fwd_impl(const FwdArgs& a) {
   p.cu_seqlens = a.cu_seqlens; p.bias_vec = a.bias_vec;
   p.kv_group = a.H / Hkv;
   p.Nk = Nk == a.N ? 0 : Nk;
-  const FwdShape shape = pick_fwd_shape(a.B, a.H, a.N, a.d, a.causal);
+  FwdShape shape = pick_fwd_shape(a.B, a.H, a.N, a.d, a.causal);
+  // the 64-row waves exist for the pinned sigmoid kernel at d = 128, ALiBi only in its causal form
+  if (shape.waves >= 64 && (SOFTMAX || !PIN || a.d != 128 || (alibi && !a.causal))) shape = FwdShape{8, 3};
   if (a.d == 128) return launch_fwd_bf16<128>(p, shape.waves, shape.v_slots, SOFTMAX, PIN, a.causal, alibi, st);
   return launch_fwd_bf16<64>(p, shape.waves, shape.v_slots, SOFTMAX, PIN, a.causal, alibi, st);
 }
@@ -627,7 +629,7 @@ int sattn_headconcat_norm_bwd(const void* x, const void* dy, const float* stats,
 }
 
 int sattn_set_fwd_waves(int waves) {
-  if (waves != 0 && waves != 4 && waves != 8) return SATTN_ERR_UNSUPPORTED;
+  if (waves != 0 && waves != 4 && waves != 8 && waves != 64 && waves != 65) return SATTN_ERR_UNSUPPORTED;
   g_fwd_waves.store(waves, std::memory_order_relaxed);
   return SATTN_OK;
 }

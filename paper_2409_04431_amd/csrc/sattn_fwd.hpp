@@ -119,6 +119,24 @@ struct DmaStager {
       issue_full<n + 1>(lds, wave);
     }
   }
+  // The same staging one instruction at a time, for a tile that lies wholly inside the tensor
+  // (for interleaving with a pinned step).  lane_off(n) is this lane's complete byte offset for
+  // instruction n relative to `base` (the instruction's own offset field, which moves the
+  // global address along with the LDS target, already taken out), so that all NI loads share
+  // one scalar base; the caller keeps the NI values in registers and calls issue_off<n> for
+  // n = 0 .. NI-1 in this order with no other staging in between (n = 0 sets M0 for all of
+  // them: lds_wave = the wave's first 1 KB piece of the LDS tile), then advance().
+  __device__ __forceinline__ uint32_t lane_off(int n) const {
+    return (col0 ^ xcol(n)) + rowoff0 + (uint32_t)n * (RPI * row_bytes - 1024);
+  }
+  template <int n>
+  __device__ __forceinline__ static void issue_off(uint32_t off, const char* sbase, uint32_t lds_wave) {
+    if constexpr (n == 0)
+      asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(off), "s"(sbase), "s"(lds_wave) : "memory");
+    else
+      asm volatile("global_load_lds_dwordx4 %0, %1 offset:%2" : : "v"(off), "s"(sbase), "n"(1024 * n) : "memory");
+  }
+  __device__ __forceinline__ void advance() { base += tile_bytes; j0 += BC; }
   // Issue the loads of the next tile into the LDS tile at byte address `lds` (wave-uniform)
   // and advance.  Rows past the end re-read row N-1.
   __device__ __forceinline__ void issue(uint32_t lds, int N, int wave, int lane) {

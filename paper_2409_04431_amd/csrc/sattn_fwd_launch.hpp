@@ -1,5 +1,6 @@
 // Definition of launch_fwd_bf16<D>; included by the one translation unit that instantiates it.
 #pragma once
+#include "sattn_fwd64.hpp"
 #include "sattn_launch.hpp"
 
 namespace sattn {
@@ -21,10 +22,34 @@ int launch_fwd_shape(const FwdParams& p, bool softmax, bool pin, int causal, boo
   return launch_fwd_variant<D, NW, VS, false, false>(p, causal, alibi, st);
 }
 
+// The 64-rows-per-wave sigmoid kernel (head dimension 128; ALiBi only in its causal form).
+template <int D>
+int launch_fwd64(FwdParams p, int causal, bool alibi, bool prescale, hipStream_t st) {
+  if constexpr (D != 128) {
+    return SATTN_ERR_UNSUPPORTED;
+  } else {
+    constexpr size_t lds = 6 * 64 * D * 2;  // 3 K slots + 3 V slots of 64 keys
+    p.n_qblocks = (p.N + 255) / 256;
+    dim3 grid(p.n_qblocks * p.B * p.H), block(256);
+    if (alibi && !causal) return SATTN_ERR_UNSUPPORTED;
+    if (alibi) return launch(attn_fwd64_kernel<D, true, true, false>, grid, block, lds, st, p);
+    if (causal) {
+      if (prescale) return launch(attn_fwd64_kernel<D, true, false, true>, grid, block, lds, st, p);
+      return launch(attn_fwd64_kernel<D, true, false, false>, grid, block, lds, st, p);
+    }
+    if (prescale) return launch(attn_fwd64_kernel<D, false, false, true>, grid, block, lds, st, p);
+    return launch(attn_fwd64_kernel<D, false, false, false>, grid, block, lds, st, p);
+  }
+}
+
 template <int D>
 int launch_fwd_bf16(FwdParams p, int waves, int v_slots, bool softmax, bool pin, int causal, bool alibi,
                     hipStream_t st) {
   if (p.kv_group < 1 || p.H % p.kv_group) return SATTN_ERR_SHAPE;
+  if (waves == 64 || waves == 65) {  // 64-row waves: 65 = with the pre-scaled Q fragments
+    if (softmax || !pin) return SATTN_ERR_UNSUPPORTED;
+    return launch_fwd64<D>(p, causal, alibi, waves == 65 && !alibi, st);
+  }
   if (waves == 4) {
     // the two-slot V ring only matters at D = 128, where it lets two workgroups share a compute unit
     if constexpr (D == 128) {

@@ -52,6 +52,8 @@ enum BwdPart { kBwdDkDv = 1, kBwdDq = 2 };
 // Forward: `waves` (4 or 8) is the number of 32-query-row waves per workgroup (sets
 // p.n_qblocks accordingly), `v_slots` (2 or 3) the depth of the V ring of 4-wave workgroups
 // at D = 128.  softmax selects the comparison kernel, pin the hand-ordered step.
+// waves = 64 / 65 selects the kernel with four waves of 64 query rows (D = 128, sigmoid,
+// pinned; 65: Q fragments pre-scaled, no ALiBi).
 template <int D>
 int launch_fwd_bf16(FwdParams p, int waves, int v_slots, bool softmax, bool pin, int causal, bool alibi,
                     hipStream_t st);

@@ -506,6 +506,72 @@ def test_forward_tile_shapes_agree_bit_for_bit_and_with_the_oracle(B, H, N, d, c
     assert np.abs(souts[4][1].cpu().numpy() - rl).max() <= 1e-3
 
 
+@pytest.mark.parametrize("B,H,N,d,causal,alibi", [
+    (1, 2, 700, 128, True, True), (2, 1, 1025, 128, False, False), (1, 2, 2048, 128, True, False),
+    (1, 1, 1536, 128, False, False), (1, 3, 96, 128, True, False), (1, 1, 1, 128, False, False),
+    (2, 2, 333, 128, True, True), (1, 1, 4096, 128, True, True), (1, 2, 257, 128, False, False),
+])
+def test_forward_with_64_row_waves(B, H, N, d, causal, alibi):
+    """The forward shape with four waves of 64 query rows (head dimension 128).  Forced shape
+    64 keeps the arithmetic of the 32-row kernels (bit-identical outputs); 65 multiplies Q by
+    the logit scale once and rounds it to bf16 (one more operand rounding), so it is held to the
+    oracle's bar only.  N = 1 ... 4096 covers: no steady-state tile at all, ragged last chunks,
+    the diagonal steps of every wave, and long pinned loops."""
+    inp = _rand_inputs(B, H, N, d, seed=64 + N)
+    slopes = W.alibi_slopes(H) if alibi else None
+    sl = _dev(slopes) if slopes is not None else None
+    bias = -math.log(max(N, 2))
+    q, k, v = (_dev(inp[n]) for n in ("q", "k", "v"))
+    outs = {}
+    try:
+        for shape in (8, 64, 65):
+            sa.sattn_set_fwd_waves(shape)
+            o = torch.full_like(q, float("nan"))
+            sa.sigmoid_attn_fwd(q, k, v, o, bias, causal, sl)
+            torch.cuda.synchronize()
+            outs[shape] = o
+    finally:
+        sa.sattn_set_fwd_waves(0)
+    assert torch.equal(outs[64], outs[8])
+    ref = orc.sigmoid_attn_fwd(inp["q"], inp["k"], inp["v"], bias, causal, slopes)
+    for shape in (64, 65):
+        assert not torch.isnan(outs[shape]).any()
+        e, er = nerr(outs[shape], ref), row_err(outs[shape], ref)
+        print(f"shape {shape}: {e:.3e}, worst row {er:.3e}")
+        assert e <= TOL_BF16 and er <= TOL_BF16, f"shape {shape}: {e:.3e}, worst row {er:.3e}"
+
+
+def test_forward_with_64_row_waves_on_packed_shared_and_cross_inputs():
+    # the entry points that reuse the forward kernels: variable-length batches, shared K/V heads,
+    # different numbers of queries and keys -- each against its own 32-row result, bit for bit
+    H, d = 4, 128
+    g = torch.Generator().manual_seed(640)
+    lens = [900, 1, 0, 333, 1500]
+    cu = torch.tensor(np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)).cuda()
+    total = sum(lens)
+    q, k, v = (torch.randn(total, H, d, generator=g).bfloat16().cuda() for _ in range(3))
+    bs = torch.tensor([-math.log(max(n, 2)) for n in lens], dtype=torch.float32).cuda()
+    Q4, K4, V4 = (torch.randn(2, H, 1100, d, generator=g).bfloat16().cuda() for _ in range(3))
+    Kg, Vg = K4[:, :2].contiguous(), V4[:, :2].contiguous()
+    Kc, Vc = (torch.randn(2, H, 1700, d, generator=g).bfloat16().cuda() for _ in range(2))
+    res = {}
+    try:
+        for shape in (8, 64):
+            sa.sattn_set_fwd_waves(shape)
+            o1 = torch.full_like(q, float("nan"))
+            sa.sigmoid_attn_varlen_fwd(q, k, v, o1, cu, max(lens), 0.0, True, None, bs)
+            o2 = torch.full_like(Q4, float("nan"))
+            sa.sigmoid_attn_mqa_fwd(Q4, Kg, Vg, o2, -7.0, True)
+            o3 = torch.full_like(Q4, float("nan"))
+            sa.sigmoid_attn_cross_fwd(Q4, Kc, Vc, o3, -7.4)
+            torch.cuda.synchronize()
+            res[shape] = (o1, o2, o3)
+    finally:
+        sa.sattn_set_fwd_waves(0)
+    for a, b_ in zip(res[8], res[64]):
+        assert not torch.isnan(b_).any() and torch.equal(a, b_)
+
+
 # ------------------------------------------------------------------ shared key/value heads
 
 @pytest.mark.parametrize("B,H,Hkv,N,d,causal,alibi", [
