@@ -156,6 +156,30 @@ def main():
     torch.cuda.synchronize()
     sustained_peak = probe_flops / pe[0].elapsed_time(pe[1]) / 1e9
 
+    # The engine clock each kernel actually runs at: one more launch of each with the in-kernel
+    # clock probe on (core cycles / ticks of the constant-rate counter, per workgroup).
+    def clock_under_load(fn, n_wg):
+        buf = torch.zeros(2 * n_wg, dtype=torch.int64, device=dev)
+        sa.sattn_set_clock_probe(buf)
+        try:
+            for _ in range(3):   # the clock needs a few launches to settle after the probe above
+                fn()
+            torch.cuda.synchronize()
+        finally:
+            sa.sattn_set_clock_probe(None)
+        c = buf.view(-1, 2).double()
+        ticks = c[:, 1].sum().item()
+        return (c[:, 0].sum().item() / ticks * sa.sattn_wall_clock_khz() / 1e3) if ticks > 0 else None
+    clocks = {}
+    if cfg.dtype == torch.bfloat16:
+        n_wg = cfg.B * cfg.H * ((cfg.N + 127) // 128)
+        clocks["fwd"] = clock_under_load(lambda: sa.sigmoid_attn_fwd(q, k, v, o, bias, cfg.causal, slopes), n_wg)
+        if cfg.backward:
+            clocks["bwd_dkdv"] = clock_under_load(
+                lambda: sa.sigmoid_attn_bwd_dkdv(q, k, v, dout, dk, dv, bias, cfg.causal, slopes), n_wg)
+            clocks["bwd_dq"] = clock_under_load(
+                lambda: sa.sigmoid_attn_bwd_dq(q, k, v, dout, dq, bias, cfg.causal, slopes), n_wg)
+
     def stats(i):   # mean / median / min of kernel i's HIP-event durations over the timed steps
         ts = sorted(e[i].elapsed_time(e[i + 1]) for e in evs)
         return {"mean": sum(ts) / len(ts), "median": ts[len(ts) // 2], "min": ts[0]}
@@ -188,13 +212,19 @@ def main():
         "config": {"workload": cfg.name, "B": cfg.B, "H": cfg.H, "N": cfg.N, "d": cfg.d, "causal": cfg.causal,
                    "alibi": cfg.alibi, "bias": bias, "flop_convention": "fwd 4BHN^2d, bwd 10BHN^2d, x0.5 causal"},
         "device": {"name": props.name, "compute_units": cus, "clock_mhz": clock_khz / 1e3,
-                   "sustained_mfma_bf16_tflops": sustained_peak},
+                   "sustained_mfma_bf16_tflops": sustained_peak,
+                   # measured inside the kernels (sattn_set_clock_probe): the clock drops under matrix
+                   # load, so the nominal 2.5 PFLOP/s (2.4 GHz) is not reachable by any kernel
+                   "engine_clock_mhz_under_load": clocks},
         "bounds": bounds, "fwd_ms_stats": stats(0),
         "fwd_waves_per_workgroup": (sa.sattn_fwd_waves(cfg.B, cfg.H, cfg.N, cfg.d, cfg.causal)
                                     if cfg.dtype == torch.bfloat16 else None),
         "fwd_ms": fwd_ms, "fwd_tflops": flops_f / fwd_ms / 1e9,
         "fwd_frac_of_bf16_mfma_peak": flops_f / fwd_ms / 1e9 / MFMA_BF16_PEAK_TFLOPS,
     }
+    if clocks.get("fwd"):
+        out["fwd_frac_of_mfma_peak_at_measured_clock"] = (
+            flops_f / fwd_ms / 1e9 / (MFMA_BF16_PEAK_TFLOPS * clocks["fwd"] * 1e3 / clock_khz))
     if cfg.backward:
         dkdv_ms, dq_ms = stats(1)["mean"], stats(2)["mean"]
         out["bwd_dkdv_ms_stats"], out["bwd_dq_ms_stats"] = stats(1), stats(2)
@@ -211,6 +241,8 @@ def main():
                            "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": ach / MFMA_BF16_PEAK_TFLOPS,
                            "traffic": measured_traffic_bytes(cfg.cfg, f"attn_bwd_kernel<{cfg.d}, 1,"),
                            "avg_launch_ms": dkdv_ms}
+        if clocks.get("bwd_dkdv"):
+            out["roofline"]["frac_at_measured_clock"] = ach / (MFMA_BF16_PEAK_TFLOPS * clocks["bwd_dkdv"] * 1e3 / clock_khz)
         out["bounds"]["bwd_dkdv"]["achieved_ms"] = dkdv_ms
         out["bounds"]["bwd_dq"]["achieved_ms"] = dq_ms
     else:

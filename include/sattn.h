@@ -193,12 +193,16 @@ int sattn_headconcat_norm_bwd(const void* x, const void* dy, const float* stats,
 
 /* Forward tile shape (Appendix F.5: the block shape of the forward kernel is a tuning
  * parameter; the paper's second variant halves B_c for d = 64).  Here the tuned quantities are
- * B_r = 32 * waves query rows per workgroup, waves in {4, 8}, and, for 4-wave workgroups at
- * d = 128, the depth of the V ring in LDS (3 slots: one workgroup per compute unit; 2 slots: two).
- * The bf16 forward entry points (sigmoid, softmax, variable-length, ...) choose them per problem
- * from d, B*H*N, the mask and the number of compute units.  sattn_fwd_waves / sattn_fwd_v_slots
- * return that choice (or a negative error code).  The outputs are bit-identical for all
- * shapes: the arithmetic of a query row does not depend on which rows share its workgroup. */
+ * the query rows per workgroup and per wave and, for 4-wave workgroups at d = 128, the depth of
+ * the V ring in LDS: 4 or 8 waves of 32 query rows (two waves per SIMD), or, at d = 128 on long
+ * key loops, 4 waves of 64 query rows (one wave per SIMD, half the LDS traffic per MFMA).  The
+ * bf16 forward entry points (sigmoid, softmax, variable-length, ...) choose them per problem
+ * from d, B*H*N, the mask and the number of compute units.  sattn_fwd_waves returns that
+ * choice as 4, 8, or 64 for the four 64-row waves (the softmax comparison kernel and
+ * non-causal ALiBi run the 8-wave shape where 64 is returned); sattn_fwd_v_slots returns the V
+ * ring depth (3; 2: two 4-wave workgroups per compute unit); both return a negative error code
+ * for bad arguments.  The outputs are bit-identical for all shapes: the arithmetic of a query
+ * row does not depend on which rows share its workgroup. */
 int sattn_fwd_waves(int B, int H, int N, int d, int causal);
 int sattn_fwd_v_slots(int B, int H, int N, int d, int causal);
 

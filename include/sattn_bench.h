@@ -17,10 +17,16 @@ extern "C" {
 #endif
 
 /* Force the forward tile shape for measurements (Appendix F.5: the block shape is a tuning
- * parameter): waves in {4, 8}, v_slots in {2, 3}; 0 = back to the automatic choice; a forced
- * v_slots only applies where that shape exists.  The value is process-wide (an atomic that
- * every forward launch reads): set it from one thread while no other thread launches, or
- * launches in flight on other threads may take either shape.  Results do not depend on it. */
+ * parameter): waves in {4, 8, 64, 65}, v_slots in {2, 3}; 0 = back to the automatic choice; a
+ * forced v_slots only applies where that shape exists, a forced 64 / 65 only for the pinned
+ * sigmoid kernel at d = 128 (other kernels then run the 8-wave shape).  64 = four waves of 64
+ * query rows.  65 = the same with Q multiplied by the logit scale and rounded to bf16 once, and
+ * the bias applied as a factor, which removes the scale-and-bias fma in front of every exp2: a
+ * measurement variant, NOT bit-identical to the other shapes and never chosen automatically (its
+ * logit error grows with |q||k|: one more bf16 rounding on an operand).  The value is
+ * process-wide (an atomic that every forward launch reads): set it from one thread while no
+ * other thread launches, or launches in flight on other threads may take either shape.  Apart
+ * from 65, results do not depend on it. */
 int sattn_set_fwd_waves(int waves);
 int sattn_set_fwd_v_slots(int v_slots);
 
@@ -53,6 +59,18 @@ int sigmoid_attn_bwd_compiler_scheduled(const void* q, const void* k, const void
  * sustains at its actual clock.  `sink` is a device pointer to blocks*256 floats that
  * receives one value per lane (keeps the loop alive).  Returns 0 or SATTN_ERR_*. */
 int sattn_mfma_bf16_probe(int blocks, int iters, float* sink, void* stream);
+
+/* Measurement aid: the engine clock a kernel actually runs at.  While a device buffer of
+ * 2 * capacity int64 is set (NULL = off; process-wide like the tile-shape setters, same
+ * threading rule), every bf16 attention kernel launched by this library has workgroup w <
+ * capacity write out[2w] = core cycles and out[2w+1] = ticks of the constant-rate counter
+ * (hipDeviceAttributeWallClockRate, in kHz) it spent in the kernel.  sum(cycles) / sum(ticks) *
+ * tick rate is the clock under that kernel's load, which on this part lies well below the
+ * nominal peak clock that the 2.5 PFLOP/s figure assumes.  Workgroups that exit at once (blocks
+ * beyond a sequence's length) write nothing: clear the buffer first.  8-byte aligned. */
+int sattn_set_clock_probe(void* device_buffer, int capacity);
+/* Rate of that constant-rate counter on the current device in kHz, or SATTN_ERR_LAUNCH. */
+int sattn_wall_clock_khz(void);
 
 /* Measurement aid: compute units and nominal peak engine clock (kHz) of the current device, as
  * the runtime reports them (host pointers).  SATTN_ERR_LAUNCH if there is no usable device. */

@@ -33,8 +33,10 @@ from .binding import (  # noqa: F401
     sattn_headconcat_norm_bwd,
     sattn_headconcat_norm_fwd,
     sattn_mfma_bf16_probe,
+    sattn_set_clock_probe,
     sattn_set_fwd_v_slots,
     sattn_set_fwd_waves,
     sattn_strerror,
     sattn_version,
+    sattn_wall_clock_khz,
 )

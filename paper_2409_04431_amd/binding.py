@@ -97,6 +97,10 @@ def load_library():
     lib.sattn_fwd_v_slots.restype = i
     lib.sattn_set_fwd_v_slots.argtypes = [i]
     lib.sattn_set_fwd_v_slots.restype = i
+    lib.sattn_set_clock_probe.argtypes = [_vp, i]
+    lib.sattn_set_clock_probe.restype = i
+    lib.sattn_wall_clock_khz.argtypes = []
+    lib.sattn_wall_clock_khz.restype = i
     lib.sattn_device_info.argtypes = [ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_int)]
     lib.sattn_device_info.restype = i
     lib.sattn_version.argtypes = []
@@ -482,3 +486,21 @@ def softmax_attn_bwd_noalloc(q, k, v, o, lse, dout, dq, dk, dv, causal=False, al
                                       _st(q), _st(k), _st(v), _st(o), _st(dout), _st(dq), _st(dk), _st(dv), _stream())
     _raise(rc, "softmax_attn_bwd_noalloc")
     return dq, dk, dv
+
+
+def sattn_set_clock_probe(buf):
+    """buf: a zeroed CUDA int64 tensor of 2 * capacity elements, or None to switch the probe off."""
+    lib = load_library()
+    if buf is None:
+        _raise(lib.sattn_set_clock_probe(None, 0), "sattn_set_clock_probe")
+        return
+    if not buf.is_cuda or buf.dtype != torch.int64 or not buf.is_contiguous():
+        raise SattnError("the clock buffer must be a contiguous CUDA int64 tensor")
+    _raise(lib.sattn_set_clock_probe(buf.data_ptr(), buf.numel() // 2), "sattn_set_clock_probe")
+
+
+def sattn_wall_clock_khz():
+    rc = load_library().sattn_wall_clock_khz()
+    if rc <= 0:
+        _raise(rc, "sattn_wall_clock_khz")
+    return rc

@@ -142,6 +142,9 @@ int make_ref(const void* ptr, const sattn_strides* s, int H, int N, int d, sattn
 // lose a few percent on long loops, where V is staged only one tile ahead.
 std::atomic<int> g_fwd_waves{0};   // 0: choose per problem; 4 or 8: forced (sattn_set_fwd_waves)
 std::atomic<int> g_fwd_vslots{0};  // 0: choose per problem; 2 or 3: forced (sattn_set_fwd_v_slots)
+std::atomic<long long*> g_clock_out{nullptr};  // sattn_set_clock_probe
+std::atomic<int> g_clock_cap{0};
+ClockProbe clock_probe() { return ClockProbe{g_clock_out.load(std::memory_order_relaxed), g_clock_cap.load(std::memory_order_relaxed)}; }
 
 int compute_units() {
   int dev = 0, n = 0;
@@ -165,6 +168,12 @@ FwdShape pick_fwd_shape(int B, int H, int N, int d, int causal) {
     const int64_t avg_tiles = (causal ? (N + 1) / 2 : N) / 64;  // 64-key tiles a workgroup visits on average
     if (wg4 <= (causal ? cus + cus / 2 : cus)) s = FwdShape{4, 3};
     else if (avg_tiles <= 48) s = FwdShape{4, 2};
+    // Long key loops with a workgroup for every compute unit: four waves of 64 query rows, which
+    // read half as much K/V from LDS per MFMA (waves = 64).  Measured 6-10 % faster than the
+    // 32-row shapes from 48 tiles per workgroup on without a mask and from 96 with the causal
+    // mask (whose last three steps per wave run unpinned and whose waves finish unevenly);
+    // equal or slower below.
+    if (avg_tiles >= (causal ? 96 : 48) && wg4 >= 2 * cus) s = FwdShape{64, 3};
   }
   const int forced_waves = g_fwd_waves.load(std::memory_order_relaxed);
   const int forced_vslots = g_fwd_vslots.load(std::memory_order_relaxed);
@@ -173,6 +182,7 @@ FwdShape pick_fwd_shape(int B, int H, int N, int d, int causal) {
     s.waves = forced_waves;
   }
   if (forced_vslots) s.v_slots = forced_vslots;
+  if (s.waves >= 64 && d != 128) s = FwdShape{4, 3};  // the 64-row waves exist at d = 128 only
   if (s.waves != 4 || d != 128) s.v_slots = 3;  // the only shape with a two-slot V ring
   return s;
 }
@@ -252,6 +262,7 @@ int fwd_impl(const FwdArgs& a) {
   p.cu_seqlens = a.cu_seqlens; p.bias_vec = a.bias_vec;
   p.kv_group = a.H / Hkv;
   p.Nk = Nk == a.N ? 0 : Nk;
+  p.clock = clock_probe();
   FwdShape shape = pick_fwd_shape(a.B, a.H, a.N, a.d, a.causal);
   // the 64-row waves exist for the pinned sigmoid kernel at d = 128, ALiBi only in its causal form
   if (shape.waves >= 64 && (SOFTMAX || !PIN || a.d != 128 || (alibi && !a.causal))) shape = FwdShape{8, 3};
@@ -334,6 +345,7 @@ int bwd_impl(const BwdArgs& a) {
   p.db_rows = a.db_rows; p.db_sb = (int64_t)a.H * a.N; p.db_sh = a.N;
   p.kv_group = a.H / Hkv;
   p.Nk = Nk == a.N ? 0 : Nk;
+  p.clock = clock_probe();
   if (SOFTMAX) {
     if (!a.lse) return SATTN_ERR_NULL;
     if ((rc = make_ref(a.o, a.so, a.H, a.N, a.d, a.dtype, &o))) return rc;
@@ -640,6 +652,13 @@ int sattn_set_fwd_v_slots(int v_slots) {
   return SATTN_OK;
 }
 
+int sattn_set_clock_probe(void* device_buffer, int capacity) {
+  if (capacity < 0 || (device_buffer && ((uintptr_t)device_buffer & 7) != 0)) return SATTN_ERR_ALIGN;
+  g_clock_cap.store(device_buffer ? capacity : 0, std::memory_order_relaxed);
+  g_clock_out.store((long long*)device_buffer, std::memory_order_relaxed);
+  return SATTN_OK;
+}
+
 int sattn_fwd_waves(int B, int H, int N, int d, int causal) {
   if (B <= 0 || H <= 0 || N <= 0) return SATTN_ERR_SHAPE;
   if (d != 64 && d != 128) return SATTN_ERR_UNSUPPORTED;
@@ -664,6 +683,16 @@ int sattn_device_info(int* compute_units, int* clock_khz) {
   return SATTN_OK;
 }
 
-int sattn_version(void) { return 101; }
+int sattn_wall_clock_khz(void) {
+  int dev = 0, khz = 0;
+  if (hipGetDevice(&dev) != hipSuccess ||
+      hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev) != hipSuccess || khz <= 0) {
+    (void)hipGetLastError();
+    return SATTN_ERR_LAUNCH;
+  }
+  return khz;
+}
+
+int sattn_version(void) { return 102; }
 
 }  // extern "C"

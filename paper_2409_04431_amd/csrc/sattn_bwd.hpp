@@ -54,6 +54,7 @@ struct BwdParams {
   int kv_group;
   // number of keys when it differs from the number of queries N (0: same); non-causal only
   int Nk;
+  ClockProbe clock;  // measurement aid, {nullptr, 0} otherwise
 };
 
 // One swizzle for tiles that are read both row-wise (ds_read_b128, 32 rows at one logical
@@ -498,6 +499,7 @@ attn_bwd_kernel(const BwdParams p) {
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, h = lane >> 5;
   const int uwave = __builtin_amdgcn_readfirstlane(wave);
+  const ClockStart clk = clock_probe_begin(p.clock);
   // the dK/dV pass runs one workgroup per K/V head and key block and streams the query heads
   // of that head's group one after the other; the dQ pass runs per query head
   const int kv_group = (MODE == BWD_DKDV && !GROUPS) ? 1 : p.kv_group;
@@ -797,6 +799,7 @@ attn_bwd_kernel(const BwdParams p) {
         }
     }
   }
+  clock_probe_end(p.clock, clk);
 }
 
 // Pre-pass of the softmax backward: per query row D_i = sum_t dO[i][t] * O[i][t] (fp32) and

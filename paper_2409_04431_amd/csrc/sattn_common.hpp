@@ -73,6 +73,28 @@ __device__ __forceinline__ void lds_write_b128(uint32_t lds_byte_addr, u32x4 v) 
   *(SATTN_LDS(u32x4)*)(uintptr_t)lds_byte_addr = v;
 }
 
+// Measurement aid: when `out` is set, workgroup w < cap writes the core cycles and the ticks of
+// the constant-rate counter it spent in the kernel to out[2w], out[2w+1]; their ratio is the
+// engine clock the kernel actually ran at (the clock drops under matrix load).
+struct ClockProbe {
+  long long* out;
+  int cap;
+};
+struct ClockStart {
+  long long cycles, ticks;
+};
+__device__ __forceinline__ ClockStart clock_probe_begin(const ClockProbe& c) {
+  ClockStart s{0, 0};
+  if (c.out) { s.cycles = clock64(); s.ticks = wall_clock64(); }
+  return s;
+}
+__device__ __forceinline__ void clock_probe_end(const ClockProbe& c, const ClockStart& s) {
+  if (c.out && threadIdx.x == 0 && (int)blockIdx.x < c.cap) {
+    c.out[2 * (int64_t)blockIdx.x] = clock64() - s.cycles;
+    c.out[2 * (int64_t)blockIdx.x + 1] = wall_clock64() - s.ticks;
+  }
+}
+
 // Workgroup id -> logical tile id so that consecutive logical ids (which share a head's
 // K/V) land on the same XCD and hence the same L2: hardware deals workgroup ids round-robin
 // over the 8 XCDs.

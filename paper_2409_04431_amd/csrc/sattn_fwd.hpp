@@ -39,6 +39,7 @@ struct FwdParams {
   int kv_group;
   // number of keys when it differs from the number of queries N (0: same); non-causal only
   int Nk;
+  ClockProbe clock;  // measurement aid, {nullptr, 0} otherwise
 };
 
 // LDS swizzles (XOR on the 16-byte chunk index within a row).
@@ -450,6 +451,7 @@ attn_fwd_kernel(const FwdParams p) {
   const int tid = threadIdx.x;
   const int wave = tid >> 6, lane = tid & 63;
   const int l32 = lane & 31, h = lane >> 5;
+  const ClockStart clk = clock_probe_begin(p.clock);
 
   const int total = p.n_qblocks * p.B * p.H;
   const int logical = xcd_remap(blockIdx.x, total);
@@ -617,6 +619,7 @@ attn_fwd_kernel(const FwdParams p) {
         *(u32x2*)(orow + 32 * dt + 8 * g + 4 * h) = w;
       }
   }
+  clock_probe_end(p.clock, clk);
 }
 
 }  // namespace sattn

@@ -283,6 +283,7 @@ attn_fwd64_kernel(const FwdParams p) {
   const int tid = threadIdx.x;
   const int wave = tid >> 6, lane = tid & 63;
   const int l32 = lane & 31, h = lane >> 5;
+  const ClockStart clk = clock_probe_begin(p.clock);
 
   const int total = p.n_qblocks * p.B * p.H;
   const int logical = xcd_remap(blockIdx.x, total);
@@ -512,6 +513,7 @@ attn_fwd64_kernel(const FwdParams p) {
         }
     }
   }
+  clock_probe_end(p.clock, clk);
 }
 
 }  // namespace sattn

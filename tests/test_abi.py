@@ -105,7 +105,11 @@ def test_forward_shape_choice(lib):
     # three-slot V ring) or the key loop short (two per compute unit, two-slot V ring)
     assert sa.sattn_fwd_waves(32, 12, 4096, 64) == 4 and sa.sattn_fwd_v_slots(32, 12, 4096, 64) == 3
     assert (sa.sattn_fwd_waves(8, 16, 4096, 128, True), sa.sattn_fwd_v_slots(8, 16, 4096, 128, True)) == (4, 2)
-    assert (sa.sattn_fwd_waves(1, 32, 16384, 128, True), sa.sattn_fwd_v_slots(1, 32, 16384, 128, True)) == (8, 3)
+    # long key loops with a workgroup for every compute unit: four waves of 64 query rows
+    assert (sa.sattn_fwd_waves(1, 32, 16384, 128, True), sa.sattn_fwd_v_slots(1, 32, 16384, 128, True)) == (64, 3)
+    assert sa.sattn_fwd_waves(2, 16, 8192, 128) == 64 and sa.sattn_fwd_waves(8, 16, 4096, 128) == 64
+    assert sa.sattn_fwd_waves(1, 4, 8192, 128) == 4 and sa.sattn_fwd_waves(1, 6, 8192, 128) == 8   # too few workgroups for 256-row blocks
+    assert sa.sattn_fwd_waves(2, 8, 65536, 64) == 4          # d = 64 has no 64-row shape
     assert (sa.sattn_fwd_waves(1, 2, 512, 128), sa.sattn_fwd_v_slots(1, 2, 512, 128)) == (4, 3)
     assert lib.sattn_fwd_waves(1, 1, 16, 100, 0) == -3 and lib.sattn_fwd_v_slots(1, 1, 16, 100, 0) == -3
     assert lib.sattn_fwd_waves(0, 1, 16, 64, 0) == -2
@@ -114,6 +118,8 @@ def test_forward_shape_choice(lib):
         sa.sattn_set_fwd_waves(8)
         assert sa.sattn_fwd_waves(1, 2, 512, 128) == 8 and sa.sattn_fwd_waves(1, 2, 512, 64) == 8
         assert sa.sattn_fwd_v_slots(8, 16, 4096, 128, True) == 3      # no two-slot ring with 8 waves
+        sa.sattn_set_fwd_waves(64)
+        assert sa.sattn_fwd_waves(1, 2, 512, 128) == 64 and sa.sattn_fwd_waves(1, 2, 512, 64) == 4
         sa.sattn_set_fwd_waves(4)
         sa.sattn_set_fwd_v_slots(2)
         assert sa.sattn_fwd_v_slots(1, 32, 16384, 128, True) == 2 and sa.sattn_fwd_v_slots(1, 2, 512, 64) == 3
