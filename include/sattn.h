@@ -292,6 +292,25 @@ int sigmoid_attn_varlen_bwd(const void* q, const void* k, const void* v, const v
                             const sattn_strides* sdq, const sattn_strides* sdk,
                             const sattn_strides* sdv, void* stream);
 
+/* Variable-length batches with the gradient of a learnable bias: sigmoid_attn_varlen_bwd, and
+ * the dQ pass also writes db_rows[h][t] = sum_j dS_tj for every packed token t that the pass
+ * covers (device pointer, contiguous [H, total_tokens] fp32, required; tokens of a sequence
+ * beyond max_seqlen are not written).  If db is not NULL (device pointer, B*H fp32), a second
+ * small kernel sums each sequence's rows in a fixed order into db[b*H + h]: with a bias per
+ * sequence (Appendix G.4) that is the gradient of that sequence's bias, per head.  total_tokens
+ * is the first dimension of the packed tensors.  Errors as sigmoid_attn_varlen_bwd and
+ * sigmoid_attn_bwd_bias_grad. */
+int sigmoid_attn_varlen_bwd_bias_grad(const void* q, const void* k, const void* v, const void* dout,
+                                      void* dq, void* dk, void* dv, float* db_rows, float* db,
+                                      const int32_t* cu_seqlens, const float* bias_per_seq,
+                                      int B, int H, int max_seqlen, int64_t total_tokens, int d,
+                                      sattn_dtype dtype, float bias, int causal,
+                                      const float* alibi_slopes,
+                                      const sattn_strides* sq, const sattn_strides* sk,
+                                      const sattn_strides* sv, const sattn_strides* sdout,
+                                      const sattn_strides* sdq, const sattn_strides* sdk,
+                                      const sattn_strides* sdv, void* stream);
+
 /* Library version: major*10000 + minor*100 + patch. */
 int sattn_version(void);
 

@@ -21,6 +21,7 @@ from .binding import (  # noqa: F401
     sigmoid_attn_mqa_bwd,
     sigmoid_attn_mqa_fwd,
     sigmoid_attn_varlen_bwd,
+    sigmoid_attn_varlen_bwd_bias_grad,
     sigmoid_attn_varlen_fwd,
     softmax_attn_bwd,
     softmax_attn_bwd_noalloc,

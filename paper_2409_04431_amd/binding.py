@@ -65,6 +65,8 @@ def load_library():
     lib.sigmoid_attn_varlen_fwd.restype = i
     lib.sigmoid_attn_varlen_bwd.argtypes = [_vp] * 7 + [ip, _vp, i, i, i, i, i, f, i, _vp] + [_SP] * 7 + [_vp]
     lib.sigmoid_attn_varlen_bwd.restype = i
+    lib.sigmoid_attn_varlen_bwd_bias_grad.argtypes = [_vp] * 9 + [ip, _vp, i, i, i, ctypes.c_int64, i, i, f, i, _vp] + [_SP] * 7 + [_vp]
+    lib.sigmoid_attn_varlen_bwd_bias_grad.restype = i
     lib.sigmoid_attn_bwd_dkdv.argtypes = [_vp] * 6 + [i, i, i, i, i, f, i, _vp] + [_SP] * 6 + [_vp]
     lib.sigmoid_attn_bwd_dkdv.restype = i
     lib.sigmoid_attn_bwd_dq.argtypes = [_vp] * 5 + [i, i, i, i, i, f, i, _vp] + [_SP] * 5 + [_vp]
@@ -160,6 +162,29 @@ def sigmoid_attn_varlen_bwd(q, k, v, dout, dq, dk, dv, cu_seqlens, max_seqlen, b
                                      _st3(dq), _st3(dk), _st3(dv), _stream())
     _raise(rc, "sigmoid_attn_varlen_bwd")
     return dq, dk, dv
+
+
+def sigmoid_attn_varlen_bwd_bias_grad(q, k, v, dout, dq, dk, dv, db_rows, cu_seqlens, max_seqlen, bias, causal=False,
+                                      alibi_slopes=None, bias_per_seq=None, db=None):
+    """sigmoid_attn_varlen_bwd plus db_rows[h, t] = sum_j dS_tj (fp32 [H, tokens]) and, if given, db[b, h]."""
+    lib = load_library()
+    B = _check_varlen(cu_seqlens, bias_per_seq, q, k, v, dout, dq, dk, dv)
+    total, H, d = q.shape
+    for t, shape, what in ((db_rows, (H, total), "db_rows"), (db, (B, H), "db")):
+        if t is None and what == "db":
+            continue
+        if t is None or not t.is_cuda or t.dtype != torch.float32 or tuple(t.shape) != shape or not t.is_contiguous():
+            raise SattnError(f"{what} must be a contiguous CUDA float32 tensor of shape {shape}")
+    bp = _vp(bias_per_seq.data_ptr()) if bias_per_seq is not None else None
+    rc = lib.sigmoid_attn_varlen_bwd_bias_grad(q.data_ptr(), k.data_ptr(), v.data_ptr(), dout.data_ptr(), dq.data_ptr(),
+                                               dk.data_ptr(), dv.data_ptr(), _vp(db_rows.data_ptr()),
+                                               _vp(db.data_ptr()) if db is not None else None,
+                                               _vp(cu_seqlens.data_ptr()), bp, B, H, int(max_seqlen), int(total), d,
+                                               SATTN_BF16, float(bias), int(bool(causal)), _slopes_ptr(alibi_slopes, H),
+                                               _st3(q), _st3(k), _st3(v), _st3(dout), _st3(dq), _st3(dk), _st3(dv),
+                                               _stream())
+    _raise(rc, "sigmoid_attn_varlen_bwd_bias_grad")
+    return dq, dk, dv, db_rows, db
 
 
 def _check_mqa(q, kv, *qlike):

@@ -111,6 +111,26 @@ rowsum_reduce_kernel(const float* rows, float* out, int H, int N, int64_t sb, in
   if (tid == 0) out[bh] = part[0];
 }
 
+// Packed sequences: out[b*H + h] = sum of rows[h*total + t] over the tokens t of sequence b that the
+// backward pass covered (its first min(length, max_seqlen) tokens), in a fixed order.
+__global__ void __launch_bounds__(256)
+rowsum_reduce_varlen_kernel(const float* rows, float* out, const int* cu_seqlens, int H, int64_t total, int max_seqlen) {
+  __shared__ float part[256];
+  const int bh = blockIdx.x, tid = threadIdx.x, b = bh / H, h = bh % H;
+  const int t0 = cu_seqlens[b], n = min(cu_seqlens[b + 1] - t0, max_seqlen);
+  const float* r = rows + (int64_t)h * total + t0;
+  float acc = 0.f;
+  for (int i = tid; i < n; i += 256) acc += r[i];
+  part[tid] = acc;
+  __syncthreads();
+#pragma unroll
+  for (int m = 128; m >= 1; m >>= 1) {
+    if (tid < m) part[tid] += part[tid + m];
+    __syncthreads();
+  }
+  if (tid == 0) out[bh] = part[0];
+}
+
 // Validate one tensor and turn it into a TensorRef.  Strides are in elements.
 int make_ref(const void* ptr, const sattn_strides* s, int H, int N, int d, sattn_dtype dt, TensorRef* out) {
   if (!ptr) return SATTN_ERR_NULL;
@@ -294,7 +314,8 @@ struct BwdArgs {
   const sattn_strides *sq, *sk, *sv, *so, *sdout, *sdq, *sdk, *sdv;
   void* workspace; size_t workspace_bytes; int parts; void* stream;
   const int* cu_seqlens = nullptr; const float* bias_vec = nullptr;  // variable-length batches
-  float* db_rows = nullptr; float* db = nullptr;                     // bias gradient (dense sigmoid only)
+  float* db_rows = nullptr; float* db = nullptr;                     // bias gradient (sigmoid only)
+  int64_t db_tokens = 0;                                             // packed sequences: tokens in db_rows' [H, tokens]
   int Hkv = 0;                                                       // K/V heads (0: one per query head)
   int Nk = 0;                                                        // keys (0: as many as queries)
 };
@@ -343,6 +364,7 @@ int bwd_impl(const BwdArgs& a) {
   p.nbias_log2 = -a.bias * kLog2e;
   p.cu_seqlens = a.cu_seqlens; p.bias_vec = a.bias_vec;
   p.db_rows = a.db_rows; p.db_sb = (int64_t)a.H * a.N; p.db_sh = a.N;
+  if (a.cu_seqlens && a.db_rows) { p.db_sb = 0; p.db_sh = a.db_tokens; }  // [H, tokens]: the kernel adds the sequence's first token
   p.kv_group = a.H / Hkv;
   p.Nk = Nk == a.N ? 0 : Nk;
   p.clock = clock_probe();
@@ -367,9 +389,14 @@ int bwd_impl(const BwdArgs& a) {
   }
   if (a.d == 128) rc = launch_bwd_bf16<128>(p, SOFTMAX, PIN, a.causal, alibi, a.parts, st);
   else rc = launch_bwd_bf16<64>(p, SOFTMAX, PIN, a.causal, alibi, a.parts, st);
-  if (rc == SATTN_OK && a.db)
-    rc = launch(rowsum_reduce_kernel, dim3(a.B * a.H), dim3(256), 0, st, (const float*)a.db_rows, a.db, a.H, a.N,
-                p.db_sb, p.db_sh);
+  if (rc == SATTN_OK && a.db) {
+    if (a.cu_seqlens)
+      rc = launch(rowsum_reduce_varlen_kernel, dim3(a.B * a.H), dim3(256), 0, st, (const float*)a.db_rows, a.db,
+                  a.cu_seqlens, a.H, a.db_tokens, a.N);
+    else
+      rc = launch(rowsum_reduce_kernel, dim3(a.B * a.H), dim3(256), 0, st, (const float*)a.db_rows, a.db, a.H, a.N,
+                  p.db_sb, p.db_sh);
+  }
   return rc;
 }
 
@@ -577,6 +604,26 @@ int sigmoid_attn_varlen_bwd(const void* q, const void* k, const void* v, const v
   BwdArgs a{q, k, v, nullptr, nullptr, dout, dq, dk, dv, B, H, max_seqlen, d, dtype, bias, causal, alibi_slopes,
             &tq, &tk, &tv, nullptr, &tdo, &tdq, &tdk, &tdv, nullptr, 0, kBwdDkDv | kBwdDq, stream};
   a.cu_seqlens = cu_seqlens; a.bias_vec = bias_per_seq;
+  return bwd_impl<false>(a);
+}
+
+int sigmoid_attn_varlen_bwd_bias_grad(const void* q, const void* k, const void* v, const void* dout, void* dq,
+                                      void* dk, void* dv, float* db_rows, float* db, const int32_t* cu_seqlens,
+                                      const float* bias_per_seq, int B, int H, int max_seqlen, int64_t total_tokens,
+                                      int d, sattn_dtype dtype, float bias, int causal, const float* alibi_slopes,
+                                      const sattn_strides* sq, const sattn_strides* sk, const sattn_strides* sv,
+                                      const sattn_strides* sdout, const sattn_strides* sdq, const sattn_strides* sdk,
+                                      const sattn_strides* sdv, void* stream) {
+  if (!cu_seqlens || !db_rows) return SATTN_ERR_NULL;
+  if (((uintptr_t)db_rows & 3) != 0 || ((uintptr_t)db & 3) != 0) return SATTN_ERR_ALIGN;
+  if (total_tokens <= 0) return SATTN_ERR_SHAPE;
+  const sattn_strides tq = varlen_strides(sq, H, d), tk = varlen_strides(sk, H, d), tv = varlen_strides(sv, H, d),
+                      tdo = varlen_strides(sdout, H, d), tdq = varlen_strides(sdq, H, d),
+                      tdk = varlen_strides(sdk, H, d), tdv = varlen_strides(sdv, H, d);
+  BwdArgs a{q, k, v, nullptr, nullptr, dout, dq, dk, dv, B, H, max_seqlen, d, dtype, bias, causal, alibi_slopes,
+            &tq, &tk, &tv, nullptr, &tdo, &tdq, &tdk, &tdv, nullptr, 0, kBwdDkDv | kBwdDq, stream};
+  a.cu_seqlens = cu_seqlens; a.bias_vec = bias_per_seq;
+  a.db_rows = db_rows; a.db = db; a.db_tokens = total_tokens;
   return bwd_impl<false>(a);
 }
 

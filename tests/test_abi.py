@@ -100,6 +100,18 @@ def test_bias_gradient_entry_point_rejects_bad_arguments(lib):
     assert lib.sigmoid_attn_bwd_bias_grad(*ptrs, 0x8000, None, *tail) == -3          # head dimension
 
 
+def test_varlen_bias_gradient_entry_point_rejects_bad_arguments(lib):
+    ptrs = [0x1000, 0x2000, 0x3000, 0x4000, 0x5000, 0x6000, 0x7000]
+    tail = lambda total=900, d=128, dtype=0: [2, 4, 512, total, d, dtype, 0.0, 1, None, *([None] * 7), None]
+    f = lib.sigmoid_attn_varlen_bwd_bias_grad
+    assert f(*ptrs, None, None, 0x9000, None, *tail()) == -1            # db_rows is required
+    assert f(*ptrs, 0x8000, None, None, None, *tail()) == -1            # cu_seqlens is required
+    assert f(*ptrs, 0x8002, None, 0x9000, None, *tail()) == -4          # fp32 alignment
+    assert f(*ptrs, 0x8000, None, 0x9000, None, *tail(total=0)) == -2
+    assert f(*ptrs, 0x8000, None, 0x9000, None, *tail(d=96)) == -3
+    assert f(*ptrs, 0x8000, None, 0x9000, None, *tail(dtype=1)) == -3   # packed sequences are bf16 only
+
+
 def test_forward_shape_choice(lib):
     # d = 64 always takes 4-wave workgroups; d = 128 while the grid is small (one per compute unit,
     # three-slot V ring) or the key loop short (two per compute unit, two-slot V ring)

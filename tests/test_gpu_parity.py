@@ -57,6 +57,19 @@ def _dev(x):
     return x.cuda()
 
 
+def _guarded(shape, dtype=torch.bfloat16, pad=256, fill=777.0):
+    """An output tensor of `shape` (NaN-filled) inside a larger buffer with sentinel values on
+    both sides, and a function that checks the sentinels are untouched."""
+    n = int(np.prod(shape))
+    buf = torch.full((n + 2 * pad,), fill, dtype=dtype, device="cuda")
+    out = buf[pad:pad + n].view(*shape)
+    out.fill_(float("nan"))
+
+    def check():
+        assert bool((buf[:pad] == fill).all()) and bool((buf[pad + n:] == fill).all()), "write outside the output tensor"
+    return out, check
+
+
 def _run_fwd_bwd(inp, bias, causal, slopes, backward=True):
     q, k, v = (_dev(inp[n]) for n in ("q", "k", "v"))
     sl = _dev(slopes) if slopes is not None else None
@@ -231,12 +244,13 @@ def _run_softmax(inp, causal, slopes):
     q, k, v, do = (_dev(inp[n]) for n in ("q", "k", "v", "dout"))
     sl = _dev(slopes) if slopes is not None else None
     B, H, N, d = q.shape
-    o = torch.full_like(q, float("nan"))
-    lse = torch.full((B, H, N), float("nan"), device="cuda")
-    dq, dk, dv = (torch.full_like(q, float("nan")) for _ in range(3))
+    (o, g0), (dq, g1), (dk, g2), (dv, g3) = (_guarded(q.shape) for _ in range(4))
+    lse, g4 = _guarded((B, H, N), torch.float32)
     sa.softmax_attn_fwd(q, k, v, o, lse, causal, sl)
     sa.softmax_attn_bwd(q, k, v, o, lse, do, dq, dk, dv, causal, sl)
     torch.cuda.synchronize()
+    for g in (g0, g1, g2, g3, g4):   # nothing written outside the outputs
+        g()
     return dict(o=o, lse=lse, dq=dq, dk=dk, dv=dv)
 
 
@@ -406,12 +420,14 @@ def test_varlen_batches_match_per_sequence_calls_and_oracle(d, causal, alibi, pe
     bias = -float(np.log(max(lens)))
     Q, K, V, DO = (_dev(t) for t in (q, k, v, do))
     sl = _dev(slopes) if slopes is not None else None
-    o, dq, dk, dv = (torch.full_like(Q, float("nan")) for _ in range(4))
+    (o, g0), (dq, g1), (dk, g2), (dv, g3) = (_guarded(Q.shape) for _ in range(4))
     cu_d = torch.from_numpy(cu).cuda()
     bp = biases.cuda() if per_seq_bias else None
     sa.sigmoid_attn_varlen_fwd(Q, K, V, o, cu_d, max(lens), bias, causal, sl, bp)
     sa.sigmoid_attn_varlen_bwd(Q, K, V, DO, dq, dk, dv, cu_d, max(lens), bias, causal, sl, bp)
     torch.cuda.synchronize()
+    for g in (g0, g1, g2, g3):   # nothing written outside the packed outputs
+        g()
     for s_, n in enumerate(lens):
         if n == 0:
             continue
@@ -469,6 +485,48 @@ def test_bias_gradient_rows_match_oracle_and_leave_the_other_gradients_unchanged
     sa.sigmoid_attn_bwd_bias_grad(q, k, v, do, dq, dk, dv, rows2, bias, causal, sl)
     torch.cuda.synchronize()
     assert torch.equal(rows2, rows)
+
+
+@pytest.mark.parametrize("d,causal,alibi", [(128, True, False), (64, False, True)])
+def test_varlen_bias_gradient_matches_per_sequence_calls_and_oracle(d, causal, alibi):
+    # the packed entry point with the row sums of dS: per sequence bit-identical to the dense bias-gradient
+    # call on that sequence alone, and within the oracle's bar; db[b, h] = the sum over the sequence's rows
+    H = 2
+    lens = [300, 1, 0, 129, 64]
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    total = int(cu[-1])
+    g = torch.Generator().manual_seed(2468)
+    q, k, v, do = (torch.randn(total, H, d, generator=g).bfloat16() for _ in range(4))
+    slopes = W.alibi_slopes(H) if alibi else None
+    sl = _dev(slopes) if slopes is not None else None
+    biases = torch.tensor([-float(np.log(max(n, 2))) for n in lens], dtype=torch.float32)
+    Q, K, V, DO = (_dev(t) for t in (q, k, v, do))
+    dq, dk, dv, dq0, dk0, dv0 = (torch.full_like(Q, float("nan")) for _ in range(6))
+    rows, guard = _guarded((H, total), torch.float32)
+    db = torch.full((len(lens), H), float("nan"), dtype=torch.float32, device="cuda")
+    cu_d = torch.from_numpy(cu).cuda()
+    sa.sigmoid_attn_varlen_bwd_bias_grad(Q, K, V, DO, dq, dk, dv, rows, cu_d, max(lens), 0.0, causal, sl, biases.cuda(), db=db)
+    sa.sigmoid_attn_varlen_bwd(Q, K, V, DO, dq0, dk0, dv0, cu_d, max(lens), 0.0, causal, sl, biases.cuda())
+    torch.cuda.synchronize()
+    guard()
+    for a_, b_ in ((dq, dq0), (dk, dk0), (dv, dv0)):   # the other gradients do not change
+        assert torch.equal(a_, b_)
+    assert not torch.isnan(rows).any()
+    for s_, n in enumerate(lens):
+        a, b_ = int(cu[s_]), int(cu[s_ + 1])
+        if n == 0:
+            assert torch.all(db[s_] == 0)
+            continue
+        dense = lambda t: t[a:b_].permute(1, 0, 2).unsqueeze(0)
+        r1 = torch.full((1, H, n), float("nan"), dtype=torch.float32, device="cuda")
+        o1, o2, o3 = (torch.empty(1, H, n, d, dtype=torch.bfloat16, device="cuda") for _ in range(3))
+        sa.sigmoid_attn_bwd_bias_grad(dense(Q), dense(K), dense(V), dense(DO), o1, o2, o3, r1, float(biases[s_]), causal, sl)
+        torch.cuda.synchronize()
+        assert torch.equal(rows[:, a:b_], r1[0])
+        f = lambda t: t[a:b_].permute(1, 0, 2).unsqueeze(0).double().numpy()
+        ref = orc.sigmoid_attn_bias_grad(f(q), f(k), f(v), f(do), float(biases[s_]), causal, slopes)
+        assert nerr(rows[:, a:b_], ref[0]) <= 2e-4
+        np.testing.assert_allclose(db[s_].cpu().numpy(), ref[0].sum(-1), rtol=2e-4, atol=2e-4 * np.abs(ref).max() * n)
 
 
 # ------------------------------------------------------------------ forward tile shape
@@ -589,11 +647,13 @@ def test_shared_kv_heads_match_oracle_and_the_expanded_dense_call(B, H, Hkv, N, 
     sl = _dev(slopes) if slopes is not None else None
     bias = -math.log(N)
     Q, K, V, DO = (_dev(t) for t in (q, k, v, do))
-    o, dq = (torch.full_like(Q, float("nan")) for _ in range(2))
-    dk, dv = (torch.full_like(K, float("nan")) for _ in range(2))
+    (o, g0), (dq, g1) = (_guarded(Q.shape) for _ in range(2))
+    (dk, g2), (dv, g3) = (_guarded(K.shape) for _ in range(2))
     sa.sigmoid_attn_mqa_fwd(Q, K, V, o, bias, causal, sl)
     sa.sigmoid_attn_mqa_bwd(Q, K, V, DO, dq, dk, dv, bias, causal, sl)
     torch.cuda.synchronize()
+    for g in (g0, g1, g2, g3):   # nothing written outside the outputs (dK/dV have fewer heads)
+        g()
     f = lambda t: t.double().numpy()
     ro = orc.sigmoid_attn_mqa_fwd(f(q), f(k), f(v), bias, causal, slopes)
     rdq, rdk, rdv = orc.sigmoid_attn_mqa_bwd(f(q), f(k), f(v), f(do), bias, causal, slopes)
@@ -627,11 +687,17 @@ def test_headconcat_norm_matches_oracle(B, H, N, d, kind, bnhd):
             return t.cuda()
         return t.permute(0, 2, 1, 3).contiguous().cuda().permute(0, 2, 1, 3)
     X, DY = dev(x), dev(dy)
-    Y, DX = (torch.full_like(X, float("nan")) for _ in range(2))
-    stats = torch.full((B, N, 2), float("nan"), dtype=torch.float32, device="cuda")
+
+    def out():   # guarded output in the same storage order as the inputs
+        t, g = _guarded((B, N, H, d) if bnhd else (B, H, N, d))
+        return (t.permute(0, 2, 1, 3) if bnhd else t), g
+    (Y, g0), (DX, g1) = out(), out()
+    stats, g2 = _guarded((B, N, 2), torch.float32)
     sa.sattn_headconcat_norm_fwd(X, Y, stats, kind, 1e-5)
     sa.sattn_headconcat_norm_bwd(X, DY, stats, DX, kind)
     torch.cuda.synchronize()
+    for g in (g0, g1, g2):   # nothing written outside the outputs
+        g()
     ry, rmean, rrstd = orc.headconcat_norm_fwd(x.double().numpy(), kind, 1e-5)
     rdx = orc.headconcat_norm_bwd(x.double().numpy(), dy.double().numpy(), kind, 1e-5)
     # fp32 statistics of exactly representable inputs; outputs rounded once to bf16 (2^-9 relative)
@@ -742,11 +808,13 @@ def test_cross_attention_matches_oracle(B, H, Nq, Nk, d):
     k, v = (torch.randn(B, H, Nk, d, generator=g).bfloat16() for _ in range(2))
     bias = -math.log(max(Nk, 2))
     Q, K, V, DO = (_dev(t) for t in (q, k, v, do))
-    o, dq = (torch.full_like(Q, float("nan")) for _ in range(2))
-    dk, dv = (torch.full_like(K, float("nan")) for _ in range(2))
+    (o, g0), (dq, g1) = (_guarded(Q.shape) for _ in range(2))
+    (dk, g2), (dv, g3) = (_guarded(K.shape) for _ in range(2))
     sa.sigmoid_attn_cross_fwd(Q, K, V, o, bias)
     sa.sigmoid_attn_cross_bwd(Q, K, V, DO, dq, dk, dv, bias)
     torch.cuda.synchronize()
+    for g in (g0, g1, g2, g3):   # nothing written outside the outputs (two different lengths)
+        g()
     f = lambda t: t.double().numpy()
     ro = orc.sigmoid_attn_cross_fwd(f(q), f(k), f(v), bias)
     rdq, rdk, rdv = orc.sigmoid_attn_cross_bwd(f(q), f(k), f(v), f(do), bias)
