@@ -453,7 +453,9 @@ __device__ __forceinline__ void bwd_full_subslots(BwdWave<D, MODE>& W, uint32_t 
 }
 
 // thr (MASK only): elements with key_of_reg(e) >= thr (DKDV) / <= thr (DQ) are kept.
-template <int D, int MODE, bool ALIBI, bool FOLD, int PAR, bool DMA, bool MASK = false>
+// SETTLE = false leaves the wait for the last MFMAs to the caller (a loop of pinned steps only,
+// which waits once after the loop).
+template <int D, int MODE, bool ALIBI, bool FOLD, int PAR, bool DMA, bool MASK = false, bool SETTLE = true>
 __device__ __forceinline__ void bwd_step_full_pinned(BwdWave<D, MODE>& W, uint32_t trimm, const uint32_t* nextrow,
                                                      uint32_t nextimm, int cs, const DmaStagerX<D, 4>& st1,
                                                      const DmaStagerX<D, 4>& st2, uint32_t dma_lds, int uwave,
@@ -474,7 +476,7 @@ __device__ __forceinline__ void bwd_step_full_pinned(BwdWave<D, MODE>& W, uint32
                                                                 dist0, dstep, thr, st1, st2, dma_lds, uwave);
   // The compiler does not know that the asm statements above are MFMAs: let the last ones
   // retire before it may touch their accumulators (copies at the join with the other path).
-  mfma_settle();
+  if constexpr (SETTLE) mfma_settle();
   if (MODE == BWD_DKDV) {
     W.pb[PAR ^ 1][0] = as_bf16x8(u32x4{wp[0], wp[1], wp[2], wp[3]});
     W.pb[PAR ^ 1][1] = as_bf16x8(u32x4{wp[4], wp[5], wp[6], wp[7]});
@@ -749,16 +751,18 @@ attn_bwd_kernel(const BwdParams p) {
       rotate(t);
     }
     if constexpr (PIN && !SOFTMAX) if (phase == 0) {
+      const bool any_steady = t <= t_s1;
       for (; t <= t_s1; ++t) {
-        bwd_step_full_pinned<D, MODE, ALIBI, FOLD, 0, false>(W, 0, W.row0, CHUNK, 32 * (2 * t - 1), st1, st2, 0, uwave);
+        bwd_step_full_pinned<D, MODE, ALIBI, FOLD, 0, false, false, false>(W, 0, W.row0, CHUNK, 32 * (2 * t - 1), st1, st2, 0, uwave);
         __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): tile t+1 has landed
         __builtin_amdgcn_s_barrier();
-        bwd_step_full_pinned<D, MODE, ALIBI, FOLD, 1, true>(W, CHUNK, W.row1, 0, 32 * (2 * t), st1, st2,
-                                                      lds0 + ((t + 2) % NSLOT) * SLOT, uwave);
+        bwd_step_full_pinned<D, MODE, ALIBI, FOLD, 1, true, false, false>(W, CHUNK, W.row1, 0, 32 * (2 * t), st1, st2,
+                                                                    lds0 + ((t + 2) % NSLOT) * SLOT, uwave);
         st1.advance();
         st2.advance();
         rotate(t);
       }
+      if (any_steady) mfma_settle();  // once for the whole loop of pinned steps
     }
     general_end = t_hi + 1;
   }
