@@ -190,10 +190,10 @@ FwdShape pick_fwd_shape(int B, int H, int N, int d, int causal) {
     else if (avg_tiles <= 48) s = FwdShape{4, 2};
     // Long key loops with a workgroup for every compute unit: four waves of 64 query rows, which
     // read half as much K/V from LDS per MFMA (waves = 64).  Measured 6-10 % faster than the
-    // 32-row shapes from 48 tiles per workgroup on without a mask and from 96 with the causal
+    // 32-row shapes from 48 tiles per workgroup on without a mask and from 64 with the causal
     // mask (whose last three steps per wave run unpinned and whose waves finish unevenly);
     // equal or slower below.
-    if (avg_tiles >= (causal ? 96 : 48) && wg4 >= 2 * cus) s = FwdShape{64, 3};
+    if (avg_tiles >= (causal ? 64 : 48) && wg4 >= 2 * cus) s = FwdShape{64, 3};
   }
   const int forced_waves = g_fwd_waves.load(std::memory_order_relaxed);
   const int forced_vslots = g_fwd_vslots.load(std::memory_order_relaxed);
