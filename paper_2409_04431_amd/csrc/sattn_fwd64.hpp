@@ -23,6 +23,8 @@
 // same kind the inputs already carry); the other variant keeps the scale-and-bias fma and is
 // bit-identical to the 32-row kernels.
 #pragma once
+#include <type_traits>
+
 #include "sattn_fwd.hpp"
 
 namespace sattn {
@@ -77,80 +79,9 @@ struct F64Wave {
   float ebias;          // PRESCALE: exp(-b), the factor of 2^u' in 1 + exp(-b) 2^u'
 };
 
-enum F64Kind { F64_NONE = 0, F64_FULL = 1, F64_LAST = 2, F64_TAIL = 3 };
-
-// ---- compiler-scheduled step for chunk c (PAR = c & 1), used where a row block's chunk is its
-// last one (diagonal / ragged end), where the pipeline drains, and for short loops.
-// Row block rb takes part according to kind[rb]:
-//   FULL: S^T(c+1); sigmoid(c); O^T += V(c-1)^T P^T(c-1)       LAST: masked sigmoid(c); O^T update
-//   TAIL: O^T update only                                        NONE: nothing
-// K fragments are refilled with chunk c+2 and V fragments with chunk c whenever some row block
-// will use them.
-template <int D, bool FOLD, bool PRESCALE, int PAR>
-__device__ __forceinline__ void f64_step(F64Wave<D>& W, int kind0, int kind1, uint32_t kaddr, uint32_t vaddr, int jc,
-                                         int Nk, bool causal) {
-  constexpr int KD = D / 16, DT = D / 32;
-  const int kind[2] = {kind0, kind1};
-  const bool any_qk = kind0 == F64_FULL || kind1 == F64_FULL;
-  const bool any_sig = any_qk || kind0 == F64_LAST || kind1 == F64_LAST;
-  const int jl = jc + 8 * W.h;  // key held by register 0 of this lane half
-#pragma unroll
-  for (int rb = 0; rb < 2; ++rb) {
-    if (kind[rb] == F64_FULL) {
-      if constexpr (FOLD) f64_mfma_s_init<true>(W.s[PAR ^ 1][rb], W.kf[0], W.qf[rb][0], W.cinit);
-      else f64_mfma_s_zero<true>(W.s[PAR ^ 1][rb], W.kf[0], W.qf[rb][0]);
-#pragma unroll
-      for (int m = 1; m < KD; ++m) f64_mfma_s<true>(W.s[PAR ^ 1][rb], W.kf[m], W.qf[rb][m]);
-    }
-  }
-  if (any_qk) {
-#pragma unroll
-    for (int m = 0; m < KD; ++m) W.kf[m] = as_bf16x8(lds_read_b128(W.koff[m] + kaddr));
-  }
-  f64_settle(W.s[PAR ^ 1][0], W.s[PAR ^ 1][1]);
-#pragma unroll
-  for (int rb = 0; rb < 2; ++rb) {
-    if (kind[rb] == F64_FULL || kind[rb] == F64_LAST) {
-      const int qi = W.qi0 + 32 * rb;
-      int lim = Nk - 1 - jl;  // LAST: registers whose key offset exceeds lim are masked
-      if (causal) lim = lim < qi - jl ? lim : qi - jl;
-      const float w = FOLD ? __builtin_fmaf(W.sl2, (float)(qi - jl), W.nbias) : W.nbias;
-      float pr[16];
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        if constexpr (PRESCALE)
-          pr[r] = __builtin_amdgcn_rcpf(__builtin_fmaf(__builtin_amdgcn_exp2f(W.s[PAR][rb][r]), W.ebias, 1.0f));
-        else
-          pr[r] = __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(__builtin_fmaf(W.s[PAR][rb][r], W.nscale, w)));
-        if (kind[rb] == F64_LAST) pr[r] = key_of_reg(r) <= lim ? pr[r] : 0.f;
-      }
-#pragma unroll
-      for (int ks = 0; ks < 2; ++ks) {
-        u32x4 pw;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) pw[j] = pack_bf16(pr[8 * ks + 2 * j], pr[8 * ks + 2 * j + 1]);
-        W.p[PAR][rb][ks] = as_bf16x8(pw);
-      }
-    }
-  }
-#pragma unroll
-  for (int rb = 0; rb < 2; ++rb) {
-    if (kind[rb] != F64_NONE) {
-#pragma unroll
-      for (int m = 0; m < 2 * DT; ++m) f64_mfma_o<true>(W.oacc[rb][m % DT], W.vf[m], W.p[PAR ^ 1][rb][m / DT]);
-    }
-  }
-  if (any_sig) {
-#pragma unroll
-    for (int m = 0; m < 2 * DT; ++m) {
-      const uint32_t a0 = W.voff[m % DT] + vaddr + (m / DT) * 16 * (D * 2);
-      W.vf[m] = join_tr(lds_read_tr16(a0), lds_read_tr16(a0 + 4 * (D * 2)));
-    }
-  }
-  f64_settle();
-}
-
-// ---- The steady-state step with a hand-pinned instruction order (both row blocks FULL).
+// ---- One pipeline step for chunk c (PAR = c & 1) with a hand-pinned instruction order.  For
+// both row blocks it issues S^T(c+1) and refills the K fragments with chunk c+2, evaluates the
+// sigmoid of chunk c, issues O^T += V(c-1)^T P^T(c-1) and refills the V fragments with chunk c.
 // Sub-slot K = 4m + ph, m = fragment index 0..KD-1:
 //   ph 0: S^T[0] MFMA with K fragment m          ph 1: O^T[0] MFMA with V fragment m
 //   ph 2: S^T[1] MFMA, refill K fragment m       ph 3: O^T[1] MFMA, refill V fragment m
@@ -161,9 +92,18 @@ __device__ __forceinline__ void f64_step(F64Wave<D>& W, int kind0, int kind1, ui
 // so a result is consumed two MFMAs later (closer than that the compiler separates dependent
 // asm statements with an s_nop of its own), and every run of transcendental instructions is
 // followed by an MFMA rather than by a plain vector instruction.
-template <int D, bool PRESCALE, int G, int Q>
+//
+// MASK: the steps at the end of a row block's key range (its diagonal / ragged last chunk, the
+// two steps that drain the pipeline, and steps a wave only sits through because another wave of
+// the workgroup still has keys to visit) run the same stream with a select per element after the
+// reciprocal: element r is kept if key_of_reg(r) <= thr, with thr a per-lane threshold -- the
+// distance to the lane's last visible key in the last chunk, "keep everything" before it, "keep
+// nothing" after it.  A select, not a product: S^T of a chunk past the range is computed from
+// whatever the ring holds, P^T must be exactly zero whatever that is.  The S^T MFMAs of a finished
+// row block are wasted work on a handful of steps per wave.
+template <int D, bool PRESCALE, bool MASK, int G, int Q>
 __device__ __forceinline__ void f64_sig_slice(const F64Wave<D>& W, const f32x16& s, float (&u)[8], uint32_t (&wp)[8],
-                                              float wv) {
+                                              float wv, int thr) {
   constexpr int e0 = 8 * (G & 1);      // first element of the group inside its row block
   constexpr int i0 = 4 * (Q & 1);      // this slice's half of the group
   if constexpr (Q < 2) {
@@ -192,14 +132,26 @@ __device__ __forceinline__ void f64_sig_slice(const F64Wave<D>& W, const f32x16&
     asm volatile("v_cvt_pk_bf16_f32 %0, %1, %2" : "=v"(wp[j]) : "v"(u[i0]), "v"(u[i0 + 1]));
     asm volatile("v_cvt_pk_bf16_f32 %0, %1, %2" : "=v"(wp[j + 1]) : "v"(u[i0 + 2]), "v"(u[i0 + 3]));
   }
+  if constexpr (MASK && (Q == 5 || Q == 6)) {
+    // selects of the half whose reciprocals were issued one sub-slot earlier (Q 5: first half,
+    // Q 6: second half; the pack of a half follows its selects by one sub-slot)
+    constexpr int m0 = 4 * (Q - 5);
+#pragma unroll
+    for (int i = m0; i < m0 + 4; ++i) {
+      uint64_t keep;
+      asm volatile("v_cmp_le_i32_e64 %0, %2, %3\n\tv_cndmask_b32_e64 %1, 0, %1, %0"
+                   : "=&s"(keep), "+v"(u[i]) : "n"(key_of_reg(e0 + i)), "v"(thr));
+    }
+  }
 }
 
 // DMA: one staging instruction (of the K tile three ahead or the V tile two ahead, see the
 // kernel) every DSTEP sub-slots: doff = this lane's offsets, dbase = the tile's first row,
 // dma_lds = this wave's first piece of the LDS tile.
-template <int D, bool FOLD, bool PRESCALE, int PAR, bool DMA, int K>
+template <int D, bool FOLD, bool PRESCALE, int PAR, bool DMA, bool MASK, int K>
 __device__ __forceinline__ void f64_subslots(F64Wave<D>& W, uint32_t kaddr, uint32_t vaddr, float (&u)[8],
                                              uint32_t (&wp0)[8], uint32_t (&wp1)[8], float wv0, float wv1,
+                                             int thr0, int thr1,
                                              const uint32_t (&doff)[4], const char* dbase, uint32_t dma_lds) {
   constexpr int KD = D / 16, DT = D / 32, NSUB = 4 * KD;
   if constexpr (K < NSUB) {
@@ -219,28 +171,30 @@ __device__ __forceinline__ void f64_subslots(F64Wave<D>& W, uint32_t kaddr, uint
     }
     // sigmoid of chunk c: group g = K / 8 (two per row block)
     static_assert(NSUB == 32, "four groups of eight sub-slots");
-    if constexpr (K < 16) f64_sig_slice<D, PRESCALE, K / 8, K % 8>(W, W.s[PAR][0], u, wp0, wv0);
-    else f64_sig_slice<D, PRESCALE, K / 8, K % 8>(W, W.s[PAR][1], u, wp1, wv1);
+    if constexpr (K < 16) f64_sig_slice<D, PRESCALE, MASK, K / 8, K % 8>(W, W.s[PAR][0], u, wp0, wv0, thr0);
+    else f64_sig_slice<D, PRESCALE, MASK, K / 8, K % 8>(W, W.s[PAR][1], u, wp1, wv1, thr1);
     if constexpr (DMA) {
       constexpr int NI = 4, DSTEP = NSUB / NI;
       if constexpr (K % DSTEP == 2) DmaStager<D, 64, 4, false>::template issue_off<K / DSTEP>(doff[K / DSTEP], dbase, dma_lds);
     }
-    f64_subslots<D, FOLD, PRESCALE, PAR, DMA, K + 1>(W, kaddr, vaddr, u, wp0, wp1, wv0, wv1, doff, dbase, dma_lds);
+    f64_subslots<D, FOLD, PRESCALE, PAR, DMA, MASK, K + 1>(W, kaddr, vaddr, u, wp0, wp1, wv0, wv1, thr0, thr1, doff, dbase,
+                                                            dma_lds);
   }
 }
 
 // kaddr / vaddr: compile-time-constant byte offsets of the K chunk c+2 / V chunk c relative to
-// W.koff / W.voff.
-template <int D, bool FOLD, bool PRESCALE, int PAR, bool DMA>
+// W.koff / W.voff.  thr0 / thr1 (MASK only): per-lane thresholds of the two row blocks.
+template <int D, bool FOLD, bool PRESCALE, int PAR, bool DMA, bool MASK = false>
 __device__ __forceinline__ void f64_step_pinned(F64Wave<D>& W, uint32_t kaddr, uint32_t vaddr, int jc,
-                                                const uint32_t (&doff)[4], const char* dbase, uint32_t dma_lds) {
+                                                const uint32_t (&doff)[4], const char* dbase, uint32_t dma_lds,
+                                                int thr0 = 0, int thr1 = 0) {
   static_assert(D == 128, "the pinned 64-row step is written for head dimension 128");
   float u[8];
   uint32_t wp0[8], wp1[8];
   const float dist0 = (float)(W.qi0 - (jc + 8 * W.h));
   const float wv0 = FOLD ? __builtin_fmaf(W.sl2, dist0, W.nbias) : W.nbias;
   const float wv1 = FOLD ? __builtin_fmaf(W.sl2, dist0 + 32.0f, W.nbias) : W.nbias;
-  f64_subslots<D, FOLD, PRESCALE, PAR, DMA, 0>(W, kaddr, vaddr, u, wp0, wp1, wv0, wv1, doff, dbase, dma_lds);
+  f64_subslots<D, FOLD, PRESCALE, PAR, DMA, MASK, 0>(W, kaddr, vaddr, u, wp0, wp1, wv0, wv1, thr0, thr1, doff, dbase, dma_lds);
   W.p[PAR][0][0] = as_bf16x8(u32x4{wp0[0], wp0[1], wp0[2], wp0[3]});
   W.p[PAR][0][1] = as_bf16x8(u32x4{wp0[4], wp0[5], wp0[6], wp0[7]});
   W.p[PAR][1][0] = as_bf16x8(u32x4{wp1[0], wp1[1], wp1[2], wp1[3]});
@@ -308,25 +262,64 @@ attn_fwd64_kernel(const FwdParams p) {
   const int q_wave0 = qb * BR + wave * 64;  // first query row of this wave
   const int qi0 = q_wave0 + l32;            // this lane's query row in row block 0
 
-  F64Wave<D> W;
-  // Q fragments: B operand of S^T = K Q^T, column = query, k = d
+  // keys this workgroup must visit, and chunks each row block of this wave must visit
+  const int q_hi = (qb * BR + BR < N ? qb * BR + BR : N) - 1;  // last valid query row of the block
+  const int Nk = p.Nk > 0 ? p.Nk : N;  // keys (N counts the queries)
+  const int kv_len = CAUSAL ? (q_hi + 1) : Nk;
+  const int n_tiles = (kv_len + BC - 1) / BC;
+  int cw[2];
 #pragma unroll
   for (int rb = 0; rb < 2; ++rb) {
-    const int qi = qi0 + 32 * rb, qi_ld = qi < N ? qi : N - 1;
+    const int q0 = q_wave0 + 32 * rb;
+    int kv = Nk;
+    if (CAUSAL) kv = q0 + 32 < N ? q0 + 32 : N;
+    cw[rb] = __builtin_amdgcn_readfirstlane(q0 < N ? (kv + 31) / 32 : 0);  // chunks 0..cw-1; row blocks past the end idle
+  }
+
+  // (staged first of all: the ring loads do not depend on Q and their latency overlaps the Q loads)
+  // LDS rings as in the 32-row kernel: K tile t in K slot t%3, V tile t in V slot t%3.  During
+  // tile t the loads of K(t+3) (into the slot of K(t), last read during tile t-1) and V(t+2)
+  // (into the slot of V(t-1)) are issued; they must have landed by the end of tile t+1.
+  DmaStager<D, BC, NW, false> kst;
+  DmaStager<D, BC, NW, true> vst;
+  constexpr int NIK = DmaStager<D, BC, NW, false>::NI, NIV = DmaStager<D, BC, NW, true>::NI;
+  const int uwave = __builtin_amdgcn_readfirstlane(wave);
+  kst.init(kbase, p.k.ss, Nk, uwave, lane);
+  vst.init(vbase, p.v.ss, Nk, uwave, lane);
+  kst.issue(kring, Nk, uwave, lane);
+  vst.issue(vring, Nk, uwave, lane);
+  if (n_tiles > 1) {
+    kst.issue(kring + TILE, Nk, uwave, lane);
+    vst.issue(vring + TILE, Nk, uwave, lane);
+  }
+  if (n_tiles > 2) kst.issue(kring + 2 * TILE, Nk, uwave, lane);
+  F64Wave<D> W;
+  // Q fragments: B operand of S^T = K Q^T, column = query, k = d.  All sixteen loads are issued
+  // before the first one is consumed (the fragments then move into their AGPRs one by one).
+  {
+    u32x4 raw[2][KD];
 #pragma unroll
-    for (int kk = 0; kk < KD; ++kk) {
-      bf16x8 f = as_bf16x8(*(const u32x4*)(qbase + (int64_t)qi_ld * p.q.ss + 16 * kk + 8 * h));
-      if constexpr (PRESCALE) {
-        u32x4 w;
+    for (int rb = 0; rb < 2; ++rb) {
+      const int qi = qi0 + 32 * rb, qi_ld = qi < N ? qi : N - 1;
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
-          w[j] = pack_bf16((float)f[2 * j] * p.nscale_log2, (float)f[2 * j + 1] * p.nscale_log2);
-        f = as_bf16x8(w);
-      }
-      W.qf[rb][kk] = f;
-      // into its AGPRs now: sixteen fragments converted at once would not fit the VGPR file
-      asm volatile("" : "+a"(W.qf[rb][kk]) : : "memory");
+      for (int kk = 0; kk < KD; ++kk) raw[rb][kk] = *(const u32x4*)(qbase + (int64_t)qi_ld * p.q.ss + 16 * kk + 8 * h);
     }
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+      for (int kk = 0; kk < KD; ++kk) {
+        bf16x8 f = as_bf16x8(raw[rb][kk]);
+        if constexpr (PRESCALE) {
+          u32x4 w;
+#pragma unroll
+          for (int j = 0; j < 4; ++j)
+            w[j] = pack_bf16((float)f[2 * j] * p.nscale_log2, (float)f[2 * j + 1] * p.nscale_log2);
+          f = as_bf16x8(w);
+        }
+        W.qf[rb][kk] = f;
+        // into its AGPRs now: sixteen converted fragments at once would not fit the VGPR file
+        asm volatile("" : "+a"(W.qf[rb][kk]) : : "memory");
+      }
   }
 #pragma unroll
   for (int rb = 0; rb < 2; ++rb)
@@ -364,36 +357,6 @@ attn_fwd64_kernel(const FwdParams p) {
     for (int m = 0; m < 2 * DT; ++m) W.vf[m] = z;  // step 0 multiplies these by P^T(-1) = 0
   }
 
-  // keys this workgroup must visit, and chunks each row block of this wave must visit
-  const int q_hi = (qb * BR + BR < N ? qb * BR + BR : N) - 1;  // last valid query row of the block
-  const int Nk = p.Nk > 0 ? p.Nk : N;  // keys (N counts the queries)
-  const int kv_len = CAUSAL ? (q_hi + 1) : Nk;
-  const int n_tiles = (kv_len + BC - 1) / BC;
-  int cw[2];
-#pragma unroll
-  for (int rb = 0; rb < 2; ++rb) {
-    const int q0 = q_wave0 + 32 * rb;
-    int kv = Nk;
-    if (CAUSAL) kv = q0 + 32 < N ? q0 + 32 : N;
-    cw[rb] = __builtin_amdgcn_readfirstlane(q0 < N ? (kv + 31) / 32 : 0);  // chunks 0..cw-1; row blocks past the end idle
-  }
-
-  // LDS rings as in the 32-row kernel: K tile t in K slot t%3, V tile t in V slot t%3.  During
-  // tile t the loads of K(t+3) (into the slot of K(t), last read during tile t-1) and V(t+2)
-  // (into the slot of V(t-1)) are issued; they must have landed by the end of tile t+1.
-  DmaStager<D, BC, NW, false> kst;
-  DmaStager<D, BC, NW, true> vst;
-  constexpr int NIK = DmaStager<D, BC, NW, false>::NI, NIV = DmaStager<D, BC, NW, true>::NI;
-  const int uwave = __builtin_amdgcn_readfirstlane(wave);
-  kst.init(kbase, p.k.ss, Nk, uwave, lane);
-  vst.init(vbase, p.v.ss, Nk, uwave, lane);
-  kst.issue(kring, Nk, uwave, lane);
-  vst.issue(vring, Nk, uwave, lane);
-  if (n_tiles > 1) {
-    kst.issue(kring + TILE, Nk, uwave, lane);
-    vst.issue(vring + TILE, Nk, uwave, lane);
-  }
-  if (n_tiles > 2) kst.issue(kring + 2 * TILE, Nk, uwave, lane);
   SATTN_WAIT_VMCNT(0);  // prologue tiles landed; the Q fragments are in registers
   __syncthreads();
 
@@ -439,14 +402,7 @@ attn_fwd64_kernel(const FwdParams p) {
         f64_tile_pinned<D, FOLD, PRESCALE, 1>(W, t + 1, kst, vst, kdoff, vdoff, kring_wave, vring_wave);
         f64_tile_pinned<D, FOLD, PRESCALE, 2>(W, t + 2, kst, vst, kdoff, vdoff, kring_wave, vring_wave);
       }
-      // up to two more steady tiles: ring positions 0 and 1
-      if (t < t_steady) {
-        f64_tile_pinned<D, FOLD, PRESCALE, 0>(W, t, kst, vst, kdoff, vdoff, kring_wave, vring_wave);
-        if (++t < t_steady) {
-          f64_tile_pinned<D, FOLD, PRESCALE, 1>(W, t, kst, vst, kdoff, vdoff, kring_wave, vring_wave);
-          ++t;
-        }
-      }
+      // (up to two more full tiles are left to the loop below)
       f64_settle();  // the compiler does not know the statements above are MFMAs
     }
   }
@@ -468,21 +424,36 @@ attn_fwd64_kernel(const FwdParams p) {
     for (int dt = 0; dt < DT; ++dt) W.voff[dt] += vadv;
     kslot = kslot == 2 ? 0 : kslot + 1;
   };
+  // The remaining steps of this wave: the last chunk of a row block (mask), the drain of its
+  // pipeline, steps it only sits through, and full steps whose staged tiles reach past the
+  // tensor's last full tile.  Per row block: FULL while c + 1 < cw, LAST (masked) at c + 1 == cw,
+  // TAIL at c == cw (only the O^T update counts), nothing afterwards.
+  const uint32_t nodma[4] = {0, 0, 0, 0};
+  auto run_step = [&](auto par_tag, int c) {
+    constexpr int PAR = decltype(par_tag)::value;
+    int thr[2];
+    bool live = false;
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb) {
+      const int n = cw[rb];
+      const bool full = c + 1 < n, last = c + 1 == n, tail = c == n && n > 0;
+      live = live || full || last || tail;
+      const int jl = 32 * c + 8 * h;           // key held by register 0 of this lane half
+      int lim = Nk - 1 - jl;                    // LAST: registers whose key offset exceeds lim are masked
+      if (CAUSAL) lim = lim < qi0 + 32 * rb - jl ? lim : qi0 + 32 * rb - jl;
+      thr[rb] = full ? 1000 : last ? lim : -1000;
+    }
+    if (!live) return;
+    f64_step_pinned<D, FOLD, PRESCALE, PAR, false, true>(W, PAR * CHUNK, PAR * CHUNK, 32 * c, nodma, nullptr, 0, thr[0], thr[1]);
+    f64_settle();  // compiler-generated code follows: let the last MFMAs retire first
+  };
   for (; t < n_tiles; ++t) {
     const bool k_more = t + 3 < n_tiles, v_more = t + 2 < n_tiles;
     const int vslot2 = kslot == 0 ? 2 : kslot - 1;  // (t+2)%3
     if (k_more) kst.issue(kring + kslot * TILE, Nk, uwave, lane);
     if (v_more) vst.issue(vring + vslot2 * TILE, Nk, uwave, lane);
-    {
-      const int c = 2 * t;
-      auto kind = [&](int n) { return c + 1 < n ? F64_FULL : c + 1 == n ? F64_LAST : c == n ? F64_TAIL : F64_NONE; };
-      f64_step<D, FOLD, PRESCALE, 0>(W, kind(cw[0]), kind(cw[1]), 0, 0, 32 * c, Nk, CAUSAL);
-    }
-    {
-      const int c = 2 * t + 1;
-      auto kind = [&](int n) { return c + 1 < n ? F64_FULL : c + 1 == n ? F64_LAST : c == n ? F64_TAIL : F64_NONE; };
-      f64_step<D, FOLD, PRESCALE, 1>(W, kind(cw[0]), kind(cw[1]), CHUNK, CHUNK, 32 * c, Nk, CAUSAL);
-    }
+    run_step(std::integral_constant<int, 0>{}, 2 * t);
+    run_step(std::integral_constant<int, 1>{}, 2 * t + 1);
     rotate();
     if (k_more) SATTN_WAIT_VMCNT(NIK + NIV);
     else if (v_more) SATTN_WAIT_VMCNT(NIV);
@@ -490,18 +461,20 @@ attn_fwd64_kernel(const FwdParams p) {
     __syncthreads();
   }
   // flush: O^T update of the last chunk when it fell on the last step of the loop
-  {
-    const int c = 2 * n_tiles;
-    const int k0 = (c == cw[0] && cw[0] > 0) ? F64_TAIL : F64_NONE, k1 = (c == cw[1] && cw[1] > 0) ? F64_TAIL : F64_NONE;
-    if (k0 != F64_NONE || k1 != F64_NONE) f64_step<D, FOLD, PRESCALE, 0>(W, k0, k1, 0, 0, 32 * c, Nk, CAUSAL);
-  }
+  run_step(std::integral_constant<int, 0>{}, 2 * n_tiles);
 
-  // ---- store O (bf16): register 4g+t of tile dt is O[qi][32dt + 8g + 4h + t]
+  // ---- store O (bf16).  Register 4g+t of tile dt is O[qi][32dt + 8g + 4h + t]: a lane holds 4
+  // consecutive features of ITS row, so storing from the registers would scatter 8-byte pieces
+  // over 64 rows per instruction.  The wave instead transposes through its own 17 KB of the (now
+  // free) ring -- rows padded to 272 bytes, which spreads the 32 rows of a write over the banks --
+  // and stores whole 256-byte rows, 16 bytes per lane, four rows per instruction.
+  {
+    constexpr int ROWB = D * 2 + 16;  // padded row
+    // every wave is past its last fragment read of the ring, but other waves may not be
+    __syncthreads();
+    const uint32_t obuf = lds0 + wave * (64 * ROWB);
 #pragma unroll
-  for (int rb = 0; rb < 2; ++rb) {
-    const int qi = qi0 + 32 * rb;
-    if (qi < N) {
-      __bf16* orow = obase + (int64_t)qi * p.o.ss;
+    for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
       for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
@@ -509,8 +482,16 @@ attn_fwd64_kernel(const FwdParams p) {
           u32x2 w;
           w[0] = pack_bf16(W.oacc[rb][dt][4 * g], W.oacc[rb][dt][4 * g + 1]);
           w[1] = pack_bf16(W.oacc[rb][dt][4 * g + 2], W.oacc[rb][dt][4 * g + 3]);
-          *(u32x2*)(orow + 32 * dt + 8 * g + 4 * h) = w;
+          *(SATTN_LDS(u32x2)*)(uintptr_t)(obuf + (32 * rb + l32) * ROWB + (32 * dt + 8 * g + 4 * h) * 2) = w;
         }
+    // the wave reads back what its own lanes wrote: only the LDS counter has to drain
+    __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
+    const int r4 = lane >> 4, c16 = lane & 15;  // row within a group of four, 16-byte chunk of the row
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int row = 4 * i + r4, qi = q_wave0 + row;
+      const u32x4 v4 = lds_read_b128(obuf + row * ROWB + c16 * 16);
+      if (qi < N) *(u32x4*)(obase + (int64_t)qi * p.o.ss + c16 * 8) = v4;
     }
   }
   clock_probe_end(p.clock, clk);
