@@ -114,6 +114,20 @@ struct DmaStagerX {
     }
   }
   __device__ __forceinline__ void advance() { base += tile_bytes; j0 += BC; }
+  // Advance unless the tile after the next one does not lie wholly inside the tensor: the
+  // stager then stays where it is and a further issue_one() stages the same tile again.
+  __device__ __forceinline__ void advance_inside(int N) {
+    if (j0 + 2 * BC <= N) advance();
+  }
+  // Before a run of issue_one() calls on a tensor that ends on a tile boundary: a stager that
+  // has already staged the last tile steps back onto it.
+  __device__ __forceinline__ void step_back_inside(int N) {
+    if (j0 + BC > N) {
+      const int back = (j0 + BC - N) / BC;
+      base -= (int64_t)back * tile_bytes;
+      j0 -= back * BC;
+    }
+  }
   // Stage the whole next tile.  Rows past the end re-read row N-1.
   __device__ __forceinline__ void issue(uint32_t lds, int N, int wave, int lane) {
     if (j0 + BC <= N) {
@@ -385,7 +399,7 @@ __device__ __forceinline__ void bsig_ops(BwdWave<D, MODE>& W, const f32x16& s, c
   }
 }
 
-template <int D, int MODE, bool ALIBI, int PAR, bool DMA, bool MASK, bool FOLD, int K>
+template <int D, int MODE, bool ALIBI, int PAR, bool DMA, bool MASK, bool FOLD, bool GUARD, int K>
 __device__ __forceinline__ void bwd_full_subslots(BwdWave<D, MODE>& W, uint32_t trimm, const uint32_t* nextrow,
                                                   uint32_t nextimm, float (&u)[16], float (&v)[16], uint32_t (&wp)[8],
                                                   uint32_t (&wd)[8], uint64_t (&km)[16], float nbias_v, float sl2_v,
@@ -403,14 +417,14 @@ __device__ __forceinline__ void bwd_full_subslots(BwdWave<D, MODE>& W, uint32_t 
       if constexpr ((K & 1) == 0) {
         // S-type product from tensor 1, then fetch the transposed tensor-1 fragment kk
         if constexpr (kk == 0 && FOLD) b_mfma_vinit(W.s[PAR], W.F[K], W.x1[kk], W.cinit);
-        else if constexpr (kk == 0) b_mfma_v0<false>(W.s[PAR], W.F[K], W.x1[kk]);
-        else b_mfma_v<false>(W.s[PAR], W.F[K], W.x1[kk]);
+        else if constexpr (kk == 0) b_mfma_v0<GUARD>(W.s[PAR], W.F[K], W.x1[kk]);
+        else b_mfma_v<GUARD>(W.s[PAR], W.F[K], W.x1[kk]);
         const uint32_t off = trimm + (kk / DT) * 16 * (D * 2);
         W.F[K] = join_tr(lds_read_tr16(W.tr[kk % DT][0] + off), lds_read_tr16(W.tr[kk % DT][1] + off));
       } else {
         // dP-type product from tensor 2
-        if constexpr (kk == 0) b_mfma_v0<false>(W.dp[PAR], W.F[K], W.x2[kk]);
-        else b_mfma_v<false>(W.dp[PAR], W.F[K], W.x2[kk]);
+        if constexpr (kk == 0) b_mfma_v0<GUARD>(W.dp[PAR], W.F[K], W.x2[kk]);
+        else b_mfma_v<GUARD>(W.dp[PAR], W.F[K], W.x2[kk]);
         if constexpr (MODE == BWD_DKDV) {
           const uint32_t off = trimm + (kk / DT) * 16 * (D * 2) + T2OFF;
           W.F[K] = join_tr(lds_read_tr16(W.tr[kk % DT][0] + off), lds_read_tr16(W.tr[kk % DT][1] + off));
@@ -424,15 +438,15 @@ __device__ __forceinline__ void bwd_full_subslots(BwdWave<D, MODE>& W, uint32_t 
       if constexpr (MODE == BWD_DKDV) {
         constexpr int j = KB / 2;
         if constexpr ((KB & 1) == 0) {
-          b_mfma_a<false>(W.acc0[j % DT], W.F[2 * j], W.dsb[PAR][j / DT]);      // dK^T += Q^T dS
+          b_mfma_a<GUARD>(W.acc0[j % DT], W.F[2 * j], W.dsb[PAR][j / DT]);      // dK^T += Q^T dS
           W.F[2 * j] = as_bf16x8(lds_read_b128(nextrow[j] + nextimm));
         } else {
-          b_mfma_a<false>(W.acc1[j % DT], W.F[2 * j + 1], W.pb[PAR][j / DT]);   // dV^T += dO^T P
+          b_mfma_a<GUARD>(W.acc1[j % DT], W.F[2 * j + 1], W.pb[PAR][j / DT]);   // dV^T += dO^T P
           W.F[2 * j + 1] = as_bf16x8(lds_read_b128(nextrow[j] + nextimm + T2OFF));
         }
       } else {
         constexpr int j = KB;
-        b_mfma_a<false>(W.acc0[j % DT], W.F[2 * j], W.dsb[PAR][j / DT]);        // dQ^T += K^T dS^T
+        b_mfma_a<GUARD>(W.acc0[j % DT], W.F[2 * j], W.dsb[PAR][j / DT]);        // dQ^T += K^T dS^T
         W.F[2 * j] = as_bf16x8(lds_read_b128(nextrow[j] + nextimm));
       }
     }
@@ -447,15 +461,17 @@ __device__ __forceinline__ void bwd_full_subslots(BwdWave<D, MODE>& W, uint32_t 
         else st2.template issue_one<n - NI>(dma_lds + 64 * D * 2, uwave);
       }
     }
-    bwd_full_subslots<D, MODE, ALIBI, PAR, DMA, MASK, FOLD, K + 1>(W, trimm, nextrow, nextimm, u, v, wp, wd, km, nbias_v, sl2_v,
+    bwd_full_subslots<D, MODE, ALIBI, PAR, DMA, MASK, FOLD, GUARD, K + 1>(W, trimm, nextrow, nextimm, u, v, wp, wd, km, nbias_v, sl2_v,
                                                              dist0, dstep, thr, st1, st2, dma_lds, uwave);
   }
 }
 
 // thr (MASK only): elements with key_of_reg(e) >= thr (DKDV) / <= thr (DQ) are kept.
+// GUARD puts the two wait states in front of every MFMA (for kernels whose register pressure
+// makes the compiler park streamed fragments in AGPRs and copy them back right before use).
 // SETTLE = false leaves the wait for the last MFMAs to the caller (a loop of pinned steps only,
 // which waits once after the loop).
-template <int D, int MODE, bool ALIBI, bool FOLD, int PAR, bool DMA, bool MASK = false, bool SETTLE = true>
+template <int D, int MODE, bool ALIBI, bool FOLD, int PAR, bool DMA, bool MASK = false, bool SETTLE = true, bool GUARD = false>
 __device__ __forceinline__ void bwd_step_full_pinned(BwdWave<D, MODE>& W, uint32_t trimm, const uint32_t* nextrow,
                                                      uint32_t nextimm, int cs, const DmaStagerX<D, 4>& st1,
                                                      const DmaStagerX<D, 4>& st2, uint32_t dma_lds, int uwave,
@@ -468,11 +484,11 @@ __device__ __forceinline__ void bwd_step_full_pinned(BwdWave<D, MODE>& W, uint32
   const float dist0 = MODE == BWD_DKDV ? (float)(bl - W.ai) : (float)(W.ai - bl);
   const float dstep = MODE == BWD_DKDV ? 1.0f : -1.0f;
   if constexpr (FOLD)  // the per-element arithmetic is the one without ALiBi, on a per-step bias
-    bwd_full_subslots<D, MODE, false, PAR, DMA, MASK, true, 0>(W, trimm, nextrow, nextimm, u, v, wp, wd, km,
+    bwd_full_subslots<D, MODE, false, PAR, DMA, MASK, true, GUARD, 0>(W, trimm, nextrow, nextimm, u, v, wp, wd, km,
                                                                __builtin_fmaf(W.sl2, dist0, W.nbias), W.sl2, dist0, dstep,
                                                                thr, st1, st2, dma_lds, uwave);
   else
-    bwd_full_subslots<D, MODE, ALIBI, PAR, DMA, MASK, false, 0>(W, trimm, nextrow, nextimm, u, v, wp, wd, km, W.nbias, W.sl2,
+    bwd_full_subslots<D, MODE, ALIBI, PAR, DMA, MASK, false, GUARD, 0>(W, trimm, nextrow, nextimm, u, v, wp, wd, km, W.nbias, W.sl2,
                                                                 dist0, dstep, thr, st1, st2, dma_lds, uwave);
   // The compiler does not know that the asm statements above are MFMAs: let the last ones
   // retire before it may touch their accumulators (copies at the join with the other path).
@@ -543,11 +559,6 @@ attn_bwd_kernel(const BwdParams p) {
 
   BwdWave<D, MODE> W;
 #pragma unroll
-  for (int kk = 0; kk < KD; ++kk) {
-    W.x1[kk] = as_bf16x8(*(const u32x4*)(x1b + (int64_t)ai_ld * x1s + 16 * kk + 8 * h));
-    W.x2[kk] = as_bf16x8(*(const u32x4*)(x2b + (int64_t)ai_ld * x2s + 16 * kk + 8 * h));
-  }
-#pragma unroll
   for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
@@ -585,6 +596,15 @@ attn_bwd_kernel(const BwdParams p) {
   const int t_lo = wg_lo / 2, t_hi = (wg_hi + 2) / 2;  // the last step is wg_hi + 2
   const int t_data_hi = wg_hi / 2;                      // last tile that has to be staged
 
+  auto load_stationary = [&]() {
+#pragma unroll
+    for (int kk = 0; kk < KD; ++kk) {
+      W.x1[kk] = as_bf16x8(*(const u32x4*)(x1b + (int64_t)ai_ld * x1s + 16 * kk + 8 * h));
+      W.x2[kk] = as_bf16x8(*(const u32x4*)(x2b + (int64_t)ai_ld * x2s + 16 * kk + 8 * h));
+    }
+  };
+  // (with a loop over query heads the fragments are loaded once, ahead of the loop)
+  if constexpr (GROUPS) load_stationary();
   for (int hq = hq0; hq < hq0 + n_hq; ++hq) {  // one pass of the pipeline per query head
   const __bf16* y1b = MODE == BWD_DKDV ? qhead(hq) : kbase;
   const __bf16* y2b = MODE == BWD_DKDV ? dohead(hq) : vbase;
@@ -624,26 +644,31 @@ attn_bwd_kernel(const BwdParams p) {
   }
 
   DmaStagerX<D, NW> st1, st2;
+  constexpr int NI_TILE = DmaStagerX<D, NW>::NI;  // staging instructions per wave, tensor and tile
   st1.init(y1b, y1s, Nt, t_lo * BC, uwave, lane);
   st2.init(y2b, y2s, Nt, t_lo * BC, uwave, lane);
-  // prologue: tiles t_lo and t_lo+1, and tile t_lo-1 (tile 0 again for t_lo = 0): the pinned
-  // steps run their second-product stage from the first step on (with zero P / dS until the
-  // pipeline has filled), so the slot it reads must hold finite data
+  // Prologue.  The workgroup's first loads share the compute unit's one path from memory, so
+  // they are kept few and ordered by need: tile t_lo, the stationary fragments, then tile
+  // t_lo+1, which may land while the first tile is computed (every tile waits for the next
+  // one before its barrier anyway).  The pinned steps run their second-product stage from the
+  // first step on, with zero P / dS until the pipeline has filled, so the slot of tile t_lo-1
+  // must hold finite data: zeros, written here.
   {
-    DmaStagerX<D, NW> p1, p2;
-    const int tp = t_lo > 0 ? t_lo - 1 : 0;
-    p1.init(y1b, y1s, Nt, tp * BC, uwave, lane);
-    p2.init(y2b, y2s, Nt, tp * BC, uwave, lane);
-    p1.issue(lds0 + ((t_lo + NSLOT - 1) % NSLOT) * SLOT, Nt, uwave, lane);
-    p2.issue(lds0 + ((t_lo + NSLOT - 1) % NSLOT) * SLOT + TILE, Nt, uwave, lane);
+    const uint32_t zslot = lds0 + ((t_lo + NSLOT - 1) % NSLOT) * SLOT + tid * 16;
+#pragma unroll
+    for (int i = 0; i < SLOT / (256 * 16); ++i) lds_write_b128(zslot + i * (256 * 16), u32x4{0, 0, 0, 0});
   }
   st1.issue(lds0 + (t_lo % NSLOT) * SLOT, Nt, uwave, lane);
   st2.issue(lds0 + (t_lo % NSLOT) * SLOT + TILE, Nt, uwave, lane);
+  if constexpr (!GROUPS) load_stationary();
   if (t_lo + 1 <= t_data_hi) {
     st1.issue(lds0 + ((t_lo + 1) % NSLOT) * SLOT, Nt, uwave, lane);
     st2.issue(lds0 + ((t_lo + 1) % NSLOT) * SLOT + TILE, Nt, uwave, lane);
+    // all but the newest 2 NI loads: tile t_lo has landed, the stationary fragments are in registers
+    SATTN_WAIT_VMCNT(2 * NI_TILE);
+  } else {
+    SATTN_WAIT_VMCNT(0);
   }
-  __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): prologue tiles landed, stationary fragments in registers
   __syncthreads();
   // rows of chunk 2*t_lo for the first step
 #pragma unroll
@@ -689,7 +714,12 @@ attn_bwd_kernel(const BwdParams p) {
   // Every variant has its one barrier per tile at the same place, so waves of a workgroup
   // may be in different loops.
   const int t_s0 = (SOFTMAX || !PIN) ? t_hi + 1 : (c_lo_s + 3) / 2;          // first tile with 2t >= c_lo+2
-  const int t_s1a = (c_hi_s + 1) / 2 - 1, t_s1b = Nt / BC - 3;      // last tile with 2t+1 <= c_hi / with tile t+2 inside the tensor
+  // last tile with 2t+1 <= c_hi / last tile whose staging needs no clamping.  The steady loop
+  // stages tile t+2 during tile t without looking at the tensor's end: when the tensor ends on
+  // a tile boundary the stager stops at the last tile and tiles t+2 past it are that tile
+  // again, written to a ring slot nobody reads; a ragged last tile needs the clamped form,
+  // so the loop ends before it.
+  const int t_s1a = (c_hi_s + 1) / 2 - 1, t_s1b = Nt % BC == 0 ? t_s1a : Nt / BC - 3;
   const int t_s1 = (SOFTMAX || !PIN) ? t_lo - 1 : (t_s1a < t_s1b ? t_s1a : t_s1b);
   auto rotate = [&](int t) {
     // rotate the per-lane addresses by one ring slot
@@ -717,7 +747,7 @@ attn_bwd_kernel(const BwdParams p) {
         constexpr bool kPinned = PIN && !SOFTMAX;  // the other kernels do not carry the pinned code at all
         if (kPinned && lane_flag(pin_s)) {
           if constexpr (kPinned)
-            bwd_step_full_pinned<D, MODE, ALIBI, FOLD, 0, false, true>(W, 0, W.row0, CHUNK, 32 * (s - 1), st1, st2, 0, uwave, thr);
+            bwd_step_full_pinned<D, MODE, ALIBI, FOLD, 0, false, true, true, GROUPS>(W, 0, W.row0, CHUNK, 32 * (s - 1), st1, st2, 0, uwave, thr);
         } else
           bwd_step<D, MODE, CAUSAL, ALIBI, SOFTMAX, 0>(W, lane_flag(doA_s), lane_flag(doS_s), lane_flag(doB_s),
                                                        lane_flag(mask_s), 0, W.row0, CHUNK, 32 * (s - 1), Nt, stat_l, stat_d);
@@ -743,7 +773,7 @@ attn_bwd_kernel(const BwdParams p) {
         constexpr bool kPinned = PIN && !SOFTMAX;  // the other kernels do not carry the pinned code at all
         if (kPinned && lane_flag(pin_s)) {
           if constexpr (kPinned)
-            bwd_step_full_pinned<D, MODE, ALIBI, FOLD, 1, false, true>(W, CHUNK, W.row1, 0, 32 * (s - 1), st1, st2, 0, uwave, thr);
+            bwd_step_full_pinned<D, MODE, ALIBI, FOLD, 1, false, true, true, GROUPS>(W, CHUNK, W.row1, 0, 32 * (s - 1), st1, st2, 0, uwave, thr);
         } else
           bwd_step<D, MODE, CAUSAL, ALIBI, SOFTMAX, 1>(W, lane_flag(doA_s), lane_flag(doS_s), lane_flag(doB_s),
                                                        lane_flag(mask_s), CHUNK, W.row1, 0, 32 * (s - 1), Nt, stat_l, stat_d);
@@ -752,14 +782,20 @@ attn_bwd_kernel(const BwdParams p) {
     }
     if constexpr (PIN && !SOFTMAX) if (phase == 0) {
       const bool any_steady = t <= t_s1;
+      // (a ragged tensor's steady loop ends early enough that its stagers never reach the end)
+      const int n_sat = Nt % BC == 0 ? Nt : 0x7fffff00;
+      if (any_steady) {
+        st1.step_back_inside(n_sat);
+        st2.step_back_inside(n_sat);
+      }
       for (; t <= t_s1; ++t) {
         bwd_step_full_pinned<D, MODE, ALIBI, FOLD, 0, false, false, false>(W, 0, W.row0, CHUNK, 32 * (2 * t - 1), st1, st2, 0, uwave);
         __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): tile t+1 has landed
         __builtin_amdgcn_s_barrier();
         bwd_step_full_pinned<D, MODE, ALIBI, FOLD, 1, true, false, false>(W, CHUNK, W.row1, 0, 32 * (2 * t), st1, st2,
                                                                     lds0 + ((t + 2) % NSLOT) * SLOT, uwave);
-        st1.advance();
-        st2.advance();
+        st1.advance_inside(n_sat);
+        st2.advance_inside(n_sat);
         rotate(t);
       }
       if (any_steady) mfma_settle();  // once for the whole loop of pinned steps
@@ -777,30 +813,18 @@ attn_bwd_kernel(const BwdParams p) {
     rs += __shfl_xor(rs, 32);
     if (h == 0 && ai < Ns) p.db_rows[b * p.db_sb + hq0 * p.db_sh + tok0 + ai] = rs;
   }
-  if (ai < Ns) {
-    const float sc = p.inv_sqrt_d;  // dQ and dK carry the 1/sqrt(d) of the logits
-    __bf16* o0 = (MODE == BWD_DKDV ? (__bf16*)p.dk.ptr + b * p.dk.sb + hkv * p.dk.sh + (tok0 + ai) * p.dk.ss
-                                   : (__bf16*)p.dq.ptr + b * p.dq.sb + hq0 * p.dq.sh + (tok0 + ai) * p.dq.ss);
-#pragma unroll
-    for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        u32x2 w;
-        w[0] = pack_bf16(W.acc0[dt][4 * g] * sc, W.acc0[dt][4 * g + 1] * sc);
-        w[1] = pack_bf16(W.acc0[dt][4 * g + 2] * sc, W.acc0[dt][4 * g + 3] * sc);
-        *(u32x2*)(o0 + 32 * dt + 8 * g + 4 * h) = w;
-      }
-    if (MODE == BWD_DKDV) {
-      __bf16* o1 = (__bf16*)p.dv.ptr + b * p.dv.sb + hkv * p.dv.sh + (tok0 + ai) * p.dv.ss;
-#pragma unroll
-      for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          u32x2 w;
-          w[0] = pack_bf16(W.acc1[dt][4 * g], W.acc1[dt][4 * g + 1]);
-          w[1] = pack_bf16(W.acc1[dt][4 * g + 2], W.acc1[dt][4 * g + 3]);
-          *(u32x2*)(o1 + 32 * dt + 8 * g + 4 * h) = w;
-        }
+  // Outputs as whole rows, transposed through the ring (free once every wave has left the loop).
+  __syncthreads();
+  {
+    const int rows_valid = Ns - a_wave0;  // <= 0 for a wave past the end
+    const uint32_t obuf = lds0 + wave * (2 * RowStore<D>::BYTES);
+    __bf16* o0 = (MODE == BWD_DKDV ? (__bf16*)p.dk.ptr + b * p.dk.sb + hkv * p.dk.sh + (tok0 + a_wave0) * p.dk.ss
+                                   : (__bf16*)p.dq.ptr + b * p.dq.sb + hq0 * p.dq.sh + (tok0 + a_wave0) * p.dq.ss);
+    // dQ and dK carry the 1/sqrt(d) of the logits
+    RowStore<D>::run(W.acc0, p.inv_sqrt_d, obuf, lane, o0, MODE == BWD_DKDV ? p.dk.ss : p.dq.ss, rows_valid);
+    if constexpr (MODE == BWD_DKDV) {
+      __bf16* o1 = (__bf16*)p.dv.ptr + b * p.dv.sb + hkv * p.dv.sh + (tok0 + a_wave0) * p.dv.ss;
+      RowStore<D>::run(W.acc1, 1.0f, obuf + RowStore<D>::BYTES, lane, o1, p.dv.ss, rows_valid);
     }
   }
   clock_probe_end(p.clock, clk);

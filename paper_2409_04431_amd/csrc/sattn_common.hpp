@@ -73,6 +73,45 @@ __device__ __forceinline__ void lds_write_b128(uint32_t lds_byte_addr, u32x4 v) 
   *(SATTN_LDS(u32x4)*)(uintptr_t)lds_byte_addr = v;
 }
 
+// s_waitcnt vmcnt(n), other counters untouched (gfx9 encoding, n < 16).
+#define SATTN_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(0x0F70 | (n))
+
+// Store a wave's 32 x D accumulator tile (DT transposed 32x32 MFMA results: register 4g+t of
+// tile dt, lane (l32, h) = element [row l32][32dt + 8g + 4h + t]) as bf16 rows of a global
+// tensor.  A lane holds four consecutive features of ITS row, so a store from the registers
+// scatters 8-byte pieces over 32 rows per instruction; the wave instead transposes through a
+// private LDS region -- rows padded by 16 bytes, which spreads the 32 rows of a write over the
+// banks -- and stores whole rows, 16 bytes per lane.  `buf` must not be in use by any wave
+// (the caller synchronises); only this wave touches it here, so the LDS counter is the only wait.
+template <int D>
+struct RowStore {
+  static constexpr int DT = D / 32, ROWB = D * 2 + 16, BYTES = 32 * ROWB;
+  static constexpr int LPR = D / 8, RPI = 64 / LPR;  // lanes per row, rows per store instruction
+  __device__ __forceinline__ static void run(const f32x16 (&acc)[DT], float scale, uint32_t buf, int lane,
+                                             __bf16* row0, int64_t stride, int rows_valid) {
+    const int l32 = lane & 31, h = lane >> 5;
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        u32x2 w;
+        w[0] = pack_bf16(acc[dt][4 * g] * scale, acc[dt][4 * g + 1] * scale);
+        w[1] = pack_bf16(acc[dt][4 * g + 2] * scale, acc[dt][4 * g + 3] * scale);
+        *(SATTN_LDS(u32x2)*)(uintptr_t)(buf + l32 * ROWB + (32 * dt + 8 * g + 4 * h) * 2) = w;
+      }
+    __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
+    const int rr = lane / LPR, cc = lane % LPR;
+    u32x4 v4[32 / RPI];
+#pragma unroll
+    for (int i = 0; i < 32 / RPI; ++i) v4[i] = lds_read_b128(buf + (RPI * i + rr) * ROWB + cc * 16);
+#pragma unroll
+    for (int i = 0; i < 32 / RPI; ++i) {
+      const int row = RPI * i + rr;
+      if (row < rows_valid) *(u32x4*)(row0 + (int64_t)row * stride + cc * 8) = v4[i];
+    }
+  }
+};
+
 // Measurement aid: when `out` is set, workgroup w < cap writes the core cycles and the ticks of
 // the constant-rate counter it spent in the kernel to out[2w], out[2w+1]; their ratio is the
 // engine clock the kernel actually ran at (the clock drops under matrix load).

@@ -160,9 +160,6 @@ struct DmaStager {
   }
 };
 
-// s_waitcnt vmcnt(n), other counters untouched (gfx9 encoding, n < 16).
-#define SATTN_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(0x0F70 | (n))
-
 // Running row statistics of the softmax comparison kernel (log2 units), one query per lane.
 struct SoftmaxState {
   float m;  // running maximum of the scaled logits
