@@ -17,10 +17,12 @@ extern "C" {
 #endif
 
 /* Force the forward tile shape for measurements (Appendix F.5: the block shape is a tuning
- * parameter): waves in {4, 8, 64, 65}, v_slots in {2, 3}; 0 = back to the automatic choice; a
+ * parameter): waves in {4, 8, 32, 64, 65}, v_slots in {2, 3}; 0 = back to the automatic choice; a
  * forced v_slots only applies where that shape exists, a forced 64 / 65 only for the pinned
- * sigmoid kernel at d = 128 (other kernels then run the 8-wave shape).  64 = four waves of 64
- * query rows.  65 = the same with Q multiplied by the logit scale and rounded to bf16 once, and
+ * sigmoid kernel at d = 128 (other kernels then run a 4-wave shape).  32 = the automatic choice
+ * among the shapes with 32 query rows per wave (4 or 8 waves), which is the choice every kernel
+ * without a 64-row form gets: it lets the sigmoid forward be timed in the shape the softmax
+ * forward runs.  64 = four waves of 64 query rows.  65 = the same with Q multiplied by the logit scale and rounded to bf16 once, and
  * the bias applied as a factor, which removes the scale-and-bias fma in front of every exp2: a
  * measurement variant, NOT bit-identical to the other shapes and never chosen automatically (its
  * logit error grows with |q||k|: one more bf16 rounding on an operand).  The value is
@@ -32,12 +34,19 @@ int sattn_set_fwd_v_slots(int v_slots);
 
 /* Comparison aids (Section 4 and Appendix F.2 compare the sigmoid kernels with softmax kernels
  * built the same way).  Same arguments, results and error behaviour as sigmoid_attn_fwd /
- * sigmoid_attn_bwd; the kernels run every pipeline step in the compiler-scheduled form that
- * the softmax comparison kernels use, instead of the hand-pinned instruction stream.  They
- * exist so that sigmoid and softmax can be timed like for like; not meant for production. */
+ * sigmoid_attn_bwd / softmax_attn_fwd; the kernels run every pipeline step in the
+ * compiler-scheduled form instead of the hand-pinned instruction stream (the softmax backward
+ * has no other form).  They exist so that sigmoid and softmax can be timed like for like at
+ * both levels of tuning; not meant for production. */
 int sigmoid_attn_fwd_compiler_scheduled(const void* q, const void* k, const void* v, void* o,
                                         int B, int H, int N, int d, sattn_dtype dtype,
                                         float bias, int causal, const float* alibi_slopes,
+                                        const sattn_strides* sq, const sattn_strides* sk,
+                                        const sattn_strides* sv, const sattn_strides* so,
+                                        void* stream);
+int softmax_attn_fwd_compiler_scheduled(const void* q, const void* k, const void* v, void* o, float* lse,
+                                        int B, int H, int N, int d, sattn_dtype dtype,
+                                        int causal, const float* alibi_slopes,
                                         const sattn_strides* sq, const sattn_strides* sk,
                                         const sattn_strides* sv, const sattn_strides* so,
                                         void* stream);

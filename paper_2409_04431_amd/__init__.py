@@ -28,6 +28,7 @@ from .binding import (  # noqa: F401
     softmax_attn_bwd_noalloc_max_rows,
     softmax_attn_bwd_workspace_bytes,
     softmax_attn_fwd,
+    softmax_attn_fwd_compiler_scheduled,
     sattn_device_info,
     sattn_fwd_v_slots,
     sattn_fwd_waves,

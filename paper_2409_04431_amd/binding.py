@@ -75,6 +75,8 @@ def load_library():
     lib.sigmoid_attn_bwd_workspace_bytes.restype = sz
     lib.softmax_attn_fwd.argtypes = [_vp, _vp, _vp, _vp, _vp, i, i, i, i, i, i, _vp, _SP, _SP, _SP, _SP, _vp]
     lib.softmax_attn_fwd.restype = i
+    lib.softmax_attn_fwd_compiler_scheduled.argtypes = lib.softmax_attn_fwd.argtypes
+    lib.softmax_attn_fwd_compiler_scheduled.restype = i
     lib.softmax_attn_bwd.argtypes = [_vp] * 9 + [i, i, i, i, i, i, _vp] + [_SP] * 8 + [_vp, sz, _vp]
     lib.softmax_attn_bwd.restype = i
     lib.softmax_attn_bwd_workspace_bytes.argtypes = [i, i, i, i, i]
@@ -305,7 +307,8 @@ def sattn_set_fwd_v_slots(v_slots):
 
 
 def sattn_set_fwd_waves(waves):
-    """Force 4 or 8 forward waves per workgroup for measurements; 0 restores the automatic choice."""
+    """Force the forward tile shape for measurements (4, 8, 64, 65; 32 = automatic among the 32-row
+    shapes); 0 restores the automatic choice."""
     _raise(load_library().sattn_set_fwd_waves(int(waves)), "sattn_set_fwd_waves")
 
 
@@ -460,18 +463,23 @@ def sigmoid_attn_bwd_dq(q, k, v, dout, dq, bias, causal=False, alibi_slopes=None
     return dq
 
 
-def softmax_attn_fwd(q, k, v, o, lse, causal=False, alibi_slopes=None):
+def softmax_attn_fwd(q, k, v, o, lse, causal=False, alibi_slopes=None, _entry="softmax_attn_fwd"):
     """Softmax flash attention forward (comparison kernel); lse is [B,H,N] float32."""
     lib = load_library()
     _check(q, k, v, o)
     B, H, N, d = q.shape
     if lse.dtype != torch.float32 or not lse.is_cuda or tuple(lse.shape) != (B, H, N) or not lse.is_contiguous():
         raise SattnError("lse must be a contiguous CUDA float32 tensor [B,H,N]")
-    rc = lib.softmax_attn_fwd(q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(), lse.data_ptr(), B, H, N, d,
+    rc = getattr(lib, _entry)(q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(), lse.data_ptr(), B, H, N, d,
                               _dtype_code(q), int(bool(causal)), _slopes_ptr(alibi_slopes, H),
                               _st(q), _st(k), _st(v), _st(o), _stream())
-    _raise(rc, "softmax_attn_fwd")
+    _raise(rc, _entry)
     return o, lse
+
+
+def softmax_attn_fwd_compiler_scheduled(q, k, v, o, lse, causal=False, alibi_slopes=None):
+    """softmax_attn_fwd with every step in the compiler-scheduled form (comparison aid)."""
+    return softmax_attn_fwd(q, k, v, o, lse, causal, alibi_slopes, _entry="softmax_attn_fwd_compiler_scheduled")
 
 
 def softmax_attn_bwd_workspace_bytes(B, H, N, d, dtype=torch.bfloat16):

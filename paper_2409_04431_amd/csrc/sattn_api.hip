@@ -160,7 +160,7 @@ int make_ref(const void* ptr, const sattn_strides* s, int H, int N, int d, sattn
 // two-slot V ring (80 KB) two 4-wave workgroups fit again; they win while a workgroup's key loop
 // is short (per-workgroup prologue, diagonal and barrier waits overlap with the neighbour) and
 // lose a few percent on long loops, where V is staged only one tile ahead.
-std::atomic<int> g_fwd_waves{0};   // 0: choose per problem; 4 or 8: forced (sattn_set_fwd_waves)
+std::atomic<int> g_fwd_waves{0};   // 0: choose per problem; 4, 8, 64, 65: forced; 32: choose among the 32-row shapes
 std::atomic<int> g_fwd_vslots{0};  // 0: choose per problem; 2 or 3: forced (sattn_set_fwd_v_slots)
 std::atomic<long long*> g_clock_out{nullptr};  // sattn_set_clock_probe
 std::atomic<int> g_clock_cap{0};
@@ -178,7 +178,10 @@ int compute_units() {
 
 struct FwdShape { int waves, v_slots; };
 
-FwdShape pick_fwd_shape(int B, int H, int N, int d, int causal) {
+// allow64 = false: the choice among the 32-row shapes only (the kernels that have no 64-row form)
+FwdShape pick_fwd_shape(int B, int H, int N, int d, int causal, bool allow64 = true) {
+  int forced_waves = g_fwd_waves.load(std::memory_order_relaxed);
+  if (forced_waves == 32) { allow64 = false; forced_waves = 0; }
   FwdShape s{8, 3};
   if (d == 64) {
     s.waves = 4;
@@ -188,21 +191,22 @@ FwdShape pick_fwd_shape(int B, int H, int N, int d, int causal) {
     const int64_t avg_tiles = (causal ? (N + 1) / 2 : N) / 64;  // 64-key tiles a workgroup visits on average
     if (wg4 <= (causal ? cus + cus / 2 : cus)) s = FwdShape{4, 3};
     else if (avg_tiles <= 48) s = FwdShape{4, 2};
-    // Long key loops with a workgroup for every compute unit: four waves of 64 query rows, which
-    // read half as much K/V from LDS per MFMA (waves = 64).  Measured 6-10 % faster than the
-    // 32-row shapes from 48 tiles per workgroup on without a mask and from 64 with the causal
-    // mask (whose last three steps per wave run unpinned and whose waves finish unevenly);
-    // equal or slower below.
-    if (avg_tiles >= (causal ? 64 : 48) && wg4 >= 2 * cus) s = FwdShape{64, 3};
+    // Long key loops on a well-filled chip: four waves of 64 query rows, which read half as much
+    // K/V from LDS per MFMA (waves = 64).  From a sweep over B, N and the mask: 3-10 % faster
+    // than the 32-row shapes from 32 tiles per workgroup on without a mask (N >= 2048) when there
+    // are two 256-row workgroups per compute unit, and from 20 tiles on average with the causal
+    // mask (N >= 2560), whose workgroups differ in length, when there are three; slower below.
+    const int64_t wg64 = (int64_t)B * H * ((N + 255) / 256);
+    if (allow64 && (causal ? (avg_tiles >= 20 && wg64 >= 3 * cus) : (avg_tiles >= 32 && wg64 >= 2 * cus)))
+      s = FwdShape{64, 3};
   }
-  const int forced_waves = g_fwd_waves.load(std::memory_order_relaxed);
   const int forced_vslots = g_fwd_vslots.load(std::memory_order_relaxed);
   if (forced_waves) {
     if (forced_waves != s.waves) s.v_slots = 3;
     s.waves = forced_waves;
   }
   if (forced_vslots) s.v_slots = forced_vslots;
-  if (s.waves >= 64 && d != 128) s = FwdShape{4, 3};  // the 64-row waves exist at d = 128 only
+  if (s.waves >= 64 && (d != 128 || !allow64)) s = FwdShape{4, 3};  // (a forced 64 where no such kernel exists)
   if (s.waves != 4 || d != 128) s.v_slots = 3;  // the only shape with a two-slot V ring
   return s;
 }
@@ -283,9 +287,9 @@ int fwd_impl(const FwdArgs& a) {
   p.kv_group = a.H / Hkv;
   p.Nk = Nk == a.N ? 0 : Nk;
   p.clock = clock_probe();
-  FwdShape shape = pick_fwd_shape(a.B, a.H, a.N, a.d, a.causal);
   // the 64-row waves exist for the pinned sigmoid kernel at d = 128, ALiBi only in its causal form
-  if (shape.waves >= 64 && (SOFTMAX || !PIN || a.d != 128 || (alibi && !a.causal))) shape = FwdShape{8, 3};
+  const bool has64 = !SOFTMAX && PIN && a.d == 128 && !(alibi && !a.causal);
+  const FwdShape shape = pick_fwd_shape(a.B, a.H, a.N, a.d, a.causal, has64);
   if (a.d == 128) return launch_fwd_bf16<128>(p, shape.waves, shape.v_slots, SOFTMAX, PIN, a.causal, alibi, st);
   return launch_fwd_bf16<64>(p, shape.waves, shape.v_slots, SOFTMAX, PIN, a.causal, alibi, st);
 }
@@ -517,6 +521,14 @@ int softmax_attn_fwd(const void* q, const void* k, const void* v, void* o, float
   return fwd_impl<true>(a);
 }
 
+int softmax_attn_fwd_compiler_scheduled(const void* q, const void* k, const void* v, void* o, float* lse, int B, int H,
+                                        int N, int d, sattn_dtype dtype, int causal, const float* alibi_slopes,
+                                        const sattn_strides* sq, const sattn_strides* sk, const sattn_strides* sv,
+                                        const sattn_strides* so, void* stream) {
+  FwdArgs a{q, k, v, o, lse, B, H, N, d, dtype, 0.0f, causal, alibi_slopes, sq, sk, sv, so, stream};
+  return fwd_impl<true, false>(a);
+}
+
 int softmax_attn_bwd(const void* q, const void* k, const void* v, const void* o, const float* lse, const void* dout,
                      void* dq, void* dk, void* dv, int B, int H, int N, int d, sattn_dtype dtype, int causal,
                      const float* alibi_slopes, const sattn_strides* sq, const sattn_strides* sk,
@@ -688,7 +700,7 @@ int sattn_headconcat_norm_bwd(const void* x, const void* dy, const float* stats,
 }
 
 int sattn_set_fwd_waves(int waves) {
-  if (waves != 0 && waves != 4 && waves != 8 && waves != 64 && waves != 65) return SATTN_ERR_UNSUPPORTED;
+  if (waves != 0 && waves != 4 && waves != 8 && waves != 32 && waves != 64 && waves != 65) return SATTN_ERR_UNSUPPORTED;
   g_fwd_waves.store(waves, std::memory_order_relaxed);
   return SATTN_OK;
 }

@@ -213,11 +213,16 @@ __device__ __forceinline__ void fwd_step(FwdWave<D>& W, uint32_t kaddr, uint32_t
   float alpha = 1.0f;
   const int jl = jc + 8 * W.h;  // key held by register 0 of this lane half
   if (SIG && SOFTMAX) {
-    // x = (s/sqrt(d) - slope|i-j|) log2(e); masked keys -> -inf
+    // x = (s/sqrt(d) - slope|i-j|) log2(e); masked keys -> -inf.  Under the causal mask every
+    // kept key has i - j >= 0: the term splits into one constant of the lane and step and a
+    // multiple of the register's key offset (a masked key gets -inf below whatever this gives).
+    const bool split = ALIBI && causal;
+    const float wstep = split ? -W.sl2 * (float)(W.qi - jl) : 0.f;
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
-      float x = s_cur[r] * W.nscale;
-      if (ALIBI) x = __builtin_fmaf(-W.sl2, __builtin_fabsf((float)(W.qi - jl) - (float)key_of_reg(r)), x);
+      float x = __builtin_fmaf(s_cur[r], W.nscale, wstep);
+      if (split) x = __builtin_fmaf(W.sl2, (float)key_of_reg(r), x);
+      else if (ALIBI) x = __builtin_fmaf(-W.sl2, __builtin_fabsf((float)(W.qi - jl) - (float)key_of_reg(r)), x);
       pr[r] = x;
     }
     if (KIND == STEP_LAST) {
@@ -415,20 +420,155 @@ __device__ __forceinline__ void fwd_step_full_pinned(FwdWave<D>& W, uint32_t kad
   W.p[PAR][1] = as_bf16x8(u32x4{wp[4], wp[5], wp[6], wp[7]});
 }
 
+// ---- The same hand-pinned stream for the softmax comparison kernel: what the sigmoid slices
+// are replaced with is the online softmax of the chunk (Appendix F.1 table, left half).  With
+// the logits transposed a lane holds 16 of its query's 32 keys of the chunk, the other lane half
+// the other 16, so the row maximum is a register tree plus one exchange between the halves.
+//   Y  x16 (ALiBi only)  y = s - (slope/scale)|i-j|: two operations per element; one under the
+//        causal mask, where i-j >= 0 splits into a constant of the lane and step (added where the
+//        maximum is scaled) and a multiple of the register's key offset (a literal)
+//   M  x8   tree of three-input maxima over y (raw logits: the scale is positive)
+//   X       exchange with the other half; m_new = max(m, scale*max), alpha = 2^(m - m_new)
+//   per group of four elements:  F x4 (u = y*scale - m_new)  E x4 (2^u)  A x4 (partial sums)  C x2 (pack)
+// The row sum (l = l*alpha + sum) and the rescaling of O^T by alpha follow the stream; O^T is
+// only touched when some lane's maximum moved, which stops early in a long key loop.
+template <int D, int AL>
+struct SmxLayout {
+  static constexpr int nY = AL == 1 ? 32 : AL == 2 ? 16 : 0, oM = nY, oX = oM + 8, oG = oX + 1, OPG = 14, NOPS = oG + 4 * OPG;
+};
+template <int D, int AL, int I>
+__device__ __forceinline__ void smx_op(FwdWave<D>& W, const f32x16& s, float (&y)[16], float (&u)[16],
+                                       float (&acc)[4], uint32_t (&wp)[8], float& nm, float& alpha, float cal, float dist0,
+                                       float wstep) {
+  using L = SmxLayout<D, AL>;
+  constexpr bool ALIBI = AL != 0;
+  if constexpr (I < L::oM && AL == 2) {
+    constexpr int e = I;
+    // y = cal * key_of_reg(e) + s  (cal = slope*log2(e) / scale here)
+    asm volatile("v_fmamk_f32 %0, %1, %2, %3" : "=v"(y[e]) : "v"(cal), "n"(__builtin_bit_cast(int, (float)key_of_reg(e))), "v"(s[e]));
+  } else if constexpr (I < L::oM) {
+    constexpr int e = I / 2;
+    if constexpr ((I & 1) == 0) {
+      const float keyf = (float)key_of_reg(e);
+      asm volatile("v_sub_f32 %0, %1, %2" : "=v"(u[e]) : "v"(dist0), "v"(keyf));
+    } else {
+      asm volatile("v_fma_f32 %0, %1, |%2|, %3" : "=v"(y[e]) : "v"(cal), "v"(u[e]), "v"(s[e]));
+    }
+  } else if constexpr (I < L::oX) {
+    constexpr int j = I - L::oM;
+    // without ALiBi the tree reads the accumulator registers themselves
+#define SATTN_SMX_Y(e) (ALIBI ? y[e] : s[e])
+    // (the temporaries are the first five entries of u, which the F stage overwrites later)
+    if constexpr (j < 5)
+      asm volatile("v_max3_f32 %0, %1, %2, %3" : "=v"(u[j]) : "v"(SATTN_SMX_Y(3 * j)), "v"(SATTN_SMX_Y(3 * j + 1)), "v"(SATTN_SMX_Y(3 * j + 2)));
+    else if constexpr (j == 5)
+      asm volatile("v_max3_f32 %0, %0, %1, %2" : "+v"(u[0]) : "v"(u[1]), "v"(u[2]));
+    else if constexpr (j == 6)
+      asm volatile("v_max3_f32 %0, %0, %1, %2" : "+v"(u[3]) : "v"(u[4]), "v"(SATTN_SMX_Y(15)));
+    else
+      asm volatile("v_max_f32 %0, %0, %1" : "+v"(u[0]) : "v"(u[3]));
+  } else if constexpr (I < L::oG) {
+    // compiler-scheduled island between the pinned halves (its inputs and outputs pin it there)
+    float mx = __builtin_fmaf(u[0], W.nscale, wstep);
+    mx = __builtin_fmaxf(mx, __shfl_xor(mx, 32));
+    const float m_new = __builtin_fmaxf(W.sm.m, mx);
+    alpha = __builtin_amdgcn_exp2f(W.sm.m - m_new);
+    W.sm.m = m_new;
+    nm = wstep - m_new;
+  } else {
+    constexpr int G = (I - L::oG) / L::OPG, i = (I - L::oG) % L::OPG, e = 4 * G + (i & 3);
+    if constexpr (i < 4) {
+      asm volatile("v_fma_f32 %0, %1, %2, %3" : "=v"(u[e]) : "v"(SATTN_SMX_Y(e)), "s"(W.nscale), "v"(nm));
+    } else if constexpr (i < 8) {
+      asm volatile("v_exp_f32 %0, %0" : "+v"(u[e]));
+    } else if constexpr (i < 12) {
+      if constexpr (G == 0) asm volatile("v_mov_b32 %0, %1" : "=v"(acc[i & 3]) : "v"(u[e]));
+      else asm volatile("v_add_f32 %0, %0, %1" : "+v"(acc[i & 3]) : "v"(u[e]));
+    } else {
+      constexpr int j = 2 * G + (i - 12);
+      asm volatile("v_cvt_pk_bf16_f32 %0, %1, %2" : "=v"(wp[j]) : "v"(u[2 * j]), "v"(u[2 * j + 1]));
+    }
+#undef SATTN_SMX_Y
+  }
+}
+template <int D, int AL, int LO, int HI>
+__device__ __forceinline__ void smx_ops(FwdWave<D>& W, const f32x16& s, float (&y)[16], float (&u)[16],
+                                        float (&acc)[4], uint32_t (&wp)[8], float& nm, float& alpha, float cal, float dist0,
+                                       float wstep) {
+  if constexpr (LO < HI) {
+    smx_op<D, AL, LO>(W, s, y, u, acc, wp, nm, alpha, cal, dist0, wstep);
+    smx_ops<D, AL, LO + 1, HI>(W, s, y, u, acc, wp, nm, alpha, cal, dist0, wstep);
+  }
+}
+
+template <int D, int AL, int PAR, int K>
+__device__ __forceinline__ void smx_subslots(FwdWave<D>& W, uint32_t kaddr, uint32_t vaddr, float (&y)[16], float (&u)[16],
+                                             float (&acc)[4], uint32_t (&wp)[8], float& nm, float& alpha,
+                                             float cal, float dist0, float wstep) {
+  constexpr int KD = D / 16, DT = D / 32, NSUB = 2 * KD, NOPS = SmxLayout<D, AL>::NOPS;
+  if constexpr (K < NSUB) {
+    constexpr int m = K / 2;
+    if constexpr ((K & 1) == 0) {
+      if constexpr (m == 0) a_mfma_zero(W.s[PAR ^ 1], W.kf[m], W.qf[m]);
+      else a_mfma(W.s[PAR ^ 1], W.kf[m], W.qf[m]);
+      W.kf[m] = as_bf16x8(lds_read_b128(W.koff[m] + kaddr));
+    } else {
+      a_mfma(W.oacc[m % DT], W.vf[m], W.p[PAR ^ 1][m / DT]);
+      const uint32_t a0 = W.voff[m % DT] + vaddr + (m / DT) * 16 * (D * 2);
+      W.vf[m] = join_tr(lds_read_tr16(a0), lds_read_tr16(a0 + 4 * (D * 2)));
+    }
+    smx_ops<D, AL, (K * NOPS) / NSUB, ((K + 1) * NOPS) / NSUB>(W, W.s[PAR], y, u, acc, wp, nm, alpha, cal, dist0, wstep);
+    smx_subslots<D, AL, PAR, K + 1>(W, kaddr, vaddr, y, u, acc, wp, nm, alpha, cal, dist0, wstep);
+  }
+}
+
+// (The sigmoid step keeps the register term of causal ALiBi in the S^T accumulators' initial
+// value, sixteen registers that this step, with its running statistics, does not have to spare.)
+template <int D, bool ALIBI, int PAR, bool CAUSAL>
+__device__ __forceinline__ void fwd_step_full_pinned_softmax(FwdWave<D>& W, uint32_t kaddr, uint32_t vaddr, int jc) {
+  constexpr int DT = D / 32;
+  float y[16], u[16], acc[4];
+  uint32_t wp[8];
+  float nm = 0.f, alpha = 1.f;
+  const float dist0 = (float)(W.qi - (jc + 8 * W.h));
+  constexpr int AL = !ALIBI ? 0 : CAUSAL ? 2 : 1;
+  // y*scale = s*scale - slope*log2(e)*|i-j|
+  const float cal = !ALIBI ? 0.f : CAUSAL ? W.sl2 / W.nscale : -W.sl2 / W.nscale;
+  const float wstep = AL == 2 ? -W.sl2 * dist0 : 0.f;
+  smx_subslots<D, AL, PAR, 0>(W, kaddr, vaddr, y, u, acc, wp, nm, alpha, cal, dist0, wstep);
+  W.p[PAR][0] = as_bf16x8(u32x4{wp[0], wp[1], wp[2], wp[3]});
+  W.p[PAR][1] = as_bf16x8(u32x4{wp[4], wp[5], wp[6], wp[7]});
+  W.sm.l = __builtin_fmaf(W.sm.l, alpha, (acc[0] + acc[1]) + (acc[2] + acc[3]));
+  // O^T holds sums relative to the previous maximum: rescale only when some maximum moved
+  if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
+    // the stream's last MFMAs must have written O^T before the vector ALU reads it, and the
+    // products must be that old before the next step's MFMA reads them (the compiler knows of neither)
+    asm volatile("s_nop 15\n\ts_nop 3" ::: "memory");
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) W.oacc[dt][r] *= alpha;
+      asm volatile("" : "+v"(W.oacc[dt]) : : "memory");
+    }
+    asm volatile("s_nop 1" ::: "memory");
+  }
+}
+
 // Dispatch one step of chunk c for a wave that owns chunks 0..cw-1.
-template <int D, bool ALIBI, bool SOFTMAX, int PAR, bool FOLD, bool PIN>
+template <int D, bool ALIBI, bool SOFTMAX, int PAR, bool FOLD, bool PIN, bool CAUSAL>
 __device__ __forceinline__ void fwd_step_any(FwdWave<D>& W, int c, int cw, uint32_t kaddr, uint32_t vaddr, int N,
                                              bool causal) {
   if (c + 1 < cw) {
-    if constexpr (SOFTMAX || !PIN) fwd_step<D, ALIBI, SOFTMAX, STEP_FULL, PAR, FOLD>(W, kaddr, vaddr, 32 * c, N, causal);
+    if constexpr (!PIN) fwd_step<D, ALIBI, SOFTMAX, STEP_FULL, PAR, FOLD>(W, kaddr, vaddr, 32 * c, N, causal);
+    else if constexpr (SOFTMAX) fwd_step_full_pinned_softmax<D, ALIBI, PAR, CAUSAL>(W, kaddr, vaddr, 32 * c);
     else fwd_step_full_pinned<D, ALIBI, PAR, FOLD>(W, kaddr, vaddr, 32 * c);
   }
   else if (c + 1 == cw) fwd_step<D, ALIBI, SOFTMAX, STEP_LAST, PAR, FOLD>(W, kaddr, vaddr, 32 * c, N, causal);
   else if (c == cw) fwd_step<D, ALIBI, SOFTMAX, STEP_TAIL, PAR, FOLD>(W, kaddr, vaddr, 32 * c, N, causal);
 }
 
-// PIN = false runs the steady-state step in its compiler-scheduled form as well (the form the
-// softmax variant always uses): the like-for-like counterpart for comparisons.
+// PIN = false runs the steady-state step in its compiler-scheduled form as well (measurement
+// aid: what the hand-pinned order is worth, for either method).
 // VS = V ring slots (3, or 2: the V tile is then staged one tile ahead instead of two, which
 // brings the ring of D = 128 down to 80 KB so that two 4-wave workgroups share a compute unit).
 template <int D, int NW, bool CAUSAL, bool ALIBI, bool SOFTMAX, bool PIN = true, int VS = 3>
@@ -569,8 +709,8 @@ attn_fwd_kernel(const FwdParams p) {
       if (v_more) vst.issue(vring + ((t + 1) & 1) * TILE, Nk, uwave, lane);
       if (k_more) kst.issue(kring + kslot * TILE, Nk, uwave, lane);
     }
-    fwd_step_any<D, ALIBI, SOFTMAX, 0, FOLD, PIN>(W, 2 * t, cw, 0, 0, Nk, CAUSAL);
-    fwd_step_any<D, ALIBI, SOFTMAX, 1, FOLD, PIN>(W, 2 * t + 1, cw, CHUNK, CHUNK, Nk, CAUSAL);
+    fwd_step_any<D, ALIBI, SOFTMAX, 0, FOLD, PIN, CAUSAL>(W, 2 * t, cw, 0, 0, Nk, CAUSAL);
+    fwd_step_any<D, ALIBI, SOFTMAX, 1, FOLD, PIN, CAUSAL>(W, 2 * t + 1, cw, CHUNK, CHUNK, Nk, CAUSAL);
     // advance the read addresses by one ring slot: K reads are at slot (t+1)%3, V reads at t%3
     const int kadv = kslot == 1 ? -2 * TILE : TILE;  // slot (t+1)%3 == 2 wraps to 0
     const int vadv = VS == 3 ? (kslot == 2 ? -2 * TILE : TILE) : ((t & 1) ? -TILE : TILE);

@@ -17,6 +17,7 @@ int launch_fwd_variant(FwdParams p, int causal, bool alibi, hipStream_t st) {
 
 template <int D, int NW, int VS>
 int launch_fwd_shape(const FwdParams& p, bool softmax, bool pin, int causal, bool alibi, hipStream_t st) {
+  if (softmax && pin) return launch_fwd_variant<D, NW, VS, true, true>(p, causal, alibi, st);
   if (softmax) return launch_fwd_variant<D, NW, VS, true, false>(p, causal, alibi, st);
   if (pin) return launch_fwd_variant<D, NW, VS, false, true>(p, causal, alibi, st);
   return launch_fwd_variant<D, NW, VS, false, false>(p, causal, alibi, st);

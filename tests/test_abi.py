@@ -116,7 +116,11 @@ def test_forward_shape_choice(lib):
     # d = 64 always takes 4-wave workgroups; d = 128 while the grid is small (one per compute unit,
     # three-slot V ring) or the key loop short (two per compute unit, two-slot V ring)
     assert sa.sattn_fwd_waves(32, 12, 4096, 64) == 4 and sa.sattn_fwd_v_slots(32, 12, 4096, 64) == 3
-    assert (sa.sattn_fwd_waves(8, 16, 4096, 128, True), sa.sattn_fwd_v_slots(8, 16, 4096, 128, True)) == (4, 2)
+    assert (sa.sattn_fwd_waves(8, 16, 4096, 128, True), sa.sattn_fwd_v_slots(8, 16, 4096, 128, True)) == (64, 3)
+    # causal: short key loops, or fewer than three 256-row workgroups per compute unit, keep 32-row waves
+    assert (sa.sattn_fwd_waves(8, 16, 2048, 128, True), sa.sattn_fwd_v_slots(8, 16, 2048, 128, True)) == (4, 2)
+    assert (sa.sattn_fwd_waves(2, 16, 4096, 128, True), sa.sattn_fwd_v_slots(2, 16, 4096, 128, True)) == (4, 2)
+    assert sa.sattn_fwd_waves(8, 16, 2048, 128) == 64 and sa.sattn_fwd_waves(8, 16, 1024, 128) != 64
     # long key loops with a workgroup for every compute unit: four waves of 64 query rows
     assert (sa.sattn_fwd_waves(1, 32, 16384, 128, True), sa.sattn_fwd_v_slots(1, 32, 16384, 128, True)) == (64, 3)
     assert sa.sattn_fwd_waves(2, 16, 8192, 128) == 64 and sa.sattn_fwd_waves(8, 16, 4096, 128) == 64
@@ -130,6 +134,9 @@ def test_forward_shape_choice(lib):
         sa.sattn_set_fwd_waves(8)
         assert sa.sattn_fwd_waves(1, 2, 512, 128) == 8 and sa.sattn_fwd_waves(1, 2, 512, 64) == 8
         assert sa.sattn_fwd_v_slots(8, 16, 4096, 128, True) == 3      # no two-slot ring with 8 waves
+        sa.sattn_set_fwd_waves(32)   # the automatic choice held to the 32-row shapes
+        assert (sa.sattn_fwd_waves(8, 16, 4096, 128, True), sa.sattn_fwd_v_slots(8, 16, 4096, 128, True)) == (4, 2)
+        assert sa.sattn_fwd_waves(1, 6, 8192, 128) == 8 and sa.sattn_fwd_waves(32, 12, 4096, 64) == 4
         sa.sattn_set_fwd_waves(64)
         assert sa.sattn_fwd_waves(1, 2, 512, 128) == 64 and sa.sattn_fwd_waves(1, 2, 512, 64) == 4
         sa.sattn_set_fwd_waves(4)

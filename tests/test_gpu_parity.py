@@ -277,6 +277,31 @@ def test_softmax_comparison_kernels_match_oracle(B, H, N, d, causal, alibi):
     assert float((o1 - 1).abs().max()) <= 1e-2
 
 
+@pytest.mark.parametrize("B,H,N,d,causal,alibi", [
+    (1, 2, 700, 128, False, False), (1, 2, 1100, 128, True, True), (2, 1, 450, 64, True, False),
+    (1, 2, 333, 64, False, True),
+])
+def test_softmax_forward_with_moving_maxima_pinned_and_compiler_scheduled(B, H, N, d, causal, alibi):
+    """Logits with a standard deviation of 4: the running maximum of a row keeps moving along
+    the key loop, so the rescaling of the partial output is exercised at many steps.  Both forms
+    of the forward (hand-pinned steady step, compiler-scheduled step) against the oracle."""
+    inp = _rand_inputs(B, H, N, d, seed=77 + N)
+    inp["q"] = (inp["q"].float() * 2).to(torch.bfloat16)
+    inp["k"] = (inp["k"].float() * 2).to(torch.bfloat16)
+    slopes = W.alibi_slopes(H) if alibi else None
+    sl = _dev(slopes) if alibi else None
+    q, k, v = (_dev(inp[n]) for n in ("q", "k", "v"))
+    ro, rl = orc.softmax_attn_fwd(inp["q"], inp["k"], inp["v"], causal, slopes.numpy() if alibi else None)
+    for entry in (sa.softmax_attn_fwd, sa.softmax_attn_fwd_compiler_scheduled):
+        (o, g0), (lse, g1) = _guarded(q.shape, torch.bfloat16), _guarded((B, H, N), torch.float32)
+        entry(q, k, v, o, lse, causal, sl)
+        torch.cuda.synchronize()
+        g0(); g1()
+        assert not torch.isnan(o).any() and not torch.isnan(lse).any()
+        assert nerr(o, ro) <= TOL_BF16 and row_err(o, ro) <= TOL_BF16, entry.__name__
+        assert float(np.abs(lse.cpu().numpy() - rl).max()) <= 2e-3, entry.__name__
+
+
 def test_softmax_full_size_config3_sampled_rows():
     c = W.CONFIGS[3]
     inp = W.make_inputs(c)

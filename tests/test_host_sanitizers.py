@@ -61,4 +61,4 @@ def test_abi_host_code_under_asan_and_ubsan(tmp_path):
     # there is no device, or succeed on a GPU machine
     assert codes[0] == -1 and codes[1] == -3 and codes[2] == -4 and codes[3] in (0, -6) and codes[5] == -1
     assert codes[10] == -7 and codes[12] == -2 and codes[13] == -2 and codes[15] == -2 and codes[17] == -2
-    assert codes[19] == -3 and codes[21] == 64 and codes[23] == 64 and codes[24] == 2 and codes[26] == -2
+    assert codes[19] == -3 and codes[21] == 64 and codes[23] == 64 and codes[24] == 3 and codes[26] == -2
