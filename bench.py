@@ -121,11 +121,17 @@ def main():
     o, dq, dk, dv = (torch.empty_like(q) for _ in range(4))
     bias = cfg.bias
 
+    # small grids run the two passes of the backward as one grid (one kernel)
+    one_grid = bool(cfg.backward and cfg.dtype == torch.bfloat16 and sa.sattn_bwd_merged(cfg.B, cfg.H, cfg.N, cfg.causal))
+
     def step(ev=None):
         if ev: ev[0].record()
         sa.sigmoid_attn_fwd(q, k, v, o, bias, cfg.causal, slopes)
         if ev: ev[1].record()
-        if cfg.backward:
+        if cfg.backward and one_grid:
+            sa.sigmoid_attn_bwd(q, k, v, dout, dq, dk, dv, bias, cfg.causal, slopes)
+            if ev: ev[2].record()
+        elif cfg.backward:
             sa.sigmoid_attn_bwd_dkdv(q, k, v, dout, dk, dv, bias, cfg.causal, slopes)
             if ev: ev[2].record()
             sa.sigmoid_attn_bwd_dq(q, k, v, dout, dq, bias, cfg.causal, slopes)
@@ -174,7 +180,10 @@ def main():
     if cfg.dtype == torch.bfloat16:
         n_wg = cfg.B * cfg.H * ((cfg.N + 127) // 128)
         clocks["fwd"] = clock_under_load(lambda: sa.sigmoid_attn_fwd(q, k, v, o, bias, cfg.causal, slopes), n_wg)
-        if cfg.backward:
+        if one_grid:
+            clocks["bwd"] = clock_under_load(
+                lambda: sa.sigmoid_attn_bwd(q, k, v, dout, dq, dk, dv, bias, cfg.causal, slopes), 2 * n_wg)
+        elif cfg.backward:
             clocks["bwd_dkdv"] = clock_under_load(
                 lambda: sa.sigmoid_attn_bwd_dkdv(q, k, v, dout, dk, dv, bias, cfg.causal, slopes), n_wg)
             clocks["bwd_dq"] = clock_under_load(
@@ -225,13 +234,39 @@ def main():
     if clocks.get("fwd"):
         out["fwd_frac_of_mfma_peak_at_measured_clock"] = (
             flops_f / fwd_ms / 1e9 / (MFMA_BF16_PEAK_TFLOPS * clocks["fwd"] * 1e3 / clock_khz))
-    if cfg.backward:
+    if cfg.backward and one_grid:
+        # one kernel runs all five products of Algorithm 2 (seven executed: S and dP twice)
+        bwd_ms = stats(1)["mean"]
+        total = flops_f + flops_b
+        out["value"] = total / ms_step / 1e9
+        out["frac_of_bf16_mfma_peak"] = out["value"] / MFMA_BF16_PEAK_TFLOPS
+        out.update({"bwd_one_grid": True, "bwd_ms": bwd_ms, "bwd_ms_stats": stats(1), "bwd_tflops": flops_b / bwd_ms / 1e9})
+        ach = flops_b / bwd_ms / 1e9
+        out["roofline"] = {"kernel": "attn_bwd_merged_kernel", "bound": "mfma", "achieved": ach,
+                           "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": ach / MFMA_BF16_PEAK_TFLOPS,
+                           "traffic": measured_traffic_bytes(cfg.cfg, f"attn_bwd_merged_kernel<{cfg.d},"),
+                           "avg_launch_ms": bwd_ms}
+        if clocks.get("bwd"):
+            out["roofline"]["frac_at_measured_clock"] = ach / (MFMA_BF16_PEAK_TFLOPS * clocks["bwd"] * 1e3 / clock_khz)
+        # the two passes on their own, for the per-kernel bounds (outside the timed steps)
+        for key, fn in (("bwd_dkdv", lambda: sa.sigmoid_attn_bwd_dkdv(q, k, v, dout, dk, dv, bias, cfg.causal, slopes)),
+                        ("bwd_dq", lambda: sa.sigmoid_attn_bwd_dq(q, k, v, dout, dq, bias, cfg.causal, slopes))):
+            for _ in range(3):
+                fn()
+            pe = _events(2)
+            pe[0].record()
+            for _ in range(10):
+                fn()
+            pe[1].record()
+            torch.cuda.synchronize()
+            out["bounds"][key]["achieved_ms"] = pe[0].elapsed_time(pe[1]) / 10
+    elif cfg.backward:
         dkdv_ms, dq_ms = stats(1)["mean"], stats(2)["mean"]
         out["bwd_dkdv_ms_stats"], out["bwd_dq_ms_stats"] = stats(1), stats(2)
         total = flops_f + flops_b
         out["value"] = total / ms_step / 1e9
         out["frac_of_bf16_mfma_peak"] = out["value"] / MFMA_BF16_PEAK_TFLOPS
-        out.update({"bwd_dkdv_ms": dkdv_ms, "bwd_dq_ms": dq_ms,
+        out.update({"bwd_one_grid": False, "bwd_dkdv_ms": dkdv_ms, "bwd_dq_ms": dq_ms,
                     "bwd_tflops": flops_b / (dkdv_ms + dq_ms) / 1e9})
         # dominant kernel: dK/dV.  Algorithmic work attributed to it: S, dP, dV, dK = 4 of the
         # 5 backward products (8*B*H*N^2*d, halved when causal); dQ's recompute is not counted.

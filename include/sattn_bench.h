@@ -32,6 +32,16 @@ extern "C" {
 int sattn_set_fwd_waves(int waves);
 int sattn_set_fwd_v_slots(int v_slots);
 
+/* Force (1) or forbid (2) the one-grid form of the sigmoid backward, in which the dK/dV and
+ * the dQ workgroups of Algorithm 2's two output owners share one launch; 0 = back to the
+ * automatic choice.  Only sigmoid_attn_bwd / sigmoid_attn_varlen_bwd have that form (both
+ * passes, self-attention, one K/V head per query head, no bias gradient).  Results do not
+ * depend on it.  Process-wide like the setters above.  Returns 0 or SATTN_ERR_UNSUPPORTED. */
+int sattn_set_bwd_merged(int mode);
+/* 1 if sigmoid_attn_bwd on a bf16 self-attention problem of this size would run its two
+ * passes as one grid, 0 if as two launches; SATTN_ERR_SHAPE for non-positive sizes. */
+int sattn_bwd_merged(int B, int H, int N, int causal);
+
 /* Comparison aids (Section 4 and Appendix F.2 compare the sigmoid kernels with softmax kernels
  * built the same way).  Same arguments, results and error behaviour as sigmoid_attn_fwd /
  * sigmoid_attn_bwd / softmax_attn_fwd; the kernels run every pipeline step in the

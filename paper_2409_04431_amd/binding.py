@@ -101,6 +101,10 @@ def load_library():
     lib.sattn_fwd_v_slots.restype = i
     lib.sattn_set_fwd_v_slots.argtypes = [i]
     lib.sattn_set_fwd_v_slots.restype = i
+    lib.sattn_set_bwd_merged.argtypes = [i]
+    lib.sattn_set_bwd_merged.restype = i
+    lib.sattn_bwd_merged.argtypes = [i, i, i, i]
+    lib.sattn_bwd_merged.restype = i
     lib.sattn_set_clock_probe.argtypes = [_vp, i]
     lib.sattn_set_clock_probe.restype = i
     lib.sattn_wall_clock_khz.argtypes = []
@@ -304,6 +308,18 @@ def sattn_fwd_v_slots(B, H, N, d, causal=False):
 def sattn_set_fwd_v_slots(v_slots):
     """Force a V ring of 2 or 3 tiles where that shape exists (4 waves, d = 128); 0 = automatic."""
     _raise(load_library().sattn_set_fwd_v_slots(int(v_slots)), "sattn_set_fwd_v_slots")
+
+
+def sattn_bwd_merged(B, H, N, causal=False):
+    """True if sigmoid_attn_bwd runs both passes of this bf16 self-attention problem as one grid."""
+    rc = load_library().sattn_bwd_merged(int(B), int(H), int(N), int(bool(causal)))
+    _raise(min(rc, 0), "sattn_bwd_merged")
+    return bool(rc)
+
+
+def sattn_set_bwd_merged(mode):
+    """1 forces, 2 forbids the one-grid form of the sigmoid backward; 0 restores the automatic choice."""
+    _raise(load_library().sattn_set_bwd_merged(int(mode)), "sattn_set_bwd_merged")
 
 
 def sattn_set_fwd_waves(waves):

@@ -505,9 +505,9 @@ __device__ __forceinline__ void bwd_step_full_pinned(BwdWave<D, MODE>& W, uint32
 // always uses): the like-for-like counterpart for comparisons.
 // GROUPS (dK/dV pass only) compiles the loop over the query heads that share a K/V head; without
 // it the pass handles exactly one query head per K/V head and p.kv_group must be 1.
+// `logical` is the workgroup's place in the pass: consecutive values share a head.
 template <int D, int MODE, bool CAUSAL, bool ALIBI, bool SOFTMAX, bool PIN = true, bool GROUPS = false>
-__global__ void __launch_bounds__(256, 1)
-attn_bwd_kernel(const BwdParams p) {
+__device__ __forceinline__ void attn_bwd_body(const BwdParams& p, const int logical) {
   static_assert(!GROUPS || MODE == BWD_DKDV, "only the dK/dV pass iterates over query heads");
   constexpr int NW = 4, BS = 32 * NW, BC = 64, KD = D / 16, DT = D / 32;
   constexpr bool FOLD = !SOFTMAX && CAUSAL && ALIBI;  // see bwd_step
@@ -522,8 +522,6 @@ attn_bwd_kernel(const BwdParams p) {
   // of that head's group one after the other; the dQ pass runs per query head
   const int kv_group = (MODE == BWD_DKDV && !GROUPS) ? 1 : p.kv_group;
   const int heads = MODE == BWD_DKDV ? p.H / kv_group : p.H;
-  const int total = p.n_blocks * p.B * heads;
-  const int logical = xcd_remap(blockIdx.x, total);
   const int bh = logical / p.n_blocks;
   // causal: heavy blocks first (late query blocks for DQ, early key blocks for DKDV)
   const int blk = (CAUSAL && MODE != BWD_DKDV) ? (p.n_blocks - 1 - logical % p.n_blocks) : (logical % p.n_blocks);
@@ -828,6 +826,28 @@ attn_bwd_kernel(const BwdParams p) {
     }
   }
   clock_probe_end(p.clock, clk);
+}
+
+template <int D, int MODE, bool CAUSAL, bool ALIBI, bool SOFTMAX, bool PIN = true, bool GROUPS = false>
+__global__ void __launch_bounds__(256, 1)
+attn_bwd_kernel(const BwdParams p) {
+  const int kv_group = (MODE == BWD_DKDV && !GROUPS) ? 1 : p.kv_group;
+  const int total = p.n_blocks * p.B * (MODE == BWD_DKDV ? p.H / kv_group : p.H);
+  attn_bwd_body<D, MODE, CAUSAL, ALIBI, SOFTMAX, PIN, GROUPS>(p, xcd_remap(blockIdx.x, total));
+}
+
+// Both passes of the sigmoid backward in one grid (self-attention, one K/V head per query
+// head): even places run the dK/dV workgroup, odd places the dQ workgroup of the same
+// (head, block) place, each pass in its own heavy-first order.  The grid is one launch, so a
+// pass's last, ragged round of workgroups is filled by the other pass, and a head's two
+// passes run on the same XCD next to each other and share its L2.
+template <int D, bool CAUSAL, bool ALIBI>
+__global__ void __launch_bounds__(256, 1)
+attn_bwd_merged_kernel(const BwdParams p) {
+  const int total = p.n_blocks * p.B * p.H;
+  const int logical = xcd_remap(blockIdx.x, 2 * total);
+  if (logical & 1) attn_bwd_body<D, BWD_DQ, CAUSAL, ALIBI, false, true, false>(p, logical >> 1);
+  else attn_bwd_body<D, BWD_DKDV, CAUSAL, ALIBI, false, true, false>(p, logical >> 1);
 }
 
 // Pre-pass of the softmax backward: per query row D_i = sum_t dO[i][t] * O[i][t] (fp32) and

@@ -5,7 +5,7 @@
 namespace sattn {
 
 template <int D, bool SOFTMAX, bool PIN>
-int launch_bwd_variant(BwdParams p, int causal, bool alibi, int parts, hipStream_t st) {
+int launch_bwd_variant(BwdParams p, int causal, bool alibi, int parts, bool merged, hipStream_t st) {
   // the dQ pass runs one workgroup per 128 queries, the dK/dV pass one per 128 keys
   const int nb_q = (p.N + 127) / 128, nb_k = ((p.Nk > 0 ? p.Nk : p.N) + 127) / 128;
   dim3 grid(nb_q * p.B * p.H), grid_k(nb_k * p.B * p.H), grid_kv(nb_k * p.B * (p.H / p.kv_group));
@@ -14,6 +14,15 @@ int launch_bwd_variant(BwdParams p, int causal, bool alibi, int parts, hipStream
   dim3 block(256);
   if (p.kv_group < 1 || p.H % p.kv_group) return SATTN_ERR_SHAPE;
   if (p.kv_group > 1 && (SOFTMAX || !PIN)) return SATTN_ERR_UNSUPPORTED;  // only the product kernels share K/V heads
+  if constexpr (!SOFTMAX && PIN) {
+    // self-attention with one K/V head per query head and both passes wanted: one grid
+    if (parts == (kBwdDkDv | kBwdDq) && p.kv_group == 1 && nb_q == nb_k && p.Nk == 0 && !p.db_rows && merged) {
+      p.n_blocks = nb_q;
+      dim3 grid2(2 * nb_q * p.B * p.H);
+      SATTN_DISPATCH2(causal, alibi, rc = launch(attn_bwd_merged_kernel<D, A, B2>, grid2, block, lds, st, p));
+      return rc;
+    }
+  }
   if (parts & kBwdDkDv) {
     p.n_blocks = nb_k;
     if constexpr (!SOFTMAX && PIN) {
@@ -40,10 +49,11 @@ int launch_bwd_variant(BwdParams p, int causal, bool alibi, int parts, hipStream
 }
 
 template <int D>
-int launch_bwd_bf16(BwdParams p, bool softmax, bool pin, int causal, bool alibi, int parts, hipStream_t st) {
-  if (softmax) return launch_bwd_variant<D, true, false>(p, causal, alibi, parts, st);
-  if (pin) return launch_bwd_variant<D, false, true>(p, causal, alibi, parts, st);
-  return launch_bwd_variant<D, false, false>(p, causal, alibi, parts, st);
+int launch_bwd_bf16(BwdParams p, bool softmax, bool pin, int causal, bool alibi, int parts, bool merged,
+                    hipStream_t st) {
+  if (softmax) return launch_bwd_variant<D, true, false>(p, causal, alibi, parts, false, st);
+  if (pin) return launch_bwd_variant<D, false, true>(p, causal, alibi, parts, merged, st);
+  return launch_bwd_variant<D, false, false>(p, causal, alibi, parts, false, st);
 }
 
 }  // namespace sattn

@@ -58,8 +58,10 @@ template <int D>
 int launch_fwd_bf16(FwdParams p, int waves, int v_slots, bool softmax, bool pin, int causal, bool alibi,
                     hipStream_t st);
 
-// Backward: `parts` is a mask of BwdPart; p.db_rows selects the dQ pass with row sums.
+// Backward: `parts` is a mask of BwdPart; p.db_rows selects the dQ pass with row sums; `merged`
+// lets the two passes of the pinned sigmoid backward share one grid where that form exists.
 template <int D>
-int launch_bwd_bf16(BwdParams p, bool softmax, bool pin, int causal, bool alibi, int parts, hipStream_t st);
+int launch_bwd_bf16(BwdParams p, bool softmax, bool pin, int causal, bool alibi, int parts, bool merged,
+                    hipStream_t st);
 
 }  // namespace sattn

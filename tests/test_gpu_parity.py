@@ -554,6 +554,37 @@ def test_varlen_bias_gradient_matches_per_sequence_calls_and_oracle(d, causal, a
         np.testing.assert_allclose(db[s_].cpu().numpy(), ref[0].sum(-1), rtol=2e-4, atol=2e-4 * np.abs(ref).max() * n)
 
 
+# ------------------------------------------------------------------ backward as one grid
+
+@pytest.mark.parametrize("B,H,N,d,causal,alibi", [(1, 2, 700, 128, True, True), (2, 3, 333, 64, False, True),
+                                                  (1, 1, 1025, 128, False, False), (3, 2, 96, 64, True, False),
+                                                  (2, 2, 512, 128, True, False)])
+def test_backward_in_one_grid_equals_the_two_launches_and_the_oracle(B, H, N, d, causal, alibi):
+    inp = _rand_inputs(B, H, N, d, seed=57 + N)
+    slopes = W.alibi_slopes(H) if alibi else None
+    sl = _dev(slopes) if alibi else None
+    bias = -math.log(N)
+    q, k, v, do = (_dev(inp[n]) for n in ("q", "k", "v", "dout"))
+    res = {}
+    try:
+        for mode in (1, 2):     # 1: both passes in one launch; 2: one launch per pass
+            sa.sattn_set_bwd_merged(mode)
+            outs = [_guarded(q.shape) for _ in range(3)]
+            sa.sigmoid_attn_bwd(q, k, v, do, outs[0][0], outs[1][0], outs[2][0], bias, causal, sl)
+            torch.cuda.synchronize()
+            for _, g in outs:
+                g()
+            res[mode] = [o for o, _ in outs]
+    finally:
+        sa.sattn_set_bwd_merged(0)
+    for a, b in zip(res[1], res[2]):
+        assert not torch.isnan(a).any() and torch.equal(a, b)
+    f = lambda t: inp[t].double().numpy()
+    ref = orc.sigmoid_attn_bwd(f("q"), f("k"), f("v"), f("dout"), bias, causal, slopes)
+    for name, got, r in zip(("dq", "dk", "dv"), res[1], ref):
+        assert nerr(got, r) <= TOL_BF16, name
+
+
 # ------------------------------------------------------------------ forward tile shape
 
 @pytest.mark.parametrize("B,H,N,d,causal,alibi", [(1, 2, 700, 128, True, True), (2, 2, 333, 64, False, True),
