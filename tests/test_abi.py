@@ -112,6 +112,21 @@ def test_varlen_bias_gradient_entry_point_rejects_bad_arguments(lib):
     assert f(*ptrs, 0x8000, None, 0x9000, None, *tail(dtype=1)) == -3   # packed sequences are bf16 only
 
 
+def test_backward_one_grid_choice(lib):
+    # small or uneven (causal) grids run both passes of the backward in one launch
+    assert sa.sattn_bwd_merged(4, 12, 1024) and sa.sattn_bwd_merged(8, 16, 2048, True)
+    assert not sa.sattn_bwd_merged(8, 16, 4096, True) and not sa.sattn_bwd_merged(8, 16, 1024)
+    assert lib.sattn_bwd_merged(0, 1, 16, 0) == -2 and lib.sattn_set_bwd_merged(3) == -3
+    try:
+        sa.sattn_set_bwd_merged(1)
+        assert sa.sattn_bwd_merged(8, 16, 4096, True)
+        sa.sattn_set_bwd_merged(2)
+        assert not sa.sattn_bwd_merged(4, 12, 1024)
+    finally:
+        sa.sattn_set_bwd_merged(0)
+    assert sa.sattn_bwd_merged(4, 12, 1024)
+
+
 def test_forward_shape_choice(lib):
     # d = 64 always takes 4-wave workgroups; d = 128 while the grid is small (one per compute unit,
     # three-slot V ring) or the key loop short (two per compute unit, two-slot V ring)
