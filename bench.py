@@ -75,6 +75,54 @@ def cpu_baseline(cfg, seconds_hint=30.0):
     }
 
 
+def paper_shape_sweep():
+    """Sigmoid against softmax kernel times on the shape of the paper's kernel benchmark
+    (Appendix F.2: batch 32, 12 heads, d = 64, sequence lengths 64 ... 64k, full and causal),
+    as a markdown table: each kernel alone, back-to-back launches between one event pair, the
+    minimum over a few repetitions.  `like for like` pairs kernels at the same level of tuning:
+    forwards both hand-pinned (d = 64 has no 64-row shape, so that is the product forward),
+    backwards both compiler-scheduled (the softmax backward has no other form)."""
+    import torch
+    import paper_2409_04431_amd as sa
+
+    def t(fn, n):
+        for _ in range(2):
+            fn()
+        torch.cuda.synchronize()
+        e = _events(2)
+        e[0].record()
+        for _ in range(n):
+            fn()
+        e[1].record()
+        torch.cuda.synchronize()
+        return e[0].elapsed_time(e[1]) / n
+    B, H, d = 32, 12, 64
+    print("| N | mask | sigmoid fwd ms | softmax fwd ms | fwd change | sigmoid fwd+bwd ms | softmax fwd+bwd ms | "
+          "fwd+bwd change | sigmoid bwd (compiler-scheduled) ms | softmax bwd ms | like-for-like bwd change | "
+          "like-for-like fwd+bwd change |")
+    print("|---|---|---|---|---|---|---|---|---|---|---|---|")
+    for N in (64, 256, 1024, 4096, 16384, 65536):
+        q, k, v, do = (torch.randn(B, H, N, d, device="cuda").bfloat16() for _ in range(4))
+        o, dq, dk, dv = (torch.empty_like(q) for _ in range(4))
+        lse = torch.empty(B, H, N, device="cuda")
+        ws = torch.empty(sa.softmax_attn_bwd_workspace_bytes(B, H, N, d), dtype=torch.uint8, device="cuda")
+        bias = -math.log(N)
+        n = 50 if N <= 4096 else (5 if N <= 16384 else 2)
+        reps = 3 if N <= 16384 else 1
+        for c in (False, True):
+            best = lambda fn: min(t(fn, n) for _ in range(reps))
+            sf = best(lambda: sa.sigmoid_attn_fwd(q, k, v, o, bias, c))
+            mf = best(lambda: sa.softmax_attn_fwd(q, k, v, o, lse, c))
+            sb = best(lambda: sa.sigmoid_attn_bwd(q, k, v, do, dq, dk, dv, bias, c))
+            mb = best(lambda: sa.softmax_attn_bwd(q, k, v, o, lse, do, dq, dk, dv, c, workspace=ws))
+            cb = best(lambda: sa.sigmoid_attn_bwd_compiler_scheduled(q, k, v, do, dq, dk, dv, bias, c))
+            print(f"| {N} | {'causal' if c else 'full'} | {sf:.3f} | {mf:.3f} | {100 * (sf / mf - 1):+.1f} % | {sf + sb:.3f} | "
+                  f"{mf + mb:.3f} | {100 * ((sf + sb) / (mf + mb) - 1):+.1f} % | {cb:.3f} | {mb:.3f} | {100 * (cb / mb - 1):+.1f} % | "
+                  f"{100 * ((sf + cb) / (mf + mb) - 1):+.1f} % |", flush=True)
+        del q, k, v, do, o, dq, dk, dv, lse, ws
+        torch.cuda.empty_cache()
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -87,6 +135,8 @@ def main():
     ap.add_argument("--softmax", action="store_true", help="accepted for compatibility: the comparison is on by default")
     ap.add_argument("--norm", action="store_true",
                     help="also time the hybrid-norm kernels (LayerNorm over the concatenated heads) on this workload's O")
+    ap.add_argument("--paper-shape-sweep", action="store_true",
+                    help="print sigmoid vs softmax kernel times on the paper's kernel-benchmark shape (a table, not the JSON line)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain 256 MiB -> 256 MiB elementwise copy kernel (scales the HBM byte counters)")
     args = ap.parse_args()
@@ -108,6 +158,9 @@ def main():
         print(json.dumps({"calibrate_copy_bytes_read": a.numel() * 4, "calibrate_copy_bytes_written": b.numel() * 4}))
         return
     sa.load_library()
+    if args.paper_shape_sweep:
+        paper_shape_sweep()
+        return
     cfg = W.CONFIGS[args.cfg]
     dev = torch.device("cuda:0")
     torch.manual_seed(1000 + cfg.cfg)

@@ -828,8 +828,12 @@ __device__ __forceinline__ void attn_bwd_body(const BwdParams& p, const int logi
   clock_probe_end(p.clock, clk);
 }
 
+// At d = 64 the ring takes 64 KB, so two workgroups fit a compute unit if the kernel stays within
+// 256 registers.  The compiler-scheduled forms (softmax, PIN = false) need that second wave per
+// SIMD to hide their schedule and sit right at the limit, so they are held to it; the pinned
+// forms use more VGPRs than a two-wave split of the register file leaves (128 + 128).
 template <int D, int MODE, bool CAUSAL, bool ALIBI, bool SOFTMAX, bool PIN = true, bool GROUPS = false>
-__global__ void __launch_bounds__(256, 1)
+__global__ void __launch_bounds__(256, ((D == 64 && (SOFTMAX || !PIN)) ? 2 : 1))
 attn_bwd_kernel(const BwdParams p) {
   const int kv_group = (MODE == BWD_DKDV && !GROUPS) ? 1 : p.kv_group;
   const int total = p.n_blocks * p.B * (MODE == BWD_DKDV ? p.H / kv_group : p.H);
