@@ -554,6 +554,73 @@ def test_varlen_bias_gradient_matches_per_sequence_calls_and_oracle(d, causal, a
         np.testing.assert_allclose(db[s_].cpu().numpy(), ref[0].sum(-1), rtol=2e-4, atol=2e-4 * np.abs(ref).max() * n)
 
 
+# ------------------------------------------------------------------ seeded random shapes and launch forms
+
+def _random_cases(n, seed=2024):
+    rng = np.random.default_rng(seed)
+    cases = []
+    for i in range(n):
+        d = int(rng.choice([64, 128]))
+        B, H = int(rng.integers(1, 4)), int(rng.integers(1, 5))
+        kind = i % 3
+        if kind == 0:      # around a tile boundary
+            N = max(1, int(rng.integers(1, 22)) * 64 + int(rng.integers(-2, 3)))
+        elif kind == 1:    # exact multiples of the 128-row block
+            N = int(rng.integers(1, 11)) * 128
+        else:
+            N = int(rng.integers(1, 1400))
+        cases.append(dict(B=B, H=H, N=N, d=d, causal=bool(rng.integers(0, 2)), alibi=bool(rng.integers(0, 2)),
+                          layout=str(rng.choice(["bhnd", "bnhd"])), waves=int(rng.choice([0, 4, 8, 64])),
+                          vslots=int(rng.choice([0, 2, 3])), merged=int(rng.integers(0, 3)),
+                          bias=float(rng.uniform(-8.0, 1.0)), scale=float(rng.choice([0.5, 1.0, 2.0])), seed=1000 + i))
+    return cases
+
+
+@pytest.mark.parametrize("c", _random_cases(72), ids=lambda c: "B{B}H{H}N{N}d{d}{causal:d}{alibi:d}{layout}w{waves}v{vslots}m{merged}".format(**c))
+def test_seeded_random_shapes_layouts_and_launch_forms_match_oracle(c):
+    """Shapes, flags, memory layouts ([B,H,N,d] or a [B,N,H,d] buffer seen through strides),
+    forward tile shapes and the one-grid / two-launch forms of the backward drawn from a seeded
+    generator: every output against the oracle, with sentinels around the output buffers."""
+    B, H, N, d = c["B"], c["H"], c["N"], c["d"]
+    inp = _rand_inputs(B, H, N, d, seed=c["seed"], scale=c["scale"])
+    inp["dout"] = (inp["dout"].float() / c["scale"]).to(torch.bfloat16)
+    slopes = W.alibi_slopes(H) if c["alibi"] else None
+    sl = _dev(slopes) if c["alibi"] else None
+
+    def place(t):   # the logical [B,H,N,d] tensor, possibly living in a [B,N,H,d] buffer
+        t = _dev(t)
+        return t.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3) if c["layout"] == "bnhd" else t
+
+    def out():
+        buf, guard = _guarded((B, N, H, d) if c["layout"] == "bnhd" else (B, H, N, d))
+        return (buf.permute(0, 2, 1, 3) if c["layout"] == "bnhd" else buf), guard
+    q, k, v, do = (place(inp[n]) for n in ("q", "k", "v", "dout"))
+    (o, g0), (dq, g1), (dk, g2), (dv, g3) = out(), out(), out(), out()
+    if c["waves"] == 64 and c["alibi"] and not c["causal"]:
+        c = dict(c, waves=0)   # the 64-row kernel has ALiBi only in its causal form; forcing it is an error
+    try:
+        sa.sattn_set_fwd_waves(c["waves"])
+        sa.sattn_set_fwd_v_slots(c["vslots"])
+        sa.sattn_set_bwd_merged(c["merged"])
+        sa.sigmoid_attn_fwd(q, k, v, o, c["bias"], c["causal"], sl)
+        sa.sigmoid_attn_bwd(q, k, v, do, dq, dk, dv, c["bias"], c["causal"], sl)
+        torch.cuda.synchronize()
+    finally:
+        sa.sattn_set_fwd_waves(0)
+        sa.sattn_set_fwd_v_slots(0)
+        sa.sattn_set_bwd_merged(0)
+    for g in (g0, g1, g2, g3):
+        g()
+    f = lambda n: inp[n].double().numpy()
+    ro = orc.sigmoid_attn_fwd(f("q"), f("k"), f("v"), c["bias"], c["causal"], slopes)
+    rq, rk, rv = orc.sigmoid_attn_bwd(f("q"), f("k"), f("v"), f("dout"), c["bias"], c["causal"], slopes)
+    for name, got, ref in (("o", o, ro), ("dq", dq, rq), ("dk", dk, rk), ("dv", dv, rv)):
+        got = got.contiguous()
+        assert not torch.isnan(got).any(), name
+        e, er = nerr(got, ref), row_err(got, ref)
+        assert e <= TOL_BF16 and er <= TOL_BF16, f"{name}: {e:.3e}, worst row {er:.3e}"
+
+
 # ------------------------------------------------------------------ backward as one grid
 
 @pytest.mark.parametrize("B,H,N,d,causal,alibi", [(1, 2, 700, 128, True, True), (2, 3, 333, 64, False, True),
