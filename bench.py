@@ -215,32 +215,62 @@ def main():
     torch.cuda.synchronize()
     sustained_peak = probe_flops / pe[0].elapsed_time(pe[1]) / 1e9
 
-    # The engine clock each kernel actually runs at: one more launch of each with the in-kernel
-    # clock probe on (core cycles / ticks of the constant-rate counter, per workgroup).
-    def clock_under_load(fn, n_wg):
-        buf = torch.zeros(2 * n_wg, dtype=torch.int64, device=dev)
+    # The engine clock each kernel actually runs at, and where a workgroup's time goes: a few
+    # more launches of each with the in-kernel probe on (per workgroup: core cycles, ticks of the
+    # constant-rate counter, and the ticks at which wave 0 issued its first tile product, entered
+    # and left the steady-state loop and began to store its outputs).
+    phases = {}
+
+    def clock_under_load(fn, n_wg, key=None):
+        buf = torch.zeros(8 * n_wg, dtype=torch.int64, device=dev)
+        # the clock needs some tens of milliseconds of the kernel's own load to settle at what the
+        # power management gives it: launch for about 60 ms, the buffer keeps the last launch
+        e = _events(2)
+        e[0].record()
+        fn()
+        e[1].record()
+        torch.cuda.synchronize()
+        n_launch = int(min(400, max(3, 60.0 / max(e[0].elapsed_time(e[1]), 1e-3))))
         sa.sattn_set_clock_probe(buf)
         try:
-            for _ in range(3):   # the clock needs a few launches to settle after the probe above
+            for _ in range(n_launch):
                 fn()
             torch.cuda.synchronize()
         finally:
             sa.sattn_set_clock_probe(None)
-        c = buf.view(-1, 2).double()
-        ticks = c[:, 1].sum().item()
-        return (c[:, 0].sum().item() / ticks * sa.sattn_wall_clock_khz() / 1e3) if ticks > 0 else None
+        c = buf.view(-1, 8).double()
+        c = c[c[:, 1] > 0]          # workgroups that ran (the last launch's values)
+        if c.shape[0] == 0:
+            return None
+        tick_us = 1e3 / sa.sattn_wall_clock_khz()
+        if key:
+            m = c.mean(0)
+            steady_tiles = c[:, 6].sum().item()
+            phases[key] = {
+                "workgroups": int(c.shape[0]), "workgroup_us": m[1].item() * tick_us,
+                "to_first_product_us": m[2].item() * tick_us,
+                "before_steady_loop_us": (m[3] - m[2]).item() * tick_us,
+                "steady_loop_us": (m[4] - m[3]).item() * tick_us,
+                "after_steady_loop_us": (m[5] - m[4]).item() * tick_us,
+                "store_us": (m[1] - m[5]).item() * tick_us,
+                "tiles": m[7].item(), "steady_tiles": m[6].item(),
+                "us_per_steady_tile": ((c[:, 4] - c[:, 3]).sum().item() * tick_us / steady_tiles) if steady_tiles else None,
+            }
+        return c[:, 0].sum().item() / c[:, 1].sum().item() * sa.sattn_wall_clock_khz() / 1e3
     clocks = {}
     if cfg.dtype == torch.bfloat16:
         n_wg = cfg.B * cfg.H * ((cfg.N + 127) // 128)
-        clocks["fwd"] = clock_under_load(lambda: sa.sigmoid_attn_fwd(q, k, v, o, bias, cfg.causal, slopes), n_wg)
+        clocks["fwd"] = clock_under_load(lambda: sa.sigmoid_attn_fwd(q, k, v, o, bias, cfg.causal, slopes), n_wg, "fwd")
         if one_grid:
             clocks["bwd"] = clock_under_load(
                 lambda: sa.sigmoid_attn_bwd(q, k, v, dout, dq, dk, dv, bias, cfg.causal, slopes), 2 * n_wg)
+            clock_under_load(lambda: sa.sigmoid_attn_bwd_dkdv(q, k, v, dout, dk, dv, bias, cfg.causal, slopes), n_wg, "bwd_dkdv")
+            clock_under_load(lambda: sa.sigmoid_attn_bwd_dq(q, k, v, dout, dq, bias, cfg.causal, slopes), n_wg, "bwd_dq")
         elif cfg.backward:
             clocks["bwd_dkdv"] = clock_under_load(
-                lambda: sa.sigmoid_attn_bwd_dkdv(q, k, v, dout, dk, dv, bias, cfg.causal, slopes), n_wg)
+                lambda: sa.sigmoid_attn_bwd_dkdv(q, k, v, dout, dk, dv, bias, cfg.causal, slopes), n_wg, "bwd_dkdv")
             clocks["bwd_dq"] = clock_under_load(
-                lambda: sa.sigmoid_attn_bwd_dq(q, k, v, dout, dq, bias, cfg.causal, slopes), n_wg)
+                lambda: sa.sigmoid_attn_bwd_dq(q, k, v, dout, dq, bias, cfg.causal, slopes), n_wg, "bwd_dq")
 
     def stats(i):   # mean / median / min of kernel i's HIP-event durations over the timed steps
         ts = sorted(e[i].elapsed_time(e[i + 1]) for e in evs)
@@ -278,6 +308,8 @@ def main():
                    # measured inside the kernels (sattn_set_clock_probe): the clock drops under matrix
                    # load, so the nominal 2.5 PFLOP/s (2.4 GHz) is not reachable by any kernel
                    "engine_clock_mhz_under_load": clocks},
+        # mean over the workgroups of one probed launch (wave 0 of each): where a workgroup's time goes
+        "workgroup_phases_us": phases,
         "bounds": bounds, "fwd_ms_stats": stats(0),
         "fwd_waves_per_workgroup": (sa.sattn_fwd_waves(cfg.B, cfg.H, cfg.N, cfg.d, cfg.causal)
                                     if cfg.dtype == torch.bfloat16 else None),

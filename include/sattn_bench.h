@@ -79,14 +79,18 @@ int sigmoid_attn_bwd_compiler_scheduled(const void* q, const void* k, const void
  * receives one value per lane (keeps the loop alive).  Returns 0 or SATTN_ERR_*. */
 int sattn_mfma_bf16_probe(int blocks, int iters, float* sink, void* stream);
 
-/* Measurement aid: the engine clock a kernel actually runs at.  While a device buffer of
- * 2 * capacity int64 is set (NULL = off; process-wide like the tile-shape setters, same
- * threading rule), every bf16 attention kernel launched by this library has workgroup w <
- * capacity write out[2w] = core cycles and out[2w+1] = ticks of the constant-rate counter
- * (hipDeviceAttributeWallClockRate, in kHz) it spent in the kernel.  sum(cycles) / sum(ticks) *
- * tick rate is the clock under that kernel's load, which on this part lies well below the
- * nominal peak clock that the 2.5 PFLOP/s figure assumes.  Workgroups that exit at once (blocks
- * beyond a sequence's length) write nothing: clear the buffer first.  8-byte aligned. */
+/* Measurement aid: the engine clock a kernel actually runs at, and where a workgroup's time
+ * goes.  While a device buffer of 8 * capacity int64 is set (NULL = off; process-wide like the
+ * tile-shape setters, same threading rule), every bf16 attention kernel launched by this
+ * library has workgroup w < capacity write out[8w] = core cycles and out[8w+1] = ticks of the
+ * constant-rate counter (hipDeviceAttributeWallClockRate, in kHz) it spent in the kernel;
+ * sum(cycles) / sum(ticks) * tick rate is the clock under that kernel's load, which on this part
+ * lies well below the nominal peak clock that the 2.5 PFLOP/s figure assumes.  out[8w+2..5] are
+ * the ticks since the kernel's start at which wave 0 of the workgroup issued its first tile
+ * product, entered its steady-state loop, left it, and began to store its outputs; out[8w+6]
+ * the tiles it ran in that loop and out[8w+7] the tiles of the workgroup.  Workgroups that exit
+ * at once (blocks beyond a sequence's length) write nothing: clear the buffer first.  8-byte
+ * aligned. */
 int sattn_set_clock_probe(void* device_buffer, int capacity);
 /* Rate of that constant-rate counter on the current device in kHz, or SATTN_ERR_LAUNCH. */
 int sattn_wall_clock_khz(void);

@@ -538,14 +538,15 @@ def softmax_attn_bwd_noalloc(q, k, v, o, lse, dout, dq, dk, dv, causal=False, al
 
 
 def sattn_set_clock_probe(buf):
-    """buf: a zeroed CUDA int64 tensor of 2 * capacity elements, or None to switch the probe off."""
+    """buf: a zeroed CUDA int64 tensor of 8 * capacity elements (eight values per workgroup), or
+    None to switch the probe off."""
     lib = load_library()
     if buf is None:
         _raise(lib.sattn_set_clock_probe(None, 0), "sattn_set_clock_probe")
         return
     if not buf.is_cuda or buf.dtype != torch.int64 or not buf.is_contiguous():
         raise SattnError("the clock buffer must be a contiguous CUDA int64 tensor")
-    _raise(lib.sattn_set_clock_probe(buf.data_ptr(), buf.numel() // 2), "sattn_set_clock_probe")
+    _raise(lib.sattn_set_clock_probe(buf.data_ptr(), buf.numel() // 8), "sattn_set_clock_probe")
 
 
 def sattn_wall_clock_khz():

@@ -191,15 +191,14 @@ FwdShape pick_fwd_shape(int B, int H, int N, int d, int causal, bool allow64 = t
     const int64_t cus = compute_units();
     const int64_t avg_tiles = (causal ? (N + 1) / 2 : N) / 64;  // 64-key tiles a workgroup visits on average
     if (wg4 <= (causal ? cus + cus / 2 : cus)) s = FwdShape{4, 3};
-    else if (avg_tiles <= 48) s = FwdShape{4, 2};
-    // Long key loops on a well-filled chip: four waves of 64 query rows, which read half as much
-    // K/V from LDS per MFMA (waves = 64).  From a sweep over B, N and the mask: 3-10 % faster
-    // than the 32-row shapes from 32 tiles per workgroup on without a mask (N >= 2048) when there
-    // are two 256-row workgroups per compute unit, and from 20 tiles on average with the causal
-    // mask (N >= 2560), whose workgroups differ in length, when there are three; slower below.
+    else if (avg_tiles < (causal ? 16 : 48)) s = FwdShape{4, 2};
+    // Long key loops with at least one 256-row workgroup per compute unit: four waves of 64 query
+    // rows, which read half as much K/V from LDS per MFMA (waves = 64).  From a sweep over B, N
+    // and the mask (with the causal launches walking several heads abreast, head_and_rank): 3-12 %
+    // faster than the best 32-row shape from 16 tiles per workgroup on average with the causal
+    // mask (N >= 2048) and from 24 without (N >= 1536); slower below.
     const int64_t wg64 = (int64_t)B * H * ((N + 255) / 256);
-    if (allow64 && (causal ? (avg_tiles >= 20 && wg64 >= 3 * cus) : (avg_tiles >= 32 && wg64 >= 2 * cus)))
-      s = FwdShape{64, 3};
+    if (allow64 && wg64 >= cus && avg_tiles >= (causal ? 16 : 24)) s = FwdShape{64, 3};
   }
   const int forced_vslots = g_fwd_vslots.load(std::memory_order_relaxed);
   if (forced_waves) {
@@ -214,15 +213,14 @@ FwdShape pick_fwd_shape(int B, int H, int N, int d, int causal, bool allow64 = t
 
 // The two passes of the sigmoid backward as one grid (where the launcher has that form: both
 // passes asked for, self-attention, one K/V head per query head).  It pays while a pass alone
-// leaves compute units idle in its last rounds of workgroups: measured 8-26 % faster with the
-// causal mask (uneven workgroups) up to 8 workgroups per pass and compute unit and 1.5 % at
-// 16, 11 % without a mask at 1.5 per unit and 1 % slower from 4 on; 10 % slower on very large
-// grids (48 per unit, d = 64), where the two passes compete for the L2.
+// cannot fill the chip: measured 10-28 % faster below two workgroups per pass and compute unit
+// (three without the causal mask), equal within 1.5 % from there to 16, and 9 % slower on very
+// large grids (48 per unit, d = 64), where the two passes compete for the L2.
 bool pick_bwd_merged(int B, int H, int N, int causal) {
   const int mode = g_bwd_merged.load(std::memory_order_relaxed);
   if (mode) return mode == 1;
   const int64_t wgs = (int64_t)B * H * ((N + 127) / 128), cus = compute_units();
-  return causal ? wgs < 16 * cus : wgs < 3 * cus;
+  return wgs < (causal ? 2 : 3) * cus;
 }
 
 int check_shape(int B, int H, int N, int d, sattn_dtype dt) {

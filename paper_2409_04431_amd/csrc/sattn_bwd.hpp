@@ -40,6 +40,7 @@ struct BwdParams {
   int npad;
   int B, H, N;
   int n_blocks;        // blocks of 128 stationary rows
+  int head_group;      // causal: heads walked abreast in the dispatch order (head_and_rank); 1 otherwise
   float nscale_log2;   // -log2(e)/sqrt(d)
   float nbias_log2;    // -b*log2(e)
   float inv_sqrt_d;
@@ -517,14 +518,15 @@ __device__ __forceinline__ void attn_bwd_body(const BwdParams& p, const int logi
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, h = lane >> 5;
   const int uwave = __builtin_amdgcn_readfirstlane(wave);
-  const ClockStart clk = clock_probe_begin(p.clock);
+  ClockStart clk = clock_probe_begin(p.clock);
   // the dK/dV pass runs one workgroup per K/V head and key block and streams the query heads
   // of that head's group one after the other; the dQ pass runs per query head
   const int kv_group = (MODE == BWD_DKDV && !GROUPS) ? 1 : p.kv_group;
   const int heads = MODE == BWD_DKDV ? p.H / kv_group : p.H;
-  const int bh = logical / p.n_blocks;
+  int bh, rank;
+  head_and_rank(logical, p.n_blocks, p.B * heads, CAUSAL ? p.head_group : 1, bh, rank);
   // causal: heavy blocks first (late query blocks for DQ, early key blocks for DKDV)
-  const int blk = (CAUSAL && MODE != BWD_DKDV) ? (p.n_blocks - 1 - logical % p.n_blocks) : (logical % p.n_blocks);
+  const int blk = (CAUSAL && MODE != BWD_DKDV) ? (p.n_blocks - 1 - rank) : rank;
   const int b = bh / heads, hd = bh % heads;  // hd: K/V head (dK/dV pass) or query head (dQ pass)
   const int hkv = MODE == BWD_DKDV ? hd : hd / kv_group;
   const int hq0 = MODE == BWD_DKDV ? hd * kv_group : hd, n_hq = MODE == BWD_DKDV ? kv_group : 1;
@@ -668,6 +670,7 @@ __device__ __forceinline__ void attn_bwd_body(const BwdParams& p, const int logi
     SATTN_WAIT_VMCNT(0);
   }
   __syncthreads();
+  clock_probe_mark(p.clock, clk, kMarkFirstProduct);
   // rows of chunk 2*t_lo for the first step
 #pragma unroll
   for (int kk = 0; kk < KD; ++kk) {
@@ -780,6 +783,8 @@ __device__ __forceinline__ void attn_bwd_body(const BwdParams& p, const int logi
     }
     if constexpr (PIN && !SOFTMAX) if (phase == 0) {
       const bool any_steady = t <= t_s1;
+      clock_probe_mark(p.clock, clk, kMarkSteadyBegin);
+      const int t_steady_begin = t;
       // (a ragged tensor's steady loop ends early enough that its stagers never reach the end)
       const int n_sat = Nt % BC == 0 ? Nt : 0x7fffff00;
       if (any_steady) {
@@ -797,6 +802,9 @@ __device__ __forceinline__ void attn_bwd_body(const BwdParams& p, const int logi
         rotate(t);
       }
       if (any_steady) mfma_settle();  // once for the whole loop of pinned steps
+      clock_probe_mark(p.clock, clk, kMarkSteadyEnd);
+      clk.steady_tiles = t - t_steady_begin;
+      clk.tiles = t_hi + 1 - t_lo;
     }
     general_end = t_hi + 1;
   }
@@ -811,6 +819,7 @@ __device__ __forceinline__ void attn_bwd_body(const BwdParams& p, const int logi
     rs += __shfl_xor(rs, 32);
     if (h == 0 && ai < Ns) p.db_rows[b * p.db_sb + hq0 * p.db_sh + tok0 + ai] = rs;
   }
+  clock_probe_mark(p.clock, clk, kMarkStore);
   // Outputs as whole rows, transposed through the ring (free once every wave has left the loop).
   __syncthreads();
   {

@@ -18,6 +18,7 @@ int launch_bwd_variant(BwdParams p, int causal, bool alibi, int parts, bool merg
     // self-attention with one K/V head per query head and both passes wanted: one grid
     if (parts == (kBwdDkDv | kBwdDq) && p.kv_group == 1 && nb_q == nb_k && p.Nk == 0 && !p.db_rows && merged) {
       p.n_blocks = nb_q;
+      p.head_group = heads_abreast(nb_q);
       dim3 grid2(2 * nb_q * p.B * p.H);
       SATTN_DISPATCH2(causal, alibi, rc = launch(attn_bwd_merged_kernel<D, A, B2>, grid2, block, lds, st, p));
       return rc;
@@ -25,6 +26,7 @@ int launch_bwd_variant(BwdParams p, int causal, bool alibi, int parts, bool merg
   }
   if (parts & kBwdDkDv) {
     p.n_blocks = nb_k;
+    p.head_group = heads_abreast(nb_k);
     if constexpr (!SOFTMAX && PIN) {
       if (p.kv_group > 1)  // one workgroup per K/V head streams the query heads of its group
         SATTN_DISPATCH2(causal, alibi,
@@ -35,6 +37,7 @@ int launch_bwd_variant(BwdParams p, int causal, bool alibi, int parts, bool merg
                       rc = launch(attn_bwd_kernel<D, BWD_DKDV, A, B2, SOFTMAX, PIN>, grid_k, block, lds, st, p));
   }
   p.n_blocks = nb_q;
+  p.head_group = heads_abreast(nb_q);
   if (rc == SATTN_OK && (parts & kBwdDq)) {
     if constexpr (!SOFTMAX && PIN) {
       if (p.db_rows) {  // the dQ pass that also writes the row sums of dS

@@ -112,25 +112,39 @@ struct RowStore {
   }
 };
 
-// Measurement aid: when `out` is set, workgroup w < cap writes the core cycles and the ticks of
-// the constant-rate counter it spent in the kernel to out[2w], out[2w+1]; their ratio is the
-// engine clock the kernel actually ran at (the clock drops under matrix load).
+// Measurement aid: when `out` is set, workgroup w < cap writes eight values to out[8w ..]:
+// [0] the core cycles and [1] the ticks of the constant-rate counter it spent in the kernel
+// (their ratio is the engine clock the kernel actually ran at: the clock drops under matrix
+// load), then the ticks since the kernel's start at which wave 0 [2] issued its first tile
+// product, [3] entered and [4] left the steady-state loop of pinned steps, [5] began to store
+// its outputs, and [6] the tiles it ran in that loop, [7] the tiles of the workgroup.
 struct ClockProbe {
   long long* out;
   int cap;
 };
 struct ClockStart {
   long long cycles, ticks;
+  int mark[4];   // phase stamps, ticks since `ticks`
+  int steady_tiles, tiles;
 };
+enum ClockMark { kMarkFirstProduct = 0, kMarkSteadyBegin = 1, kMarkSteadyEnd = 2, kMarkStore = 3 };
 __device__ __forceinline__ ClockStart clock_probe_begin(const ClockProbe& c) {
-  ClockStart s{0, 0};
+  ClockStart s{0, 0, {0, 0, 0, 0}, 0, 0};
   if (c.out) { s.cycles = clock64(); s.ticks = wall_clock64(); }
   return s;
 }
+__device__ __forceinline__ void clock_probe_mark(const ClockProbe& c, ClockStart& s, int which) {
+  if (c.out) s.mark[which] = (int)(wall_clock64() - s.ticks);
+}
 __device__ __forceinline__ void clock_probe_end(const ClockProbe& c, const ClockStart& s) {
   if (c.out && threadIdx.x == 0 && (int)blockIdx.x < c.cap) {
-    c.out[2 * (int64_t)blockIdx.x] = clock64() - s.cycles;
-    c.out[2 * (int64_t)blockIdx.x + 1] = wall_clock64() - s.ticks;
+    long long* o = c.out + 8 * (int64_t)blockIdx.x;
+    o[0] = clock64() - s.cycles;
+    o[1] = wall_clock64() - s.ticks;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) o[2 + i] = s.mark[i];
+    o[6] = s.steady_tiles;
+    o[7] = s.tiles;
   }
 }
 
@@ -142,6 +156,21 @@ __device__ __forceinline__ int xcd_remap(int bid, int total) {
   int xcd = bid % kXcd, slot = bid / kXcd;
   int c = total / kXcd, r = total % kXcd;
   return xcd * c + (xcd < r ? xcd : r) + slot;
+}
+
+// Place of a workgroup in its launch -> (head, rank of the block in that head's dispatch
+// order).  With group > 1 consecutive places walk one rank over `group` heads before moving on
+// to the next rank.  A causal head's blocks differ widely in length and are dispatched longest
+// first; when a head has fewer blocks than an XCD has compute units, the units would otherwise
+// hold the short tail of one head next to the long start of the next all the time, and the
+// launch ends with long blocks still running on a few units.  Walking a few heads abreast keeps
+// blocks of similar length together and the short ones for the end.
+__device__ __forceinline__ void head_and_rank(int place, int n_blocks, int n_heads, int group, int& head, int& rank) {
+  const int per_group = group * n_blocks;
+  const int G = place / per_group, r = place - G * per_group;
+  const int left = n_heads - G * group, g_this = left < group ? left : group;
+  rank = r / g_this;
+  head = G * group + (r - rank * g_this);
 }
 
 }  // namespace sattn

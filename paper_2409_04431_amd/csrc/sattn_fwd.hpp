@@ -28,6 +28,7 @@ struct FwdParams {
   float* lse;           // softmax only: [B,H,N]
   int B, H, N;
   int n_qblocks;
+  int head_group;     // causal: heads walked abreast in the dispatch order (head_and_rank); 1 otherwise
   float nscale_log2;  // -log2(e)/sqrt(d)   (softmax: +log2(e)/sqrt(d))
   float nbias_log2;   // -b*log2(e)
   // variable-length batches (nullptr otherwise): sequence b owns tokens cu_seqlens[b] ..
@@ -588,13 +589,14 @@ attn_fwd_kernel(const FwdParams p) {
   const int tid = threadIdx.x;
   const int wave = tid >> 6, lane = tid & 63;
   const int l32 = lane & 31, h = lane >> 5;
-  const ClockStart clk = clock_probe_begin(p.clock);
+  ClockStart clk = clock_probe_begin(p.clock);
 
   const int total = p.n_qblocks * p.B * p.H;
   const int logical = xcd_remap(blockIdx.x, total);
-  const int bh = logical / p.n_qblocks;
+  int bh, rank;
+  head_and_rank(logical, p.n_qblocks, p.B * p.H, CAUSAL ? p.head_group : 1, bh, rank);
   // causal: heavy (late) query blocks first
-  const int qb = CAUSAL ? (p.n_qblocks - 1 - logical % p.n_qblocks) : (logical % p.n_qblocks);
+  const int qb = CAUSAL ? (p.n_qblocks - 1 - rank) : rank;
   const int b = bh / p.H, hd = bh % p.H;
   int N = p.N;
   int64_t tok0 = 0;
@@ -683,6 +685,7 @@ attn_fwd_kernel(const FwdParams p) {
   SATTN_WAIT_VMCNT(0);  // prologue tiles landed; the Q fragment is in registers
   __syncthreads();
 
+  clock_probe_mark(p.clock, clk, kMarkFirstProduct);
   // step -1: S^T(0) into s[0], then fetch K(1)
   if (cw > 0) {
 #pragma unroll
@@ -699,6 +702,9 @@ attn_fwd_kernel(const FwdParams p) {
 #pragma unroll
   for (int kk = 0; kk < KD; ++kk) W.koff[kk] += TILE;  // K reads now point at tile 1
   int kslot = 0;  // ring slot of K tile t == slot that K(t+3) will overwrite; with VS = 3 V tile t is in the same slot index
+  // (this kernel picks the form of every step on the fly: its whole tile loop counts as steady)
+  clock_probe_mark(p.clock, clk, kMarkSteadyBegin);
+  clk.steady_tiles = clk.tiles = n_tiles;
   for (int t = 0; t < n_tiles; ++t) {
     const bool k_more = t + 3 < n_tiles, v_more = t + (VS == 3 ? 2 : 1) < n_tiles;
     if (VS == 3) {
@@ -730,8 +736,10 @@ attn_fwd_kernel(const FwdParams p) {
     }
     __syncthreads();
   }
+  clock_probe_mark(p.clock, clk, kMarkSteadyEnd);
   // flush: O^T update of the last chunk when it fell on the last step of the loop
   if (cw == 2 * n_tiles && cw > 0) fwd_step<D, ALIBI, SOFTMAX, STEP_TAIL, 0, FOLD>(W, 0, 0, 0, Nk, CAUSAL);
+  clock_probe_mark(p.clock, clk, kMarkStore);
 
   if (SOFTMAX) {
     // normalise by the row sum (both lane halves) and write the natural-log row log-sum-exp

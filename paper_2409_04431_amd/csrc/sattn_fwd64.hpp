@@ -237,12 +237,13 @@ attn_fwd64_kernel(const FwdParams p) {
   const int tid = threadIdx.x;
   const int wave = tid >> 6, lane = tid & 63;
   const int l32 = lane & 31, h = lane >> 5;
-  const ClockStart clk = clock_probe_begin(p.clock);
+  ClockStart clk = clock_probe_begin(p.clock);
 
   const int total = p.n_qblocks * p.B * p.H;
   const int logical = xcd_remap(blockIdx.x, total);
-  const int bh = logical / p.n_qblocks;
-  const int qb = CAUSAL ? (p.n_qblocks - 1 - logical % p.n_qblocks) : (logical % p.n_qblocks);  // causal: heavy first
+  int bh, rank;
+  head_and_rank(logical, p.n_qblocks, p.B * p.H, CAUSAL ? p.head_group : 1, bh, rank);
+  const int qb = CAUSAL ? (p.n_qblocks - 1 - rank) : rank;  // causal: heavy first
   const int b = bh / p.H, hd = bh % p.H;
   int N = p.N;
   int64_t tok0 = 0;
@@ -360,6 +361,7 @@ attn_fwd64_kernel(const FwdParams p) {
   SATTN_WAIT_VMCNT(0);  // prologue tiles landed; the Q fragments are in registers
   __syncthreads();
 
+  clock_probe_mark(p.clock, clk, kMarkFirstProduct);
   // step -1: S^T(0) into s[0], then fetch K(1).  (cw[1] is either 0, row block 1 lying past
   // the end, or >= cw[0].)
   if (cw[0] > 0) {
@@ -387,6 +389,7 @@ attn_fwd64_kernel(const FwdParams p) {
   // variant of a tile has its one barrier at the same place, so the waves of a workgroup may be
   // in different loops.
   int t = 0;
+  clock_probe_mark(p.clock, clk, kMarkSteadyBegin);
   if constexpr (D == 128) {
     static_assert(NIK == 4 && NIV == 4, "four staging instructions per wave and tile");
     const int t_full = (cw[0] - 1) / 2;       // tiles t < t_full: 2t + 2 < cw[0]
@@ -406,6 +409,9 @@ attn_fwd64_kernel(const FwdParams p) {
       f64_settle();  // the compiler does not know the statements above are MFMAs
     }
   }
+  clock_probe_mark(p.clock, clk, kMarkSteadyEnd);
+  clk.steady_tiles = t;
+  clk.tiles = n_tiles;
   // The remaining tiles take the ring position from t: K reads at slot (t+1)%3, V reads at t%3.
   int kslot = t % 3;  // ring slot of K tile t == slot that K(t+3) will overwrite; V tile t is in the same slot index
   {
@@ -463,6 +469,7 @@ attn_fwd64_kernel(const FwdParams p) {
   // flush: O^T update of the last chunk when it fell on the last step of the loop
   run_step(std::integral_constant<int, 0>{}, 2 * n_tiles);
 
+  clock_probe_mark(p.clock, clk, kMarkStore);
   // ---- store O (bf16).  Register 4g+t of tile dt is O[qi][32dt + 8g + 4h + t]: a lane holds 4
   // consecutive features of ITS row, so storing from the registers would scatter 8-byte pieces
   // over 64 rows per instruction.  The wave instead transposes through its own 17 KB of the (now

@@ -9,6 +9,7 @@ template <int D, int NW, int VS, bool SOFTMAX, bool PIN>
 int launch_fwd_variant(FwdParams p, int causal, bool alibi, hipStream_t st) {
   constexpr size_t lds = (3 + VS) * 64 * D * 2;  // 3 K slots + VS V slots of 64 keys
   p.n_qblocks = (p.N + 32 * NW - 1) / (32 * NW);
+  p.head_group = heads_abreast(p.n_qblocks);
   dim3 grid(p.n_qblocks * p.B * p.H), block(64 * NW);
   int rc = SATTN_OK;
   SATTN_DISPATCH2(causal, alibi, rc = launch(attn_fwd_kernel<D, NW, A, B2, SOFTMAX, PIN, VS>, grid, block, lds, st, p));
@@ -31,6 +32,7 @@ int launch_fwd64(FwdParams p, int causal, bool alibi, bool prescale, hipStream_t
   } else {
     constexpr size_t lds = 6 * 64 * D * 2;  // 3 K slots + 3 V slots of 64 keys
     p.n_qblocks = (p.N + 255) / 256;
+    p.head_group = heads_abreast(p.n_qblocks);
     dim3 grid(p.n_qblocks * p.B * p.H), block(256);
     if (alibi && !causal) return SATTN_ERR_UNSUPPORTED;
     if (alibi) return launch(attn_fwd64_kernel<D, true, true, false>, grid, block, lds, st, p);

@@ -49,6 +49,14 @@ int launch(K kernel, dim3 grid, dim3 block, size_t lds, hipStream_t st, Args... 
 
 enum BwdPart { kBwdDkDv = 1, kBwdDq = 2 };
 
+// Heads walked abreast in the dispatch order of a causal launch (head_and_rank): enough of them
+// that one rank of blocks covers the 32 compute units of an XCD, at most 8 (their K/V should
+// stay in the XCD's L2 together).
+inline int heads_abreast(int n_blocks) {
+  const int g = n_blocks > 0 ? 32 / n_blocks : 1;
+  return g < 1 ? 1 : (g > 8 ? 8 : g);
+}
+
 // Forward: `waves` (4 or 8) is the number of 32-query-row waves per workgroup (sets
 // p.n_qblocks accordingly), `v_slots` (2 or 3) the depth of the V ring of 4-wave workgroups
 // at D = 128.  softmax selects the comparison kernel, pin the hand-ordered step.

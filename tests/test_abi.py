@@ -114,8 +114,9 @@ def test_varlen_bias_gradient_entry_point_rejects_bad_arguments(lib):
 
 def test_backward_one_grid_choice(lib):
     # small or uneven (causal) grids run both passes of the backward in one launch
-    assert sa.sattn_bwd_merged(4, 12, 1024) and sa.sattn_bwd_merged(8, 16, 2048, True)
+    assert sa.sattn_bwd_merged(4, 12, 1024) and sa.sattn_bwd_merged(1, 16, 2048, True)
     assert not sa.sattn_bwd_merged(8, 16, 4096, True) and not sa.sattn_bwd_merged(8, 16, 1024)
+    assert not sa.sattn_bwd_merged(2, 16, 2048, True)
     assert lib.sattn_bwd_merged(0, 1, 16, 0) == -2 and lib.sattn_set_bwd_merged(3) == -3
     try:
         sa.sattn_set_bwd_merged(1)
@@ -132,10 +133,11 @@ def test_forward_shape_choice(lib):
     # three-slot V ring) or the key loop short (two per compute unit, two-slot V ring)
     assert sa.sattn_fwd_waves(32, 12, 4096, 64) == 4 and sa.sattn_fwd_v_slots(32, 12, 4096, 64) == 3
     assert (sa.sattn_fwd_waves(8, 16, 4096, 128, True), sa.sattn_fwd_v_slots(8, 16, 4096, 128, True)) == (64, 3)
-    # causal: short key loops, or fewer than three 256-row workgroups per compute unit, keep 32-row waves
-    assert (sa.sattn_fwd_waves(8, 16, 2048, 128, True), sa.sattn_fwd_v_slots(8, 16, 2048, 128, True)) == (4, 2)
-    assert (sa.sattn_fwd_waves(2, 16, 4096, 128, True), sa.sattn_fwd_v_slots(2, 16, 4096, 128, True)) == (4, 2)
-    assert sa.sattn_fwd_waves(8, 16, 2048, 128) == 64 and sa.sattn_fwd_waves(8, 16, 1024, 128) != 64
+    # 64-row waves from 2048 tokens with the causal mask, 1536 without, given a 256-row workgroup per compute unit
+    assert sa.sattn_fwd_waves(8, 16, 2048, 128, True) == 64 and sa.sattn_fwd_waves(2, 16, 4096, 128, True) == 64
+    assert (sa.sattn_fwd_waves(8, 16, 1536, 128, True), sa.sattn_fwd_v_slots(8, 16, 1536, 128, True)) == (4, 2)
+    assert (sa.sattn_fwd_waves(1, 16, 2048, 128, True), sa.sattn_fwd_v_slots(1, 16, 2048, 128, True)) == (4, 3)
+    assert sa.sattn_fwd_waves(8, 16, 1536, 128) == 64 and sa.sattn_fwd_waves(8, 16, 1024, 128) == 4
     # long key loops with a workgroup for every compute unit: four waves of 64 query rows
     assert (sa.sattn_fwd_waves(1, 32, 16384, 128, True), sa.sattn_fwd_v_slots(1, 32, 16384, 128, True)) == (64, 3)
     assert sa.sattn_fwd_waves(2, 16, 8192, 128) == 64 and sa.sattn_fwd_waves(8, 16, 4096, 128) == 64
@@ -150,7 +152,8 @@ def test_forward_shape_choice(lib):
         assert sa.sattn_fwd_waves(1, 2, 512, 128) == 8 and sa.sattn_fwd_waves(1, 2, 512, 64) == 8
         assert sa.sattn_fwd_v_slots(8, 16, 4096, 128, True) == 3      # no two-slot ring with 8 waves
         sa.sattn_set_fwd_waves(32)   # the automatic choice held to the 32-row shapes
-        assert (sa.sattn_fwd_waves(8, 16, 4096, 128, True), sa.sattn_fwd_v_slots(8, 16, 4096, 128, True)) == (4, 2)
+        assert (sa.sattn_fwd_waves(8, 16, 4096, 128, True), sa.sattn_fwd_v_slots(8, 16, 4096, 128, True)) == (8, 3)
+        assert (sa.sattn_fwd_waves(8, 16, 1024, 128, True), sa.sattn_fwd_v_slots(8, 16, 1024, 128, True)) == (4, 2)
         assert sa.sattn_fwd_waves(1, 6, 8192, 128) == 8 and sa.sattn_fwd_waves(32, 12, 4096, 64) == 4
         sa.sattn_set_fwd_waves(64)
         assert sa.sattn_fwd_waves(1, 2, 512, 128) == 64 and sa.sattn_fwd_waves(1, 2, 512, 64) == 4

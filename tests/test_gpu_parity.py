@@ -554,6 +554,40 @@ def test_varlen_bias_gradient_matches_per_sequence_calls_and_oracle(d, causal, a
         np.testing.assert_allclose(db[s_].cpu().numpy(), ref[0].sum(-1), rtol=2e-4, atol=2e-4 * np.abs(ref).max() * n)
 
 
+# ------------------------------------------------------------------ measurement aids
+
+def test_clock_probe_records_per_workgroup_and_respects_its_capacity():
+    B, H, N, d = 2, 3, 1024, 128
+    inp = _rand_inputs(B, H, N, d, seed=5)
+    q, k, v, do = (_dev(inp[n]) for n in ("q", "k", "v", "dout"))
+    o, dq, dk, dv = (torch.empty_like(q) for _ in range(4))
+    bias = -math.log(N)
+    ref = torch.empty_like(q)
+    sa.sigmoid_attn_fwd(q, k, v, ref, bias, True)
+    n_wg = B * H * (N // 128)            # workgroups of each backward pass
+    cap = n_wg - 5                        # fewer slots than workgroups: the rest must not write
+    for name, fn in (("fwd", lambda: sa.sigmoid_attn_fwd(q, k, v, o, bias, True)),
+                     ("dkdv", lambda: sa.sigmoid_attn_bwd_dkdv(q, k, v, do, dk, dv, bias, True)),
+                     ("dq", lambda: sa.sigmoid_attn_bwd_dq(q, k, v, do, dq, bias, True))):
+        buf = torch.zeros(8 * cap + 64, dtype=torch.int64, device="cuda")
+        buf[8 * cap:] = -7
+        sa.sattn_set_clock_probe(buf[:8 * cap])
+        try:
+            fn()
+            torch.cuda.synchronize()
+        finally:
+            sa.sattn_set_clock_probe(None)
+        assert bool((buf[8 * cap:] == -7).all()), name
+        c = buf[:8 * cap].view(-1, 8).cpu()
+        ran = c[c[:, 1] > 0]
+        assert ran.shape[0] > 0, name
+        assert bool((ran[:, 0] > 0).all())                       # core cycles
+        m = ran[:, 2:6]                                           # stamps in order, all before the end
+        assert bool((m[:, 0] > 0).all()) and bool((m[:, 1:] >= m[:, :-1]).all()) and bool((m[:, 3] <= ran[:, 1]).all()), name
+        assert bool((ran[:, 6] <= ran[:, 7]).all()) and bool((ran[:, 7] >= 1).all()) and bool((ran[:, 7] <= N // 64 + 1).all()), name
+    assert torch.equal(o, ref)   # the probe does not change results
+
+
 # ------------------------------------------------------------------ seeded random shapes and launch forms
 
 def _random_cases(n, seed=2024):
