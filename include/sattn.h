@@ -213,9 +213,9 @@ const char* sattn_strerror(int code);
  * heads; any Hkv that divides H is accepted).  Query head h attends to K/V head
  * h / (H / Hkv).  q, o, dout, dq are [B, H, N, d]; k, v, dk, dv are [B, Hkv, N, d] (strides as
  * usual, NULL = contiguous with that head count).  dK/dV of a shared head is the sum over its
- * query heads, accumulated in fp32 inside one workgroup (no atomics, no workspace).  bf16
- * only (SATTN_ERR_UNSUPPORTED for fp32 unless Hkv == H); SATTN_ERR_SHAPE if Hkv does not
- * divide H.  Otherwise as sigmoid_attn_fwd / sigmoid_attn_bwd. */
+ * query heads, accumulated in fp32 inside one workgroup (no atomics, no workspace).  bf16 or
+ * fp32; SATTN_ERR_SHAPE if Hkv does not divide H.  Otherwise as sigmoid_attn_fwd /
+ * sigmoid_attn_bwd. */
 int sigmoid_attn_mqa_fwd(const void* q, const void* k, const void* v, void* o,
                          int B, int H, int Hkv, int N, int d, sattn_dtype dtype,
                          float bias, int causal, const float* alibi_slopes,
@@ -232,7 +232,7 @@ int sigmoid_attn_mqa_bwd(const void* q, const void* k, const void* v, const void
 
 /* Different numbers of queries and keys (the definition of Section 2 with Q of n_q rows and
  * K, V of n_k rows; the paper's models only use n_q = n_k).  q, o, dout, dq are [B,H,Nq,d];
- * k, v, dk, dv are [B,H,Nk,d].  Plain sigmoid attention only: bf16, no causal mask, no ALiBi
+ * k, v, dk, dv are [B,H,Nk,d].  Plain sigmoid attention only (bf16 or fp32): no causal mask, no ALiBi
  * (both are defined by positions that the two sides would have to share), one K/V head per
  * query head; `bias` is the caller's (the paper's rule gives -ln(Nk)).  Otherwise as
  * sigmoid_attn_fwd / sigmoid_attn_bwd. */
@@ -273,7 +273,7 @@ int sigmoid_attn_bwd_bias_grad(const void* q, const void* k, const void* v, cons
  * cu_seqlens[0] >= 0) and attends only to itself.  max_seqlen bounds every length (tokens of
  * a longer sequence beyond it are not written).  bias_per_seq is a device pointer to B floats
  * or NULL (then `bias` applies to every sequence).  Strides: `batch` is ignored, `head` and
- * `seq` (token) as usual; NULL = contiguous [tokens, H, d].  bf16 only.  Same error codes and
+ * `seq` (token) as usual; NULL = contiguous [tokens, H, d].  bf16 or fp32.  Same error codes and
  * stream semantics as the dense entry points; the offsets themselves are not validated. */
 int sigmoid_attn_varlen_fwd(const void* q, const void* k, const void* v, void* o,
                             const int32_t* cu_seqlens, const float* bias_per_seq,

@@ -124,8 +124,9 @@ def sattn_strerror(code):
 def _check_varlen(cu_seqlens, bias_per_seq, *ts):
     t0 = ts[0]
     for t in ts:
-        if not t.is_cuda or t.dim() != 3 or t.shape != t0.shape or t.dtype != torch.bfloat16 or t.stride(2) != 1:
-            raise SattnError("varlen tensors must be CUDA bf16 [tokens, H, d] with a contiguous last dimension")
+        if (not t.is_cuda or t.dim() != 3 or t.shape != t0.shape or t.dtype != t0.dtype
+                or t.dtype not in (torch.bfloat16, torch.float32) or t.stride(2) != 1):
+            raise SattnError("varlen tensors must be CUDA bf16 or fp32 [tokens, H, d] of one dtype with a contiguous last dimension")
     if not cu_seqlens.is_cuda or cu_seqlens.dtype != torch.int32 or cu_seqlens.dim() != 1 or not cu_seqlens.is_contiguous():
         raise SattnError("cu_seqlens must be a contiguous CUDA int32 vector of B+1 offsets")
     B = cu_seqlens.numel() - 1
@@ -147,7 +148,7 @@ def sigmoid_attn_varlen_fwd(q, k, v, o, cu_seqlens, max_seqlen, bias, causal=Fal
     _, H, d = q.shape
     bp = _vp(bias_per_seq.data_ptr()) if bias_per_seq is not None else None
     rc = lib.sigmoid_attn_varlen_fwd(q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(),
-                                     _vp(cu_seqlens.data_ptr()), bp, B, H, int(max_seqlen), d, SATTN_BF16,
+                                     _vp(cu_seqlens.data_ptr()), bp, B, H, int(max_seqlen), d, _dtype_code(q),
                                      float(bias), int(bool(causal)), _slopes_ptr(alibi_slopes, H),
                                      _st3(q), _st3(k), _st3(v), _st3(o), _stream())
     _raise(rc, "sigmoid_attn_varlen_fwd")
@@ -163,7 +164,7 @@ def sigmoid_attn_varlen_bwd(q, k, v, dout, dq, dk, dv, cu_seqlens, max_seqlen, b
     bp = _vp(bias_per_seq.data_ptr()) if bias_per_seq is not None else None
     rc = lib.sigmoid_attn_varlen_bwd(q.data_ptr(), k.data_ptr(), v.data_ptr(), dout.data_ptr(), dq.data_ptr(),
                                      dk.data_ptr(), dv.data_ptr(), _vp(cu_seqlens.data_ptr()), bp, B, H,
-                                     int(max_seqlen), d, SATTN_BF16, float(bias), int(bool(causal)),
+                                     int(max_seqlen), d, _dtype_code(q), float(bias), int(bool(causal)),
                                      _slopes_ptr(alibi_slopes, H), _st3(q), _st3(k), _st3(v), _st3(dout),
                                      _st3(dq), _st3(dk), _st3(dv), _stream())
     _raise(rc, "sigmoid_attn_varlen_bwd")
@@ -186,7 +187,7 @@ def sigmoid_attn_varlen_bwd_bias_grad(q, k, v, dout, dq, dk, dv, db_rows, cu_seq
                                                dk.data_ptr(), dv.data_ptr(), _vp(db_rows.data_ptr()),
                                                _vp(db.data_ptr()) if db is not None else None,
                                                _vp(cu_seqlens.data_ptr()), bp, B, H, int(max_seqlen), int(total), d,
-                                               SATTN_BF16, float(bias), int(bool(causal)), _slopes_ptr(alibi_slopes, H),
+                                               _dtype_code(q), float(bias), int(bool(causal)), _slopes_ptr(alibi_slopes, H),
                                                _st3(q), _st3(k), _st3(v), _st3(dout), _st3(dq), _st3(dk), _st3(dv),
                                                _stream())
     _raise(rc, "sigmoid_attn_varlen_bwd_bias_grad")

@@ -234,7 +234,8 @@ int check_shape(int B, int H, int N, int d, sattn_dtype dt) {
 
 // ---------------------------------------------------------------- forward
 template <int D>
-int launch_fwd_f32(const F32Params& p, int causal, bool alibi, hipStream_t st) {
+int launch_fwd_f32(F32Params p, int causal, bool alibi, hipStream_t st) {
+  p.n_blocks = (p.N + 127) / 128;
   dim3 grid(p.n_blocks * p.B * p.H), block(256);
   int rc = SATTN_OK;
   SATTN_DISPATCH2(causal, alibi, rc = launch(sigmoid_f32_kernel<D, F32_FWD, A, B2>, grid, block, 0, st, p));
@@ -256,7 +257,7 @@ template <typename Args>
 int check_cross(const Args& a, bool softmax, bool pin, int Hkv, int* Nk) {
   *Nk = a.Nk > 0 ? a.Nk : a.N;
   if (*Nk == a.N) return SATTN_OK;
-  if (softmax || !pin || a.dtype != SATTN_BF16 || a.causal || a.slopes || a.cu_seqlens || Hkv != a.H)
+  if (softmax || !pin || a.causal || a.slopes || a.cu_seqlens || Hkv != a.H)
     return SATTN_ERR_UNSUPPORTED;
   return check_shape(a.B, a.H, *Nk, a.d, a.dtype);
 }
@@ -267,7 +268,7 @@ int fwd_impl(const FwdArgs& a) {
   if (rc) return rc;
   const int Hkv = a.Hkv ? a.Hkv : a.H;
   if (Hkv <= 0 || a.H % Hkv) return SATTN_ERR_SHAPE;
-  if (Hkv != a.H && (SOFTMAX || !PIN || a.dtype != SATTN_BF16)) return SATTN_ERR_UNSUPPORTED;
+  if (Hkv != a.H && (SOFTMAX || !PIN)) return SATTN_ERR_UNSUPPORTED;
   int Nk;
   if ((rc = check_cross(a, SOFTMAX, PIN, Hkv, &Nk))) return rc;
   TensorRef q, k, v, o;
@@ -280,12 +281,14 @@ int fwd_impl(const FwdArgs& a) {
   const bool alibi = a.slopes != nullptr;
   const float inv_sqrt_d = 1.0f / sqrtf((float)a.d);
   if (a.dtype == SATTN_F32) {
-    if (SOFTMAX || a.cu_seqlens) return SATTN_ERR_UNSUPPORTED;  // comparison and varlen kernels: bf16 only
+    if (SOFTMAX || !PIN) return SATTN_ERR_UNSUPPORTED;  // comparison kernels and twins: bf16 only
     F32Params p{};
     p.q = q; p.k = k; p.v = v; p.out0 = o;
     p.slopes = a.slopes; p.B = a.B; p.H = a.H; p.N = a.N;
-    p.n_blocks = (a.N + 127) / 128;
     p.scale = inv_sqrt_d; p.bias = a.bias;
+    p.cu_seqlens = a.cu_seqlens; p.bias_vec = a.bias_vec;
+    p.kv_group = a.H / Hkv;
+    p.Nk = Nk == a.N ? 0 : Nk;
     if (a.d == 128) return launch_fwd_f32<128>(p, a.causal, alibi, st);
     return launch_fwd_f32<64>(p, a.causal, alibi, st);
   }
@@ -310,16 +313,20 @@ int fwd_impl(const FwdArgs& a) {
 template <int D>
 int launch_bwd_f32(F32Params p, int causal, bool alibi, int parts, TensorRef dq, TensorRef dk, TensorRef dv,
                    hipStream_t st) {
-  p.n_blocks = (p.N + 127) / 128;
-  dim3 grid(p.n_blocks * p.B * p.H), block(256);
+  // the dQ pass runs one workgroup per query head and 128 queries, the dK/dV pass one per K/V
+  // head and 128 keys
+  const int nb_q = (p.N + 127) / 128, nb_k = ((p.Nk > 0 ? p.Nk : p.N) + 127) / 128;
+  dim3 grid_q(nb_q * p.B * p.H), grid_kv(nb_k * p.B * (p.H / p.kv_group)), block(256);
   int rc = SATTN_OK;
   if (parts & kBwdDkDv) {
+    p.n_blocks = nb_k;
     p.out0 = dk; p.out1 = dv;
-    SATTN_DISPATCH2(causal, alibi, rc = launch(sigmoid_f32_kernel<D, F32_DKDV, A, B2>, grid, block, 0, st, p));
+    SATTN_DISPATCH2(causal, alibi, rc = launch(sigmoid_f32_kernel<D, F32_DKDV, A, B2>, grid_kv, block, 0, st, p));
   }
   if (rc == SATTN_OK && (parts & kBwdDq)) {
+    p.n_blocks = nb_q;
     p.out0 = dq; p.out1 = TensorRef{};
-    SATTN_DISPATCH2(causal, alibi, rc = launch(sigmoid_f32_kernel<D, F32_DQ, A, B2>, grid, block, 0, st, p));
+    SATTN_DISPATCH2(causal, alibi, rc = launch(sigmoid_f32_kernel<D, F32_DQ, A, B2>, grid_q, block, 0, st, p));
   }
   return rc;
 }
@@ -342,7 +349,7 @@ int bwd_impl(const BwdArgs& a) {
   if (rc) return rc;
   const int Hkv = a.Hkv ? a.Hkv : a.H;
   if (Hkv <= 0 || a.H % Hkv) return SATTN_ERR_SHAPE;
-  if (Hkv != a.H && (SOFTMAX || !PIN || a.dtype != SATTN_BF16)) return SATTN_ERR_UNSUPPORTED;
+  if (Hkv != a.H && (SOFTMAX || !PIN)) return SATTN_ERR_UNSUPPORTED;
   int Nk;
   if ((rc = check_cross(a, SOFTMAX, PIN, Hkv, &Nk))) return rc;
   if (Nk != a.N && a.db_rows) return SATTN_ERR_UNSUPPORTED;
@@ -358,17 +365,26 @@ int bwd_impl(const BwdArgs& a) {
   const bool alibi = a.slopes != nullptr;
   const float inv_sqrt_d = 1.0f / sqrtf((float)a.d);
   if (a.dtype == SATTN_F32) {
-    if (SOFTMAX || a.cu_seqlens) return SATTN_ERR_UNSUPPORTED;
+    if (SOFTMAX || !PIN) return SATTN_ERR_UNSUPPORTED;  // comparison kernels and twins: bf16 only
     F32Params p{};
     p.q = q; p.k = k; p.v = v; p.dout = dout;
     p.slopes = a.slopes; p.B = a.B; p.H = a.H; p.N = a.N;
     p.scale = inv_sqrt_d; p.bias = a.bias;
+    p.cu_seqlens = a.cu_seqlens; p.bias_vec = a.bias_vec;
+    p.kv_group = a.H / Hkv;
+    p.Nk = Nk == a.N ? 0 : Nk;
     p.db_rows = a.db_rows; p.db_sb = (int64_t)a.H * a.N; p.db_sh = a.N;
+    if (a.cu_seqlens && a.db_rows) { p.db_sb = 0; p.db_sh = a.db_tokens; }  // [H, tokens], as in the bf16 path
     if (a.d == 128) rc = launch_bwd_f32<128>(p, a.causal, alibi, a.parts, dq, dk, dv, st);
     else rc = launch_bwd_f32<64>(p, a.causal, alibi, a.parts, dq, dk, dv, st);
-    if (rc == SATTN_OK && a.db)
-      rc = launch(rowsum_reduce_kernel, dim3(a.B * a.H), dim3(256), 0, st, (const float*)a.db_rows, a.db, a.H, a.N,
-                  p.db_sb, p.db_sh);
+    if (rc == SATTN_OK && a.db) {
+      if (a.cu_seqlens)
+        rc = launch(rowsum_reduce_varlen_kernel, dim3(a.B * a.H), dim3(256), 0, st, (const float*)a.db_rows, a.db,
+                    a.cu_seqlens, a.H, a.db_tokens, a.N);
+      else
+        rc = launch(rowsum_reduce_kernel, dim3(a.B * a.H), dim3(256), 0, st, (const float*)a.db_rows, a.db, a.H, a.N,
+                    p.db_sb, p.db_sh);
+    }
     return rc;
   }
   BwdParams p{};

@@ -30,8 +30,17 @@ struct F32Params {
   float scale;   // 1/sqrt(d)
   float bias;
   // DQ only, optional: row sums of dS, element (b, h, i) at b*db_sb + h*db_sh + i
+  // (+ the sequence's first token in a variable-length call)
   float* db_rows;
   int64_t db_sb, db_sh;
+  // The same extensions as the bf16 kernels' parameter blocks: packed sequences of different
+  // lengths (cu_seqlens, optional bias per sequence), query head h reading K/V head
+  // h / kv_group (>= 1; the dK/dV pass then runs per K/V head and sums over its query heads),
+  // and a number of keys Nk that differs from the number of queries N (0: same; non-causal).
+  const int* cu_seqlens;
+  const float* bias_vec;
+  int kv_group;
+  int Nk;
 };
 
 __device__ __forceinline__ f32x16 mfma_f32(float a, float b, f32x16 c) {
@@ -49,27 +58,46 @@ sigmoid_f32_kernel(const F32Params p) {
   __shared__ float t2[32 * LD];
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, h = lane >> 5;
+  // the dK/dV pass runs one workgroup per K/V head and key block and streams the query heads of
+  // that head's group one after the other; the other passes run per query head
+  const int heads = MODE == F32_DKDV ? p.H / p.kv_group : p.H;
   const int bh = blockIdx.x / p.n_blocks, blk = blockIdx.x % p.n_blocks;
-  const int b = bh / p.H, hd = bh % p.H, N = p.N;
+  const int b = bh / heads, hd = bh % heads;
+  const int hkv = MODE == F32_DKDV ? hd : hd / p.kv_group;
+  const int hq0 = MODE == F32_DKDV ? hd * p.kv_group : hd, n_hq = MODE == F32_DKDV ? p.kv_group : 1;
+  int N = p.N;
+  int64_t tok0 = 0;
+  float bias = p.bias;
+  if (p.cu_seqlens) {
+    tok0 = p.cu_seqlens[b];
+    const int len = p.cu_seqlens[b + 1] - (int)tok0;
+    N = len < p.N ? len : p.N;  // never beyond the span the host checked
+    if (p.bias_vec) bias = p.bias_vec[b];
+    if (blk * BS >= N) return;  // this sequence has no such block (whole workgroup)
+  }
+  // N counts the queries, Nk the keys; Ns / Nt are the row counts of this pass's stationary /
+  // streamed side
+  const int Nk = p.Nk > 0 ? p.Nk : N;
+  const int Ns = MODE == F32_DKDV ? Nk : N, Nt = MODE == F32_DKDV ? N : Nk;
 
-  const float* qb = (const float*)p.q.ptr + b * p.q.sb + hd * p.q.sh;
-  const float* kb = (const float*)p.k.ptr + b * p.k.sb + hd * p.k.sh;
-  const float* vb = (const float*)p.v.ptr + b * p.v.sb + hd * p.v.sh;
-  const float* dob = TWO ? (const float*)p.dout.ptr + b * p.dout.sb + hd * p.dout.sh : nullptr;
+  const float* kb = (const float*)p.k.ptr + b * p.k.sb + hkv * p.k.sh + tok0 * p.k.ss;
+  const float* vb = (const float*)p.v.ptr + b * p.v.sb + hkv * p.v.sh + tok0 * p.v.ss;
+  auto qhead = [&](int hq) { return (const float*)p.q.ptr + b * p.q.sb + hq * p.q.sh + tok0 * p.q.ss; };
+  auto dohead = [&](int hq) {
+    return TWO ? (const float*)p.dout.ptr + b * p.dout.sb + hq * p.dout.sh + tok0 * p.dout.ss : nullptr;
+  };
 
-  // stationary side: x1 (and x2); streaming side: y1, y2
-  const float* x1 = MODE == F32_DKDV ? kb : qb;
+  // stationary side: x1 (and x2); streaming side: y1, y2 (per query head in the dK/dV pass)
+  const float* x1 = MODE == F32_DKDV ? kb : qhead(hq0);
   const int64_t x1s = MODE == F32_DKDV ? p.k.ss : p.q.ss;
-  const float* x2 = MODE == F32_DKDV ? vb : dob;
+  const float* x2 = MODE == F32_DKDV ? vb : dohead(hq0);
   const int64_t x2s = MODE == F32_DKDV ? p.v.ss : p.dout.ss;
-  const float* y1 = MODE == F32_DKDV ? qb : kb;
   const int64_t y1s = MODE == F32_DKDV ? p.q.ss : p.k.ss;
-  const float* y2 = MODE == F32_DKDV ? dob : vb;
   const int64_t y2s = MODE == F32_DKDV ? p.dout.ss : p.v.ss;
 
   const int a_wave0 = blk * BS + wave * 32;  // first stationary row of the wave
   const int ai = a_wave0 + l32;              // this lane's stationary row (query, or key for DKDV)
-  const int ai_ld = ai < N ? ai : N - 1;
+  const int ai_ld = ai < Ns ? ai : Ns - 1;
 
   float xf1[D / 2], xf2[TWO ? D / 2 : 1];
 #pragma unroll
@@ -85,24 +113,27 @@ sigmoid_f32_kernel(const F32Params p) {
       acc0[dt][r] = 0.f;
       if (MODE == F32_DKDV) acc1[dt][r] = 0.f;
     }
-  const float slope = ALIBI ? p.slopes[hd] : 0.f;
   float dbsum = 0.f;  // DQ: sum of this lane's dS elements
 
   // range of streaming tiles (32 rows each)
-  const int a_hi = (blk * BS + BS < N ? blk * BS + BS : N) - 1;
-  int t_lo = 0, t_hi = (N + 31) / 32;
+  const int a_hi = (blk * BS + BS < Ns ? blk * BS + BS : Ns) - 1;
+  int t_lo = 0, t_hi = (Nt + 31) / 32;
   if (CAUSAL) {
     if (MODE == F32_DKDV) t_lo = (blk * BS) / 32;  // queries before the first key see nothing
     else t_hi = a_hi / 32 + 1;                      // keys after the last query are masked
   }
 
+  for (int hq = hq0; hq < hq0 + n_hq; ++hq) {  // one pass over the streamed side per query head
+  const float* y1 = MODE == F32_DKDV ? qhead(hq) : kb;
+  const float* y2 = MODE == F32_DKDV ? dohead(hq) : vb;
+  const float slope = ALIBI ? p.slopes[hq] : 0.f;
   for (int t = t_lo; t < t_hi; ++t) {
     const int b0 = t * 32;  // first streaming row of the tile
     __syncthreads();        // previous tile fully consumed
     for (int idx = tid; idx < 32 * (D / 4); idx += NT) {
       int r = idx / (D / 4), c = idx % (D / 4);
       int row = b0 + r;
-      row = row < N ? row : N - 1;
+      row = row < Nt ? row : Nt - 1;
       f32x4 u = *(const f32x4*)(y1 + (int64_t)row * y1s + 4 * c);
       f32x4 w = *(const f32x4*)(y2 + (int64_t)row * y2s + 4 * c);
       float* d1 = &t1[r * LD + 4 * c];
@@ -113,7 +144,7 @@ sigmoid_f32_kernel(const F32Params p) {
     __syncthreads();
 
     // wave-uniform skip of tiles that are entirely masked for this wave
-    bool live = a_wave0 < N;
+    bool live = a_wave0 < Ns;
     if (CAUSAL) {
       if (MODE == F32_DKDV) live = live && (b0 + 31 >= a_wave0);  // some query >= some key
       else live = live && (b0 <= a_wave0 + 31);                   // some key <= some query
@@ -136,10 +167,10 @@ sigmoid_f32_kernel(const F32Params p) {
       const int bi = b0 + 8 * (r >> 2) + 4 * h + (r & 3);
       const int qrow = MODE == F32_DKDV ? bi : ai;
       const int krow = MODE == F32_DKDV ? ai : bi;
-      float tt = s[r] * p.scale + p.bias;
+      float tt = s[r] * p.scale + bias;
       if (ALIBI) tt -= slope * fabsf((float)(qrow - krow));
       float pv = 1.0f / (1.0f + expf(-tt));
-      bool keep = bi < N && (!CAUSAL || krow <= qrow);
+      bool keep = bi < Nt && (!CAUSAL || krow <= qrow);
       pv = keep ? pv : 0.f;
       pr[r] = pv;
       if (TWO) ds[r] = pv * (1.0f - pv) * dp[r];
@@ -160,15 +191,16 @@ sigmoid_f32_kernel(const F32Params p) {
       }
     }
   }
+  }  // query heads
 
   if (MODE == F32_DQ) {
     // the two halves of the wave hold the sums over different keys of the same query row
     dbsum += __shfl_xor(dbsum, 32);
-    if (p.db_rows && h == 0 && ai < N) p.db_rows[b * p.db_sb + hd * p.db_sh + ai] = dbsum;
+    if (p.db_rows && h == 0 && ai < Ns) p.db_rows[b * p.db_sb + hd * p.db_sh + tok0 + ai] = dbsum;
   }
-  if (ai < N) {
+  if (ai < Ns) {
     const float osc = MODE == F32_FWD ? 1.0f : p.scale;  // dQ, dK carry the 1/sqrt(d) of the logits
-    float* o0 = (float*)p.out0.ptr + b * p.out0.sb + hd * p.out0.sh + (int64_t)ai * p.out0.ss;
+    float* o0 = (float*)p.out0.ptr + b * p.out0.sb + hd * p.out0.sh + (tok0 + ai) * p.out0.ss;
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
@@ -177,7 +209,7 @@ sigmoid_f32_kernel(const F32Params p) {
         *(f32x4*)(o0 + 32 * dt + 8 * g + 4 * h) = w;
       }
     if (MODE == F32_DKDV) {
-      float* o1 = (float*)p.out1.ptr + b * p.out1.sb + hd * p.out1.sh + (int64_t)ai * p.out1.ss;
+      float* o1 = (float*)p.out1.ptr + b * p.out1.sb + hd * p.out1.sh + (tok0 + ai) * p.out1.ss;
 #pragma unroll
       for (int dt = 0; dt < DT; ++dt)
 #pragma unroll

@@ -79,15 +79,15 @@ def test_varlen_entry_points_reject_bad_arguments(lib):
     ptrs = [0x1000, 0x2000, 0x3000, 0x4000]
     tail = [2, 4, 512, 128, 0, 0.0, 1, None, None, None, None, None, None]       # B H max_seqlen d dtype bias causal ...
     assert lib.sigmoid_attn_varlen_fwd(*ptrs, None, None, *tail) == -1          # cu_seqlens NULL
-    assert lib.sigmoid_attn_varlen_fwd(*ptrs, 0x5000, None, 2, 4, 512, 128, 1, 0.0, 1, None, None, None, None,
-                                       None, None) == -3                        # fp32: no varlen kernels
+    assert lib.sigmoid_attn_varlen_fwd(*ptrs, 0x5000, None, 2, 4, 512, 128, 2, 0.0, 1, None, None, None, None,
+                                       None, None) == -3                        # no such dtype
     assert lib.sigmoid_attn_varlen_fwd(*ptrs, 0x5000, None, 2, 4, 512, 96, 0, 0.0, 1, None, None, None, None,
                                        None, None) == -3                        # head dimension
     assert lib.sigmoid_attn_varlen_fwd(*ptrs, 0x5000, None, 2, 4, 0, 128, 0, 0.0, 1, None, None, None, None,
                                        None, None) == -2                        # max_seqlen
     bptrs = [0x1000, 0x2000, 0x3000, 0x4000, 0x5000, 0x6000, 0x7000]
     assert lib.sigmoid_attn_varlen_bwd(*bptrs, None, None, 2, 4, 512, 128, 0, 0.0, 1, None, *([None] * 7), None) == -1
-    assert lib.sigmoid_attn_varlen_bwd(*bptrs, 0x8000, None, 2, 4, 512, 128, 1, 0.0, 1, None, *([None] * 7), None) == -3
+    assert lib.sigmoid_attn_varlen_bwd(*bptrs, 0x8000, None, 2, 4, 512, 128, 2, 0.0, 1, None, *([None] * 7), None) == -3
 
 
 def test_bias_gradient_entry_point_rejects_bad_arguments(lib):
@@ -109,7 +109,7 @@ def test_varlen_bias_gradient_entry_point_rejects_bad_arguments(lib):
     assert f(*ptrs, 0x8002, None, 0x9000, None, *tail()) == -4          # fp32 alignment
     assert f(*ptrs, 0x8000, None, 0x9000, None, *tail(total=0)) == -2
     assert f(*ptrs, 0x8000, None, 0x9000, None, *tail(d=96)) == -3
-    assert f(*ptrs, 0x8000, None, 0x9000, None, *tail(dtype=1)) == -3   # packed sequences are bf16 only
+    assert f(*ptrs, 0x8000, None, 0x9000, None, *tail(dtype=2)) == -3   # no such dtype (bf16 and fp32 exist)
 
 
 def test_backward_one_grid_choice(lib):
@@ -171,11 +171,11 @@ def test_shared_kv_head_entry_points_reject_bad_arguments(lib):
     args = lambda H, Hkv, dtype=0: [*ptrs, 1, H, Hkv, 64, 64, dtype, 0.0, 0, None, None, None, None, None, None]
     assert lib.sigmoid_attn_mqa_fwd(*args(6, 4)) == -2          # Hkv must divide H
     assert lib.sigmoid_attn_mqa_fwd(*args(6, 0)) == -2
-    assert lib.sigmoid_attn_mqa_fwd(*args(6, 2, 1)) == -3       # fp32 has no shared-head kernels
+    assert lib.sigmoid_attn_mqa_fwd(*args(6, 2, 2)) == -3       # no such dtype (bf16 and fp32 exist)
     bptrs = [0x1000, 0x2000, 0x3000, 0x4000, 0x5000, 0x6000, 0x7000]
     bargs = lambda H, Hkv, dtype=0: [*bptrs, 1, H, Hkv, 64, 64, dtype, 0.0, 0, None, *([None] * 7), None]
     assert lib.sigmoid_attn_mqa_bwd(*bargs(8, 3)) == -2
-    assert lib.sigmoid_attn_mqa_bwd(*bargs(8, 2, 1)) == -3
+    assert lib.sigmoid_attn_mqa_bwd(*bargs(8, 2, 2)) == -3
     bptrs[5] = None
     assert lib.sigmoid_attn_mqa_bwd(*bargs(8, 2)) == -1         # dk NULL
 
@@ -196,7 +196,7 @@ def test_cross_attention_entry_points_reject_bad_arguments(lib):
     f = lambda Nq=64, Nk=96, d=64, dtype=0: lib.sigmoid_attn_cross_fwd(*ptrs, 1, 2, Nq, Nk, d, dtype, 0.0,
                                                                        None, None, None, None, None)
     assert f(Nk=0) == -2 and f(Nq=0) == -2
-    assert f(dtype=1) == -3                         # fp32 has no such kernels
+    assert f(dtype=2) == -3                         # no such dtype (bf16 and fp32 exist)
     assert f(d=96) == -3
     bptrs = [0x1000, 0x2000, 0x3000, 0x4000, 0x5000, None, 0x7000]
     assert lib.sigmoid_attn_cross_bwd(*bptrs, 1, 2, 64, 96, 64, 0, 0.0, *([None] * 7), None) == -1

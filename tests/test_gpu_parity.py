@@ -554,6 +554,91 @@ def test_varlen_bias_gradient_matches_per_sequence_calls_and_oracle(d, causal, a
         np.testing.assert_allclose(db[s_].cpu().numpy(), ref[0].sum(-1), rtol=2e-4, atol=2e-4 * np.abs(ref).max() * n)
 
 
+# ------------------------------------------------------------------ fp32 forms of the extended entry points
+
+def test_fp32_variable_length_with_bias_gradient_matches_oracle():
+    H, d, causal = 2, 64, True
+    lens = [70, 1, 0, 200, 129]
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    total = int(cu[-1])
+    g = torch.Generator().manual_seed(99)
+    q, k, v, do = (torch.randn(total, H, d, generator=g) for _ in range(4))
+    slopes = W.alibi_slopes(H)
+    biases = torch.tensor([-float(np.log(max(n, 2))) for n in lens], dtype=torch.float32)
+    Q, K, V, DO = (_dev(t) for t in (q, k, v, do))
+    outs = [_guarded(Q.shape, torch.float32) for _ in range(4)]
+    (o, _), (dq, _), (dk, _), (dv, _) = outs
+    db_rows = torch.full((H, total), float("nan"), dtype=torch.float32, device="cuda")
+    db = torch.full((len(lens), H), float("nan"), dtype=torch.float32, device="cuda")
+    cu_d = torch.from_numpy(cu).cuda()
+    sa.sigmoid_attn_varlen_fwd(Q, K, V, o, cu_d, max(lens), 0.0, causal, _dev(slopes), biases.cuda())
+    sa.sigmoid_attn_varlen_bwd_bias_grad(Q, K, V, DO, dq, dk, dv, db_rows, cu_d, max(lens), 0.0, causal, _dev(slopes),
+                                         biases.cuda(), db)
+    torch.cuda.synchronize()
+    for _, guard in outs:
+        guard()
+    for s_, n in enumerate(lens):
+        a, b_ = int(cu[s_]), int(cu[s_ + 1])
+        if n == 0:
+            assert bool((db[s_] == 0).all())
+            continue
+        bs = float(biases[s_])
+        dense = lambda t: t[a:b_].permute(1, 0, 2).unsqueeze(0).double().numpy()
+        ro = orc.sigmoid_attn_fwd(dense(q), dense(k), dense(v), bs, causal, slopes)
+        rq, rk, rv = orc.sigmoid_attn_bwd(dense(q), dense(k), dense(v), dense(do), bs, causal, slopes)
+        rrows = orc.sigmoid_attn_bias_grad(dense(q), dense(k), dense(v), dense(do), bs, causal, slopes)
+        rdb = rrows.sum(-1)
+        for name, got, ref in (("o", o, ro), ("dq", dq, rq), ("dk", dk, rk), ("dv", dv, rv)):
+            e = nerr(got[a:b_].permute(1, 0, 2).unsqueeze(0).contiguous(), ref)
+            assert e <= TOL_F32, f"{name} of sequence {s_}: {e:.3e}"
+        assert nerr(db_rows[:, a:b_].unsqueeze(0).contiguous(), rrows) <= TOL_F32
+        assert nerr(db[s_:s_ + 1], rdb) <= TOL_F32
+
+
+@pytest.mark.parametrize("B,H,Hkv,N,d,causal,alibi", [(1, 4, 2, 150, 64, True, True), (2, 4, 1, 257, 128, False, False)])
+def test_fp32_shared_kv_heads_match_oracle(B, H, Hkv, N, d, causal, alibi):
+    g = torch.Generator().manual_seed(31 + N)
+    q, do = (torch.randn(B, H, N, d, generator=g) for _ in range(2))
+    k, v = (torch.randn(B, Hkv, N, d, generator=g) for _ in range(2))
+    slopes = W.alibi_slopes(H) if alibi else None
+    sl = _dev(slopes) if alibi else None
+    bias = -math.log(N)
+    Q, K, V, DO = (_dev(t) for t in (q, k, v, do))
+    (o, g0), (dq, g1) = (_guarded(Q.shape, torch.float32) for _ in range(2))
+    (dk, g2), (dv, g3) = (_guarded(K.shape, torch.float32) for _ in range(2))
+    sa.sigmoid_attn_mqa_fwd(Q, K, V, o, bias, causal, sl)
+    sa.sigmoid_attn_mqa_bwd(Q, K, V, DO, dq, dk, dv, bias, causal, sl)
+    torch.cuda.synchronize()
+    for guard in (g0, g1, g2, g3):
+        guard()
+    f = lambda t: t.double().numpy()
+    ro = orc.sigmoid_attn_mqa_fwd(f(q), f(k), f(v), bias, causal, slopes)
+    rdq, rdk, rdv = orc.sigmoid_attn_mqa_bwd(f(q), f(k), f(v), f(do), bias, causal, slopes)
+    for name, got, ref in (("o", o, ro), ("dq", dq, rdq), ("dk", dk, rdk), ("dv", dv, rdv)):
+        assert nerr(got, ref) <= TOL_F32, f"{name}: {nerr(got, ref):.3e}"
+
+
+@pytest.mark.parametrize("B,H,Nq,Nk,d", [(1, 2, 100, 333, 64), (1, 1, 257, 64, 128), (2, 1, 1, 130, 64)])
+def test_fp32_cross_attention_matches_oracle(B, H, Nq, Nk, d):
+    g = torch.Generator().manual_seed(700 + Nq + Nk)
+    q, do = (torch.randn(B, H, Nq, d, generator=g) for _ in range(2))
+    k, v = (torch.randn(B, H, Nk, d, generator=g) for _ in range(2))
+    bias = -math.log(max(Nk, 2))
+    Q, K, V, DO = (_dev(t) for t in (q, k, v, do))
+    (o, g0), (dq, g1) = (_guarded(Q.shape, torch.float32) for _ in range(2))
+    (dk, g2), (dv, g3) = (_guarded(K.shape, torch.float32) for _ in range(2))
+    sa.sigmoid_attn_cross_fwd(Q, K, V, o, bias)
+    sa.sigmoid_attn_cross_bwd(Q, K, V, DO, dq, dk, dv, bias)
+    torch.cuda.synchronize()
+    for guard in (g0, g1, g2, g3):
+        guard()
+    f = lambda t: t.double().numpy()
+    ro = orc.sigmoid_attn_cross_fwd(f(q), f(k), f(v), bias)
+    rdq, rdk, rdv = orc.sigmoid_attn_cross_bwd(f(q), f(k), f(v), f(do), bias)
+    for name, got, ref in (("o", o, ro), ("dq", dq, rdq), ("dk", dk, rdk), ("dv", dv, rdv)):
+        assert nerr(got, ref) <= TOL_F32, f"{name}: {nerr(got, ref):.3e}"
+
+
 # ------------------------------------------------------------------ measurement aids
 
 def test_clock_probe_records_per_workgroup_and_respects_its_capacity():
