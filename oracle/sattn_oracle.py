@@ -240,25 +240,41 @@ def headconcat_norm_bwd(o, dy, kind="layer", eps=1e-5):
 
 
 # ---- different numbers of queries and keys: the definition of Section 2 with Q of n_q rows and
-# K, V of n_k rows (no mask, no ALiBi), written with fp64 matrix products.
+# K, V of n_k rows, written with fp64 matrix products.
 #   P = sigmoid(Q K^T / sqrt(d) + b)  [n_q x n_k],  O = P V
 #   dV = P^T dO,  dP = dO V^T,  dS = P (1 - P) dP,  dQ = dS K / sqrt(d),  dK = dS^T Q / sqrt(d)
+# The paper's models only use n_q = n_k, so where the causal mask (Appendix E.1's decoder
+# setting) and ALiBi (Section 5.3) sit when the two differ is a reading: the queries are taken
+# to be the LAST n_q positions of the key sequence (query i sits at position i + n_k - n_q, as
+# when a prefix's keys and values are already there and new tokens attend to them): key j is
+# visible to query i iff j <= i + n_k - n_q, and the ALiBi distance is |i + n_k - n_q - j|.
+# With n_q = n_k both reduce to the square definitions.
 
-def _cross_probs(q, k, bias):
+def _cross_probs(q, k, bias, causal=False, alibi_slopes=None):
     d = q.shape[-1]
+    H, nq, nk = q.shape[1], q.shape[2], k.shape[2]
     t = np.einsum("bhid,bhjd->bhij", q, k) / math.sqrt(d) + bias
-    return np.where(t >= 0, 1.0 / (1.0 + np.exp(-np.abs(t))), np.exp(-np.abs(t)) / (1.0 + np.exp(-np.abs(t))))
+    pos_q = np.arange(nq)[:, None] + (nk - nq)
+    pos_k = np.arange(nk)[None, :]
+    if alibi_slopes is not None:
+        m = np.asarray(alibi_slopes, dtype=np.float64).reshape(1, H, 1, 1)
+        t = t - m * np.abs(pos_q - pos_k)[None, None]
+    e = np.exp(-np.abs(t))
+    p = np.where(t >= 0, 1.0 / (1.0 + e), e / (1.0 + e))
+    if causal:
+        p = p * (pos_k <= pos_q)[None, None]
+    return p
 
 
-def sigmoid_attn_cross_fwd(q, k, v, bias):
+def sigmoid_attn_cross_fwd(q, k, v, bias, causal=False, alibi_slopes=None):
     q, k, v = _f64(q), _f64(k), _f64(v)
-    return np.einsum("bhij,bhjd->bhid", _cross_probs(q, k, bias), v)
+    return np.einsum("bhij,bhjd->bhid", _cross_probs(q, k, bias, causal, alibi_slopes), v)
 
 
-def sigmoid_attn_cross_bwd(q, k, v, dout, bias):
+def sigmoid_attn_cross_bwd(q, k, v, dout, bias, causal=False, alibi_slopes=None):
     q, k, v, dout = _f64(q), _f64(k), _f64(v), _f64(dout)
     inv = 1.0 / math.sqrt(q.shape[-1])
-    p = _cross_probs(q, k, bias)
+    p = _cross_probs(q, k, bias, causal, alibi_slopes)
     dv = np.einsum("bhij,bhid->bhjd", p, dout)
-    ds = p * (1.0 - p) * np.einsum("bhid,bhjd->bhij", dout, v)
+    ds = p * (1.0 - p) * np.einsum("bhid,bhjd->bhij", dout, v)   # masked pairs: p = 0, so dS = 0
     return np.einsum("bhij,bhjd->bhid", ds, k) * inv, np.einsum("bhij,bhid->bhjd", ds, q) * inv, dv

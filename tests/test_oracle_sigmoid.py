@@ -382,6 +382,66 @@ def test_cross_attention_pins():
                                np.broadcast_to(v.sum(2, keepdims=True) / (1 + math.exp(0.4)), o.shape), rtol=1e-13)
 
 
+@pytest.mark.parametrize("Nq,Nk", [(5, 12), (12, 12), (1, 9), (9, 4)])
+@pytest.mark.parametrize("alibi", [False, True])
+def test_cross_attention_with_end_aligned_causal_mask_pins(Nq, Nk, alibi):
+    """The reading for n_q != n_k: the queries are the last n_q positions of the key sequence."""
+    B, H, d = 2, 3, 8
+    q, dout = _rand(B, H, Nq, d), _rand(B, H, Nq, d)
+    k, v = _rand(B, H, Nk, d), _rand(B, H, Nk, d)
+    slopes = np.array([0.5, 0.25, 0.0625]) if alibi else None
+    b = -0.7
+    o = orc.sigmoid_attn_cross_fwd(q, k, v, b, True, slopes)
+    dq, dk, dv = orc.sigmoid_attn_cross_bwd(q, k, v, dout, b, True, slopes)
+    if Nk >= Nq:
+        # (1) the square causal attention (the pinned C oracle) over all n_k positions, whose last
+        # n_q queries are ours: its last n_q output rows are our output; with zero upstream
+        # gradient on the earlier rows its dK, dV are ours and the last rows of its dQ are our dQ
+        qf = np.concatenate([_rand(B, H, Nk - Nq, d), q], axis=2)
+        df = np.concatenate([np.zeros((B, H, Nk - Nq, d)), dout], axis=2)
+        np.testing.assert_allclose(orc.sigmoid_attn_fwd(qf, k, v, b, True, slopes)[:, :, Nk - Nq:], o, rtol=1e-12, atol=1e-14)
+        sq, sk, sv = orc.sigmoid_attn_bwd(qf, k, v, df, b, True, slopes)
+        np.testing.assert_allclose(sq[:, :, Nk - Nq:], dq, rtol=1e-11, atol=1e-14)
+        np.testing.assert_allclose(sk, dk, rtol=1e-11, atol=1e-14)
+        np.testing.assert_allclose(sv, dv, rtol=1e-11, atol=1e-14)
+    else:
+        # (2) more queries than keys: the first n_q - n_k queries sit before every key and see
+        # nothing; the rest is the square causal attention of the last n_k queries
+        cut = Nq - Nk
+        assert np.all(o[:, :, :cut] == 0) and np.all(dq[:, :, :cut] == 0)
+        np.testing.assert_allclose(orc.sigmoid_attn_fwd(q[:, :, cut:], k, v, b, True, slopes), o[:, :, cut:], rtol=1e-12, atol=1e-14)
+        sq, sk, sv = orc.sigmoid_attn_bwd(q[:, :, cut:], k, v, dout[:, :, cut:], b, True, slopes)
+        np.testing.assert_allclose(sq, dq[:, :, cut:], rtol=1e-11, atol=1e-14)
+        np.testing.assert_allclose(sk, dk, rtol=1e-11, atol=1e-14)
+        np.testing.assert_allclose(sv, dv, rtol=1e-11, atol=1e-14)
+    # (3) brute force over pairs, straight from the definition
+    ref = np.zeros_like(o)
+    for bb in range(B):
+        for h in range(H):
+            for i in range(Nq):
+                for j in range(Nk):
+                    pi = i + Nk - Nq
+                    if j > pi:
+                        continue
+                    t = q[bb, h, i] @ k[bb, h, j] / math.sqrt(d) + b - (slopes[h] * abs(pi - j) if alibi else 0.0)
+                    ref[bb, h, i] += v[bb, h, j] / (1.0 + math.exp(-t))
+    np.testing.assert_allclose(o, ref, rtol=1e-12, atol=1e-14)
+    # (4) torch autograd with an explicit mask
+    tq, tk, tv = (torch.tensor(x, dtype=torch.float64, requires_grad=True) for x in (q, k, v))
+    pos_q = torch.arange(Nq)[:, None] + (Nk - Nq)
+    pos_k = torch.arange(Nk)[None, :]
+    t = tq @ tk.transpose(-1, -2) / math.sqrt(d) + b
+    if alibi:
+        t = t - torch.tensor(slopes).reshape(1, H, 1, 1) * (pos_q - pos_k).abs()
+    to = (torch.sigmoid(t) * (pos_k <= pos_q)) @ tv
+    (to * torch.tensor(dout)).sum().backward()
+    np.testing.assert_allclose(o, to.detach().numpy(), rtol=1e-12, atol=1e-14)
+    for got, ref_g in ((dq, tq.grad), (dk, tk.grad), (dv, tv.grad)):
+        np.testing.assert_allclose(got, ref_g.numpy(), rtol=1e-10, atol=1e-13)
+    # (5) without the mask and slopes the extended functions are the plain ones
+    np.testing.assert_array_equal(orc.sigmoid_attn_cross_fwd(q, k, v, b), orc.sigmoid_attn_cross_fwd(q, k, v, b, False, None))
+
+
 # ------------------------------------------------------------------ hybrid-norm
 
 @pytest.mark.parametrize("kind", ["layer", "rms"])
