@@ -248,6 +248,29 @@ int sigmoid_attn_cross_bwd(const void* q, const void* k, const void* v, const vo
                            const sattn_strides* sdq, const sattn_strides* sdk,
                            const sattn_strides* sdv, void* stream);
 
+/* The same with the queries placed at the END of the key sequence: query i sits at position
+ * i + Nk - Nq (the keys and values of a prefix are already there and Nq new tokens attend to
+ * them).  That placement is this library's reading, the paper's models only have Nq = Nk; it
+ * gives the causal mask (Appendix E.1: key j is kept for query i iff j <= i + Nk - Nq) and
+ * ALiBi (Section 5.3: distance |i + Nk - Nq - j|) a meaning when the two counts differ; with
+ * Nq = Nk the calls equal sigmoid_attn_fwd / sigmoid_attn_bwd, with Nq > Nk the first Nq - Nk
+ * queries see no key (their outputs and gradients are zero).  causal and alibi_slopes as in
+ * sigmoid_attn_fwd.  fp32 takes any pair of counts; bf16 with the causal mask needs Nk - Nq to
+ * be a multiple of 32 (SATTN_ERR_UNSUPPORTED otherwise).  One K/V head per query head. */
+int sigmoid_attn_cross_aligned_fwd(const void* q, const void* k, const void* v, void* o,
+                                   int B, int H, int Nq, int Nk, int d, sattn_dtype dtype, float bias,
+                                   int causal, const float* alibi_slopes,
+                                   const sattn_strides* sq, const sattn_strides* sk,
+                                   const sattn_strides* sv, const sattn_strides* so, void* stream);
+int sigmoid_attn_cross_aligned_bwd(const void* q, const void* k, const void* v, const void* dout,
+                                   void* dq, void* dk, void* dv,
+                                   int B, int H, int Nq, int Nk, int d, sattn_dtype dtype, float bias,
+                                   int causal, const float* alibi_slopes,
+                                   const sattn_strides* sq, const sattn_strides* sk,
+                                   const sattn_strides* sv, const sattn_strides* sdout,
+                                   const sattn_strides* sdq, const sattn_strides* sdk,
+                                   const sattn_strides* sdv, void* stream);
+
 /* Backward with the gradient of a learnable bias (Section 5.4 and Appendix G.4 train with a
  * learnable scalar b, one per layer; Appendix F.1 backward table: T = S + b, so dL/db is the
  * sum of dS over the pairs the bias enters).  Same as sigmoid_attn_bwd (bf16 or fp32), and the

@@ -58,6 +58,10 @@ def load_library():
     lib.sigmoid_attn_cross_fwd.restype = i
     lib.sigmoid_attn_cross_bwd.argtypes = [_vp] * 7 + [i, i, i, i, i, i, f] + [_SP] * 7 + [_vp]
     lib.sigmoid_attn_cross_bwd.restype = i
+    lib.sigmoid_attn_cross_aligned_fwd.argtypes = [_vp, _vp, _vp, _vp, i, i, i, i, i, i, f, i, _vp, _SP, _SP, _SP, _SP, _vp]
+    lib.sigmoid_attn_cross_aligned_fwd.restype = i
+    lib.sigmoid_attn_cross_aligned_bwd.argtypes = [_vp] * 7 + [i, i, i, i, i, i, f, i, _vp] + [_SP] * 7 + [_vp]
+    lib.sigmoid_attn_cross_aligned_bwd.restype = i
     lib.sigmoid_attn_bwd_bias_grad.argtypes = [_vp] * 9 + [i, i, i, i, i, f, i, _vp] + [_SP] * 7 + [_vp]
     lib.sigmoid_attn_bwd_bias_grad.restype = i
     ip = ctypes.c_void_p
@@ -287,6 +291,30 @@ def sigmoid_attn_cross_bwd(q, k, v, dout, dq, dk, dv, bias):
                                     dk.data_ptr(), dv.data_ptr(), B, H, Nq, Nk, d, _dtype_code(q), float(bias),
                                     _st(q), _st(k), _st(v), _st(dout), _st(dq), _st(dk), _st(dv), _stream())
     _raise(rc, "sigmoid_attn_cross_bwd")
+    return dq, dk, dv
+
+
+def sigmoid_attn_cross_aligned_fwd(q, k, v, o, bias, causal=False, alibi_slopes=None):
+    """Sigmoid attention of Nq queries placed at the end of an Nk-key sequence (query i at position
+    i + Nk - Nq), with the causal mask and ALiBi of that placement: q, o [B,H,Nq,d]; k, v [B,H,Nk,d]."""
+    lib = load_library()
+    B, H, Nq, Nk, d = _check_cross(q, (k, v), o)
+    rc = lib.sigmoid_attn_cross_aligned_fwd(q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(), B, H, Nq, Nk, d,
+                                            _dtype_code(q), float(bias), int(bool(causal)), _slopes_ptr(alibi_slopes, H),
+                                            _st(q), _st(k), _st(v), _st(o), _stream())
+    _raise(rc, "sigmoid_attn_cross_aligned_fwd")
+    return o
+
+
+def sigmoid_attn_cross_aligned_bwd(q, k, v, dout, dq, dk, dv, bias, causal=False, alibi_slopes=None):
+    """Backward of sigmoid_attn_cross_aligned_fwd: dq [B,H,Nq,d]; dk, dv [B,H,Nk,d]."""
+    lib = load_library()
+    B, H, Nq, Nk, d = _check_cross(q, (k, v, dk, dv), dout, dq)
+    rc = lib.sigmoid_attn_cross_aligned_bwd(q.data_ptr(), k.data_ptr(), v.data_ptr(), dout.data_ptr(), dq.data_ptr(),
+                                            dk.data_ptr(), dv.data_ptr(), B, H, Nq, Nk, d, _dtype_code(q), float(bias),
+                                            int(bool(causal)), _slopes_ptr(alibi_slopes, H), _st(q), _st(k), _st(v),
+                                            _st(dout), _st(dq), _st(dk), _st(dv), _stream())
+    _raise(rc, "sigmoid_attn_cross_aligned_bwd")
     return dq, dk, dv
 
 

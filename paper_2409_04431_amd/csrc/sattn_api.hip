@@ -249,16 +249,21 @@ struct FwdArgs {
   const int* cu_seqlens = nullptr; const float* bias_vec = nullptr;  // variable-length batches
   int Hkv = 0;                                                       // K/V heads (0: one per query head)
   int Nk = 0;                                                        // keys (0: as many as queries)
+  bool end_aligned = false;                                          // queries = the last N positions of the key sequence
 };
 
-// A key count that differs from the query count: plain (non-causal, no ALiBi) bf16 sigmoid
-// attention with one K/V head per query head only.
+// A key count that differs from the query count: sigmoid attention with one K/V head per query
+// head.  Without `end_aligned` plain attention only (no mask, no ALiBi: positions undefined);
+// with it the queries sit at the end of the key sequence, which defines both; the bf16 kernels
+// then need the offset Nk - N to be a multiple of 32 under the causal mask (a wave's query rows
+// and a key chunk must meet in one diagonal chunk), the fp32 kernel takes any.
 template <typename Args>
 int check_cross(const Args& a, bool softmax, bool pin, int Hkv, int* Nk) {
   *Nk = a.Nk > 0 ? a.Nk : a.N;
   if (*Nk == a.N) return SATTN_OK;
-  if (softmax || !pin || a.causal || a.slopes || a.cu_seqlens || Hkv != a.H)
-    return SATTN_ERR_UNSUPPORTED;
+  if (softmax || !pin || a.cu_seqlens || Hkv != a.H) return SATTN_ERR_UNSUPPORTED;
+  if (!a.end_aligned && (a.causal || a.slopes)) return SATTN_ERR_UNSUPPORTED;
+  if (a.end_aligned && a.causal && a.dtype == SATTN_BF16 && (*Nk - a.N) % 32 != 0) return SATTN_ERR_UNSUPPORTED;
   return check_shape(a.B, a.H, *Nk, a.d, a.dtype);
 }
 
@@ -289,6 +294,7 @@ int fwd_impl(const FwdArgs& a) {
     p.cu_seqlens = a.cu_seqlens; p.bias_vec = a.bias_vec;
     p.kv_group = a.H / Hkv;
     p.Nk = Nk == a.N ? 0 : Nk;
+    p.qoff = a.end_aligned ? Nk - a.N : 0;
     if (a.d == 128) return launch_fwd_f32<128>(p, a.causal, alibi, st);
     return launch_fwd_f32<64>(p, a.causal, alibi, st);
   }
@@ -301,6 +307,7 @@ int fwd_impl(const FwdArgs& a) {
   p.cu_seqlens = a.cu_seqlens; p.bias_vec = a.bias_vec;
   p.kv_group = a.H / Hkv;
   p.Nk = Nk == a.N ? 0 : Nk;
+  p.qoff = a.end_aligned ? Nk - a.N : 0;
   p.clock = clock_probe();
   // the 64-row waves exist for the pinned sigmoid kernel at d = 128, ALiBi only in its causal form
   const bool has64 = !SOFTMAX && PIN && a.d == 128 && !(alibi && !a.causal);
@@ -341,6 +348,7 @@ struct BwdArgs {
   int64_t db_tokens = 0;                                             // packed sequences: tokens in db_rows' [H, tokens]
   int Hkv = 0;                                                       // K/V heads (0: one per query head)
   int Nk = 0;                                                        // keys (0: as many as queries)
+  bool end_aligned = false;                                          // queries = the last N positions of the key sequence
 };
 
 template <bool SOFTMAX, bool PIN = true>
@@ -373,6 +381,7 @@ int bwd_impl(const BwdArgs& a) {
     p.cu_seqlens = a.cu_seqlens; p.bias_vec = a.bias_vec;
     p.kv_group = a.H / Hkv;
     p.Nk = Nk == a.N ? 0 : Nk;
+    p.qoff = a.end_aligned ? Nk - a.N : 0;
     p.db_rows = a.db_rows; p.db_sb = (int64_t)a.H * a.N; p.db_sh = a.N;
     if (a.cu_seqlens && a.db_rows) { p.db_sb = 0; p.db_sh = a.db_tokens; }  // [H, tokens], as in the bf16 path
     if (a.d == 128) rc = launch_bwd_f32<128>(p, a.causal, alibi, a.parts, dq, dk, dv, st);
@@ -399,6 +408,7 @@ int bwd_impl(const BwdArgs& a) {
   if (a.cu_seqlens && a.db_rows) { p.db_sb = 0; p.db_sh = a.db_tokens; }  // [H, tokens]: the kernel adds the sequence's first token
   p.kv_group = a.H / Hkv;
   p.Nk = Nk == a.N ? 0 : Nk;
+  p.qoff = a.end_aligned ? Nk - a.N : 0;
   p.clock = clock_probe();
   if (SOFTMAX) {
     if (!a.lse) return SATTN_ERR_NULL;
@@ -708,6 +718,31 @@ int sigmoid_attn_cross_bwd(const void* q, const void* k, const void* v, const vo
   BwdArgs a{q, k, v, nullptr, nullptr, dout, dq, dk, dv, B, H, Nq, d, dtype, bias, 0, nullptr,
             sq, sk, sv, nullptr, sdout, sdq, sdk, sdv, nullptr, 0, kBwdDkDv | kBwdDq, stream};
   a.Nk = Nk;
+  return bwd_impl<false>(a);
+}
+
+int sigmoid_attn_cross_aligned_fwd(const void* q, const void* k, const void* v, void* o, int B, int H, int Nq, int Nk,
+                                   int d, sattn_dtype dtype, float bias, int causal, const float* alibi_slopes,
+                                   const sattn_strides* sq, const sattn_strides* sk, const sattn_strides* sv,
+                                   const sattn_strides* so, void* stream) {
+  if (Nk <= 0) return SATTN_ERR_SHAPE;
+  FwdArgs a{q, k, v, o, nullptr, B, H, Nq, d, dtype, bias, causal, alibi_slopes, sq, sk, sv, so, stream};
+  a.Nk = Nk;
+  a.end_aligned = true;
+  return fwd_impl<false>(a);
+}
+
+int sigmoid_attn_cross_aligned_bwd(const void* q, const void* k, const void* v, const void* dout, void* dq, void* dk,
+                                   void* dv, int B, int H, int Nq, int Nk, int d, sattn_dtype dtype, float bias,
+                                   int causal, const float* alibi_slopes, const sattn_strides* sq,
+                                   const sattn_strides* sk, const sattn_strides* sv, const sattn_strides* sdout,
+                                   const sattn_strides* sdq, const sattn_strides* sdk, const sattn_strides* sdv,
+                                   void* stream) {
+  if (Nk <= 0) return SATTN_ERR_SHAPE;
+  BwdArgs a{q, k, v, nullptr, nullptr, dout, dq, dk, dv, B, H, Nq, d, dtype, bias, causal, alibi_slopes,
+            sq, sk, sv, nullptr, sdout, sdq, sdk, sdv, nullptr, 0, kBwdDkDv | kBwdDq, stream};
+  a.Nk = Nk;
+  a.end_aligned = true;
   return bwd_impl<false>(a);
 }
 

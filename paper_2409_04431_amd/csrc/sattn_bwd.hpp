@@ -53,8 +53,10 @@ struct BwdParams {
   // shared key/value heads: query head h reads K/V head h / kv_group (1 = one per query head);
   // k, v, dk, dv then have H / kv_group heads
   int kv_group;
-  // number of keys when it differs from the number of queries N (0: same); non-causal only
+  // number of keys when it differs from the number of queries N (0: same)
   int Nk;
+  // position of query 0 on the key axis (see FwdParams::qoff); a multiple of 32
+  int qoff;
   ClockProbe clock;  // measurement aid, {nullptr, 0} otherwise
 };
 
@@ -539,7 +541,7 @@ __device__ __forceinline__ void attn_bwd_body(const BwdParams& p, const int logi
     if (p.bias_vec) nbias_log2 = -p.bias_vec[b] * kLog2e;
     if (blk * BS >= N) return;  // this sequence has no such block (whole workgroup)
   }
-  // keys may differ in number from queries (cross attention, non-causal only): N counts the
+  // keys may differ in number from queries (cross attention): N counts the
   // queries, Nk the keys; Ns / Nt are the row counts of this pass's stationary / streamed side
   const int Nk = p.Nk > 0 ? p.Nk : N;
   const int Ns = MODE == BWD_DKDV ? Nk : N, Nt = MODE == BWD_DKDV ? N : Nk;
@@ -565,7 +567,10 @@ __device__ __forceinline__ void attn_bwd_body(const BwdParams& p, const int logi
       W.acc0[dt][r] = 0.f;
       if (MODE == BWD_DKDV) W.acc1[dt][r] = 0.f;
     }
-  W.ai = ai; W.h = h;
+  // W.ai is only ever used as a position, compared with or subtracted from the streamed side's
+  // row index: a key's place on the query axis in the dK/dV pass, a query's place on the key
+  // axis in the dQ pass
+  W.ai = MODE == BWD_DKDV ? ai - p.qoff : ai + p.qoff; W.h = h;
   W.nscale = p.nscale_log2; W.nbias = nbias_log2;
   W.nlse = 0.f; W.dstat = 0.f;
   W.dbs[0] = W.dbs[1] = W.dbs[2] = W.dbs[3] = 0.f;
@@ -579,12 +584,17 @@ __device__ __forceinline__ void attn_bwd_body(const BwdParams& p, const int logi
   int wg_lo = 0, wg_hi = n_chunks - 1, c_lo = 0, c_hi = n_chunks - 1;
   if (CAUSAL) {
     if (MODE == BWD_DKDV) {
-      wg_lo = (blk * BS) / 32;  // queries before the block's first key see none of its keys
-      c_lo = a_wave0 / 32;
+      // queries before the block's first key (at place key - qoff on the query axis) see none of its keys
+      const int first = blk * BS - p.qoff, first_w = a_wave0 - p.qoff;
+      wg_lo = (first > 0 ? first : 0) / 32;
+      c_lo = (first_w > 0 ? first_w : 0) / 32;
     } else {
-      const int a_hi = (blk * BS + BS < Nt ? blk * BS + BS : Nt) - 1;
-      wg_hi = a_hi / 32;        // keys after the block's last query are masked
-      c_hi = (a_wave0 + 31 < Nt ? a_wave0 + 31 : Nt - 1) / 32;
+      // keys after the block's last query (at place query + qoff on the key axis) are masked
+      const int a_hi = (blk * BS + BS < Ns ? blk * BS + BS : Ns) - 1 + p.qoff;
+      const int last_w = (a_wave0 + 31 < Ns ? a_wave0 + 31 : Ns - 1) + p.qoff;
+      wg_hi = (a_hi < 0 ? 0 : (a_hi < Nt ? a_hi : Nt - 1)) / 32;
+      c_hi = (last_w < Nt ? last_w : Nt - 1) / 32;
+      if (last_w < 0) { c_lo = 1; c_hi = 0; }  // every key lies after this wave's queries
     }
   }
   if (a_wave0 >= Ns) { c_lo = 1; c_hi = 0; }  // wave past the end: no chunks
@@ -705,8 +715,8 @@ __device__ __forceinline__ void attn_bwd_body(const BwdParams& p, const int logi
     // outside it) is cheaper in the flag-driven form, which skips the dead stages
     pin = PIN && !SOFTMAX && !(MODE == BWD_DKDV && ragged) && (int)doA + (int)doS + (int)doB >= 2;
     if (!doS) thr = NONE;
-    else if (MODE == BWD_DKDV) thr = (CAUSAL && s - 1 == c_lo_s) ? ai - bl : ALL;
-    else thr = (s - 1 == c_hi_s) ? ((CAUSAL && ai < Nt - 1 ? ai : Nt - 1) - bl) : ALL;
+    else if (MODE == BWD_DKDV) thr = (CAUSAL && s - 1 == c_lo_s) ? W.ai - bl : ALL;
+    else thr = (s - 1 == c_hi_s) ? ((CAUSAL && W.ai < Nt - 1 ? W.ai : Nt - 1) - bl) : ALL;
   };
   // A wave issues about one instruction every six cycles whatever the instruction, so the
   // per-tile control flow is kept out of the steady state: tiles whose two steps are both

@@ -41,6 +41,10 @@ struct F32Params {
   const float* bias_vec;
   int kv_group;
   int Nk;
+  // position of query 0 on the key axis (Nk - N when the queries are the last N positions of the
+  // key sequence, else 0; any value here): causal keeps key j for query i iff j <= i + qoff,
+  // ALiBi measures |i + qoff - j|
+  int qoff;
 };
 
 __device__ __forceinline__ f32x16 mfma_f32(float a, float b, f32x16 c) {
@@ -119,8 +123,13 @@ sigmoid_f32_kernel(const F32Params p) {
   const int a_hi = (blk * BS + BS < Ns ? blk * BS + BS : Ns) - 1;
   int t_lo = 0, t_hi = (Nt + 31) / 32;
   if (CAUSAL) {
-    if (MODE == F32_DKDV) t_lo = (blk * BS) / 32;  // queries before the first key see nothing
-    else t_hi = a_hi / 32 + 1;                      // keys after the last query are masked
+    if (MODE == F32_DKDV) {  // queries before the first key's place on the query axis see nothing
+      const int first = blk * BS - p.qoff;
+      t_lo = (first > 0 ? first : 0) / 32;
+    } else {                 // keys after the last query's place on the key axis are masked
+      const int last = a_hi + p.qoff;
+      t_hi = last < 0 ? 0 : (last < Nt ? last : Nt - 1) / 32 + 1;
+    }
   }
 
   for (int hq = hq0; hq < hq0 + n_hq; ++hq) {  // one pass over the streamed side per query head
@@ -146,8 +155,8 @@ sigmoid_f32_kernel(const F32Params p) {
     // wave-uniform skip of tiles that are entirely masked for this wave
     bool live = a_wave0 < Ns;
     if (CAUSAL) {
-      if (MODE == F32_DKDV) live = live && (b0 + 31 >= a_wave0);  // some query >= some key
-      else live = live && (b0 <= a_wave0 + 31);                   // some key <= some query
+      if (MODE == F32_DKDV) live = live && (b0 + 31 + p.qoff >= a_wave0);  // some query at or after some key
+      else live = live && (b0 <= a_wave0 + 31 + p.qoff);                   // some key at or before some query
     }
     if (!live) continue;
 
@@ -165,7 +174,7 @@ sigmoid_f32_kernel(const F32Params p) {
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
       const int bi = b0 + 8 * (r >> 2) + 4 * h + (r & 3);
-      const int qrow = MODE == F32_DKDV ? bi : ai;
+      const int qrow = (MODE == F32_DKDV ? bi : ai) + p.qoff;  // the query's place on the key axis
       const int krow = MODE == F32_DKDV ? ai : bi;
       float tt = s[r] * p.scale + bias;
       if (ALIBI) tt -= slope * fabsf((float)(qrow - krow));

@@ -38,8 +38,13 @@ struct FwdParams {
   const float* bias_vec;
   // shared key/value heads: query head h reads K/V head h / kv_group (1 = one per query head)
   int kv_group;
-  // number of keys when it differs from the number of queries N (0: same); non-causal only
+  // number of keys when it differs from the number of queries N (0: same)
   int Nk;
+  // position of query 0 on the key axis (Nk - N when the queries are the last N positions of the
+  // key sequence, else 0): the causal mask keeps key j for query i iff j <= i + qoff, and ALiBi
+  // measures |i + qoff - j|.  A multiple of 32 in these kernels (a wave's query rows and a key
+  // chunk then still meet in one diagonal chunk).
+  int qoff;
   ClockProbe clock;  // measurement aid, {nullptr, 0} otherwise
 };
 
@@ -638,7 +643,7 @@ attn_fwd_kernel(const FwdParams p) {
       int c = 4 * dt + 2 * blk1 + ((i16 & 3) >> 1);
       W.voff[dt] = vring + row * (D * 2) + ((c ^ Swz<D>::v(row)) << 4) + ((i16 & 1) << 3);
     }
-    W.qi = qi; W.h = h;
+    W.qi = qi + p.qoff; W.h = h;  // (W.qi is only ever used as a position)
     W.nscale = p.nscale_log2; W.nbias = nbias_log2;
     W.sl2 = ALIBI ? p.slopes[hd] * kLog2e : 0.f;
     W.sm = SoftmaxState{-__builtin_inff(), 0.f};
@@ -657,10 +662,14 @@ attn_fwd_kernel(const FwdParams p) {
   // keys this workgroup must visit, and chunks this wave must visit
   const int q_hi = (qb * BR + BR < N ? qb * BR + BR : N) - 1;  // last valid query row of the block
   const int Nk = p.Nk > 0 ? p.Nk : N;  // keys (N counts the queries)
-  const int kv_len = CAUSAL ? (q_hi + 1) : Nk;
+  auto visible = [&](int rows) {  // keys visible to the first `rows` queries: positions < rows + qoff
+    const int kv = rows + p.qoff;
+    return kv < 0 ? 0 : (kv < Nk ? kv : Nk);
+  };
+  const int kv_len = CAUSAL ? visible(q_hi + 1) : Nk;
   const int n_tiles = (kv_len + BC - 1) / BC;
   int kv_wave = Nk;
-  if (CAUSAL) kv_wave = q_wave0 + 32 < N ? q_wave0 + 32 : N;
+  if (CAUSAL) kv_wave = visible(q_wave0 + 32 < N ? q_wave0 + 32 : N);
   const int cw = q_wave0 < N ? (kv_wave + 31) / 32 : 0;  // chunks 0..cw-1; waves past the end idle
 
   // LDS rings: K tile t in K slot t%3, V tile t in V slot t%VS.  At the start of tile t the

@@ -266,14 +266,18 @@ attn_fwd64_kernel(const FwdParams p) {
   // keys this workgroup must visit, and chunks each row block of this wave must visit
   const int q_hi = (qb * BR + BR < N ? qb * BR + BR : N) - 1;  // last valid query row of the block
   const int Nk = p.Nk > 0 ? p.Nk : N;  // keys (N counts the queries)
-  const int kv_len = CAUSAL ? (q_hi + 1) : Nk;
+  auto visible = [&](int rows) {  // keys visible to the first `rows` queries: positions < rows + qoff
+    const int kv = rows + p.qoff;
+    return kv < 0 ? 0 : (kv < Nk ? kv : Nk);
+  };
+  const int kv_len = CAUSAL ? visible(q_hi + 1) : Nk;
   const int n_tiles = (kv_len + BC - 1) / BC;
   int cw[2];
 #pragma unroll
   for (int rb = 0; rb < 2; ++rb) {
     const int q0 = q_wave0 + 32 * rb;
     int kv = Nk;
-    if (CAUSAL) kv = q0 + 32 < N ? q0 + 32 : N;
+    if (CAUSAL) kv = visible(q0 + 32 < N ? q0 + 32 : N);
     cw[rb] = __builtin_amdgcn_readfirstlane(q0 < N ? (kv + 31) / 32 : 0);  // chunks 0..cw-1; row blocks past the end idle
   }
 
@@ -339,7 +343,7 @@ attn_fwd64_kernel(const FwdParams p) {
       int c = 4 * dt + 2 * blk1 + ((i16 & 3) >> 1);
       W.voff[dt] = vring + row * (D * 2) + ((c ^ Swz<D>::v(row)) << 4) + ((i16 & 1) << 3);
     }
-    W.qi0 = qi0; W.h = h;
+    W.qi0 = qi0 + p.qoff; W.h = h;  // (a position: the row's place on the key axis)
     W.nscale = p.nscale_log2; W.nbias = nbias_log2;
     W.sl2 = ALIBI ? p.slopes[hd] * kLog2e : 0.f;
     // wave-uniform: into a scalar register, so that the fma reads it as its one scalar operand
@@ -363,8 +367,8 @@ attn_fwd64_kernel(const FwdParams p) {
 
   clock_probe_mark(p.clock, clk, kMarkFirstProduct);
   // step -1: S^T(0) into s[0], then fetch K(1).  (cw[1] is either 0, row block 1 lying past
-  // the end, or >= cw[0].)
-  if (cw[0] > 0) {
+  // the end, or >= cw[0]; cw[0] alone is 0 when only row block 0 lies before the first key.)
+  if (cw[0] > 0 || cw[1] > 0) {
 #pragma unroll
     for (int kk = 0; kk < KD; ++kk) W.kf[kk] = as_bf16x8(lds_read_b128(W.koff[kk]));
 #pragma unroll
@@ -446,7 +450,7 @@ attn_fwd64_kernel(const FwdParams p) {
       live = live || full || last || tail;
       const int jl = 32 * c + 8 * h;           // key held by register 0 of this lane half
       int lim = Nk - 1 - jl;                    // LAST: registers whose key offset exceeds lim are masked
-      if (CAUSAL) lim = lim < qi0 + 32 * rb - jl ? lim : qi0 + 32 * rb - jl;
+      if (CAUSAL) lim = lim < W.qi0 + 32 * rb - jl ? lim : W.qi0 + 32 * rb - jl;
       thr[rb] = full ? 1000 : last ? lim : -1000;
     }
     if (!live) return;

@@ -202,6 +202,22 @@ def test_cross_attention_entry_points_reject_bad_arguments(lib):
     assert lib.sigmoid_attn_cross_bwd(*bptrs, 1, 2, 64, 96, 64, 0, 0.0, *([None] * 7), None) == -1
 
 
+def test_end_aligned_cross_attention_entry_points_reject_bad_arguments(lib):
+    ptrs = [0x1000, 0x2000, 0x3000, 0x4000]
+    f = lambda Nq=64, Nk=96, d=64, dtype=0, causal=1, q=0x1000: lib.sigmoid_attn_cross_aligned_fwd(
+        q, *ptrs[1:], 1, 2, Nq, Nk, d, dtype, 0.0, causal, None, None, None, None, None, None)
+    assert f(Nk=0) == -2 and f(Nq=0) == -2
+    assert f(dtype=2) == -3 and f(d=96) == -3
+    assert f(Nq=64, Nk=100) == -3                   # bf16 + causal: the offset must be a multiple of 32
+    assert f(Nq=100, Nk=64) == -3
+    assert f(q=None) == -1
+    bptrs = [0x1000, 0x2000, 0x3000, 0x4000, 0x5000, None, 0x7000]
+    g = lambda Nq, Nk, causal: lib.sigmoid_attn_cross_aligned_bwd(*bptrs, 1, 2, Nq, Nk, 64, 0, 0.0, causal, None,
+                                                                  *([None] * 7), None)
+    assert g(64, 96, 1) == -1                       # dk missing
+    assert g(64, 100, 1) == -3
+
+
 def test_binding_refuses_cpu_tensors():
     import torch
     t = torch.zeros(1, 1, 8, 64, dtype=torch.bfloat16)

@@ -1069,3 +1069,90 @@ def test_cross_attention_matches_oracle(B, H, Nq, Nk, d):
         sa.sigmoid_attn_bwd(Q, K, V, DO, dq2, dk2, dv2, bias)
         torch.cuda.synchronize()
         assert torch.equal(o, o2) and torch.equal(dq, dq2) and torch.equal(dk, dk2) and torch.equal(dv, dv2)
+
+
+def _aligned_case(B, H, Nq, Nk, d, causal, alibi, dtype, seed):
+    g = torch.Generator().manual_seed(seed)
+    cast = (lambda t: t.bfloat16()) if dtype == torch.bfloat16 else (lambda t: t)
+    q, do = (cast(torch.randn(B, H, Nq, d, generator=g)) for _ in range(2))
+    k, v = (cast(torch.randn(B, H, Nk, d, generator=g)) for _ in range(2))
+    slopes = W.alibi_slopes(H) if alibi else None
+    sl = _dev(slopes) if slopes is not None else None
+    bias = -math.log(max(Nk, 2))
+    Q, K, V, DO = (_dev(t) for t in (q, k, v, do))
+    (o, g0), (dq, g1) = (_guarded(Q.shape, dtype) for _ in range(2))
+    (dk, g2), (dv, g3) = (_guarded(K.shape, dtype) for _ in range(2))
+    sa.sigmoid_attn_cross_aligned_fwd(Q, K, V, o, bias, causal, sl)
+    sa.sigmoid_attn_cross_aligned_bwd(Q, K, V, DO, dq, dk, dv, bias, causal, sl)
+    torch.cuda.synchronize()
+    for guard in (g0, g1, g2, g3):
+        guard()
+    f = lambda t: t.double().numpy()
+    sl64 = None if slopes is None else slopes.double().numpy()
+    ro = orc.sigmoid_attn_cross_fwd(f(q), f(k), f(v), bias, causal, sl64)
+    rdq, rdk, rdv = orc.sigmoid_attn_cross_bwd(f(q), f(k), f(v), f(do), bias, causal, sl64)
+    return (Q, K, V, DO, sl, bias), (o, dq, dk, dv), (ro, rdq, rdk, rdv)
+
+
+# Queries placed at the end of the key sequence (a prefix of keys and values is already there):
+# the causal mask and ALiBi of that placement.  bf16 offsets are multiples of 32 under the mask.
+@pytest.mark.parametrize("B,H,Nq,Nk,d,causal,alibi", [
+    (1, 2, 300, 1100, 128, True, False),     # a prefix of 800 keys, ragged
+    (1, 2, 300, 1100, 128, True, True),
+    (2, 1, 1024, 256, 128, True, True),      # fewer keys than queries: the first 768 queries see none
+    (1, 3, 1, 705, 64, True, True),          # one new token
+    (1, 2, 640, 32, 64, True, False),
+    (1, 1, 129, 2049, 64, True, True),
+    (1, 2, 1500, 3100, 128, True, True),     # steady-state loops of every kernel
+    (1, 2, 1500, 3100, 64, True, False),
+    (1, 2, 1100, 940, 128, True, True),      # offset -160: a 64-row wave whose first row block sees no key
+    (1, 2, 300, 1001, 128, False, True),     # no mask: any offset; ALiBi measured from the shifted position
+    (1, 2, 1001, 300, 64, False, True),
+])
+def test_end_aligned_cross_attention_matches_oracle(B, H, Nq, Nk, d, causal, alibi):
+    args, got, ref = _aligned_case(B, H, Nq, Nk, d, causal, alibi, torch.bfloat16, 7100 + Nq + Nk)
+    for name, x, r in zip(("o", "dq", "dk", "dv"), got, ref):
+        assert not torch.isnan(x).any(), name
+        assert nerr(x, r) <= TOL_BF16, f"{name}: {nerr(x, r):.3e}"
+    Q, K, V, DO, sl, bias = args
+    if d == 128 and (causal or not alibi):   # the 64-row forward shape (no ALiBi without the mask) computes the same numbers
+        try:
+            sa.sattn_set_fwd_waves(64)
+            o64 = torch.full_like(Q, float("nan"))
+            sa.sigmoid_attn_cross_aligned_fwd(Q, K, V, o64, bias, causal, sl)
+            torch.cuda.synchronize()
+        finally:
+            sa.sattn_set_fwd_waves(0)
+        assert torch.equal(o64, got[0])
+
+
+def test_end_aligned_cross_attention_with_equal_counts_is_self_attention():
+    B, H, N, d = 1, 2, 777, 128
+    args, got, _ = _aligned_case(B, H, N, N, d, True, True, torch.bfloat16, 7177)
+    Q, K, V, DO, sl, bias = args
+    o2, dq2, dk2, dv2 = (torch.empty_like(Q) for _ in range(4))
+    sa.sigmoid_attn_fwd(Q, K, V, o2, bias, True, sl)
+    sa.sigmoid_attn_bwd(Q, K, V, DO, dq2, dk2, dv2, bias, True, sl)
+    torch.cuda.synchronize()
+    for a, b_ in zip(got, (o2, dq2, dk2, dv2)):
+        assert torch.equal(a, b_)
+
+
+def test_end_aligned_cross_attention_rejects_unaligned_offsets_in_bf16():
+    q = torch.zeros(1, 1, 64, 64, dtype=torch.bfloat16, device="cuda")
+    k = torch.zeros(1, 1, 100, 64, dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(sa.SattnError):
+        sa.sigmoid_attn_cross_aligned_fwd(q, k, k, torch.empty_like(q), 0.0, True)
+
+
+@pytest.mark.parametrize("B,H,Nq,Nk,d,causal,alibi", [
+    (1, 2, 100, 333, 64, True, True),        # any offset in fp32
+    (1, 1, 333, 100, 128, True, False),
+    (2, 2, 65, 64, 64, True, True),
+    (1, 2, 50, 1000, 128, False, True),
+    (1, 1, 257, 290, 128, True, True),
+])
+def test_fp32_end_aligned_cross_attention_matches_oracle(B, H, Nq, Nk, d, causal, alibi):
+    _, got, ref = _aligned_case(B, H, Nq, Nk, d, causal, alibi, torch.float32, 7300 + Nq + Nk)
+    for name, x, r in zip(("o", "dq", "dk", "dv"), got, ref):
+        assert nerr(x, r) <= TOL_F32, f"{name}: {nerr(x, r):.3e}"
