@@ -17,15 +17,17 @@ extern "C" {
 #endif
 
 /* Force the forward tile shape for measurements (Appendix F.5: the block shape is a tuning
- * parameter): waves in {4, 8, 32, 64, 65}, v_slots in {2, 3}; 0 = back to the automatic choice; a
- * forced v_slots only applies where that shape exists, a forced 64 / 65 only for the pinned
+ * parameter): waves in {4, 8, 32, 64, 65, 66}, v_slots in {2, 3}; 0 = back to the automatic choice; a
+ * forced v_slots only applies where that shape exists, a forced 64 / 65 / 66 only for the pinned
  * sigmoid kernel at d = 128 (other kernels then run a 4-wave shape).  32 = the automatic choice
  * among the shapes with 32 query rows per wave (4 or 8 waves), which is the choice every kernel
  * without a 64-row form gets: it lets the sigmoid forward be timed in the shape the softmax
  * forward runs.  64 = four waves of 64 query rows.  65 = the same with Q multiplied by the logit scale and rounded to bf16 once, and
  * the bias applied as a factor, which removes the scale-and-bias fma in front of every exp2: a
  * measurement variant, NOT bit-identical to the other shapes and never chosen automatically (its
- * logit error grows with |q||k|: one more bf16 rounding on an operand).  The value is
+ * logit error grows with |q||k|: one more bf16 rounding on an operand).  66 = as 64 with one
+ * query block per workgroup also under the causal mask (64 deals a head's blocks out in pairs,
+ * longest with shortest, where their number is even).  The value is
  * process-wide (an atomic that every forward launch reads): set it from one thread while no
  * other thread launches, or launches in flight on other threads may take either shape.  Apart
  * from 65, results do not depend on it. */

@@ -352,7 +352,7 @@ def sattn_set_bwd_merged(mode):
 
 
 def sattn_set_fwd_waves(waves):
-    """Force the forward tile shape for measurements (4, 8, 64, 65; 32 = automatic among the 32-row
+    """Force the forward tile shape for measurements (4, 8, 64, 65, 66; 32 = automatic among the 32-row
     shapes); 0 restores the automatic choice."""
     _raise(load_library().sattn_set_fwd_waves(int(waves)), "sattn_set_fwd_waves")
 

@@ -160,7 +160,7 @@ int make_ref(const void* ptr, const sattn_strides* s, int H, int N, int d, sattn
 // two-slot V ring (80 KB) two 4-wave workgroups fit again; they win while a workgroup's key loop
 // is short (per-workgroup prologue, diagonal and barrier waits overlap with the neighbour) and
 // lose a few percent on long loops, where V is staged only one tile ahead.
-std::atomic<int> g_fwd_waves{0};   // 0: choose per problem; 4, 8, 64, 65: forced; 32: choose among the 32-row shapes
+std::atomic<int> g_fwd_waves{0};   // 0: choose per problem; 4, 8, 64, 65, 66: forced; 32: choose among the 32-row shapes
 std::atomic<int> g_fwd_vslots{0};  // 0: choose per problem; 2 or 3: forced (sattn_set_fwd_v_slots)
 std::atomic<int> g_bwd_merged{0};  // 0: choose per problem; 1: one grid wherever that form exists; 2: never (sattn_set_bwd_merged)
 std::atomic<long long*> g_clock_out{nullptr};  // sattn_set_clock_probe
@@ -312,6 +312,12 @@ int fwd_impl(const FwdArgs& a) {
   // the 64-row waves exist for the pinned sigmoid kernel at d = 128, ALiBi only in its causal form
   const bool has64 = !SOFTMAX && PIN && a.d == 128 && !(alibi && !a.causal);
   const FwdShape shape = pick_fwd_shape(a.B, a.H, a.N, a.d, a.causal, has64);
+  // The 64-row causal kernel deals a head's blocks out in pairs of equal work (longest with
+  // shortest) where that still leaves a workgroup per compute unit.  Measured against single
+  // blocks: 2-3.5 % faster from 16 blocks per head (N >= 4096), 3 % slower at 8 (B16 H16 N2048).
+  // (66: single blocks, for that comparison.)
+  const int nb64 = (a.N + 255) / 256;
+  p.pair = shape.waves != 66 && a.causal && nb64 >= 16 && (int64_t)a.B * a.H * (nb64 / 2) >= compute_units();
   if (a.d == 128) return launch_fwd_bf16<128>(p, shape.waves, shape.v_slots, SOFTMAX, PIN, a.causal, alibi, st);
   return launch_fwd_bf16<64>(p, shape.waves, shape.v_slots, SOFTMAX, PIN, a.causal, alibi, st);
 }
@@ -764,7 +770,7 @@ int sattn_headconcat_norm_bwd(const void* x, const void* dy, const float* stats,
 }
 
 int sattn_set_fwd_waves(int waves) {
-  if (waves != 0 && waves != 4 && waves != 8 && waves != 32 && waves != 64 && waves != 65) return SATTN_ERR_UNSUPPORTED;
+  if (waves != 0 && waves != 4 && waves != 8 && waves != 32 && (waves < 64 || waves > 66)) return SATTN_ERR_UNSUPPORTED;
   g_fwd_waves.store(waves, std::memory_order_relaxed);
   return SATTN_OK;
 }

@@ -136,9 +136,10 @@ __device__ __forceinline__ ClockStart clock_probe_begin(const ClockProbe& c) {
 __device__ __forceinline__ void clock_probe_mark(const ClockProbe& c, ClockStart& s, int which) {
   if (c.out) s.mark[which] = (int)(wall_clock64() - s.ticks);
 }
-__device__ __forceinline__ void clock_probe_end(const ClockProbe& c, const ClockStart& s) {
-  if (c.out && threadIdx.x == 0 && (int)blockIdx.x < c.cap) {
-    long long* o = c.out + 8 * (int64_t)blockIdx.x;
+// `record`: the slot written (one per workgroup, or one per block of a workgroup that handles several)
+__device__ __forceinline__ void clock_probe_end(const ClockProbe& c, const ClockStart& s, int record) {
+  if (c.out && threadIdx.x == 0 && record < c.cap) {
+    long long* o = c.out + 8 * (int64_t)record;
     o[0] = clock64() - s.cycles;
     o[1] = wall_clock64() - s.ticks;
 #pragma unroll
@@ -146,6 +147,9 @@ __device__ __forceinline__ void clock_probe_end(const ClockProbe& c, const Clock
     o[6] = s.steady_tiles;
     o[7] = s.tiles;
   }
+}
+__device__ __forceinline__ void clock_probe_end(const ClockProbe& c, const ClockStart& s) {
+  clock_probe_end(c, s, (int)blockIdx.x);
 }
 
 // Workgroup id -> logical tile id so that consecutive logical ids (which share a head's

@@ -45,6 +45,9 @@ struct FwdParams {
   // measures |i + qoff - j|.  A multiple of 32 in these kernels (a wave's query rows and a key
   // chunk then still meet in one diagonal chunk).
   int qoff;
+  // 64-row causal kernel: every workgroup handles two query blocks of its head, the r-th longest
+  // and the r-th shortest (n_qblocks even), so that all workgroups of a launch do the same work
+  int pair;
   ClockProbe clock;  // measurement aid, {nullptr, 0} otherwise
 };
 

@@ -219,9 +219,10 @@ __device__ __forceinline__ void f64_tile_pinned(F64Wave<D>& W, int t, DmaStager<
   __builtin_amdgcn_s_barrier();
 }
 
+// One query block (256 rows of head bh) from the first load to the last store; `record` is its
+// slot in the clock probe's buffer.
 template <int D, bool CAUSAL, bool ALIBI, bool PRESCALE>
-__global__ void __launch_bounds__(256, 1)
-attn_fwd64_kernel(const FwdParams p) {
+__device__ __forceinline__ void attn_fwd64_block(const FwdParams& p, const int bh, const int qb, const int record) {
   static_assert(!ALIBI || CAUSAL, "ALiBi only in the causal form whose per-element cost folds away");
   static_assert(!(ALIBI && PRESCALE), "the pre-scaled form has no per-step bias");
   constexpr int NW = 4, BR = 64 * NW, BC = 64;
@@ -239,11 +240,6 @@ attn_fwd64_kernel(const FwdParams p) {
   const int l32 = lane & 31, h = lane >> 5;
   ClockStart clk = clock_probe_begin(p.clock);
 
-  const int total = p.n_qblocks * p.B * p.H;
-  const int logical = xcd_remap(blockIdx.x, total);
-  int bh, rank;
-  head_and_rank(logical, p.n_qblocks, p.B * p.H, CAUSAL ? p.head_group : 1, bh, rank);
-  const int qb = CAUSAL ? (p.n_qblocks - 1 - rank) : rank;  // causal: heavy first
   const int b = bh / p.H, hd = bh % p.H;
   int N = p.N;
   int64_t tok0 = 0;
@@ -505,7 +501,29 @@ attn_fwd64_kernel(const FwdParams p) {
       if (qi < N) *(u32x4*)(obase + (int64_t)qi * p.o.ss + c16 * 8) = v4;
     }
   }
-  clock_probe_end(p.clock, clk);
+  clock_probe_end(p.clock, clk, record);
+}
+
+template <int D, bool CAUSAL, bool ALIBI, bool PRESCALE>
+__global__ void __launch_bounds__(256, 1)
+attn_fwd64_kernel(const FwdParams p) {
+  // blocks of a head this launch deals out: pairs (longest with shortest, ...) or single blocks
+  const int places = (CAUSAL && p.pair) ? p.n_qblocks / 2 : p.n_qblocks;
+  const int logical = xcd_remap(blockIdx.x, places * p.B * p.H);
+  int bh, rank;
+  head_and_rank(logical, places, p.B * p.H, CAUSAL ? p.head_group : 1, bh, rank);
+  // Under the causal mask block q of a head visits q + 1 key tiles (in units of the block):
+  // blocks n-1-r and r together visit n + 1 whatever r is.  Equal workgroups leave no ragged
+  // end of the launch, and a compute unit pays the gap between two workgroups half as often.
+  const int n_parts = (CAUSAL && p.pair) ? 2 : 1;
+#pragma nounroll
+  for (int part = 0; part < n_parts; ++part) {
+    // causal: heavy first, within a pair and (single blocks) within the launch
+    const int qb = (CAUSAL && part == 0) ? p.n_qblocks - 1 - rank : rank;
+    attn_fwd64_block<D, CAUSAL, ALIBI, PRESCALE>(p, bh, qb, (int)(blockIdx.x + part * gridDim.x));
+    // the block's epilogue reads the ring that the next block's first loads refill
+    if (part + 1 < n_parts) __syncthreads();
+  }
 }
 
 }  // namespace sattn

@@ -841,6 +841,49 @@ def test_forward_with_64_row_waves(B, H, N, d, causal, alibi):
         assert e <= TOL_BF16 and er <= TOL_BF16, f"shape {shape}: {e:.3e}, worst row {er:.3e}"
 
 
+@pytest.mark.parametrize("B,H,N,alibi", [(16, 16, 4096, False), (8, 32, 4100, True), (2, 64, 7600, True)])
+def test_forward_with_paired_causal_blocks(B, H, N, alibi):
+    """Causal launches of the 64-row forward deal a head's blocks out in pairs (longest with
+    shortest) when there are at least 16 of them and a pair per compute unit: same numbers as
+    single blocks (forced shape 66), bit for bit; sampled rows against the oracle; and the clock
+    probe still gets one record per block.  N = 4100 has 17 blocks (odd: not paired)."""
+    d = 128
+    g = torch.Generator().manual_seed(6600 + N)
+    q, k, v = (torch.randn(B, H, N, d, generator=g).bfloat16() for _ in range(3))
+    slopes = W.alibi_slopes(H) if alibi else None
+    sl = _dev(slopes) if slopes is not None else None
+    bias = -math.log(N)
+    Q, K, V = (_dev(t) for t in (q, k, v))
+    outs = {}
+    n_blocks = B * H * ((N + 255) // 256)
+    buf = torch.zeros(8 * n_blocks + 64, dtype=torch.int64, device="cuda")
+    buf[8 * n_blocks:] = -7
+    try:
+        for shape in (66, 64):
+            sa.sattn_set_fwd_waves(shape)
+            o, guard = _guarded(Q.shape)
+            if shape == 64:
+                sa.sattn_set_clock_probe(buf[:8 * n_blocks])
+            sa.sigmoid_attn_fwd(Q, K, V, o, bias, True, sl)
+            torch.cuda.synchronize()
+            guard()
+            outs[shape] = o
+    finally:
+        sa.sattn_set_clock_probe(None)
+        sa.sattn_set_fwd_waves(0)
+    assert not torch.isnan(outs[64]).any() and torch.equal(outs[64], outs[66])
+    rec = buf[:8 * n_blocks].view(-1, 8).cpu()
+    assert bool((buf[8 * n_blocks:] == -7).all()) and bool((rec[:, 1] > 0).all())   # every block left its record
+    assert int(rec[:, 7].sum()) == B * H * sum(min((256 * (b + 1) + 63) // 64, (N + 63) // 64) for b in range((N + 255) // 256))
+    rows = np.array(sorted({0, 31, 255, 256, N // 2, N - 257, N - 1}))
+    f = lambda t: t.double().numpy()
+    for (b, h) in ((0, 0), (B - 1, H - 1), (B // 2, 3)):
+        ref = orc.sigmoid_attn_fwd_rows(f(q[b, h]), f(k[b, h]), f(v[b, h]), bias, True,
+                                        0.0 if slopes is None else float(slopes[h]), rows)
+        got = outs[64][b, h][torch.as_tensor(rows, device="cuda")]
+        assert row_err(got, ref) <= TOL_BF16, f"{(b, h)}: {row_err(got, ref):.3e}"
+
+
 def test_forward_with_64_row_waves_on_packed_shared_and_cross_inputs():
     # the entry points that reuse the forward kernels: variable-length batches, shared K/V heads,
     # different numbers of queries and keys -- each against its own 32-row result, bit for bit
