@@ -36,7 +36,8 @@ int sattn_set_fwd_v_slots(int v_slots);
 
 /* Force (1) or forbid (2) the one-grid form of the sigmoid backward, in which the dK/dV and
  * the dQ workgroups of Algorithm 2's two output owners share one launch; 0 = back to the
- * automatic choice.  Only sigmoid_attn_bwd / sigmoid_attn_varlen_bwd have that form (both
+ * automatic choice; 3 = forbid it and also keep one block per workgroup in the causal passes
+ * (which otherwise deal a long head's blocks out in pairs, longest with shortest).  Only sigmoid_attn_bwd / sigmoid_attn_varlen_bwd have that form (both
  * passes, self-attention, one K/V head per query head, no bias gradient).  Results do not
  * depend on it.  Process-wide like the setters above.  Returns 0 or SATTN_ERR_UNSUPPORTED. */
 int sattn_set_bwd_merged(int mode);

@@ -347,7 +347,8 @@ def sattn_bwd_merged(B, H, N, causal=False):
 
 
 def sattn_set_bwd_merged(mode):
-    """1 forces, 2 forbids the one-grid form of the sigmoid backward; 0 restores the automatic choice."""
+    """1 forces, 2 forbids the one-grid form of the sigmoid backward (3: forbids it and the pairing of
+    causal blocks as well); 0 restores the automatic choice."""
     _raise(load_library().sattn_set_bwd_merged(int(mode)), "sattn_set_bwd_merged")
 
 

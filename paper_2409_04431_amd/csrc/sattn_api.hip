@@ -6,6 +6,7 @@
 #include <hip/hip_runtime.h>
 #include <math.h>
 
+#include <algorithm>
 #include <atomic>
 #include <mutex>
 #include <map>
@@ -162,7 +163,7 @@ int make_ref(const void* ptr, const sattn_strides* s, int H, int N, int d, sattn
 // lose a few percent on long loops, where V is staged only one tile ahead.
 std::atomic<int> g_fwd_waves{0};   // 0: choose per problem; 4, 8, 64, 65, 66: forced; 32: choose among the 32-row shapes
 std::atomic<int> g_fwd_vslots{0};  // 0: choose per problem; 2 or 3: forced (sattn_set_fwd_v_slots)
-std::atomic<int> g_bwd_merged{0};  // 0: choose per problem; 1: one grid wherever that form exists; 2: never (sattn_set_bwd_merged)
+std::atomic<int> g_bwd_merged{0};  // 0: choose per problem; 1: one grid wherever that form exists; 2: never; 3: never, and single blocks (sattn_set_bwd_merged)
 std::atomic<long long*> g_clock_out{nullptr};  // sattn_set_clock_probe
 std::atomic<int> g_clock_cap{0};
 ClockProbe clock_probe() { return ClockProbe{g_clock_out.load(std::memory_order_relaxed), g_clock_cap.load(std::memory_order_relaxed)}; }
@@ -436,6 +437,10 @@ int bwd_impl(const BwdArgs& a) {
     p.nlse2 = nlse2; p.dvec = dvec; p.npad = npad;
   }
   const bool merged = pick_bwd_merged(a.B, a.H, a.N, a.causal);
+  // causal passes deal a head's blocks out in pairs of equal work (longest with shortest) where
+  // a head has at least 16 and a pair per compute unit remains (see the 64-row forward)
+  p.pair = a.causal && !SOFTMAX && PIN && g_bwd_merged.load(std::memory_order_relaxed) != 3 &&
+           (int64_t)a.B * Hkv * ((std::min(a.N, Nk) + 127) / 128 / 2) >= compute_units();
   if (a.d == 128) rc = launch_bwd_bf16<128>(p, SOFTMAX, PIN, a.causal, alibi, a.parts, merged, st);
   else rc = launch_bwd_bf16<64>(p, SOFTMAX, PIN, a.causal, alibi, a.parts, merged, st);
   if (rc == SATTN_OK && a.db) {
@@ -781,7 +786,7 @@ int sattn_bwd_merged(int B, int H, int N, int causal) {
 }
 
 int sattn_set_bwd_merged(int mode) {
-  if (mode < 0 || mode > 2) return SATTN_ERR_UNSUPPORTED;
+  if (mode < 0 || mode > 3) return SATTN_ERR_UNSUPPORTED;
   g_bwd_merged.store(mode, std::memory_order_relaxed);
   return SATTN_OK;
 }

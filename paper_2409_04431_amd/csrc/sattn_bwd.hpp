@@ -57,6 +57,9 @@ struct BwdParams {
   int Nk;
   // position of query 0 on the key axis (see FwdParams::qoff); a multiple of 32
   int qoff;
+  // causal passes: every workgroup handles two blocks of its head, the r-th longest and the r-th
+  // shortest (n_blocks even), so that all workgroups of a launch do the same work
+  int pair;
   ClockProbe clock;  // measurement aid, {nullptr, 0} otherwise
 };
 
@@ -508,9 +511,12 @@ __device__ __forceinline__ void bwd_step_full_pinned(BwdWave<D, MODE>& W, uint32
 // always uses): the like-for-like counterpart for comparisons.
 // GROUPS (dK/dV pass only) compiles the loop over the query heads that share a K/V head; without
 // it the pass handles exactly one query head per K/V head and p.kv_group must be 1.
-// `logical` is the workgroup's place in the pass: consecutive values share a head.
+// One block (128 rows of the stationary side) of head bh -- a K/V head in the dK/dV pass, a
+// query head in the dQ pass -- from the first load to the last store; `record` is its slot in
+// the clock probe's buffer.
 template <int D, int MODE, bool CAUSAL, bool ALIBI, bool SOFTMAX, bool PIN = true, bool GROUPS = false>
-__device__ __forceinline__ void attn_bwd_body(const BwdParams& p, const int logical) {
+__device__ __forceinline__ void attn_bwd_body(const BwdParams& p, const int bh, const int blk, const int record,
+                                              const int tid) {
   static_assert(!GROUPS || MODE == BWD_DKDV, "only the dK/dV pass iterates over query heads");
   constexpr int NW = 4, BS = 32 * NW, BC = 64, KD = D / 16, DT = D / 32;
   constexpr bool FOLD = !SOFTMAX && CAUSAL && ALIBI;  // see bwd_step
@@ -518,17 +524,13 @@ __device__ __forceinline__ void attn_bwd_body(const BwdParams& p, const int logi
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   const uint32_t lds0 = (uint32_t)(uintptr_t)(SATTN_LDS(char)*)smem;
 
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, h = lane >> 5;
+  const int wave = tid >> 6, lane = tid & 63, l32 = lane & 31, h = lane >> 5;
   const int uwave = __builtin_amdgcn_readfirstlane(wave);
   ClockStart clk = clock_probe_begin(p.clock);
   // the dK/dV pass runs one workgroup per K/V head and key block and streams the query heads
   // of that head's group one after the other; the dQ pass runs per query head
   const int kv_group = (MODE == BWD_DKDV && !GROUPS) ? 1 : p.kv_group;
   const int heads = MODE == BWD_DKDV ? p.H / kv_group : p.H;
-  int bh, rank;
-  head_and_rank(logical, p.n_blocks, p.B * heads, CAUSAL ? p.head_group : 1, bh, rank);
-  // causal: heavy blocks first (late query blocks for DQ, early key blocks for DKDV)
-  const int blk = (CAUSAL && MODE != BWD_DKDV) ? (p.n_blocks - 1 - rank) : rank;
   const int b = bh / heads, hd = bh % heads;  // hd: K/V head (dK/dV pass) or query head (dQ pass)
   const int hkv = MODE == BWD_DKDV ? hd : hd / kv_group;
   const int hq0 = MODE == BWD_DKDV ? hd * kv_group : hd, n_hq = MODE == BWD_DKDV ? kv_group : 1;
@@ -844,7 +846,21 @@ __device__ __forceinline__ void attn_bwd_body(const BwdParams& p, const int logi
       RowStore<D>::run(W.acc1, 1.0f, obuf + RowStore<D>::BYTES, lane, o1, p.dv.ss, rows_valid);
     }
   }
-  clock_probe_end(p.clock, clk);
+  clock_probe_end(p.clock, clk, record);
+}
+
+// Place `logical` of a pass (consecutive places share a head) -> head and block, a head's blocks
+// in heavy-first order under the causal mask (late query blocks for the dQ pass, early key
+// blocks for the dK/dV pass); `places` = blocks dealt out per head.
+template <int MODE, bool CAUSAL, bool GROUPS>
+__device__ __forceinline__ void bwd_place(const BwdParams& p, int logical, int places, int& bh, int& rank) {
+  const int kv_group = (MODE == BWD_DKDV && !GROUPS) ? 1 : p.kv_group;
+  const int heads = MODE == BWD_DKDV ? p.H / kv_group : p.H;
+  head_and_rank(logical, places, p.B * heads, CAUSAL ? p.head_group : 1, bh, rank);
+}
+template <int MODE, bool CAUSAL>
+__device__ __forceinline__ int bwd_block_of_rank(const BwdParams& p, int rank) {
+  return (CAUSAL && MODE != BWD_DKDV) ? (p.n_blocks - 1 - rank) : rank;
 }
 
 // At d = 64 the ring takes 64 KB, so two workgroups fit a compute unit if the kernel stays within
@@ -855,8 +871,35 @@ template <int D, int MODE, bool CAUSAL, bool ALIBI, bool SOFTMAX, bool PIN = tru
 __global__ void __launch_bounds__(256, ((D == 64 && (SOFTMAX || !PIN)) ? 2 : 1))
 attn_bwd_kernel(const BwdParams p) {
   const int kv_group = (MODE == BWD_DKDV && !GROUPS) ? 1 : p.kv_group;
-  const int total = p.n_blocks * p.B * (MODE == BWD_DKDV ? p.H / kv_group : p.H);
-  attn_bwd_body<D, MODE, CAUSAL, ALIBI, SOFTMAX, PIN, GROUPS>(p, xcd_remap(blockIdx.x, total));
+  // Under the causal mask the r-th longest and the r-th shortest block of a head together stream
+  // the same number of tiles whatever r is: a workgroup that runs such a pair makes all
+  // workgroups of the launch equal (no ragged end) and halves the gaps between workgroups.
+  // (only the pinned sigmoid passes carry the loop: it costs a few registers, which the kernels
+  // held to 256 of them do not have)
+  constexpr bool kCanPair = CAUSAL && !SOFTMAX && PIN && !GROUPS && MODE != BWD_DQ_DB;
+  const bool pair = kCanPair && p.pair;
+  const int places = pair ? p.n_blocks / 2 : p.n_blocks;
+  const int total = places * p.B * (MODE == BWD_DKDV ? p.H / kv_group : p.H);
+  int bh, rank;
+  bwd_place<MODE, CAUSAL, GROUPS>(p, xcd_remap(blockIdx.x, total), places, bh, rank);
+  if constexpr (!kCanPair) {
+    attn_bwd_body<D, MODE, CAUSAL, ALIBI, SOFTMAX, PIN, GROUPS>(p, bh, bwd_block_of_rank<MODE, CAUSAL>(p, rank),
+                                                                (int)blockIdx.x, (int)threadIdx.x);
+    return;
+  }
+  const int n_parts = pair ? 2 : 1;
+#pragma nounroll
+  for (int part = 0; part < n_parts; ++part) {
+    const int blk = bwd_block_of_rank<MODE, CAUSAL>(p, part == 0 ? rank : p.n_blocks - 1 - rank);
+    // The thread index goes in through an opaque copy made inside the loop: nothing derived from
+    // it (lane addresses, swizzles, folded constants) can then be hoisted out of the loop and
+    // held in registers across the whole block, which cost 60-90 registers and spills.
+    int tid = threadIdx.x;
+    asm volatile("" : "+v"(tid));
+    attn_bwd_body<D, MODE, CAUSAL, ALIBI, SOFTMAX, PIN, GROUPS>(p, bh, blk, (int)(blockIdx.x + part * gridDim.x), tid);
+    // the block's epilogue transposes through the ring that the next block's first loads refill
+    if (part + 1 < n_parts) __syncthreads();
+  }
 }
 
 // Both passes of the sigmoid backward in one grid (self-attention, one K/V head per query
@@ -869,8 +912,14 @@ __global__ void __launch_bounds__(256, 1)
 attn_bwd_merged_kernel(const BwdParams p) {
   const int total = p.n_blocks * p.B * p.H;
   const int logical = xcd_remap(blockIdx.x, 2 * total);
-  if (logical & 1) attn_bwd_body<D, BWD_DQ, CAUSAL, ALIBI, false, true, false>(p, logical >> 1);
-  else attn_bwd_body<D, BWD_DKDV, CAUSAL, ALIBI, false, true, false>(p, logical >> 1);
+  int bh, rank;
+  if (logical & 1) {
+    bwd_place<BWD_DQ, CAUSAL, false>(p, logical >> 1, p.n_blocks, bh, rank);
+    attn_bwd_body<D, BWD_DQ, CAUSAL, ALIBI, false, true, false>(p, bh, bwd_block_of_rank<BWD_DQ, CAUSAL>(p, rank), (int)blockIdx.x, (int)threadIdx.x);
+  } else {
+    bwd_place<BWD_DKDV, CAUSAL, false>(p, logical >> 1, p.n_blocks, bh, rank);
+    attn_bwd_body<D, BWD_DKDV, CAUSAL, ALIBI, false, true, false>(p, bh, bwd_block_of_rank<BWD_DKDV, CAUSAL>(p, rank), (int)blockIdx.x, (int)threadIdx.x);
+  }
 }
 
 // Pre-pass of the softmax backward: per query row D_i = sum_t dO[i][t] * O[i][t] (fp32) and

@@ -8,7 +8,12 @@ template <int D, bool SOFTMAX, bool PIN>
 int launch_bwd_variant(BwdParams p, int causal, bool alibi, int parts, bool merged, hipStream_t st) {
   // the dQ pass runs one workgroup per 128 queries, the dK/dV pass one per 128 keys
   const int nb_q = (p.N + 127) / 128, nb_k = ((p.Nk > 0 ? p.Nk : p.N) + 127) / 128;
-  dim3 grid(nb_q * p.B * p.H), grid_k(nb_k * p.B * p.H), grid_kv(nb_k * p.B * (p.H / p.kv_group));
+  // pairs of blocks per workgroup: causal pinned sigmoid passes over equal-length sequences with
+  // one K/V head per query head and an even number (at least 16) of blocks per head
+  const bool may_pair = p.pair && causal && !SOFTMAX && PIN && !p.cu_seqlens && p.kv_group == 1;
+  const bool pair_q = may_pair && !p.db_rows && nb_q % 2 == 0 && nb_q >= 16, pair_k = may_pair && nb_k % 2 == 0 && nb_k >= 16;
+  dim3 grid((pair_q ? nb_q / 2 : nb_q) * p.B * p.H), grid_k((pair_k ? nb_k / 2 : nb_k) * p.B * p.H),
+      grid_kv(nb_k * p.B * (p.H / p.kv_group));
   int rc = SATTN_OK;
   constexpr size_t lds = 4 * 2 * 64 * D * 2;                    // 4 ring slots of two 64-row tiles
   dim3 block(256);
@@ -19,6 +24,7 @@ int launch_bwd_variant(BwdParams p, int causal, bool alibi, int parts, bool merg
     if (parts == (kBwdDkDv | kBwdDq) && p.kv_group == 1 && nb_q == nb_k && p.Nk == 0 && !p.db_rows && merged) {
       p.n_blocks = nb_q;
       p.head_group = heads_abreast(nb_q);
+      p.pair = 0;
       dim3 grid2(2 * nb_q * p.B * p.H);
       SATTN_DISPATCH2(causal, alibi, rc = launch(attn_bwd_merged_kernel<D, A, B2>, grid2, block, lds, st, p));
       return rc;
@@ -27,6 +33,7 @@ int launch_bwd_variant(BwdParams p, int causal, bool alibi, int parts, bool merg
   if (parts & kBwdDkDv) {
     p.n_blocks = nb_k;
     p.head_group = heads_abreast(nb_k);
+    p.pair = pair_k;
     if constexpr (!SOFTMAX && PIN) {
       if (p.kv_group > 1)  // one workgroup per K/V head streams the query heads of its group
         SATTN_DISPATCH2(causal, alibi,
@@ -38,6 +45,7 @@ int launch_bwd_variant(BwdParams p, int causal, bool alibi, int parts, bool merg
   }
   p.n_blocks = nb_q;
   p.head_group = heads_abreast(nb_q);
+  p.pair = pair_q;
   if (rc == SATTN_OK && (parts & kBwdDq)) {
     if constexpr (!SOFTMAX && PIN) {
       if (p.db_rows) {  // the dQ pass that also writes the row sums of dS

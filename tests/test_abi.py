@@ -117,12 +117,13 @@ def test_backward_one_grid_choice(lib):
     assert sa.sattn_bwd_merged(4, 12, 1024) and sa.sattn_bwd_merged(1, 16, 2048, True)
     assert not sa.sattn_bwd_merged(8, 16, 4096, True) and not sa.sattn_bwd_merged(8, 16, 1024)
     assert not sa.sattn_bwd_merged(2, 16, 2048, True)
-    assert lib.sattn_bwd_merged(0, 1, 16, 0) == -2 and lib.sattn_set_bwd_merged(3) == -3
+    assert lib.sattn_bwd_merged(0, 1, 16, 0) == -2 and lib.sattn_set_bwd_merged(4) == -3
     try:
         sa.sattn_set_bwd_merged(1)
         assert sa.sattn_bwd_merged(8, 16, 4096, True)
-        sa.sattn_set_bwd_merged(2)
-        assert not sa.sattn_bwd_merged(4, 12, 1024)
+        for mode in (2, 3):                      # 3 also keeps one block per workgroup
+            sa.sattn_set_bwd_merged(mode)
+            assert not sa.sattn_bwd_merged(4, 12, 1024)
     finally:
         sa.sattn_set_bwd_merged(0)
     assert sa.sattn_bwd_merged(4, 12, 1024)

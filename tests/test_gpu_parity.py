@@ -884,6 +884,57 @@ def test_forward_with_paired_causal_blocks(B, H, N, alibi):
         assert row_err(got, ref) <= TOL_BF16, f"{(b, h)}: {row_err(got, ref):.3e}"
 
 
+@pytest.mark.parametrize("B,H,N,d,alibi", [(8, 8, 2048, 128, True), (4, 16, 2100, 64, False), (16, 4, 4096, 64, True)])
+def test_backward_with_paired_causal_blocks(B, H, N, d, alibi):
+    """The causal backward passes deal a head's 128-row blocks out in pairs (longest with
+    shortest) when there are at least 16 of them, an even number, and a pair per compute unit:
+    same numbers as single blocks (mode 3 of the one-grid setter), bit for bit; sampled rows
+    against the oracle; one clock-probe record per block.  N = 2100 has 17 blocks (not paired)."""
+    g = torch.Generator().manual_seed(6700 + N + d)
+    q, k, v, do = (torch.randn(B, H, N, d, generator=g).bfloat16() for _ in range(4))
+    slopes = W.alibi_slopes(H) if alibi else None
+    sl = _dev(slopes) if slopes is not None else None
+    bias = -math.log(N)
+    Q, K, V, DO = (_dev(t) for t in (q, k, v, do))
+    n_blocks = B * H * ((N + 127) // 128)
+    outs = {}
+    try:
+        for mode in (3, 2):
+            sa.sattn_set_bwd_merged(mode)
+            (dq, g0), (dk, g1), (dv, g2) = (_guarded(Q.shape) for _ in range(3))
+            sa.sigmoid_attn_bwd(Q, K, V, DO, dq, dk, dv, bias, True, sl)
+            torch.cuda.synchronize()
+            for guard in (g0, g1, g2):
+                guard()
+            outs[mode] = (dq, dk, dv)
+        for fn in (lambda: sa.sigmoid_attn_bwd_dkdv(Q, K, V, DO, dk, dv, bias, True, sl),
+                   lambda: sa.sigmoid_attn_bwd_dq(Q, K, V, DO, dq, bias, True, sl)):
+            buf = torch.zeros(8 * n_blocks + 64, dtype=torch.int64, device="cuda")
+            buf[8 * n_blocks:] = -7
+            sa.sattn_set_clock_probe(buf[:8 * n_blocks])
+            fn()
+            torch.cuda.synchronize()
+            sa.sattn_set_clock_probe(None)
+            rec = buf[:8 * n_blocks].view(-1, 8).cpu()
+            assert bool((buf[8 * n_blocks:] == -7).all()) and bool((rec[:, 1] > 0).all())
+    finally:
+        sa.sattn_set_clock_probe(None)
+        sa.sattn_set_bwd_merged(0)
+    for a, b_ in zip(outs[2], outs[3]):
+        assert not torch.isnan(a).any() and torch.equal(a, b_)
+    rows = np.array(sorted({0, 31, 127, 128, N // 2, N - 129, N - 1}))
+    ridx = torch.as_tensor(rows, device="cuda")
+    f = lambda t: t.double().numpy()
+    dq, dk, dv = outs[2]
+    for (b, h) in ((0, 0), (B - 1, H - 1), (B // 2, 1)):
+        slope = 0.0 if slopes is None else float(slopes[h])
+        rq = orc.sigmoid_attn_dq_rows(f(q[b, h]), f(k[b, h]), f(v[b, h]), f(do[b, h]), bias, True, slope, rows)
+        rk, rv = orc.sigmoid_attn_dkdv_rows(f(q[b, h]), f(k[b, h]), f(v[b, h]), f(do[b, h]), bias, True, slope, rows)
+        for name, got, ref in (("dq", dq, rq), ("dk", dk, rk), ("dv", dv, rv)):
+            e = row_err(got[b, h][ridx], ref)
+            assert e <= TOL_BF16, f"{name} {(b, h)}: {e:.3e}"
+
+
 def test_forward_with_64_row_waves_on_packed_shared_and_cross_inputs():
     # the entry points that reuse the forward kernels: variable-length batches, shared K/V heads,
     # different numbers of queries and keys -- each against its own 32-row result, bit for bit
