@@ -438,7 +438,7 @@ int bwd_impl(const BwdArgs& a) {
   }
   const bool merged = pick_bwd_merged(a.B, a.H, a.N, a.causal);
   // causal passes deal a head's blocks out in pairs of equal work (longest with shortest) where
-  // a head has at least 16 and a pair per compute unit remains (see the 64-row forward)
+  // a pair per compute unit remains (see the 64-row forward)
   p.pair = a.causal && !SOFTMAX && PIN && g_bwd_merged.load(std::memory_order_relaxed) != 3 &&
            (int64_t)a.B * Hkv * ((std::min(a.N, Nk) + 127) / 128 / 2) >= compute_units();
   if (a.d == 128) rc = launch_bwd_bf16<128>(p, SOFTMAX, PIN, a.causal, alibi, a.parts, merged, st);

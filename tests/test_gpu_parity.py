@@ -887,7 +887,7 @@ def test_forward_with_paired_causal_blocks(B, H, N, alibi):
 @pytest.mark.parametrize("B,H,N,d,alibi", [(8, 8, 2048, 128, True), (4, 16, 2100, 64, False), (16, 4, 4096, 64, True)])
 def test_backward_with_paired_causal_blocks(B, H, N, d, alibi):
     """The causal backward passes deal a head's 128-row blocks out in pairs (longest with
-    shortest) when there are at least 16 of them, an even number, and a pair per compute unit:
+    shortest) when there is an even number of them (at least 4) and a pair per compute unit:
     same numbers as single blocks (mode 3 of the one-grid setter), bit for bit; sampled rows
     against the oracle; one clock-probe record per block.  N = 2100 has 17 blocks (not paired)."""
     g = torch.Generator().manual_seed(6700 + N + d)
