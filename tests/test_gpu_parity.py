@@ -1220,6 +1220,56 @@ def test_end_aligned_cross_attention_matches_oracle(B, H, Nq, Nk, d, causal, ali
         assert torch.equal(o64, got[0])
 
 
+def test_end_aligned_cross_attention_with_paired_blocks():
+    """Enough heads and blocks that the causal kernels deal the blocks out in pairs, with the
+    queries at the end of a longer key sequence: bit-equal to single blocks, and sampled rows
+    against the square causal oracle on the whole sequence (queries and output gradients of the
+    prefix positions padded with zeros, which changes nothing for the sampled outputs)."""
+    B, H, Nq, Nk, d = 2, 16, 4096, 5120, 128
+    off = Nk - Nq
+    g = torch.Generator().manual_seed(7400)
+    q, do = (torch.randn(B, H, Nq, d, generator=g).bfloat16() for _ in range(2))
+    k, v = (torch.randn(B, H, Nk, d, generator=g).bfloat16() for _ in range(2))
+    slopes = W.alibi_slopes(H)
+    sl = _dev(slopes)
+    bias = -math.log(Nk)
+    Q, K, V, DO = (_dev(t) for t in (q, k, v, do))
+    outs = {}
+    try:
+        for waves, mode in ((66, 3), (0, 0)):
+            sa.sattn_set_fwd_waves(waves)
+            sa.sattn_set_bwd_merged(mode)
+            (o, g0), (dq, g1) = (_guarded(Q.shape) for _ in range(2))
+            (dk, g2), (dv, g3) = (_guarded(K.shape) for _ in range(2))
+            sa.sigmoid_attn_cross_aligned_fwd(Q, K, V, o, bias, True, sl)
+            sa.sigmoid_attn_cross_aligned_bwd(Q, K, V, DO, dq, dk, dv, bias, True, sl)
+            torch.cuda.synchronize()
+            for guard in (g0, g1, g2, g3):
+                guard()
+            outs[waves] = (o, dq, dk, dv)
+    finally:
+        sa.sattn_set_fwd_waves(0)
+        sa.sattn_set_bwd_merged(0)
+    for a, b_ in zip(outs[0], outs[66]):
+        assert not torch.isnan(a).any() and torch.equal(a, b_)
+    o, dq, dk, dv = outs[0]
+    f = lambda t: t.double().numpy()
+    qrows = np.array(sorted({0, 31, 255, 256, Nq // 2, Nq - 257, Nq - 1}))
+    krows = np.array(sorted({0, 127, off - 1, off, off + 130, Nk // 2, Nk - 129, Nk - 1}))
+    for (b, h) in ((0, 0), (1, 15), (1, 6)):
+        qp, dop = np.zeros((Nk, d)), np.zeros((Nk, d))
+        qp[off:], dop[off:] = f(q[b, h]), f(do[b, h])
+        kk, vv, slope = f(k[b, h]), f(v[b, h]), float(slopes[h])
+        ro = orc.sigmoid_attn_fwd_rows(qp, kk, vv, bias, True, slope, qrows + off)
+        rq = orc.sigmoid_attn_dq_rows(qp, kk, vv, dop, bias, True, slope, qrows + off)
+        rk, rv = orc.sigmoid_attn_dkdv_rows(qp, kk, vv, dop, bias, True, slope, krows)
+        qi, ki = torch.as_tensor(qrows, device="cuda"), torch.as_tensor(krows, device="cuda")
+        for name, got, ref in (("o", o[b, h][qi], ro), ("dq", dq[b, h][qi], rq), ("dk", dk[b, h][ki], rk),
+                               ("dv", dv[b, h][ki], rv)):
+            e = row_err(got, ref)
+            assert e <= TOL_BF16, f"{name} {(b, h)}: {e:.3e}"
+
+
 def test_end_aligned_cross_attention_with_equal_counts_is_self_attention():
     B, H, N, d = 1, 2, 777, 128
     args, got, _ = _aligned_case(B, H, N, N, d, True, True, torch.bfloat16, 7177)
