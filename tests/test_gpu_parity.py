@@ -884,7 +884,8 @@ def test_forward_with_paired_causal_blocks(B, H, N, alibi):
         assert row_err(got, ref) <= TOL_BF16, f"{(b, h)}: {row_err(got, ref):.3e}"
 
 
-@pytest.mark.parametrize("B,H,N,d,alibi", [(8, 8, 2048, 128, True), (4, 16, 2100, 64, False), (16, 4, 4096, 64, True)])
+@pytest.mark.parametrize("B,H,N,d,alibi", [(8, 8, 2048, 128, True), (4, 16, 2100, 64, False), (16, 4, 4096, 64, True),
+                                           (4, 4, 4000, 128, True), (8, 8, 1000, 64, False)])   # the last two: ragged last block
 def test_backward_with_paired_causal_blocks(B, H, N, d, alibi):
     """The causal backward passes deal a head's 128-row blocks out in pairs (longest with
     shortest) when there is an even number of them (at least 4) and a pair per compute unit:
