@@ -635,9 +635,17 @@ __device__ __forceinline__ void attn_bwd_body(const BwdParams& p, const int bh, 
 #pragma unroll
   for (int r = 0; r < 16; ++r)  // DKDV: |i-j| = (bl - ai) + key_of_reg(r); DQ: (ai - bl) - key_of_reg(r)
     W.cinit[r] = FOLD ? (MODE == BWD_DKDV ? W.sl2 : -W.sl2) * (float)key_of_reg(r) / p.nscale_log2 : 0.f;
+  // (With a loop over query heads the set-up below goes through an opaque copy of the thread
+  // index made inside the loop: otherwise everything that depends on the lane alone -- these
+  // addresses, the stagers' offsets -- is hoisted out of the loop and held in registers across
+  // the whole pipeline, which these kernels cannot afford.)
+  int tid_s = tid;
+  if constexpr (GROUPS) asm volatile("" : "+v"(tid_s));
+  const int lane_s = tid_s & 63, l32_s = lane_s & 31, h_s = lane_s >> 5;
   // per-lane LDS addresses (the ring slot of tile t is t % 4)
   {
-    const int kap = kappa(l32), i16 = lane & 15, blk1 = (lane >> 4) & 1;
+    const int kap = kappa(l32_s), i16 = lane_s & 15, blk1 = (lane_s >> 4) & 1;
+    const int h = h_s;
 #pragma unroll
     for (int kk = 0; kk < KD; ++kk) {
       const uint32_t o = lds0 + kap * (D * 2) + (((2 * kk + h) ^ SwzX<D>::f(kap)) << 4);
@@ -657,8 +665,8 @@ __device__ __forceinline__ void attn_bwd_body(const BwdParams& p, const int bh, 
 
   DmaStagerX<D, NW> st1, st2;
   constexpr int NI_TILE = DmaStagerX<D, NW>::NI;  // staging instructions per wave, tensor and tile
-  st1.init(y1b, y1s, Nt, t_lo * BC, uwave, lane);
-  st2.init(y2b, y2s, Nt, t_lo * BC, uwave, lane);
+  st1.init(y1b, y1s, Nt, t_lo * BC, uwave, lane_s);
+  st2.init(y2b, y2s, Nt, t_lo * BC, uwave, lane_s);
   // Prologue.  The workgroup's first loads share the compute unit's one path from memory, so
   // they are kept few and ordered by need: tile t_lo, the stationary fragments, then tile
   // t_lo+1, which may land while the first tile is computed (every tile waits for the next
@@ -666,7 +674,7 @@ __device__ __forceinline__ void attn_bwd_body(const BwdParams& p, const int bh, 
   // first step on, with zero P / dS until the pipeline has filled, so the slot of tile t_lo-1
   // must hold finite data: zeros, written here.
   {
-    const uint32_t zslot = lds0 + ((t_lo + NSLOT - 1) % NSLOT) * SLOT + tid * 16;
+    const uint32_t zslot = lds0 + ((t_lo + NSLOT - 1) % NSLOT) * SLOT + tid_s * 16;
 #pragma unroll
     for (int i = 0; i < SLOT / (256 * 16); ++i) lds_write_b128(zslot + i * (256 * 16), u32x4{0, 0, 0, 0});
   }
