@@ -884,7 +884,7 @@ attn_bwd_kernel(const BwdParams p) {
   // workgroups of the launch equal (no ragged end) and halves the gaps between workgroups.
   // (only the pinned sigmoid passes carry the loop: it costs a few registers, which the kernels
   // held to 256 of them do not have)
-  constexpr bool kCanPair = CAUSAL && !SOFTMAX && PIN && !GROUPS && MODE != BWD_DQ_DB;
+  constexpr bool kCanPair = CAUSAL && !SOFTMAX && PIN && MODE != BWD_DQ_DB;
   const bool pair = kCanPair && p.pair;
   const int places = pair ? p.n_blocks / 2 : p.n_blocks;
   const int total = places * p.B * (MODE == BWD_DKDV ? p.H / kv_group : p.H);

@@ -9,12 +9,12 @@ int launch_bwd_variant(BwdParams p, int causal, bool alibi, int parts, bool merg
   // the dQ pass runs one workgroup per 128 queries, the dK/dV pass one per 128 keys
   const int nb_q = (p.N + 127) / 128, nb_k = ((p.Nk > 0 ? p.Nk : p.N) + 127) / 128;
   // pairs of blocks per workgroup: causal pinned sigmoid passes over equal-length sequences with
-  // one K/V head per query head and an even number of blocks per head (measured from 4 blocks
-  // up: 0-3 % faster than single blocks, never slower)
-  const bool may_pair = p.pair && causal && !SOFTMAX && PIN && !p.cu_seqlens && p.kv_group == 1;
+  // an even number of blocks per head (measured from 4 blocks up: 0-3 % faster than single
+  // blocks, never slower)
+  const bool may_pair = p.pair && causal && !SOFTMAX && PIN && !p.cu_seqlens;
   const bool pair_q = may_pair && !p.db_rows && nb_q % 2 == 0 && nb_q >= 4, pair_k = may_pair && nb_k % 2 == 0 && nb_k >= 4;
   dim3 grid((pair_q ? nb_q / 2 : nb_q) * p.B * p.H), grid_k((pair_k ? nb_k / 2 : nb_k) * p.B * p.H),
-      grid_kv(nb_k * p.B * (p.H / p.kv_group));
+      grid_kv((pair_k ? nb_k / 2 : nb_k) * p.B * (p.H / p.kv_group));
   int rc = SATTN_OK;
   constexpr size_t lds = 4 * 2 * 64 * D * 2;                    // 4 ring slots of two 64-row tiles
   dim3 block(256);

@@ -936,6 +936,49 @@ def test_backward_with_paired_causal_blocks(B, H, N, d, alibi):
             assert e <= TOL_BF16, f"{name} {(b, h)}: {e:.3e}"
 
 
+@pytest.mark.parametrize("B,H,Hkv,N,d,alibi", [(8, 16, 4, 2048, 128, True), (8, 8, 2, 4096, 64, False), (16, 16, 16, 1024, 128, False)])
+def test_shared_kv_heads_with_paired_causal_blocks(B, H, Hkv, N, d, alibi):
+    """The grouped dK/dV pass deals key blocks out in pairs as the dense one does: bit-equal to
+    single blocks (whose results the other shared-head tests hold to the oracle), and dK, dV of
+    sampled key rows against the oracle summed over the group's query heads."""
+    g = torch.Generator().manual_seed(6800 + N + Hkv)
+    q, do = (torch.randn(B, H, N, d, generator=g).bfloat16() for _ in range(2))
+    k, v = (torch.randn(B, Hkv, N, d, generator=g).bfloat16() for _ in range(2))
+    slopes = W.alibi_slopes(H) if alibi else None
+    sl = _dev(slopes) if slopes is not None else None
+    bias = -math.log(N)
+    Q, K, V, DO = (_dev(t) for t in (q, k, v, do))
+    outs = {}
+    try:
+        for mode in (3, 0):
+            sa.sattn_set_bwd_merged(mode)
+            (dq, g0) = _guarded(Q.shape)
+            (dk, g1), (dv, g2) = (_guarded(K.shape) for _ in range(2))
+            sa.sigmoid_attn_mqa_bwd(Q, K, V, DO, dq, dk, dv, bias, True, sl)
+            torch.cuda.synchronize()
+            for guard in (g0, g1, g2):
+                guard()
+            outs[mode] = (dq, dk, dv)
+    finally:
+        sa.sattn_set_bwd_merged(0)
+    for a, b_ in zip(outs[0], outs[3]):
+        assert not torch.isnan(a).any() and torch.equal(a, b_)
+    rows = np.array(sorted({0, 127, 128, N // 2 + 5, N - 129, N - 1}))
+    ridx = torch.as_tensor(rows, device="cuda")
+    f = lambda t: t.double().numpy()
+    G = H // Hkv
+    for (b, gk) in ((0, 0), (B - 1, Hkv - 1)):
+        rk, rv = np.zeros((len(rows), d)), np.zeros((len(rows), d))
+        for h in range(gk * G, (gk + 1) * G):
+            a, b2 = orc.sigmoid_attn_dkdv_rows(f(q[b, h]), f(k[b, gk]), f(v[b, gk]), f(do[b, h]), bias, True,
+                                               0.0 if slopes is None else float(slopes[h]), rows)
+            rk += a
+            rv += b2
+        for name, got, ref in (("dk", outs[0][1][b, gk][ridx], rk), ("dv", outs[0][2][b, gk][ridx], rv)):
+            e = row_err(got, ref)
+            assert e <= TOL_BF16, f"{name} {(b, gk)}: {e:.3e}"
+
+
 def test_forward_with_64_row_waves_on_packed_shared_and_cross_inputs():
     # the entry points that reuse the forward kernels: variable-length batches, shared K/V heads,
     # different numbers of queries and keys -- each against its own 32-row result, bit for bit
