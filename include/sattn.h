@@ -230,6 +230,27 @@ int sigmoid_attn_mqa_bwd(const void* q, const void* k, const void* v, const void
                          const sattn_strides* sdq, const sattn_strides* sdk,
                          const sattn_strides* sdv, void* stream);
 
+/* sigmoid_attn_mqa_bwd for problems with few K/V heads (Section 5.1 trains with one): there the
+ * dK/dV pass, one workgroup per K/V head and 128 keys, leaves compute units idle or unevenly
+ * loaded, and this form splits the query heads of a group over 2, 4, ... workgroups that write
+ * fp32 partial dK, dV to `workspace` (device memory, 16-byte aligned, at least
+ * sigmoid_attn_mqa_bwd_workspace_bytes(...) bytes, contents undefined before and after), added
+ * up and rounded to bf16 once by a second kernel.  ..._workspace_bytes returns 0 where the
+ * library would not split (enough K/V heads, fp32, invalid arguments): the call then equals
+ * sigmoid_attn_mqa_bwd and workspace may be NULL.  The results differ from sigmoid_attn_mqa_bwd's
+ * only in the order of the fp32 sums over the query heads.  SATTN_ERR_WORKSPACE if the
+ * workspace is NULL or too small where one is needed. */
+size_t sigmoid_attn_mqa_bwd_workspace_bytes(int B, int H, int Hkv, int N, int d, sattn_dtype dtype, int causal);
+int sigmoid_attn_mqa_bwd_split(const void* q, const void* k, const void* v, const void* dout,
+                               void* dq, void* dk, void* dv,
+                               int B, int H, int Hkv, int N, int d, sattn_dtype dtype,
+                               float bias, int causal, const float* alibi_slopes,
+                               const sattn_strides* sq, const sattn_strides* sk,
+                               const sattn_strides* sv, const sattn_strides* sdout,
+                               const sattn_strides* sdq, const sattn_strides* sdk,
+                               const sattn_strides* sdv, void* workspace, size_t workspace_bytes,
+                               void* stream);
+
 /* Different numbers of queries and keys (the definition of Section 2 with Q of n_q rows and
  * K, V of n_k rows; the paper's models only use n_q = n_k).  q, o, dout, dq are [B,H,Nq,d];
  * k, v, dk, dv are [B,H,Nk,d].  Plain sigmoid attention only (bf16 or fp32): no causal mask, no ALiBi

@@ -54,6 +54,10 @@ def load_library():
     lib.sigmoid_attn_mqa_fwd.restype = i
     lib.sigmoid_attn_mqa_bwd.argtypes = [_vp] * 7 + [i, i, i, i, i, i, f, i, _vp] + [_SP] * 7 + [_vp]
     lib.sigmoid_attn_mqa_bwd.restype = i
+    lib.sigmoid_attn_mqa_bwd_split.argtypes = [_vp] * 7 + [i, i, i, i, i, i, f, i, _vp] + [_SP] * 7 + [_vp, sz, _vp]
+    lib.sigmoid_attn_mqa_bwd_split.restype = i
+    lib.sigmoid_attn_mqa_bwd_workspace_bytes.argtypes = [i, i, i, i, i, i, i]
+    lib.sigmoid_attn_mqa_bwd_workspace_bytes.restype = sz
     lib.sigmoid_attn_cross_fwd.argtypes = [_vp, _vp, _vp, _vp, i, i, i, i, i, i, f, _SP, _SP, _SP, _SP, _vp]
     lib.sigmoid_attn_cross_fwd.restype = i
     lib.sigmoid_attn_cross_bwd.argtypes = [_vp] * 7 + [i, i, i, i, i, i, f] + [_SP] * 7 + [_vp]
@@ -228,6 +232,30 @@ def sigmoid_attn_mqa_bwd(q, k, v, dout, dq, dk, dv, bias, causal=False, alibi_sl
                                   int(bool(causal)), _slopes_ptr(alibi_slopes, H), _st(q), _st(k), _st(v),
                                   _st(dout), _st(dq), _st(dk), _st(dv), _stream())
     _raise(rc, "sigmoid_attn_mqa_bwd")
+    return dq, dk, dv
+
+
+def sigmoid_attn_mqa_bwd_workspace_bytes(B, H, Hkv, N, d, dtype=torch.bfloat16, causal=False):
+    """Bytes of workspace sigmoid_attn_mqa_bwd_split wants for this problem (0: it would not split)."""
+    code = SATTN_BF16 if dtype == torch.bfloat16 else SATTN_F32
+    return int(load_library().sigmoid_attn_mqa_bwd_workspace_bytes(B, H, Hkv, N, d, code, int(bool(causal))))
+
+
+def sigmoid_attn_mqa_bwd_split(q, k, v, dout, dq, dk, dv, bias, causal=False, alibi_slopes=None, workspace=None):
+    """sigmoid_attn_mqa_bwd with a group's query heads split over several workgroups where K/V heads are
+    few (fp32 partial sums in `workspace`, allocated here when not given)."""
+    lib = load_library()
+    B, H, Hkv, N, d = _check_mqa(q, (k, v, dk, dv), dout, dq)
+    need = sigmoid_attn_mqa_bwd_workspace_bytes(B, H, Hkv, N, d, q.dtype, causal)
+    if workspace is None and need:
+        workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+    wp = _vp(workspace.data_ptr()) if workspace is not None else None
+    wb = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    rc = lib.sigmoid_attn_mqa_bwd_split(q.data_ptr(), k.data_ptr(), v.data_ptr(), dout.data_ptr(), dq.data_ptr(),
+                                        dk.data_ptr(), dv.data_ptr(), B, H, Hkv, N, d, _dtype_code(q), float(bias),
+                                        int(bool(causal)), _slopes_ptr(alibi_slopes, H), _st(q), _st(k), _st(v),
+                                        _st(dout), _st(dq), _st(dk), _st(dv), wp, wb, _stream())
+    _raise(rc, "sigmoid_attn_mqa_bwd_split")
     return dq, dk, dv
 
 

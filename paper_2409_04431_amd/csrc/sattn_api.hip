@@ -224,6 +224,18 @@ bool pick_bwd_merged(int B, int H, int N, int causal) {
   return wgs < (causal ? 2 : 3) * cus;
 }
 
+// Workgroups over which the dK/dV pass splits the query heads of one K/V head (a power of two
+// that divides the group): one per K/V head and key block leaves compute units idle when there
+// are few K/V heads -- with one K/V head, 8 sequences of 4096 tokens make 256 workgroups of
+// unequal causal work -- so the group is split until the pass has two workgroups per compute
+// unit under the causal mask (enough to deal the blocks out in pairs of equal work), one without.
+int pick_group_split(int B, int Hkv, int group, int N, int causal) {
+  const int64_t wgs = (int64_t)B * Hkv * ((N + 127) / 128), want = (int64_t)(causal ? 2 : 1) * compute_units();
+  int s = 1;
+  while (wgs * s < want && group % (2 * s) == 0) s *= 2;
+  return s;
+}
+
 int check_shape(int B, int H, int N, int d, sattn_dtype dt) {
   if (dt != SATTN_BF16 && dt != SATTN_F32) return SATTN_ERR_UNSUPPORTED;
   if (d != 64 && d != 128) return SATTN_ERR_UNSUPPORTED;
@@ -356,6 +368,7 @@ struct BwdArgs {
   int Hkv = 0;                                                       // K/V heads (0: one per query head)
   int Nk = 0;                                                        // keys (0: as many as queries)
   bool end_aligned = false;                                          // queries = the last N positions of the key sequence
+  bool group_split = false;                                          // shared K/V heads: split a group over workgroups (workspace)
 };
 
 template <bool SOFTMAX, bool PIN = true>
@@ -437,10 +450,21 @@ int bwd_impl(const BwdArgs& a) {
     p.nlse2 = nlse2; p.dvec = dvec; p.npad = npad;
   }
   const bool merged = pick_bwd_merged(a.B, a.H, a.N, a.causal);
+  int n_split = 1;
+  if (a.group_split && !SOFTMAX && PIN && Hkv != a.H && !a.cu_seqlens && Nk == a.N && (a.parts & kBwdDkDv)) {
+    n_split = pick_group_split(a.B, Hkv, a.H / Hkv, a.N, a.causal);
+    if (n_split > 1) {
+      const size_t need = 2 * (size_t)n_split * a.B * Hkv * a.N * a.d * sizeof(float);
+      if (!a.workspace || a.workspace_bytes < need) return SATTN_ERR_WORKSPACE;
+      if (((uintptr_t)a.workspace & 15) != 0) return SATTN_ERR_ALIGN;
+      p.n_split = n_split;
+      p.part = (float*)a.workspace;
+    }
+  }
   // causal passes deal a head's blocks out in pairs of equal work (longest with shortest) where
   // a pair per compute unit remains (see the 64-row forward)
   p.pair = a.causal && !SOFTMAX && PIN && g_bwd_merged.load(std::memory_order_relaxed) != 3 &&
-           (int64_t)a.B * Hkv * ((std::min(a.N, Nk) + 127) / 128 / 2) >= compute_units();
+           (int64_t)a.B * Hkv * n_split * ((std::min(a.N, Nk) + 127) / 128 / 2) >= compute_units();
   if (a.d == 128) rc = launch_bwd_bf16<128>(p, SOFTMAX, PIN, a.causal, alibi, a.parts, merged, st);
   else rc = launch_bwd_bf16<64>(p, SOFTMAX, PIN, a.causal, alibi, a.parts, merged, st);
   if (rc == SATTN_OK && a.db) {
@@ -708,6 +732,26 @@ int sigmoid_attn_mqa_bwd(const void* q, const void* k, const void* v, const void
   BwdArgs a{q, k, v, nullptr, nullptr, dout, dq, dk, dv, B, H, N, d, dtype, bias, causal, alibi_slopes,
             sq, sk, sv, nullptr, sdout, sdq, sdk, sdv, nullptr, 0, kBwdDkDv | kBwdDq, stream};
   a.Hkv = Hkv;
+  return bwd_impl<false>(a);
+}
+
+size_t sigmoid_attn_mqa_bwd_workspace_bytes(int B, int H, int Hkv, int N, int d, sattn_dtype dtype, int causal) {
+  if (check_shape(B, H, N, d, dtype) != SATTN_OK || Hkv <= 0 || H % Hkv || Hkv == H || dtype != SATTN_BF16) return 0;
+  const int s = pick_group_split(B, Hkv, H / Hkv, N, causal);
+  return s > 1 ? 2 * (size_t)s * B * Hkv * N * d * sizeof(float) : 0;
+}
+
+int sigmoid_attn_mqa_bwd_split(const void* q, const void* k, const void* v, const void* dout, void* dq, void* dk,
+                               void* dv, int B, int H, int Hkv, int N, int d, sattn_dtype dtype, float bias,
+                               int causal, const float* alibi_slopes, const sattn_strides* sq,
+                               const sattn_strides* sk, const sattn_strides* sv, const sattn_strides* sdout,
+                               const sattn_strides* sdq, const sattn_strides* sdk, const sattn_strides* sdv,
+                               void* workspace, size_t workspace_bytes, void* stream) {
+  if (Hkv <= 0) return SATTN_ERR_SHAPE;
+  BwdArgs a{q, k, v, nullptr, nullptr, dout, dq, dk, dv, B, H, N, d, dtype, bias, causal, alibi_slopes,
+            sq, sk, sv, nullptr, sdout, sdq, sdk, sdv, workspace, workspace_bytes, kBwdDkDv | kBwdDq, stream};
+  a.Hkv = Hkv;
+  a.group_split = true;
   return bwd_impl<false>(a);
 }
 

@@ -53,6 +53,12 @@ struct BwdParams {
   // shared key/value heads: query head h reads K/V head h / kv_group (1 = one per query head);
   // k, v, dk, dv then have H / kv_group heads
   int kv_group;
+  // grouped dK/dV pass only: a group's query heads are split over n_split workgroups (a divisor
+  // of kv_group; 0 or 1: no split), each of which writes its fp32 partial dK, dV (unscaled) to
+  // part[(which * n_split + split) * B * (H / kv_group) + b * (H / kv_group) + head][key][d],
+  // which = 0 for dK, 1 for dV; a second kernel adds the partials up
+  int n_split;
+  float* part;
   // number of keys when it differs from the number of queries N (0: same)
   int Nk;
   // position of query 0 on the key axis (see FwdParams::qoff); a multiple of 32
@@ -531,9 +537,13 @@ __device__ __forceinline__ void attn_bwd_body(const BwdParams& p, const int bh, 
   // of that head's group one after the other; the dQ pass runs per query head
   const int kv_group = (MODE == BWD_DKDV && !GROUPS) ? 1 : p.kv_group;
   const int heads = MODE == BWD_DKDV ? p.H / kv_group : p.H;
-  const int b = bh / heads, hd = bh % heads;  // hd: K/V head (dK/dV pass) or query head (dQ pass)
+  // (a split group: bh counts (batch, K/V head, split) triples, the split running fastest)
+  const int n_split = (GROUPS && p.n_split > 1) ? p.n_split : 1;
+  const int split = GROUPS ? bh % n_split : 0, bh_g = GROUPS ? bh / n_split : bh;
+  const int b = bh_g / heads, hd = bh_g % heads;  // hd: K/V head (dK/dV pass) or query head (dQ pass)
   const int hkv = MODE == BWD_DKDV ? hd : hd / kv_group;
-  const int hq0 = MODE == BWD_DKDV ? hd * kv_group : hd, n_hq = MODE == BWD_DKDV ? kv_group : 1;
+  const int n_hq = MODE == BWD_DKDV ? kv_group / n_split : 1;
+  const int hq0 = MODE == BWD_DKDV ? hd * kv_group + split * n_hq : hd;
   int N = p.N;
   int64_t tok0 = 0;
   float nbias_log2 = p.nbias_log2;
@@ -842,7 +852,25 @@ __device__ __forceinline__ void attn_bwd_body(const BwdParams& p, const int bh, 
   clock_probe_mark(p.clock, clk, kMarkStore);
   // Outputs as whole rows, transposed through the ring (free once every wave has left the loop).
   __syncthreads();
-  {
+  if (GROUPS && n_split > 1) {
+    // fp32 partial sums of this workgroup's share of the group, straight from the accumulators:
+    // register 4g+t of tile dt is element [row ai][32dt + 8g + 4h + t]
+    if (ai < Ns) {
+      const int64_t slab = (int64_t)p.B * heads * Ns * D;  // one [B, Hkv, keys, d] tensor
+      float* pk = p.part + (int64_t)split * slab + (((int64_t)b * heads + hd) * Ns + ai) * D;
+      float* pv = pk + (int64_t)n_split * slab;
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          *(f32x4*)(pk + 32 * dt + 8 * g + 4 * h) =
+              f32x4{W.acc0[dt][4 * g], W.acc0[dt][4 * g + 1], W.acc0[dt][4 * g + 2], W.acc0[dt][4 * g + 3]};
+          if constexpr (MODE == BWD_DKDV)
+            *(f32x4*)(pv + 32 * dt + 8 * g + 4 * h) =
+                f32x4{W.acc1[dt][4 * g], W.acc1[dt][4 * g + 1], W.acc1[dt][4 * g + 2], W.acc1[dt][4 * g + 3]};
+        }
+    }
+  } else {
     const int rows_valid = Ns - a_wave0;  // <= 0 for a wave past the end
     const uint32_t obuf = lds0 + wave * (2 * RowStore<D>::BYTES);
     __bf16* o0 = (MODE == BWD_DKDV ? (__bf16*)p.dk.ptr + b * p.dk.sb + hkv * p.dk.sh + (tok0 + a_wave0) * p.dk.ss
@@ -864,7 +892,8 @@ template <int MODE, bool CAUSAL, bool GROUPS>
 __device__ __forceinline__ void bwd_place(const BwdParams& p, int logical, int places, int& bh, int& rank) {
   const int kv_group = (MODE == BWD_DKDV && !GROUPS) ? 1 : p.kv_group;
   const int heads = MODE == BWD_DKDV ? p.H / kv_group : p.H;
-  head_and_rank(logical, places, p.B * heads, CAUSAL ? p.head_group : 1, bh, rank);
+  const int n_split = (GROUPS && p.n_split > 1) ? p.n_split : 1;
+  head_and_rank(logical, places, p.B * heads * n_split, CAUSAL ? p.head_group : 1, bh, rank);
 }
 template <int MODE, bool CAUSAL>
 __device__ __forceinline__ int bwd_block_of_rank(const BwdParams& p, int rank) {
@@ -887,7 +916,7 @@ attn_bwd_kernel(const BwdParams p) {
   constexpr bool kCanPair = CAUSAL && !SOFTMAX && PIN && MODE != BWD_DQ_DB;
   const bool pair = kCanPair && p.pair;
   const int places = pair ? p.n_blocks / 2 : p.n_blocks;
-  const int total = places * p.B * (MODE == BWD_DKDV ? p.H / kv_group : p.H);
+  const int total = places * p.B * (MODE == BWD_DKDV ? p.H / kv_group : p.H) * ((GROUPS && p.n_split > 1) ? p.n_split : 1);
   int bh, rank;
   bwd_place<MODE, CAUSAL, GROUPS>(p, xcd_remap(blockIdx.x, total), places, bh, rank);
   if constexpr (!kCanPair) {
@@ -928,6 +957,38 @@ attn_bwd_merged_kernel(const BwdParams p) {
     bwd_place<BWD_DKDV, CAUSAL, false>(p, logical >> 1, p.n_blocks, bh, rank);
     attn_bwd_body<D, BWD_DKDV, CAUSAL, ALIBI, false, true, false>(p, bh, bwd_block_of_rank<BWD_DKDV, CAUSAL>(p, rank), (int)blockIdx.x, (int)threadIdx.x);
   }
+}
+
+// Second kernel of a split grouped dK/dV pass: dK = inv_sqrt_d * sum of the dK partials, dV =
+// sum of the dV partials, rounded to bf16 once.  One thread per eight consecutive features;
+// blockIdx.y = 0 for dK, 1 for dV.
+template <int D>
+__global__ void __launch_bounds__(256)
+group_partials_reduce_kernel(const float* part, TensorRef dk, TensorRef dv, int n_split, int B, int Hkv, int Nk,
+                             float inv_sqrt_d) {
+  const int which = blockIdx.y;
+  const int64_t slab = (int64_t)B * Hkv * Nk * D;
+  const int64_t e0 = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 8;
+  if (e0 >= slab) return;
+  const float* src = part + (int64_t)which * n_split * slab + e0;
+  f32x4 lo = {0.f, 0.f, 0.f, 0.f}, hi = {0.f, 0.f, 0.f, 0.f};
+  for (int s = 0; s < n_split; ++s) {
+    const f32x4 a = *(const f32x4*)(src + (int64_t)s * slab), c = *(const f32x4*)(src + (int64_t)s * slab + 4);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { lo[i] += a[i]; hi[i] += c[i]; }
+  }
+  const float scale = which == 0 ? inv_sqrt_d : 1.0f;
+  const int col = (int)(e0 % D);
+  const int64_t row_all = e0 / D;
+  const int row = (int)(row_all % Nk);
+  const int bh = (int)(row_all / Nk), b = bh / Hkv, hd = bh % Hkv;
+  const TensorRef& o = which == 0 ? dk : dv;
+  u32x4 w;
+  w[0] = pack_bf16(lo[0] * scale, lo[1] * scale);
+  w[1] = pack_bf16(lo[2] * scale, lo[3] * scale);
+  w[2] = pack_bf16(hi[0] * scale, hi[1] * scale);
+  w[3] = pack_bf16(hi[2] * scale, hi[3] * scale);
+  *(u32x4*)((__bf16*)o.ptr + b * o.sb + hd * o.sh + (int64_t)row * o.ss + col) = w;
 }
 
 // Pre-pass of the softmax backward: per query row D_i = sum_t dO[i][t] * O[i][t] (fp32) and

@@ -14,7 +14,7 @@ int launch_bwd_variant(BwdParams p, int causal, bool alibi, int parts, bool merg
   const bool may_pair = p.pair && causal && !SOFTMAX && PIN && !p.cu_seqlens;
   const bool pair_q = may_pair && !p.db_rows && nb_q % 2 == 0 && nb_q >= 4, pair_k = may_pair && nb_k % 2 == 0 && nb_k >= 4;
   dim3 grid((pair_q ? nb_q / 2 : nb_q) * p.B * p.H), grid_k((pair_k ? nb_k / 2 : nb_k) * p.B * p.H),
-      grid_kv((pair_k ? nb_k / 2 : nb_k) * p.B * (p.H / p.kv_group));
+      grid_kv((pair_k ? nb_k / 2 : nb_k) * p.B * (p.H / p.kv_group) * (p.n_split > 1 ? p.n_split : 1));
   int rc = SATTN_OK;
   constexpr size_t lds = 4 * 2 * 64 * D * 2;                    // 4 ring slots of two 64-row tiles
   dim3 block(256);
@@ -36,9 +36,16 @@ int launch_bwd_variant(BwdParams p, int causal, bool alibi, int parts, bool merg
     p.head_group = heads_abreast(nb_k);
     p.pair = pair_k;
     if constexpr (!SOFTMAX && PIN) {
-      if (p.kv_group > 1)  // one workgroup per K/V head streams the query heads of its group
+      if (p.kv_group > 1) {  // one workgroup per K/V head (and split) streams the query heads of its group
         SATTN_DISPATCH2(causal, alibi,
                         rc = launch(attn_bwd_kernel<D, BWD_DKDV, A, B2, false, true, true>, grid_kv, block, lds, st, p));
+        if (rc == SATTN_OK && p.n_split > 1) {
+          const int Hkv = p.H / p.kv_group, Nk = p.Nk > 0 ? p.Nk : p.N;
+          const int64_t threads = ((int64_t)p.B * Hkv * Nk * D + 7) / 8;
+          rc = launch(group_partials_reduce_kernel<D>, dim3((unsigned)((threads + 255) / 256), 2), dim3(256), 0, st,
+                      (const float*)p.part, p.dk, p.dv, p.n_split, p.B, Hkv, Nk, p.inv_sqrt_d);
+        }
+      }
     }
     if (p.kv_group == 1)
       SATTN_DISPATCH2(causal, alibi,

@@ -219,6 +219,26 @@ def test_end_aligned_cross_attention_entry_points_reject_bad_arguments(lib):
     assert g(64, 100, 1) == -3
 
 
+def test_split_group_backward_workspace_size_and_rejections(lib):
+    f = lambda *a: sa.sigmoid_attn_mqa_bwd_workspace_bytes(*a)
+    import torch
+    # (the library counts 256 compute units where it finds no device, as here)
+    # one K/V head, 8 x 32 key blocks: 256 workgroups, two per compute unit wanted under the mask
+    assert f(8, 16, 1, 4096, 128, torch.bfloat16, True) == 2 * 2 * 8 * 1 * 4096 * 128 * 4
+    assert f(8, 16, 1, 4096, 128, torch.bfloat16, False) == 0          # one per compute unit is enough without it
+    assert f(1, 16, 1, 4096, 128, torch.bfloat16, True) == 2 * 16 * 4096 * 128 * 4   # 32 blocks: split 16 ways
+    assert f(1, 6, 2, 520, 128, torch.bfloat16, True) == 0             # groups of three
+    assert f(8, 16, 16, 4096, 128, torch.bfloat16, True) == 0 and f(8, 16, 3, 4096, 128, torch.bfloat16, True) == 0
+    assert f(8, 16, 1, 4096, 128, torch.float32, True) == 0
+    ptrs = [0x1000, 0x2000, 0x3000, 0x4000, 0x5000, 0x6000, 0x7000]
+    call = lambda ws, nbytes, Hkv=1: lib.sigmoid_attn_mqa_bwd_split(*ptrs, 8, 16, Hkv, 4096, 128, 0, 0.0, 1, None,
+                                                                    *([None] * 7), ws, nbytes, None)
+    assert call(None, 0) == -5                                         # SATTN_ERR_WORKSPACE
+    assert call(0x10000, 1024) == -5
+    assert call(0x10004, 1 << 30) == -4
+    assert call(None, 0, Hkv=5) == -2
+
+
 def test_binding_refuses_cpu_tensors():
     import torch
     t = torch.zeros(1, 1, 8, 64, dtype=torch.bfloat16)

@@ -979,6 +979,66 @@ def test_shared_kv_heads_with_paired_causal_blocks(B, H, Hkv, N, d, alibi):
             assert e <= TOL_BF16, f"{name} {(b, gk)}: {e:.3e}"
 
 
+@pytest.mark.parametrize("B,H,Hkv,N,d,causal,alibi", [
+    (1, 8, 1, 700, 128, True, True),        # one K/V head: the group split over up to 8 workgroups
+    (2, 4, 1, 333, 64, False, False),       # ragged, no mask
+    (1, 6, 2, 520, 128, True, False),       # groups of three: cannot be split (stays one workgroup per group)
+    (1, 16, 2, 1024, 64, True, True),
+])
+def test_shared_kv_heads_with_split_groups_match_oracle(B, H, Hkv, N, d, causal, alibi):
+    g = torch.Generator().manual_seed(6900 + N + H)
+    q, do = (torch.randn(B, H, N, d, generator=g).bfloat16() for _ in range(2))
+    k, v = (torch.randn(B, Hkv, N, d, generator=g).bfloat16() for _ in range(2))
+    slopes = W.alibi_slopes(H) if alibi else None
+    sl = _dev(slopes) if slopes is not None else None
+    bias = -math.log(N)
+    Q, K, V, DO = (_dev(t) for t in (q, k, v, do))
+    need = sa.sigmoid_attn_mqa_bwd_workspace_bytes(B, H, Hkv, N, d, torch.bfloat16, causal)
+    assert (need > 0) == ((H // Hkv) % 2 == 0)     # these grids are far too small not to split an even group
+    buf = torch.full((need + 512,), 77, dtype=torch.uint8, device="cuda")   # workspace with sentinels on both sides
+    ws = buf[256:256 + need]
+    gw = lambda: bool((buf[:256] == 77).all()) and bool((buf[256 + need:] == 77).all()) or pytest.fail("write outside the workspace")
+    (dq, g0) = _guarded(Q.shape)
+    (dk, g1), (dv, g2) = (_guarded(K.shape) for _ in range(2))
+    sa.sigmoid_attn_mqa_bwd_split(Q, K, V, DO, dq, dk, dv, bias, causal, sl, ws if need else None)
+    torch.cuda.synchronize()
+    for guard in (g0, g1, g2, gw):
+        guard()
+    f = lambda t: t.double().numpy()
+    sl64 = None if slopes is None else slopes.double().numpy()
+    rdq, rdk, rdv = orc.sigmoid_attn_mqa_bwd(f(q), f(k), f(v), f(do), bias, causal, sl64)
+    for name, got, ref in (("dq", dq, rdq), ("dk", dk, rdk), ("dv", dv, rdv)):
+        assert not torch.isnan(got).any(), name
+        e, er = nerr(got, ref), row_err(got, ref)
+        assert e <= TOL_BF16 and er <= TOL_BF16, f"{name}: {e:.3e}, worst row {er:.3e}"
+    if need:   # too small a workspace is refused, nothing written
+        with pytest.raises(sa.SattnError):
+            sa.sigmoid_attn_mqa_bwd_split(Q, K, V, DO, dq, dk, dv, bias, causal, sl, ws[:need - 16])
+
+
+def test_shared_kv_heads_with_split_groups_at_full_size():
+    """One K/V head at the headline size (256 unequal workgroups without the split): the split
+    form against the one-workgroup-per-group form, which the other tests hold to the oracle --
+    they differ in the order of the fp32 sums over the query heads and in nothing else."""
+    B, H, Hkv, N, d = 8, 16, 1, 4096, 128
+    g = torch.Generator().manual_seed(6999)
+    q, do = (torch.randn(B, H, N, d, generator=g).bfloat16() for _ in range(2))
+    k, v = (torch.randn(B, Hkv, N, d, generator=g).bfloat16() for _ in range(2))
+    bias = -math.log(N)
+    Q, K, V, DO = (_dev(t) for t in (q, k, v, do))
+    dq, dq2 = torch.empty_like(Q), torch.empty_like(Q)
+    dk, dv, dk2, dv2 = (torch.full_like(K, float("nan")) for _ in range(4))
+    assert sa.sigmoid_attn_mqa_bwd_workspace_bytes(B, H, Hkv, N, d, torch.bfloat16, True) == 2 * 2 * B * N * d * 4
+    sa.sigmoid_attn_mqa_bwd(Q, K, V, DO, dq, dk, dv, bias, True)
+    sa.sigmoid_attn_mqa_bwd_split(Q, K, V, DO, dq2, dk2, dv2, bias, True)
+    torch.cuda.synchronize()
+    assert torch.equal(dq, dq2)
+    for name, a, b_ in (("dk", dk, dk2), ("dv", dv, dv2)):
+        assert not torch.isnan(b_).any()
+        e = row_err(b_, a.double().cpu().numpy())
+        assert e <= 2 ** -7, f"{name}: {e:.3e}"       # two bf16 roundings of nearly equal fp32 sums
+
+
 def test_forward_with_64_row_waves_on_packed_shared_and_cross_inputs():
     # the entry points that reuse the forward kernels: variable-length batches, shared K/V heads,
     # different numbers of queries and keys -- each against its own 32-row result, bit for bit
