@@ -405,7 +405,15 @@ __device__ __forceinline__ void attn_fwd64_block(const FwdParams& p, const int b
         f64_tile_pinned<D, FOLD, PRESCALE, 1>(W, t + 1, kst, vst, kdoff, vdoff, kring_wave, vring_wave);
         f64_tile_pinned<D, FOLD, PRESCALE, 2>(W, t + 2, kst, vst, kdoff, vdoff, kring_wave, vring_wave);
       }
-      // (up to two more full tiles are left to the loop below)
+      // the one or two steady tiles left over by the unrolling (t is a multiple of 3 here)
+      if (t + 1 <= t_steady) {
+        f64_tile_pinned<D, FOLD, PRESCALE, 0>(W, t, kst, vst, kdoff, vdoff, kring_wave, vring_wave);
+        ++t;
+      }
+      if (t + 1 <= t_steady) {
+        f64_tile_pinned<D, FOLD, PRESCALE, 1>(W, t, kst, vst, kdoff, vdoff, kring_wave, vring_wave);
+        ++t;
+      }
       f64_settle();  // the compiler does not know the statements above are MFMAs
     }
   }
