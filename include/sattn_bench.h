@@ -47,9 +47,10 @@ int sattn_bwd_merged(int B, int H, int N, int causal);
 
 /* Comparison aids (Section 4 and Appendix F.2 compare the sigmoid kernels with softmax kernels
  * built the same way).  Same arguments, results and error behaviour as sigmoid_attn_fwd /
- * sigmoid_attn_bwd / softmax_attn_fwd; the kernels run every pipeline step in the
- * compiler-scheduled form instead of the hand-pinned instruction stream (the softmax backward
- * has no other form).  They exist so that sigmoid and softmax can be timed like for like at
+ * sigmoid_attn_bwd / softmax_attn_fwd / softmax_attn_bwd; the kernels run every pipeline step
+ * in the compiler-scheduled form instead of the hand-pinned instruction stream (of the softmax
+ * backward only the dQ pass has a hand-pinned form; its dK/dV pass is compiler-scheduled in
+ * softmax_attn_bwd too).  They exist so that sigmoid and softmax can be timed like for like at
  * both levels of tuning; not meant for production. */
 int sigmoid_attn_fwd_compiler_scheduled(const void* q, const void* k, const void* v, void* o,
                                         int B, int H, int N, int d, sattn_dtype dtype,
@@ -71,6 +72,16 @@ int sigmoid_attn_bwd_compiler_scheduled(const void* q, const void* k, const void
                                         const sattn_strides* sv, const sattn_strides* sdout,
                                         const sattn_strides* sdq, const sattn_strides* sdk,
                                         const sattn_strides* sdv,
+                                        void* workspace, size_t workspace_bytes, void* stream);
+int softmax_attn_bwd_compiler_scheduled(const void* q, const void* k, const void* v, const void* o,
+                                        const float* lse, const void* dout,
+                                        void* dq, void* dk, void* dv,
+                                        int B, int H, int N, int d, sattn_dtype dtype,
+                                        int causal, const float* alibi_slopes,
+                                        const sattn_strides* sq, const sattn_strides* sk,
+                                        const sattn_strides* sv, const sattn_strides* so,
+                                        const sattn_strides* sdout, const sattn_strides* sdq,
+                                        const sattn_strides* sdk, const sattn_strides* sdv,
                                         void* workspace, size_t workspace_bytes, void* stream);
 
 /* Measurement aid (Appendix F.2 reports kernel times; here they are also quoted as a fraction

@@ -87,6 +87,8 @@ def load_library():
     lib.softmax_attn_fwd_compiler_scheduled.restype = i
     lib.softmax_attn_bwd.argtypes = [_vp] * 9 + [i, i, i, i, i, i, _vp] + [_SP] * 8 + [_vp, sz, _vp]
     lib.softmax_attn_bwd.restype = i
+    lib.softmax_attn_bwd_compiler_scheduled.argtypes = lib.softmax_attn_bwd.argtypes
+    lib.softmax_attn_bwd_compiler_scheduled.restype = i
     lib.softmax_attn_bwd_workspace_bytes.argtypes = [i, i, i, i, i]
     lib.softmax_attn_bwd_workspace_bytes.restype = sz
     lib.softmax_attn_bwd_noalloc.argtypes = [_vp] * 9 + [i, i, i, i, i, i, _vp] + [_SP] * 8 + [_vp]
@@ -575,6 +577,25 @@ def softmax_attn_bwd(q, k, v, o, lse, dout, dq, dk, dv, causal=False, alibi_slop
                               _dtype_code(q), int(bool(causal)), _slopes_ptr(alibi_slopes, H),
                               _st(q), _st(k), _st(v), _st(o), _st(dout), _st(dq), _st(dk), _st(dv), wp, wb, _stream())
     _raise(rc, "softmax_attn_bwd")
+    return dq, dk, dv
+
+
+def softmax_attn_bwd_compiler_scheduled(q, k, v, o, lse, dout, dq, dk, dv, causal=False, alibi_slopes=None, workspace=None):
+    """softmax_attn_bwd with both passes in the compiler-scheduled form (measurement aid)."""
+    lib = load_library()
+    _check(q, k, v, o, dout, dq, dk, dv)
+    B, H, N, d = q.shape
+    need = softmax_attn_bwd_workspace_bytes(B, H, N, d, q.dtype)
+    if workspace is None and need:
+        workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+    wp = _vp(workspace.data_ptr()) if workspace is not None else None
+    wb = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    rc = lib.softmax_attn_bwd_compiler_scheduled(q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(), lse.data_ptr(),
+                                                 dout.data_ptr(), dq.data_ptr(), dk.data_ptr(), dv.data_ptr(), B, H, N, d,
+                                                 _dtype_code(q), int(bool(causal)), _slopes_ptr(alibi_slopes, H),
+                                                 _st(q), _st(k), _st(v), _st(o), _st(dout), _st(dq), _st(dk), _st(dv),
+                                                 wp, wb, _stream())
+    _raise(rc, "softmax_attn_bwd_compiler_scheduled")
     return dq, dk, dv
 
 

@@ -614,6 +614,18 @@ int softmax_attn_bwd(const void* q, const void* k, const void* v, const void* o,
   return bwd_impl<true>(a);
 }
 
+int softmax_attn_bwd_compiler_scheduled(const void* q, const void* k, const void* v, const void* o, const float* lse,
+                                        const void* dout, void* dq, void* dk, void* dv, int B, int H, int N, int d,
+                                        sattn_dtype dtype, int causal, const float* alibi_slopes,
+                                        const sattn_strides* sq, const sattn_strides* sk, const sattn_strides* sv,
+                                        const sattn_strides* so, const sattn_strides* sdout, const sattn_strides* sdq,
+                                        const sattn_strides* sdk, const sattn_strides* sdv, void* workspace,
+                                        size_t workspace_bytes, void* stream) {
+  BwdArgs a{q, k, v, o, lse, dout, dq, dk, dv, B, H, N, d, dtype, 0.0f, causal, alibi_slopes,
+            sq, sk, sv, so, sdout, sdq, sdk, sdv, workspace, workspace_bytes, kBwdDkDv | kBwdDq, stream};
+  return bwd_impl<true, false>(a);
+}
+
 size_t softmax_attn_bwd_workspace_bytes(int B, int H, int N, int d, sattn_dtype dtype) {
   if (check_shape(B, H, N, d, dtype) != SATTN_OK) return 0;
   // rowsum(dO o O) and the rescaled log-sum-exp: two fp32 per query row, rows padded to 64

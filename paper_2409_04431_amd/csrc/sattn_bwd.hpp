@@ -351,17 +351,23 @@ __device__ __forceinline__ void bwd_step(BwdWave<D, MODE>& W, bool doA, bool doS
 // MASK adds C (keep = key_of_reg(e) >= thr for DKDV, <= thr for DQ; p = keep ? p : 0) and
 // D (dS = keep ? dS : 0): selects, so that a masked element is exactly zero whatever the
 // logit and dP registers hold (they are not even finite in a dead pipeline stage).
-template <int MODE, bool MASK>
+// SMX: the softmax comparison kernel's arithmetic in the same stream (dQ pass, where the row
+// statistics are per lane): per group F x4 (x = s*scale - lse[- alibi], in log2 units) X x4
+// (p = 2^x) [C x4] Q x4 (dP - D) M x4 (dS = . * p) [D x4] CD x2: no 1+e, no reciprocal.
+template <int MODE, bool MASK, bool SMX = false>
 struct BsigLayout {
   static constexpr int nC = MASK ? 4 : 0, nP = MODE == BWD_DKDV ? 2 : 0, nB = MODE == BWD_DQ_DB ? 4 : 0;
-  static constexpr int oX = 4, oA = 8, oR = 12, oC = 16, oQ = 16 + nC, oM = oQ + 4, oD = oM + 4, oB = oD + nC,
+  static constexpr int nAR = SMX ? 0 : 4;
+  static constexpr int oX = 4, oA = 8, oR = oA + nAR, oC = oR + nAR, oQ = oC + nC, oM = oQ + 4, oD = oM + 4, oB = oD + nC,
                        oP = oB + nB, oS = oP + nP, OPG = oS + 2, NOPS = 4 * OPG;
 };
-template <int D, int MODE, bool ALIBI, bool MASK, int I>
+// nbias_v: the bias term of the exponent (SMX: -lse of the lane's row, log2 units); sl2_v: the
+// ALiBi slope (SMX: negated, the exponent has the other sign); dstat_v (SMX): D of the lane's row.
+template <int D, int MODE, bool ALIBI, bool MASK, bool SMX, int I>
 __device__ __forceinline__ void bsig_op(BwdWave<D, MODE>& W, const f32x16& s, const f32x16& dp, float (&u)[16],
                                         float (&v)[16], uint32_t (&wp)[8], uint32_t (&wd)[8], uint64_t (&km)[16],
-                                        float nbias_v, float sl2_v, float dist0, float dstep, int thr) {
-  using L = BsigLayout<MODE, MASK>;
+                                        float nbias_v, float sl2_v, float dist0, float dstep, int thr, float dstat_v) {
+  using L = BsigLayout<MODE, MASK, SMX>;
   constexpr int G = I / L::OPG, i = I % L::OPG, e = 4 * G + (i & 3);
   if constexpr (i < L::oX) {
     if constexpr (ALIBI) {
@@ -369,9 +375,11 @@ __device__ __forceinline__ void bsig_op(BwdWave<D, MODE>& W, const f32x16& s, co
       const float keyf = (float)key_of_reg(e);
       asm volatile("v_fma_f32 %0, %1, %2, %3" : "=v"(t) : "v"(dstep), "v"(keyf), "v"(dist0));
       asm volatile("v_fma_f32 %0, %1, |%2|, %3" : "=v"(w) : "v"(sl2_v), "v"(t), "v"(nbias_v));
-      asm volatile("v_fma_f32 %0, %1, %2, %3" : "=v"(u[e]) : "v"(s[e]), "s"(W.nscale), "v"(w));
+      if constexpr (SMX) asm volatile("v_fma_f32 %0, %1, -%2, %3" : "=v"(u[e]) : "v"(s[e]), "s"(W.nscale), "v"(w));
+      else asm volatile("v_fma_f32 %0, %1, %2, %3" : "=v"(u[e]) : "v"(s[e]), "s"(W.nscale), "v"(w));
     } else {
-      asm volatile("v_fma_f32 %0, %1, %2, %3" : "=v"(u[e]) : "v"(s[e]), "s"(W.nscale), "v"(nbias_v));
+      if constexpr (SMX) asm volatile("v_fma_f32 %0, %1, -%2, %3" : "=v"(u[e]) : "v"(s[e]), "s"(W.nscale), "v"(nbias_v));
+      else asm volatile("v_fma_f32 %0, %1, %2, %3" : "=v"(u[e]) : "v"(s[e]), "s"(W.nscale), "v"(nbias_v));
     }
   } else if constexpr (i < L::oA) {
     asm volatile("v_exp_f32 %0, %0" : "+v"(u[e]));
@@ -386,9 +394,11 @@ __device__ __forceinline__ void bsig_op(BwdWave<D, MODE>& W, const f32x16& s, co
     else
       asm volatile("v_cmp_le_i32_e64 %0, %2, %3\n\tv_cndmask_b32_e64 %1, 0, %1, %0" : "=&s"(km[e]), "+v"(u[e]) : "n"(kor), "v"(thr));
   } else if constexpr (i < L::oM) {
-    asm volatile("v_fma_f32 %0, -%1, %1, %1" : "=v"(v[e]) : "v"(u[e]));
+    if constexpr (SMX) asm volatile("v_sub_f32 %0, %1, %2" : "=v"(v[e]) : "v"(dp[e]), "v"(dstat_v));
+    else asm volatile("v_fma_f32 %0, -%1, %1, %1" : "=v"(v[e]) : "v"(u[e]));
   } else if constexpr (i < L::oD) {
-    asm volatile("v_mul_f32 %0, %0, %1" : "+v"(v[e]) : "v"(dp[e]));
+    if constexpr (SMX) asm volatile("v_mul_f32 %0, %0, %1" : "+v"(v[e]) : "v"(u[e]));
+    else asm volatile("v_mul_f32 %0, %0, %1" : "+v"(v[e]) : "v"(dp[e]));
   } else if constexpr (i < L::oB) {
     asm volatile("v_cndmask_b32_e64 %0, 0, %0, %1" : "+v"(v[e]) : "s"(km[e]));
   } else if constexpr (i < L::oP) {
@@ -401,28 +411,29 @@ __device__ __forceinline__ void bsig_op(BwdWave<D, MODE>& W, const f32x16& s, co
     asm volatile("v_cvt_pk_bf16_f32 %0, %1, %2" : "=v"(wd[j]) : "v"(v[2 * j]), "v"(v[2 * j + 1]));
   }
 }
-template <int D, int MODE, bool ALIBI, bool MASK, int LO, int HI>
+template <int D, int MODE, bool ALIBI, bool MASK, bool SMX, int LO, int HI>
 __device__ __forceinline__ void bsig_ops(BwdWave<D, MODE>& W, const f32x16& s, const f32x16& dp, float (&u)[16],
                                          float (&v)[16], uint32_t (&wp)[8], uint32_t (&wd)[8], uint64_t (&km)[16],
-                                         float nbias_v, float sl2_v, float dist0, float dstep, int thr) {
+                                         float nbias_v, float sl2_v, float dist0, float dstep, int thr, float dstat_v) {
   if constexpr (LO < HI) {
-    bsig_op<D, MODE, ALIBI, MASK, LO>(W, s, dp, u, v, wp, wd, km, nbias_v, sl2_v, dist0, dstep, thr);
-    bsig_ops<D, MODE, ALIBI, MASK, LO + 1, HI>(W, s, dp, u, v, wp, wd, km, nbias_v, sl2_v, dist0, dstep, thr);
+    bsig_op<D, MODE, ALIBI, MASK, SMX, LO>(W, s, dp, u, v, wp, wd, km, nbias_v, sl2_v, dist0, dstep, thr, dstat_v);
+    bsig_ops<D, MODE, ALIBI, MASK, SMX, LO + 1, HI>(W, s, dp, u, v, wp, wd, km, nbias_v, sl2_v, dist0, dstep, thr, dstat_v);
   }
 }
 
-template <int D, int MODE, bool ALIBI, int PAR, bool DMA, bool MASK, bool FOLD, bool GUARD, int K>
+template <int D, int MODE, bool ALIBI, int PAR, bool DMA, bool MASK, bool FOLD, bool GUARD, bool SMX, int K>
 __device__ __forceinline__ void bwd_full_subslots(BwdWave<D, MODE>& W, uint32_t trimm, const uint32_t* nextrow,
                                                   uint32_t nextimm, float (&u)[16], float (&v)[16], uint32_t (&wp)[8],
                                                   uint32_t (&wd)[8], uint64_t (&km)[16], float nbias_v, float sl2_v,
-                                                  float dist0, float dstep, int thr, const DmaStagerX<D, 4>& st1,
+                                                  float dist0, float dstep, int thr, float dstat_v,
+                                                  const DmaStagerX<D, 4>& st1,
                                                   const DmaStagerX<D, 4>& st2, uint32_t dma_lds, int uwave) {
   constexpr int KD = D / 16, DT = D / 32;
   constexpr uint32_t T2OFF = 64 * D * 2;
   constexpr int NA = 2 * KD;                               // first-product MFMAs
   constexpr int NB = MODE == BWD_DKDV ? 2 * KD : KD;       // second-product MFMAs
   constexpr int NSUB = NA + NB;
-  constexpr int NOPS = BsigLayout<MODE, MASK>::NOPS;
+  constexpr int NOPS = BsigLayout<MODE, MASK, SMX>::NOPS;
   if constexpr (K < NSUB) {
     if constexpr (K < NA) {
       constexpr int kk = K / 2;
@@ -462,8 +473,9 @@ __device__ __forceinline__ void bwd_full_subslots(BwdWave<D, MODE>& W, uint32_t 
         W.F[2 * j] = as_bf16x8(lds_read_b128(nextrow[j] + nextimm));
       }
     }
-    bsig_ops<D, MODE, ALIBI, MASK, (K * NOPS) / NSUB, ((K + 1) * NOPS) / NSUB>(W, W.s[PAR ^ 1], W.dp[PAR ^ 1], u, v, wp, wd,
-                                                                               km, nbias_v, sl2_v, dist0, dstep, thr);
+    bsig_ops<D, MODE, ALIBI, MASK, SMX, (K * NOPS) / NSUB, ((K + 1) * NOPS) / NSUB>(W, W.s[PAR ^ 1], W.dp[PAR ^ 1], u, v, wp,
+                                                                                    wd, km, nbias_v, sl2_v, dist0, dstep,
+                                                                                    thr, dstat_v);
     if constexpr (DMA) {
       // one staging instruction of the tile two ahead every DSTEP sub-slots
       constexpr int NI = DmaStagerX<D, 4>::NI, DSTEP = NSUB / (2 * NI);
@@ -473,8 +485,9 @@ __device__ __forceinline__ void bwd_full_subslots(BwdWave<D, MODE>& W, uint32_t 
         else st2.template issue_one<n - NI>(dma_lds + 64 * D * 2, uwave);
       }
     }
-    bwd_full_subslots<D, MODE, ALIBI, PAR, DMA, MASK, FOLD, GUARD, K + 1>(W, trimm, nextrow, nextimm, u, v, wp, wd, km, nbias_v, sl2_v,
-                                                             dist0, dstep, thr, st1, st2, dma_lds, uwave);
+    bwd_full_subslots<D, MODE, ALIBI, PAR, DMA, MASK, FOLD, GUARD, SMX, K + 1>(W, trimm, nextrow, nextimm, u, v, wp, wd, km,
+                                                                               nbias_v, sl2_v, dist0, dstep, thr, dstat_v, st1,
+                                                                               st2, dma_lds, uwave);
   }
 }
 
@@ -483,7 +496,9 @@ __device__ __forceinline__ void bwd_full_subslots(BwdWave<D, MODE>& W, uint32_t 
 // makes the compiler park streamed fragments in AGPRs and copy them back right before use).
 // SETTLE = false leaves the wait for the last MFMAs to the caller (a loop of pinned steps only,
 // which waits once after the loop).
-template <int D, int MODE, bool ALIBI, bool FOLD, int PAR, bool DMA, bool MASK = false, bool SETTLE = true, bool GUARD = false>
+// SMX: the softmax arithmetic (dQ pass; W.nlse and W.dstat hold the lane's row statistics).
+template <int D, int MODE, bool ALIBI, bool FOLD, int PAR, bool DMA, bool MASK = false, bool SETTLE = true, bool GUARD = false,
+          bool SMX = false>
 __device__ __forceinline__ void bwd_step_full_pinned(BwdWave<D, MODE>& W, uint32_t trimm, const uint32_t* nextrow,
                                                      uint32_t nextimm, int cs, const DmaStagerX<D, 4>& st1,
                                                      const DmaStagerX<D, 4>& st2, uint32_t dma_lds, int uwave,
@@ -495,13 +510,15 @@ __device__ __forceinline__ void bwd_step_full_pinned(BwdWave<D, MODE>& W, uint32
   const int bl = cs + 8 * W.h;
   const float dist0 = MODE == BWD_DKDV ? (float)(bl - W.ai) : (float)(W.ai - bl);
   const float dstep = MODE == BWD_DKDV ? 1.0f : -1.0f;
+  static_assert(!SMX || (!FOLD && MODE == BWD_DQ), "softmax: the dQ pass, ALiBi in its |i-j| form");
   if constexpr (FOLD)  // the per-element arithmetic is the one without ALiBi, on a per-step bias
-    bwd_full_subslots<D, MODE, false, PAR, DMA, MASK, true, GUARD, 0>(W, trimm, nextrow, nextimm, u, v, wp, wd, km,
-                                                               __builtin_fmaf(W.sl2, dist0, W.nbias), W.sl2, dist0, dstep,
-                                                               thr, st1, st2, dma_lds, uwave);
+    bwd_full_subslots<D, MODE, false, PAR, DMA, MASK, true, GUARD, false, 0>(W, trimm, nextrow, nextimm, u, v, wp, wd, km,
+                                                                      __builtin_fmaf(W.sl2, dist0, W.nbias), W.sl2, dist0,
+                                                                      dstep, thr, 0.f, st1, st2, dma_lds, uwave);
   else
-    bwd_full_subslots<D, MODE, ALIBI, PAR, DMA, MASK, false, GUARD, 0>(W, trimm, nextrow, nextimm, u, v, wp, wd, km, W.nbias, W.sl2,
-                                                                dist0, dstep, thr, st1, st2, dma_lds, uwave);
+    bwd_full_subslots<D, MODE, ALIBI, PAR, DMA, MASK, false, GUARD, SMX, 0>(W, trimm, nextrow, nextimm, u, v, wp, wd, km,
+                                                                     SMX ? W.nlse : W.nbias, SMX ? -W.sl2 : W.sl2, dist0,
+                                                                     dstep, thr, W.dstat, st1, st2, dma_lds, uwave);
   // The compiler does not know that the asm statements above are MFMAs: let the last ones
   // retire before it may touch their accumulators (copies at the join with the other path).
   if constexpr (SETTLE) mfma_settle();
@@ -526,6 +543,9 @@ __device__ __forceinline__ void attn_bwd_body(const BwdParams& p, const int bh, 
   static_assert(!GROUPS || MODE == BWD_DKDV, "only the dK/dV pass iterates over query heads");
   constexpr int NW = 4, BS = 32 * NW, BC = 64, KD = D / 16, DT = D / 32;
   constexpr bool FOLD = !SOFTMAX && CAUSAL && ALIBI;  // see bwd_step
+  // kernels that carry the pinned steps: the sigmoid passes and the softmax dQ pass (whose row
+  // statistics are per lane; the softmax dK/dV pass reads them per element and stays compiler-scheduled)
+  constexpr bool kPinned = PIN && (!SOFTMAX || MODE == BWD_DQ);
   constexpr int TILE = BC * D * 2, SLOT = 2 * TILE, CHUNK = 32 * D * 2, NSLOT = 4;
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   const uint32_t lds0 = (uint32_t)(uintptr_t)(SATTN_LDS(char)*)smem;
@@ -733,7 +753,7 @@ __device__ __forceinline__ void attn_bwd_body(const BwdParams& p, const int bh, 
     const bool ragged = doS && s - 1 == c_hi_s && cs + 32 > Nt;
     // a step with at most one live stage (first and last step of the wave's range, steps
     // outside it) is cheaper in the flag-driven form, which skips the dead stages
-    pin = PIN && !SOFTMAX && !(MODE == BWD_DKDV && ragged) && (int)doA + (int)doS + (int)doB >= 2;
+    pin = kPinned && !(MODE == BWD_DKDV && ragged) && (int)doA + (int)doS + (int)doB >= 2;
     if (!doS) thr = NONE;
     else if (MODE == BWD_DKDV) thr = (CAUSAL && s - 1 == c_lo_s) ? W.ai - bl : ALL;
     else thr = (s - 1 == c_hi_s) ? ((CAUSAL && W.ai < Nt - 1 ? W.ai : Nt - 1) - bl) : ALL;
@@ -744,14 +764,14 @@ __device__ __forceinline__ void attn_bwd_body(const BwdParams& p, const int bh, 
   // loop of pinned steps only; the tiles before and after run the flag-driven general body.
   // Every variant has its one barrier per tile at the same place, so waves of a workgroup
   // may be in different loops.
-  const int t_s0 = (SOFTMAX || !PIN) ? t_hi + 1 : (c_lo_s + 3) / 2;          // first tile with 2t >= c_lo+2
+  const int t_s0 = !kPinned ? t_hi + 1 : (c_lo_s + 3) / 2;          // first tile with 2t >= c_lo+2
   // last tile with 2t+1 <= c_hi / last tile whose staging needs no clamping.  The steady loop
   // stages tile t+2 during tile t without looking at the tensor's end: when the tensor ends on
   // a tile boundary the stager stops at the last tile and tiles t+2 past it are that tile
   // again, written to a ring slot nobody reads; a ragged last tile needs the clamped form,
   // so the loop ends before it.
   const int t_s1a = (c_hi_s + 1) / 2 - 1, t_s1b = Nt % BC == 0 ? t_s1a : Nt / BC - 3;
-  const int t_s1 = (SOFTMAX || !PIN) ? t_lo - 1 : (t_s1a < t_s1b ? t_s1a : t_s1b);
+  const int t_s1 = !kPinned ? t_lo - 1 : (t_s1a < t_s1b ? t_s1a : t_s1b);
   auto rotate = [&](int t) {
     // rotate the per-lane addresses by one ring slot
     const int s0 = t % NSLOT;  // row0 points at slot s0, row1 at s0+1, tr at s0-1 (mod 4)
@@ -775,10 +795,10 @@ __device__ __forceinline__ void attn_bwd_body(const BwdParams& p, const int bh, 
         bool pin_s;
         int thr;
         step_kind(s, pin_s, thr);
-        constexpr bool kPinned = PIN && !SOFTMAX;  // the other kernels do not carry the pinned code at all
+        // (the other kernels do not carry the pinned code at all)
         if (kPinned && lane_flag(pin_s)) {
           if constexpr (kPinned)
-            bwd_step_full_pinned<D, MODE, ALIBI, FOLD, 0, false, true, true, GROUPS>(W, 0, W.row0, CHUNK, 32 * (s - 1), st1, st2, 0, uwave, thr);
+            bwd_step_full_pinned<D, MODE, ALIBI, FOLD, 0, false, true, true, GROUPS, SOFTMAX>(W, 0, W.row0, CHUNK, 32 * (s - 1), st1, st2, 0, uwave, thr);
         } else
           bwd_step<D, MODE, CAUSAL, ALIBI, SOFTMAX, 0>(W, lane_flag(doA_s), lane_flag(doS_s), lane_flag(doB_s),
                                                        lane_flag(mask_s), 0, W.row0, CHUNK, 32 * (s - 1), Nt, stat_l, stat_d);
@@ -801,17 +821,17 @@ __device__ __forceinline__ void attn_bwd_body(const BwdParams& p, const int bh, 
           st2.issue(dma_lds + TILE, Nt, uwave, lane);
         }
         // rows of chunk s+1 come from tile t+1 (first half); transposed reads of chunk s-2 from tile t-1 (second half)
-        constexpr bool kPinned = PIN && !SOFTMAX;  // the other kernels do not carry the pinned code at all
+        // (the other kernels do not carry the pinned code at all)
         if (kPinned && lane_flag(pin_s)) {
           if constexpr (kPinned)
-            bwd_step_full_pinned<D, MODE, ALIBI, FOLD, 1, false, true, true, GROUPS>(W, CHUNK, W.row1, 0, 32 * (s - 1), st1, st2, 0, uwave, thr);
+            bwd_step_full_pinned<D, MODE, ALIBI, FOLD, 1, false, true, true, GROUPS, SOFTMAX>(W, CHUNK, W.row1, 0, 32 * (s - 1), st1, st2, 0, uwave, thr);
         } else
           bwd_step<D, MODE, CAUSAL, ALIBI, SOFTMAX, 1>(W, lane_flag(doA_s), lane_flag(doS_s), lane_flag(doB_s),
                                                        lane_flag(mask_s), CHUNK, W.row1, 0, 32 * (s - 1), Nt, stat_l, stat_d);
       }
       rotate(t);
     }
-    if constexpr (PIN && !SOFTMAX) if (phase == 0) {
+    if constexpr (kPinned) if (phase == 0) {
       const bool any_steady = t <= t_s1;
       clock_probe_mark(p.clock, clk, kMarkSteadyBegin);
       const int t_steady_begin = t;
@@ -822,10 +842,10 @@ __device__ __forceinline__ void attn_bwd_body(const BwdParams& p, const int bh, 
         st2.step_back_inside(n_sat);
       }
       for (; t <= t_s1; ++t) {
-        bwd_step_full_pinned<D, MODE, ALIBI, FOLD, 0, false, false, false>(W, 0, W.row0, CHUNK, 32 * (2 * t - 1), st1, st2, 0, uwave);
+        bwd_step_full_pinned<D, MODE, ALIBI, FOLD, 0, false, false, false, false, SOFTMAX>(W, 0, W.row0, CHUNK, 32 * (2 * t - 1), st1, st2, 0, uwave);
         __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): tile t+1 has landed
         __builtin_amdgcn_s_barrier();
-        bwd_step_full_pinned<D, MODE, ALIBI, FOLD, 1, true, false, false>(W, CHUNK, W.row1, 0, 32 * (2 * t), st1, st2,
+        bwd_step_full_pinned<D, MODE, ALIBI, FOLD, 1, true, false, false, false, SOFTMAX>(W, CHUNK, W.row1, 0, 32 * (2 * t), st1, st2,
                                                                     lds0 + ((t + 2) % NSLOT) * SLOT, uwave);
         st1.advance_inside(n_sat);
         st2.advance_inside(n_sat);
@@ -905,7 +925,7 @@ __device__ __forceinline__ int bwd_block_of_rank(const BwdParams& p, int rank) {
 // SIMD to hide their schedule and sit right at the limit, so they are held to it; the pinned
 // forms use more VGPRs than a two-wave split of the register file leaves (128 + 128).
 template <int D, int MODE, bool CAUSAL, bool ALIBI, bool SOFTMAX, bool PIN = true, bool GROUPS = false>
-__global__ void __launch_bounds__(256, ((D == 64 && (SOFTMAX || !PIN)) ? 2 : 1))
+__global__ void __launch_bounds__(256, ((D == 64 && (!PIN || (SOFTMAX && MODE != BWD_DQ))) ? 2 : 1))
 attn_bwd_kernel(const BwdParams p) {
   const int kv_group = (MODE == BWD_DKDV && !GROUPS) ? 1 : p.kv_group;
   // Under the causal mask the r-th longest and the r-th shortest block of a head together stream

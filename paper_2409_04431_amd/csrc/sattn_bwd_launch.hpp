@@ -47,9 +47,10 @@ int launch_bwd_variant(BwdParams p, int causal, bool alibi, int parts, bool merg
         }
       }
     }
+    // (the softmax dK/dV pass has the compiler-scheduled form only: its row statistics differ per element)
     if (p.kv_group == 1)
       SATTN_DISPATCH2(causal, alibi,
-                      rc = launch(attn_bwd_kernel<D, BWD_DKDV, A, B2, SOFTMAX, PIN>, grid_k, block, lds, st, p));
+                      rc = launch(attn_bwd_kernel<D, BWD_DKDV, A, B2, SOFTMAX, PIN && !SOFTMAX>, grid_k, block, lds, st, p));
   }
   p.n_blocks = nb_q;
   p.head_group = heads_abreast(nb_q);
@@ -70,6 +71,7 @@ int launch_bwd_variant(BwdParams p, int causal, bool alibi, int parts, bool merg
 template <int D>
 int launch_bwd_bf16(BwdParams p, bool softmax, bool pin, int causal, bool alibi, int parts, bool merged,
                     hipStream_t st) {
+  if (softmax && pin) return launch_bwd_variant<D, true, true>(p, causal, alibi, parts, false, st);
   if (softmax) return launch_bwd_variant<D, true, false>(p, causal, alibi, parts, false, st);
   if (pin) return launch_bwd_variant<D, false, true>(p, causal, alibi, parts, merged, st);
   return launch_bwd_variant<D, false, false>(p, causal, alibi, parts, false, st);
