@@ -463,7 +463,7 @@ int bwd_impl(const BwdArgs& a) {
   }
   // causal passes deal a head's blocks out in pairs of equal work (longest with shortest) where
   // a pair per compute unit remains (see the 64-row forward)
-  p.pair = a.causal && !SOFTMAX && PIN && g_bwd_merged.load(std::memory_order_relaxed) != 3 &&
+  p.pair = a.causal && PIN && g_bwd_merged.load(std::memory_order_relaxed) != 3 &&
            (int64_t)a.B * Hkv * n_split * ((std::min(a.N, Nk) + 127) / 128 / 2) >= compute_units();
   if (a.d == 128) rc = launch_bwd_bf16<128>(p, SOFTMAX, PIN, a.causal, alibi, a.parts, merged, st);
   else rc = launch_bwd_bf16<64>(p, SOFTMAX, PIN, a.causal, alibi, a.parts, merged, st);

@@ -165,6 +165,32 @@ struct DmaStagerX {
   }
 };
 
+// Softmax dK/dV pass: the row statistics of a streamed tile of 64 queries (-lse*log2e and D, two
+// fp32 per query, from the [B*H, npad] vectors of the pre-pass) travel with the tile: 256 + 256
+// bytes into a side ring of four slots behind the tile ring, by the same asynchronous loads
+// (one dword per lane; every wave issues them, all writing the same values).
+struct StatStager {
+  static constexpr int SLOT = 512;
+  const float* l;  // -lse*log2e of this (batch, head), wave-uniform
+  const float* d;  // D of this (batch, head)
+  int last_tile;   // npad / 64 - 1
+  __device__ __forceinline__ static const float* scalar_ptr(const float* ptr) {
+    const uint64_t u = (uint64_t)ptr;
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)u), hi = __builtin_amdgcn_readfirstlane((uint32_t)(u >> 32));
+    return (const float*)(((uint64_t)hi << 32) | lo);
+  }
+  __device__ __forceinline__ void init(const float* l_, const float* d_, int npad) {
+    l = scalar_ptr(l_); d = scalar_ptr(d_); last_tile = npad / 64 - 1;
+  }
+  // stage the statistics of tile `tile` (clamped to the last one) into the side-ring slot at `lds`
+  __device__ __forceinline__ void issue(uint32_t lds, int tile, int lane) const {
+    const int t = tile < last_tile ? tile : last_tile;
+    const uint32_t o = (uint32_t)lane * 4;
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1" : : "v"(o), "s"(l + 64 * t), "s"(lds) : "memory");
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1" : : "v"(o), "s"(d + 64 * t), "s"(lds + 256) : "memory");
+  }
+};
+
 // A wave-uniform flag as a per-lane value the compiler cannot prove uniform.
 __device__ __forceinline__ bool lane_flag(bool uniform) {
   int x;
@@ -363,12 +389,33 @@ struct BsigLayout {
 };
 // nbias_v: the bias term of the exponent (SMX: -lse of the lane's row, log2 units); sl2_v: the
 // ALiBi slope (SMX: negated, the exponent has the other sign); dstat_v (SMX): D of the lane's row.
+// SMX in the dK/dV pass: the statistics belong to the streamed queries, one pair per element.
+// The lane's sixteen queries are rows bl..bl+7 and bl+16..bl+23 of the chunk (bl = 8h), group G
+// of four elements rows 4(G&1) + 16(G>>1) + 0..3: two 16-byte LDS reads per group from the side
+// ring (stat = address of row bl's -lse; D is 256 bytes further), issued one group ahead.
+struct BsigStats {
+  f32x4 l[4], d[4];
+  uint32_t stat;
+};
+template <int G>
+__device__ __forceinline__ void bsig_load_stats(BsigStats& st) {
+  constexpr uint32_t off = (4 * (G & 1) + 16 * (G >> 1)) * 4;
+  st.l[G] = *(SATTN_LDS(f32x4)*)(uintptr_t)(st.stat + off);
+  st.d[G] = *(SATTN_LDS(f32x4)*)(uintptr_t)(st.stat + off + 256);
+}
 template <int D, int MODE, bool ALIBI, bool MASK, bool SMX, int I>
 __device__ __forceinline__ void bsig_op(BwdWave<D, MODE>& W, const f32x16& s, const f32x16& dp, float (&u)[16],
                                         float (&v)[16], uint32_t (&wp)[8], uint32_t (&wd)[8], uint64_t (&km)[16],
-                                        float nbias_v, float sl2_v, float dist0, float dstep, int thr, float dstat_v) {
+                                        float nbias_v, float sl2_v, float dist0, float dstep, int thr, float dstat_v,
+                                        BsigStats& st) {
   using L = BsigLayout<MODE, MASK, SMX>;
   constexpr int G = I / L::OPG, i = I % L::OPG, e = 4 * G + (i & 3);
+  if constexpr (SMX && MODE == BWD_DKDV) {
+    if constexpr (I == 0) { bsig_load_stats<0>(st); bsig_load_stats<1>(st); }
+    else if constexpr (i == 0 && G + 1 < 4) bsig_load_stats<G + 1>(st);
+    if constexpr (i < L::oX) nbias_v = st.l[G][i & 3];
+    if constexpr (i >= L::oQ && i < L::oM) dstat_v = st.d[G][i & 3];
+  }
   if constexpr (i < L::oX) {
     if constexpr (ALIBI) {
       float t, w;
@@ -414,10 +461,11 @@ __device__ __forceinline__ void bsig_op(BwdWave<D, MODE>& W, const f32x16& s, co
 template <int D, int MODE, bool ALIBI, bool MASK, bool SMX, int LO, int HI>
 __device__ __forceinline__ void bsig_ops(BwdWave<D, MODE>& W, const f32x16& s, const f32x16& dp, float (&u)[16],
                                          float (&v)[16], uint32_t (&wp)[8], uint32_t (&wd)[8], uint64_t (&km)[16],
-                                         float nbias_v, float sl2_v, float dist0, float dstep, int thr, float dstat_v) {
+                                         float nbias_v, float sl2_v, float dist0, float dstep, int thr, float dstat_v,
+                                         BsigStats& st) {
   if constexpr (LO < HI) {
-    bsig_op<D, MODE, ALIBI, MASK, SMX, LO>(W, s, dp, u, v, wp, wd, km, nbias_v, sl2_v, dist0, dstep, thr, dstat_v);
-    bsig_ops<D, MODE, ALIBI, MASK, SMX, LO + 1, HI>(W, s, dp, u, v, wp, wd, km, nbias_v, sl2_v, dist0, dstep, thr, dstat_v);
+    bsig_op<D, MODE, ALIBI, MASK, SMX, LO>(W, s, dp, u, v, wp, wd, km, nbias_v, sl2_v, dist0, dstep, thr, dstat_v, st);
+    bsig_ops<D, MODE, ALIBI, MASK, SMX, LO + 1, HI>(W, s, dp, u, v, wp, wd, km, nbias_v, sl2_v, dist0, dstep, thr, dstat_v, st);
   }
 }
 
@@ -425,7 +473,7 @@ template <int D, int MODE, bool ALIBI, int PAR, bool DMA, bool MASK, bool FOLD, 
 __device__ __forceinline__ void bwd_full_subslots(BwdWave<D, MODE>& W, uint32_t trimm, const uint32_t* nextrow,
                                                   uint32_t nextimm, float (&u)[16], float (&v)[16], uint32_t (&wp)[8],
                                                   uint32_t (&wd)[8], uint64_t (&km)[16], float nbias_v, float sl2_v,
-                                                  float dist0, float dstep, int thr, float dstat_v,
+                                                  float dist0, float dstep, int thr, float dstat_v, BsigStats& stats,
                                                   const DmaStagerX<D, 4>& st1,
                                                   const DmaStagerX<D, 4>& st2, uint32_t dma_lds, int uwave) {
   constexpr int KD = D / 16, DT = D / 32;
@@ -475,7 +523,7 @@ __device__ __forceinline__ void bwd_full_subslots(BwdWave<D, MODE>& W, uint32_t 
     }
     bsig_ops<D, MODE, ALIBI, MASK, SMX, (K * NOPS) / NSUB, ((K + 1) * NOPS) / NSUB>(W, W.s[PAR ^ 1], W.dp[PAR ^ 1], u, v, wp,
                                                                                     wd, km, nbias_v, sl2_v, dist0, dstep,
-                                                                                    thr, dstat_v);
+                                                                                    thr, dstat_v, stats);
     if constexpr (DMA) {
       // one staging instruction of the tile two ahead every DSTEP sub-slots
       constexpr int NI = DmaStagerX<D, 4>::NI, DSTEP = NSUB / (2 * NI);
@@ -486,8 +534,8 @@ __device__ __forceinline__ void bwd_full_subslots(BwdWave<D, MODE>& W, uint32_t 
       }
     }
     bwd_full_subslots<D, MODE, ALIBI, PAR, DMA, MASK, FOLD, GUARD, SMX, K + 1>(W, trimm, nextrow, nextimm, u, v, wp, wd, km,
-                                                                               nbias_v, sl2_v, dist0, dstep, thr, dstat_v, st1,
-                                                                               st2, dma_lds, uwave);
+                                                                               nbias_v, sl2_v, dist0, dstep, thr, dstat_v,
+                                                                               stats, st1, st2, dma_lds, uwave);
   }
 }
 
@@ -496,29 +544,32 @@ __device__ __forceinline__ void bwd_full_subslots(BwdWave<D, MODE>& W, uint32_t 
 // makes the compiler park streamed fragments in AGPRs and copy them back right before use).
 // SETTLE = false leaves the wait for the last MFMAs to the caller (a loop of pinned steps only,
 // which waits once after the loop).
-// SMX: the softmax arithmetic (dQ pass; W.nlse and W.dstat hold the lane's row statistics).
+// SMX: the softmax arithmetic (dQ pass: W.nlse and W.dstat hold the lane's row statistics; dK/dV
+// pass: `stat` = LDS address of the statistics of the lane's first query in the chunk).
 template <int D, int MODE, bool ALIBI, bool FOLD, int PAR, bool DMA, bool MASK = false, bool SETTLE = true, bool GUARD = false,
           bool SMX = false>
 __device__ __forceinline__ void bwd_step_full_pinned(BwdWave<D, MODE>& W, uint32_t trimm, const uint32_t* nextrow,
                                                      uint32_t nextimm, int cs, const DmaStagerX<D, 4>& st1,
                                                      const DmaStagerX<D, 4>& st2, uint32_t dma_lds, int uwave,
-                                                     int thr = 0) {
+                                                     int thr = 0, uint32_t stat = 0) {
   float u[16], v[16];
   uint32_t wp[8], wd[8];
   uint64_t km[16];
+  BsigStats stats;
+  stats.stat = stat;
   // |i-j| of register r: DKDV streams queries (b - a), DQ streams keys (a - b)
   const int bl = cs + 8 * W.h;
   const float dist0 = MODE == BWD_DKDV ? (float)(bl - W.ai) : (float)(W.ai - bl);
   const float dstep = MODE == BWD_DKDV ? 1.0f : -1.0f;
-  static_assert(!SMX || (!FOLD && MODE == BWD_DQ), "softmax: the dQ pass, ALiBi in its |i-j| form");
+  static_assert(!SMX || !FOLD, "softmax: ALiBi in its |i-j| form");
   if constexpr (FOLD)  // the per-element arithmetic is the one without ALiBi, on a per-step bias
     bwd_full_subslots<D, MODE, false, PAR, DMA, MASK, true, GUARD, false, 0>(W, trimm, nextrow, nextimm, u, v, wp, wd, km,
                                                                       __builtin_fmaf(W.sl2, dist0, W.nbias), W.sl2, dist0,
-                                                                      dstep, thr, 0.f, st1, st2, dma_lds, uwave);
+                                                                      dstep, thr, 0.f, stats, st1, st2, dma_lds, uwave);
   else
     bwd_full_subslots<D, MODE, ALIBI, PAR, DMA, MASK, false, GUARD, SMX, 0>(W, trimm, nextrow, nextimm, u, v, wp, wd, km,
                                                                      SMX ? W.nlse : W.nbias, SMX ? -W.sl2 : W.sl2, dist0,
-                                                                     dstep, thr, W.dstat, st1, st2, dma_lds, uwave);
+                                                                     dstep, thr, W.dstat, stats, st1, st2, dma_lds, uwave);
   // The compiler does not know that the asm statements above are MFMAs: let the last ones
   // retire before it may touch their accumulators (copies at the join with the other path).
   if constexpr (SETTLE) mfma_settle();
@@ -543,9 +594,10 @@ __device__ __forceinline__ void attn_bwd_body(const BwdParams& p, const int bh, 
   static_assert(!GROUPS || MODE == BWD_DKDV, "only the dK/dV pass iterates over query heads");
   constexpr int NW = 4, BS = 32 * NW, BC = 64, KD = D / 16, DT = D / 32;
   constexpr bool FOLD = !SOFTMAX && CAUSAL && ALIBI;  // see bwd_step
-  // kernels that carry the pinned steps: the sigmoid passes and the softmax dQ pass (whose row
-  // statistics are per lane; the softmax dK/dV pass reads them per element and stays compiler-scheduled)
-  constexpr bool kPinned = PIN && (!SOFTMAX || MODE == BWD_DQ);
+  // kernels that carry the pinned steps; kStats: the softmax dK/dV pass, whose pinned steps read
+  // the row statistics of the streamed queries from a side ring in LDS
+  constexpr bool kPinned = PIN;
+  constexpr bool kStats = SOFTMAX && MODE == BWD_DKDV && kPinned;
   constexpr int TILE = BC * D * 2, SLOT = 2 * TILE, CHUNK = 32 * D * 2, NSLOT = 4;
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   const uint32_t lds0 = (uint32_t)(uintptr_t)(SATTN_LDS(char)*)smem;
@@ -697,6 +749,16 @@ __device__ __forceinline__ void attn_bwd_body(const BwdParams& p, const int bh, 
   constexpr int NI_TILE = DmaStagerX<D, NW>::NI;  // staging instructions per wave, tensor and tile
   st1.init(y1b, y1s, Nt, t_lo * BC, uwave, lane_s);
   st2.init(y2b, y2s, Nt, t_lo * BC, uwave, lane_s);
+  // side ring of the streamed queries' statistics (softmax dK/dV): slot of tile t = t % 4, behind the tile ring
+  const uint32_t stat_base = lds0 + NSLOT * SLOT;
+  StatStager sst;
+  if constexpr (kStats) sst.init(stat_l, stat_d, p.npad);
+  auto stage_stats = [&](int tile, int slot_of) {  // the statistics of `tile` into the side-ring slot of tile `slot_of`
+    if constexpr (kStats) sst.issue(stat_base + (slot_of % NSLOT) * StatStager::SLOT, tile, lane);
+  };
+  // address of the statistics of this lane's first query in chunk c
+  // (c = -1, the empty stage of the very first step, maps to a slot like any other: its elements are masked)
+  auto stat_of_chunk = [&](int c) { return stat_base + ((c >> 1) & (NSLOT - 1)) * StatStager::SLOT + ((c & 1) * 32 + 8 * h) * 4; };
   // Prologue.  The workgroup's first loads share the compute unit's one path from memory, so
   // they are kept few and ordered by need: tile t_lo, the stationary fragments, then tile
   // t_lo+1, which may land while the first tile is computed (every tile waits for the next
@@ -710,12 +772,16 @@ __device__ __forceinline__ void attn_bwd_body(const BwdParams& p, const int bh, 
   }
   st1.issue(lds0 + (t_lo % NSLOT) * SLOT, Nt, uwave, lane);
   st2.issue(lds0 + (t_lo % NSLOT) * SLOT + TILE, Nt, uwave, lane);
+  stage_stats(t_lo, t_lo);
   if constexpr (!GROUPS) load_stationary();
   if (t_lo + 1 <= t_data_hi) {
     st1.issue(lds0 + ((t_lo + 1) % NSLOT) * SLOT, Nt, uwave, lane);
     st2.issue(lds0 + ((t_lo + 1) % NSLOT) * SLOT + TILE, Nt, uwave, lane);
-    // all but the newest 2 NI loads: tile t_lo has landed, the stationary fragments are in registers
-    SATTN_WAIT_VMCNT(2 * NI_TILE);
+    stage_stats(t_lo + 1, t_lo + 1);
+    // all but the newest 2 NI loads (+ 2 for the statistics): tile t_lo has landed, the
+    // stationary fragments are in registers
+    if constexpr (kStats) SATTN_WAIT_VMCNT(2 * NI_TILE + 2);
+    else SATTN_WAIT_VMCNT(2 * NI_TILE);
   } else {
     SATTN_WAIT_VMCNT(0);
   }
@@ -798,7 +864,7 @@ __device__ __forceinline__ void attn_bwd_body(const BwdParams& p, const int bh, 
         // (the other kernels do not carry the pinned code at all)
         if (kPinned && lane_flag(pin_s)) {
           if constexpr (kPinned)
-            bwd_step_full_pinned<D, MODE, ALIBI, FOLD, 0, false, true, true, GROUPS, SOFTMAX>(W, 0, W.row0, CHUNK, 32 * (s - 1), st1, st2, 0, uwave, thr);
+            bwd_step_full_pinned<D, MODE, ALIBI, FOLD, 0, false, true, true, GROUPS, SOFTMAX>(W, 0, W.row0, CHUNK, 32 * (s - 1), st1, st2, 0, uwave, thr, stat_of_chunk(s - 1));
         } else
           bwd_step<D, MODE, CAUSAL, ALIBI, SOFTMAX, 0>(W, lane_flag(doA_s), lane_flag(doS_s), lane_flag(doB_s),
                                                        lane_flag(mask_s), 0, W.row0, CHUNK, 32 * (s - 1), Nt, stat_l, stat_d);
@@ -819,12 +885,13 @@ __device__ __forceinline__ void attn_bwd_body(const BwdParams& p, const int bh, 
           const uint32_t dma_lds = lds0 + ((t + 2) % NSLOT) * SLOT;
           st1.issue(dma_lds, Nt, uwave, lane);
           st2.issue(dma_lds + TILE, Nt, uwave, lane);
+          stage_stats(t + 2, t + 2);
         }
         // rows of chunk s+1 come from tile t+1 (first half); transposed reads of chunk s-2 from tile t-1 (second half)
         // (the other kernels do not carry the pinned code at all)
         if (kPinned && lane_flag(pin_s)) {
           if constexpr (kPinned)
-            bwd_step_full_pinned<D, MODE, ALIBI, FOLD, 1, false, true, true, GROUPS, SOFTMAX>(W, CHUNK, W.row1, 0, 32 * (s - 1), st1, st2, 0, uwave, thr);
+            bwd_step_full_pinned<D, MODE, ALIBI, FOLD, 1, false, true, true, GROUPS, SOFTMAX>(W, CHUNK, W.row1, 0, 32 * (s - 1), st1, st2, 0, uwave, thr, stat_of_chunk(s - 1));
         } else
           bwd_step<D, MODE, CAUSAL, ALIBI, SOFTMAX, 1>(W, lane_flag(doA_s), lane_flag(doS_s), lane_flag(doB_s),
                                                        lane_flag(mask_s), CHUNK, W.row1, 0, 32 * (s - 1), Nt, stat_l, stat_d);
@@ -842,11 +909,13 @@ __device__ __forceinline__ void attn_bwd_body(const BwdParams& p, const int bh, 
         st2.step_back_inside(n_sat);
       }
       for (; t <= t_s1; ++t) {
-        bwd_step_full_pinned<D, MODE, ALIBI, FOLD, 0, false, false, false, false, SOFTMAX>(W, 0, W.row0, CHUNK, 32 * (2 * t - 1), st1, st2, 0, uwave);
+        bwd_step_full_pinned<D, MODE, ALIBI, FOLD, 0, false, false, false, false, SOFTMAX>(W, 0, W.row0, CHUNK, 32 * (2 * t - 1), st1, st2, 0, uwave, 0, stat_of_chunk(2 * t - 1));
         __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): tile t+1 has landed
         __builtin_amdgcn_s_barrier();
+        stage_stats(st1.j0 / BC, t + 2);  // (the tile the stager is at: t + 2, or the last one again, see above)
         bwd_step_full_pinned<D, MODE, ALIBI, FOLD, 1, true, false, false, false, SOFTMAX>(W, CHUNK, W.row1, 0, 32 * (2 * t), st1, st2,
-                                                                    lds0 + ((t + 2) % NSLOT) * SLOT, uwave);
+                                                                    lds0 + ((t + 2) % NSLOT) * SLOT, uwave, 0,
+                                                                    stat_of_chunk(2 * t));
         st1.advance_inside(n_sat);
         st2.advance_inside(n_sat);
         rotate(t);
@@ -925,15 +994,15 @@ __device__ __forceinline__ int bwd_block_of_rank(const BwdParams& p, int rank) {
 // SIMD to hide their schedule and sit right at the limit, so they are held to it; the pinned
 // forms use more VGPRs than a two-wave split of the register file leaves (128 + 128).
 template <int D, int MODE, bool CAUSAL, bool ALIBI, bool SOFTMAX, bool PIN = true, bool GROUPS = false>
-__global__ void __launch_bounds__(256, ((D == 64 && (!PIN || (SOFTMAX && MODE != BWD_DQ))) ? 2 : 1))
+__global__ void __launch_bounds__(256, ((D == 64 && !PIN) ? 2 : 1))
 attn_bwd_kernel(const BwdParams p) {
   const int kv_group = (MODE == BWD_DKDV && !GROUPS) ? 1 : p.kv_group;
   // Under the causal mask the r-th longest and the r-th shortest block of a head together stream
   // the same number of tiles whatever r is: a workgroup that runs such a pair makes all
   // workgroups of the launch equal (no ragged end) and halves the gaps between workgroups.
-  // (only the pinned sigmoid passes carry the loop: it costs a few registers, which the kernels
-  // held to 256 of them do not have)
-  constexpr bool kCanPair = CAUSAL && !SOFTMAX && PIN && MODE != BWD_DQ_DB;
+  // (only the pinned passes carry the loop: it costs a few registers, which the kernels held to
+  // 256 of them do not have)
+  constexpr bool kCanPair = CAUSAL && PIN && MODE != BWD_DQ_DB;
   const bool pair = kCanPair && p.pair;
   const int places = pair ? p.n_blocks / 2 : p.n_blocks;
   const int total = places * p.B * (MODE == BWD_DKDV ? p.H / kv_group : p.H) * ((GROUPS && p.n_split > 1) ? p.n_split : 1);

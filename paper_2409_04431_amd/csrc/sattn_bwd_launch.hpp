@@ -11,7 +11,7 @@ int launch_bwd_variant(BwdParams p, int causal, bool alibi, int parts, bool merg
   // pairs of blocks per workgroup: causal pinned sigmoid passes over equal-length sequences with
   // an even number of blocks per head (measured from 4 blocks up: 0-3 % faster than single
   // blocks, never slower)
-  const bool may_pair = p.pair && causal && !SOFTMAX && PIN && !p.cu_seqlens;
+  const bool may_pair = p.pair && causal && PIN && !p.cu_seqlens;
   const bool pair_q = may_pair && !p.db_rows && nb_q % 2 == 0 && nb_q >= 4, pair_k = may_pair && nb_k % 2 == 0 && nb_k >= 4;
   dim3 grid((pair_q ? nb_q / 2 : nb_q) * p.B * p.H), grid_k((pair_k ? nb_k / 2 : nb_k) * p.B * p.H),
       grid_kv((pair_k ? nb_k / 2 : nb_k) * p.B * (p.H / p.kv_group) * (p.n_split > 1 ? p.n_split : 1));
@@ -47,10 +47,10 @@ int launch_bwd_variant(BwdParams p, int causal, bool alibi, int parts, bool merg
         }
       }
     }
-    // (the softmax dK/dV pass has the compiler-scheduled form only: its row statistics differ per element)
+    // (the pinned softmax dK/dV pass keeps the streamed queries' statistics in a side ring behind the tiles)
     if (p.kv_group == 1)
-      SATTN_DISPATCH2(causal, alibi,
-                      rc = launch(attn_bwd_kernel<D, BWD_DKDV, A, B2, SOFTMAX, PIN && !SOFTMAX>, grid_k, block, lds, st, p));
+      SATTN_DISPATCH2(causal, alibi, rc = launch(attn_bwd_kernel<D, BWD_DKDV, A, B2, SOFTMAX, PIN>, grid_k, block,
+                                                 lds + ((SOFTMAX && PIN) ? 4 * StatStager::SLOT : 0), st, p));
   }
   p.n_blocks = nb_q;
   p.head_group = heads_abreast(nb_q);
