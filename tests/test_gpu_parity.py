@@ -1039,6 +1039,49 @@ def test_shared_kv_heads_with_split_groups_at_full_size():
         assert e <= 2 ** -7, f"{name}: {e:.3e}"       # two bf16 roundings of nearly equal fp32 sums
 
 
+@pytest.mark.parametrize("B,H,N,d,alibi", [(8, 8, 2048, 128, True), (16, 8, 1000, 64, False), (4, 16, 2100, 128, False)])
+def test_softmax_backward_pinned_paired_and_compiler_scheduled_forms_agree(B, H, N, d, alibi):
+    """The softmax comparison backward in its three forms on a causal problem large enough for the
+    paired blocks: hand-pinned with pairs (the default), hand-pinned with single blocks (bit-equal)
+    and compiler-scheduled (same arithmetic, another summation order inside the MFMAs' inputs:
+    equal to a bf16 rounding); sampled rows of the default against the oracle.  N = 1000 has a
+    ragged last block, N = 2100 an odd number of blocks (not paired)."""
+    g = torch.Generator().manual_seed(7700 + N + d)
+    q, k, v, do = (torch.randn(B, H, N, d, generator=g).bfloat16() for _ in range(4))
+    slopes = W.alibi_slopes(H) if alibi else None
+    sl = _dev(slopes) if slopes is not None else None
+    Q, K, V, DO = (_dev(t) for t in (q, k, v, do))
+    o = torch.empty_like(Q)
+    lse = torch.empty(B, H, N, dtype=torch.float32, device="cuda")
+    sa.softmax_attn_fwd(Q, K, V, o, lse, True, sl)
+    outs = {}
+    try:
+        for name, mode, fn in (("paired", 0, sa.softmax_attn_bwd), ("single", 3, sa.softmax_attn_bwd),
+                               ("cs", 0, sa.softmax_attn_bwd_compiler_scheduled)):
+            sa.sattn_set_bwd_merged(mode)
+            (dq, g0), (dk, g1), (dv, g2) = (_guarded(Q.shape) for _ in range(3))
+            fn(Q, K, V, o, lse, DO, dq, dk, dv, True, sl)
+            torch.cuda.synchronize()
+            for guard in (g0, g1, g2):
+                guard()
+            outs[name] = (dq, dk, dv)
+    finally:
+        sa.sattn_set_bwd_merged(0)
+    for a, b_, c in zip(outs["paired"], outs["single"], outs["cs"]):
+        assert not torch.isnan(a).any() and torch.equal(a, b_)
+        assert row_err(a, c.double().cpu().numpy()) <= 2 ** -7
+    rows = np.array(sorted({0, 31, 127, 128, N // 2, N - 129, N - 1}))
+    ridx = torch.as_tensor(rows, device="cuda")
+    f = lambda t: t.double().numpy()
+    for (b, h) in ((0, 0), (B - 1, H - 1)):
+        sl1 = None if slopes is None else slopes[h:h + 1].double().numpy()
+        one = lambda t: f(t[b:b + 1, h:h + 1])
+        rq, rk, rv = orc.softmax_attn_bwd(one(q), one(k), one(v), one(do), True, sl1)
+        for name, got, ref in (("dq", outs["paired"][0], rq), ("dk", outs["paired"][1], rk), ("dv", outs["paired"][2], rv)):
+            e = row_err(got[b, h][ridx], ref[0, 0][rows])
+            assert e <= TOL_BF16, f"{name} {(b, h)}: {e:.3e}"
+
+
 def test_forward_with_64_row_waves_on_packed_shared_and_cross_inputs():
     # the entry points that reuse the forward kernels: variable-length batches, shared K/V heads,
     # different numbers of queries and keys -- each against its own 32-row result, bit for bit
