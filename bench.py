@@ -426,9 +426,8 @@ def main():
                                          "same 32-rows-per-wave tile shape (sigmoid_fwd may run the 64-row shape, "
                                          "which the softmax kernel does not have); backward, like for like = "
                                          "sigmoid_bwd over softmax_bwd: both hand-pinned, same tile shape, causal "
-                                         "blocks in pairs in both (softmax_bwd includes its pre-pass launch; the "
-                                         "sigmoid backward may run its two passes in one grid, a form the softmax "
-                                         "backward does not have); the _compiler_scheduled ratios compare the "
+                                         "blocks in pairs and small grids as one grid in both (softmax_bwd "
+                                         "includes its pre-pass launch); the _compiler_scheduled ratios compare the "
                                          "twins without any hand-pinned stream",
                              "ms": cmp_ms}
         out["softmax_fwd_ms"] = cmp_ms["softmax_fwd"]["mean"]

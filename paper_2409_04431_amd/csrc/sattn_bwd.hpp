@@ -1028,12 +1028,13 @@ attn_bwd_kernel(const BwdParams p) {
   }
 }
 
-// Both passes of the sigmoid backward in one grid (self-attention, one K/V head per query
+// Both passes of the pinned backward in one grid (self-attention, one K/V head per query
 // head): even places run the dK/dV workgroup, odd places the dQ workgroup of the same
 // (head, block) place, each pass in its own heavy-first order.  The grid is one launch, so a
 // pass's last, ragged round of workgroups is filled by the other pass, and a head's two
-// passes run on the same XCD next to each other and share its L2.
-template <int D, bool CAUSAL, bool ALIBI>
+// passes run on the same XCD next to each other and share its L2.  (SOFTMAX: the comparison
+// kernel's two passes; its pre-pass stays a launch of its own.)
+template <int D, bool CAUSAL, bool ALIBI, bool SOFTMAX = false>
 __global__ void __launch_bounds__(256, 1)
 attn_bwd_merged_kernel(const BwdParams p) {
   const int total = p.n_blocks * p.B * p.H;
@@ -1041,10 +1042,10 @@ attn_bwd_merged_kernel(const BwdParams p) {
   int bh, rank;
   if (logical & 1) {
     bwd_place<BWD_DQ, CAUSAL, false>(p, logical >> 1, p.n_blocks, bh, rank);
-    attn_bwd_body<D, BWD_DQ, CAUSAL, ALIBI, false, true, false>(p, bh, bwd_block_of_rank<BWD_DQ, CAUSAL>(p, rank), (int)blockIdx.x, (int)threadIdx.x);
+    attn_bwd_body<D, BWD_DQ, CAUSAL, ALIBI, SOFTMAX, true, false>(p, bh, bwd_block_of_rank<BWD_DQ, CAUSAL>(p, rank), (int)blockIdx.x, (int)threadIdx.x);
   } else {
     bwd_place<BWD_DKDV, CAUSAL, false>(p, logical >> 1, p.n_blocks, bh, rank);
-    attn_bwd_body<D, BWD_DKDV, CAUSAL, ALIBI, false, true, false>(p, bh, bwd_block_of_rank<BWD_DKDV, CAUSAL>(p, rank), (int)blockIdx.x, (int)threadIdx.x);
+    attn_bwd_body<D, BWD_DKDV, CAUSAL, ALIBI, SOFTMAX, true, false>(p, bh, bwd_block_of_rank<BWD_DKDV, CAUSAL>(p, rank), (int)blockIdx.x, (int)threadIdx.x);
   }
 }
 

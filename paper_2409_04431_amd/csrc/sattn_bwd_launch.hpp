@@ -20,14 +20,15 @@ int launch_bwd_variant(BwdParams p, int causal, bool alibi, int parts, bool merg
   dim3 block(256);
   if (p.kv_group < 1 || p.H % p.kv_group) return SATTN_ERR_SHAPE;
   if (p.kv_group > 1 && (SOFTMAX || !PIN)) return SATTN_ERR_UNSUPPORTED;  // only the product kernels share K/V heads
-  if constexpr (!SOFTMAX && PIN) {
+  if constexpr (PIN) {
     // self-attention with one K/V head per query head and both passes wanted: one grid
     if (parts == (kBwdDkDv | kBwdDq) && p.kv_group == 1 && nb_q == nb_k && p.Nk == 0 && !p.db_rows && merged) {
       p.n_blocks = nb_q;
       p.head_group = heads_abreast(nb_q);
       p.pair = 0;
       dim3 grid2(2 * nb_q * p.B * p.H);
-      SATTN_DISPATCH2(causal, alibi, rc = launch(attn_bwd_merged_kernel<D, A, B2>, grid2, block, lds, st, p));
+      SATTN_DISPATCH2(causal, alibi, rc = launch(attn_bwd_merged_kernel<D, A, B2, SOFTMAX>, grid2, block,
+                                                 lds + (SOFTMAX ? 4 * StatStager::SLOT : 0), st, p));
       return rc;
     }
   }
@@ -71,7 +72,7 @@ int launch_bwd_variant(BwdParams p, int causal, bool alibi, int parts, bool merg
 template <int D>
 int launch_bwd_bf16(BwdParams p, bool softmax, bool pin, int causal, bool alibi, int parts, bool merged,
                     hipStream_t st) {
-  if (softmax && pin) return launch_bwd_variant<D, true, true>(p, causal, alibi, parts, false, st);
+  if (softmax && pin) return launch_bwd_variant<D, true, true>(p, causal, alibi, parts, merged, st);
   if (softmax) return launch_bwd_variant<D, true, false>(p, causal, alibi, parts, false, st);
   if (pin) return launch_bwd_variant<D, false, true>(p, causal, alibi, parts, merged, st);
   return launch_bwd_variant<D, false, false>(p, causal, alibi, parts, false, st);
