@@ -35,6 +35,20 @@ def test_header_symbols_are_exported(lib):
         assert hasattr(lib, n), f"{n} declared in include/*.h but not exported"
 
 
+def test_headers_are_plain_c(tmp_path):
+    """The boundary is a C ABI: both headers compile as C99 and as C++11 on their own."""
+    import shutil
+    import subprocess
+    for cc, std, ext in (("gcc", "-std=c99", "c"), ("g++", "-std=c++11", "cpp")):
+        if shutil.which(cc) is None:
+            pytest.skip(f"{cc} not installed")
+        src = tmp_path / f"hdr.{ext}"
+        src.write_text("".join(f'#include "{h}"\n' for h in HEADERS) + "int main(void) { return 0; }\n")
+        res = subprocess.run([cc, std, "-Wall", "-Wextra", "-pedantic", "-Werror", "-c", str(src), "-o", str(tmp_path / "hdr.o")],
+                             capture_output=True, text=True)
+        assert res.returncode == 0, res.stderr
+
+
 def test_version_and_error_strings(lib):
     assert sa.sattn_version() >= 100
     for code in range(0, -8, -1):
